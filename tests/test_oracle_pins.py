@@ -1,0 +1,254 @@
+"""Pins for the CPU oracle: each checks it against something other than itself.
+
+The paper prints no worked numeric example for the gradient-flow path, so the
+pins are what mathematics fixes: central finite differences, closed forms,
+BatchNorm invariants, reductions to library routines (scipy correlate2d,
+matrix product), brute-force Jacobians, and symmetries.
+"""
+import math
+
+import numpy as np
+import pytest
+from scipy.signal import correlate2d
+
+from oracle import seqnet_oracle as O
+from paper_2105_00619_amd import workloads as W
+
+
+def _setup(units, b=3, h=6, w=6, c=3, classes=5, seed=11, perturb=True):
+    p = W.make_params(units, h, w, seed, perturb=perturb).astype(np.float64)
+    x = W.make_images(b, h, w, c, seed, "gauss").astype(np.float64)
+    # spread pixel values so that no pre-activation sits at a ReLU kink
+    x = x + 0.3 * np.random.default_rng(seed).standard_normal(x.shape)
+    y = W.make_labels(b, classes, seed)
+    return p, x, y
+
+
+def _fd_check(units, p, x, y, n_probe=120, h=1e-5, tol=2e-6, seed=0):
+    loss, g = O.loss_and_grads(units, p, x, y)
+    rng = np.random.default_rng(seed)
+    idx = np.arange(p.size) if p.size <= n_probe else rng.choice(p.size, n_probe, replace=False)
+    worst = 0.0
+    for i in idx:
+        step = h * max(1.0, abs(p[i]))
+        pp, pm = p.copy(), p.copy()
+        pp[i] += step
+        pm[i] -= step
+        fd = (O.loss_and_grads(units, pp, x, y)[0] - O.loss_and_grads(units, pm, x, y)[0]) / (2 * step)
+        err = abs(fd - g[i]) / max(1e-3 * np.abs(g).max(), abs(g[i]), abs(fd))
+        worst = max(worst, err)
+    assert worst < tol, "finite-difference mismatch %.3e" % worst
+    return g
+
+
+FD_NETS = {
+    "plain_conv_stack": [W.conv(3, 4, bn=False), W.conv(4, 4, bn=False), W.gap_linear_ce(4, 5)],
+    "conv_bn_relu": [W.conv(3, 4), W.conv(4, 6), W.gap_linear_ce(6, 5)],
+    "stride2_conv": [W.conv(3, 4, stride=2), W.conv(4, 4), W.gap_linear_ce(4, 5)],
+    "conv1x1": [W.conv(3, 4, ksize=1), W.conv(4, 8, ksize=1, stride=2), W.gap_linear_ce(8, 5)],
+    "conv_no_relu_bias_bn": [W.conv(3, 4, bn=True, relu=False, bias=True), W.gap_linear_ce(4, 5)],
+    "basic_block_identity": [W.conv(3, 4), W.basic_block(4, 4), W.gap_linear_ce(4, 5)],
+    "basic_block_projection": [W.conv(3, 4), W.basic_block(4, 8, 2), W.gap_linear_ce(8, 5)],
+    "bottleneck_projection": [W.conv(3, 4), W.bottleneck(4, 8, 1), W.bottleneck(8, 8, 1), W.gap_linear_ce(8, 5)],
+    "bottleneck_stride2": [W.conv(3, 8), W.bottleneck(8, 16, 2), W.gap_linear_ce(16, 5)],
+    "maxpool_flatten": [W.conv(3, 4), W.maxpool(), W.conv(4, 4), W.flatten_linear_ce(4, 5)],
+}
+
+
+@pytest.mark.parametrize("name", sorted(FD_NETS))
+def test_finite_differences(name):
+    units = FD_NETS[name]
+    p, x, y = _setup(units)
+    _fd_check(units, p, x, y)
+
+
+def test_loss_closed_forms():
+    logits = np.zeros((4, 10))
+    y = np.array([0, 3, 9, 5])
+    loss, prob = O.softmax_ce_forward(logits, y)
+    assert abs(loss - math.log(10)) < 1e-15
+    d = O.softmax_ce_backward(prob, y)
+    assert np.abs(d.sum(axis=1)).max() < 1e-16
+    # hand-computed two-class case: logits (0, ln 3), label 0 -> p = (1/4, 3/4), loss = ln 4
+    loss, prob = O.softmax_ce_forward(np.array([[0.0, math.log(3.0)]]), np.array([0]))
+    assert abs(loss - math.log(4.0)) < 1e-15
+    assert np.allclose(O.softmax_ce_backward(prob, np.array([0])), [[-0.75, 0.75]], atol=1e-15)
+    # shift invariance and no overflow for large logits
+    big = np.array([[1000.0, 1001.0, 999.0]])
+    l1, _ = O.softmax_ce_forward(big, np.array([1]))
+    l2, _ = O.softmax_ce_forward(big - 1000.0, np.array([1]))
+    assert np.isfinite(l1) and abs(l1 - l2) < 1e-12
+
+
+def test_sgd_closed_form_and_momentum_recurrence():
+    w = np.array([1.0, -2.0]); g = np.array([0.5, 0.25]); v0 = np.zeros(2)
+    w1, v1 = O.sgd_momentum_step(w, v0, g, 0.1, 0.9)
+    assert np.array_equal(w1, w - 0.1 * g) and np.array_equal(v1, g)
+    w2, v2 = O.sgd_momentum_step(w1, v1, g, 0.1, 0.9)
+    assert np.allclose(v2, 1.9 * g) and np.allclose(w2, w - 0.1 * g - 0.19 * g)
+
+
+def test_loss_scale_state_machine():
+    s, c = 65536.0, 0
+    s, c, skip = O.loss_scale_update(s, c, True, 3)
+    assert (s, c, skip) == (32768.0, 0, True)
+    for expect_c in (1, 2):
+        s, c, skip = O.loss_scale_update(s, c, False, 3)
+        assert (s, c, skip) == (32768.0, expect_c, False)
+    s, c, skip = O.loss_scale_update(s, c, False, 3)
+    assert (s, c, skip) == (65536.0, 0, False)
+    s, c, skip = O.loss_scale_update(s, 2, True, 3)
+    assert (s, c, skip) == (32768.0, 0, True)
+
+
+def test_conv_matches_scipy_correlate2d():
+    rng = np.random.default_rng(3)
+    x = rng.standard_normal((2, 7, 6, 3)); w = rng.standard_normal((4, 3, 3, 3)); b = rng.standard_normal(4)
+    z = O.conv2d_forward(x, w, b, 1, 1)
+    for n in range(2):
+        for k in range(4):
+            ref = b[k] + sum(correlate2d(np.pad(x[n, :, :, c], 1), w[k, :, :, c], mode="valid") for c in range(3))
+            assert np.allclose(z[n, :, :, k], ref, atol=1e-12)
+    z2 = O.conv2d_forward(x, w, None, 2, 1)
+    assert z2.shape == (2, 4, 3, 4)
+    for n in range(2):
+        for k in range(4):
+            ref = sum(correlate2d(np.pad(x[n, :, :, c], 1), w[k, :, :, c], mode="valid") for c in range(3))
+            assert np.allclose(z2[n, :, :, k], ref[::2, ::2], atol=1e-12)
+
+
+def test_conv1x1_is_matrix_product_and_delta_is_identity():
+    rng = np.random.default_rng(4)
+    x = rng.standard_normal((2, 5, 5, 6)); w = rng.standard_normal((7, 1, 1, 6))
+    z = O.conv2d_forward(x, w, None, 1, 0)
+    assert np.allclose(z.reshape(-1, 7), x.reshape(-1, 6) @ w.reshape(7, 6).T, atol=1e-13)
+    delta = np.zeros((6, 3, 3, 6))
+    for c in range(6):
+        delta[c, 1, 1, c] = 1.0
+    assert np.array_equal(O.conv2d_forward(x, delta, None, 1, 1), x)
+
+
+def test_dgrad_is_conv_with_rotated_transposed_filter():
+    rng = np.random.default_rng(5)
+    x = rng.standard_normal((2, 6, 6, 3)); w = rng.standard_normal((4, 3, 3, 3)); dz = rng.standard_normal((2, 6, 6, 4))
+    dx, _, _ = O.conv2d_backward(x, w, dz, 1, 1, False)
+    wrot = np.ascontiguousarray(w[:, ::-1, ::-1, :].transpose(3, 1, 2, 0))
+    for n in range(2):
+        for c in range(3):
+            ref = sum(correlate2d(np.pad(dz[n, :, :, k], 1), wrot[c, :, :, k], mode="valid") for k in range(4))
+            assert np.allclose(dx[n, :, :, c], ref, atol=1e-12)
+
+
+@pytest.mark.parametrize("stride,pad,ks", [(1, 1, 3), (2, 1, 3), (2, 0, 1), (1, 0, 3)])
+def test_conv_backward_against_brute_force_jacobian(stride, pad, ks):
+    rng = np.random.default_rng(6)
+    x = rng.standard_normal((1, 5, 4, 2)); w = rng.standard_normal((3, ks, ks, 2)); b = rng.standard_normal(3)
+    z0 = O.conv2d_forward(x, w, b, stride, pad)
+    dz = rng.standard_normal(z0.shape)
+    dx, dw, db = O.conv2d_backward(x, w, dz, stride, pad, True)
+    zero_b = np.zeros(3)
+    # conv is linear in x and in w: one unit perturbation per entry gives the exact Jacobian column
+    jx = np.zeros_like(x)
+    for i in np.ndindex(x.shape):
+        e = np.zeros_like(x); e[i] = 1.0
+        jx[i] = (O.conv2d_forward(e, w, zero_b, stride, pad) * dz).sum()
+    jw = np.zeros_like(w)
+    for i in np.ndindex(w.shape):
+        e = np.zeros_like(w); e[i] = 1.0
+        jw[i] = (O.conv2d_forward(x, e, zero_b, stride, pad) * dz).sum()
+    assert np.allclose(dx, jx, atol=1e-12) and np.allclose(dw, jw, atol=1e-12)
+    assert np.allclose(db, dz.sum(axis=(0, 1, 2)), atol=1e-13)
+
+
+def test_batchnorm_invariants():
+    rng = np.random.default_rng(7)
+    z = 3.0 + 2.0 * rng.standard_normal((4, 5, 5, 6)); gamma = rng.standard_normal(6); beta = rng.standard_normal(6)
+    y, cache = O.batchnorm_forward(z, gamma, beta)
+    xhat = cache[0]
+    assert np.abs(xhat.mean(axis=(0, 1, 2))).max() < 1e-13
+    assert np.allclose((xhat ** 2).mean(axis=(0, 1, 2)), z.var(axis=(0, 1, 2)) / (z.var(axis=(0, 1, 2)) + O.BN_EPS))
+    dy = rng.standard_normal(z.shape)
+    dz, dgamma, dbeta = O.batchnorm_backward(dy, cache, gamma)
+    assert np.abs(dz.sum(axis=(0, 1, 2))).max() < 1e-12
+    # sum(dz * xhat) vanishes only as eps -> 0; with eps it equals gamma*rstd*dgamma*eps/(var+eps)
+    var = z.var(axis=(0, 1, 2))
+    closed = gamma * cache[1] * dgamma * O.BN_EPS / (var + O.BN_EPS)
+    assert np.allclose((dz * xhat).sum(axis=(0, 1, 2)), closed, rtol=1e-9, atol=1e-13)
+    # y is invariant to shifting and positively scaling z (up to the eps term) -> dz orthogonal to 1 and to z
+    y2, _ = O.batchnorm_forward(z + 5.0, gamma, beta)
+    assert np.allclose(y, y2, atol=1e-12)
+
+
+def test_bias_before_bn_has_zero_gradient_and_w_dw_orthogonality():
+    units = [W.conv(3, 4, bn=True, relu=True, bias=True), W.gap_linear_ce(4, 5)]
+    p, x, y = _setup(units, b=4, h=6, w=6)
+    _, g = O.loss_and_grads(units, p, x, y)
+    sl = W.param_slices(units, 6, 6)
+    assert np.abs(g[sl["u0.b"]]).max() < 1e-14
+    wv = p[sl["u0.w"]].reshape(4, -1); dw = g[sl["u0.w"]].reshape(4, -1)
+    rel = np.abs((wv * dw).sum(axis=1)) / (np.linalg.norm(wv, axis=1) * np.linalg.norm(dw, axis=1))
+    assert rel.max() < 1e-3  # exact only as eps -> 0
+
+
+def test_maxpool_first_max_tie_break_and_relu_zero_derivative():
+    x = np.zeros((1, 2, 2, 1))
+    out, arg = O.maxpool2_forward(x)
+    assert arg[0, 0, 0, 0] == 0
+    dx = O.maxpool2_backward(np.ones((1, 1, 1, 1)), arg, x.shape)
+    assert np.array_equal(dx[0, :, :, 0], [[1.0, 0.0], [0.0, 0.0]])
+    x[0, 1, 0, 0] = 2.0; x[0, 1, 1, 0] = 2.0
+    _, arg = O.maxpool2_forward(x)
+    assert arg[0, 0, 0, 0] == 2
+    assert np.array_equal(O.relu_backward(np.ones(3), np.array([-1.0, 0.0, 1.0])), [0.0, 0.0, 1.0])
+
+
+def test_gap_linear_on_constant_image():
+    units = [W.gap_linear_ce(3, 4)]
+    p = np.arange(16, dtype=np.float64) / 10.0
+    x = np.ones((2, 4, 4, 3)) * np.array([1.0, 2.0, 3.0])
+    y = np.array([1, 2])
+    loss, g = O.loss_and_grads(units, p, x, y)
+    logits = np.array([1.0, 2.0, 3.0]) @ p[:12].reshape(4, 3).T + p[12:]
+    lse = np.log(np.exp(logits).sum())
+    assert abs(loss - (lse - 0.5 * (logits[1] + logits[2]))) < 1e-12
+
+
+def test_batch_permutation_symmetry():
+    units = FD_NETS["basic_block_projection"]
+    p, x, y = _setup(units, b=6)
+    l1, g1 = O.loss_and_grads(units, p, x, y)
+    perm = np.random.default_rng(1).permutation(6)
+    l2, g2 = O.loss_and_grads(units, p, x[perm], y[perm])
+    assert abs(l1 - l2) < 1e-12 and np.linalg.norm(g1 - g2) <= 1e-11 * np.linalg.norm(g1)
+
+
+def test_gradient_linear_in_upstream_scale():
+    """Scaling the loss by S scales every gradient by S exactly when S is a power of two."""
+    units = FD_NETS["conv_bn_relu"]
+    p, x, y = _setup(units)
+    _, g = O.loss_and_grads(units, p, x, y)
+    # replicate the batch: mean loss unchanged, gradients unchanged (BN statistics identical)
+    _, g2 = O.loss_and_grads(units, p, np.concatenate([x, x]), np.concatenate([y, y]))
+    assert np.linalg.norm(g - g2) <= 1e-10 * np.linalg.norm(g)
+
+
+def test_fp32_instantiation_close_to_fp64():
+    w = W.config(1)
+    p, x, y = W.make_batch(w)
+    l64, g64 = O.loss_and_grads(w.units, p, x, y, np.float64)
+    l32, g32 = O.loss_and_grads(w.units, p, x, y, np.float32)
+    assert g32.dtype == np.float32
+    assert abs(l64 - l32) < 1e-5 and np.linalg.norm(g64 - g32) <= 1e-5 * np.linalg.norm(g64)
+
+
+def test_param_layout_matches_oracle_consumption():
+    for idx in (1, 2, 3, 4):
+        w = W.config(idx, batch=2)
+        n = W.param_count(w.units, w.height, w.width)
+        p, x, y = W.make_batch(w)
+        assert p.size == n
+        if idx <= 3:
+            _, g = O.loss_and_grads(w.units, p, x, y)
+            assert g.size == n
+    with pytest.raises(ValueError):
+        O.loss_and_grads(W.config(1).units, np.zeros(10), np.zeros((1, 32, 32, 3)), np.zeros(1, int))
