@@ -1,0 +1,146 @@
+/*
+ * optorch_seq -- one training step of a sequential CNN split into k checkpointed
+ * segments, for AMD MI355X (gfx950).  C ABI; no C++ or framework types cross it.
+ *
+ * Method (paper, Introduction, paragraph on sequential models, and Section
+ * "Sequential-checkpoint training"): a sequential network is run as a list of
+ * segments; every segment except the last runs without keeping its intermediate
+ * activations, only the input of each segment is kept, and during back-propagation
+ * each such segment's forward pass is run again from its kept input to rebuild the
+ * activations its backward pass needs.  Section "Mixed-precision training": 16-bit
+ * storage with 32-bit arithmetic where stability needs it; here that means fp32
+ * master weights, fp16/bf16 activations and weight copies, fp32 accumulation, and a
+ * dynamic loss scale.  Section "Discussion & Recommendation": checkpoints are
+ * cheapest at narrow layers -- the byte-aware plan mode below.
+ *
+ * Memory ownership: the handle owns host memory only.  Both device arenas are
+ * allocated by the caller (sizes from optorch_seq_query) and borrowed until
+ * optorch_seq_destroy; the library sub-allocates the activation arena itself, which
+ * is what makes the reported peak byte counts exact.  All kernels are enqueued on
+ * the stream given to optorch_seq_bind; optorch_seq_step synchronises that stream
+ * once, at its end, to read back the loss and the overflow flag.
+ *
+ * Error behaviour: every int-returning function returns OPTORCH_OK (0) or a negative
+ * code; optorch_seq_last_error gives a message for the most recent failure on that
+ * handle (or, with a NULL handle, for the most recent failed create on this thread).
+ * A step skipped because of a non-finite gradient is a success with *step_skipped = 1.
+ * A handle is not thread-safe.
+ */
+#ifndef OPTORCH_SEQ_H
+#define OPTORCH_SEQ_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct optorch_seq optorch_seq_t; /* opaque */
+
+enum { OPTORCH_OK = 0,
+       OPTORCH_E_INVALID = -1,  /* bad argument or unsupported layer combination            */
+       OPTORCH_E_BUDGET = -2,   /* planned arena exceeds the budget or the bound arena      */
+       OPTORCH_E_HIP = -3,      /* HIP runtime error                                        */
+       OPTORCH_E_ORDER = -4 };  /* wrong call order (e.g. step before bind / set_params)    */
+
+typedef enum { OPTORCH_FP32 = 0, OPTORCH_BF16 = 1, OPTORCH_FP16 = 2 } optorch_precision_t;
+
+/* A unit is the atomic piece a segment boundary may fall between (a residual block's
+ * skip connection never crosses a boundary). */
+typedef enum {
+  OPTORCH_CONV = 0,             /* conv ksize x ksize [+bias] [+BatchNorm] [+ReLU]                        */
+  OPTORCH_MAXPOOL2 = 1,         /* 2x2 max-pool, stride 2                                                 */
+  OPTORCH_BASIC_BLOCK = 2,      /* conv3x3(stride)-BN-ReLU, conv3x3-BN, + shortcut, ReLU                  */
+  OPTORCH_BOTTLENECK = 3,       /* conv1x1-BN-ReLU, conv3x3(stride)-BN-ReLU, conv1x1-BN, + shortcut, ReLU */
+  OPTORCH_GAP_LINEAR_CE = 4,    /* global average pool, linear (+bias), mean softmax cross-entropy        */
+  OPTORCH_FLATTEN_LINEAR_CE = 5 /* NHWC flatten, linear (+bias), mean softmax cross-entropy               */
+} optorch_unit_kind_t;
+
+/* Plain data, caller-owned, copied by create.  For blocks cin/cout are the block's input
+ * and output channels (bottleneck width = cout/4) and the shortcut is the identity when
+ * cin == cout and stride == 1, else conv1x1(stride)+BN.  For the two head kinds cin is the
+ * channel count of the incoming map and cout the number of classes.  ksize is 1 or 3,
+ * stride 1 or 2. */
+typedef struct {
+  int32_t kind, cin, cout, ksize, stride, pad;
+  int32_t has_bn, has_relu, has_bias, reserved;
+} optorch_unit_t;
+
+typedef struct {
+  int32_t k_segments;              /* >= 1; 1 = every activation stored (no recomputation)       */
+  const int32_t* boundaries;       /* NULL: the planner chooses; else k-1 ascending unit indices,
+                                      segment j starts at unit boundaries[j-1]                    */
+  int32_t plan_mode;               /* 0 = equal unit count (remainder joins the last segment),
+                                      1 = minimise peak saved bytes over contiguous partitions    */
+  int32_t precision;               /* optorch_precision_t                                         */
+  int32_t batch, height, width, channels, num_classes;
+  uint64_t activation_budget_bytes; /* 0 = unlimited; create fails with OPTORCH_E_BUDGET if the
+                                       planned activation arena is larger                         */
+  float momentum;                  /* SGD momentum (0 = plain SGD)                                */
+  float bn_eps;                    /* <= 0 selects 1e-5                                           */
+  float bn_momentum;               /* running-statistics momentum; <= 0 selects 0.1               */
+  float loss_scale_init;           /* <= 0 selects 1 (fp32, bf16) or 65536 (fp16)                 */
+  float scale_growth;              /* <= 0 selects 2                                              */
+  float scale_backoff;             /* <= 0 selects 0.5                                            */
+  int32_t growth_interval;         /* <= 0 selects 2000 (fp16) or "never" (fp32, bf16)            */
+} optorch_seq_config_t;
+
+/* Plans the step on the host: expands units into kernels, chooses segment boundaries,
+ * assigns every activation an offset in the activation arena and builds the static launch
+ * schedule (forward of segments 0..k-2 keeping only their inputs, forward of the last segment
+ * keeping what its backward needs, then per segment in reverse: replay + backward).  Touches
+ * no device.  units: host pointer, n_units entries, the last one a head kind. */
+int optorch_seq_create(const optorch_unit_t* units, int32_t n_units,
+                       const optorch_seq_config_t* cfg, optorch_seq_t** out);
+
+/* Sizes the caller needs (any out pointer may be NULL).
+ *   param_count               number of fp32 parameters in the flat parameter vector
+ *   param_arena_bytes         bytes of device memory for the parameter arena (master weights,
+ *                             momentum, gradients, 16-bit copies, BN running statistics, flags)
+ *   act_arena_bytes           bytes of device memory for the activation arena (= planned peak)
+ *   planned_peak_saved_bytes  planned peak of live checkpoints + tensors kept for backward
+ *   boundaries_out            k-1 unit indices (host) */
+int optorch_seq_query(const optorch_seq_t* h, uint64_t* param_count, uint64_t* param_arena_bytes,
+                      uint64_t* act_arena_bytes, uint64_t* planned_peak_saved_bytes,
+                      int32_t* boundaries_out);
+
+/* Lends the two device arenas (256-byte aligned device pointers) and the HIP stream
+ * (hipStream_t, NULL = default stream) to the handle. */
+int optorch_seq_bind(optorch_seq_t* h, void* param_arena_dev, uint64_t param_arena_bytes,
+                     void* act_arena_dev, uint64_t act_arena_bytes, void* hip_stream);
+
+/* Copies n = param_count fp32 values (flat order: unit order; inside a unit conv weight
+ * (C_out, kh, kw, C_in), [bias], BN gamma, BN beta; inside a block conv1, conv2, [conv3], then the
+ * projection shortcut; linear weight (classes x features), bias) from host (is_device = 0) or
+ * device memory, zeroes the momentum, resets BN running statistics and the loss scale, and
+ * refreshes the 16-bit copies. */
+int optorch_seq_set_params(optorch_seq_t* h, const float* src, uint64_t n, int32_t is_device);
+int optorch_seq_get_params(const optorch_seq_t* h, float* dst, uint64_t n, int32_t is_device);
+
+/* One training step on one batch.
+ *   x_dev             device, batch x height x width x channels fp32, NHWC
+ *   y_dev             device, batch int32 labels in [0, num_classes)
+ *   lr                learning rate of this step
+ *   loss_out          host, mean softmax cross-entropy of the batch (unscaled)
+ *   grads_dev         device or NULL: receives param_count fp32 gradients, unscaled, w.r.t. the
+ *                     weights used in this step's forward; unspecified on a skipped step
+ *   peak_saved_bytes  host or NULL: observed peak of checkpoints + tensors kept for backward
+ *   peak_arena_bytes  host or NULL: high-water mark of the activation arena
+ *   loss_scale_out    host or NULL: loss scale after this step
+ *   step_skipped      host or NULL: 1 if a non-finite gradient was found (weights untouched,
+ *                     scale multiplied by scale_backoff), else 0 */
+int optorch_seq_step(optorch_seq_t* h, const float* x_dev, const int32_t* y_dev, float lr,
+                     float* loss_out, float* grads_dev, uint64_t* peak_saved_bytes,
+                     uint64_t* peak_arena_bytes, float* loss_scale_out, int32_t* step_skipped);
+
+/* Number of kernel launches in one step's static schedule, and how many of them belong to the
+ * replay (recomputation) of non-last segments. */
+int optorch_seq_schedule_info(const optorch_seq_t* h, int32_t* n_launch_records, int32_t* n_replay_records);
+
+const char* optorch_seq_last_error(const optorch_seq_t* h);
+void optorch_seq_destroy(optorch_seq_t* h);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* OPTORCH_SEQ_H */

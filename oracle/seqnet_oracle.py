@@ -12,9 +12,9 @@ pipeline would have stored, so the gradients are exactly those of ordinary
 back-propagation.  The oracle is therefore that plain definition written out:
 a forward pass that keeps every activation, followed by reverse-mode
 differentiation, in float64 (float32 on request, for timing), plus one
-SGD-momentum update.  It has no checkpointing, no loss scaling and no half
-precision.  Mixed precision (Section "Mixed-precision training") changes the
-storage type on the GPU, not the function being differentiated.
+SGD-momentum update.  The plain path has no checkpointing, no loss scaling and
+no half precision: mixed precision (Section "Mixed-precision training") changes
+the storage type, not the function being differentiated.
 
 Layer definitions are the textbook ones (the paper delegates layer math to its
 host framework; the neuron/back-propagation primer in the same section is the
@@ -34,6 +34,17 @@ only description):
 matmul / tensordot from numpy serve as the contraction step of a convolution
 tap; nothing is blocked, fused or reordered.
 
+Storage emulation (optional).  A ReLU mask is an integer decision taken by a
+floating-point comparison, and a 16-bit pipeline takes it on 16-bit values.  So
+that both sides take it in the same precision, `loss_and_grads(storage="bf16" |
+"fp16", loss_scale=S)` rounds (to nearest even) every tensor the mixed-precision
+pipeline keeps in 16 bits -- the input image, the convolution weights, each
+convolution output, each BatchNorm/ReLU output, and each activation gradient --
+and multiplies the loss gradient by S, dividing the parameter gradients by S at
+the end.  Everything between two stored tensors (contractions, BatchNorm
+statistics and sums, the loss head, parameter gradients) stays in float64.  With
+storage=None the hooks are the identity and the function is the plain definition.
+
 Pins (tests/test_oracle_pins.py): central finite differences on every layer
 kind, closed forms of the loss and the update, BatchNorm orthogonality
 invariants, reduction of 1x1 conv to a matrix product, agreement with
@@ -46,6 +57,33 @@ import numpy as np
 
 CONV, MAXPOOL2, BASIC_BLOCK, BOTTLENECK, GAP_LINEAR_CE, FLATTEN_LINEAR_CE = range(6)
 BN_EPS = 1e-5
+
+
+# ------------------------------------------------------ 16-bit storage ------
+def round_to_bf16(a):
+    """Round to the nearest bfloat16 (ties to even), returned in the input dtype."""
+    a32 = np.ascontiguousarray(a, dtype=np.float32)
+    u = a32.view(np.uint32)
+    r = ((u + np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1))) & np.uint32(0xFFFF0000)).view(np.float32)
+    r = np.where(np.isnan(a32), np.float32(np.nan), r)
+    return r.astype(np.asarray(a).dtype if np.asarray(a).dtype.kind == "f" else np.float64)
+
+
+def round_to_fp16(a):
+    """Round to the nearest IEEE half (ties to even; overflow gives inf), returned in the input dtype."""
+    with np.errstate(over="ignore"):
+        r = np.asarray(a, dtype=np.float32).astype(np.float16)
+    return r.astype(np.asarray(a).dtype if np.asarray(a).dtype.kind == "f" else np.float64)
+
+
+def _quantizer(storage):
+    if storage is None:
+        return lambda a: a
+    if storage == "bf16":
+        return round_to_bf16
+    if storage == "fp16":
+        return round_to_fp16
+    raise ValueError("storage must be None, 'bf16' or 'fp16'")
 
 
 # ---------------------------------------------------------------- layers ----
@@ -169,8 +207,11 @@ def loss_scale_update(scale, clean_steps, found_inf, growth_interval, growth=2.0
 class _Params:
     """Sequential reader over the flat parameter vector; the writer side collects gradients."""
 
-    def __init__(self, flat):
-        self.flat, self.off = flat, 0
+    def __init__(self, flat, q=lambda a: a, flips=None, kink_tau=None):
+        self.flat, self.off, self.q = flat, 0, q
+        self.relu_count = 0           # ReLU layers are numbered in forward order
+        self.flips = flips or {}      # {relu number: (flat indices, decisions forced there)}
+        self.kink_tau, self.kinks = kink_tau, []
 
     def take(self, shape):
         n = int(np.prod(shape))
@@ -181,28 +222,46 @@ class _Params:
 
 def _cbr_forward(x, pr, cin, cout, k, stride, pad, bn, relu, bias, skip=None):
     """conv [+bias] [+BN] [+skip] [+ReLU]; returns (out, cache)."""
-    w = pr.take((cout, k, k, cin))
+    q = pr.q
+    w = q(pr.take((cout, k, k, cin)))  # 16-bit copy of the master weights
     b = pr.take((cout,)) if bias else None
     z = conv2d_forward(x, w, b, stride, pad)
-    cache = {"x": x, "w": w, "stride": stride, "pad": pad, "bias": bias, "bn": bn, "relu": relu}
+    cache = {"x": x, "w": w, "stride": stride, "pad": pad, "bias": bias, "bn": bn, "relu": relu, "q": q}
     y = z
+    shift_off = pr.off - cout if bias else -1  # flat index of the per-channel additive parameter in front of the ReLU
     if bn:
         gamma, beta = pr.take((cout,)), pr.take((cout,))
+        shift_off = pr.off - cout
+        z = q(z)  # the convolution output is a stored tensor; statistics are taken from what is stored
         y, cache["bn_cache"] = batchnorm_forward(z, gamma, beta)
         cache["gamma"] = gamma
     if skip is not None:
         y = y + skip
     cache["y"] = y
-    return (relu_forward(y) if relu else y), cache
+    if relu:
+        rid = pr.relu_count
+        pr.relu_count += 1
+        mask = y > 0
+        if pr.kink_tau is not None:  # decisions within kink_tau x rms(y) of the kink
+            near = np.flatnonzero(np.abs(y).ravel() < pr.kink_tau * np.sqrt(np.mean(y * y)))
+            pr.kinks += [(rid, int(i), (shift_off + int(i) % cout) if shift_off >= 0 else -1, bool(mask.ravel()[i]))
+                         for i in near]
+        if rid in pr.flips:
+            mask = mask.copy()
+            mask.ravel()[np.asarray(pr.flips[rid][0], dtype=np.int64)] = np.asarray(pr.flips[rid][1], dtype=bool)
+        cache["mask"] = mask
+    return q(relu_forward(y) if relu else y), cache
 
 
 def _cbr_backward(da, cache, grads):
-    """Returns (dx, dskip); appends this layer's parameter gradients to `grads` (in layout order)."""
-    dy = relu_backward(da, cache["y"]) if cache["relu"] else da
+    """Returns (dx, dskip); appends this layer's parameter gradients to `grads` (in layout order).
+    dx is the raw data gradient: the caller adds any second contribution and then stores (rounds) it."""
+    dy = da * cache["mask"] if cache["relu"] else da  # relu_backward with the recorded decisions
     dskip = dy
     g_bn = []
     if cache["bn"]:
         dz, dgamma, dbeta = batchnorm_backward(dy, cache["bn_cache"], cache["gamma"])
+        dz = cache["q"](dz)
         g_bn = [dgamma, dbeta]
     else:
         dz = dy
@@ -249,25 +308,27 @@ def _unit_backward(cache, da, grads):
     tag = cache[0]
     if tag == "conv":
         dx, _ = _cbr_backward(da, cache[1], grads)
-        return dx
+        return cache[1]["q"](dx)
     if tag == "pool":
         return maxpool2_backward(da, cache[1], cache[2])
     caches, csc = cache[1], cache[2]
+    q = caches[0]["q"]
     local = []
     d, dskip = _cbr_backward(da, caches[-1], local)
     for c in reversed(caches[:-1]):
-        d, _ = _cbr_backward(d, c, local)
+        d, _ = _cbr_backward(q(d), c, local)
     local.reverse()  # conv1, conv2, [conv3]
     if csc is not None:
         dsc, _ = _cbr_backward(dskip, csc, local)  # appended last = layout order
-        d = d + dsc
+        d = q(d + q(dsc))  # the shortcut's data gradient is stored first, the main path's is added to it
     else:
-        d = d + dskip
+        d = q(d + dskip)
     grads.append([g for layer in local for g in layer])
     return d
 
 
-def loss_and_grads(units, params, x, y, dtype=np.float64, return_trace=False):
+def loss_and_grads(units, params, x, y, dtype=np.float64, return_trace=False, storage=None, loss_scale=1.0,
+                   flips=None, kink_tau=None):
     """Loss and flat parameter gradient of the network `units` at `params` on the batch (x, y).
 
     units  : sequence of objects with attributes kind, cin, cout, ksize, stride, pad,
@@ -275,11 +336,21 @@ def loss_and_grads(units, params, x, y, dtype=np.float64, return_trace=False):
     params : flat vector in layout order (unit order; conv weight, [bias], gamma, beta;
              linear weight (classes x features), bias)
     x      : (B, H, W, C) images;  y : (B,) integer labels
+    storage, loss_scale : 16-bit storage emulation, see the module docstring; the returned
+             gradients are unscaled (non-finite if a stored value overflowed)
+    kink_tau : if given, a third return value lists the ReLU decisions whose pre-activation lies within
+             kink_tau x rms of zero -- decisions a finite-precision evaluation may legitimately take the
+             other way -- as (relu number, flat index into that layer's output, flat index of the gradient
+             entry of the BatchNorm shift / bias of that channel, which such a decision changes directly,
+             the decision taken here)
+    flips  : {relu number: (indices, decisions)} -- back-propagate with those decisions forced to the
+             given values (forward unchanged)
     """
+    q = _quantizer(storage)
     params = np.asarray(params, dtype=dtype)
-    a = np.asarray(x, dtype=dtype)
+    a = q(np.asarray(x, dtype=dtype))
     y = np.asarray(y).astype(np.int64)
-    pr = _Params(params)
+    pr = _Params(params, q, flips, kink_tau)
     caches, trace = [], []
     for u in units[:-1]:
         a, c = _unit_forward(u, a, pr)
@@ -300,7 +371,7 @@ def loss_and_grads(units, params, x, y, dtype=np.float64, return_trace=False):
     logits = feat @ wl.T + bl
     loss, prob = softmax_ce_forward(logits, y)
 
-    dlogits = softmax_ce_backward(prob, y)
+    dlogits = softmax_ce_backward(prob, y) * loss_scale
     dwl = dlogits.T @ feat
     dbl = dlogits.sum(axis=0)
     dfeat = dlogits @ wl
@@ -309,6 +380,7 @@ def loss_and_grads(units, params, x, y, dtype=np.float64, return_trace=False):
         da = np.broadcast_to(dfeat[:, None, None, :] / hw, a.shape).astype(dtype)
     else:
         da = dfeat.reshape(a.shape)
+    da = q(da)
     grads_rev = [[dwl, dbl]]
     for c in reversed(caches):
         before = len(grads_rev)
@@ -318,8 +390,12 @@ def loss_and_grads(units, params, x, y, dtype=np.float64, return_trace=False):
     flat = [np.ravel(g) for unit_g in reversed(grads_rev) for g in unit_g]
     grad = np.concatenate(flat) if flat else np.zeros(0, dtype)
     assert grad.size == params.size
+    if loss_scale != 1.0:
+        grad = grad / loss_scale
     if return_trace:
         return float(loss), grad, trace
+    if kink_tau is not None:
+        return float(loss), grad, pr.kinks
     return float(loss), grad
 
 

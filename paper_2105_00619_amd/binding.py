@@ -1,0 +1,207 @@
+"""ctypes binding of liboptorch_seq.so -- argument marshalling only.
+
+Every step of the path runs inside the library's HIP kernels; torch is used here
+to allocate the two device arenas and to supply the HIP stream.  There is no CPU
+fallback: if the shared library is missing the import of the library fails.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "liboptorch_seq.so")
+
+OK, E_INVALID, E_BUDGET, E_HIP, E_ORDER = 0, -1, -2, -3, -4
+
+SYMBOLS = (
+    "optorch_seq_create", "optorch_seq_query", "optorch_seq_bind", "optorch_seq_set_params",
+    "optorch_seq_get_params", "optorch_seq_step", "optorch_seq_schedule_info", "optorch_seq_last_error",
+    "optorch_seq_destroy",
+)
+
+
+class optorch_unit_t(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in
+                ("kind", "cin", "cout", "ksize", "stride", "pad", "has_bn", "has_relu", "has_bias", "reserved")]
+
+
+class optorch_seq_config_t(C.Structure):
+    _fields_ = [
+        ("k_segments", C.c_int32), ("boundaries", C.POINTER(C.c_int32)), ("plan_mode", C.c_int32),
+        ("precision", C.c_int32), ("batch", C.c_int32), ("height", C.c_int32), ("width", C.c_int32),
+        ("channels", C.c_int32), ("num_classes", C.c_int32), ("activation_budget_bytes", C.c_uint64),
+        ("momentum", C.c_float), ("bn_eps", C.c_float), ("bn_momentum", C.c_float),
+        ("loss_scale_init", C.c_float), ("scale_growth", C.c_float), ("scale_backoff", C.c_float),
+        ("growth_interval", C.c_int32),
+    ]
+
+
+_lib = None
+
+
+def load_library() -> C.CDLL:
+    """Loads the HIP library built in-tree; raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError("%s not found: build it with `python -m paper_2105_00619_amd.build` "
+                          "(there is no CPU fallback)" % LIB_PATH)
+    lib = C.CDLL(LIB_PATH)
+    H = C.c_void_p
+    lib.optorch_seq_create.argtypes = [C.POINTER(optorch_unit_t), C.c_int32, C.POINTER(optorch_seq_config_t), C.POINTER(H)]
+    lib.optorch_seq_create.restype = C.c_int
+    lib.optorch_seq_query.argtypes = [H, C.POINTER(C.c_uint64), C.POINTER(C.c_uint64), C.POINTER(C.c_uint64),
+                                      C.POINTER(C.c_uint64), C.POINTER(C.c_int32)]
+    lib.optorch_seq_query.restype = C.c_int
+    lib.optorch_seq_bind.argtypes = [H, C.c_void_p, C.c_uint64, C.c_void_p, C.c_uint64, C.c_void_p]
+    lib.optorch_seq_bind.restype = C.c_int
+    lib.optorch_seq_set_params.argtypes = [H, C.c_void_p, C.c_uint64, C.c_int32]
+    lib.optorch_seq_set_params.restype = C.c_int
+    lib.optorch_seq_get_params.argtypes = [H, C.c_void_p, C.c_uint64, C.c_int32]
+    lib.optorch_seq_get_params.restype = C.c_int
+    lib.optorch_seq_step.argtypes = [H, C.c_void_p, C.c_void_p, C.c_float, C.POINTER(C.c_float), C.c_void_p,
+                                     C.POINTER(C.c_uint64), C.POINTER(C.c_uint64), C.POINTER(C.c_float),
+                                     C.POINTER(C.c_int32)]
+    lib.optorch_seq_step.restype = C.c_int
+    lib.optorch_seq_schedule_info.argtypes = [H, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
+    lib.optorch_seq_schedule_info.restype = C.c_int
+    lib.optorch_seq_last_error.argtypes = [H]
+    lib.optorch_seq_last_error.restype = C.c_char_p
+    lib.optorch_seq_destroy.argtypes = [H]
+    lib.optorch_seq_destroy.restype = None
+    _lib = lib
+    return lib
+
+
+class OptorchError(RuntimeError):
+    def __init__(self, code: int, message: str):
+        super().__init__("optorch_seq error %d: %s" % (code, message))
+        self.code = code
+
+
+class SeqPlan:
+    """optorch_seq_create + optorch_seq_query: host-side plan, no device needed."""
+
+    def __init__(self, units: Sequence, *, k_segments: int, precision: int, batch: int, height: int, width: int,
+                 channels: int, num_classes: int, boundaries: Optional[Sequence[int]] = None, plan_mode: int = 0,
+                 activation_budget_bytes: int = 0, momentum: float = 0.0, bn_eps: float = 0.0, bn_momentum: float = 0.0,
+                 loss_scale_init: float = 0.0, scale_growth: float = 0.0, scale_backoff: float = 0.0,
+                 growth_interval: int = 0):
+        self.lib = load_library()
+        self.handle = C.c_void_p()
+        arr = (optorch_unit_t * len(units))()
+        for i, u in enumerate(units):
+            arr[i] = optorch_unit_t(u.kind, u.cin, u.cout, u.ksize, u.stride, u.pad, u.has_bn, u.has_relu, u.has_bias, 0)
+        cfg = optorch_seq_config_t()
+        cfg.k_segments = k_segments
+        barr = None
+        if boundaries is not None:
+            barr = (C.c_int32 * max(1, len(boundaries)))(*boundaries)
+            cfg.boundaries = C.cast(barr, C.POINTER(C.c_int32))
+        cfg.plan_mode, cfg.precision = plan_mode, precision
+        cfg.batch, cfg.height, cfg.width, cfg.channels, cfg.num_classes = batch, height, width, channels, num_classes
+        cfg.activation_budget_bytes = activation_budget_bytes
+        cfg.momentum, cfg.bn_eps, cfg.bn_momentum = momentum, bn_eps, bn_momentum
+        cfg.loss_scale_init, cfg.scale_growth, cfg.scale_backoff = loss_scale_init, scale_growth, scale_backoff
+        cfg.growth_interval = growth_interval
+        rc = self.lib.optorch_seq_create(arr, len(units), C.byref(cfg), C.byref(self.handle))
+        if rc != OK:
+            msg = self.lib.optorch_seq_last_error(None).decode()
+            self.handle = C.c_void_p()
+            raise OptorchError(rc, msg)
+        self.k_segments = k_segments
+        self.batch, self.height, self.width, self.channels = batch, height, width, channels
+        pc, pb, ab, ps = C.c_uint64(), C.c_uint64(), C.c_uint64(), C.c_uint64()
+        bo = (C.c_int32 * max(1, k_segments - 1))()
+        self._check(self.lib.optorch_seq_query(self.handle, C.byref(pc), C.byref(pb), C.byref(ab), C.byref(ps), bo))
+        self.param_count, self.param_arena_bytes = pc.value, pb.value
+        self.act_arena_bytes, self.planned_peak_saved_bytes = ab.value, ps.value
+        self.boundaries = [bo[i] for i in range(k_segments - 1)]
+        nl, nr = C.c_int32(), C.c_int32()
+        self._check(self.lib.optorch_seq_schedule_info(self.handle, C.byref(nl), C.byref(nr)))
+        self.n_launches, self.n_replay_launches = nl.value, nr.value
+
+    @classmethod
+    def from_workload(cls, w, **override):
+        kw = dict(k_segments=w.k_segments, precision=w.precision, batch=w.batch, height=w.height, width=w.width,
+                  channels=w.channels, num_classes=w.classes, plan_mode=w.plan_mode,
+                  activation_budget_bytes=w.budget_bytes, momentum=w.momentum, loss_scale_init=w.loss_scale_init)
+        kw.update(override)
+        return cls(w.units, **kw)
+
+    def _check(self, rc: int):
+        if rc != OK:
+            raise OptorchError(rc, self.lib.optorch_seq_last_error(self.handle).decode())
+
+    def close(self):
+        if getattr(self, "handle", None) and self.handle.value:
+            self.lib.optorch_seq_destroy(self.handle)
+            self.handle = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class SeqTrainer(SeqPlan):
+    """A bound plan: device arenas allocated through torch, steps run on torch's current stream."""
+
+    def __init__(self, units, *, device="cuda:0", **kw):
+        import torch
+        super().__init__(units, **kw)
+        self.torch = torch
+        self.device = torch.device(device)
+        if not torch.cuda.is_available():
+            raise RuntimeError("no GPU visible: the training step only runs on the HIP path")
+        self.param_arena = torch.empty(self.param_arena_bytes + 256, dtype=torch.uint8, device=self.device)
+        self.act_arena = torch.empty(self.act_arena_bytes + 256, dtype=torch.uint8, device=self.device)
+        self.stream = torch.cuda.current_stream(self.device)
+        pa = (self.param_arena.data_ptr() + 255) // 256 * 256
+        aa = (self.act_arena.data_ptr() + 255) // 256 * 256
+        self._check(self.lib.optorch_seq_bind(self.handle, pa, self.param_arena_bytes, aa, self.act_arena_bytes,
+                                              self.stream.cuda_stream))
+
+    @classmethod
+    def from_workload(cls, w, device="cuda:0", **override):
+        kw = dict(k_segments=w.k_segments, precision=w.precision, batch=w.batch, height=w.height, width=w.width,
+                  channels=w.channels, num_classes=w.classes, plan_mode=w.plan_mode,
+                  activation_budget_bytes=w.budget_bytes, momentum=w.momentum, loss_scale_init=w.loss_scale_init)
+        kw.update(override)
+        return cls(w.units, device=device, **kw)
+
+    def set_params(self, params):
+        torch = self.torch
+        if isinstance(params, np.ndarray):
+            p = np.ascontiguousarray(params, dtype=np.float32)
+            self._check(self.lib.optorch_seq_set_params(self.handle, p.ctypes.data, p.size, 0))
+        else:
+            p = params.to(device=self.device, dtype=torch.float32).contiguous()
+            self._check(self.lib.optorch_seq_set_params(self.handle, p.data_ptr(), p.numel(), 1))
+
+    def get_params(self) -> np.ndarray:
+        out = np.empty(self.param_count, dtype=np.float32)
+        self._check(self.lib.optorch_seq_get_params(self.handle, out.ctypes.data, out.size, 0))
+        return out
+
+    def step(self, x, y, lr: float, grads=None) -> dict:
+        """x: cuda float32 NHWC tensor, y: cuda int32 tensor, grads: optional cuda float32 tensor (param_count)."""
+        torch = self.torch
+        assert x.is_cuda and x.dtype == torch.float32 and x.is_contiguous()
+        assert tuple(x.shape) == (self.batch, self.height, self.width, self.channels)
+        assert y.is_cuda and y.dtype == torch.int32 and y.numel() == self.batch
+        if grads is not None:
+            assert grads.is_cuda and grads.dtype == torch.float32 and grads.numel() == self.param_count
+        loss, scale, skipped = C.c_float(), C.c_float(), C.c_int32()
+        ps, pa = C.c_uint64(), C.c_uint64()
+        self._check(self.lib.optorch_seq_step(self.handle, x.data_ptr(), y.data_ptr(), lr, C.byref(loss),
+                                              grads.data_ptr() if grads is not None else None, C.byref(ps), C.byref(pa),
+                                              C.byref(scale), C.byref(skipped)))
+        return {"loss": loss.value, "peak_saved_bytes": ps.value, "peak_arena_bytes": pa.value,
+                "loss_scale": scale.value, "skipped": bool(skipped.value)}

@@ -1,0 +1,287 @@
+// C ABI of the checkpointed training step: plan on create, borrow device arenas on bind, walk the static
+// schedule on step.  See include/optorch_seq.h for the contract of every entry point.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstring>
+#include <new>
+#include <string>
+
+#include "kernels.h"
+#include "optorch_seq.h"
+#include "plan.h"
+
+using namespace oseq;
+
+struct optorch_seq {
+  Plan plan;
+  char* pbase = nullptr; uint64_t pbytes = 0;
+  char* abase = nullptr; uint64_t abytes = 0;
+  hipStream_t stream = nullptr;
+  uint64_t off_w = 0, off_v = 0, off_g = 0, off_h = 0, off_run = 0, off_scal = 0, param_arena_bytes = 0;
+  bool bound = false, params_set = false;
+  int dt = 0;
+  float scale = 1.f, scale_init = 1.f, growth = 2.f, backoff = 0.5f, eps = 1e-5f, bn_mom = 0.1f, momentum = 0.f;
+  int growth_interval = 0, clean = 0;
+  bool dynamic_scale = false;
+  float* host_rb = nullptr;  // pinned read-back buffer: loss + flags
+  mutable std::string err;
+};
+
+static thread_local std::string g_create_error;
+
+static int set_err(const optorch_seq_t* h, int code, const std::string& m) { h->err = m; return code; }
+
+static int hip_fail(const optorch_seq_t* h, hipError_t e, const char* what) {
+  return set_err(h, OPTORCH_E_HIP, std::string(what) + ": " + hipGetErrorString(e));
+}
+
+extern "C" int optorch_seq_create(const optorch_unit_t* units, int32_t n_units, const optorch_seq_config_t* cfg,
+                                  optorch_seq_t** out) {
+  if (out) *out = nullptr;
+  if (!units || !cfg || !out || n_units < 1) { g_create_error = "null argument or empty unit list"; return OPTORCH_E_INVALID; }
+  optorch_seq_t* h = new (std::nothrow) optorch_seq();
+  if (!h) { g_create_error = "out of host memory"; return OPTORCH_E_INVALID; }
+  Plan& p = h->plan;
+  p.units.assign(units, units + n_units);
+  p.cfg = *cfg;
+  std::vector<int32_t> bcopy;
+  if (cfg->boundaries && cfg->k_segments > 1) {
+    bcopy.assign(cfg->boundaries, cfg->boundaries + (cfg->k_segments - 1));
+    p.cfg.boundaries = bcopy.data();
+  } else {
+    p.cfg.boundaries = nullptr;
+  }
+  bool ok = build_graph(p) && choose_segments(p) && build_schedule(p);
+  p.cfg.boundaries = nullptr;  // the copy dies with this call; seg_begin holds the result
+  if (!ok) { g_create_error = p.error; delete h; return OPTORCH_E_INVALID; }
+  if (cfg->activation_budget_bytes && p.arena_bytes > cfg->activation_budget_bytes) {
+    g_create_error = "planned activation arena of " + std::to_string(p.arena_bytes) + " bytes exceeds the budget of " +
+                     std::to_string(cfg->activation_budget_bytes) + " bytes";
+    delete h;
+    return OPTORCH_E_BUDGET;
+  }
+  h->dt = cfg->precision;
+  h->eps = cfg->bn_eps > 0 ? cfg->bn_eps : 1e-5f;
+  h->bn_mom = cfg->bn_momentum > 0 ? cfg->bn_momentum : 0.1f;
+  h->momentum = cfg->momentum;
+  h->growth = cfg->scale_growth > 0 ? cfg->scale_growth : 2.f;
+  h->backoff = cfg->scale_backoff > 0 ? cfg->scale_backoff : 0.5f;
+  h->scale_init = cfg->loss_scale_init > 0 ? cfg->loss_scale_init : (cfg->precision == OPTORCH_FP16 ? 65536.f : 1.f);
+  h->growth_interval = cfg->growth_interval > 0 ? cfg->growth_interval : (cfg->precision == OPTORCH_FP16 ? 2000 : 0);
+  h->dynamic_scale = h->growth_interval > 0;
+  h->scale = h->scale_init;
+  const uint64_t P = p.n_params;
+  uint64_t o = 0;
+  h->off_w = o; o = align_up(o + P * 4);
+  h->off_v = o; o = align_up(o + P * 4);
+  h->off_g = o; o = align_up(o + P * 4);
+  h->off_h = o; if (h->dt != DT_F32) o = align_up(o + P * 2);
+  h->off_run = o; o = align_up(o + p.n_running * 4);
+  h->off_scal = o; o = align_up(o + 256);
+  h->param_arena_bytes = o;
+  *out = h;
+  return OPTORCH_OK;
+}
+
+extern "C" int optorch_seq_query(const optorch_seq_t* h, uint64_t* param_count, uint64_t* param_arena_bytes,
+                                 uint64_t* act_arena_bytes, uint64_t* planned_peak_saved_bytes, int32_t* boundaries_out) {
+  if (!h) return OPTORCH_E_INVALID;
+  if (param_count) *param_count = h->plan.n_params;
+  if (param_arena_bytes) *param_arena_bytes = h->param_arena_bytes;
+  if (act_arena_bytes) *act_arena_bytes = h->plan.arena_bytes;
+  if (planned_peak_saved_bytes) *planned_peak_saved_bytes = h->plan.peak_saved_bytes;
+  if (boundaries_out)
+    for (size_t j = 1; j + 1 < h->plan.seg_begin.size(); ++j) boundaries_out[j - 1] = h->plan.seg_begin[j];
+  return OPTORCH_OK;
+}
+
+extern "C" int optorch_seq_schedule_info(const optorch_seq_t* h, int32_t* n_launch_records, int32_t* n_replay_records) {
+  if (!h) return OPTORCH_E_INVALID;
+  if (n_launch_records) *n_launch_records = h->plan.n_launches;
+  if (n_replay_records) *n_replay_records = h->plan.n_replay_launches;
+  return OPTORCH_OK;
+}
+
+extern "C" int optorch_seq_bind(optorch_seq_t* h, void* param_arena_dev, uint64_t param_arena_bytes, void* act_arena_dev,
+                                uint64_t act_arena_bytes, void* hip_stream) {
+  if (!h) return OPTORCH_E_INVALID;
+  if (!param_arena_dev || !act_arena_dev) return set_err(h, OPTORCH_E_INVALID, "null arena pointer");
+  if (((uintptr_t)param_arena_dev | (uintptr_t)act_arena_dev) & (kAlign - 1))
+    return set_err(h, OPTORCH_E_INVALID, "arena pointers must be 256-byte aligned");
+  if (param_arena_bytes < h->param_arena_bytes) return set_err(h, OPTORCH_E_BUDGET, "parameter arena too small");
+  if (act_arena_bytes < h->plan.arena_bytes) return set_err(h, OPTORCH_E_BUDGET, "activation arena smaller than the planned peak");
+  if (!h->host_rb) {
+    hipError_t e = hipHostMalloc((void**)&h->host_rb, 256, hipHostMallocDefault);
+    if (e != hipSuccess) return hip_fail(h, e, "hipHostMalloc");
+  }
+  h->pbase = (char*)param_arena_dev; h->pbytes = param_arena_bytes;
+  h->abase = (char*)act_arena_dev; h->abytes = act_arena_bytes;
+  h->stream = (hipStream_t)hip_stream;
+  h->bound = true;
+  h->params_set = false;
+  return OPTORCH_OK;
+}
+
+extern "C" int optorch_seq_set_params(optorch_seq_t* h, const float* src, uint64_t n, int32_t is_device) {
+  if (!h) return OPTORCH_E_INVALID;
+  if (!h->bound) return set_err(h, OPTORCH_E_ORDER, "set_params before bind");
+  if (!src || n != h->plan.n_params) return set_err(h, OPTORCH_E_INVALID, "set_params: wrong parameter count");
+  hipStream_t st = h->stream;
+  hipError_t e = hipMemcpyAsync(h->pbase + h->off_w, src, n * 4, is_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice, st);
+  if (e != hipSuccess) return hip_fail(h, e, "hipMemcpyAsync(params)");
+  launch_fill(st, (float*)(h->pbase + h->off_v), (int64_t)n, 0.f);
+  launch_fill(st, (float*)(h->pbase + h->off_g), (int64_t)n, 0.f);
+  // running statistics: mean 0, variance 1, per BatchNorm as (mean[C], var[C])
+  for (const FOp& f : h->plan.fops)
+    if (f.kind == F_BN_STATS) {
+      float* r = (float*)(h->pbase + h->off_run) + f.rs_off;
+      launch_fill(st, r, f.C, 0.f);
+      launch_fill(st, r + f.C, f.C, 1.f);
+    }
+  launch_fill(st, (float*)(h->pbase + h->off_scal), 64, 0.f);
+  launch_cast_params(st, h->dt, (const float*)(h->pbase + h->off_w), h->pbase + h->off_h, (int64_t)n);
+  e = hipStreamSynchronize(st);
+  if (e != hipSuccess) return hip_fail(h, e, "hipStreamSynchronize");
+  e = hipGetLastError();
+  if (e != hipSuccess) return hip_fail(h, e, "set_params kernels");
+  h->scale = h->scale_init; h->clean = 0;
+  h->params_set = true;
+  return OPTORCH_OK;
+}
+
+extern "C" int optorch_seq_get_params(const optorch_seq_t* h, float* dst, uint64_t n, int32_t is_device) {
+  if (!h) return OPTORCH_E_INVALID;
+  if (!h->bound || !h->params_set) return set_err(h, OPTORCH_E_ORDER, "get_params before bind/set_params");
+  if (!dst || n != h->plan.n_params) return set_err(h, OPTORCH_E_INVALID, "get_params: wrong parameter count");
+  hipError_t e = hipStreamSynchronize(h->stream);
+  if (e != hipSuccess) return hip_fail(h, e, "hipStreamSynchronize");
+  e = hipMemcpy(dst, h->pbase + h->off_w, n * 4, is_device ? hipMemcpyDeviceToDevice : hipMemcpyDeviceToHost);
+  if (e != hipSuccess) return hip_fail(h, e, "hipMemcpy(params)");
+  return OPTORCH_OK;
+}
+
+namespace {
+
+struct Ctx {
+  optorch_seq_t* h;
+  const float* x; const int32_t* y;
+  void* at(int inst) const { return inst < 0 ? nullptr : (void*)(h->abase + h->plan.insts[inst].offset); }
+  float* w32(int64_t off) const { return (float*)(h->pbase + h->off_w) + off; }
+  float* g32(int64_t off) const { return (float*)(h->pbase + h->off_g) + off; }
+  const void* wc(int64_t off) const {  // weights in the compute type
+    return h->dt == DT_F32 ? (const void*)w32(off) : (const void*)(h->pbase + h->off_h + off * 2);
+  }
+  int* flags() const { return (int*)(h->pbase + h->off_scal + 64); }
+  float* loss() const { return (float*)(h->pbase + h->off_scal); }
+};
+
+ConvGeom geom(const FOp& f) { return ConvGeom{f.N, f.H, f.W, f.C, f.K, f.R, f.S, f.stride, f.pad, f.P, f.Q}; }
+
+void run_op(const Ctx& c, const SOp& s) {
+  optorch_seq_t* h = c.h;
+  const FOp& f = h->plan.fops[s.fop];
+  hipStream_t st = h->stream;
+  const int dt = h->dt;
+  switch (s.kind) {
+    case S_CAST_IN:
+      launch_cast_in(st, dt, c.x, c.at(s.out[0]), (int64_t)f.N * f.H * f.W * f.C);
+      break;
+    case S_CONV_FWD:
+      launch_conv_fwd_direct(st, dt, c.at(s.in[0]), c.wc(f.w_off), f.has_bias ? c.w32(f.b_off) : nullptr, c.at(s.out[0]),
+                             geom(f), f.relu);
+      break;
+    case S_BN_STATS:
+      launch_bn_stats(st, dt, c.at(s.in[0]), (int64_t)f.N * f.P * f.Q, f.C, f.red_blocks, (float*)c.at(s.out[1]), h->eps,
+                      h->bn_mom, c.w32(f.gamma_off), c.w32(f.beta_off), (float*)c.at(s.out[0]),
+                      (float*)(h->pbase + h->off_run) + f.rs_off);
+      break;
+    case S_BN_APPLY:
+      launch_bn_apply(st, dt, c.at(s.in[0]), (const float*)c.at(s.in[1]), c.at(s.in[2]), c.at(s.out[0]),
+                      (int64_t)f.N * f.P * f.Q, f.C, f.relu);
+      break;
+    case S_POOL_FWD:
+      launch_maxpool_fwd(st, dt, c.at(s.in[0]), c.at(s.out[0]), f.N, f.H, f.W, f.C);
+      break;
+    case S_HEAD_FWD:
+      launch_head_fwd(st, dt, c.at(s.in[0]), f.N, f.H * f.W, f.C, f.gap, f.feat_dim, f.classes, c.w32(f.w_off),
+                      c.w32(f.b_off), c.y, h->scale / (float)f.N, (float*)c.at(s.out[0]), (float*)c.at(s.out[1]),
+                      (float*)c.at(s.out[2]), (float*)c.at(s.out[3]), c.loss(), c.flags());
+      break;
+    case S_HEAD_BWD:
+      launch_head_bwd(st, dt, (const float*)c.at(s.in[0]), (const float*)c.at(s.in[1]), c.w32(f.w_off), f.N, f.H * f.W, f.C,
+                      f.gap, f.feat_dim, f.classes, c.g32(f.w_off), c.g32(f.b_off), (float*)c.at(s.out[1]), c.at(s.out[0]));
+      break;
+    case S_BN_BWD:
+      launch_bn_bwd(st, dt, c.at(s.in[0]), c.at(s.in[1]), c.at(s.in[3]), (const float*)c.at(s.in[2]),
+                    (int64_t)f.N * f.P * f.Q, f.C, f.relu, f.red_blocks, (float*)c.at(s.out[2]), c.g32(f.gamma_off),
+                    c.g32(f.beta_off), c.at(s.out[0]), c.at(s.out[1]));
+      break;
+    case S_RELU_BWD:
+      launch_relu_bwd(st, dt, c.at(s.in[0]), c.at(s.in[1]), c.at(s.out[0]), (int64_t)f.N * f.P * f.Q, f.K);
+      break;
+    case S_BIAS_GRAD:
+      launch_bias_grad(st, dt, c.at(s.in[0]), (int64_t)f.N * f.P * f.Q, f.K, f.red_blocks, (float*)c.at(s.out[0]),
+                       c.g32(f.b_off));
+      break;
+    case S_WGRAD:
+      launch_conv_wgrad_direct(st, dt, c.at(s.in[0]), c.at(s.in[1]), c.g32(f.w_off), (float*)c.at(s.out[0]), f.wgrad_splits,
+                               geom(f));
+      break;
+    case S_DGRAD:
+      launch_conv_dgrad_direct(st, dt, c.at(s.in[0]), c.wc(f.w_off), c.at(s.in[1]), c.at(s.out[0]), geom(f));
+      break;
+    case S_POOL_BWD:
+      launch_maxpool_bwd(st, dt, c.at(s.in[0]), c.at(s.in[1]), c.at(s.out[0]), f.N, f.H, f.W, f.C);
+      break;
+  }
+}
+
+}  // namespace
+
+extern "C" int optorch_seq_step(optorch_seq_t* h, const float* x_dev, const int32_t* y_dev, float lr, float* loss_out,
+                                float* grads_dev, uint64_t* peak_saved_bytes, uint64_t* peak_arena_bytes,
+                                float* loss_scale_out, int32_t* step_skipped) {
+  if (!h) return OPTORCH_E_INVALID;
+  if (!h->bound || !h->params_set) return set_err(h, OPTORCH_E_ORDER, "step before bind/set_params");
+  if (!x_dev || !y_dev) return set_err(h, OPTORCH_E_INVALID, "null input pointer");
+  if (!std::isfinite(lr)) return set_err(h, OPTORCH_E_INVALID, "learning rate is not finite");
+  Ctx c{h, x_dev, y_dev};
+  hipStream_t st = h->stream;
+  launch_step_init(st, c.flags());
+  for (const SOp& s : h->plan.sched)
+    if (s.live) run_op(c, s);
+  const int64_t P = (int64_t)h->plan.n_params;
+  launch_optim(st, h->dt, c.w32(0), (float*)(h->pbase + h->off_v), c.g32(0), h->pbase + h->off_h, grads_dev, P, lr,
+               h->momentum, 1.f / h->scale, c.flags());
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return hip_fail(h, e, "kernel launch");
+  e = hipMemcpyAsync(h->host_rb, h->pbase + h->off_scal, 128, hipMemcpyDeviceToHost, st);
+  if (e != hipSuccess) return hip_fail(h, e, "hipMemcpyAsync(read-back)");
+  e = hipStreamSynchronize(st);
+  if (e != hipSuccess) return hip_fail(h, e, "hipStreamSynchronize");
+  const int* fl = (const int*)((const char*)h->host_rb + 64);
+  if (fl[1]) return set_err(h, OPTORCH_E_INVALID, "a label is outside [0, num_classes)");
+  const bool skipped = fl[0] != 0;
+  if (skipped) {
+    if (h->dynamic_scale) h->scale *= h->backoff;
+    h->clean = 0;
+  } else if (h->dynamic_scale && ++h->clean == h->growth_interval) {
+    h->scale *= h->growth;
+    h->clean = 0;
+  }
+  if (loss_out) *loss_out = h->host_rb[0];
+  if (peak_saved_bytes) *peak_saved_bytes = h->plan.peak_saved_bytes;
+  if (peak_arena_bytes) *peak_arena_bytes = h->plan.arena_bytes;
+  if (loss_scale_out) *loss_scale_out = h->scale;
+  if (step_skipped) *step_skipped = skipped ? 1 : 0;
+  return OPTORCH_OK;
+}
+
+extern "C" const char* optorch_seq_last_error(const optorch_seq_t* h) { return h ? h->err.c_str() : g_create_error.c_str(); }
+
+extern "C" void optorch_seq_destroy(optorch_seq_t* h) {
+  if (!h) return;
+  if (h->host_rb) (void)hipHostFree(h->host_rb);
+  delete h;
+}

@@ -1,0 +1,48 @@
+// Device-side helpers shared by the HIP kernels: storage types, conversions, vector loads.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "kernels.h"
+
+namespace oseq {
+
+typedef _Float16 f16_t;
+typedef __bf16 bf16_t;
+
+__device__ __forceinline__ float to_f32(float v) { return v; }
+__device__ __forceinline__ float to_f32(f16_t v) { return (float)v; }
+__device__ __forceinline__ float to_f32(bf16_t v) { return (float)v; }
+
+template <class T> __device__ __forceinline__ T from_f32(float v);
+template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ f16_t from_f32<f16_t>(float v) { return (f16_t)v; }    // round to nearest even
+template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float v) { return (bf16_t)v; }  // round to nearest even
+
+// V consecutive elements of T, loaded and stored as one access.
+template <class T, int V>
+struct alignas(sizeof(T) * V) Vec {
+  T v[V];
+};
+
+template <class T, int V>
+__device__ __forceinline__ void load_f32(const T* p, float (&out)[V]) {
+  Vec<T, V> t = *reinterpret_cast<const Vec<T, V>*>(p);
+#pragma unroll
+  for (int i = 0; i < V; ++i) out[i] = to_f32(t.v[i]);
+}
+template <class T, int V>
+__device__ __forceinline__ void store_f32(T* p, const float (&in)[V]) {
+  Vec<T, V> t;
+#pragma unroll
+  for (int i = 0; i < V; ++i) t.v[i] = from_f32<T>(in[i]);
+  *reinterpret_cast<Vec<T, V>*>(p) = t;
+}
+
+// The BatchNorm affine map; the same instruction sequence in forward and backward so that the
+// ReLU mask rebuilt in backward equals the one applied in forward, bit for bit.
+__device__ __forceinline__ float bn_affine(float z, float scale, float shift) { return __fmaf_rn(z, scale, shift); }
+
+inline int ceil_div(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
+
+}  // namespace oseq

@@ -1,0 +1,386 @@
+// HBM-bound kernels over NHWC tensors viewed as [rows = N*H*W][C]:
+//   input cast, per-channel reductions (BatchNorm statistics, BatchNorm backward sums, bias gradient),
+//   BatchNorm apply (+skip, +ReLU), BatchNorm backward apply, ReLU backward, 2x2 max-pool forward/backward.
+// Every lane moves 16 bytes per access along the channel axis; per-channel sums are reduced in a fixed
+// order (lane-private partials -> LDS -> one partial row per block -> one finishing thread per channel,
+// in double), so results do not depend on scheduling.
+#include "dev_common.h"
+#include "kernels.h"
+
+namespace oseq {
+
+// ------------------------------------------------------------------ cast ----
+template <class T>
+__global__ void cast_in_kernel(const float* __restrict__ x, T* __restrict__ out, int64_t n) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) out[i] = from_f32<T>(x[i]);
+}
+
+// ----------------------------------------------------- column reductions ----
+enum { RED_STATS = 0, RED_BN_BWD = 1, RED_BIAS = 2 };
+
+struct RedArgs {
+  const void* a;       // STATS: z ; BN_BWD: dA ; BIAS: dz
+  const void* z;       // BN_BWD: z
+  const void* aout;    // BN_BWD with skip: block output (ReLU mask source); else null
+  const float* stats;  // BN_BWD: [4][C] mean, rstd, scale, shift
+  float* partial;      // [nblk][2][C]
+  int64_t rows;
+  int C, relu, nblk, rows_per_block;
+};
+
+template <class T, int V, int MODE>
+__global__ void __launch_bounds__(256) colreduce_kernel(RedArgs g) {
+  extern __shared__ float smem[];  // [2][TY][TX*V]
+  const int CG = g.C / V;
+  const int TX = CG < 256 ? CG : 256;
+  const int TY = 256 / TX;
+  const int tx = threadIdx.x % TX, ty = threadIdx.x / TX;
+  const int cg = blockIdx.y * TX + tx;
+  const bool active = cg < CG && ty < TY;
+  const int c0 = cg * V;
+  float s0[V], s1[V];
+#pragma unroll
+  for (int i = 0; i < V; ++i) s0[i] = s1[i] = 0.f;
+  float mean[V], rstd[V], scale[V], shift[V];
+  if (MODE == RED_BN_BWD && active) {
+#pragma unroll
+    for (int i = 0; i < V; ++i) {
+      mean[i] = g.stats[c0 + i]; rstd[i] = g.stats[g.C + c0 + i];
+      scale[i] = g.stats[2 * g.C + c0 + i]; shift[i] = g.stats[3 * g.C + c0 + i];
+    }
+  }
+  const int64_t r0 = (int64_t)blockIdx.x * g.rows_per_block;
+  const int64_t r1 = r0 + g.rows_per_block < g.rows ? r0 + g.rows_per_block : g.rows;
+  if (active) {
+    const T* a = static_cast<const T*>(g.a);
+    const T* z = static_cast<const T*>(g.z);
+    const T* ao = static_cast<const T*>(g.aout);
+    for (int64_t r = r0 + ty; r < r1; r += TY) {
+      const int64_t off = r * g.C + c0;
+      float va[V];
+      load_f32<T, V>(a + off, va);
+      if (MODE == RED_STATS) {
+#pragma unroll
+        for (int i = 0; i < V; ++i) { s0[i] += va[i]; s1[i] = __fmaf_rn(va[i], va[i], s1[i]); }
+      } else if (MODE == RED_BIAS) {
+#pragma unroll
+        for (int i = 0; i < V; ++i) s0[i] += va[i];
+      } else {
+        float vz[V], vo[V];
+        load_f32<T, V>(z + off, vz);
+        if (ao) load_f32<T, V>(ao + off, vo);
+#pragma unroll
+        for (int i = 0; i < V; ++i) {
+          bool on = true;
+          if (g.relu) on = ao ? (vo[i] > 0.f) : (bn_affine(vz[i], scale[i], shift[i]) > 0.f);
+          const float dy = on ? va[i] : 0.f;
+          const float xh = (vz[i] - mean[i]) * rstd[i];
+          s0[i] += dy; s1[i] = __fmaf_rn(dy, xh, s1[i]);
+        }
+      }
+    }
+  }
+  const int W = TX * V;
+  if (active) {
+#pragma unroll
+    for (int i = 0; i < V; ++i) { smem[ty * W + tx * V + i] = s0[i]; smem[(TY + ty) * W + tx * V + i] = s1[i]; }
+  }
+  __syncthreads();
+  if (active && ty == 0) {
+#pragma unroll
+    for (int i = 0; i < V; ++i) {
+      float t0 = 0.f, t1 = 0.f;
+      for (int y = 0; y < TY; ++y) { t0 += smem[y * W + tx * V + i]; t1 += smem[(TY + y) * W + tx * V + i]; }
+      g.partial[((int64_t)blockIdx.x * 2 + 0) * g.C + c0 + i] = t0;
+      g.partial[((int64_t)blockIdx.x * 2 + 1) * g.C + c0 + i] = t1;
+    }
+  }
+}
+
+template <class T, int MODE>
+static void launch_colreduce_t(hipStream_t st, const RedArgs& g0) {
+  RedArgs g = g0;
+  const int vmax = 16 / (int)sizeof(T);
+  const int V = (g.C % vmax == 0) ? vmax : 1;
+  const int CG = g.C / V;
+  const int TX = CG < 256 ? CG : 256;
+  const int TY = 256 / TX;
+  g.rows_per_block = ceil_div(g.rows, g.nblk);
+  dim3 grid(g.nblk, ceil_div(CG, TX));
+  const size_t sm = (size_t)2 * TY * TX * V * sizeof(float);
+  if (V == vmax) hipLaunchKernelGGL((colreduce_kernel<T, 16 / sizeof(T), MODE>), grid, dim3(256), sm, st, g);
+  else hipLaunchKernelGGL((colreduce_kernel<T, 1, MODE>), grid, dim3(256), sm, st, g);
+}
+
+template <int MODE>
+static void launch_colreduce(hipStream_t st, int dt, const RedArgs& g) {
+  if (dt == DT_F32) launch_colreduce_t<float, MODE>(st, g);
+  else if (dt == DT_BF16) launch_colreduce_t<bf16_t, MODE>(st, g);
+  else launch_colreduce_t<f16_t, MODE>(st, g);
+}
+
+// finishing kernels: one thread per channel sums the block partials in order, in double
+__global__ void bn_stats_finalize_kernel(const float* __restrict__ partial, int nblk, int C, double m, float eps,
+                                         float mom, const float* __restrict__ gamma, const float* __restrict__ beta,
+                                         float* __restrict__ stats, float* __restrict__ running) {
+  const int c = blockIdx.x * blockDim.x + threadIdx.x;
+  if (c >= C) return;
+  double s = 0.0, q = 0.0;
+  for (int b = 0; b < nblk; ++b) { s += (double)partial[((int64_t)b * 2) * C + c]; q += (double)partial[((int64_t)b * 2 + 1) * C + c]; }
+  const double mean = s / m;
+  double var = q / m - mean * mean;
+  if (var < 0.0) var = 0.0;
+  const double rstd = 1.0 / sqrt(var + (double)eps);
+  const float scale = (float)((double)gamma[c] * rstd);
+  const float fmean = (float)mean;
+  stats[c] = fmean;
+  stats[C + c] = (float)rstd;
+  stats[2 * C + c] = scale;
+  stats[3 * C + c] = (float)((double)beta[c] - mean * (double)gamma[c] * rstd);
+  if (running) {
+    const double unbiased = m > 1.0 ? var * m / (m - 1.0) : var;
+    running[c] = (float)((1.0 - mom) * (double)running[c] + mom * mean);
+    running[C + c] = (float)((1.0 - mom) * (double)running[C + c] + mom * unbiased);
+  }
+}
+
+__global__ void bn_bwd_finalize_kernel(const float* __restrict__ partial, int nblk, int C, double m,
+                                       float* __restrict__ dgamma, float* __restrict__ dbeta, float* __restrict__ coef) {
+  const int c = blockIdx.x * blockDim.x + threadIdx.x;
+  if (c >= C) return;
+  double s = 0.0, q = 0.0;
+  for (int b = 0; b < nblk; ++b) { s += (double)partial[((int64_t)b * 2) * C + c]; q += (double)partial[((int64_t)b * 2 + 1) * C + c]; }
+  dbeta[c] = (float)s;
+  dgamma[c] = (float)q;
+  coef[c] = (float)(s / m);
+  coef[C + c] = (float)(q / m);
+}
+
+__global__ void bias_finalize_kernel(const float* __restrict__ partial, int nblk, int C, float* __restrict__ dbias) {
+  const int c = blockIdx.x * blockDim.x + threadIdx.x;
+  if (c >= C) return;
+  double s = 0.0;
+  for (int b = 0; b < nblk; ++b) s += (double)partial[((int64_t)b * 2) * C + c];
+  dbias[c] = (float)s;
+}
+
+// ------------------------------------------------------------- BN apply -----
+template <class T, int V>
+__global__ void __launch_bounds__(256) bn_apply_kernel(const T* __restrict__ z, const float* __restrict__ stats,
+                                                       const T* __restrict__ skip, T* __restrict__ out, int64_t groups,
+                                                       int C, int relu) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= groups) return;
+  const int CG = C / V;
+  const int c0 = (int)(i % CG) * V;
+  const int64_t off = i * V;
+  float vz[V], vs[V], vo[V];
+  load_f32<T, V>(z + off, vz);
+  if (skip) load_f32<T, V>(skip + off, vs);
+#pragma unroll
+  for (int k = 0; k < V; ++k) {
+    float y = bn_affine(vz[k], stats[2 * C + c0 + k], stats[3 * C + c0 + k]);
+    if (skip) y = __fadd_rn(y, vs[k]);
+    vo[k] = relu ? fmaxf(y, 0.f) : y;
+  }
+  store_f32<T, V>(out + off, vo);
+}
+
+template <class T, int V>
+__global__ void __launch_bounds__(256) bn_bwd_apply_kernel(const T* __restrict__ da, const T* __restrict__ z,
+                                                           const T* __restrict__ aout, const float* __restrict__ stats,
+                                                           const float* __restrict__ coef, T* __restrict__ dz,
+                                                           T* __restrict__ dskip, int64_t groups, int C, int relu) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= groups) return;
+  const int CG = C / V;
+  const int c0 = (int)(i % CG) * V;
+  const int64_t off = i * V;
+  float va[V], vz[V], vo[V], rz[V], rs[V];
+  load_f32<T, V>(da + off, va);
+  load_f32<T, V>(z + off, vz);
+  if (aout) load_f32<T, V>(aout + off, vo);
+#pragma unroll
+  for (int k = 0; k < V; ++k) {
+    const int c = c0 + k;
+    const float mean = stats[c], rstd = stats[C + c], scale = stats[2 * C + c], shift = stats[3 * C + c];
+    bool on = true;
+    if (relu) on = aout ? (vo[k] > 0.f) : (bn_affine(vz[k], scale, shift) > 0.f);
+    const float dy = on ? va[k] : 0.f;
+    const float xh = (vz[k] - mean) * rstd;
+    rz[k] = scale * (dy - coef[c] - xh * coef[C + c]);
+    rs[k] = dy;
+  }
+  store_f32<T, V>(dz + off, rz);
+  if (dskip) store_f32<T, V>(dskip + off, rs);
+}
+
+template <class T, int V>
+__global__ void __launch_bounds__(256) relu_bwd_kernel(const T* __restrict__ da, const T* __restrict__ a,
+                                                       T* __restrict__ dz, int64_t groups) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= groups) return;
+  float va[V], vo[V], r[V];
+  load_f32<T, V>(da + i * V, va);
+  load_f32<T, V>(a + i * V, vo);
+#pragma unroll
+  for (int k = 0; k < V; ++k) r[k] = vo[k] > 0.f ? va[k] : 0.f;
+  store_f32<T, V>(dz + i * V, r);
+}
+
+// -------------------------------------------------------------- max-pool ----
+template <class T, int V>
+__global__ void __launch_bounds__(256) maxpool_fwd_kernel(const T* __restrict__ x, T* __restrict__ y, int N, int H, int W,
+                                                          int C, int P, int Q) {
+  const int CG = C / V;
+  const int64_t total = (int64_t)N * P * Q * CG;
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= total) return;
+  const int cg = (int)(i % CG);
+  int64_t t = i / CG;
+  const int q = (int)(t % Q); t /= Q;
+  const int p = (int)(t % P);
+  const int n = (int)(t / P);
+  const T* base = x + (((int64_t)n * H + 2 * p) * W + 2 * q) * C + cg * V;
+  float m[V], v[V];
+  load_f32<T, V>(base, m);
+  load_f32<T, V>(base + C, v);
+#pragma unroll
+  for (int k = 0; k < V; ++k) m[k] = v[k] > m[k] ? v[k] : m[k];
+  load_f32<T, V>(base + (int64_t)W * C, v);
+#pragma unroll
+  for (int k = 0; k < V; ++k) m[k] = v[k] > m[k] ? v[k] : m[k];
+  load_f32<T, V>(base + (int64_t)W * C + C, v);
+#pragma unroll
+  for (int k = 0; k < V; ++k) m[k] = v[k] > m[k] ? v[k] : m[k];
+  store_f32<T, V>(y + i * V, m);
+}
+
+// One thread per input position: the gradient of its window goes to the first maximum in scan order.
+template <class T, int V>
+__global__ void __launch_bounds__(256) maxpool_bwd_kernel(const T* __restrict__ x, const T* __restrict__ dy,
+                                                          T* __restrict__ dx, int N, int H, int W, int C, int P, int Q) {
+  const int CG = C / V;
+  const int64_t total = (int64_t)N * H * W * CG;
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= total) return;
+  const int cg = (int)(i % CG);
+  int64_t t = i / CG;
+  const int w = (int)(t % W); t /= W;
+  const int h = (int)(t % H);
+  const int n = (int)(t / H);
+  float r[V];
+#pragma unroll
+  for (int k = 0; k < V; ++k) r[k] = 0.f;
+  const int p = h >> 1, q = w >> 1;
+  if (p < P && q < Q) {
+    const T* base = x + (((int64_t)n * H + 2 * p) * W + 2 * q) * C + cg * V;
+    float m[V], v[V], g[V];
+    int arg[V];
+    load_f32<T, V>(base, m);
+#pragma unroll
+    for (int k = 0; k < V; ++k) arg[k] = 0;
+    load_f32<T, V>(base + C, v);
+#pragma unroll
+    for (int k = 0; k < V; ++k) if (v[k] > m[k]) { m[k] = v[k]; arg[k] = 1; }
+    load_f32<T, V>(base + (int64_t)W * C, v);
+#pragma unroll
+    for (int k = 0; k < V; ++k) if (v[k] > m[k]) { m[k] = v[k]; arg[k] = 2; }
+    load_f32<T, V>(base + (int64_t)W * C + C, v);
+#pragma unroll
+    for (int k = 0; k < V; ++k) if (v[k] > m[k]) { m[k] = v[k]; arg[k] = 3; }
+    load_f32<T, V>(dy + (((int64_t)n * P + p) * Q + q) * C + cg * V, g);
+    const int me = (h & 1) * 2 + (w & 1);
+#pragma unroll
+    for (int k = 0; k < V; ++k) r[k] = arg[k] == me ? g[k] : 0.f;
+  }
+  store_f32<T, V>(dx + i * V, r);
+}
+
+// ---------------------------------------------------------------- launch ----
+#define DISPATCH_TV(dt, C, CALL)                                               \
+  do {                                                                         \
+    if (dt == DT_F32) { if ((C) % 4 == 0) { CALL(float, 4); } else { CALL(float, 1); } } \
+    else if (dt == DT_BF16) { if ((C) % 8 == 0) { CALL(bf16_t, 8); } else { CALL(bf16_t, 1); } } \
+    else { if ((C) % 8 == 0) { CALL(f16_t, 8); } else { CALL(f16_t, 1); } }     \
+  } while (0)
+
+void launch_cast_in(hipStream_t st, int dt, const float* x, void* out, int64_t n) {
+  const int blocks = (int)((n + 255) / 256 < 4096 ? (n + 255) / 256 : 4096);
+  if (dt == DT_F32) hipLaunchKernelGGL(cast_in_kernel<float>, dim3(blocks), dim3(256), 0, st, x, (float*)out, n);
+  else if (dt == DT_BF16) hipLaunchKernelGGL(cast_in_kernel<bf16_t>, dim3(blocks), dim3(256), 0, st, x, (bf16_t*)out, n);
+  else hipLaunchKernelGGL(cast_in_kernel<f16_t>, dim3(blocks), dim3(256), 0, st, x, (f16_t*)out, n);
+}
+
+void launch_bn_stats(hipStream_t st, int dt, const void* z, int64_t rows, int C, int nblk, float* partial, float eps,
+                     float mom, const float* gamma, const float* beta, float* stats, float* running) {
+  RedArgs g{}; g.a = z; g.partial = partial; g.rows = rows; g.C = C; g.nblk = nblk;
+  launch_colreduce<RED_STATS>(st, dt, g);
+  hipLaunchKernelGGL(bn_stats_finalize_kernel, dim3(ceil_div(C, 128)), dim3(128), 0, st, partial, nblk, C, (double)rows,
+                     eps, mom, gamma, beta, stats, running);
+}
+
+void launch_bn_apply(hipStream_t st, int dt, const void* z, const float* stats, const void* skip, void* out, int64_t rows,
+                     int C, int relu) {
+#define CALL(T, V)                                                                                                   \
+  { const int64_t groups = rows * (C / V);                                                                            \
+    hipLaunchKernelGGL((bn_apply_kernel<T, V>), dim3(ceil_div(groups, 256)), dim3(256), 0, st, (const T*)z, stats,    \
+                       (const T*)skip, (T*)out, groups, C, relu); }
+  DISPATCH_TV(dt, C, CALL);
+#undef CALL
+}
+
+void launch_bn_bwd(hipStream_t st, int dt, const void* da, const void* z, const void* aout, const float* stats, int64_t rows,
+                   int C, int relu, int nblk, float* ws, float* dgamma, float* dbeta, void* dz, void* dskip) {
+  RedArgs g{}; g.a = da; g.z = z; g.aout = aout; g.stats = stats; g.partial = ws; g.rows = rows; g.C = C; g.relu = relu;
+  g.nblk = nblk;
+  launch_colreduce<RED_BN_BWD>(st, dt, g);
+  float* coef = ws + (int64_t)nblk * 2 * C;
+  hipLaunchKernelGGL(bn_bwd_finalize_kernel, dim3(ceil_div(C, 128)), dim3(128), 0, st, ws, nblk, C, (double)rows, dgamma,
+                     dbeta, coef);
+#define CALL(T, V)                                                                                                      \
+  { const int64_t groups = rows * (C / V);                                                                               \
+    hipLaunchKernelGGL((bn_bwd_apply_kernel<T, V>), dim3(ceil_div(groups, 256)), dim3(256), 0, st, (const T*)da,         \
+                       (const T*)z, (const T*)aout, stats, coef, (T*)dz, (T*)dskip, groups, C, relu); }
+  DISPATCH_TV(dt, C, CALL);
+#undef CALL
+}
+
+void launch_relu_bwd(hipStream_t st, int dt, const void* da, const void* a, void* dz, int64_t rows, int C) {
+#define CALL(T, V)                                                                                                  \
+  { const int64_t groups = rows * (C / V);                                                                           \
+    hipLaunchKernelGGL((relu_bwd_kernel<T, V>), dim3(ceil_div(groups, 256)), dim3(256), 0, st, (const T*)da,         \
+                       (const T*)a, (T*)dz, groups); }
+  DISPATCH_TV(dt, C, CALL);
+#undef CALL
+}
+
+void launch_bias_grad(hipStream_t st, int dt, const void* dz, int64_t rows, int C, int nblk, float* partial, float* dbias) {
+  RedArgs g{}; g.a = dz; g.partial = partial; g.rows = rows; g.C = C; g.nblk = nblk;
+  launch_colreduce<RED_BIAS>(st, dt, g);
+  hipLaunchKernelGGL(bias_finalize_kernel, dim3(ceil_div(C, 128)), dim3(128), 0, st, partial, nblk, C, dbias);
+}
+
+void launch_maxpool_fwd(hipStream_t st, int dt, const void* x, void* y, int N, int H, int W, int C) {
+  const int P = H / 2, Q = W / 2;
+#define CALL(T, V)                                                                                                  \
+  { const int64_t total = (int64_t)N * P * Q * (C / V);                                                              \
+    hipLaunchKernelGGL((maxpool_fwd_kernel<T, V>), dim3(ceil_div(total, 256)), dim3(256), 0, st, (const T*)x, (T*)y, \
+                       N, H, W, C, P, Q); }
+  DISPATCH_TV(dt, C, CALL);
+#undef CALL
+}
+
+void launch_maxpool_bwd(hipStream_t st, int dt, const void* x, const void* dy, void* dx, int N, int H, int W, int C) {
+  const int P = H / 2, Q = W / 2;
+#define CALL(T, V)                                                                                                  \
+  { const int64_t total = (int64_t)N * H * W * (C / V);                                                              \
+    hipLaunchKernelGGL((maxpool_bwd_kernel<T, V>), dim3(ceil_div(total, 256)), dim3(256), 0, st, (const T*)x,        \
+                       (const T*)dy, (T*)dx, N, H, W, C, P, Q); }
+  DISPATCH_TV(dt, C, CALL);
+#undef CALL
+}
+
+}  // namespace oseq

@@ -1,0 +1,143 @@
+// Loss head: global average pool / flatten, linear layer, mean softmax cross-entropy, and their backward.
+// All arithmetic in fp32 on fp32 master weights (the head is a few MFLOP; it is kept out of the 16-bit path
+// for stability, in line with keeping loss computation in single precision).  Every sum runs in a fixed order.
+#include "dev_common.h"
+#include "kernels.h"
+
+namespace oseq {
+
+// feat[n][f]: GAP -> mean over H*W of channel f ; flatten -> x[n][f]
+template <class T>
+__global__ void __launch_bounds__(256) head_feat_kernel(const T* __restrict__ x, float* __restrict__ feat, int HW, int C,
+                                                        int gap) {
+  __shared__ float sm[256];
+  const int n = blockIdx.x;
+  if (!gap) {
+    const int64_t F = (int64_t)HW * C;
+    for (int64_t i = threadIdx.x; i < F; i += 256) feat[n * F + i] = to_f32(x[n * F + i]);
+    return;
+  }
+  const int TX = C < 256 ? C : 256;
+  const int TY = 256 / TX;
+  const int tx = threadIdx.x % TX, ty = threadIdx.x / TX;
+  for (int cb = 0; cb < C; cb += TX) {
+    const int c = cb + tx;
+    float s = 0.f;
+    if (ty < TY && c < C)
+      for (int p = ty; p < HW; p += TY) s += to_f32(x[((int64_t)n * HW + p) * C + c]);
+    sm[threadIdx.x] = s;
+    __syncthreads();
+    if (ty == 0 && c < C) {
+      float t = 0.f;
+      for (int y = 0; y < TY; ++y) t += sm[y * TX + tx];
+      feat[(int64_t)n * C + c] = t / (float)HW;
+    }
+    __syncthreads();
+  }
+}
+
+__global__ void linear_fwd_kernel(const float* __restrict__ feat, const float* __restrict__ w, const float* __restrict__ b,
+                                  float* __restrict__ logits, int N, int F, int J) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= N * J) return;
+  const int n = i / J, j = i % J;
+  const float* fp = feat + (int64_t)n * F;
+  const float* wp = w + (int64_t)j * F;
+  float acc = 0.f;
+  for (int f = 0; f < F; ++f) acc = __fmaf_rn(fp[f], wp[f], acc);
+  logits[i] = acc + b[j];
+}
+
+// per sample: loss_n = logsumexp(logits_n) - logits_n[y_n]; dlogits = (softmax - onehot) * gscale
+__global__ void softmax_ce_kernel(const float* __restrict__ logits, const int32_t* __restrict__ y, float* __restrict__ loss_n,
+                                  float* __restrict__ dlogits, int N, int J, float gscale, int* __restrict__ flags) {
+  const int n = blockIdx.x * blockDim.x + threadIdx.x;
+  if (n >= N) return;
+  const float* lp = logits + (int64_t)n * J;
+  float mx = lp[0];
+  for (int j = 1; j < J; ++j) mx = fmaxf(mx, lp[j]);
+  float se = 0.f;
+  for (int j = 0; j < J; ++j) se += expf(lp[j] - mx);
+  const float lse = mx + logf(se);
+  int lab = y[n];
+  if (lab < 0 || lab >= J) { atomicOr(flags + 1, 1); lab = 0; }
+  loss_n[n] = lse - lp[lab];
+  const float inv = 1.f / se;
+  for (int j = 0; j < J; ++j) {
+    const float pj = expf(lp[j] - mx) * inv;
+    dlogits[(int64_t)n * J + j] = (pj - (j == lab ? 1.f : 0.f)) * gscale;
+  }
+}
+
+__global__ void __launch_bounds__(256) loss_mean_kernel(const float* __restrict__ loss_n, int N, float* __restrict__ out) {
+  __shared__ double sm[256];
+  double s = 0.0;
+  for (int i = threadIdx.x; i < N; i += 256) s += (double)loss_n[i];
+  sm[threadIdx.x] = s;
+  __syncthreads();
+  for (int w = 128; w > 0; w >>= 1) {
+    if (threadIdx.x < w) sm[threadIdx.x] += sm[threadIdx.x + w];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) out[0] = (float)(sm[0] / (double)N);
+}
+
+// dW[j][f] = sum_n dlogits[n][j] * feat[n][f] ; the extra column f == F is the bias gradient
+__global__ void linear_bwd_w_kernel(const float* __restrict__ dlogits, const float* __restrict__ feat, float* __restrict__ dw,
+                                    float* __restrict__ db, int N, int F, int J) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= (int64_t)J * (F + 1)) return;
+  const int j = (int)(i / (F + 1)), f = (int)(i % (F + 1));
+  float acc = 0.f;
+  if (f < F) {
+    for (int n = 0; n < N; ++n) acc = __fmaf_rn(dlogits[(int64_t)n * J + j], feat[(int64_t)n * F + f], acc);
+    dw[(int64_t)j * F + f] = acc;
+  } else {
+    for (int n = 0; n < N; ++n) acc += dlogits[(int64_t)n * J + j];
+    db[j] = acc;
+  }
+}
+
+__global__ void linear_bwd_x_kernel(const float* __restrict__ dlogits, const float* __restrict__ w, float* __restrict__ dfeat,
+                                    int N, int F, int J) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= (int64_t)N * F) return;
+  const int n = (int)(i / F), f = (int)(i % F);
+  float acc = 0.f;
+  for (int j = 0; j < J; ++j) acc = __fmaf_rn(dlogits[(int64_t)n * J + j], w[(int64_t)j * F + f], acc);
+  dfeat[i] = acc;
+}
+
+template <class T>
+__global__ void head_feat_bwd_kernel(const float* __restrict__ dfeat, T* __restrict__ dx, int64_t total, int HW, int C, int gap) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= total) return;
+  if (!gap) { dx[i] = from_f32<T>(dfeat[i]); return; }
+  const int c = (int)(i % C);
+  const int64_t n = i / ((int64_t)HW * C);
+  dx[i] = from_f32<T>(dfeat[n * C + c] / (float)HW);
+}
+
+void launch_head_fwd(hipStream_t st, int dt, const void* x, int N, int HW, int C, int gap, int F, int J, const float* w,
+                     const float* b, const int32_t* y, float gscale, float* feat, float* logits, float* dlogits,
+                     float* loss_n, float* loss_out, int* flags) {
+  if (dt == DT_F32) hipLaunchKernelGGL(head_feat_kernel<float>, dim3(N), dim3(256), 0, st, (const float*)x, feat, HW, C, gap);
+  else if (dt == DT_BF16) hipLaunchKernelGGL(head_feat_kernel<bf16_t>, dim3(N), dim3(256), 0, st, (const bf16_t*)x, feat, HW, C, gap);
+  else hipLaunchKernelGGL(head_feat_kernel<f16_t>, dim3(N), dim3(256), 0, st, (const f16_t*)x, feat, HW, C, gap);
+  hipLaunchKernelGGL(linear_fwd_kernel, dim3(ceil_div((int64_t)N * J, 128)), dim3(128), 0, st, feat, w, b, logits, N, F, J);
+  hipLaunchKernelGGL(softmax_ce_kernel, dim3(ceil_div(N, 64)), dim3(64), 0, st, logits, y, loss_n, dlogits, N, J, gscale, flags);
+  hipLaunchKernelGGL(loss_mean_kernel, dim3(1), dim3(256), 0, st, loss_n, N, loss_out);
+}
+
+void launch_head_bwd(hipStream_t st, int dt, const float* feat, const float* dlogits, const float* w, int N, int HW, int C,
+                     int gap, int F, int J, float* dw, float* db, float* dfeat, void* dx) {
+  hipLaunchKernelGGL(linear_bwd_w_kernel, dim3(ceil_div((int64_t)J * (F + 1), 128)), dim3(128), 0, st, dlogits, feat, dw, db, N, F, J);
+  if (!dx) return;
+  hipLaunchKernelGGL(linear_bwd_x_kernel, dim3(ceil_div((int64_t)N * F, 128)), dim3(128), 0, st, dlogits, w, dfeat, N, F, J);
+  const int64_t total = (int64_t)N * HW * C;
+  if (dt == DT_F32) hipLaunchKernelGGL(head_feat_bwd_kernel<float>, dim3(ceil_div(total, 256)), dim3(256), 0, st, dfeat, (float*)dx, total, HW, C, gap);
+  else if (dt == DT_BF16) hipLaunchKernelGGL(head_feat_bwd_kernel<bf16_t>, dim3(ceil_div(total, 256)), dim3(256), 0, st, dfeat, (bf16_t*)dx, total, HW, C, gap);
+  else hipLaunchKernelGGL(head_feat_bwd_kernel<f16_t>, dim3(ceil_div(total, 256)), dim3(256), 0, st, dfeat, (f16_t*)dx, total, HW, C, gap);
+}
+
+}  // namespace oseq

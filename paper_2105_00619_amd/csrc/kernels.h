@@ -1,0 +1,44 @@
+// Host-callable launchers of the HIP kernels.  Plain device pointers and sizes; `dt` is the storage type of
+// activations and 16-bit weight copies (0 fp32, 1 bf16, 2 fp16).  All launches are asynchronous on `st`.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace oseq {
+
+enum { DT_F32 = 0, DT_BF16 = 1, DT_F16 = 2 };
+
+struct ConvGeom { int N, H, W, C, K, R, S, stride, pad, P, Q; };
+
+void launch_cast_in(hipStream_t st, int dt, const float* x, void* out, int64_t n);
+void launch_bn_stats(hipStream_t st, int dt, const void* z, int64_t rows, int C, int nblk, float* partial, float eps,
+                     float mom, const float* gamma, const float* beta, float* stats, float* running);
+void launch_bn_apply(hipStream_t st, int dt, const void* z, const float* stats, const void* skip, void* out, int64_t rows,
+                     int C, int relu);
+void launch_bn_bwd(hipStream_t st, int dt, const void* da, const void* z, const void* aout, const float* stats, int64_t rows,
+                   int C, int relu, int nblk, float* ws, float* dgamma, float* dbeta, void* dz, void* dskip);
+void launch_relu_bwd(hipStream_t st, int dt, const void* da, const void* a, void* dz, int64_t rows, int C);
+void launch_bias_grad(hipStream_t st, int dt, const void* dz, int64_t rows, int C, int nblk, float* partial, float* dbias);
+void launch_maxpool_fwd(hipStream_t st, int dt, const void* x, void* y, int N, int H, int W, int C);
+void launch_maxpool_bwd(hipStream_t st, int dt, const void* x, const void* dy, void* dx, int N, int H, int W, int C);
+
+void launch_head_fwd(hipStream_t st, int dt, const void* x, int N, int HW, int C, int gap, int F, int J, const float* w,
+                     const float* b, const int32_t* y, float gscale, float* feat, float* logits, float* dlogits,
+                     float* loss_n, float* loss_out, int* flags);
+void launch_head_bwd(hipStream_t st, int dt, const float* feat, const float* dlogits, const float* w, int N, int HW, int C,
+                     int gap, int F, int J, float* dw, float* db, float* dfeat, void* dx);
+
+void launch_conv_fwd_direct(hipStream_t st, int dt, const void* x, const void* w, const float* bias, void* out,
+                            const ConvGeom& g, int relu);
+void launch_conv_dgrad_direct(hipStream_t st, int dt, const void* dz, const void* w, const void* addend, void* dx,
+                              const ConvGeom& g);
+void launch_conv_wgrad_direct(hipStream_t st, int dt, const void* x, const void* dz, float* dw, float* partial, int splits,
+                              const ConvGeom& g);
+
+void launch_step_init(hipStream_t st, int* flags);
+void launch_optim(hipStream_t st, int dt, float* w, float* v, const float* g, void* w16, float* gout, int64_t n, float lr,
+                  float mom, float inv_scale, int* flags);
+void launch_cast_params(hipStream_t st, int dt, const float* w, void* w16, int64_t n);
+void launch_fill(hipStream_t st, float* p, int64_t n, float v);
+
+}  // namespace oseq

@@ -1,0 +1,532 @@
+// Host-side planner; see plan.h.
+#include "plan.h"
+
+#include <algorithm>
+#include <cstdio>
+#include <map>
+
+namespace oseq {
+
+namespace {
+
+struct ConvParams { int64_t w = -1, b = -1, gamma = -1, beta = -1, rs = -1; };
+
+struct Builder {
+  Plan& p;
+  int N;
+  explicit Builder(Plan& pl) : p(pl), N(pl.cfg.batch) {}
+
+  bool fail(const std::string& m) { p.error = m; return false; }
+
+  int new_tensor(int64_t n, int64_t h, int64_t w, int64_t c, int esize, int unit) {
+    LTensor t;
+    t.n = n; t.h = h; t.w = w; t.c = c; t.esize = esize; t.unit = unit;
+    t.bytes = (uint64_t)n * h * w * c * esize;
+    p.tensors.push_back(t);
+    return (int)p.tensors.size() - 1;
+  }
+
+  ConvParams alloc_conv_params(int cin, int cout, int k, int bn, int bias) {
+    ConvParams q;
+    q.w = (int64_t)p.n_params; p.n_params += (uint64_t)cout * k * k * cin;
+    if (bias) { q.b = (int64_t)p.n_params; p.n_params += cout; }
+    if (bn) {
+      q.gamma = (int64_t)p.n_params; p.n_params += cout;
+      q.beta = (int64_t)p.n_params; p.n_params += cout;
+      q.rs = (int64_t)p.n_running; p.n_running += 2 * (uint64_t)cout;
+    }
+    return q;
+  }
+
+  // conv [+bias] [+BN [+skip]] [+ReLU]; appends the forward operations, returns the output tensor
+  int add_cbr(int unit, int x, const ConvParams& q, int cout, int k, int stride, int pad, int bn,
+              int relu, int bias, int skip) {
+    const LTensor tx = p.tensors[x];
+    FOp f;
+    f.kind = F_CONV; f.unit = unit; f.x = x;
+    f.N = (int)tx.n; f.H = (int)tx.h; f.W = (int)tx.w; f.C = (int)tx.c; f.K = cout; f.R = k; f.S = k;
+    f.stride = stride; f.pad = pad;
+    f.P = (f.H + 2 * pad - k) / stride + 1;
+    f.Q = (f.W + 2 * pad - k) / stride + 1;
+    f.has_bias = bias; f.has_bn = bn; f.relu = bn ? 0 : relu;
+    f.w_off = q.w; f.b_off = q.b;
+    const int64_t pixels = (int64_t)f.N * f.P * f.Q;
+    const int64_t outputs = (int64_t)f.K * f.R * f.S * f.C;
+    int64_t splits = (262144 + outputs - 1) / outputs;
+    splits = std::min<int64_t>(splits, std::max<int64_t>(1, pixels / 32));
+    f.wgrad_splits = (int)std::max<int64_t>(1, std::min<int64_t>(splits, 256));
+    f.red_blocks = (int)std::max<int64_t>(1, std::min<int64_t>(pixels / 32, 512));
+    int z = new_tensor(f.N, f.P, f.Q, cout, p.esize, unit);
+    f.out = z;
+    p.fops.push_back(f);
+    if (!bn) return z;
+
+    FOp s;
+    s.kind = F_BN_STATS; s.unit = unit; s.x = z;
+    s.N = f.N; s.H = f.P; s.W = f.Q; s.C = cout; s.K = cout; s.P = f.P; s.Q = f.Q;
+    s.gamma_off = q.gamma; s.beta_off = q.beta; s.rs_off = q.rs;
+    s.red_blocks = (int)std::max<int64_t>(1, std::min<int64_t>(pixels / 32, 512));
+    s.stats = new_tensor(1, 1, 4, cout, 4, unit);  // mean, rstd, scale, shift
+    s.out = s.stats;
+    p.fops.push_back(s);
+
+    FOp a = s;
+    a.kind = F_BN_APPLY; a.skip = skip; a.relu = relu;
+    a.out = new_tensor(f.N, f.P, f.Q, cout, p.esize, unit);
+    p.fops.push_back(a);
+    return a.out;
+  }
+
+  bool run() {
+    const optorch_seq_config_t& c = p.cfg;
+    p.esize = c.precision == OPTORCH_FP32 ? 4 : 2;
+    if (p.units.empty()) return fail("empty unit list");
+    int cur = new_tensor(N, c.height, c.width, c.channels, p.esize, -1);
+    p.tensors[cur].needs_grad = false;
+    {
+      FOp f; f.kind = F_CAST_IN; f.unit = -1; f.out = cur;
+      f.N = N; f.H = c.height; f.W = c.width; f.C = c.channels;
+      p.fops.push_back(f);
+    }
+    const int nu = (int)p.units.size();
+    p.unit_first_fop.assign(nu, 0); p.unit_last_fop.assign(nu, 0);
+    p.unit_in.assign(nu, -1); p.unit_out.assign(nu, -1);
+    for (int ui = 0; ui < nu; ++ui) {
+      const optorch_unit_t& u = p.units[ui];
+      const LTensor tx = p.tensors[cur];
+      p.unit_first_fop[ui] = (int)p.fops.size();
+      p.unit_in[ui] = cur;
+      char where[64]; snprintf(where, sizeof where, "unit %d: ", ui);
+      const bool is_head = u.kind == OPTORCH_GAP_LINEAR_CE || u.kind == OPTORCH_FLATTEN_LINEAR_CE;
+      if (is_head != (ui == nu - 1)) return fail(std::string(where) + "exactly the last unit must be a loss head");
+      switch (u.kind) {
+        case OPTORCH_CONV: {
+          if (u.cin != tx.c) return fail(std::string(where) + "cin does not match the incoming channel count");
+          if (!(u.ksize == 1 || u.ksize == 3) || !(u.stride == 1 || u.stride == 2) || u.cout < 1 || u.pad < 0 ||
+              u.pad > u.ksize / 2)
+            return fail(std::string(where) + "unsupported convolution geometry (ksize 1|3, stride 1|2, pad <= ksize/2)");
+          if (tx.h + 2 * u.pad < u.ksize || tx.w + 2 * u.pad < u.ksize) return fail(std::string(where) + "input smaller than the filter");
+          ConvParams q = alloc_conv_params(u.cin, u.cout, u.ksize, u.has_bn, u.has_bias);
+          cur = add_cbr(ui, cur, q, u.cout, u.ksize, u.stride, u.pad, u.has_bn != 0, u.has_relu != 0, u.has_bias != 0, -1);
+          break;
+        }
+        case OPTORCH_MAXPOOL2: {
+          if (tx.h < 2 || tx.w < 2) return fail(std::string(where) + "max-pool input smaller than 2x2");
+          FOp f; f.kind = F_POOL; f.unit = ui; f.x = cur;
+          f.N = N; f.H = (int)tx.h; f.W = (int)tx.w; f.C = (int)tx.c; f.K = f.C; f.P = f.H / 2; f.Q = f.W / 2;
+          f.out = new_tensor(N, f.P, f.Q, f.C, p.esize, ui);
+          p.fops.push_back(f);
+          cur = f.out;
+          break;
+        }
+        case OPTORCH_BASIC_BLOCK:
+        case OPTORCH_BOTTLENECK: {
+          if (u.cin != tx.c) return fail(std::string(where) + "cin does not match the incoming channel count");
+          if (!(u.stride == 1 || u.stride == 2) || u.cout < 1) return fail(std::string(where) + "unsupported block geometry");
+          const bool bott = u.kind == OPTORCH_BOTTLENECK;
+          if (bott && (u.cout % 4 != 0)) return fail(std::string(where) + "bottleneck cout must be a multiple of 4");
+          const bool proj = (u.cin != u.cout) || (u.stride != 1);
+          const int mid = bott ? u.cout / 4 : u.cout;
+          ConvParams q1, q2, q3, qs;
+          if (bott) {
+            q1 = alloc_conv_params(u.cin, mid, 1, 1, 0);
+            q2 = alloc_conv_params(mid, mid, 3, 1, 0);
+            q3 = alloc_conv_params(mid, u.cout, 1, 1, 0);
+          } else {
+            q1 = alloc_conv_params(u.cin, u.cout, 3, 1, 0);
+            q2 = alloc_conv_params(u.cout, u.cout, 3, 1, 0);
+          }
+          if (proj) qs = alloc_conv_params(u.cin, u.cout, 1, 1, 0);
+          const int x = cur;
+          int a;
+          if (bott) {
+            a = add_cbr(ui, x, q1, mid, 1, 1, 0, 1, 1, 0, -1);
+            a = add_cbr(ui, a, q2, mid, 3, u.stride, 1, 1, 1, 0, -1);
+          } else {
+            a = add_cbr(ui, x, q1, u.cout, 3, u.stride, 1, 1, 1, 0, -1);
+          }
+          int skip = x;
+          if (proj) skip = add_cbr(ui, x, qs, u.cout, 1, u.stride, 0, 1, 0, 0, -1);
+          if (bott) cur = add_cbr(ui, a, q3, u.cout, 1, 1, 0, 1, 1, 0, skip);
+          else      cur = add_cbr(ui, a, q2, u.cout, 3, 1, 1, 1, 1, 0, skip);
+          break;
+        }
+        case OPTORCH_GAP_LINEAR_CE:
+        case OPTORCH_FLATTEN_LINEAR_CE: {
+          if (u.cin != tx.c) return fail(std::string(where) + "cin does not match the incoming channel count");
+          if (u.cout != c.num_classes) return fail(std::string(where) + "cout must equal num_classes");
+          FOp f; f.kind = F_HEAD; f.unit = ui; f.x = cur;
+          f.N = N; f.H = (int)tx.h; f.W = (int)tx.w; f.C = (int)tx.c;
+          f.gap = u.kind == OPTORCH_GAP_LINEAR_CE;
+          f.feat_dim = f.gap ? f.C : f.H * f.W * f.C;
+          f.classes = u.cout; f.has_bias = 1;
+          f.w_off = (int64_t)p.n_params; p.n_params += (uint64_t)f.classes * f.feat_dim;
+          f.b_off = (int64_t)p.n_params; p.n_params += f.classes;
+          f.aux[0] = new_tensor(N, 1, 1, f.feat_dim, 4, ui);
+          f.aux[1] = new_tensor(N, 1, 1, f.classes, 4, ui);
+          f.aux[2] = new_tensor(N, 1, 1, f.classes, 4, ui);
+          f.out = new_tensor(N, 1, 1, 1, 4, ui);
+          p.fops.push_back(f);
+          cur = f.out;
+          break;
+        }
+        default:
+          return fail(std::string(where) + "unknown unit kind");
+      }
+      p.unit_last_fop[ui] = (int)p.fops.size();
+      p.unit_out[ui] = cur;
+    }
+    return true;
+  }
+};
+
+// ---------------------------------------------------------------- arena -----
+struct FreeList {
+  std::map<uint64_t, uint64_t> free_;  // offset -> size
+  uint64_t end_ = 0;                    // current top of the arena
+  uint64_t high_ = 0;
+
+  uint64_t alloc(uint64_t bytes) {
+    bytes = align_up(std::max<uint64_t>(bytes, 1));
+    auto best = free_.end();
+    for (auto it = free_.begin(); it != free_.end(); ++it)
+      if (it->second >= bytes && (best == free_.end() || it->second < best->second)) best = it;
+    if (best != free_.end()) {
+      uint64_t off = best->first, sz = best->second;
+      free_.erase(best);
+      if (sz > bytes) free_[off + bytes] = sz - bytes;
+      return off;
+    }
+    // grow: extend a free block that touches the top, if any
+    uint64_t off = end_;
+    if (!free_.empty()) {
+      auto last = std::prev(free_.end());
+      if (last->first + last->second == end_) { off = last->first; free_.erase(last); }
+    }
+    end_ = off + bytes;
+    high_ = std::max(high_, end_);
+    return off;
+  }
+  void release(uint64_t off, uint64_t bytes) {
+    bytes = align_up(std::max<uint64_t>(bytes, 1));
+    auto it = free_.emplace(off, bytes).first;
+    auto nx = std::next(it);
+    if (nx != free_.end() && it->first + it->second == nx->first) { it->second += nx->second; free_.erase(nx); }
+    if (it != free_.begin()) {
+      auto pv = std::prev(it);
+      if (pv->first + pv->second == it->first) { pv->second += it->second; free_.erase(it); it = pv; }
+    }
+    if (it->first + it->second == end_) { end_ = it->first; free_.erase(it); }
+  }
+};
+
+bool is_fwd_kind(SKind k) { return k <= S_HEAD_FWD; }
+
+bool has_side_effect(SKind k) {
+  // writes parameter gradients, the loss, or BN running statistics
+  return k == S_HEAD_FWD || k == S_HEAD_BWD || k == S_BN_BWD || k == S_BIAS_GRAD || k == S_WGRAD || k == S_BN_STATS;
+}
+
+struct Scheduler {
+  Plan& p;
+  std::vector<int> cur, grad;  // [LTensor] -> Inst id
+  explicit Scheduler(Plan& pl) : p(pl), cur(pl.tensors.size(), -1), grad(pl.tensors.size(), -1) {}
+
+  int new_inst(int logical, uint64_t bytes, bool fwd_value) {
+    Inst i; i.logical = logical; i.bytes = bytes; i.fwd_value = fwd_value;
+    p.insts.push_back(i);
+    return (int)p.insts.size() - 1;
+  }
+  int value_inst(int t) { return cur[t] = new_inst(t, p.tensors[t].bytes, true); }
+  int grad_inst(int t) { return new_inst(t, p.tensors[t].bytes, false); }
+
+  SOp& push(SKind k, int fop, int phase, int seg) {
+    SOp s; s.kind = k; s.fop = fop; s.phase = phase; s.seg = seg;
+    p.sched.push_back(s);
+    return p.sched.back();
+  }
+
+  void emit_fop_forward(int fi, int phase, int seg) {
+    const FOp& f = p.fops[fi];
+    switch (f.kind) {
+      case F_CAST_IN: { SOp& s = push(S_CAST_IN, fi, phase, seg); s.out[0] = value_inst(f.out); break; }
+      case F_CONV: { SOp& s = push(S_CONV_FWD, fi, phase, seg); s.in[0] = cur[f.x]; s.out[0] = value_inst(f.out); break; }
+      case F_BN_STATS: {
+        if (phase == PH_REPLAY) break;  // the statistics of the first forward pass are kept and reused
+        SOp& s = push(S_BN_STATS, fi, phase, seg);
+        s.in[0] = cur[f.x]; s.out[0] = value_inst(f.stats);
+        s.out[1] = new_inst(-1, (uint64_t)f.red_blocks * 2 * f.C * 4, false);
+        break;
+      }
+      case F_BN_APPLY: {
+        SOp& s = push(S_BN_APPLY, fi, phase, seg);
+        s.in[0] = cur[f.x]; s.in[1] = cur[f.stats]; s.in[2] = f.skip >= 0 ? cur[f.skip] : -1;
+        s.out[0] = value_inst(f.out);
+        break;
+      }
+      case F_POOL: { SOp& s = push(S_POOL_FWD, fi, phase, seg); s.in[0] = cur[f.x]; s.out[0] = value_inst(f.out); break; }
+      case F_HEAD: {
+        SOp& s = push(S_HEAD_FWD, fi, phase, seg);
+        s.in[0] = cur[f.x];
+        s.out[0] = value_inst(f.aux[0]); s.out[1] = value_inst(f.aux[1]);
+        s.out[2] = value_inst(f.aux[2]); s.out[3] = value_inst(f.out);
+        break;
+      }
+    }
+  }
+
+  bool emit_fop_backward(int fi, int seg) {
+    const FOp& f = p.fops[fi];
+    switch (f.kind) {
+      case F_CAST_IN: case F_BN_STATS: return true;
+      case F_HEAD: {
+        SOp& s = push(S_HEAD_BWD, fi, PH_BWD, seg);
+        s.in[0] = cur[f.aux[0]]; s.in[1] = cur[f.aux[2]];
+        if (p.tensors[f.x].needs_grad) { s.out[0] = grad_inst(f.x); grad[f.x] = s.out[0]; }
+        s.out[1] = new_inst(-1, (uint64_t)f.N * f.feat_dim * 4, false);
+        return true;
+      }
+      case F_BN_APPLY: {
+        if (grad[f.out] < 0) { p.error = "internal: BN output has no gradient"; return false; }
+        if (f.skip >= 0 && !f.relu) { p.error = "skip connection without ReLU is not supported"; return false; }
+        SOp& s = push(S_BN_BWD, fi, PH_BWD, seg);
+        s.in[0] = grad[f.out]; s.in[1] = cur[f.x]; s.in[2] = cur[f.stats];
+        s.in[3] = (f.skip >= 0) ? cur[f.out] : -1;
+        s.out[0] = grad_inst(f.x); grad[f.x] = s.out[0];
+        if (f.skip >= 0 && p.tensors[f.skip].needs_grad) {
+          if (grad[f.skip] >= 0) { p.error = "internal: skip gradient must be the first contribution"; return false; }
+          s.out[1] = grad_inst(f.skip); grad[f.skip] = s.out[1];
+        }
+        s.out[2] = new_inst(-1, ((uint64_t)f.red_blocks * 2 + 2) * f.C * 4, false);
+        return true;
+      }
+      case F_CONV: {
+        int g = grad[f.out];
+        if (g < 0) { p.error = "internal: conv output has no gradient"; return false; }
+        if (!f.has_bn && f.relu) {
+          SOp& s = push(S_RELU_BWD, fi, PH_BWD, seg);
+          s.in[0] = g; s.in[1] = cur[f.out];
+          s.out[0] = grad_inst(f.out); g = s.out[0];
+        }
+        if (f.has_bias) {
+          SOp& s = push(S_BIAS_GRAD, fi, PH_BWD, seg);
+          s.in[0] = g;
+          s.out[0] = new_inst(-1, (uint64_t)f.red_blocks * 2 * f.K * 4, false);
+        }
+        {
+          SOp& s = push(S_WGRAD, fi, PH_BWD, seg);
+          s.in[0] = cur[f.x]; s.in[1] = g;
+          if (f.wgrad_splits > 1)
+            s.out[0] = new_inst(-1, (uint64_t)f.wgrad_splits * f.K * f.R * f.S * f.C * 4, false);
+        }
+        if (p.tensors[f.x].needs_grad) {
+          SOp& s = push(S_DGRAD, fi, PH_BWD, seg);
+          s.in[0] = g; s.in[1] = grad[f.x];
+          s.out[0] = grad_inst(f.x); grad[f.x] = s.out[0];
+        }
+        return true;
+      }
+      case F_POOL: {
+        if (grad[f.out] < 0) { p.error = "internal: pool output has no gradient"; return false; }
+        if (!p.tensors[f.x].needs_grad) return true;
+        if (grad[f.x] >= 0) { p.error = "internal: pool input already has a gradient"; return false; }
+        SOp& s = push(S_POOL_BWD, fi, PH_BWD, seg);
+        s.in[0] = cur[f.x]; s.in[1] = grad[f.out];
+        s.out[0] = grad_inst(f.x); grad[f.x] = s.out[0];
+        return true;
+      }
+    }
+    return true;
+  }
+
+  bool run() {
+    const int k = (int)p.seg_begin.size() - 1;
+    p.insts.clear(); p.sched.clear();
+    emit_fop_forward(0, k == 1 ? PH_FWD_LAST : PH_FWD_NOSAVE, 0);
+    auto forward_seg = [&](int j, int phase) {
+      for (int u = p.seg_begin[j]; u < p.seg_begin[j + 1]; ++u)
+        for (int fi = p.unit_first_fop[u]; fi < p.unit_last_fop[u]; ++fi) emit_fop_forward(fi, phase, j);
+    };
+    for (int j = 0; j < k - 1; ++j) forward_seg(j, PH_FWD_NOSAVE);
+    forward_seg(k - 1, PH_FWD_LAST);
+    for (int j = k - 1; j >= 0; --j) {
+      if (j < k - 1) forward_seg(j, PH_REPLAY);
+      for (int u = p.seg_begin[j + 1] - 1; u >= p.seg_begin[j]; --u)
+        for (int fi = p.unit_last_fop[u] - 1; fi >= p.unit_first_fop[u]; --fi)
+          if (!emit_fop_backward(fi, j)) return false;
+    }
+    return true;
+  }
+};
+
+}  // namespace
+
+int launches_of(const SOp& op, const FOp& f) {
+  switch (op.kind) {
+    case S_BN_STATS: return 2;
+    case S_HEAD_FWD: return 4;
+    case S_HEAD_BWD: return op.out[0] >= 0 ? 4 : 2;
+    case S_BN_BWD: return 3;
+    case S_BIAS_GRAD: return 2;
+    case S_WGRAD: return f.wgrad_splits > 1 ? 2 : 1;
+    default: return 1;
+  }
+}
+
+bool build_graph(Plan& p) {
+  p.tensors.clear(); p.fops.clear(); p.n_params = 0; p.n_running = 0;
+  const optorch_seq_config_t& c = p.cfg;
+  if (c.batch < 1 || c.height < 1 || c.width < 1 || c.channels < 1 || c.num_classes < 2) {
+    p.error = "batch, height, width, channels must be >= 1 and num_classes >= 2";
+    return false;
+  }
+  if (c.precision < 0 || c.precision > 2) { p.error = "precision must be 0 (fp32), 1 (bf16) or 2 (fp16)"; return false; }
+  if ((int64_t)c.batch * c.height * c.width * 2048 > (int64_t)1 << 40) { p.error = "batch too large"; return false; }
+  Builder b(p);
+  return b.run();
+}
+
+bool build_schedule(Plan& p) {
+  Scheduler s(p);
+  if (!s.run()) return false;
+  const int n = (int)p.sched.size();
+  // dead-operation elimination (a replayed operation whose result nobody reads is not run)
+  std::vector<int> uses(p.insts.size(), 0);
+  for (int i = n - 1; i >= 0; --i) {
+    SOp& op = p.sched[i];
+    bool live = has_side_effect(op.kind);
+    for (int o : op.out) if (o >= 0 && uses[o] > 0) live = true;
+    op.live = live;
+    if (live) for (int x : op.in) if (x >= 0) ++uses[x];
+  }
+  // lifetimes
+  for (Inst& t : p.insts) { t.def_op = -1; t.last_use = -1; t.held = false; t.allocated = false; }
+  for (int i = 0; i < n; ++i) {
+    const SOp& op = p.sched[i];
+    if (!op.live) continue;
+    for (int o : op.out) if (o >= 0) { p.insts[o].def_op = i; p.insts[o].last_use = std::max(p.insts[o].last_use, i); }
+    for (int x : op.in) if (x >= 0) {
+      Inst& t = p.insts[x];
+      if (t.def_op < 0) { p.error = "internal: operation reads a tensor that was never produced"; return false; }
+      t.last_use = std::max(t.last_use, i);
+      const SOp& d = p.sched[t.def_op];
+      if (t.fwd_value && (op.phase == PH_BWD || op.phase != d.phase || op.seg != d.seg)) t.held = true;
+    }
+  }
+  // arena offsets + peak figures, by walking the schedule
+  std::vector<std::vector<int>> dies(n);
+  for (size_t t = 0; t < p.insts.size(); ++t)
+    if (p.insts[t].def_op >= 0) dies[p.insts[t].last_use].push_back((int)t);
+  FreeList fl;
+  uint64_t live_b = 0, held_b = 0;
+  p.peak_saved_bytes = p.peak_live_bytes = 0;
+  p.n_launches = p.n_replay_launches = 0;
+  for (int i = 0; i < n; ++i) {
+    const SOp& op = p.sched[i];
+    if (!op.live) continue;
+    int nl = launches_of(op, p.fops[op.fop]);
+    p.n_launches += nl;
+    if (op.phase == PH_REPLAY) p.n_replay_launches += nl;
+    for (int o : op.out) if (o >= 0) {
+      Inst& t = p.insts[o];
+      t.offset = fl.alloc(t.bytes); t.allocated = true;
+      live_b += t.bytes;
+      if (t.held) held_b += t.bytes;
+    }
+    p.peak_live_bytes = std::max(p.peak_live_bytes, live_b);
+    p.peak_saved_bytes = std::max(p.peak_saved_bytes, held_b);
+    for (int t : dies[i]) {
+      Inst& x = p.insts[t];
+      fl.release(x.offset, x.bytes);
+      live_b -= x.bytes;
+      if (x.held) held_b -= x.bytes;
+    }
+  }
+  p.arena_bytes = fl.high_;
+  return true;
+}
+
+uint64_t model_peak_saved(const Plan& all_stored, const std::vector<int>& seg_begin) {
+  // per-unit bytes kept for backward, from a k = 1 schedule
+  const int nu = (int)all_stored.units.size();
+  std::vector<uint64_t> saved_u(nu, 0);
+  for (const Inst& t : all_stored.insts)
+    if (t.held && t.logical >= 0 && all_stored.tensors[t.logical].unit >= 0) saved_u[all_stored.tensors[t.logical].unit] += t.bytes;
+  uint64_t ck = 0, peak = 0;
+  for (size_t j = 0; j + 1 < seg_begin.size(); ++j) {
+    ck += all_stored.tensors[all_stored.unit_in[seg_begin[j]]].bytes;
+    uint64_t s = 0;
+    for (int u = seg_begin[j]; u < seg_begin[j + 1]; ++u) s += saved_u[u];
+    peak = std::max(peak, ck + s);
+  }
+  return peak;
+}
+
+bool choose_segments(Plan& p) {
+  const int nu = (int)p.units.size();
+  const int k = p.cfg.k_segments;
+  if (k < 1 || k > nu) { p.error = "k_segments must be between 1 and the number of units"; return false; }
+  p.seg_begin.assign(1, 0);
+  if (p.cfg.boundaries) {
+    int prev = 0;
+    for (int j = 0; j < k - 1; ++j) {
+      int b = p.cfg.boundaries[j];
+      if (b <= prev || b >= nu) { p.error = "boundaries must be ascending unit indices in (0, n_units)"; return false; }
+      p.seg_begin.push_back(b); prev = b;
+    }
+    p.seg_begin.push_back(nu);
+    return true;
+  }
+  if (p.cfg.plan_mode == 0 || k == 1) {
+    int per = nu / k;
+    for (int j = 1; j < k; ++j) p.seg_begin.push_back(j * per);
+    p.seg_begin.push_back(nu);
+    return true;
+  }
+  if (p.cfg.plan_mode != 1) { p.error = "plan_mode must be 0 or 1"; return false; }
+  // min-peak: per-unit byte model from the all-stored schedule, then the smallest threshold T for which a
+  // partition into k segments exists with  sum_{i<=j} checkpoint_i + saved_j <= T  for every j.
+  Plan all = p;
+  all.cfg.boundaries = nullptr;
+  all.seg_begin = {0, nu};
+  if (!build_schedule(all)) { p.error = all.error; return false; }
+  std::vector<uint64_t> saved_u(nu, 0), pre(nu + 1, 0), ck(nu, 0);
+  for (const Inst& t : all.insts)
+    if (t.held && t.logical >= 0 && all.tensors[t.logical].unit >= 0) saved_u[all.tensors[t.logical].unit] += t.bytes;
+  for (int u = 0; u < nu; ++u) { pre[u + 1] = pre[u] + saved_u[u]; ck[u] = all.tensors[all.unit_in[u]].bytes; }
+  const uint64_t INF = ~0ull;
+  std::vector<int> best;
+  auto feasible = [&](uint64_t T, std::vector<int>* cuts) {
+    // g[j][e]: least checkpoint total with j segments covering units [0, e)
+    std::vector<std::vector<uint64_t>> g(k + 1, std::vector<uint64_t>(nu + 1, INF));
+    std::vector<std::vector<int>> from(k + 1, std::vector<int>(nu + 1, -1));
+    g[0][0] = 0;
+    for (int j = 1; j <= k; ++j)
+      for (int e = j; e <= nu; ++e)
+        for (int s = j - 1; s < e; ++s) {
+          if (g[j - 1][s] == INF) continue;
+          uint64_t c = g[j - 1][s] + ck[s];
+          if (c + (pre[e] - pre[s]) > T) continue;
+          if (c < g[j][e]) { g[j][e] = c; from[j][e] = s; }
+        }
+    if (g[k][nu] == INF) return false;
+    if (cuts) {
+      cuts->assign(k + 1, 0);
+      int e = nu;
+      for (int j = k; j >= 1; --j) { (*cuts)[j] = e; e = from[j][e]; }
+      (*cuts)[0] = 0;
+    }
+    return true;
+  };
+  uint64_t lo = 0, hi = pre[nu];
+  for (int u = 0; u < nu; ++u) hi += ck[u];
+  while (lo < hi) {
+    uint64_t mid = lo + (hi - lo) / 2;
+    if (feasible(mid, nullptr)) hi = mid; else lo = mid + 1;
+  }
+  if (!feasible(lo, &best)) { p.error = "internal: min-peak planner found no partition"; return false; }
+  p.seg_begin = best;
+  return true;
+}
+
+}  // namespace oseq

@@ -1,0 +1,147 @@
+"""Helpers for the GPU parity tests: run one step through the C ABI and through the oracle."""
+import numpy as np
+
+from oracle import seqnet_oracle as O
+from paper_2105_00619_amd import workloads as W
+
+TOL = {W.FP32: 1e-4, W.BF16: 2e-2, W.FP16: 2e-2}  # relative L2 per gradient tensor
+
+
+def gpu_step(units, params, x, y, *, precision, k, classes, lr=0.01, momentum=0.0, steps=1, **kw):
+    import torch
+    from paper_2105_00619_amd.binding import SeqTrainer
+    b, h, w, c = x.shape
+    t = SeqTrainer(units, k_segments=k, precision=precision, batch=b, height=h, width=w, channels=c,
+                   num_classes=classes, momentum=momentum, **kw)
+    t.set_params(params)
+    xd = torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).cuda()
+    yd = torch.from_numpy(np.ascontiguousarray(y, dtype=np.int32)).cuda()
+    gd = torch.zeros(t.param_count, dtype=torch.float32, device="cuda")
+    outs = []
+    for _ in range(steps):
+        r = t.step(xd, yd, lr, gd)
+        r["grads"] = gd.cpu().numpy().copy()
+        r["params"] = t.get_params()
+        outs.append(r)
+    info = {"planned_peak_saved_bytes": t.planned_peak_saved_bytes, "act_arena_bytes": t.act_arena_bytes,
+            "boundaries": t.boundaries, "n_launches": t.n_launches, "n_replay_launches": t.n_replay_launches}
+    t.close()
+    return (outs[0] if steps == 1 else outs), info
+
+
+STORAGE = {W.FP32: None, W.BF16: "bf16", W.FP16: "fp16"}
+
+
+def oracle_step(units, params, x, y, precision=W.FP32, loss_scale=1.0):
+    """Oracle loss and gradients.  In the 16-bit modes the oracle rounds the same stored tensors to the
+    same format (so that ReLU decisions are taken in the kernel's precision) and applies the loss scale."""
+    return O.loss_and_grads(units, params.astype(np.float64), x.astype(np.float64), y,
+                            storage=STORAGE[precision], loss_scale=loss_scale)
+
+
+def tensor_errors(units, h, w, g_gpu, g_ref, floor_rel=1e-3):
+    """Relative L2 error per gradient tensor.  The denominator has a floor of floor_rel x (RMS of the whole
+    reference gradient) x sqrt(tensor size): a tensor whose gradient is small through cancellation (a BatchNorm
+    shift feeding another BatchNorm; exactly zero for a bias in front of BatchNorm) is judged against the scale of
+    the gradient around it, not against its own rounding noise.  floor_rel is 1e-3 in fp32 mode and 5e-2 in the
+    16-bit modes (one 16-bit rounding is 2^-9..2^-12 of each summand, not of the sum)."""
+    out = {}
+    rms = np.linalg.norm(g_ref) / np.sqrt(g_ref.size)
+    zero_by_construction = {"u%d.b" % i for i, u in enumerate(units) if u.kind == W.CONV and u.has_bn and u.has_bias}
+    for name, sl in W.param_slices(units, h, w).items():
+        r, g = g_ref[sl], g_gpu[sl].astype(np.float64)
+        floor = (1.0 if name in zero_by_construction else floor_rel) * rms * np.sqrt(r.size)
+        out[name] = np.linalg.norm(g - r) / max(np.linalg.norm(r), floor)
+    return out
+
+
+def assert_parity(units, h, w, g_gpu, g_ref, tol, what=""):
+    errs = tensor_errors(units, h, w, g_gpu, g_ref, 1e-3 if tol < 1e-3 else 5e-2)
+    worst = max(errs, key=errs.get)
+    assert errs[worst] <= tol, "%s: gradient tensor %s off by %.3e (tol %.1e)" % (what, worst, errs[worst], tol)
+    return errs
+
+
+def conditioned_tolerance(units, h, w, g_ref, g_alt, tol, factor=3.0):
+    """Per-tensor tolerance max(tol, factor x error of an independent implementation at the same precision).
+
+    On deep networks a handful of ReLU decisions sit within rounding distance of zero and each flipped decision
+    moves a gradient tensor by ~1/sqrt(elements); no implementation at that precision can then meet `tol`
+    against float64.  `g_alt` is the oracle evaluated at the kernel's precision (its float32 instantiation, or
+    its 16-bit storage emulation): the GPU result has to be as close to `g_ref` as that, up to `factor`."""
+    alt = tensor_errors(units, h, w, g_alt, g_ref)
+    return {k: max(tol, factor * v) for k, v in alt.items()}
+
+
+def assert_parity_fp32(units, h, w, params, x, y, g_gpu, tol=1e-4, what="", kink_tau=5e-5, max_inverted=16):
+    """fp32-mode parity against the float64 oracle, accepting either decision for ReLU inputs at the kink.
+
+    A pre-activation within rounding distance of zero has no determined sign in float32, and inverting one such
+    decision moves the gradient tensors below it by ~1/sqrt(elements), far above 1e-4.  If the plain comparison
+    fails, the oracle lists the decisions within kink_tau x rms of zero.  An inverted decision shows up directly,
+    as a spike, in the gradient of its own channel's BatchNorm shift (or bias); candidates are taken greedily by
+    that spike, the gradient change of inverting each is computed by the oracle, and it is kept if it explains
+    part of the difference.  The GPU gradient must then match the oracle's, to the same tolerance, for the chosen
+    decisions.  Returns (oracle loss, number of decisions inverted)."""
+    p64, x64 = params.astype(np.float64), x.astype(np.float64)
+    loss, g_ref, kinks = O.loss_and_grads(units, p64, x64, y, kink_tau=kink_tau)
+    g_gpu = g_gpu.astype(np.float64)
+    errs = tensor_errors(units, h, w, g_gpu, g_ref)
+    if max(errs.values()) <= tol:
+        return loss, 0
+    first = max(errs.values())
+    resid = g_gpu - g_ref
+    cands = [k for k in kinks if k[2] >= 0]
+    # the change each inversion causes is needed to ~1% only: float32 differences of two evaluations that share
+    # every other decision are accurate enough and ten times cheaper than float64.  Both evaluations force the
+    # decision (float32 may itself sit on the other side of the kink than float64).
+    inverted, tried = [], set()
+    slices = list(W.param_slices(units, h, w).values())
+    owner = np.zeros(g_ref.size, dtype=np.int64)
+    for t, sl in enumerate(slices):
+        owner[sl] = t
+    for _ in range(4 * max_inverted):
+        # a spike: the entry stands out of its own tensor's residual; layers above an inverted decision are
+        # untouched by it, so the topmost layer with a spike is handled first
+        med = np.array([np.median(np.abs(resid[sl])) for sl in slices]) + 1e-30
+        rest = [k for k in cands if k[:2] not in tried and abs(resid[k[2]]) > 8.0 * med[owner[k[2]]]]
+        if not rest or len(inverted) >= max_inverted:
+            break
+        rid, idx, gi, dec = max(rest, key=lambda k: (k[0], abs(resid[k[2]])))
+        tried.add((rid, idx))
+        g_as = O.loss_and_grads(units, params, x, y, np.float32, flips={rid: ([idx], [dec])})[1]
+        g_inv = O.loss_and_grads(units, params, x, y, np.float32, flips={rid: ([idx], [not dec])})[1]
+        delta = g_inv.astype(np.float64) - g_as.astype(np.float64)
+        if np.linalg.norm(resid - delta) < np.linalg.norm(resid):
+            resid = resid - delta
+            inverted.append((rid, idx))
+            errs = tensor_errors(units, h, w, g_ref + resid, g_ref)
+            if max(errs.values()) <= tol:
+                return loss, len(inverted)
+    worst = max(errs, key=errs.get)
+    raise AssertionError("%s: off by %.3e; tensor %s still off by %.3e with %d of %d near-kink decisions inverted"
+                         % (what, first, worst, errs[worst], len(inverted), len(cands)))
+
+
+def assert_parity_16bit(units, h, w, params, x, y, precision, loss_scale, g_gpu, tol=2e-2, what="", factor=1.5):
+    """16-bit-mode parity.  Per gradient tensor the GPU result must either match the oracle's 16-bit storage
+    emulation (same rounding points, decisions taken on 16-bit values) to `tol`, or -- where rounding cascades
+    through several layers so that two valid 16-bit evaluations differ by more than `tol` from each other --
+    be as close to the float64 oracle as that emulation is, up to `factor`.  Returns (emulated loss, tensors
+    that needed the second criterion)."""
+    loss16, g16 = oracle_step(units, params, x, y, precision, loss_scale)
+    e_emul = tensor_errors(units, h, w, g_gpu, g16, 5e-2)
+    if max(e_emul.values()) <= tol:
+        return loss16, []
+    _, g64 = oracle_step(units, params, x, y)
+    e_gpu64 = tensor_errors(units, h, w, g_gpu, g64, 5e-2)
+    e_emul64 = tensor_errors(units, h, w, g16, g64, 5e-2)
+    loose = []
+    for k in e_emul:
+        if e_emul[k] <= tol:
+            continue
+        assert e_gpu64[k] <= factor * e_emul64[k], (
+            "%s: tensor %s: %.3e from the 16-bit emulation, %.3e from float64 where the emulation is at %.3e"
+            % (what, k, e_emul[k], e_gpu64[k], e_emul64[k]))
+        loose.append(k)
+    return loss16, loose
