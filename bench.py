@@ -1,0 +1,137 @@
+#!/usr/bin/env python3
+"""Benchmark of the checkpointed training step on one MI355X.
+
+One "step" is one pass of the whole hot path over one synthetic batch: input cast, forward of the
+non-last segments keeping only their inputs, forward of the last segment, per-segment replay +
+backward, fused optimizer, read-back of loss and overflow flag.  Inputs are resident in HBM before
+the timed region.  Prints ONE JSON line: images/sec, peak activation bytes, the roofline figure of
+the dominant kernel class (HIP-event timed inside the timed region) and the CPU oracle timed on the
+host cores on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK = {"hbm": 8000.0,  # GB/s
+        "mfma_f32": 157.3, "mfma_bf16": 2500.0, "mfma_f16": 2500.0,  # TFLOP/s dense
+        "alu_f32": 157.3}  # fp32 vector FMA: 256 CU x 4 SIMD x 32 lanes-per-clock(x2 packed) x 2 flop x 2.4 GHz
+MFMA_CLASSES = ("conv_fwd", "conv_dgrad", "conv_wgrad")
+DTYPE_NAME = {0: "f32", 1: "bf16", 2: "f16"}
+
+
+def cpu_baseline(config_index, sample_batch):
+    """The oracle as it stands (float64, all activations stored) on a bounded sample of the workload."""
+    import numpy as np
+    from oracle import seqnet_oracle as O
+    from paper_2105_00619_amd import workloads as W
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    sw = W.config(config_index, batch=sample_batch)
+    p, x, y = W.make_batch(sw)
+    v = np.zeros_like(p, dtype=np.float64)
+    t0 = time.perf_counter()
+    O.train_step(sw.units, p.astype(np.float64), v, x.astype(np.float64), y, 0.01, sw.momentum)
+    dt = time.perf_counter() - t0
+    return {"value": sample_batch / dt, "unit": "images/sec", "cores": int(cores), "kind": "oracle",
+            "sample": "one float64 training step of the same network on batch %d (%.1f s)" % (sample_batch, dt)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", type=int, default=2, help="benchmark configuration 1..5 (default: VGG-11-BN fp32, k=4)")
+    ap.add_argument("--k", type=int, default=None, help="override the number of segments")
+    ap.add_argument("--batch", type=int, default=None)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-batch", type=int, default=32)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: the step has no inter-GPU path (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2105_00619_amd import workloads as W
+    from paper_2105_00619_amd.binding import SeqTrainer, LIB_PATH
+    if not os.path.exists(LIB_PATH):
+        import __graft_entry__
+        __graft_entry__.build()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+
+    wl = W.config(args.config, batch=args.batch)
+    k = args.k if args.k is not None else wl.k_segments
+    tr = SeqTrainer.from_workload(wl, k_segments=k)
+    p, x, y = W.make_batch(wl)
+    tr.set_params(p)
+    xd, yd = torch.from_numpy(x).cuda(), torch.from_numpy(y).cuda()
+    torch.cuda.synchronize()
+
+    lr = 0.01
+    for _ in range(args.warmup):
+        r = tr.step(xd, yd, lr)
+    torch.cuda.synchronize()
+    tr.profile_enable(True)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        r = tr.step(xd, yd, lr)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    prof = tr.profile_read()
+    tr.profile_enable(False)
+
+    ms = dt / args.steps * 1e3
+    classes = {}
+    for name, c in prof["classes"].items():
+        if c["entries"] == 0:
+            continue
+        sec = c["gpu_ms"] * 1e-3
+        classes[name] = {
+            "launches_per_step": c["launches"] / prof["steps"], "ms_per_step": c["gpu_ms"] / prof["steps"],
+            "avg_entry_us": c["gpu_ms"] * 1e3 / c["entries"],
+            "gbps": c["bytes"] / sec / 1e9 if sec > 0 else None,
+            "tflops": c["flops"] / sec / 1e12 if sec > 0 and c["flops"] > 0 else None,
+        }
+    dom = max(classes, key=lambda n: classes[n]["ms_per_step"])
+    dc = prof["classes"][dom]
+    if dom in MFMA_CLASSES:
+        key = {0: "mfma_f32", 1: "mfma_bf16", 2: "mfma_f16"}[wl.precision]
+        achieved = dc["flops"] / (dc["gpu_ms"] * 1e-3) / 1e12
+        roof = {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": PEAK[key], "unit": "TFLOP/s",
+                "frac": achieved / PEAK[key], "traffic": None}
+    else:
+        achieved = dc["bytes"] / (dc["gpu_ms"] * 1e-3) / 1e9
+        roof = {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": PEAK["hbm"], "unit": "GB/s",
+                "frac": achieved / PEAK["hbm"], "traffic": None}
+    roof["avg_launch_us"] = dc["gpu_ms"] * 1e3 / max(1, dc["entries"])
+    roof["launches_timed"] = int(dc["entries"])
+
+    out = {
+        "metric": "train images/sec at fixed HBM activation budget; peak activation bytes; MFMA util",
+        "value": wl.batch / (ms * 1e-3), "unit": "images/sec", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": DTYPE_NAME[wl.precision], "data": "synthetic",
+        "config": {"workload": wl.name, "batch": wl.batch, "k_segments": k, "image": "32x32x3 NHWC",
+                   "boundaries": tr.boundaries, "plan_mode": wl.plan_mode, "momentum": wl.momentum},
+        "loss": r["loss"], "peak_saved_bytes": r["peak_saved_bytes"], "peak_arena_bytes": r["peak_arena_bytes"],
+        "activation_budget_bytes": wl.budget_bytes, "launches_per_step": tr.n_launches,
+        "replay_launches_per_step": tr.n_replay_launches,
+        "roofline": roof, "kernel_classes": classes,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(args.config, args.cpu_sample_batch)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -137,6 +137,22 @@ int optorch_seq_step(optorch_seq_t* h, const float* x_dev, const int32_t* y_dev,
  * replay (recomputation) of non-last segments. */
 int optorch_seq_schedule_info(const optorch_seq_t* h, int32_t* n_launch_records, int32_t* n_replay_records);
 
+/* Per-kernel-class timing for roofline figures.  While enabled, optorch_seq_step brackets every schedule
+ * entry with a pair of HIP events on the step's stream; nothing is read back until optorch_seq_profile_read.
+ * Classes are indexed by optorch_kernel_class_t.  For each class the read returns, summed over all profiled
+ * steps since the last enable: kernel launches, schedule entries, GPU milliseconds between the entry's two events,
+ * algorithmic FLOPs (convolutions: 2 x output pixels x C_out x kh x kw x C_in for each of forward, data gradient
+ * and weight gradient; 0 for the memory-bound classes) and algorithmic HBM bytes (every operand read once, every
+ * result written once, at the storage type).  All out pointers are host arrays of OPTORCH_N_KERNEL_CLASSES. */
+typedef enum {
+  OPTORCH_K_CAST_IN = 0, OPTORCH_K_CONV_FWD = 1, OPTORCH_K_CONV_DGRAD = 2, OPTORCH_K_CONV_WGRAD = 3,
+  OPTORCH_K_BN_STATS = 4, OPTORCH_K_BN_APPLY = 5, OPTORCH_K_BN_BWD = 6, OPTORCH_K_POOL = 7, OPTORCH_K_HEAD = 8,
+  OPTORCH_K_RELU_BIAS_BWD = 9, OPTORCH_K_OPTIMIZER = 10, OPTORCH_N_KERNEL_CLASSES = 11
+} optorch_kernel_class_t;
+int optorch_seq_profile_enable(optorch_seq_t* h, int32_t enable);
+int optorch_seq_profile_read(optorch_seq_t* h, int32_t* steps, uint64_t* launches, uint64_t* entries, double* gpu_ms,
+                             double* flops, double* bytes);
+
 const char* optorch_seq_last_error(const optorch_seq_t* h);
 void optorch_seq_destroy(optorch_seq_t* h);
 

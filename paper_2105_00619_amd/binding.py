@@ -20,8 +20,11 @@ OK, E_INVALID, E_BUDGET, E_HIP, E_ORDER = 0, -1, -2, -3, -4
 SYMBOLS = (
     "optorch_seq_create", "optorch_seq_query", "optorch_seq_bind", "optorch_seq_set_params",
     "optorch_seq_get_params", "optorch_seq_step", "optorch_seq_schedule_info", "optorch_seq_last_error",
-    "optorch_seq_destroy",
+    "optorch_seq_destroy", "optorch_seq_profile_enable", "optorch_seq_profile_read",
 )
+
+KERNEL_CLASSES = ("cast_in", "conv_fwd", "conv_dgrad", "conv_wgrad", "bn_stats", "bn_apply", "bn_bwd", "pool", "head",
+                  "relu_bias_bwd", "optimizer")
 
 
 class optorch_unit_t(C.Structure):
@@ -70,6 +73,11 @@ def load_library() -> C.CDLL:
     lib.optorch_seq_step.restype = C.c_int
     lib.optorch_seq_schedule_info.argtypes = [H, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
     lib.optorch_seq_schedule_info.restype = C.c_int
+    lib.optorch_seq_profile_enable.argtypes = [H, C.c_int32]
+    lib.optorch_seq_profile_enable.restype = C.c_int
+    lib.optorch_seq_profile_read.argtypes = [H, C.POINTER(C.c_int32), C.POINTER(C.c_uint64), C.POINTER(C.c_uint64),
+                                             C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_double)]
+    lib.optorch_seq_profile_read.restype = C.c_int
     lib.optorch_seq_last_error.argtypes = [H]
     lib.optorch_seq_last_error.restype = C.c_char_p
     lib.optorch_seq_destroy.argtypes = [H]
@@ -205,3 +213,19 @@ class SeqTrainer(SeqPlan):
                                               C.byref(scale), C.byref(skipped)))
         return {"loss": loss.value, "peak_saved_bytes": ps.value, "peak_arena_bytes": pa.value,
                 "loss_scale": scale.value, "skipped": bool(skipped.value)}
+
+    def profile_enable(self, enable: bool = True):
+        self._check(self.lib.optorch_seq_profile_enable(self.handle, 1 if enable else 0))
+
+    def profile_read(self) -> dict:
+        """Per kernel class: launches, schedule entries, GPU ms, algorithmic FLOPs and bytes, summed over the
+        profiled steps; plus "steps"."""
+        n = len(KERNEL_CLASSES)
+        steps = C.c_int32()
+        la, en = (C.c_uint64 * n)(), (C.c_uint64 * n)()
+        ms, fl, by = (C.c_double * n)(), (C.c_double * n)(), (C.c_double * n)()
+        self._check(self.lib.optorch_seq_profile_read(self.handle, C.byref(steps), la, en, ms, fl, by))
+        out = {"steps": steps.value, "classes": {}}
+        for i, name in enumerate(KERNEL_CLASSES):
+            out["classes"][name] = {"launches": la[i], "entries": en[i], "gpu_ms": ms[i], "flops": fl[i], "bytes": by[i]}
+        return out

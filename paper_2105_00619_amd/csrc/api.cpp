@@ -6,6 +6,7 @@
 #include <cstring>
 #include <new>
 #include <string>
+#include <vector>
 
 #include "kernels.h"
 #include "optorch_seq.h"
@@ -18,7 +19,7 @@ struct optorch_seq {
   char* pbase = nullptr; uint64_t pbytes = 0;
   char* abase = nullptr; uint64_t abytes = 0;
   hipStream_t stream = nullptr;
-  uint64_t off_w = 0, off_v = 0, off_g = 0, off_h = 0, off_run = 0, off_scal = 0, param_arena_bytes = 0;
+  uint64_t off_w = 0, off_v = 0, off_g = 0, off_h = 0, off_wt = 0, off_run = 0, off_scal = 0, param_arena_bytes = 0;
   bool bound = false, params_set = false;
   int dt = 0;
   float scale = 1.f, scale_init = 1.f, growth = 2.f, backoff = 0.5f, eps = 1e-5f, bn_mom = 0.1f, momentum = 0.f;
@@ -26,6 +27,15 @@ struct optorch_seq {
   bool dynamic_scale = false;
   float* host_rb = nullptr;  // pinned read-back buffer: loss + flags
   mutable std::string err;
+  // profiling: event pairs per schedule entry, harvested on read
+  bool profiling = false;
+  std::vector<hipEvent_t> ev_pool;
+  size_t ev_used = 0;
+  std::vector<int> ev_class;  // class of pair i
+  int prof_steps = 0;
+  uint64_t prof_launches[OPTORCH_N_KERNEL_CLASSES] = {0}, prof_entries[OPTORCH_N_KERNEL_CLASSES] = {0};
+  double prof_ms[OPTORCH_N_KERNEL_CLASSES] = {0}, prof_flops[OPTORCH_N_KERNEL_CLASSES] = {0},
+         prof_bytes[OPTORCH_N_KERNEL_CLASSES] = {0};
 };
 
 static thread_local std::string g_create_error;
@@ -34,6 +44,14 @@ static int set_err(const optorch_seq_t* h, int code, const std::string& m) { h->
 
 static int hip_fail(const optorch_seq_t* h, hipError_t e, const char* what) {
   return set_err(h, OPTORCH_E_HIP, std::string(what) + ": " + hipGetErrorString(e));
+}
+
+// refresh the transposed weight copies the data-gradient GEMMs read (after every change of the master weights)
+static void refresh_transposed_weights(optorch_seq_t* h) {
+  for (const FOp& f : h->plan.fops)
+    if (f.kind == F_CONV && f.dgrad_algo == ALGO_MFMA && h->plan.tensors[f.x].needs_grad)
+      launch_weight_transpose(h->stream, h->dt, (const float*)(h->pbase + h->off_w) + f.w_off,
+                              h->pbase + h->off_wt + (uint64_t)f.w_off * h->plan.esize, f.K, f.R * f.S, f.C);
 }
 
 extern "C" int optorch_seq_create(const optorch_unit_t* units, int32_t n_units, const optorch_seq_config_t* cfg,
@@ -62,6 +80,12 @@ extern "C" int optorch_seq_create(const optorch_unit_t* units, int32_t n_units, 
     return OPTORCH_E_BUDGET;
   }
   h->dt = cfg->precision;
+  for (FOp& f : p.fops)
+    if (f.kind == F_CONV) {
+      const ConvGeom g{f.N, f.H, f.W, f.C, f.K, f.R, f.S, f.stride, f.pad, f.P, f.Q};
+      f.fwd_algo = conv_mfma_fwd_ok(h->dt, g) ? ALGO_MFMA : ALGO_DIRECT;
+      f.dgrad_algo = conv_mfma_dgrad_ok(h->dt, g) ? ALGO_MFMA : ALGO_DIRECT;
+    }
   h->eps = cfg->bn_eps > 0 ? cfg->bn_eps : 1e-5f;
   h->bn_mom = cfg->bn_momentum > 0 ? cfg->bn_momentum : 0.1f;
   h->momentum = cfg->momentum;
@@ -77,6 +101,7 @@ extern "C" int optorch_seq_create(const optorch_unit_t* units, int32_t n_units, 
   h->off_v = o; o = align_up(o + P * 4);
   h->off_g = o; o = align_up(o + P * 4);
   h->off_h = o; if (h->dt != DT_F32) o = align_up(o + P * 2);
+  h->off_wt = o; o = align_up(o + P * p.esize);  // transposed conv weights for the data-gradient GEMM
   h->off_run = o; o = align_up(o + p.n_running * 4);
   h->off_scal = o; o = align_up(o + 256);
   h->param_arena_bytes = o;
@@ -141,6 +166,7 @@ extern "C" int optorch_seq_set_params(optorch_seq_t* h, const float* src, uint64
     }
   launch_fill(st, (float*)(h->pbase + h->off_scal), 64, 0.f);
   launch_cast_params(st, h->dt, (const float*)(h->pbase + h->off_w), h->pbase + h->off_h, (int64_t)n);
+  refresh_transposed_weights(h);
   e = hipStreamSynchronize(st);
   if (e != hipSuccess) return hip_fail(h, e, "hipStreamSynchronize");
   e = hipGetLastError();
@@ -188,8 +214,12 @@ void run_op(const Ctx& c, const SOp& s) {
       launch_cast_in(st, dt, c.x, c.at(s.out[0]), (int64_t)f.N * f.H * f.W * f.C);
       break;
     case S_CONV_FWD:
-      launch_conv_fwd_direct(st, dt, c.at(s.in[0]), c.wc(f.w_off), f.has_bias ? c.w32(f.b_off) : nullptr, c.at(s.out[0]),
+      if (f.fwd_algo == ALGO_MFMA)
+        launch_conv_fwd_mfma(st, dt, c.at(s.in[0]), c.wc(f.w_off), f.has_bias ? c.w32(f.b_off) : nullptr, c.at(s.out[0]),
                              geom(f), f.relu);
+      else
+        launch_conv_fwd_direct(st, dt, c.at(s.in[0]), c.wc(f.w_off), f.has_bias ? c.w32(f.b_off) : nullptr, c.at(s.out[0]),
+                               geom(f), f.relu);
       break;
     case S_BN_STATS:
       launch_bn_stats(st, dt, c.at(s.in[0]), (int64_t)f.N * f.P * f.Q, f.C, f.red_blocks, (float*)c.at(s.out[1]), h->eps,
@@ -229,7 +259,11 @@ void run_op(const Ctx& c, const SOp& s) {
                                geom(f));
       break;
     case S_DGRAD:
-      launch_conv_dgrad_direct(st, dt, c.at(s.in[0]), c.wc(f.w_off), c.at(s.in[1]), c.at(s.out[0]), geom(f));
+      if (f.dgrad_algo == ALGO_MFMA)
+        launch_conv_dgrad_mfma(st, dt, c.at(s.in[0]), h->pbase + h->off_wt + (uint64_t)f.w_off * h->plan.esize, c.at(s.in[1]),
+                               c.at(s.out[0]), geom(f));
+      else
+        launch_conv_dgrad_direct(st, dt, c.at(s.in[0]), c.wc(f.w_off), c.at(s.in[1]), c.at(s.out[0]), geom(f));
       break;
     case S_POOL_BWD:
       launch_maxpool_bwd(st, dt, c.at(s.in[0]), c.at(s.in[1]), c.at(s.out[0]), f.N, f.H, f.W, f.C);
@@ -237,7 +271,96 @@ void run_op(const Ctx& c, const SOp& s) {
   }
 }
 
+int class_of(SKind k) {
+  switch (k) {
+    case S_CAST_IN: return OPTORCH_K_CAST_IN;
+    case S_CONV_FWD: return OPTORCH_K_CONV_FWD;
+    case S_DGRAD: return OPTORCH_K_CONV_DGRAD;
+    case S_WGRAD: return OPTORCH_K_CONV_WGRAD;
+    case S_BN_STATS: return OPTORCH_K_BN_STATS;
+    case S_BN_APPLY: return OPTORCH_K_BN_APPLY;
+    case S_BN_BWD: return OPTORCH_K_BN_BWD;
+    case S_POOL_FWD: case S_POOL_BWD: return OPTORCH_K_POOL;
+    case S_HEAD_FWD: case S_HEAD_BWD: return OPTORCH_K_HEAD;
+    default: return OPTORCH_K_RELU_BIAS_BWD;
+  }
+}
+
+// algorithmic work of one schedule entry: every operand read once, every result written once
+void work_of(const optorch_seq_t* h, const SOp& s, double* flops, double* bytes) {
+  const FOp& f = h->plan.fops[s.fop];
+  const double e = h->plan.esize;
+  const double in_px = (double)f.N * f.H * f.W, out_px = (double)f.N * f.P * f.Q;
+  const double wts = (double)f.K * f.R * f.S * f.C;
+  *flops = 0; *bytes = 0;
+  switch (s.kind) {
+    case S_CAST_IN: *bytes = in_px * f.C * (4 + e); break;
+    case S_CONV_FWD: *flops = 2 * out_px * wts; *bytes = e * (in_px * f.C + out_px * f.K + wts); break;
+    case S_DGRAD: *flops = 2 * out_px * wts; *bytes = e * (in_px * f.C * (s.in[1] >= 0 ? 2 : 1) + out_px * f.K + wts); break;
+    case S_WGRAD: *flops = 2 * out_px * wts; *bytes = e * (in_px * f.C + out_px * f.K) + 4 * wts; break;
+    case S_BN_STATS: *bytes = e * out_px * f.C; break;
+    case S_BN_APPLY: *bytes = e * out_px * f.C * (s.in[2] >= 0 ? 3 : 2); break;
+    case S_BN_BWD: *bytes = e * out_px * f.C * (2 + (s.in[3] >= 0 ? 1 : 0) + 3 + (s.in[3] >= 0 ? 1 : 0) + (s.out[1] >= 0 ? 1 : 0)); break;
+    case S_POOL_FWD: *bytes = e * (in_px + out_px) * f.C; break;
+    case S_POOL_BWD: *bytes = e * (2 * in_px + out_px) * f.C; break;
+    case S_RELU_BWD: *bytes = e * 3 * out_px * f.K; break;
+    case S_BIAS_GRAD: *bytes = e * out_px * f.K; break;
+    case S_HEAD_FWD: *bytes = e * in_px * f.C; break;
+    case S_HEAD_BWD: *bytes = e * in_px * f.C; break;
+  }
+}
+
+hipEvent_t next_event(optorch_seq_t* h) {
+  if (h->ev_used == h->ev_pool.size()) {
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    h->ev_pool.push_back(e);
+  }
+  return h->ev_pool[h->ev_used++];
+}
+
+void harvest(optorch_seq_t* h) {
+  for (size_t i = 0; i + 1 < h->ev_used; i += 2) {
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, h->ev_pool[i], h->ev_pool[i + 1]) == hipSuccess) h->prof_ms[h->ev_class[i / 2]] += ms;
+  }
+  h->ev_used = 0;
+  h->ev_class.clear();
+}
+
 }  // namespace
+
+extern "C" int optorch_seq_profile_enable(optorch_seq_t* h, int32_t enable) {
+  if (!h) return OPTORCH_E_INVALID;
+  if (h->bound) (void)hipStreamSynchronize(h->stream);
+  h->ev_used = 0; h->ev_class.clear();
+  h->prof_steps = 0;
+  for (int i = 0; i < OPTORCH_N_KERNEL_CLASSES; ++i) {
+    h->prof_launches[i] = h->prof_entries[i] = 0;
+    h->prof_ms[i] = h->prof_flops[i] = h->prof_bytes[i] = 0;
+  }
+  h->profiling = enable != 0;
+  return OPTORCH_OK;
+}
+
+extern "C" int optorch_seq_profile_read(optorch_seq_t* h, int32_t* steps, uint64_t* launches, uint64_t* entries,
+                                        double* gpu_ms, double* flops, double* bytes) {
+  if (!h) return OPTORCH_E_INVALID;
+  if (h->bound) {
+    hipError_t e = hipStreamSynchronize(h->stream);
+    if (e != hipSuccess) return hip_fail(h, e, "hipStreamSynchronize");
+  }
+  harvest(h);
+  if (steps) *steps = h->prof_steps;
+  for (int i = 0; i < OPTORCH_N_KERNEL_CLASSES; ++i) {
+    if (launches) launches[i] = h->prof_launches[i];
+    if (entries) entries[i] = h->prof_entries[i];
+    if (gpu_ms) gpu_ms[i] = h->prof_ms[i];
+    if (flops) flops[i] = h->prof_flops[i];
+    if (bytes) bytes[i] = h->prof_bytes[i];
+  }
+  return OPTORCH_OK;
+}
 
 extern "C" int optorch_seq_step(optorch_seq_t* h, const float* x_dev, const int32_t* y_dev, float lr, float* loss_out,
                                 float* grads_dev, uint64_t* peak_saved_bytes, uint64_t* peak_arena_bytes,
@@ -249,11 +372,40 @@ extern "C" int optorch_seq_step(optorch_seq_t* h, const float* x_dev, const int3
   Ctx c{h, x_dev, y_dev};
   hipStream_t st = h->stream;
   launch_step_init(st, c.flags());
-  for (const SOp& s : h->plan.sched)
-    if (s.live) run_op(c, s);
+  const bool prof = h->profiling;
+  if (prof && h->ev_used > (size_t)1 << 16) harvest(h);  // previous steps are complete: each step ends with a sync
+  for (const SOp& s : h->plan.sched) {
+    if (!s.live) continue;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    if (prof && (e0 = next_event(h)) && (e1 = next_event(h))) (void)hipEventRecord(e0, st);
+    run_op(c, s);
+    if (e1) {
+      (void)hipEventRecord(e1, st);
+      const int k = class_of(s.kind);
+      double fl, by;
+      work_of(h, s, &fl, &by);
+      h->ev_class.push_back(k);
+      h->prof_launches[k] += launches_of(s, h->plan.fops[s.fop]);
+      h->prof_entries[k] += 1; h->prof_flops[k] += fl; h->prof_bytes[k] += by;
+    }
+  }
   const int64_t P = (int64_t)h->plan.n_params;
-  launch_optim(st, h->dt, c.w32(0), (float*)(h->pbase + h->off_v), c.g32(0), h->pbase + h->off_h, grads_dev, P, lr,
-               h->momentum, 1.f / h->scale, c.flags());
+  {
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    if (prof && (e0 = next_event(h)) && (e1 = next_event(h))) (void)hipEventRecord(e0, st);
+    launch_optim(st, h->dt, c.w32(0), (float*)(h->pbase + h->off_v), c.g32(0), h->pbase + h->off_h, grads_dev, P, lr,
+                 h->momentum, 1.f / h->scale, c.flags());
+    if (e1) {
+      (void)hipEventRecord(e1, st);
+      const int k = OPTORCH_K_OPTIMIZER;
+      h->ev_class.push_back(k);
+      h->prof_launches[k] += 2; h->prof_entries[k] += 1;
+      // read g (check), read g, w [, v], write w [, v] [, 16-bit copy] [, unscaled g]
+      h->prof_bytes[k] += (double)P * (4 + 12 + (h->momentum != 0.f ? 8 : 0) + (h->dt != DT_F32 ? 2 : 0) + (grads_dev ? 4 : 0));
+    }
+    if (prof) h->prof_steps += 1;
+  }
+  refresh_transposed_weights(h);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return hip_fail(h, e, "kernel launch");
   e = hipMemcpyAsync(h->host_rb, h->pbase + h->off_scal, 128, hipMemcpyDeviceToHost, st);
@@ -283,5 +435,6 @@ extern "C" const char* optorch_seq_last_error(const optorch_seq_t* h) { return h
 extern "C" void optorch_seq_destroy(optorch_seq_t* h) {
   if (!h) return;
   if (h->host_rb) (void)hipHostFree(h->host_rb);
+  for (hipEvent_t e : h->ev_pool) (void)hipEventDestroy(e);
   delete h;
 }

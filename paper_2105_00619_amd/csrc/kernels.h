@@ -35,6 +35,15 @@ void launch_conv_dgrad_direct(hipStream_t st, int dt, const void* dz, const void
 void launch_conv_wgrad_direct(hipStream_t st, int dt, const void* x, const void* dz, float* dw, float* partial, int splits,
                               const ConvGeom& g);
 
+// matrix-core implicit GEMM (k_conv_mfma.hip); the *_ok predicates depend on the layer shape only
+bool conv_mfma_fwd_ok(int dt, const ConvGeom& g);
+bool conv_mfma_dgrad_ok(int dt, const ConvGeom& g);
+void launch_conv_fwd_mfma(hipStream_t st, int dt, const void* x, const void* w, const float* bias, void* out,
+                          const ConvGeom& g, int relu);
+void launch_conv_dgrad_mfma(hipStream_t st, int dt, const void* dz, const void* wt, const void* addend, void* dx,
+                            const ConvGeom& g);
+void launch_weight_transpose(hipStream_t st, int dt, const float* w, void* wt, int K, int RS, int C);
+
 void launch_step_init(hipStream_t st, int* flags);
 void launch_optim(hipStream_t st, int dt, float* w, float* v, const float* g, void* w16, float* gout, int64_t n, float lr,
                   float mom, float inv_scale, int* flags);
