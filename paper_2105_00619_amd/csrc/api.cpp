@@ -70,7 +70,18 @@ extern "C" int optorch_seq_create(const optorch_unit_t* units, int32_t n_units, 
   } else {
     p.cfg.boundaries = nullptr;
   }
-  bool ok = build_graph(p) && choose_segments(p) && build_schedule(p);
+  bool ok = build_graph(p);
+  if (ok) {  // kernel choice per convolution, from the layer shape only (never from k or from free memory)
+    for (FOp& f : p.fops)
+      if (f.kind == F_CONV) {
+        const ConvGeom g{f.N, f.H, f.W, f.C, f.K, f.R, f.S, f.stride, f.pad, f.P, f.Q};
+        f.fwd_algo = conv_mfma_fwd_ok(cfg->precision, g) ? ALGO_MFMA : ALGO_DIRECT;
+        f.dgrad_algo = conv_mfma_dgrad_ok(cfg->precision, g) ? ALGO_MFMA : ALGO_DIRECT;
+        f.wgrad_algo = conv_mfma_wgrad_ok(cfg->precision, g) ? ALGO_MFMA : ALGO_DIRECT;
+        if (f.wgrad_algo == ALGO_MFMA) f.wgrad_splits = conv_mfma_wgrad_splits(cfg->precision, g);
+      }
+    ok = choose_segments(p) && build_schedule(p);
+  }
   p.cfg.boundaries = nullptr;  // the copy dies with this call; seg_begin holds the result
   if (!ok) { g_create_error = p.error; delete h; return OPTORCH_E_INVALID; }
   if (cfg->activation_budget_bytes && p.arena_bytes > cfg->activation_budget_bytes) {
@@ -80,12 +91,6 @@ extern "C" int optorch_seq_create(const optorch_unit_t* units, int32_t n_units, 
     return OPTORCH_E_BUDGET;
   }
   h->dt = cfg->precision;
-  for (FOp& f : p.fops)
-    if (f.kind == F_CONV) {
-      const ConvGeom g{f.N, f.H, f.W, f.C, f.K, f.R, f.S, f.stride, f.pad, f.P, f.Q};
-      f.fwd_algo = conv_mfma_fwd_ok(h->dt, g) ? ALGO_MFMA : ALGO_DIRECT;
-      f.dgrad_algo = conv_mfma_dgrad_ok(h->dt, g) ? ALGO_MFMA : ALGO_DIRECT;
-    }
   h->eps = cfg->bn_eps > 0 ? cfg->bn_eps : 1e-5f;
   h->bn_mom = cfg->bn_momentum > 0 ? cfg->bn_momentum : 0.1f;
   h->momentum = cfg->momentum;
@@ -255,8 +260,12 @@ void run_op(const Ctx& c, const SOp& s) {
                        c.g32(f.b_off));
       break;
     case S_WGRAD:
-      launch_conv_wgrad_direct(st, dt, c.at(s.in[0]), c.at(s.in[1]), c.g32(f.w_off), (float*)c.at(s.out[0]), f.wgrad_splits,
+      if (f.wgrad_algo == ALGO_MFMA)
+        launch_conv_wgrad_mfma(st, dt, c.at(s.in[0]), c.at(s.in[1]), c.g32(f.w_off), (float*)c.at(s.out[0]), f.wgrad_splits,
                                geom(f));
+      else
+        launch_conv_wgrad_direct(st, dt, c.at(s.in[0]), c.at(s.in[1]), c.g32(f.w_off), (float*)c.at(s.out[0]),
+                                 f.wgrad_splits, geom(f));
       break;
     case S_DGRAD:
       if (f.dgrad_algo == ALGO_MFMA)

@@ -252,4 +252,264 @@ void launch_weight_transpose(hipStream_t st, int dt, const float* w, void* wt, i
   else hipLaunchKernelGGL(weight_transpose_kernel<f16_t>, grid, block, 0, st, w, (f16_t*)wt, K, RS, C);
 }
 
+// ------------------------------------------------------------------------------------------------------------
+// Weight gradient:  dw[k][tap][c] = sum over pixels m of dz[m][k] * x_tap[m][c]   (fp32 result)
+// One block owns a (BM output channels) x (BN input channels) tile of ONE filter tap and a fixed chunk of the
+// pixel range (blockIdx.z); chunks are summed afterwards in order, so the result does not depend on scheduling.
+// Both operands arrive pixel-major (the reduction index is the slow one), but an MFMA lane wants consecutive
+// reduction elements.  fp32: the tile is stored as loaded and lanes read it with a stride.  16-bit: each thread
+// loads two channels of several consecutive pixels, interleaves them in registers (byte permutes) and stores
+// channel-major rows, so the MFMA operands are read exactly as in the forward kernel.
+// ------------------------------------------------------------------------------------------------------------
+struct FastDiv {  // floor(m / d) for m * d < 2^48
+  uint64_t magic; uint32_t d;
+  __device__ __forceinline__ uint32_t div(uint32_t m) const { return (uint32_t)(((uint64_t)m * magic) >> 48); }
+};
+static FastDiv make_fastdiv(uint32_t d) { FastDiv f; f.d = d; f.magic = (((uint64_t)1 << 48) + d - 1) / d; return f; }
+
+struct WGradArgs {
+  int H, W, C, K, R, S, stride, pad, P, Q;
+  int pixels, chunk;  // chunk: pixels per blockIdx.z, a multiple of the depth tile
+  FastDiv divQ, divPQ;
+};
+
+template <class T> struct WFrag;
+template <> struct WFrag<float> {
+  static constexpr int DEPTH = 16;  // pixels per depth tile
+  float v[8];
+  __device__ __forceinline__ void load(const float* tile, int pitch, int col, int g) {
+#pragma unroll
+    for (int t = 0; t < 8; ++t) v[t] = tile[(g * 8 + t) * pitch + col];
+  }
+  __device__ static __forceinline__ void mma(const WFrag& a, const WFrag& b, v16f& c) {
+#pragma unroll
+    for (int t = 0; t < 8; ++t) c = __builtin_amdgcn_mfma_f32_32x32x2f32(a.v[t], b.v[t], c, 0, 0, 0);
+  }
+};
+
+__device__ __forceinline__ uint32_t pack_lo(uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x05040100u); }
+__device__ __forceinline__ uint32_t pack_hi(uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x07060302u); }
+
+template <class T, int BM, int BN>
+__global__ void __launch_bounds__(256) conv_wgrad_kernel(const T* __restrict__ x, const T* __restrict__ dz,
+                                                         float* __restrict__ out, WGradArgs a) {
+  constexpr bool F32 = sizeof(T) == 4;
+  constexpr int DEPTH = F32 ? 16 : 32;
+  constexpr int MI = BM / 64, NI = BN / 64;
+  // fp32: tiles [DEPTH][BM+4] floats; 16-bit: tiles [BM][DEPTH+8] halves (80-byte rows)
+  constexpr int A_ELEMS = F32 ? DEPTH * (BM + 4) : BM * (DEPTH + 8);
+  constexpr int B_ELEMS = F32 ? DEPTH * (BN + 4) : BN * (DEPTH + 8);
+  __shared__ __attribute__((aligned(16))) T As[2][A_ELEMS];
+  __shared__ __attribute__((aligned(16))) T Bs[2][B_ELEMS];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1, g = lane >> 5, l32 = lane & 31;
+  const int k0 = blockIdx.x * BM;
+  const int ctiles = a.C / BN;
+  const int tap = blockIdx.y / ctiles, c0 = (blockIdx.y - tap * ctiles) * BN;
+  const int r = tap / a.S, s = tap - r * a.S;
+  const int mbeg = blockIdx.z * a.chunk;
+  const int mend = mbeg + a.chunk < a.pixels ? mbeg + a.chunk : a.pixels;
+  const int ntiles = mend > mbeg ? (mend - mbeg + DEPTH - 1) / DEPTH : 0;
+
+  // ---- fp32 staging: 16-byte chunks, rows = pixels --------------------------------------------------------
+  constexpr int A_CH32 = DEPTH * (BM / 4) / 256 > 0 ? DEPTH * (BM / 4) / 256 : 1;
+  constexpr int B_CH32 = DEPTH * (BN / 4) / 256 > 0 ? DEPTH * (BN / 4) / 256 : 1;
+  // ---- 16-bit staging: each thread owns a channel pair and PXA / PXB consecutive pixels ---------------------
+  constexpr int PXA = BM / 16, PXB = BN / 16;
+  Chunk ra[F32 ? A_CH32 : 1], rb[F32 ? B_CH32 : 1];
+  uint32_t ha[F32 ? 1 : PXA], hb[F32 ? 1 : PXB];
+
+  auto src_pixel = [&](int m, int64_t& off) -> bool {  // x offset (elements) of pixel m under this block's tap
+    if (m >= mend) return false;
+    const uint32_t n = a.divPQ.div((uint32_t)m);
+    const uint32_t rem = (uint32_t)m - n * a.divPQ.d;
+    const uint32_t p = a.divQ.div(rem);
+    const uint32_t q = rem - p * a.divQ.d;
+    const int ih = (int)p * a.stride + r - a.pad, iw = (int)q * a.stride + s - a.pad;
+    if (ih < 0 || ih >= a.H || iw < 0 || iw >= a.W) return false;
+    off = (((int64_t)n * a.H + ih) * a.W + iw) * a.C;
+    return true;
+  };
+
+  auto gload = [&](int t) {
+    const int mt = mbeg + t * DEPTH;
+    if constexpr (F32) {
+#pragma unroll
+      for (int i = 0; i < A_CH32; ++i) {
+        const int id = tid + i * 256, px = id / (BM / 4), kv = id % (BM / 4);
+        const int m = mt + px;
+        ra[i] = (px < DEPTH && m < mend) ? *reinterpret_cast<const Chunk*>(dz + (int64_t)m * a.K + k0 + kv * 4)
+                                         : Chunk{{0u, 0u, 0u, 0u}};
+      }
+#pragma unroll
+      for (int i = 0; i < B_CH32; ++i) {
+        const int id = tid + i * 256, px = id / (BN / 4), cv = id % (BN / 4);
+        int64_t off = 0;
+        const bool ok = px < DEPTH && src_pixel(mt + px, off);
+        rb[i] = ok ? *reinterpret_cast<const Chunk*>(x + off + c0 + cv * 4) : Chunk{{0u, 0u, 0u, 0u}};
+      }
+    } else {
+      {
+        const int cp = tid % (BM / 2), pg = tid / (BM / 2);
+#pragma unroll
+        for (int i = 0; i < PXA; ++i) {
+          const int m = mt + pg * PXA + i;
+          ha[i] = m < mend ? *reinterpret_cast<const uint32_t*>(dz + (int64_t)m * a.K + k0 + 2 * cp) : 0u;
+        }
+      }
+      {
+        const int cp = tid % (BN / 2), pg = tid / (BN / 2);
+#pragma unroll
+        for (int i = 0; i < PXB; ++i) {
+          int64_t off = 0;
+          const bool ok = src_pixel(mt + pg * PXB + i, off);
+          hb[i] = ok ? *reinterpret_cast<const uint32_t*>(x + off + c0 + 2 * cp) : 0u;
+        }
+      }
+    }
+  };
+  auto sstore = [&](int buf) {
+    if constexpr (F32) {
+#pragma unroll
+      for (int i = 0; i < A_CH32; ++i) {
+        const int id = tid + i * 256, px = id / (BM / 4), kv = id % (BM / 4);
+        if (px < DEPTH) *reinterpret_cast<Chunk*>(&As[buf][px * (BM + 4) + kv * 4]) = ra[i];
+      }
+#pragma unroll
+      for (int i = 0; i < B_CH32; ++i) {
+        const int id = tid + i * 256, px = id / (BN / 4), cv = id % (BN / 4);
+        if (px < DEPTH) *reinterpret_cast<Chunk*>(&Bs[buf][px * (BN + 4) + cv * 4]) = rb[i];
+      }
+    } else {
+      {
+        const int cp = tid % (BM / 2), pg = tid / (BM / 2);
+        uint32_t* lo = reinterpret_cast<uint32_t*>(&As[buf][(2 * cp) * (DEPTH + 8) + pg * PXA]);
+        uint32_t* hi = reinterpret_cast<uint32_t*>(&As[buf][(2 * cp + 1) * (DEPTH + 8) + pg * PXA]);
+#pragma unroll
+        for (int i = 0; i < PXA / 2; ++i) { lo[i] = pack_lo(ha[2 * i], ha[2 * i + 1]); hi[i] = pack_hi(ha[2 * i], ha[2 * i + 1]); }
+      }
+      {
+        const int cp = tid % (BN / 2), pg = tid / (BN / 2);
+        uint32_t* lo = reinterpret_cast<uint32_t*>(&Bs[buf][(2 * cp) * (DEPTH + 8) + pg * PXB]);
+        uint32_t* hi = reinterpret_cast<uint32_t*>(&Bs[buf][(2 * cp + 1) * (DEPTH + 8) + pg * PXB]);
+#pragma unroll
+        for (int i = 0; i < PXB / 2; ++i) { lo[i] = pack_lo(hb[2 * i], hb[2 * i + 1]); hi[i] = pack_hi(hb[2 * i], hb[2 * i + 1]); }
+      }
+    }
+  };
+
+  v16f acc[MI][NI];
+#pragma unroll
+  for (int i = 0; i < MI; ++i)
+#pragma unroll
+    for (int j = 0; j < NI; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+  if (ntiles > 0) {
+    gload(0);
+    sstore(0);
+  }
+  __syncthreads();
+  for (int t = 0; t < ntiles; ++t) {
+    const int buf = t & 1;
+    if (t + 1 < ntiles) gload(t + 1);
+    if constexpr (F32) {
+      WFrag<float> fa[MI], fb[NI];
+#pragma unroll
+      for (int i = 0; i < MI; ++i) fa[i].load(reinterpret_cast<const float*>(As[buf]), BM + 4, wm * (BM / 2) + i * 32 + l32, g);
+#pragma unroll
+      for (int j = 0; j < NI; ++j) fb[j].load(reinterpret_cast<const float*>(Bs[buf]), BN + 4, wn * (BN / 2) + j * 32 + l32, g);
+#pragma unroll
+      for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NI; ++j) WFrag<float>::mma(fa[i], fb[j], acc[i][j]);
+    } else {
+      Frag<T> fa[MI], fb[NI];
+#pragma unroll
+      for (int i = 0; i < MI; ++i) fa[i].load(&As[buf][(wm * (BM / 2) + i * 32 + l32) * (DEPTH + 8) + g * 16]);
+#pragma unroll
+      for (int j = 0; j < NI; ++j) fb[j].load(&Bs[buf][(wn * (BN / 2) + j * 32 + l32) * (DEPTH + 8) + g * 16]);
+#pragma unroll
+      for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NI; ++j) Frag<T>::mma(fa[i], fb[j], acc[i][j]);
+    }
+    if (t + 1 < ntiles) sstore(buf ^ 1);
+    __syncthreads();
+  }
+
+  const int64_t outputs = (int64_t)a.K * a.R * a.S * a.C;
+  float* dst = out + (int64_t)blockIdx.z * outputs;
+#pragma unroll
+  for (int i = 0; i < MI; ++i)
+#pragma unroll
+    for (int j = 0; j < NI; ++j) {
+      const int c = c0 + wn * (BN / 2) + j * 32 + l32;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int k = k0 + wm * (BM / 2) + i * 32 + 8 * (e >> 2) + 4 * g + (e & 3);
+        dst[((int64_t)k * a.R * a.S + tap) * a.C + c] = acc[i][j][e];
+      }
+    }
+}
+
+bool conv_mfma_wgrad_ok(int dt, const ConvGeom& g) {
+  (void)dt;
+  return g.C % 64 == 0 && g.K % 64 == 0 && (int64_t)g.N * g.P * g.Q < (1 << 24) && g.P * g.Q < (1 << 24);
+}
+
+// number of pixel chunks, from the layer shape only
+int conv_mfma_wgrad_splits(int dt, const ConvGeom& g) {
+  const int depth = dt == DT_F32 ? 16 : 32;
+  const int bm = g.K % 128 == 0 ? 128 : 64, bn = g.C % 128 == 0 ? 128 : 64;
+  const int64_t tiles = (int64_t)(g.K / bm) * (g.C / bn) * g.R * g.S;
+  const int64_t pixels = (int64_t)g.N * g.P * g.Q;
+  int64_t want = (1024 + tiles - 1) / tiles;                       // aim at ~1024 blocks
+  const int64_t most = (pixels + 4 * depth - 1) / (4 * depth);     // at least four depth tiles per chunk
+  if (want > most) want = most;
+  if (want > 64) want = 64;
+  return (int)(want < 1 ? 1 : want);
+}
+
+template <class T>
+static void launch_wgrad_t(hipStream_t st, const void* x, const void* dz, float* dst, int splits, const ConvGeom& g) {
+  constexpr int depth = sizeof(T) == 4 ? 16 : 32;
+  WGradArgs a;
+  a.H = g.H; a.W = g.W; a.C = g.C; a.K = g.K; a.R = g.R; a.S = g.S; a.stride = g.stride; a.pad = g.pad; a.P = g.P; a.Q = g.Q;
+  a.pixels = g.N * g.P * g.Q;
+  int chunk = (a.pixels + splits - 1) / splits;
+  a.chunk = (chunk + depth - 1) / depth * depth;
+  a.divQ = make_fastdiv((uint32_t)g.Q);
+  a.divPQ = make_fastdiv((uint32_t)(g.P * g.Q));
+  const bool m128 = g.K % 128 == 0, n128 = g.C % 128 == 0;
+  const int bm = m128 ? 128 : 64, bn = n128 ? 128 : 64;
+  dim3 grid(g.K / bm, g.R * g.S * (g.C / bn), splits), block(256);
+  if (m128 && n128) hipLaunchKernelGGL((conv_wgrad_kernel<T, 128, 128>), grid, block, 0, st, (const T*)x, (const T*)dz, dst, a);
+  else if (m128) hipLaunchKernelGGL((conv_wgrad_kernel<T, 128, 64>), grid, block, 0, st, (const T*)x, (const T*)dz, dst, a);
+  else if (n128) hipLaunchKernelGGL((conv_wgrad_kernel<T, 64, 128>), grid, block, 0, st, (const T*)x, (const T*)dz, dst, a);
+  else hipLaunchKernelGGL((conv_wgrad_kernel<T, 64, 64>), grid, block, 0, st, (const T*)x, (const T*)dz, dst, a);
+}
+
+__global__ void wgrad_reduce_kernel(const float* __restrict__ partial, float* __restrict__ out, int64_t n, int splits) {
+  const int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
+  if (i >= n) return;
+  v4f acc = *reinterpret_cast<const v4f*>(partial + i);
+  for (int s = 1; s < splits; ++s) acc += *reinterpret_cast<const v4f*>(partial + (int64_t)s * n + i);
+  *reinterpret_cast<v4f*>(out + i) = acc;
+}
+
+void launch_conv_wgrad_mfma(hipStream_t st, int dt, const void* x, const void* dz, float* dw, float* partial, int splits,
+                            const ConvGeom& g) {
+  float* dst = splits > 1 ? partial : dw;
+  if (dt == DT_F32) launch_wgrad_t<float>(st, x, dz, dst, splits, g);
+  else if (dt == DT_BF16) launch_wgrad_t<bf16_t>(st, x, dz, dst, splits, g);
+  else launch_wgrad_t<f16_t>(st, x, dz, dst, splits, g);
+  if (splits > 1) {
+    const int64_t n = (int64_t)g.K * g.R * g.S * g.C;  // a multiple of 4 (C % 64 == 0)
+    hipLaunchKernelGGL(wgrad_reduce_kernel, dim3(ceil_div(n / 4, 256)), dim3(256), 0, st, partial, dw, n, splits);
+  }
+}
+
 }  // namespace oseq

@@ -42,6 +42,10 @@ void launch_conv_fwd_mfma(hipStream_t st, int dt, const void* x, const void* w, 
                           const ConvGeom& g, int relu);
 void launch_conv_dgrad_mfma(hipStream_t st, int dt, const void* dz, const void* wt, const void* addend, void* dx,
                             const ConvGeom& g);
+bool conv_mfma_wgrad_ok(int dt, const ConvGeom& g);
+int conv_mfma_wgrad_splits(int dt, const ConvGeom& g);
+void launch_conv_wgrad_mfma(hipStream_t st, int dt, const void* x, const void* dz, float* dw, float* partial, int splits,
+                            const ConvGeom& g);
 void launch_weight_transpose(hipStream_t st, int dt, const float* w, void* wt, int K, int RS, int C);
 
 void launch_step_init(hipStream_t st, int* flags);
