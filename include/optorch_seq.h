@@ -153,6 +153,13 @@ int optorch_seq_profile_enable(optorch_seq_t* h, int32_t enable);
 int optorch_seq_profile_read(optorch_seq_t* h, int32_t* steps, uint64_t* launches, uint64_t* entries, double* gpu_ms,
                              double* flops, double* bytes);
 
+/* The same timing per schedule entry (one entry = one operation of one unit in one phase; live entries only, in
+ * launch order).  capacity: length of the host out arrays; *n receives the number of entries (it may exceed
+ * capacity, then only the first `capacity` are written).  kind: optorch_kernel_class_t; phase: 0 forward without
+ * keeping, 1 forward of the last segment, 2 replay, 3 backward; gpu_ms, flops, bytes: sums over the profiled steps. */
+int optorch_seq_profile_read_entries(optorch_seq_t* h, int32_t capacity, int32_t* n, int32_t* kind, int32_t* unit,
+                                     int32_t* phase, double* gpu_ms, double* flops, double* bytes);
+
 const char* optorch_seq_last_error(const optorch_seq_t* h);
 void optorch_seq_destroy(optorch_seq_t* h);
 

@@ -20,7 +20,7 @@ OK, E_INVALID, E_BUDGET, E_HIP, E_ORDER = 0, -1, -2, -3, -4
 SYMBOLS = (
     "optorch_seq_create", "optorch_seq_query", "optorch_seq_bind", "optorch_seq_set_params",
     "optorch_seq_get_params", "optorch_seq_step", "optorch_seq_schedule_info", "optorch_seq_last_error",
-    "optorch_seq_destroy", "optorch_seq_profile_enable", "optorch_seq_profile_read",
+    "optorch_seq_destroy", "optorch_seq_profile_enable", "optorch_seq_profile_read", "optorch_seq_profile_read_entries",
 )
 
 KERNEL_CLASSES = ("cast_in", "conv_fwd", "conv_dgrad", "conv_wgrad", "bn_stats", "bn_apply", "bn_bwd", "pool", "head",
@@ -78,6 +78,10 @@ def load_library() -> C.CDLL:
     lib.optorch_seq_profile_read.argtypes = [H, C.POINTER(C.c_int32), C.POINTER(C.c_uint64), C.POINTER(C.c_uint64),
                                              C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_double)]
     lib.optorch_seq_profile_read.restype = C.c_int
+    lib.optorch_seq_profile_read_entries.argtypes = [H, C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_int32),
+                                                     C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_double),
+                                                     C.POINTER(C.c_double), C.POINTER(C.c_double)]
+    lib.optorch_seq_profile_read_entries.restype = C.c_int
     lib.optorch_seq_last_error.argtypes = [H]
     lib.optorch_seq_last_error.restype = C.c_char_p
     lib.optorch_seq_destroy.argtypes = [H]
@@ -229,3 +233,13 @@ class SeqTrainer(SeqPlan):
         for i, name in enumerate(KERNEL_CLASSES):
             out["classes"][name] = {"launches": la[i], "entries": en[i], "gpu_ms": ms[i], "flops": fl[i], "bytes": by[i]}
         return out
+
+    def profile_read_entries(self) -> list:
+        """Per schedule entry, in launch order: kernel class, unit, phase, GPU ms, algorithmic FLOPs and bytes."""
+        cap = 8192
+        n = C.c_int32()
+        kind, unit, phase = (C.c_int32 * cap)(), (C.c_int32 * cap)(), (C.c_int32 * cap)()
+        ms, fl, by = (C.c_double * cap)(), (C.c_double * cap)(), (C.c_double * cap)()
+        self._check(self.lib.optorch_seq_profile_read_entries(self.handle, cap, C.byref(n), kind, unit, phase, ms, fl, by))
+        return [{"kind": KERNEL_CLASSES[kind[i]], "unit": unit[i], "phase": phase[i], "gpu_ms": ms[i], "flops": fl[i],
+                 "bytes": by[i]} for i in range(min(n.value, cap))]

@@ -32,6 +32,8 @@ struct optorch_seq {
   std::vector<hipEvent_t> ev_pool;
   size_t ev_used = 0;
   std::vector<int> ev_class;  // class of pair i
+  std::vector<int> ev_entry;  // schedule index of pair i (-1: optimizer)
+  std::vector<double> entry_ms;  // per schedule entry
   int prof_steps = 0;
   uint64_t prof_launches[OPTORCH_N_KERNEL_CLASSES] = {0}, prof_entries[OPTORCH_N_KERNEL_CLASSES] = {0};
   double prof_ms[OPTORCH_N_KERNEL_CLASSES] = {0}, prof_flops[OPTORCH_N_KERNEL_CLASSES] = {0},
@@ -75,10 +77,14 @@ extern "C" int optorch_seq_create(const optorch_unit_t* units, int32_t n_units, 
     for (FOp& f : p.fops)
       if (f.kind == F_CONV) {
         const ConvGeom g{f.N, f.H, f.W, f.C, f.K, f.R, f.S, f.stride, f.pad, f.P, f.Q};
-        f.fwd_algo = conv_mfma_fwd_ok(cfg->precision, g) ? ALGO_MFMA : ALGO_DIRECT;
-        f.dgrad_algo = conv_mfma_dgrad_ok(cfg->precision, g) ? ALGO_MFMA : ALGO_DIRECT;
-        f.wgrad_algo = conv_mfma_wgrad_ok(cfg->precision, g) ? ALGO_MFMA : ALGO_DIRECT;
-        if (f.wgrad_algo == ALGO_MFMA) f.wgrad_splits = conv_mfma_wgrad_splits(cfg->precision, g);
+        const int dt = cfg->precision;
+        f.fwd_algo = conv_mfma_fwd_ok(dt, g) ? ALGO_MFMA : conv_smallc_fwd_ok(g) ? ALGO_SMALLC : ALGO_DIRECT;
+        f.dgrad_algo = conv_mfma_dgrad_ok(dt, g) ? ALGO_MFMA : ALGO_DIRECT;
+        f.wgrad_algo = conv_mfma_wgrad_ok(dt, g) ? ALGO_MFMA : conv_smallc_wgrad_ok(g) ? ALGO_SMALLC : ALGO_DIRECT;
+        if (f.fwd_algo == ALGO_MFMA) f.fwd_splits = conv_mfma_fwd_splits(dt, g);
+        if (f.dgrad_algo == ALGO_MFMA) f.dgrad_splits = conv_mfma_dgrad_splits(dt, g);
+        if (f.wgrad_algo == ALGO_MFMA) f.wgrad_splits = conv_mfma_wgrad_splits(dt, g);
+        if (f.wgrad_algo == ALGO_SMALLC) f.wgrad_splits = conv_smallc_wgrad_splits(g);
       }
     ok = choose_segments(p) && build_schedule(p);
   }
@@ -221,7 +227,10 @@ void run_op(const Ctx& c, const SOp& s) {
     case S_CONV_FWD:
       if (f.fwd_algo == ALGO_MFMA)
         launch_conv_fwd_mfma(st, dt, c.at(s.in[0]), c.wc(f.w_off), f.has_bias ? c.w32(f.b_off) : nullptr, c.at(s.out[0]),
-                             geom(f), f.relu);
+                             (float*)c.at(s.out[1]), f.fwd_splits, geom(f), f.relu);
+      else if (f.fwd_algo == ALGO_SMALLC)
+        launch_conv_fwd_smallc(st, dt, c.at(s.in[0]), c.wc(f.w_off), f.has_bias ? c.w32(f.b_off) : nullptr, c.at(s.out[0]),
+                               geom(f), f.relu);
       else
         launch_conv_fwd_direct(st, dt, c.at(s.in[0]), c.wc(f.w_off), f.has_bias ? c.w32(f.b_off) : nullptr, c.at(s.out[0]),
                                geom(f), f.relu);
@@ -263,6 +272,9 @@ void run_op(const Ctx& c, const SOp& s) {
       if (f.wgrad_algo == ALGO_MFMA)
         launch_conv_wgrad_mfma(st, dt, c.at(s.in[0]), c.at(s.in[1]), c.g32(f.w_off), (float*)c.at(s.out[0]), f.wgrad_splits,
                                geom(f));
+      else if (f.wgrad_algo == ALGO_SMALLC)
+        launch_conv_wgrad_smallc(st, dt, c.at(s.in[0]), c.at(s.in[1]), c.g32(f.w_off), (float*)c.at(s.out[0]),
+                                 f.wgrad_splits, geom(f));
       else
         launch_conv_wgrad_direct(st, dt, c.at(s.in[0]), c.at(s.in[1]), c.g32(f.w_off), (float*)c.at(s.out[0]),
                                  f.wgrad_splits, geom(f));
@@ -270,7 +282,7 @@ void run_op(const Ctx& c, const SOp& s) {
     case S_DGRAD:
       if (f.dgrad_algo == ALGO_MFMA)
         launch_conv_dgrad_mfma(st, dt, c.at(s.in[0]), h->pbase + h->off_wt + (uint64_t)f.w_off * h->plan.esize, c.at(s.in[1]),
-                               c.at(s.out[0]), geom(f));
+                               c.at(s.out[0]), (float*)c.at(s.out[1]), f.dgrad_splits, geom(f));
       else
         launch_conv_dgrad_direct(st, dt, c.at(s.in[0]), c.wc(f.w_off), c.at(s.in[1]), c.at(s.out[0]), geom(f));
       break;
@@ -331,10 +343,14 @@ hipEvent_t next_event(optorch_seq_t* h) {
 void harvest(optorch_seq_t* h) {
   for (size_t i = 0; i + 1 < h->ev_used; i += 2) {
     float ms = 0.f;
-    if (hipEventElapsedTime(&ms, h->ev_pool[i], h->ev_pool[i + 1]) == hipSuccess) h->prof_ms[h->ev_class[i / 2]] += ms;
+    if (hipEventElapsedTime(&ms, h->ev_pool[i], h->ev_pool[i + 1]) == hipSuccess) {
+      h->prof_ms[h->ev_class[i / 2]] += ms;
+      if (h->ev_entry[i / 2] >= 0) h->entry_ms[h->ev_entry[i / 2]] += ms;
+    }
   }
   h->ev_used = 0;
   h->ev_class.clear();
+  h->ev_entry.clear();
 }
 
 }  // namespace
@@ -342,7 +358,8 @@ void harvest(optorch_seq_t* h) {
 extern "C" int optorch_seq_profile_enable(optorch_seq_t* h, int32_t enable) {
   if (!h) return OPTORCH_E_INVALID;
   if (h->bound) (void)hipStreamSynchronize(h->stream);
-  h->ev_used = 0; h->ev_class.clear();
+  h->ev_used = 0; h->ev_class.clear(); h->ev_entry.clear();
+  h->entry_ms.assign(h->plan.sched.size(), 0.0);
   h->prof_steps = 0;
   for (int i = 0; i < OPTORCH_N_KERNEL_CLASSES; ++i) {
     h->prof_launches[i] = h->prof_entries[i] = 0;
@@ -371,6 +388,34 @@ extern "C" int optorch_seq_profile_read(optorch_seq_t* h, int32_t* steps, uint64
   return OPTORCH_OK;
 }
 
+extern "C" int optorch_seq_profile_read_entries(optorch_seq_t* h, int32_t capacity, int32_t* n, int32_t* kind, int32_t* unit,
+                                                int32_t* phase, double* gpu_ms, double* flops, double* bytes) {
+  if (!h || !n) return OPTORCH_E_INVALID;
+  if (h->bound) {
+    hipError_t e = hipStreamSynchronize(h->stream);
+    if (e != hipSuccess) return hip_fail(h, e, "hipStreamSynchronize");
+  }
+  harvest(h);
+  int32_t cnt = 0;
+  for (size_t si = 0; si < h->plan.sched.size(); ++si) {
+    const SOp& s = h->plan.sched[si];
+    if (!s.live) continue;
+    if (cnt < capacity) {
+      double fl, by;
+      work_of(h, s, &fl, &by);
+      if (kind) kind[cnt] = class_of(s.kind);
+      if (unit) unit[cnt] = h->plan.fops[s.fop].unit;
+      if (phase) phase[cnt] = s.phase;
+      if (gpu_ms) gpu_ms[cnt] = si < h->entry_ms.size() ? h->entry_ms[si] : 0.0;
+      if (flops) flops[cnt] = fl * h->prof_steps;
+      if (bytes) bytes[cnt] = by * h->prof_steps;
+    }
+    ++cnt;
+  }
+  *n = cnt;
+  return OPTORCH_OK;
+}
+
 extern "C" int optorch_seq_step(optorch_seq_t* h, const float* x_dev, const int32_t* y_dev, float lr, float* loss_out,
                                 float* grads_dev, uint64_t* peak_saved_bytes, uint64_t* peak_arena_bytes,
                                 float* loss_scale_out, int32_t* step_skipped) {
@@ -383,7 +428,8 @@ extern "C" int optorch_seq_step(optorch_seq_t* h, const float* x_dev, const int3
   launch_step_init(st, c.flags());
   const bool prof = h->profiling;
   if (prof && h->ev_used > (size_t)1 << 16) harvest(h);  // previous steps are complete: each step ends with a sync
-  for (const SOp& s : h->plan.sched) {
+  for (size_t si = 0; si < h->plan.sched.size(); ++si) {
+    const SOp& s = h->plan.sched[si];
     if (!s.live) continue;
     hipEvent_t e0 = nullptr, e1 = nullptr;
     if (prof && (e0 = next_event(h)) && (e1 = next_event(h))) (void)hipEventRecord(e0, st);
@@ -394,6 +440,7 @@ extern "C" int optorch_seq_step(optorch_seq_t* h, const float* x_dev, const int3
       double fl, by;
       work_of(h, s, &fl, &by);
       h->ev_class.push_back(k);
+      h->ev_entry.push_back((int)si);
       h->prof_launches[k] += launches_of(s, h->plan.fops[s.fop]);
       h->prof_entries[k] += 1; h->prof_flops[k] += fl; h->prof_bytes[k] += by;
     }
@@ -408,6 +455,7 @@ extern "C" int optorch_seq_step(optorch_seq_t* h, const float* x_dev, const int3
       (void)hipEventRecord(e1, st);
       const int k = OPTORCH_K_OPTIMIZER;
       h->ev_class.push_back(k);
+      h->ev_entry.push_back(-1);
       h->prof_launches[k] += 2; h->prof_entries[k] += 1;
       // read g (check), read g, w [, v], write w [, v] [, 16-bit copy] [, unscaled g]
       h->prof_bytes[k] += (double)P * (4 + 12 + (h->momentum != 0.f ? 8 : 0) + (h->dt != DT_F32 ? 2 : 0) + (grads_dev ? 4 : 0));

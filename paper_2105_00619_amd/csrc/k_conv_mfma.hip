@@ -33,6 +33,7 @@ struct IGemmArgs {
   int dstH, dstW;         // pixel grid of the result
   int M, Ng, Kg;          // GEMM sizes: rows (pixels), columns (channels), depth (R*S*srcC)
   int R, S, stride, pad, relu;
+  int kt_per_split;       // depth tiles per blockIdx.z when the depth is split
 };
 
 template <class T> struct Frag;  // 32 bytes of one operand row, and the MFMAs that consume it
@@ -71,10 +72,12 @@ template <> struct Frag<f16_t> {
 // Within a depth tile the two lane groups (lanes 0-31, 32-63) own disjoint halves of the depth range and every MFMA
 // pairs the same depth indices of A and B, so any assignment of depth indices to (lane group, step) gives the same sum.
 
-template <class T, int BN, int MODE>
+// SPLIT: blockIdx.z owns a fixed range of depth tiles and writes raw fp32 sums to partial[z][M][Ng]; a second
+// kernel adds the ranges in order and applies the epilogue (layers with few output pixels, to fill the chip).
+template <class T, int BN, int MODE, bool SPLIT>
 __global__ void __launch_bounds__(256) conv_igemm_kernel(const T* __restrict__ src, const T* __restrict__ wmat,
                                                          const float* __restrict__ bias, const T* __restrict__ addend,
-                                                         T* __restrict__ out, IGemmArgs a) {
+                                                         T* __restrict__ out, float* __restrict__ partial, IGemmArgs a) {
   constexpr int BM = 128;
   constexpr int BK = Frag<T>::BK;
   constexpr int EV = 16 / (int)sizeof(T);   // elements per 16-byte chunk
@@ -146,11 +149,14 @@ __global__ void __launch_bounds__(256) conv_igemm_kernel(const T* __restrict__ s
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-  const int nkt = a.Kg / BK;
-  gload(0);
-  sstore(0);
+  const int kt0 = SPLIT ? blockIdx.z * a.kt_per_split : 0;
+  const int nkt = SPLIT ? (kt0 + a.kt_per_split < a.Kg / BK ? kt0 + a.kt_per_split : a.Kg / BK) : a.Kg / BK;
+  if (kt0 < nkt) {
+    gload(kt0);
+    sstore(kt0 & 1);
+  }
   __syncthreads();
-  for (int kt = 0; kt < nkt; ++kt) {
+  for (int kt = kt0; kt < nkt; ++kt) {
     const int buf = kt & 1;
     if (kt + 1 < nkt) gload(kt + 1);
     Frag<T> fa[2], fb[NI];
@@ -178,36 +184,80 @@ __global__ void __launch_bounds__(256) conv_igemm_kernel(const T* __restrict__ s
         const int row = m0 + wm * 64 + i * 32 + 8 * (e >> 2) + 4 * g + (e & 3);
         if (row < a.M) {
           const int64_t o = (int64_t)row * a.Ng + col;
-          float v = acc[i][j][e] + bv;
-          if (addend) v += to_f32(addend[o]);
-          if (a.relu) v = fmaxf(v, 0.f);
-          out[o] = from_f32<T>(v);
+          if (SPLIT) {
+            partial[(int64_t)blockIdx.z * a.M * a.Ng + o] = acc[i][j][e];
+          } else {
+            float v = acc[i][j][e] + bv;
+            if (addend) v += to_f32(addend[o]);
+            if (a.relu) v = fmaxf(v, 0.f);
+            out[o] = from_f32<T>(v);
+          }
         }
       }
     }
 }
 
+template <class T>
+__global__ void __launch_bounds__(256) splitk_epilogue_kernel(const float* __restrict__ partial, int splits, int64_t n, int Ng,
+                                                              const float* __restrict__ bias, const T* __restrict__ addend,
+                                                              T* __restrict__ out, int relu) {
+  const int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
+  if (i >= n) return;
+  v4f acc = *reinterpret_cast<const v4f*>(partial + i);
+  for (int z = 1; z < splits; ++z) acc += *reinterpret_cast<const v4f*>(partial + (int64_t)z * n + i);
+  const int col = (int)(i % Ng);
+  float r[4];
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    float v = acc[e];
+    if (bias) v += bias[col + e];
+    if (addend) v += to_f32(addend[i + e]);
+    r[e] = relu ? fmaxf(v, 0.f) : v;
+  }
+  store_f32<T, 4>(out + i, r);
+}
+
 template <class T, int MODE>
 static void launch_igemm_t(hipStream_t st, const void* src, const void* wmat, const float* bias, const void* addend, void* out,
-                           const IGemmArgs& a) {
-  if (a.Ng % 128 == 0) {
-    dim3 grid(ceil_div(a.M, 128), a.Ng / 128);
-    hipLaunchKernelGGL((conv_igemm_kernel<T, 128, MODE>), grid, dim3(256), 0, st, (const T*)src, (const T*)wmat, bias,
-                       (const T*)addend, (T*)out, a);
+                           float* partial, int splits, const IGemmArgs& a0) {
+  IGemmArgs a = a0;
+  const int bk = Frag<T>::BK;
+  a.kt_per_split = ceil_div(a.Kg / bk, splits);
+  const bool wide = a.Ng % 128 == 0;
+  dim3 grid(ceil_div(a.M, 128), a.Ng / (wide ? 128 : 64), splits), block(256);
+  if (splits > 1) {
+    if (wide) hipLaunchKernelGGL((conv_igemm_kernel<T, 128, MODE, true>), grid, block, 0, st, (const T*)src, (const T*)wmat, bias, (const T*)addend, (T*)out, partial, a);
+    else hipLaunchKernelGGL((conv_igemm_kernel<T, 64, MODE, true>), grid, block, 0, st, (const T*)src, (const T*)wmat, bias, (const T*)addend, (T*)out, partial, a);
+    const int64_t n = (int64_t)a.M * a.Ng;  // a multiple of 4: Ng % 64 == 0
+    hipLaunchKernelGGL(splitk_epilogue_kernel<T>, dim3(ceil_div(n / 4, 256)), dim3(256), 0, st, partial, splits, n, a.Ng, bias,
+                       (const T*)addend, (T*)out, a.relu);
   } else {
-    dim3 grid(ceil_div(a.M, 128), a.Ng / 64);
-    hipLaunchKernelGGL((conv_igemm_kernel<T, 64, MODE>), grid, dim3(256), 0, st, (const T*)src, (const T*)wmat, bias,
-                       (const T*)addend, (T*)out, a);
+    if (wide) hipLaunchKernelGGL((conv_igemm_kernel<T, 128, MODE, false>), grid, block, 0, st, (const T*)src, (const T*)wmat, bias, (const T*)addend, (T*)out, partial, a);
+    else hipLaunchKernelGGL((conv_igemm_kernel<T, 64, MODE, false>), grid, block, 0, st, (const T*)src, (const T*)wmat, bias, (const T*)addend, (T*)out, partial, a);
   }
 }
 
 template <int MODE>
 static void launch_igemm(hipStream_t st, int dt, const void* src, const void* wmat, const float* bias, const void* addend,
-                         void* out, const IGemmArgs& a) {
-  if (dt == DT_F32) launch_igemm_t<float, MODE>(st, src, wmat, bias, addend, out, a);
-  else if (dt == DT_BF16) launch_igemm_t<bf16_t, MODE>(st, src, wmat, bias, addend, out, a);
-  else launch_igemm_t<f16_t, MODE>(st, src, wmat, bias, addend, out, a);
+                         void* out, float* partial, int splits, const IGemmArgs& a) {
+  if (dt == DT_F32) launch_igemm_t<float, MODE>(st, src, wmat, bias, addend, out, partial, splits, a);
+  else if (dt == DT_BF16) launch_igemm_t<bf16_t, MODE>(st, src, wmat, bias, addend, out, partial, splits, a);
+  else launch_igemm_t<f16_t, MODE>(st, src, wmat, bias, addend, out, partial, splits, a);
 }
+
+// depth splits of a GEMM with M rows, Ng columns and depth Kg: from the shape only
+static int igemm_splits(int dt, int64_t M, int Ng, int Kg) {
+  const int bk = dt == DT_F32 ? 16 : 32;
+  const int64_t blocks = ((M + 127) / 128) * (Ng / (Ng % 128 == 0 ? 128 : 64));
+  if (blocks >= 256) return 1;
+  int64_t s = (512 + blocks - 1) / blocks;
+  const int64_t most = (Kg / bk) / 8;  // at least eight depth tiles per range
+  if (s > most) s = most;
+  if (s > 32) s = 32;
+  return (int)(s < 1 ? 1 : s);
+}
+int conv_mfma_fwd_splits(int dt, const ConvGeom& g) { return igemm_splits(dt, (int64_t)g.N * g.P * g.Q, g.K, g.R * g.S * g.C); }
+int conv_mfma_dgrad_splits(int dt, const ConvGeom& g) { return igemm_splits(dt, (int64_t)g.N * g.H * g.W, g.C, g.R * g.S * g.K); }
 
 bool conv_mfma_fwd_ok(int dt, const ConvGeom& g) {
   const int bk = dt == DT_F32 ? 16 : 32;
@@ -219,16 +269,16 @@ bool conv_mfma_dgrad_ok(int dt, const ConvGeom& g) {
 }
 
 void launch_conv_fwd_mfma(hipStream_t st, int dt, const void* x, const void* w, const float* bias, void* out,
-                          const ConvGeom& g, int relu) {
-  IGemmArgs a{g.H, g.W, g.C, g.P, g.Q, g.N * g.P * g.Q, g.K, g.R * g.S * g.C, g.R, g.S, g.stride, g.pad, relu};
-  launch_igemm<IG_FWD>(st, dt, x, w, bias, nullptr, out, a);
+                          float* partial, int splits, const ConvGeom& g, int relu) {
+  IGemmArgs a{g.H, g.W, g.C, g.P, g.Q, g.N * g.P * g.Q, g.K, g.R * g.S * g.C, g.R, g.S, g.stride, g.pad, relu, 0};
+  launch_igemm<IG_FWD>(st, dt, x, w, bias, nullptr, out, partial, splits, a);
 }
 
 // wt: the (C_in, kh, kw, C_out) transpose of the weights, in the compute type
 void launch_conv_dgrad_mfma(hipStream_t st, int dt, const void* dz, const void* wt, const void* addend, void* dx,
-                            const ConvGeom& g) {
-  IGemmArgs a{g.P, g.Q, g.K, g.H, g.W, g.N * g.H * g.W, g.C, g.R * g.S * g.K, g.R, g.S, g.stride, g.pad, 0};
-  launch_igemm<IG_DGRAD>(st, dt, dz, wt, nullptr, addend, dx, a);
+                            float* partial, int splits, const ConvGeom& g) {
+  IGemmArgs a{g.P, g.Q, g.K, g.H, g.W, g.N * g.H * g.W, g.C, g.R * g.S * g.K, g.R, g.S, g.stride, g.pad, 0, 0};
+  launch_igemm<IG_DGRAD>(st, dt, dz, wt, nullptr, addend, dx, partial, splits, a);
 }
 
 // (C_out, R*S, C_in) fp32 master weights -> (C_in, R*S, C_out) in the compute type

@@ -121,23 +121,41 @@ static void launch_colreduce(hipStream_t st, int dt, const RedArgs& g) {
   else launch_colreduce_t<f16_t, MODE>(st, g);
 }
 
-// finishing kernels: one thread per channel sums the block partials in order, in double
-__global__ void bn_stats_finalize_kernel(const float* __restrict__ partial, int nblk, int C, double m, float eps,
-                                         float mom, const float* __restrict__ gamma, const float* __restrict__ beta,
-                                         float* __restrict__ stats, float* __restrict__ running) {
-  const int c = blockIdx.x * blockDim.x + threadIdx.x;
+// finishing kernels: one wavefront per channel; lane l sums the block partials l, l+64, ... in double, then the
+// 64 lane sums are combined by a fixed butterfly, so the result is the same on every run
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+  return v;
+}
+
+__device__ __forceinline__ void partial_sums(const float* __restrict__ partial, int nblk, int C, int c, double& s, double& q) {
+  const int lane = threadIdx.x & 63;
+  s = 0.0; q = 0.0;
+  for (int b = lane; b < nblk; b += 64) {
+    s += (double)partial[((int64_t)b * 2) * C + c];
+    q += (double)partial[((int64_t)b * 2 + 1) * C + c];
+  }
+  s = wave_sum(s);
+  q = wave_sum(q);
+}
+
+__global__ void __launch_bounds__(256) bn_stats_finalize_kernel(const float* __restrict__ partial, int nblk, int C, double m,
+                                                                float eps, float mom, const float* __restrict__ gamma,
+                                                                const float* __restrict__ beta, float* __restrict__ stats,
+                                                                float* __restrict__ running) {
+  const int c = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (c >= C) return;
-  double s = 0.0, q = 0.0;
-  for (int b = 0; b < nblk; ++b) { s += (double)partial[((int64_t)b * 2) * C + c]; q += (double)partial[((int64_t)b * 2 + 1) * C + c]; }
+  double s, q;
+  partial_sums(partial, nblk, C, c, s, q);
+  if ((threadIdx.x & 63) != 0) return;
   const double mean = s / m;
   double var = q / m - mean * mean;
   if (var < 0.0) var = 0.0;
   const double rstd = 1.0 / sqrt(var + (double)eps);
-  const float scale = (float)((double)gamma[c] * rstd);
-  const float fmean = (float)mean;
-  stats[c] = fmean;
+  stats[c] = (float)mean;
   stats[C + c] = (float)rstd;
-  stats[2 * C + c] = scale;
+  stats[2 * C + c] = (float)((double)gamma[c] * rstd);
   stats[3 * C + c] = (float)((double)beta[c] - mean * (double)gamma[c] * rstd);
   if (running) {
     const double unbiased = m > 1.0 ? var * m / (m - 1.0) : var;
@@ -146,24 +164,27 @@ __global__ void bn_stats_finalize_kernel(const float* __restrict__ partial, int 
   }
 }
 
-__global__ void bn_bwd_finalize_kernel(const float* __restrict__ partial, int nblk, int C, double m,
-                                       float* __restrict__ dgamma, float* __restrict__ dbeta, float* __restrict__ coef) {
-  const int c = blockIdx.x * blockDim.x + threadIdx.x;
+__global__ void __launch_bounds__(256) bn_bwd_finalize_kernel(const float* __restrict__ partial, int nblk, int C, double m,
+                                                              float* __restrict__ dgamma, float* __restrict__ dbeta,
+                                                              float* __restrict__ coef) {
+  const int c = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (c >= C) return;
-  double s = 0.0, q = 0.0;
-  for (int b = 0; b < nblk; ++b) { s += (double)partial[((int64_t)b * 2) * C + c]; q += (double)partial[((int64_t)b * 2 + 1) * C + c]; }
+  double s, q;
+  partial_sums(partial, nblk, C, c, s, q);
+  if ((threadIdx.x & 63) != 0) return;
   dbeta[c] = (float)s;
   dgamma[c] = (float)q;
   coef[c] = (float)(s / m);
   coef[C + c] = (float)(q / m);
 }
 
-__global__ void bias_finalize_kernel(const float* __restrict__ partial, int nblk, int C, float* __restrict__ dbias) {
-  const int c = blockIdx.x * blockDim.x + threadIdx.x;
+__global__ void __launch_bounds__(256) bias_finalize_kernel(const float* __restrict__ partial, int nblk, int C,
+                                                            float* __restrict__ dbias) {
+  const int c = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (c >= C) return;
-  double s = 0.0;
-  for (int b = 0; b < nblk; ++b) s += (double)partial[((int64_t)b * 2) * C + c];
-  dbias[c] = (float)s;
+  double s, q;
+  partial_sums(partial, nblk, C, c, s, q);
+  if ((threadIdx.x & 63) == 0) dbias[c] = (float)s;
 }
 
 // ------------------------------------------------------------- BN apply -----
@@ -318,7 +339,7 @@ void launch_bn_stats(hipStream_t st, int dt, const void* z, int64_t rows, int C,
                      float mom, const float* gamma, const float* beta, float* stats, float* running) {
   RedArgs g{}; g.a = z; g.partial = partial; g.rows = rows; g.C = C; g.nblk = nblk;
   launch_colreduce<RED_STATS>(st, dt, g);
-  hipLaunchKernelGGL(bn_stats_finalize_kernel, dim3(ceil_div(C, 128)), dim3(128), 0, st, partial, nblk, C, (double)rows,
+  hipLaunchKernelGGL(bn_stats_finalize_kernel, dim3(ceil_div(C, 4)), dim3(256), 0, st, partial, nblk, C, (double)rows,
                      eps, mom, gamma, beta, stats, running);
 }
 
@@ -338,7 +359,7 @@ void launch_bn_bwd(hipStream_t st, int dt, const void* da, const void* z, const 
   g.nblk = nblk;
   launch_colreduce<RED_BN_BWD>(st, dt, g);
   float* coef = ws + (int64_t)nblk * 2 * C;
-  hipLaunchKernelGGL(bn_bwd_finalize_kernel, dim3(ceil_div(C, 128)), dim3(128), 0, st, ws, nblk, C, (double)rows, dgamma,
+  hipLaunchKernelGGL(bn_bwd_finalize_kernel, dim3(ceil_div(C, 4)), dim3(256), 0, st, ws, nblk, C, (double)rows, dgamma,
                      dbeta, coef);
 #define CALL(T, V)                                                                                                      \
   { const int64_t groups = rows * (C / V);                                                                               \
@@ -360,7 +381,7 @@ void launch_relu_bwd(hipStream_t st, int dt, const void* da, const void* a, void
 void launch_bias_grad(hipStream_t st, int dt, const void* dz, int64_t rows, int C, int nblk, float* partial, float* dbias) {
   RedArgs g{}; g.a = dz; g.partial = partial; g.rows = rows; g.C = C; g.nblk = nblk;
   launch_colreduce<RED_BIAS>(st, dt, g);
-  hipLaunchKernelGGL(bias_finalize_kernel, dim3(ceil_div(C, 128)), dim3(128), 0, st, partial, nblk, C, dbias);
+  hipLaunchKernelGGL(bias_finalize_kernel, dim3(ceil_div(C, 4)), dim3(256), 0, st, partial, nblk, C, dbias);
 }
 
 void launch_maxpool_fwd(hipStream_t st, int dt, const void* x, void* y, int N, int H, int W, int C) {

@@ -35,13 +35,25 @@ void launch_conv_dgrad_direct(hipStream_t st, int dt, const void* dz, const void
 void launch_conv_wgrad_direct(hipStream_t st, int dt, const void* x, const void* dz, float* dw, float* partial, int splits,
                               const ConvGeom& g);
 
+// few input channels (the stem): plain-FMA kernels with the weights in LDS
+bool conv_smallc_fwd_ok(const ConvGeom& g);
+bool conv_smallc_wgrad_ok(const ConvGeom& g);
+int conv_smallc_wgrad_splits(const ConvGeom& g);
+void launch_conv_fwd_smallc(hipStream_t st, int dt, const void* x, const void* w, const float* bias, void* out,
+                            const ConvGeom& g, int relu);
+void launch_conv_wgrad_smallc(hipStream_t st, int dt, const void* x, const void* dz, float* dw, float* partial, int splits,
+                              const ConvGeom& g);
+
 // matrix-core implicit GEMM (k_conv_mfma.hip); the *_ok predicates depend on the layer shape only
 bool conv_mfma_fwd_ok(int dt, const ConvGeom& g);
 bool conv_mfma_dgrad_ok(int dt, const ConvGeom& g);
+int conv_mfma_fwd_splits(int dt, const ConvGeom& g);
+int conv_mfma_dgrad_splits(int dt, const ConvGeom& g);
+// partial: fp32 workspace of splits * (output elements) floats when splits > 1, else unused
 void launch_conv_fwd_mfma(hipStream_t st, int dt, const void* x, const void* w, const float* bias, void* out,
-                          const ConvGeom& g, int relu);
+                          float* partial, int splits, const ConvGeom& g, int relu);
 void launch_conv_dgrad_mfma(hipStream_t st, int dt, const void* dz, const void* wt, const void* addend, void* dx,
-                            const ConvGeom& g);
+                            float* partial, int splits, const ConvGeom& g);
 bool conv_mfma_wgrad_ok(int dt, const ConvGeom& g);
 int conv_mfma_wgrad_splits(int dt, const ConvGeom& g);
 void launch_conv_wgrad_mfma(hipStream_t st, int dt, const void* x, const void* dz, float* dw, float* partial, int splits,

@@ -250,7 +250,12 @@ struct Scheduler {
     const FOp& f = p.fops[fi];
     switch (f.kind) {
       case F_CAST_IN: { SOp& s = push(S_CAST_IN, fi, phase, seg); s.out[0] = value_inst(f.out); break; }
-      case F_CONV: { SOp& s = push(S_CONV_FWD, fi, phase, seg); s.in[0] = cur[f.x]; s.out[0] = value_inst(f.out); break; }
+      case F_CONV: {
+        SOp& s = push(S_CONV_FWD, fi, phase, seg);
+        s.in[0] = cur[f.x]; s.out[0] = value_inst(f.out);
+        if (f.fwd_splits > 1) s.out[1] = new_inst(-1, (uint64_t)f.fwd_splits * f.N * f.P * f.Q * f.K * 4, false);
+        break;
+      }
       case F_BN_STATS: {
         if (phase == PH_REPLAY) break;  // the statistics of the first forward pass are kept and reused
         SOp& s = push(S_BN_STATS, fi, phase, seg);
@@ -323,6 +328,7 @@ struct Scheduler {
           SOp& s = push(S_DGRAD, fi, PH_BWD, seg);
           s.in[0] = g; s.in[1] = grad[f.x];
           s.out[0] = grad_inst(f.x); grad[f.x] = s.out[0];
+          if (f.dgrad_splits > 1) s.out[1] = new_inst(-1, (uint64_t)f.dgrad_splits * f.N * f.H * f.W * f.C * 4, false);
         }
         return true;
       }
@@ -369,6 +375,8 @@ int launches_of(const SOp& op, const FOp& f) {
     case S_BN_BWD: return 3;
     case S_BIAS_GRAD: return 2;
     case S_WGRAD: return f.wgrad_splits > 1 ? 2 : 1;
+    case S_CONV_FWD: return f.fwd_splits > 1 ? 2 : 1;
+    case S_DGRAD: return f.dgrad_splits > 1 ? 2 : 1;
     default: return 1;
   }
 }

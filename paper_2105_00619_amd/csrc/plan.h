@@ -31,7 +31,7 @@ struct LTensor {
 
 enum FKind { F_CAST_IN, F_CONV, F_BN_STATS, F_BN_APPLY, F_POOL, F_HEAD };
 
-enum ConvAlgo { ALGO_DIRECT = 0, ALGO_MFMA = 1 };
+enum ConvAlgo { ALGO_DIRECT = 0, ALGO_MFMA = 1, ALGO_SMALLC = 2 };
 
 // One forward operation of the network.
 struct FOp {
@@ -46,6 +46,7 @@ struct FOp {
   int gap = 0, feat_dim = 0, classes = 0;
   int fwd_algo = ALGO_DIRECT, dgrad_algo = ALGO_DIRECT, wgrad_algo = ALGO_DIRECT;
   int wgrad_splits = 1;      // fixed by shape only: deterministic split of the pixel reduction
+  int fwd_splits = 1, dgrad_splits = 1;  // fixed by shape only: deterministic split of the GEMM depth
   int red_blocks = 1;        // row blocks of the per-channel reductions (BN statistics, BN backward)
 };
 
