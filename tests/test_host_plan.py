@@ -1,0 +1,119 @@
+"""Host-side tests (no GPU): the C-ABI library loads and exports what the header declares; the planner's
+byte counts, boundaries, budget check and argument validation."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2105_00619_amd import workloads as W
+from paper_2105_00619_amd import binding
+from paper_2105_00619_amd.binding import OptorchError, SeqPlan
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _built():
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2105_00619_amd import build
+        build.build(verbose=False)
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "optorch_seq.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(optorch_seq_\w+)\s*\(", header))
+    assert declared and declared == set(binding.SYMBOLS)
+    lib = ctypes.CDLL(binding.LIB_PATH)
+    for name in declared:
+        assert getattr(lib, name) is not None
+
+
+def _plan(idx, **kw):
+    return SeqPlan.from_workload(W.config(idx), **kw)
+
+
+def test_param_counts_match_generator_layout():
+    for idx in (1, 2, 3, 4, 5):
+        w = W.config(idx)
+        assert _plan(idx, activation_budget_bytes=0).param_count == W.param_count(w.units, w.height, w.width)
+
+
+def test_config2_all_stored_bytes_match_the_analytic_count():
+    # VGG-11-BN, fp32, batch 128, every activation stored: the input, per conv the pre-BN output Z, the post-ReLU
+    # output A and the four per-channel BN vectors, per pool its output (the last pool's output feeds only the head,
+    # which keeps the flattened features and the loss gradient instead)
+    b, e = 128, 4
+    h, total, c = 32, b * 32 * 32 * 3 * e, 3
+    widths = [64, "M", 128, "M", 256, 256, "M", 512, 512, "M", 512, 512, "M"]
+    for i, wd in enumerate(widths):
+        if wd == "M":
+            h //= 2
+            if i != len(widths) - 1:
+                total += b * h * h * c * e
+        else:
+            c = wd
+            total += 2 * b * h * h * c * e + 4 * c * 4
+    total += b * 512 * 4 + b * 10 * 4  # head: features, loss gradient w.r.t. logits
+    p = _plan(2, k_segments=1)
+    assert p.planned_peak_saved_bytes == total
+    assert p.n_replay_launches == 0
+
+
+def test_peak_shrinks_with_segments_and_plan_is_reproducible():
+    p1, p4, p4b = _plan(2, k_segments=1), _plan(2, k_segments=4), _plan(2, k_segments=4)
+    assert p4.boundaries == [3, 6, 9] == p4b.boundaries
+    assert p4.planned_peak_saved_bytes < 0.6 * p1.planned_peak_saved_bytes
+    assert (p4.act_arena_bytes, p4.planned_peak_saved_bytes) == (p4b.act_arena_bytes, p4b.planned_peak_saved_bytes)
+    assert p4.n_replay_launches > 0 and p4.n_launches > p1.n_launches
+    assert p4.act_arena_bytes >= p4.planned_peak_saved_bytes
+    # the byte-aware plan is never worse than the equal-count plan
+    pm = _plan(2, k_segments=4, plan_mode=1)
+    assert pm.planned_peak_saved_bytes <= p4.planned_peak_saved_bytes
+    # 16-bit storage halves the activation bytes of the same plan (BN vectors and the fp32 head aside)
+    ph = _plan(2, k_segments=1, precision=W.BF16)
+    assert 0.49 < ph.planned_peak_saved_bytes / p1.planned_peak_saved_bytes < 0.51
+
+
+def test_min_peak_plan_checkpoints_at_the_narrow_layer():
+    # an hour-glass: wide - wide - narrow - wide - wide; one boundary (k = 2) belongs after the narrow layer
+    units = [W.conv(3, 64), W.conv(64, 64), W.conv(64, 8), W.conv(8, 64), W.conv(64, 64), W.gap_linear_ce(64, 10)]
+    p = SeqPlan(units, k_segments=2, precision=W.FP32, batch=32, height=32, width=32, channels=3, num_classes=10, plan_mode=1)
+    assert p.boundaries == [3]
+    eq = SeqPlan(units, k_segments=2, precision=W.FP32, batch=32, height=32, width=32, channels=3, num_classes=10, plan_mode=0)
+    assert p.planned_peak_saved_bytes <= eq.planned_peak_saved_bytes
+    ex = SeqPlan(units, k_segments=2, precision=W.FP32, batch=32, height=32, width=32, channels=3, num_classes=10, boundaries=[3])
+    assert ex.planned_peak_saved_bytes == p.planned_peak_saved_bytes
+
+
+def test_config5_budget_needs_the_byte_aware_plan():
+    w = W.config(5)
+    ok = SeqPlan.from_workload(w)  # min-peak plan, 32 GiB budget
+    assert ok.act_arena_bytes <= 32 << 30
+    with pytest.raises(OptorchError) as e:
+        SeqPlan.from_workload(w, plan_mode=0)  # equal count does not fit
+    assert e.value.code == binding.E_BUDGET
+    with pytest.raises(OptorchError) as e:
+        SeqPlan.from_workload(w, k_segments=1)  # all stored: far above the budget
+    assert e.value.code == binding.E_BUDGET
+    free = SeqPlan.from_workload(w, k_segments=1, activation_budget_bytes=0)
+    assert free.planned_peak_saved_bytes > 3 * ok.planned_peak_saved_bytes
+
+
+@pytest.mark.parametrize("units,kw", [
+    ([W.conv(4, 8), W.gap_linear_ce(8, 10)], {}),                                   # cin does not match the image
+    ([W.conv(3, 8)], {}),                                                            # no loss head
+    ([W.gap_linear_ce(3, 10), W.conv(3, 8)], {}),                                    # head not last
+    ([W.conv(3, 8), W.gap_linear_ce(8, 7)], {}),                                     # classes mismatch
+    ([W.conv(3, 8, ksize=5, pad=2), W.gap_linear_ce(8, 10)], {}),                    # unsupported filter size
+    ([W.conv(3, 8), W.gap_linear_ce(8, 10)], {"k_segments": 3}),                     # more segments than units
+    ([W.conv(3, 8), W.conv(8, 8), W.gap_linear_ce(8, 10)], {"k_segments": 2, "boundaries": [0]}),  # bad boundary
+    ([W.conv(3, 8), W.gap_linear_ce(8, 10)], {"precision": 7}),
+])
+def test_invalid_arguments_are_rejected(units, kw):
+    args = dict(k_segments=1, precision=W.FP32, batch=4, height=8, width=8, channels=3, num_classes=10)
+    args.update(kw)
+    with pytest.raises(OptorchError) as e:
+        SeqPlan(units, **args)
+    assert e.value.code == binding.E_INVALID and str(e.value)
