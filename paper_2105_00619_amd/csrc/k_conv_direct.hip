@@ -168,15 +168,21 @@ __global__ void __launch_bounds__(256) conv_wgrad_smallc_kernel(const T* __restr
 #pragma unroll
   for (int j = 0; j < SMALLC_MAX / 4; ++j) acc[j] = 0.f;
   for (int64_t mt = m0; mt < m1; mt += 64) {
-    for (int i = threadIdx.x; i < 64 * g.K; i += 256) {
+    // all global loads of the sub-tile are issued before the first LDS store (fixed trip counts, unrolled)
+    float vd[16], vx[(64 * SMALLC_MAX + 255) / 256];
+#pragma unroll
+    for (int it = 0; it < 16; ++it) {
+      const int i = threadIdx.x + it * 256;
       const int px = i / g.K, k = i - px * g.K;
-      dzs[px * 65 + k] = mt + px < m1 ? to_f32(dz[(mt + px) * g.K + k]) : 0.f;
+      vd[it] = (i < 64 * g.K && mt + px < m1) ? to_f32(dz[(mt + px) * g.K + k]) : 0.f;
     }
-    for (int i = threadIdx.x; i < 64 * rsc; i += 256) {
+#pragma unroll
+    for (int it = 0; it < (64 * SMALLC_MAX + 255) / 256; ++it) {
+      const int i = threadIdx.x + it * 256;
       const int px = i / rsc, e = i - px * rsc;
       float v = 0.f;
       const int64_t m = mt + px;
-      if (m < m1) {
+      if (i < 64 * rsc && m < m1) {
         const int c = e % g.C, tap = e / g.C, s = tap % g.S, r = tap / g.S;
         const int q = (int)(m % g.Q);
         const int64_t t = m / g.Q;
@@ -184,10 +190,23 @@ __global__ void __launch_bounds__(256) conv_wgrad_smallc_kernel(const T* __restr
         const int ih = p * g.stride + r - g.pad, iw = q * g.stride + s - g.pad;
         if (ih >= 0 && ih < g.H && iw >= 0 && iw < g.W) v = to_f32(x[(((int64_t)n * g.H + ih) * g.W + iw) * g.C + c]);
       }
-      xs[px * (SMALLC_MAX + 1) + e] = v;
+      vx[it] = v;
+    }
+#pragma unroll
+    for (int it = 0; it < 16; ++it) {
+      const int i = threadIdx.x + it * 256;
+      const int px = i / g.K, k = i - px * g.K;
+      if (i < 64 * g.K) dzs[px * 65 + k] = vd[it];
+    }
+#pragma unroll
+    for (int it = 0; it < (64 * SMALLC_MAX + 255) / 256; ++it) {
+      const int i = threadIdx.x + it * 256;
+      const int px = i / rsc, e = i - px * rsc;
+      if (i < 64 * rsc) xs[px * (SMALLC_MAX + 1) + e] = vx[it];
     }
     __syncthreads();
     if (tk < g.K) {
+#pragma unroll 4
       for (int px = 0; px < 64; ++px) {
         const float d = dzs[px * 65 + tk];
 #pragma unroll
@@ -220,7 +239,7 @@ bool conv_smallc_fwd_ok(const ConvGeom& g) { return g.C <= 4 && g.R == 3 && g.S 
 bool conv_smallc_wgrad_ok(const ConvGeom& g) { return g.C <= 4 && g.R * g.S * g.C <= SMALLC_MAX && g.K <= 64; }
 int conv_smallc_wgrad_splits(const ConvGeom& g) {
   const int64_t pixels = (int64_t)g.N * g.P * g.Q;
-  int64_t b = (pixels + 511) / 512;
+  int64_t b = (pixels + 255) / 256;
   return (int)(b < 1 ? 1 : (b > 1024 ? 1024 : b));
 }
 

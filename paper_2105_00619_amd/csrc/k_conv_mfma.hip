@@ -24,7 +24,9 @@ typedef __attribute__((ext_vector_type(8))) __bf16 v8bf;
 typedef __attribute__((ext_vector_type(8))) _Float16 v8h;
 typedef __attribute__((ext_vector_type(4))) float v4f;
 
-struct alignas(16) Chunk { uint32_t w[4]; };
+// 16 bytes in flight between global memory and LDS: a first-class vector value, never a stack object
+typedef __attribute__((ext_vector_type(4))) uint32_t Chunk;
+__device__ __forceinline__ Chunk zero_chunk() { Chunk c = {0u, 0u, 0u, 0u}; return c; }
 
 enum { IG_FWD = 0, IG_DGRAD = 1 };
 
@@ -41,7 +43,19 @@ template <> struct Frag<float> {
   static constexpr int BK = 16;
   v4f lo, hi;
   __device__ __forceinline__ void load(const float* p) { lo = *(const v4f*)p; hi = *(const v4f*)(p + 4); }
+  __device__ __forceinline__ void load_lo(const float* p) { lo = *(const v4f*)p; }
+  __device__ __forceinline__ void load_hi(const float* p) { hi = *(const v4f*)(p + 4); }
+  static constexpr int HALF_STEPS = 4;  // MFMAs per operand half
+  __device__ static __forceinline__ void mma_half(const Frag& a, const Frag& b, v16f& c, int half, int t) {
+    c = half == 0 ? __builtin_amdgcn_mfma_f32_32x32x2f32(a.lo[t], b.lo[t], c, 0, 0, 0)
+                  : __builtin_amdgcn_mfma_f32_32x32x2f32(a.hi[t], b.hi[t], c, 0, 0, 0);
+  }
   static constexpr int lane_off(int g) { return g * 8; }
+  static constexpr int STEPS = 8;
+  __device__ static __forceinline__ void mma_step(const Frag& a, const Frag& b, v16f& c, int t) {
+    c = t < 4 ? __builtin_amdgcn_mfma_f32_32x32x2f32(a.lo[t & 3], b.lo[t & 3], c, 0, 0, 0)
+              : __builtin_amdgcn_mfma_f32_32x32x2f32(a.hi[t & 3], b.hi[t & 3], c, 0, 0, 0);
+  }
   __device__ static __forceinline__ void mma(const Frag& a, const Frag& b, v16f& c) {
 #pragma unroll
     for (int t = 0; t < 4; ++t) c = __builtin_amdgcn_mfma_f32_32x32x2f32(a.lo[t], b.lo[t], c, 0, 0, 0);
@@ -53,7 +67,19 @@ template <> struct Frag<bf16_t> {
   static constexpr int BK = 32;
   v8bf lo, hi;
   __device__ __forceinline__ void load(const bf16_t* p) { lo = *(const v8bf*)p; hi = *(const v8bf*)(p + 8); }
+  __device__ __forceinline__ void load_lo(const bf16_t* p) { lo = *(const v8bf*)p; }
+  __device__ __forceinline__ void load_hi(const bf16_t* p) { hi = *(const v8bf*)(p + 8); }
+  static constexpr int HALF_STEPS = 1;
+  __device__ static __forceinline__ void mma_half(const Frag& a, const Frag& b, v16f& c, int half, int) {
+    c = half == 0 ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.lo, b.lo, c, 0, 0, 0)
+                  : __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.hi, b.hi, c, 0, 0, 0);
+  }
   static constexpr int lane_off(int g) { return g * 16; }
+  static constexpr int STEPS = 2;
+  __device__ static __forceinline__ void mma_step(const Frag& a, const Frag& b, v16f& c, int t) {
+    c = t == 0 ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.lo, b.lo, c, 0, 0, 0)
+               : __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.hi, b.hi, c, 0, 0, 0);
+  }
   __device__ static __forceinline__ void mma(const Frag& a, const Frag& b, v16f& c) {
     c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.lo, b.lo, c, 0, 0, 0);
     c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.hi, b.hi, c, 0, 0, 0);
@@ -63,7 +89,19 @@ template <> struct Frag<f16_t> {
   static constexpr int BK = 32;
   v8h lo, hi;
   __device__ __forceinline__ void load(const f16_t* p) { lo = *(const v8h*)p; hi = *(const v8h*)(p + 8); }
+  __device__ __forceinline__ void load_lo(const f16_t* p) { lo = *(const v8h*)p; }
+  __device__ __forceinline__ void load_hi(const f16_t* p) { hi = *(const v8h*)(p + 8); }
+  static constexpr int HALF_STEPS = 1;
+  __device__ static __forceinline__ void mma_half(const Frag& a, const Frag& b, v16f& c, int half, int) {
+    c = half == 0 ? __builtin_amdgcn_mfma_f32_32x32x16_f16(a.lo, b.lo, c, 0, 0, 0)
+                  : __builtin_amdgcn_mfma_f32_32x32x16_f16(a.hi, b.hi, c, 0, 0, 0);
+  }
   static constexpr int lane_off(int g) { return g * 16; }
+  static constexpr int STEPS = 2;
+  __device__ static __forceinline__ void mma_step(const Frag& a, const Frag& b, v16f& c, int t) {
+    c = t == 0 ? __builtin_amdgcn_mfma_f32_32x32x16_f16(a.lo, b.lo, c, 0, 0, 0)
+               : __builtin_amdgcn_mfma_f32_32x32x16_f16(a.hi, b.hi, c, 0, 0, 0);
+  }
   __device__ static __forceinline__ void mma(const Frag& a, const Frag& b, v16f& c) {
     c = __builtin_amdgcn_mfma_f32_32x32x16_f16(a.lo, b.lo, c, 0, 0, 0);
     c = __builtin_amdgcn_mfma_f32_32x32x16_f16(a.hi, b.hi, c, 0, 0, 0);
@@ -74,20 +112,25 @@ template <> struct Frag<f16_t> {
 
 // SPLIT: blockIdx.z owns a fixed range of depth tiles and writes raw fp32 sums to partial[z][M][Ng]; a second
 // kernel adds the ranges in order and applies the epilogue (layers with few output pixels, to fill the chip).
-template <class T, int BN, int MODE, bool SPLIT>
+// Pipeline: two LDS stages and two register generations; the global loads of depth tile j+2 are issued before the
+// MFMAs of tile j and stored to LDS after the MFMAs of tile j+1, so they have two compute phases to arrive.
+template <int V> struct IC { static constexpr int value = V; };
+
+template <class T, int BM, int BN, int MODE, bool SPLIT>
 __global__ void __launch_bounds__(256) conv_igemm_kernel(const T* __restrict__ src, const T* __restrict__ wmat,
                                                          const float* __restrict__ bias, const T* __restrict__ addend,
                                                          T* __restrict__ out, float* __restrict__ partial, IGemmArgs a) {
-  constexpr int BM = 128;
   constexpr int BK = Frag<T>::BK;
   constexpr int EV = 16 / (int)sizeof(T);   // elements per 16-byte chunk
   constexpr int PITCH = BK + EV;            // LDS row pitch in elements (80 bytes)
-  constexpr int NI = BN / 64;               // 32-column MFMA tiles per wavefront
+  constexpr int MI = BM / 64, NI = BN / 64; // 32x32 MFMA tiles per wavefront
   constexpr int A_CH = BM * 4 / 256;        // 16-byte chunks per thread and depth tile (4 chunks per row)
   constexpr int B_CH = BN * 4 / 256;
   __shared__ T As[2][BM * PITCH];
   __shared__ T Bs[2][BN * PITCH];
 
+  // kernel arguments used inside the loaders, as plain scalars (the struct itself must not be captured by address)
+  const int srcH = a.srcH, srcW = a.srcW, srcC = a.srcC, S_ = a.S, stride = a.stride, pad = a.pad, Kg = a.Kg;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1, g = lane >> 5, l32 = lane & 31;
   const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
@@ -95,93 +138,106 @@ __global__ void __launch_bounds__(256) conv_igemm_kernel(const T* __restrict__ s
 
   // pixel coordinates of this thread's A rows
   int pn[A_CH], pa[A_CH], pb[A_CH];
-  bool prow[A_CH];
 #pragma unroll
   for (int i = 0; i < A_CH; ++i) {
     const int m = m0 + row0 + i * 64;
-    prow[i] = m < a.M;
-    const int mm = prow[i] ? m : 0;
+    const int mm = m < a.M ? m : 0;
     pb[i] = mm % a.dstW;
     const int t = mm / a.dstW;
     pa[i] = t % a.dstH;
-    pn[i] = t / a.dstH;
+    pn[i] = m < a.M ? t / a.dstH : -1;  // -1: row beyond the last pixel
   }
   const T* brow[B_CH];
 #pragma unroll
-  for (int i = 0; i < B_CH; ++i) brow[i] = wmat + (int64_t)(n0 + row0 + i * 64) * a.Kg + vec * EV;
+  for (int i = 0; i < B_CH; ++i) brow[i] = wmat + (int64_t)(n0 + row0 + i * 64) * Kg + vec * EV;
 
-  Chunk ra[A_CH], rb[B_CH];
-  auto gload = [&](int kt) {
+  // Global loads are unconditional (addresses of out-of-image taps are clamped into the tensor) and the zeroing is
+  // applied when the chunk is written to LDS: straight-line loads let the hardware keep several generations in flight.
+  Chunk ra[2][A_CH], rb[2][B_CH];
+  unsigned okm[2] = {0u, 0u};  // per generation: bit i set if A chunk i is inside the image
+  auto gload = [&, srcH, srcW, srcC, S_, stride, pad](auto P, int kt) {
+    constexpr int p = decltype(P)::value;
     const int kk0 = kt * BK;
-    const int tap = kk0 / a.srcC, c0 = kk0 - tap * a.srcC;
-    const int r = tap / a.S, s = tap - r * a.S;
+    const int tap = kk0 / srcC, c0 = kk0 - tap * srcC;
+    const int r = tap / S_, s = tap - r * S_;
+    unsigned m = 0u;
 #pragma unroll
     for (int i = 0; i < A_CH; ++i) {
       int y, x;
-      bool ok = prow[i];
+      bool ok = pn[i] >= 0;
       if (MODE == IG_FWD) {
-        y = pa[i] * a.stride + r - a.pad;
-        x = pb[i] * a.stride + s - a.pad;
+        y = pa[i] * stride + r - pad;
+        x = pb[i] * stride + s - pad;
       } else {
-        const int ty = pa[i] + a.pad - r, tx = pb[i] + a.pad - s;
+        const int ty = pa[i] + pad - r, tx = pb[i] + pad - s;
         ok = ok && ty >= 0 && tx >= 0;
-        if (a.stride == 2) { ok = ok && !((ty | tx) & 1); y = ty >> 1; x = tx >> 1; } else { y = ty; x = tx; }
+        if (stride == 2) { ok = ok && !((ty | tx) & 1); y = ty >> 1; x = tx >> 1; } else { y = ty; x = tx; }
       }
-      ok = ok && y >= 0 && y < a.srcH && x >= 0 && x < a.srcW;
-      if (ok) ra[i] = *reinterpret_cast<const Chunk*>(src + (((int64_t)pn[i] * a.srcH + y) * a.srcW + x) * a.srcC + c0 + vec * EV);
-      else ra[i] = Chunk{{0u, 0u, 0u, 0u}};
+      ok = ok && y >= 0 && y < srcH && x >= 0 && x < srcW;
+      const int yc = ok ? y : 0, xc = ok ? x : 0, nc = ok ? pn[i] : 0;
+      ra[p][i] = *reinterpret_cast<const Chunk*>(src + (((int64_t)nc * srcH + yc) * srcW + xc) * srcC + c0 + vec * EV);
+      m |= ok ? (1u << i) : 0u;
     }
+    okm[p] = m;
 #pragma unroll
-    for (int i = 0; i < B_CH; ++i) rb[i] = *reinterpret_cast<const Chunk*>(brow[i] + kk0);
+    for (int i = 0; i < B_CH; ++i) rb[p][i] = *reinterpret_cast<const Chunk*>(brow[i] + kk0);
   };
-  auto sstore = [&](int buf) {
+  auto sstore = [&](auto P) {  // generation p goes to LDS stage p
+    constexpr int p = decltype(P)::value;
 #pragma unroll
-    for (int i = 0; i < A_CH; ++i) *reinterpret_cast<Chunk*>(&As[buf][(row0 + i * 64) * PITCH + vec * EV]) = ra[i];
+    for (int i = 0; i < A_CH; ++i)
+      *reinterpret_cast<Chunk*>(&As[p][(row0 + i * 64) * PITCH + vec * EV]) = ((okm[p] >> i) & 1u) ? ra[p][i] : zero_chunk();
 #pragma unroll
-    for (int i = 0; i < B_CH; ++i) *reinterpret_cast<Chunk*>(&Bs[buf][(row0 + i * 64) * PITCH + vec * EV]) = rb[i];
+    for (int i = 0; i < B_CH; ++i) *reinterpret_cast<Chunk*>(&Bs[p][(row0 + i * 64) * PITCH + vec * EV]) = rb[p][i];
   };
 
-  v16f acc[2][NI];
+  v16f acc[MI][NI];
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < MI; ++i)
 #pragma unroll
     for (int j = 0; j < NI; ++j)
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
   const int kt0 = SPLIT ? blockIdx.z * a.kt_per_split : 0;
-  const int nkt = SPLIT ? (kt0 + a.kt_per_split < a.Kg / BK ? kt0 + a.kt_per_split : a.Kg / BK) : a.Kg / BK;
-  if (kt0 < nkt) {
-    gload(kt0);
-    sstore(kt0 & 1);
-  }
+  const int kt1 = SPLIT ? (kt0 + a.kt_per_split < a.Kg / BK ? kt0 + a.kt_per_split : a.Kg / BK) : a.Kg / BK;
+  const int n = kt1 > kt0 ? kt1 - kt0 : 0;
+  if (n > 0) { gload(IC<0>{}, kt0); sstore(IC<0>{}); }
+  if (n > 1) gload(IC<1>{}, kt0 + 1);
   __syncthreads();
-  for (int kt = kt0; kt < nkt; ++kt) {
-    const int buf = kt & 1;
-    if (kt + 1 < nkt) gload(kt + 1);
-    Frag<T> fa[2], fb[NI];
+  auto body = [&](auto P, int j) {  // depth tile j of this block; its data sits in LDS stage p = j & 1
+    constexpr int p = decltype(P)::value;
+    if (j + 2 < n) gload(P, kt0 + j + 2);
+    Frag<T> fa[MI], fb[NI];
 #pragma unroll
-    for (int i = 0; i < 2; ++i) fa[i].load(&As[buf][(wm * 64 + i * 32 + l32) * PITCH + Frag<T>::lane_off(g)]);
+    for (int i = 0; i < MI; ++i) fa[i].load(&As[p][(wm * (BM / 2) + i * 32 + l32) * PITCH + Frag<T>::lane_off(g)]);
 #pragma unroll
-    for (int j = 0; j < NI; ++j) fb[j].load(&Bs[buf][(wn * (BN / 2) + j * 32 + l32) * PITCH + Frag<T>::lane_off(g)]);
+    for (int jn = 0; jn < NI; ++jn) fb[jn].load(&Bs[p][(wn * (BN / 2) + jn * 32 + l32) * PITCH + Frag<T>::lane_off(g)]);
+    // consecutive MFMAs go to different accumulators, so none waits for the one issued just before it
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int t = 0; t < Frag<T>::STEPS; ++t)
 #pragma unroll
-      for (int j = 0; j < NI; ++j) Frag<T>::mma(fa[i], fb[j], acc[i][j]);
-    if (kt + 1 < nkt) sstore(buf ^ 1);
+      for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int jn = 0; jn < NI; ++jn) Frag<T>::mma_step(fa[i], fb[jn], acc[i][jn], t);
+    if (j + 1 < n) sstore(IC<1 - p>{});
     __syncthreads();
+  };
+  for (int j = 0; j < n; j += 2) {
+    body(IC<0>{}, j);
+    if (j + 1 < n) body(IC<1>{}, j + 1);
   }
 
   // epilogue: accumulator element e of lane (g, l32) is row 8*(e/4) + 4*g + e%4, column l32 of its 32x32 tile
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < MI; ++i)
 #pragma unroll
     for (int j = 0; j < NI; ++j) {
       const int col = n0 + wn * (BN / 2) + j * 32 + l32;
       const float bv = bias ? bias[col] : 0.f;
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
-        const int row = m0 + wm * 64 + i * 32 + 8 * (e >> 2) + 4 * g + (e & 3);
+        const int row = m0 + wm * (BM / 2) + i * 32 + 8 * (e >> 2) + 4 * g + (e & 3);
         if (row < a.M) {
           const int64_t o = (int64_t)row * a.Ng + col;
           if (SPLIT) {
@@ -195,6 +251,337 @@ __global__ void __launch_bounds__(256) conv_igemm_kernel(const T* __restrict__ s
         }
       }
     }
+}
+
+// ------------------------------------------------------------------------------------------------------------
+// 3x3, stride 1: the input patch of the block's pixels (with its halo and zero border) is staged in LDS once per
+// channel chunk and serves all nine filter taps, so the vector-memory path carries every input line once instead
+// of nine times; only the 64-byte-deep weight tile changes from tap to tap.
+//   block = 256 threads = 4 wavefronts (2 x 2); block tile = 2 pixel sub-tiles x BN channels; a wavefront owns one
+//   sub-tile (up to 128 pixels = TI images x TR rows x TC columns) and BN/2 channels: 4 x (BN/64) MFMA 32x32 tiles.
+//   LDS: 2 patch buffers [2*NPOS positions][80 B], 2 weight stages [BN][80 B], address tables.
+//   Pipeline (one barrier per tap): the weight tile of (chunk c+1, tap t) is requested before the MFMAs of (c, t)
+//   and parked in registers until the end of step (c+1, t-1); the next chunk's patch is requested during taps 0-3
+//   and stored during taps 5-8.  All loads are straight-line, so five steps of loads stay in flight.  The data gradient of a stride-1 convolution is the same computation on dz with the taps visited in
+//   reverse and the border (kh-1-pad).
+// ------------------------------------------------------------------------------------------------------------
+struct PatchArgs {
+  int N, srcH, srcW, srcC;   // gathered tensor
+  int dstH, dstW, Ng;        // pixel grid and channels of the result
+  int pad, flip;             // border of the gather; flip: weight tap index 8 - t (data gradient)
+  int TI, TR, TC, SR, SC, NPOS, TP;
+  int tiles_r, tiles_c, NT;
+  int relu;
+};
+
+constexpr int PATCH_MAX_POS = 256;  // positions per sub-tile
+
+template <class T, int BN>
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) conv3x3_patch_kernel(const T* __restrict__ src, const T* __restrict__ wmat,
+                                                            const float* __restrict__ bias, const T* __restrict__ addend,
+                                                            T* __restrict__ out, PatchArgs a) {
+  constexpr int CCE = Frag<T>::BK;           // channels per chunk (64 bytes)
+  constexpr int EV = 16 / (int)sizeof(T);
+  constexpr int PITCH = CCE + EV;            // elements per LDS row (80 bytes)
+  constexpr int NI = BN / 64;
+  constexpr int B_CH = BN * 4 / 256;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  T* patch = reinterpret_cast<T*>(smem_raw);                                  // [2][2*PATCH_MAX_POS][PITCH]
+  T* Bs = patch + 2 * 2 * PATCH_MAX_POS * PITCH;                              // [3][BN][PITCH]
+  int64_t* src_off = reinterpret_cast<int64_t*>(Bs + 3 * BN * PITCH);         // [2*PATCH_MAX_POS]
+  int64_t* out_off = src_off + 2 * PATCH_MAX_POS;                             // [256]
+  int* apos = reinterpret_cast<int*>(out_off + 256);                          // [256]
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1, g = lane >> 5, l32 = lane & 31;
+  const int n0c = blockIdx.y * BN;
+  const int npos2 = 2 * a.NPOS;
+  const int srcC = a.srcC, flip = a.flip, SC = a.SC;
+
+  // ---- address tables ------------------------------------------------------------------------------------------
+  for (int e = tid; e < npos2; e += 256) {
+    const int u = e / a.NPOS, rem = e - u * a.NPOS;
+    const int ti = rem / (a.SR * a.SC), rr = rem - ti * (a.SR * a.SC);
+    const int sy = rr / a.SC, sx = rr - sy * a.SC;
+    const int tile = 2 * blockIdx.x + u;
+    int64_t off = -1;
+    if (tile < a.NT) {
+      const int ci = tile % a.tiles_c, t2 = tile / a.tiles_c;
+      const int ri = t2 % a.tiles_r, ii = t2 / a.tiles_r;
+      const int n = ii * a.TI + ti, y = ri * a.TR - a.pad + sy, x = ci * a.TC - a.pad + sx;
+      if (n < a.N && y >= 0 && y < a.srcH && x >= 0 && x < a.srcW) off = (((int64_t)n * a.srcH + y) * a.srcW + x) * a.srcC;
+    }
+    src_off[e] = off;
+  }
+  {
+    const int m2 = tid, u = m2 >> 7, m = m2 & 127;
+    const int tile = 2 * blockIdx.x + u;
+    int64_t off = -1;
+    int ap = 0;
+    if (m < a.TP && tile < a.NT) {
+      const int ti = m / (a.TR * a.TC), rr = m - ti * (a.TR * a.TC);
+      const int tr = rr / a.TC, tc = rr - tr * a.TC;
+      const int ci = tile % a.tiles_c, t2 = tile / a.tiles_c;
+      const int ri = t2 % a.tiles_r, ii = t2 / a.tiles_r;
+      const int n = ii * a.TI + ti, p = ri * a.TR + tr, q = ci * a.TC + tc;
+      ap = u * a.NPOS + (ti * a.SR + tr) * a.SC + tc;
+      if (n < a.N && p < a.dstH && q < a.dstW) off = (((int64_t)n * a.dstH + p) * a.dstW + q) * a.Ng;
+    }
+    out_off[m2] = off;
+    apos[m2] = ap;
+  }
+  __syncthreads();
+
+  const int nchunks = srcC / CCE;
+  const int Kg = 9 * srcC;
+
+  // ---- loaders ---------------------------------------------------------------------------------------------------
+  Chunk PR[8];  // patch chunks in flight (next channel chunk)
+  // weight tiles in flight: one generation per tap, requested a whole channel chunk (nine steps) ahead
+  // (a = rows 0-63, b = rows 64-127 of the tile)
+  Chunk BRa[9], BRb[9];
+  const int bvec = tid & 3, brow0 = tid >> 2;
+  // patch pieces of this thread: slot sl covers the 16-byte piece idx = sl*256 + tid.  Loads are unconditional
+  // (pieces outside the image read the tensor's first pixel) and are zeroed when written to LDS.
+  const T* pptr[8];
+  unsigned pvalid = 0u, pstore = 0u;
+#pragma unroll
+  for (int sl = 0; sl < 8; ++sl) {
+    const int idx = sl * 256 + tid;
+    const int pos = idx >> 2, v = idx & 3;
+    int64_t off = 0;
+    if (pos < npos2) {
+      pstore |= 1u << sl;
+      const int64_t o = src_off[pos];
+      if (o >= 0) { off = o; pvalid |= 1u << sl; }
+    }
+    pptr[sl] = src + off + v * EV;
+  }
+  auto patch_load = [&](int slot, int chunk) { return *reinterpret_cast<const Chunk*>(pptr[slot] + chunk * CCE); };
+  auto patch_store = [&](int slot, int buf, const Chunk& c) {
+    const int idx = slot * 256 + tid;
+    const int pos = idx >> 2, v = idx & 3;
+    if ((pstore >> slot) & 1u)
+      *reinterpret_cast<Chunk*>(&patch[(buf * 2 * PATCH_MAX_POS + pos) * PITCH + v * EV]) = ((pvalid >> slot) & 1u) ? c : zero_chunk();
+  };
+  const T* wrow = wmat + (int64_t)(n0c + brow0) * Kg + bvec * EV;
+  // weight tile of global step gs = chunk*9 + tap -> registers REG
+  // weight tile of tap slot t_ of channel chunk ch_ -> registers of generation t_
+#define B_LOAD(t_, ch_)                                                                                       \
+  {                                                                                                           \
+    const int tap_ = flip ? 8 - (t_) : (t_);                                                                  \
+    const T* wp_ = wrow + tap_ * srcC + (ch_) * CCE;                                                          \
+    BRa[t_] = *reinterpret_cast<const Chunk*>(wp_);                                                           \
+    if (B_CH > 1) BRb[t_] = *reinterpret_cast<const Chunk*>(wp_ + (int64_t)64 * Kg);                          \
+  }
+#define B_STORE(t_, stage_)                                                                                   \
+  {                                                                                                           \
+    *reinterpret_cast<Chunk*>(&Bs[((stage_) * BN + brow0) * PITCH + bvec * EV]) = BRa[t_];                    \
+    if (B_CH > 1) *reinterpret_cast<Chunk*>(&Bs[((stage_) * BN + brow0 + 64) * PITCH + bvec * EV]) = BRb[t_]; \
+  }
+
+  // ---- prologue -----------------------------------------------------------------------------------------------
+#pragma unroll
+  for (int sl = 0; sl < 8; ++sl) PR[sl] = patch_load(sl, 0);
+#pragma unroll
+  for (int t = 0; t < 9; ++t) B_LOAD(t, 0);
+#pragma unroll
+  for (int sl = 0; sl < 8; ++sl) patch_store(sl, 0, PR[sl]);
+  B_STORE(0, 0);
+  B_STORE(1, 1);
+  __syncthreads();
+
+  int arow[4];  // LDS element offset of tap (0,0) for this lane's four 32-row groups
+#pragma unroll
+  for (int i = 0; i < 4; ++i) arow[i] = apos[wm * 128 + i * 32 + l32] * PITCH + Frag<T>::lane_off(g);
+  const int bfrag = (wn * (BN / 2) + l32) * PITCH + Frag<T>::lane_off(g);  // this lane's row in a weight stage
+
+  v16f acc[4][NI];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < NI; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+  // Operand fragments live in one set of registers.  Each half (first / second 16 bytes of the 32-byte depth slice) is
+  // reloaded for the next step right after the MFMAs that consumed it have been issued, so the LDS reads of step g+1
+  // run under the MFMAs of step g and nothing waits on LDS latency.  Weight stage = step % 3; the weight tile of step
+  // g+2 is written at the end of step g, the next chunk's patch during taps 4-7, so both are complete one barrier
+  // before their first read.
+  Frag<T> fa[4], fb[NI];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) fa[i].load(patch + arow[i]);
+#pragma unroll
+  for (int j = 0; j < NI; ++j) fb[j].load(&Bs[bfrag + j * 32 * PITCH]);
+
+  // one channel chunk = nine taps; LAST = no chunk follows (no patch prefetch, weight requests stop at the end)
+  auto chunk_body = [&](auto LAST, int chunk) {
+    constexpr bool last = decltype(LAST)::value != 0;
+    const int pbuf = chunk & 1;
+    const T* pcur = patch + pbuf * 2 * PATCH_MAX_POS * PITCH;
+    const T* pnxt = patch + (pbuf ^ 1) * 2 * PATCH_MAX_POS * PITCH;
+#pragma unroll
+    for (int t = 0; t < 9; ++t) {
+      // where the next step reads its operands
+      const bool has_next = !last || t + 1 < 9;
+      const int tn = (t + 1) % 9;
+      const T* pn = t + 1 < 9 ? pcur : pnxt;
+      const int tapoff_n = ((tn / 3) * SC + (tn % 3)) * PITCH;
+      const T* bn_ = &Bs[((t + 1) % 3) * BN * PITCH + bfrag];
+      // requests: the weight tile this tap will need in the next chunk, two pieces of the next patch during taps 0-3
+      if (!last) B_LOAD(t, chunk + 1);
+      if (!last && t < 4) { PR[2 * t] = patch_load(2 * t, chunk + 1); PR[2 * t + 1] = patch_load(2 * t + 1, chunk + 1); }
+      // first halves
+#pragma unroll
+      for (int st = 0; st < Frag<T>::HALF_STEPS; ++st)
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int j = 0; j < NI; ++j) Frag<T>::mma_half(fa[i], fb[j], acc[i][j], 0, st);
+      __builtin_amdgcn_sched_barrier(0);
+      if (has_next) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) fa[i].load_lo(pn + arow[i] + tapoff_n);
+#pragma unroll
+        for (int j = 0; j < NI; ++j) fb[j].load_lo(bn_ + j * 32 * PITCH);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      // second halves
+#pragma unroll
+      for (int st = 0; st < Frag<T>::HALF_STEPS; ++st)
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int j = 0; j < NI; ++j) Frag<T>::mma_half(fa[i], fb[j], acc[i][j], 1, st);
+      __builtin_amdgcn_sched_barrier(0);
+      if (has_next) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) fa[i].load_hi(pn + arow[i] + tapoff_n);
+#pragma unroll
+        for (int j = 0; j < NI; ++j) fb[j].load_hi(bn_ + j * 32 * PITCH);
+      }
+      // parked data goes to LDS: weight tile of step g+2, patch pieces requested four taps ago
+      if (t + 2 < 9) B_STORE(t + 2, (t + 2) % 3) else if (!last) B_STORE(t + 2 - 9, (t + 2) % 3)
+      if (!last && t >= 4 && t < 8) { patch_store(2 * (t - 4), pbuf ^ 1, PR[2 * (t - 4)]); patch_store(2 * (t - 4) + 1, pbuf ^ 1, PR[2 * (t - 4) + 1]); }
+      __syncthreads();
+    }
+  };
+  for (int chunk = 0; chunk + 1 < nchunks; ++chunk) chunk_body(IC<0>{}, chunk);
+  chunk_body(IC<1>{}, nchunks - 1);
+
+  // ---- epilogue ---------------------------------------------------------------------------------------------------
+  // The accumulators go through LDS (the patch buffers are free now), one 128-pixel sub-tile at a time as fp32
+  // [row][BN + 4], so that every lane then handles 8 consecutive channels of one pixel: bias / residual addend / ReLU
+  // in fp32, one rounding, one 16-byte (8-byte for fp32: two) store; a wavefront writes whole rows.
+  {
+    float* ep = reinterpret_cast<float*>(smem_raw);
+    constexpr int EP_PITCH = BN + 4;
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      __syncthreads();
+      if (wm == u) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int j = 0; j < NI; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e)
+              ep[(i * 32 + 8 * (e >> 2) + 4 * g + (e & 3)) * EP_PITCH + wn * (BN / 2) + j * 32 + l32] = acc[i][j][e];
+      }
+      __syncthreads();
+      constexpr int GROUPS = BN / 8;              // 8-channel groups per row
+      constexpr int PER_THREAD = 128 * GROUPS / 256;
+#pragma unroll
+      for (int it = 0; it < PER_THREAD; ++it) {
+        const int id = it * 256 + tid;
+        const int row = id / GROUPS, c8 = (id - row * GROUPS) * 8;
+        const int64_t ro = out_off[u * 128 + row];
+        if (ro >= 0) {
+          const v4f x0 = *reinterpret_cast<const v4f*>(&ep[row * EP_PITCH + c8]);
+          const v4f x1 = *reinterpret_cast<const v4f*>(&ep[row * EP_PITCH + c8 + 4]);
+          float v[8] = {x0[0], x0[1], x0[2], x0[3], x1[0], x1[1], x1[2], x1[3]};
+          const int col = n0c + c8;
+          if (bias) {
+#pragma unroll
+            for (int k = 0; k < 8; ++k) v[k] += bias[col + k];
+          }
+          if (addend) {
+            float ad[8];
+            load_f32<T, 8>(addend + ro + col, ad);
+#pragma unroll
+            for (int k = 0; k < 8; ++k) v[k] += ad[k];
+          }
+          if (a.relu) {
+#pragma unroll
+            for (int k = 0; k < 8; ++k) v[k] = fmaxf(v[k], 0.f);
+          }
+          store_f32<T, 8>(out + ro + col, v);
+        }
+      }
+    }
+  }
+}
+
+#undef B_LOAD
+#undef B_STORE
+
+template <class T> constexpr size_t patch_smem_bytes(int bn) {
+  return (size_t)(2 * 2 * PATCH_MAX_POS + 3 * bn) * (Frag<T>::BK + 16 / sizeof(T)) * sizeof(T) + 2 * PATCH_MAX_POS * 8 + 256 * 8 +
+         256 * 4;
+}
+
+// tile geometry of the patch kernel for a (dstH x dstW) pixel grid gathered with a 3x3 window; false if it does not fit
+static bool patch_geometry(int N, int dstH, int dstW, PatchArgs& a) {
+  int tc = dstW < 128 ? dstW : 128;
+  int tr = 128 / tc; if (tr > dstH) tr = dstH; if (tr < 1) tr = 1;
+  int ti = (tr == dstH && tc == dstW) ? 128 / (dstH * dstW) : 1;
+  if (ti > N) ti = N; if (ti < 1) ti = 1;
+  while (ti > 1 && ti * (tr + 2) * (tc + 2) > PATCH_MAX_POS) ti /= 2;
+  while (tr > 1 && ti * (tr + 2) * (tc + 2) > PATCH_MAX_POS) --tr;
+  while (tc > 1 && ti * (tr + 2) * (tc + 2) > PATCH_MAX_POS) tc /= 2;
+  if (ti * (tr + 2) * (tc + 2) > PATCH_MAX_POS) return false;
+  a.TI = ti; a.TR = tr; a.TC = tc; a.SR = tr + 2; a.SC = tc + 2;
+  a.NPOS = ti * a.SR * a.SC; a.TP = ti * tr * tc;
+  a.tiles_r = (dstH + tr - 1) / tr; a.tiles_c = (dstW + tc - 1) / tc;
+  a.NT = ((N + ti - 1) / ti) * a.tiles_r * a.tiles_c;
+  return true;
+}
+
+// the patch kernel pays off when the tile rows are well used and there are enough blocks to fill the chip
+int g_patch_min_blocks = 96;  // tuning constant (shape-only rule; not part of the C ABI)
+static bool patch_ok(int dt, int N, int dstH, int dstW, int srcC, int Ng, int R, int S, int stride) {
+  if (R != 3 || S != 3 || stride != 1) return false;
+  if (srcC % (dt == DT_F32 ? 16 : 32) != 0 || Ng % 64 != 0) return false;
+  PatchArgs a{};
+  if (!patch_geometry(N, dstH, dstW, a)) return false;
+  if (a.TP < 96) return false;
+  const int64_t blocks = (int64_t)((a.NT + 1) / 2) * (Ng / (Ng % 128 == 0 ? 128 : 64));
+  return blocks >= g_patch_min_blocks;
+}
+
+template <class T>
+static void launch_patch_t(hipStream_t st, const void* src, const void* wmat, const float* bias, const void* addend, void* out,
+                           PatchArgs a) {
+  const bool wide = a.Ng % 128 == 0;
+  dim3 grid((a.NT + 1) / 2, a.Ng / (wide ? 128 : 64)), block(256);
+  static bool attr_done[2] = {false, false};
+  if (wide) {
+    const size_t sm = patch_smem_bytes<T>(128);
+    if (!attr_done[0]) { (void)hipFuncSetAttribute((const void*)conv3x3_patch_kernel<T, 128>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sm); attr_done[0] = true; }
+    hipLaunchKernelGGL((conv3x3_patch_kernel<T, 128>), grid, block, sm, st, (const T*)src, (const T*)wmat, bias, (const T*)addend, (T*)out, a);
+  } else {
+    const size_t sm = patch_smem_bytes<T>(64);
+    if (!attr_done[1]) { (void)hipFuncSetAttribute((const void*)conv3x3_patch_kernel<T, 64>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sm); attr_done[1] = true; }
+    hipLaunchKernelGGL((conv3x3_patch_kernel<T, 64>), grid, block, sm, st, (const T*)src, (const T*)wmat, bias, (const T*)addend, (T*)out, a);
+  }
+}
+
+static void launch_patch(hipStream_t st, int dt, const void* src, const void* wmat, const float* bias, const void* addend, void* out,
+                         const PatchArgs& a) {
+  if (dt == DT_F32) launch_patch_t<float>(st, src, wmat, bias, addend, out, a);
+  else if (dt == DT_BF16) launch_patch_t<bf16_t>(st, src, wmat, bias, addend, out, a);
+  else launch_patch_t<f16_t>(st, src, wmat, bias, addend, out, a);
 }
 
 template <class T>
@@ -217,6 +604,12 @@ __global__ void __launch_bounds__(256) splitk_epilogue_kernel(const float* __res
   store_f32<T, 4>(out + i, r);
 }
 
+// rows per block: 256 when that still gives every CU two blocks, else 128 (from the shape only)
+static int igemm_bm(int64_t M, int Ng) {
+  const int64_t cols = Ng / (Ng % 128 == 0 ? 128 : 64);
+  return ((M + 255) / 256) * cols >= 512 ? 256 : 128;
+}
+
 template <class T, int MODE>
 static void launch_igemm_t(hipStream_t st, const void* src, const void* wmat, const float* bias, const void* addend, void* out,
                            float* partial, int splits, const IGemmArgs& a0) {
@@ -224,17 +617,22 @@ static void launch_igemm_t(hipStream_t st, const void* src, const void* wmat, co
   const int bk = Frag<T>::BK;
   a.kt_per_split = ceil_div(a.Kg / bk, splits);
   const bool wide = a.Ng % 128 == 0;
-  dim3 grid(ceil_div(a.M, 128), a.Ng / (wide ? 128 : 64), splits), block(256);
+  const int bm = splits > 1 ? 128 : igemm_bm(a.M, a.Ng);
+  dim3 grid(ceil_div(a.M, bm), a.Ng / (wide ? 128 : 64), splits), block(256);
+#define IGEMM_LAUNCH(BM_, BN_, SPLIT_)                                                                                   \
+  hipLaunchKernelGGL((conv_igemm_kernel<T, BM_, BN_, MODE, SPLIT_>), grid, block, 0, st, (const T*)src, (const T*)wmat, \
+                     bias, (const T*)addend, (T*)out, partial, a)
   if (splits > 1) {
-    if (wide) hipLaunchKernelGGL((conv_igemm_kernel<T, 128, MODE, true>), grid, block, 0, st, (const T*)src, (const T*)wmat, bias, (const T*)addend, (T*)out, partial, a);
-    else hipLaunchKernelGGL((conv_igemm_kernel<T, 64, MODE, true>), grid, block, 0, st, (const T*)src, (const T*)wmat, bias, (const T*)addend, (T*)out, partial, a);
+    if (wide) IGEMM_LAUNCH(128, 128, true); else IGEMM_LAUNCH(128, 64, true);
     const int64_t n = (int64_t)a.M * a.Ng;  // a multiple of 4: Ng % 64 == 0
     hipLaunchKernelGGL(splitk_epilogue_kernel<T>, dim3(ceil_div(n / 4, 256)), dim3(256), 0, st, partial, splits, n, a.Ng, bias,
                        (const T*)addend, (T*)out, a.relu);
+  } else if (bm == 256) {
+    if (wide) IGEMM_LAUNCH(256, 128, false); else IGEMM_LAUNCH(256, 64, false);
   } else {
-    if (wide) hipLaunchKernelGGL((conv_igemm_kernel<T, 128, MODE, false>), grid, block, 0, st, (const T*)src, (const T*)wmat, bias, (const T*)addend, (T*)out, partial, a);
-    else hipLaunchKernelGGL((conv_igemm_kernel<T, 64, MODE, false>), grid, block, 0, st, (const T*)src, (const T*)wmat, bias, (const T*)addend, (T*)out, partial, a);
+    if (wide) IGEMM_LAUNCH(128, 128, false); else IGEMM_LAUNCH(128, 64, false);
   }
+#undef IGEMM_LAUNCH
 }
 
 template <int MODE>
@@ -256,8 +654,14 @@ static int igemm_splits(int dt, int64_t M, int Ng, int Kg) {
   if (s > 32) s = 32;
   return (int)(s < 1 ? 1 : s);
 }
-int conv_mfma_fwd_splits(int dt, const ConvGeom& g) { return igemm_splits(dt, (int64_t)g.N * g.P * g.Q, g.K, g.R * g.S * g.C); }
-int conv_mfma_dgrad_splits(int dt, const ConvGeom& g) { return igemm_splits(dt, (int64_t)g.N * g.H * g.W, g.C, g.R * g.S * g.K); }
+int conv_mfma_fwd_splits(int dt, const ConvGeom& g) {
+  if (patch_ok(dt, g.N, g.P, g.Q, g.C, g.K, g.R, g.S, g.stride)) return 1;
+  return igemm_splits(dt, (int64_t)g.N * g.P * g.Q, g.K, g.R * g.S * g.C);
+}
+int conv_mfma_dgrad_splits(int dt, const ConvGeom& g) {
+  if (patch_ok(dt, g.N, g.H, g.W, g.K, g.C, g.R, g.S, g.stride)) return 1;
+  return igemm_splits(dt, (int64_t)g.N * g.H * g.W, g.C, g.R * g.S * g.K);
+}
 
 bool conv_mfma_fwd_ok(int dt, const ConvGeom& g) {
   const int bk = dt == DT_F32 ? 16 : 32;
@@ -270,6 +674,14 @@ bool conv_mfma_dgrad_ok(int dt, const ConvGeom& g) {
 
 void launch_conv_fwd_mfma(hipStream_t st, int dt, const void* x, const void* w, const float* bias, void* out,
                           float* partial, int splits, const ConvGeom& g, int relu) {
+  if (patch_ok(dt, g.N, g.P, g.Q, g.C, g.K, g.R, g.S, g.stride)) {
+    PatchArgs pa{};
+    patch_geometry(g.N, g.P, g.Q, pa);
+    pa.N = g.N; pa.srcH = g.H; pa.srcW = g.W; pa.srcC = g.C; pa.dstH = g.P; pa.dstW = g.Q; pa.Ng = g.K;
+    pa.pad = g.pad; pa.flip = 0; pa.relu = relu;
+    launch_patch(st, dt, x, w, bias, nullptr, out, pa);
+    return;
+  }
   IGemmArgs a{g.H, g.W, g.C, g.P, g.Q, g.N * g.P * g.Q, g.K, g.R * g.S * g.C, g.R, g.S, g.stride, g.pad, relu, 0};
   launch_igemm<IG_FWD>(st, dt, x, w, bias, nullptr, out, partial, splits, a);
 }
@@ -277,6 +689,14 @@ void launch_conv_fwd_mfma(hipStream_t st, int dt, const void* x, const void* w, 
 // wt: the (C_in, kh, kw, C_out) transpose of the weights, in the compute type
 void launch_conv_dgrad_mfma(hipStream_t st, int dt, const void* dz, const void* wt, const void* addend, void* dx,
                             float* partial, int splits, const ConvGeom& g) {
+  if (patch_ok(dt, g.N, g.H, g.W, g.K, g.C, g.R, g.S, g.stride)) {
+    PatchArgs pa{};
+    patch_geometry(g.N, g.H, g.W, pa);
+    pa.N = g.N; pa.srcH = g.P; pa.srcW = g.Q; pa.srcC = g.K; pa.dstH = g.H; pa.dstW = g.W; pa.Ng = g.C;
+    pa.pad = g.R - 1 - g.pad; pa.flip = 1; pa.relu = 0;
+    launch_patch(st, dt, dz, wt, nullptr, addend, dx, pa);
+    return;
+  }
   IGemmArgs a{g.P, g.Q, g.K, g.H, g.W, g.N * g.H * g.W, g.C, g.R * g.S * g.K, g.R, g.S, g.stride, g.pad, 0, 0};
   launch_igemm<IG_DGRAD>(st, dt, dz, wt, nullptr, addend, dx, partial, splits, a);
 }
@@ -367,37 +787,43 @@ __global__ void __launch_bounds__(256) conv_wgrad_kernel(const T* __restrict__ x
   constexpr int B_CH32 = DEPTH * (BN / 4) / 256 > 0 ? DEPTH * (BN / 4) / 256 : 1;
   // ---- 16-bit staging: each thread owns a channel pair and PXA / PXB consecutive pixels ---------------------
   constexpr int PXA = BM / 16, PXB = BN / 16;
+  // Loads are unconditional (pixels past the range or outside the image read pixel 0 / the tensor start) and are
+  // zeroed when written to LDS, so that the next tile's loads stay in flight during the MFMAs of the current one.
   Chunk ra[F32 ? A_CH32 : 1], rb[F32 ? B_CH32 : 1];
   uint32_t ha[F32 ? 1 : PXA], hb[F32 ? 1 : PXB];
+  unsigned va = 0u, vb = 0u;  // validity bits of the pieces in flight
 
   auto src_pixel = [&](int m, int64_t& off) -> bool {  // x offset (elements) of pixel m under this block's tap
-    if (m >= mend) return false;
-    const uint32_t n = a.divPQ.div((uint32_t)m);
-    const uint32_t rem = (uint32_t)m - n * a.divPQ.d;
+    const int mm = m < mend ? m : mbeg;
+    const uint32_t n = a.divPQ.div((uint32_t)mm);
+    const uint32_t rem = (uint32_t)mm - n * a.divPQ.d;
     const uint32_t p = a.divQ.div(rem);
     const uint32_t q = rem - p * a.divQ.d;
     const int ih = (int)p * a.stride + r - a.pad, iw = (int)q * a.stride + s - a.pad;
-    if (ih < 0 || ih >= a.H || iw < 0 || iw >= a.W) return false;
-    off = (((int64_t)n * a.H + ih) * a.W + iw) * a.C;
-    return true;
+    const bool ok = m < mend && ih >= 0 && ih < a.H && iw >= 0 && iw < a.W;
+    off = ok ? (((int64_t)n * a.H + ih) * a.W + iw) * a.C : 0;
+    return ok;
   };
 
   auto gload = [&](int t) {
     const int mt = mbeg + t * DEPTH;
+    va = 0u; vb = 0u;
     if constexpr (F32) {
 #pragma unroll
       for (int i = 0; i < A_CH32; ++i) {
         const int id = tid + i * 256, px = id / (BM / 4), kv = id % (BM / 4);
         const int m = mt + px;
-        ra[i] = (px < DEPTH && m < mend) ? *reinterpret_cast<const Chunk*>(dz + (int64_t)m * a.K + k0 + kv * 4)
-                                         : Chunk{{0u, 0u, 0u, 0u}};
+        const bool ok = m < mend;
+        ra[i] = *reinterpret_cast<const Chunk*>(dz + (int64_t)(ok ? m : mbeg) * a.K + k0 + kv * 4);
+        va |= ok ? (1u << i) : 0u;
       }
 #pragma unroll
       for (int i = 0; i < B_CH32; ++i) {
         const int id = tid + i * 256, px = id / (BN / 4), cv = id % (BN / 4);
         int64_t off = 0;
-        const bool ok = px < DEPTH && src_pixel(mt + px, off);
-        rb[i] = ok ? *reinterpret_cast<const Chunk*>(x + off + c0 + cv * 4) : Chunk{{0u, 0u, 0u, 0u}};
+        const bool ok = src_pixel(mt + px, off);
+        rb[i] = *reinterpret_cast<const Chunk*>(x + off + c0 + cv * 4);
+        vb |= ok ? (1u << i) : 0u;
       }
     } else {
       {
@@ -405,7 +831,9 @@ __global__ void __launch_bounds__(256) conv_wgrad_kernel(const T* __restrict__ x
 #pragma unroll
         for (int i = 0; i < PXA; ++i) {
           const int m = mt + pg * PXA + i;
-          ha[i] = m < mend ? *reinterpret_cast<const uint32_t*>(dz + (int64_t)m * a.K + k0 + 2 * cp) : 0u;
+          const bool ok = m < mend;
+          ha[i] = *reinterpret_cast<const uint32_t*>(dz + (int64_t)(ok ? m : mbeg) * a.K + k0 + 2 * cp);
+          va |= ok ? (1u << i) : 0u;
         }
       }
       {
@@ -414,7 +842,8 @@ __global__ void __launch_bounds__(256) conv_wgrad_kernel(const T* __restrict__ x
         for (int i = 0; i < PXB; ++i) {
           int64_t off = 0;
           const bool ok = src_pixel(mt + pg * PXB + i, off);
-          hb[i] = ok ? *reinterpret_cast<const uint32_t*>(x + off + c0 + 2 * cp) : 0u;
+          hb[i] = *reinterpret_cast<const uint32_t*>(x + off + c0 + 2 * cp);
+          vb |= ok ? (1u << i) : 0u;
         }
       }
     }
@@ -424,12 +853,12 @@ __global__ void __launch_bounds__(256) conv_wgrad_kernel(const T* __restrict__ x
 #pragma unroll
       for (int i = 0; i < A_CH32; ++i) {
         const int id = tid + i * 256, px = id / (BM / 4), kv = id % (BM / 4);
-        if (px < DEPTH) *reinterpret_cast<Chunk*>(&As[buf][px * (BM + 4) + kv * 4]) = ra[i];
+        *reinterpret_cast<Chunk*>(&As[buf][px * (BM + 4) + kv * 4]) = ((va >> i) & 1u) ? ra[i] : zero_chunk();
       }
 #pragma unroll
       for (int i = 0; i < B_CH32; ++i) {
         const int id = tid + i * 256, px = id / (BN / 4), cv = id % (BN / 4);
-        if (px < DEPTH) *reinterpret_cast<Chunk*>(&Bs[buf][px * (BN + 4) + cv * 4]) = rb[i];
+        *reinterpret_cast<Chunk*>(&Bs[buf][px * (BN + 4) + cv * 4]) = ((vb >> i) & 1u) ? rb[i] : zero_chunk();
       }
     } else {
       {
@@ -437,14 +866,20 @@ __global__ void __launch_bounds__(256) conv_wgrad_kernel(const T* __restrict__ x
         uint32_t* lo = reinterpret_cast<uint32_t*>(&As[buf][(2 * cp) * (DEPTH + 8) + pg * PXA]);
         uint32_t* hi = reinterpret_cast<uint32_t*>(&As[buf][(2 * cp + 1) * (DEPTH + 8) + pg * PXA]);
 #pragma unroll
-        for (int i = 0; i < PXA / 2; ++i) { lo[i] = pack_lo(ha[2 * i], ha[2 * i + 1]); hi[i] = pack_hi(ha[2 * i], ha[2 * i + 1]); }
+        for (int i = 0; i < PXA / 2; ++i) {
+          const uint32_t e0 = ((va >> (2 * i)) & 1u) ? ha[2 * i] : 0u, e1 = ((va >> (2 * i + 1)) & 1u) ? ha[2 * i + 1] : 0u;
+          lo[i] = pack_lo(e0, e1); hi[i] = pack_hi(e0, e1);
+        }
       }
       {
         const int cp = tid % (BN / 2), pg = tid / (BN / 2);
         uint32_t* lo = reinterpret_cast<uint32_t*>(&Bs[buf][(2 * cp) * (DEPTH + 8) + pg * PXB]);
         uint32_t* hi = reinterpret_cast<uint32_t*>(&Bs[buf][(2 * cp + 1) * (DEPTH + 8) + pg * PXB]);
 #pragma unroll
-        for (int i = 0; i < PXB / 2; ++i) { lo[i] = pack_lo(hb[2 * i], hb[2 * i + 1]); hi[i] = pack_hi(hb[2 * i], hb[2 * i + 1]); }
+        for (int i = 0; i < PXB / 2; ++i) {
+          const uint32_t e0 = ((vb >> (2 * i)) & 1u) ? hb[2 * i] : 0u, e1 = ((vb >> (2 * i + 1)) & 1u) ? hb[2 * i + 1] : 0u;
+          lo[i] = pack_lo(e0, e1); hi[i] = pack_hi(e0, e1);
+        }
       }
     }
   };

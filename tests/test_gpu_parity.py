@@ -67,6 +67,12 @@ LAYER_NETS = {
                                           W.bottleneck(256, 512, 2), W.gap_linear_ce(512, 10)]),
     "vgg_tail_512": (256, 4, 32, [W.conv(256, 512), W.maxpool(), W.conv(512, 512), W.maxpool(),
                                   W.flatten_linear_ce(512, 10)]),
+    # batches large enough for the LDS-patch 3x3 kernel (forward and data gradient), incl. ragged row tiles (20x20)
+    # and a border-free convolution
+    "patch_64_at32": (64, 32, 24, [W.conv(64, 64), W.conv(64, 64), W.gap_linear_ce(64, 10)]),
+    "patch_128_at16": (128, 16, 96, [W.conv(128, 128), W.conv(128, 128), W.gap_linear_ce(128, 10)]),
+    "patch_ragged_20": (64, 20, 48, [W.conv(64, 64), W.conv(64, 128), W.conv(128, 64, pad=0), W.gap_linear_ce(64, 10)]),
+    "patch_block_256_at8": (256, 8, 192, [W.basic_block(256, 256), W.gap_linear_ce(256, 10)]),
 }
 
 
@@ -103,9 +109,9 @@ def test_config2_full_size_fp32_matches_oracle():
     wl = W.config(2)
     p, x, y = W.make_batch(wl)
     r, info = gpu_step(wl.units, p, x, y, precision=W.FP32, k=wl.k_segments, classes=wl.classes)
-    loss, n_inverted = assert_parity_fp32(wl.units, 32, 32, p, x, y, r["grads"], 1e-4, wl.name)
+    loss, n_inverted = assert_parity_fp32(wl.units, 32, 32, p, x, y, r["grads"], 1e-4, wl.name, below_tol=2e-2)
     print("config 2 full size: %d near-kink ReLU decisions taken the other way" % n_inverted)
-    assert abs(r["loss"] - loss) <= 1e-4 * max(1.0, abs(loss))
+    assert abs(r["loss"] - loss) <= 1e-5 * max(1.0, abs(loss))
     assert info["n_replay_launches"] > 0 and info["boundaries"] == [3, 6, 9]
 
 
