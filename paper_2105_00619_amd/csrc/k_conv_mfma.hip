@@ -112,9 +112,16 @@ template <> struct Frag<f16_t> {
 
 // SPLIT: blockIdx.z owns a fixed range of depth tiles and writes raw fp32 sums to partial[z][M][Ng]; a second
 // kernel adds the ranges in order and applies the epilogue (layers with few output pixels, to fill the chip).
-// Pipeline: two LDS stages and two register generations; the global loads of depth tile j+2 are issued before the
-// MFMAs of tile j and stored to LDS after the MFMAs of tile j+1, so they have two compute phases to arrive.
+// Pipeline: three LDS stages, two register generations.  Iteration j: MFMAs of tile j from operand registers; the
+// halves of those registers are reloaded with tile j+1 (LDS stage (j+1)%3) as soon as their MFMAs are issued; the
+// global loads of tile j+3 are issued at the top and written to LDS stage j%3 at the end of iteration j+1.
 template <int V> struct IC { static constexpr int value = V; };
+
+template <class T, int BM, int BN> constexpr size_t igemm_smem_bytes() {
+  constexpr size_t stages = (size_t)3 * (BM + BN) * (Frag<T>::BK + 16 / sizeof(T)) * sizeof(T);
+  constexpr size_t epi = (size_t)(BM / 2) * (BN + 4) * 4;
+  return stages > epi ? stages : epi;
+}
 
 template <class T, int BM, int BN, int MODE, bool SPLIT>
 __global__ void __launch_bounds__(256) conv_igemm_kernel(const T* __restrict__ src, const T* __restrict__ wmat,
@@ -126,10 +133,11 @@ __global__ void __launch_bounds__(256) conv_igemm_kernel(const T* __restrict__ s
   constexpr int MI = BM / 64, NI = BN / 64; // 32x32 MFMA tiles per wavefront
   constexpr int A_CH = BM * 4 / 256;        // 16-byte chunks per thread and depth tile (4 chunks per row)
   constexpr int B_CH = BN * 4 / 256;
-  __shared__ T As[2][BM * PITCH];
-  __shared__ T Bs[2][BN * PITCH];
+  constexpr int STAGE = (BM + BN) * PITCH;  // elements per LDS stage: A rows then B rows
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  T* lds = reinterpret_cast<T*>(smem_raw);
 
-  // kernel arguments used inside the loaders, as plain scalars (the struct itself must not be captured by address)
+  // kernel arguments used inside the loaders, as plain scalars
   const int srcH = a.srcH, srcW = a.srcW, srcC = a.srcC, S_ = a.S, stride = a.stride, pad = a.pad, Kg = a.Kg;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1, g = lane >> 5, l32 = lane & 31;
@@ -182,13 +190,14 @@ __global__ void __launch_bounds__(256) conv_igemm_kernel(const T* __restrict__ s
 #pragma unroll
     for (int i = 0; i < B_CH; ++i) rb[p][i] = *reinterpret_cast<const Chunk*>(brow[i] + kk0);
   };
-  auto sstore = [&](auto P) {  // generation p goes to LDS stage p
+  auto sstore = [&](auto P, int stage) {  // register generation p -> LDS stage
     constexpr int p = decltype(P)::value;
+    T* st = lds + stage * STAGE;
 #pragma unroll
     for (int i = 0; i < A_CH; ++i)
-      *reinterpret_cast<Chunk*>(&As[p][(row0 + i * 64) * PITCH + vec * EV]) = ((okm[p] >> i) & 1u) ? ra[p][i] : zero_chunk();
+      *reinterpret_cast<Chunk*>(&st[(row0 + i * 64) * PITCH + vec * EV]) = ((okm[p] >> i) & 1u) ? ra[p][i] : zero_chunk();
 #pragma unroll
-    for (int i = 0; i < B_CH; ++i) *reinterpret_cast<Chunk*>(&Bs[p][(row0 + i * 64) * PITCH + vec * EV]) = rb[p][i];
+    for (int i = 0; i < B_CH; ++i) *reinterpret_cast<Chunk*>(&st[(BM + row0 + i * 64) * PITCH + vec * EV]) = rb[p][i];
   };
 
   v16f acc[MI][NI];
@@ -202,55 +211,125 @@ __global__ void __launch_bounds__(256) conv_igemm_kernel(const T* __restrict__ s
   const int kt0 = SPLIT ? blockIdx.z * a.kt_per_split : 0;
   const int kt1 = SPLIT ? (kt0 + a.kt_per_split < a.Kg / BK ? kt0 + a.kt_per_split : a.Kg / BK) : a.Kg / BK;
   const int n = kt1 > kt0 ? kt1 - kt0 : 0;
-  if (n > 0) { gload(IC<0>{}, kt0); sstore(IC<0>{}); }
-  if (n > 1) gload(IC<1>{}, kt0 + 1);
+  // prologue: tiles 0 and 1 into LDS stages 0 and 1, tile 2 on its way in generation 0
+  if (n > 0) { gload(IC<0>{}, kt0); sstore(IC<0>{}, 0); }
+  if (n > 1) { gload(IC<1>{}, kt0 + 1); sstore(IC<1>{}, 1); }
+  if (n > 2) gload(IC<0>{}, kt0 + 2);
   __syncthreads();
-  auto body = [&](auto P, int j) {  // depth tile j of this block; its data sits in LDS stage p = j & 1
-    constexpr int p = decltype(P)::value;
-    if (j + 2 < n) gload(P, kt0 + j + 2);
-    Frag<T> fa[MI], fb[NI];
+  const int afrag = (wm * (BM / 2) + l32) * PITCH + Frag<T>::lane_off(g);
+  const int bfrag = (BM + wn * (BN / 2) + l32) * PITCH + Frag<T>::lane_off(g);
+  Frag<T> fa[MI], fb[NI];
+  if (n > 0) {
 #pragma unroll
-    for (int i = 0; i < MI; ++i) fa[i].load(&As[p][(wm * (BM / 2) + i * 32 + l32) * PITCH + Frag<T>::lane_off(g)]);
+    for (int i = 0; i < MI; ++i) fa[i].load(lds + afrag + i * 32 * PITCH);
 #pragma unroll
-    for (int jn = 0; jn < NI; ++jn) fb[jn].load(&Bs[p][(wn * (BN / 2) + jn * 32 + l32) * PITCH + Frag<T>::lane_off(g)]);
-    // consecutive MFMAs go to different accumulators, so none waits for the one issued just before it
+    for (int jn = 0; jn < NI; ++jn) fb[jn].load(lds + bfrag + jn * 32 * PITCH);
+  }
+  // iteration j: generation (j & 1) holds tile j+2 (issued at iteration j-1 or in the prologue)
+  auto body = [&](auto P, int j, int stage) {
+    constexpr int p = decltype(P)::value;  // = j & 1
+    const T* nxt = lds + (stage == 2 ? 0 : stage + 1) * STAGE;
+    const bool has_next = j + 1 < n;
+    if (j + 3 < n) gload(IC<1 - p>{}, kt0 + j + 3);
 #pragma unroll
-    for (int t = 0; t < Frag<T>::STEPS; ++t)
+    for (int st = 0; st < Frag<T>::HALF_STEPS; ++st)
 #pragma unroll
       for (int i = 0; i < MI; ++i)
 #pragma unroll
-        for (int jn = 0; jn < NI; ++jn) Frag<T>::mma_step(fa[i], fb[jn], acc[i][jn], t);
-    if (j + 1 < n) sstore(IC<1 - p>{});
+        for (int jn = 0; jn < NI; ++jn) Frag<T>::mma_half(fa[i], fb[jn], acc[i][jn], 0, st);
+    __builtin_amdgcn_sched_barrier(0);
+    if (has_next) {
+#pragma unroll
+      for (int i = 0; i < MI; ++i) fa[i].load_lo(nxt + afrag + i * 32 * PITCH);
+#pragma unroll
+      for (int jn = 0; jn < NI; ++jn) fb[jn].load_lo(nxt + bfrag + jn * 32 * PITCH);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int st = 0; st < Frag<T>::HALF_STEPS; ++st)
+#pragma unroll
+      for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int jn = 0; jn < NI; ++jn) Frag<T>::mma_half(fa[i], fb[jn], acc[i][jn], 1, st);
+    __builtin_amdgcn_sched_barrier(0);
+    if (has_next) {
+#pragma unroll
+      for (int i = 0; i < MI; ++i) fa[i].load_hi(nxt + afrag + i * 32 * PITCH);
+#pragma unroll
+      for (int jn = 0; jn < NI; ++jn) fb[jn].load_hi(nxt + bfrag + jn * 32 * PITCH);
+    }
+    if (j + 2 < n) sstore(P, stage == 0 ? 2 : stage - 1);  // tile j+2 -> stage (j+2)%3
     __syncthreads();
   };
-  for (int j = 0; j < n; j += 2) {
-    body(IC<0>{}, j);
-    if (j + 1 < n) body(IC<1>{}, j + 1);
+  {
+    int stage = 0;
+    for (int j = 0; j < n; j += 2) {
+      body(IC<0>{}, j, stage);
+      stage = stage == 2 ? 0 : stage + 1;
+      if (j + 1 < n) {
+        body(IC<1>{}, j + 1, stage);
+        stage = stage == 2 ? 0 : stage + 1;
+      }
+    }
   }
 
-  // epilogue: accumulator element e of lane (g, l32) is row 8*(e/4) + 4*g + e%4, column l32 of its 32x32 tile
+  // epilogue through LDS, one half of the rows (the two wavefronts with the same wm) at a time, as fp32 [row][BN+4];
+  // then every lane handles 8 consecutive channels of one pixel: bias / addend / ReLU in fp32, one rounding, one store
+  {
+    float* ep = reinterpret_cast<float*>(smem_raw);
+    constexpr int EP_PITCH = BN + 4;
+    constexpr int HR = BM / 2;  // rows per pass
 #pragma unroll
-  for (int i = 0; i < MI; ++i)
+    for (int u = 0; u < 2; ++u) {
+      __syncthreads();
+      if (wm == u) {
 #pragma unroll
-    for (int j = 0; j < NI; ++j) {
-      const int col = n0 + wn * (BN / 2) + j * 32 + l32;
-      const float bv = bias ? bias[col] : 0.f;
+        for (int i = 0; i < MI; ++i)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int row = m0 + wm * (BM / 2) + i * 32 + 8 * (e >> 2) + 4 * g + (e & 3);
-        if (row < a.M) {
-          const int64_t o = (int64_t)row * a.Ng + col;
+          for (int jn = 0; jn < NI; ++jn)
+#pragma unroll
+            for (int e = 0; e < 16; ++e)
+              ep[(i * 32 + 8 * (e >> 2) + 4 * g + (e & 3)) * EP_PITCH + wn * (BN / 2) + jn * 32 + l32] = acc[i][jn][e];
+      }
+      __syncthreads();
+      constexpr int GROUPS = BN / 8;
+      constexpr int PER_THREAD = HR * GROUPS / 256;
+#pragma unroll
+      for (int it = 0; it < PER_THREAD; ++it) {
+        const int id = it * 256 + tid;
+        const int row = id / GROUPS, c8 = (id - row * GROUPS) * 8;
+        const int grow = m0 + u * HR + row;
+        if (grow < a.M) {
+          const v4f x0 = *reinterpret_cast<const v4f*>(&ep[row * EP_PITCH + c8]);
+          const v4f x1 = *reinterpret_cast<const v4f*>(&ep[row * EP_PITCH + c8 + 4]);
+          const int col = n0 + c8;
+          const int64_t o = (int64_t)grow * a.Ng + col;
           if (SPLIT) {
-            partial[(int64_t)blockIdx.z * a.M * a.Ng + o] = acc[i][j][e];
+            float* dst = partial + (int64_t)blockIdx.z * a.M * a.Ng + o;
+            *reinterpret_cast<v4f*>(dst) = x0;
+            *reinterpret_cast<v4f*>(dst + 4) = x1;
           } else {
-            float v = acc[i][j][e] + bv;
-            if (addend) v += to_f32(addend[o]);
-            if (a.relu) v = fmaxf(v, 0.f);
-            out[o] = from_f32<T>(v);
+            float v[8] = {x0[0], x0[1], x0[2], x0[3], x1[0], x1[1], x1[2], x1[3]};
+            if (bias) {
+#pragma unroll
+              for (int k = 0; k < 8; ++k) v[k] += bias[col + k];
+            }
+            if (addend) {
+              float ad[8];
+              load_f32<T, 8>(addend + o, ad);
+#pragma unroll
+              for (int k = 0; k < 8; ++k) v[k] += ad[k];
+            }
+            if (a.relu) {
+#pragma unroll
+              for (int k = 0; k < 8; ++k) v[k] = fmaxf(v[k], 0.f);
+            }
+            store_f32<T, 8>(out + o, v);
           }
         }
       }
     }
+  }
 }
 
 // ------------------------------------------------------------------------------------------------------------
@@ -620,17 +699,26 @@ static void launch_igemm_t(hipStream_t st, const void* src, const void* wmat, co
   const int bm = splits > 1 ? 128 : igemm_bm(a.M, a.Ng);
   dim3 grid(ceil_div(a.M, bm), a.Ng / (wide ? 128 : 64), splits), block(256);
 #define IGEMM_LAUNCH(BM_, BN_, SPLIT_)                                                                                   \
-  hipLaunchKernelGGL((conv_igemm_kernel<T, BM_, BN_, MODE, SPLIT_>), grid, block, 0, st, (const T*)src, (const T*)wmat, \
-                     bias, (const T*)addend, (T*)out, partial, a)
+  {                                                                                                                      \
+    constexpr size_t sm_ = igemm_smem_bytes<T, BM_, BN_>();                                                              \
+    static bool attr_ = false;                                                                                           \
+    if (!attr_) {                                                                                                        \
+      (void)hipFuncSetAttribute((const void*)conv_igemm_kernel<T, BM_, BN_, MODE, SPLIT_>,                               \
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)sm_);                                   \
+      attr_ = true;                                                                                                      \
+    }                                                                                                                    \
+    hipLaunchKernelGGL((conv_igemm_kernel<T, BM_, BN_, MODE, SPLIT_>), grid, block, sm_, st, (const T*)src,              \
+                       (const T*)wmat, bias, (const T*)addend, (T*)out, partial, a);                                     \
+  }
   if (splits > 1) {
-    if (wide) IGEMM_LAUNCH(128, 128, true); else IGEMM_LAUNCH(128, 64, true);
+    if (wide) IGEMM_LAUNCH(128, 128, true) else IGEMM_LAUNCH(128, 64, true)
     const int64_t n = (int64_t)a.M * a.Ng;  // a multiple of 4: Ng % 64 == 0
     hipLaunchKernelGGL(splitk_epilogue_kernel<T>, dim3(ceil_div(n / 4, 256)), dim3(256), 0, st, partial, splits, n, a.Ng, bias,
                        (const T*)addend, (T*)out, a.relu);
   } else if (bm == 256) {
-    if (wide) IGEMM_LAUNCH(256, 128, false); else IGEMM_LAUNCH(256, 64, false);
+    if (wide) IGEMM_LAUNCH(256, 128, false) else IGEMM_LAUNCH(256, 64, false)
   } else {
-    if (wide) IGEMM_LAUNCH(128, 128, false); else IGEMM_LAUNCH(128, 64, false);
+    if (wide) IGEMM_LAUNCH(128, 128, false) else IGEMM_LAUNCH(128, 64, false)
   }
 #undef IGEMM_LAUNCH
 }
