@@ -815,9 +815,8 @@ void launch_weight_transpose(hipStream_t st, int dt, const float* w, void* wt, i
 // One block owns a (BM output channels) x (BN input channels) tile of ONE filter tap and a fixed chunk of the
 // pixel range (blockIdx.z); chunks are summed afterwards in order, so the result does not depend on scheduling.
 // Both operands arrive pixel-major (the reduction index is the slow one), but an MFMA lane wants consecutive
-// reduction elements.  fp32: the tile is stored as loaded and lanes read it with a stride.  16-bit: each thread
-// loads two channels of several consecutive pixels, interleaves them in registers (byte permutes) and stores
-// channel-major rows, so the MFMA operands are read exactly as in the forward kernel.
+// reduction elements.  The tiles are stored in LDS exactly as loaded (16-byte chunks, [pixel][channel]); fp32 lanes
+// read them with a stride, 16-bit lanes use the transposing LDS read of gfx950 (ds_read_b64_tr_b16).
 // ------------------------------------------------------------------------------------------------------------
 struct FastDiv {  // floor(m / d) for m * d < 2^48
   uint64_t magic; uint32_t d;
@@ -845,8 +844,16 @@ template <> struct WFrag<float> {
   }
 };
 
-__device__ __forceinline__ uint32_t pack_lo(uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x05040100u); }
-__device__ __forceinline__ uint32_t pack_hi(uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x07060302u); }
+typedef __attribute__((ext_vector_type(4))) short v4s;
+typedef __attribute__((ext_vector_type(8))) short v8s;
+// two transposing 64-bit LDS reads (see the weight-gradient kernel): 8 consecutive reduction elements of one channel
+template <class T>
+__device__ __forceinline__ v8s tr_read8(const T* p0, const T* p1) {
+  const v4s a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s*)(p0));
+  const v4s b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s*)(p1));
+  v8s r = {a[0], a[1], a[2], a[3], b[0], b[1], b[2], b[3]};
+  return r;
+}
 
 template <class T, int BM, int BN>
 __global__ void __launch_bounds__(256) conv_wgrad_kernel(const T* __restrict__ x, const T* __restrict__ dz,
@@ -854,11 +861,12 @@ __global__ void __launch_bounds__(256) conv_wgrad_kernel(const T* __restrict__ x
   constexpr bool F32 = sizeof(T) == 4;
   constexpr int DEPTH = F32 ? 16 : 32;
   constexpr int MI = BM / 64, NI = BN / 64;
-  // fp32: tiles [DEPTH][BM+4] floats; 16-bit: tiles [BM][DEPTH+8] halves (80-byte rows)
-  constexpr int A_ELEMS = F32 ? DEPTH * (BM + 4) : BM * (DEPTH + 8);
-  constexpr int B_ELEMS = F32 ? DEPTH * (BN + 4) : BN * (DEPTH + 8);
-  __shared__ __attribute__((aligned(16))) T As[2][A_ELEMS];
-  __shared__ __attribute__((aligned(16))) T Bs[2][B_ELEMS];
+  // one LDS stage, pixel-major exactly as loaded: [DEPTH][BM + pad] then [DEPTH][BN + pad] (pad: 4 floats / 16 halves)
+  constexpr int PADE = F32 ? 4 : 16;
+  constexpr int A_ELEMS = DEPTH * (BM + PADE);
+  constexpr int B_ELEMS = DEPTH * (BN + PADE);
+  constexpr int STAGE = A_ELEMS + B_ELEMS;
+  __shared__ __attribute__((aligned(16))) T lds[3 * STAGE];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1, g = lane >> 5, l32 = lane & 31;
@@ -868,107 +876,63 @@ __global__ void __launch_bounds__(256) conv_wgrad_kernel(const T* __restrict__ x
   const int r = tap / a.S, s = tap - r * a.S;
   const int mbeg = blockIdx.z * a.chunk;
   const int mend = mbeg + a.chunk < a.pixels ? mbeg + a.chunk : a.pixels;
-  const int ntiles = mend > mbeg ? (mend - mbeg + DEPTH - 1) / DEPTH : 0;
+  const int n = mend > mbeg ? (mend - mbeg + DEPTH - 1) / DEPTH : 0;
+  const int K = a.K, C = a.C, H = a.H, W = a.W, P = a.P, Q = a.Q, cstride = a.stride, pad = a.pad;
+  const FastDiv divQ = a.divQ, divPQ = a.divPQ;
 
-  // ---- fp32 staging: 16-byte chunks, rows = pixels --------------------------------------------------------
-  constexpr int A_CH32 = DEPTH * (BM / 4) / 256 > 0 ? DEPTH * (BM / 4) / 256 : 1;
-  constexpr int B_CH32 = DEPTH * (BN / 4) / 256 > 0 ? DEPTH * (BN / 4) / 256 : 1;
-  // ---- 16-bit staging: each thread owns a channel pair and PXA / PXB consecutive pixels ---------------------
-  constexpr int PXA = BM / 16, PXB = BN / 16;
-  // Loads are unconditional (pixels past the range or outside the image read pixel 0 / the tensor start) and are
-  // zeroed when written to LDS, so that the next tile's loads stay in flight during the MFMAs of the current one.
-  Chunk ra[F32 ? A_CH32 : 1], rb[F32 ? B_CH32 : 1];
-  uint32_t ha[F32 ? 1 : PXA], hb[F32 ? 1 : PXB];
-  unsigned va = 0u, vb = 0u;  // validity bits of the pieces in flight
+  // staging: 16-byte chunks, rows = pixels (EV elements per chunk)
+  constexpr int EV = 16 / (int)sizeof(T);
+  constexpr int A_CH32 = DEPTH * (BM / EV) / 256, B_CH32 = DEPTH * (BN / EV) / 256;
+  Chunk ra[2][A_CH32], rb[2][B_CH32];
+  unsigned va[2] = {0u, 0u}, vb[2] = {0u, 0u};  // validity bits of the pieces in flight, per generation
 
-  auto src_pixel = [&](int m, int64_t& off) -> bool {  // x offset (elements) of pixel m under this block's tap
-    const int mm = m < mend ? m : mbeg;
-    const uint32_t n = a.divPQ.div((uint32_t)mm);
-    const uint32_t rem = (uint32_t)mm - n * a.divPQ.d;
-    const uint32_t p = a.divQ.div(rem);
-    const uint32_t q = rem - p * a.divQ.d;
-    const int ih = (int)p * a.stride + r - a.pad, iw = (int)q * a.stride + s - a.pad;
-    const bool ok = m < mend && ih >= 0 && ih < a.H && iw >= 0 && iw < a.W;
-    off = ok ? (((int64_t)n * a.H + ih) * a.W + iw) * a.C : 0;
+  // Loads are unconditional (pixels past the range or outside the image read pixel mbeg / the tensor start) and are
+  // zeroed when written to LDS, so that later tiles' loads stay in flight during the MFMAs of the current one.
+  auto tap_offset = [&](int n_, int p_, int q_, int64_t& off) -> bool {  // x offset of (image, row, col) under this tap
+    const int ih = p_ * cstride + r - pad, iw = q_ * cstride + s - pad;
+    const bool ok = ih >= 0 && ih < H && iw >= 0 && iw < W;
+    off = ok ? (((int64_t)n_ * H + ih) * W + iw) * C : 0;
     return ok;
   };
-
-  auto gload = [&](int t) {
+  auto gload = [&](auto G, int t) {
+    constexpr int p = decltype(G)::value;
     const int mt = mbeg + t * DEPTH;
-    va = 0u; vb = 0u;
-    if constexpr (F32) {
+    unsigned ma = 0u, mb = 0u;
 #pragma unroll
-      for (int i = 0; i < A_CH32; ++i) {
-        const int id = tid + i * 256, px = id / (BM / 4), kv = id % (BM / 4);
-        const int m = mt + px;
-        const bool ok = m < mend;
-        ra[i] = *reinterpret_cast<const Chunk*>(dz + (int64_t)(ok ? m : mbeg) * a.K + k0 + kv * 4);
-        va |= ok ? (1u << i) : 0u;
-      }
-#pragma unroll
-      for (int i = 0; i < B_CH32; ++i) {
-        const int id = tid + i * 256, px = id / (BN / 4), cv = id % (BN / 4);
-        int64_t off = 0;
-        const bool ok = src_pixel(mt + px, off);
-        rb[i] = *reinterpret_cast<const Chunk*>(x + off + c0 + cv * 4);
-        vb |= ok ? (1u << i) : 0u;
-      }
-    } else {
-      {
-        const int cp = tid % (BM / 2), pg = tid / (BM / 2);
-#pragma unroll
-        for (int i = 0; i < PXA; ++i) {
-          const int m = mt + pg * PXA + i;
-          const bool ok = m < mend;
-          ha[i] = *reinterpret_cast<const uint32_t*>(dz + (int64_t)(ok ? m : mbeg) * a.K + k0 + 2 * cp);
-          va |= ok ? (1u << i) : 0u;
-        }
-      }
-      {
-        const int cp = tid % (BN / 2), pg = tid / (BN / 2);
-#pragma unroll
-        for (int i = 0; i < PXB; ++i) {
-          int64_t off = 0;
-          const bool ok = src_pixel(mt + pg * PXB + i, off);
-          hb[i] = *reinterpret_cast<const uint32_t*>(x + off + c0 + 2 * cp);
-          vb |= ok ? (1u << i) : 0u;
-        }
-      }
+    for (int i = 0; i < A_CH32; ++i) {
+      const int id = tid + i * 256, px = id / (BM / EV), kv = id % (BM / EV);
+      const int m = mt + px;
+      const bool ok = m < mend;
+      ra[p][i] = *reinterpret_cast<const Chunk*>(dz + (int64_t)(ok ? m : mbeg) * K + k0 + kv * EV);
+      ma |= ok ? (1u << i) : 0u;
     }
+#pragma unroll
+    for (int i = 0; i < B_CH32; ++i) {
+      const int id = tid + i * 256, px = id / (BN / EV), cv = id % (BN / EV);
+      const int m = mt + px;
+      const int mm = m < mend ? m : mbeg;
+      const uint32_t n_ = divPQ.div((uint32_t)mm), rem = (uint32_t)mm - n_ * divPQ.d;
+      const uint32_t p_ = divQ.div(rem), q_ = rem - p_ * divQ.d;
+      int64_t off;
+      const bool ok = tap_offset((int)n_, (int)p_, (int)q_, off) && m < mend;
+      rb[p][i] = *reinterpret_cast<const Chunk*>(x + (ok ? off : 0) + c0 + cv * EV);
+      mb |= ok ? (1u << i) : 0u;
+    }
+    va[p] = ma; vb[p] = mb;
   };
-  auto sstore = [&](int buf) {
-    if constexpr (F32) {
+  auto sstore = [&](auto G, int stage) {
+    constexpr int p = decltype(G)::value;
+    T* sa = lds + stage * STAGE;
+    T* sb = sa + A_ELEMS;
 #pragma unroll
-      for (int i = 0; i < A_CH32; ++i) {
-        const int id = tid + i * 256, px = id / (BM / 4), kv = id % (BM / 4);
-        *reinterpret_cast<Chunk*>(&As[buf][px * (BM + 4) + kv * 4]) = ((va >> i) & 1u) ? ra[i] : zero_chunk();
-      }
+    for (int i = 0; i < A_CH32; ++i) {
+      const int id = tid + i * 256, px = id / (BM / EV), kv = id % (BM / EV);
+      *reinterpret_cast<Chunk*>(&sa[px * (BM + PADE) + kv * EV]) = ((va[p] >> i) & 1u) ? ra[p][i] : zero_chunk();
+    }
 #pragma unroll
-      for (int i = 0; i < B_CH32; ++i) {
-        const int id = tid + i * 256, px = id / (BN / 4), cv = id % (BN / 4);
-        *reinterpret_cast<Chunk*>(&Bs[buf][px * (BN + 4) + cv * 4]) = ((vb >> i) & 1u) ? rb[i] : zero_chunk();
-      }
-    } else {
-      {
-        const int cp = tid % (BM / 2), pg = tid / (BM / 2);
-        uint32_t* lo = reinterpret_cast<uint32_t*>(&As[buf][(2 * cp) * (DEPTH + 8) + pg * PXA]);
-        uint32_t* hi = reinterpret_cast<uint32_t*>(&As[buf][(2 * cp + 1) * (DEPTH + 8) + pg * PXA]);
-#pragma unroll
-        for (int i = 0; i < PXA / 2; ++i) {
-          const uint32_t e0 = ((va >> (2 * i)) & 1u) ? ha[2 * i] : 0u, e1 = ((va >> (2 * i + 1)) & 1u) ? ha[2 * i + 1] : 0u;
-          lo[i] = pack_lo(e0, e1); hi[i] = pack_hi(e0, e1);
-        }
-      }
-      {
-        const int cp = tid % (BN / 2), pg = tid / (BN / 2);
-        uint32_t* lo = reinterpret_cast<uint32_t*>(&Bs[buf][(2 * cp) * (DEPTH + 8) + pg * PXB]);
-        uint32_t* hi = reinterpret_cast<uint32_t*>(&Bs[buf][(2 * cp + 1) * (DEPTH + 8) + pg * PXB]);
-#pragma unroll
-        for (int i = 0; i < PXB / 2; ++i) {
-          const uint32_t e0 = ((vb >> (2 * i)) & 1u) ? hb[2 * i] : 0u, e1 = ((vb >> (2 * i + 1)) & 1u) ? hb[2 * i + 1] : 0u;
-          lo[i] = pack_lo(e0, e1); hi[i] = pack_hi(e0, e1);
-        }
-      }
+    for (int i = 0; i < B_CH32; ++i) {
+      const int id = tid + i * 256, px = id / (BN / EV), cv = id % (BN / EV);
+      *reinterpret_cast<Chunk*>(&sb[px * (BN + PADE) + cv * EV]) = ((vb[p] >> i) & 1u) ? rb[p][i] : zero_chunk();
     }
   };
 
@@ -980,40 +944,96 @@ __global__ void __launch_bounds__(256) conv_wgrad_kernel(const T* __restrict__ x
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-  if (ntiles > 0) {
-    gload(0);
-    sstore(0);
-  }
-  __syncthreads();
-  for (int t = 0; t < ntiles; ++t) {
-    const int buf = t & 1;
-    if (t + 1 < ntiles) gload(t + 1);
+  // operand registers: fp32 8 scalars per 32-row tile (pixels g*8 .. g*8+7 of the depth tile), 16-bit a 32-byte slice
+  float fa32[F32 ? MI : 1][8], fb32[F32 ? NI : 1][8];
+  Frag<T> fa[F32 ? 1 : MI], fb[F32 ? 1 : NI];
+  const int acol = wm * (BM / 2) + l32, bcol = wn * (BN / 2) + l32;
+  auto load_half = [&](int half, int stage) {
+    const T* sa = lds + stage * STAGE;
+    const T* sb = sa + A_ELEMS;
     if constexpr (F32) {
-      WFrag<float> fa[MI], fb[NI];
+      const float* fsa = reinterpret_cast<const float*>(sa);
+      const float* fsb = reinterpret_cast<const float*>(sb);
 #pragma unroll
-      for (int i = 0; i < MI; ++i) fa[i].load(reinterpret_cast<const float*>(As[buf]), BM + 4, wm * (BM / 2) + i * 32 + l32, g);
+      for (int t = 0; t < 4; ++t) {
+        const int px = g * 8 + half * 4 + t;
 #pragma unroll
-      for (int j = 0; j < NI; ++j) fb[j].load(reinterpret_cast<const float*>(Bs[buf]), BN + 4, wn * (BN / 2) + j * 32 + l32, g);
+        for (int i = 0; i < MI; ++i) fa32[i][half * 4 + t] = fsa[px * (BM + PADE) + acol + i * 32];
 #pragma unroll
-      for (int i = 0; i < MI; ++i)
-#pragma unroll
-        for (int j = 0; j < NI; ++j) WFrag<float>::mma(fa[i], fb[j], acc[i][j]);
+        for (int j = 0; j < NI; ++j) fb32[j][half * 4 + t] = fsb[px * (BN + PADE) + bcol + j * 32];
+      }
     } else {
-      Frag<T> fa[MI], fb[NI];
+      // Transposing LDS read (ds_read_b64_tr_b16): within 16 lanes, lane r points at 4 consecutive channels of pixel
+      // k0 + r/4 starting at channel 4*(r%4); lane l receives channel l of the 16 at pixels k0..k0+3.  Two reads give
+      // the 8 pixels of one operand half for channel (tile base + l32).
+      const int r16 = l32 & 15;
+      const int kbase = g * 16 + half * 8 + (r16 >> 2);
+      const int coff = (l32 & 16) + 4 * (r16 & 3);
 #pragma unroll
-      for (int i = 0; i < MI; ++i) fa[i].load(&As[buf][(wm * (BM / 2) + i * 32 + l32) * (DEPTH + 8) + g * 16]);
+      for (int i = 0; i < MI; ++i) {
+        const T* pp = sa + kbase * (BM + PADE) + wm * (BM / 2) + i * 32 + coff;
+        const v8s v = tr_read8(pp, pp + 4 * (BM + PADE));
+        if (half == 0) fa[i].lo = __builtin_bit_cast(decltype(fa[i].lo), v); else fa[i].hi = __builtin_bit_cast(decltype(fa[i].hi), v);
+      }
 #pragma unroll
-      for (int j = 0; j < NI; ++j) fb[j].load(&Bs[buf][(wn * (BN / 2) + j * 32 + l32) * (DEPTH + 8) + g * 16]);
+      for (int j = 0; j < NI; ++j) {
+        const T* pp = sb + kbase * (BN + PADE) + wn * (BN / 2) + j * 32 + coff;
+        const v8s v = tr_read8(pp, pp + 4 * (BN + PADE));
+        if (half == 0) fb[j].lo = __builtin_bit_cast(decltype(fb[j].lo), v); else fb[j].hi = __builtin_bit_cast(decltype(fb[j].hi), v);
+      }
+    }
+  };
+  auto mma_half = [&](int half) {
+    if constexpr (F32) {
+#pragma unroll
+      for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+          for (int j = 0; j < NI; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa32[i][half * 4 + t], fb32[j][half * 4 + t], acc[i][j], 0, 0, 0);
+    } else {
 #pragma unroll
       for (int i = 0; i < MI; ++i)
 #pragma unroll
-        for (int j = 0; j < NI; ++j) Frag<T>::mma(fa[i], fb[j], acc[i][j]);
+        for (int j = 0; j < NI; ++j) Frag<T>::mma_half(fa[i], fb[j], acc[i][j], half, 0);
     }
-    if (t + 1 < ntiles) sstore(buf ^ 1);
+  };
+
+  // pipeline as in the forward kernel: three LDS stages, two register generations, operand reload under the MFMAs
+  if (n > 0) { gload(IC<0>{}, 0); sstore(IC<0>{}, 0); }
+  if (n > 1) { gload(IC<1>{}, 1); sstore(IC<1>{}, 1); }
+  if (n > 2) gload(IC<0>{}, 2);
+  __syncthreads();
+  if (n > 0) { load_half(0, 0); load_half(1, 0); }
+  auto body = [&](auto G, int j, int stage) {
+    constexpr int p = decltype(G)::value;  // = j & 1: this generation holds tile j+2
+    const int nstage = stage == 2 ? 0 : stage + 1;
+    const bool has_next = j + 1 < n;
+    if (j + 3 < n) gload(IC<1 - p>{}, j + 3);
+    mma_half(0);
+    __builtin_amdgcn_sched_barrier(0);
+    if (has_next) load_half(0, nstage);
+    __builtin_amdgcn_sched_barrier(0);
+    mma_half(1);
+    __builtin_amdgcn_sched_barrier(0);
+    if (has_next) load_half(1, nstage);
+    if (j + 2 < n) sstore(G, stage == 0 ? 2 : stage - 1);
     __syncthreads();
+  };
+  {
+    int stage = 0;
+    for (int j = 0; j < n; j += 2) {
+      body(IC<0>{}, j, stage);
+      stage = stage == 2 ? 0 : stage + 1;
+      if (j + 1 < n) {
+        body(IC<1>{}, j + 1, stage);
+        stage = stage == 2 ? 0 : stage + 1;
+      }
+    }
   }
 
-  const int64_t outputs = (int64_t)a.K * a.R * a.S * a.C;
+  const int64_t outputs = (int64_t)K * a.R * a.S * C;
   float* dst = out + (int64_t)blockIdx.z * outputs;
 #pragma unroll
   for (int i = 0; i < MI; ++i)
@@ -1023,7 +1043,7 @@ __global__ void __launch_bounds__(256) conv_wgrad_kernel(const T* __restrict__ x
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
         const int k = k0 + wm * (BM / 2) + i * 32 + 8 * (e >> 2) + 4 * g + (e & 3);
-        dst[((int64_t)k * a.R * a.S + tap) * a.C + c] = acc[i][j][e];
+        dst[((int64_t)k * a.R * a.S + tap) * C + c] = acc[i][j][e];
       }
     }
 }
