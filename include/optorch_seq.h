@@ -150,6 +150,10 @@ typedef enum {
   OPTORCH_K_RELU_BIAS_BWD = 9, OPTORCH_K_OPTIMIZER = 10, OPTORCH_N_KERNEL_CLASSES = 11
 } optorch_kernel_class_t;
 int optorch_seq_profile_enable(optorch_seq_t* h, int32_t enable);
+/* Restricts the event pairs to the classes whose bit (1u << optorch_kernel_class_t) is set in class_mask; all
+ * classes by default.  Events cost host and GPU front-end time, so timing one class perturbs a step far less
+ * than timing all of them.  Takes effect from the next step; call optorch_seq_profile_enable to reset the sums. */
+int optorch_seq_profile_select(optorch_seq_t* h, uint32_t class_mask);
 int optorch_seq_profile_read(optorch_seq_t* h, int32_t* steps, uint64_t* launches, uint64_t* entries, double* gpu_ms,
                              double* flops, double* bytes);
 

@@ -20,7 +20,7 @@ OK, E_INVALID, E_BUDGET, E_HIP, E_ORDER = 0, -1, -2, -3, -4
 SYMBOLS = (
     "optorch_seq_create", "optorch_seq_query", "optorch_seq_bind", "optorch_seq_set_params",
     "optorch_seq_get_params", "optorch_seq_step", "optorch_seq_schedule_info", "optorch_seq_last_error",
-    "optorch_seq_destroy", "optorch_seq_profile_enable", "optorch_seq_profile_read", "optorch_seq_profile_read_entries",
+    "optorch_seq_destroy", "optorch_seq_profile_enable", "optorch_seq_profile_select", "optorch_seq_profile_read", "optorch_seq_profile_read_entries",
 )
 
 KERNEL_CLASSES = ("cast_in", "conv_fwd", "conv_dgrad", "conv_wgrad", "bn_stats", "bn_apply", "bn_bwd", "pool", "head",
@@ -75,6 +75,8 @@ def load_library() -> C.CDLL:
     lib.optorch_seq_schedule_info.restype = C.c_int
     lib.optorch_seq_profile_enable.argtypes = [H, C.c_int32]
     lib.optorch_seq_profile_enable.restype = C.c_int
+    lib.optorch_seq_profile_select.argtypes = [H, C.c_uint32]
+    lib.optorch_seq_profile_select.restype = C.c_int
     lib.optorch_seq_profile_read.argtypes = [H, C.POINTER(C.c_int32), C.POINTER(C.c_uint64), C.POINTER(C.c_uint64),
                                              C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_double)]
     lib.optorch_seq_profile_read.restype = C.c_int
@@ -220,6 +222,11 @@ class SeqTrainer(SeqPlan):
 
     def profile_enable(self, enable: bool = True):
         self._check(self.lib.optorch_seq_profile_enable(self.handle, 1 if enable else 0))
+
+    def profile_select(self, classes=None):
+        """Restrict event timing to the named kernel classes (None: all)."""
+        mask = 0xFFFFFFFF if classes is None else sum(1 << KERNEL_CLASSES.index(c) for c in classes)
+        self._check(self.lib.optorch_seq_profile_select(self.handle, mask))
 
     def profile_read(self) -> dict:
         """Per kernel class: launches, schedule entries, GPU ms, algorithmic FLOPs and bytes, summed over the

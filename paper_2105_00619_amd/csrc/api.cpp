@@ -29,6 +29,7 @@ struct optorch_seq {
   mutable std::string err;
   // profiling: event pairs per schedule entry, harvested on read
   bool profiling = false;
+  uint32_t prof_mask = 0xffffffffu;  // kernel classes whose entries are bracketed by events
   std::vector<hipEvent_t> ev_pool;
   size_t ev_used = 0;
   std::vector<int> ev_class;  // class of pair i
@@ -369,6 +370,12 @@ extern "C" int optorch_seq_profile_enable(optorch_seq_t* h, int32_t enable) {
   return OPTORCH_OK;
 }
 
+extern "C" int optorch_seq_profile_select(optorch_seq_t* h, uint32_t class_mask) {
+  if (!h) return OPTORCH_E_INVALID;
+  h->prof_mask = class_mask;
+  return OPTORCH_OK;
+}
+
 extern "C" int optorch_seq_profile_read(optorch_seq_t* h, int32_t* steps, uint64_t* launches, uint64_t* entries,
                                         double* gpu_ms, double* flops, double* bytes) {
   if (!h) return OPTORCH_E_INVALID;
@@ -432,7 +439,8 @@ extern "C" int optorch_seq_step(optorch_seq_t* h, const float* x_dev, const int3
     const SOp& s = h->plan.sched[si];
     if (!s.live) continue;
     hipEvent_t e0 = nullptr, e1 = nullptr;
-    if (prof && (e0 = next_event(h)) && (e1 = next_event(h))) (void)hipEventRecord(e0, st);
+    if (prof && ((h->prof_mask >> class_of(s.kind)) & 1u) && (e0 = next_event(h)) && (e1 = next_event(h)))
+      (void)hipEventRecord(e0, st);
     run_op(c, s);
     if (e1) {
       (void)hipEventRecord(e1, st);
@@ -448,7 +456,8 @@ extern "C" int optorch_seq_step(optorch_seq_t* h, const float* x_dev, const int3
   const int64_t P = (int64_t)h->plan.n_params;
   {
     hipEvent_t e0 = nullptr, e1 = nullptr;
-    if (prof && (e0 = next_event(h)) && (e1 = next_event(h))) (void)hipEventRecord(e0, st);
+    if (prof && ((h->prof_mask >> OPTORCH_K_OPTIMIZER) & 1u) && (e0 = next_event(h)) && (e1 = next_event(h)))
+      (void)hipEventRecord(e0, st);
     launch_optim(st, h->dt, c.w32(0), (float*)(h->pbase + h->off_v), c.g32(0), h->pbase + h->off_h, grads_dev, P, lr,
                  h->momentum, 1.f / h->scale, c.flags());
     if (e1) {

@@ -226,11 +226,14 @@ __global__ void __launch_bounds__(256) conv_igemm_kernel(const T* __restrict__ s
     for (int jn = 0; jn < NI; ++jn) fb[jn].load(lds + bfrag + jn * 32 * PITCH);
   }
   // iteration j: generation (j & 1) holds tile j+2 (issued at iteration j-1 or in the prologue)
-  auto body = [&](auto P, int j, int stage) {
+  // TAIL = 0: steady state, every step unconditional (a branch around the loads would make the compiler wait for
+  // the newest loads before each LDS store); TAIL = 1: the last iterations, with the range checks.
+  auto body = [&](auto P, auto TAILC, int j, int stage) {
     constexpr int p = decltype(P)::value;  // = j & 1
+    constexpr bool TAIL = decltype(TAILC)::value != 0;
     const T* nxt = lds + (stage == 2 ? 0 : stage + 1) * STAGE;
-    const bool has_next = j + 1 < n;
-    if (j + 3 < n) gload(IC<1 - p>{}, kt0 + j + 3);
+    const bool has_next = TAIL ? j + 1 < n : true;
+    if (!TAIL || j + 3 < n) gload(IC<1 - p>{}, kt0 + j + 3);
 #pragma unroll
     for (int st = 0; st < Frag<T>::HALF_STEPS; ++st)
 #pragma unroll
@@ -258,16 +261,22 @@ __global__ void __launch_bounds__(256) conv_igemm_kernel(const T* __restrict__ s
 #pragma unroll
       for (int jn = 0; jn < NI; ++jn) fb[jn].load_hi(nxt + bfrag + jn * 32 * PITCH);
     }
-    if (j + 2 < n) sstore(P, stage == 0 ? 2 : stage - 1);  // tile j+2 -> stage (j+2)%3
+    if (!TAIL || j + 2 < n) sstore(P, stage == 0 ? 2 : stage - 1);  // tile j+2 -> stage (j+2)%3
     __syncthreads();
   };
   {
-    int stage = 0;
-    for (int j = 0; j < n; j += 2) {
-      body(IC<0>{}, j, stage);
+    int stage = 0, j = 0;
+    for (; j + 4 < n; j += 2) {
+      body(IC<0>{}, IC<0>{}, j, stage);
+      stage = stage == 2 ? 0 : stage + 1;
+      body(IC<1>{}, IC<0>{}, j + 1, stage);
+      stage = stage == 2 ? 0 : stage + 1;
+    }
+    for (; j < n; j += 2) {
+      body(IC<0>{}, IC<1>{}, j, stage);
       stage = stage == 2 ? 0 : stage + 1;
       if (j + 1 < n) {
-        body(IC<1>{}, j + 1, stage);
+        body(IC<1>{}, IC<1>{}, j + 1, stage);
         stage = stage == 2 ? 0 : stage + 1;
       }
     }
@@ -336,13 +345,16 @@ __global__ void __launch_bounds__(256) conv_igemm_kernel(const T* __restrict__ s
 // 3x3, stride 1: the input patch of the block's pixels (with its halo and zero border) is staged in LDS once per
 // channel chunk and serves all nine filter taps, so the vector-memory path carries every input line once instead
 // of nine times; only the 64-byte-deep weight tile changes from tap to tap.
-//   block = 256 threads = 4 wavefronts (2 x 2); block tile = 2 pixel sub-tiles x BN channels; a wavefront owns one
-//   sub-tile (up to 128 pixels = TI images x TR rows x TC columns) and BN/2 channels: 4 x (BN/64) MFMA 32x32 tiles.
-//   LDS: 2 patch buffers [2*NPOS positions][80 B], 2 weight stages [BN][80 B], address tables.
+//   block = 256 threads = 4 wavefronts (2 x 2); block tile = 64*MI pixel rows x BN channels; a wavefront owns 32*MI
+//   rows and BN/2 channels: MI x (BN/64) MFMA 32x32 tiles.  The rows are SUBT pixel sub-tiles of 64*MI/SUBT pixels
+//   (TI images x TR rows x TC columns each, with their own halo).  Variants: (MI 4, SUBT 2) for large layers,
+//   (2, 1) and (1, 1) so that layers with few pixels still give every CU a block.
+//   LDS: 2 patch buffers [SUBT*256 positions][80 B], 3 weight stages [BN][80 B], address tables.
 //   Pipeline (one barrier per tap): the weight tile of (chunk c+1, tap t) is requested before the MFMAs of (c, t)
 //   and parked in registers until the end of step (c+1, t-1); the next chunk's patch is requested during taps 0-3
-//   and stored during taps 5-8.  All loads are straight-line, so five steps of loads stay in flight.  The data gradient of a stride-1 convolution is the same computation on dz with the taps visited in
-//   reverse and the border (kh-1-pad).
+//   and stored during taps 4-7.  All loads are straight-line, so several steps of loads stay in flight.
+//   The data gradient of a stride-1 convolution is the same computation on dz with the taps visited in reverse and
+//   the border (kh-1-pad).
 // ------------------------------------------------------------------------------------------------------------
 struct PatchArgs {
   int N, srcH, srcW, srcC;   // gathered tensor
@@ -355,26 +367,30 @@ struct PatchArgs {
 
 constexpr int PATCH_MAX_POS = 256;  // positions per sub-tile
 
-template <class T, int BN>
-__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) conv3x3_patch_kernel(const T* __restrict__ src, const T* __restrict__ wmat,
-                                                            const float* __restrict__ bias, const T* __restrict__ addend,
-                                                            T* __restrict__ out, PatchArgs a) {
+template <class T, int BN, int MI, int SUBT>
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, MI == 4 ? 1 : 2)))
+conv3x3_patch_kernel(const T* __restrict__ src, const T* __restrict__ wmat, const float* __restrict__ bias,
+                     const T* __restrict__ addend, T* __restrict__ out, PatchArgs a) {
+  constexpr int ROWS = 64 * MI;              // pixel rows of the block
+  constexpr int TPC = ROWS / SUBT;           // rows (pixel capacity) per sub-tile
+  constexpr int NSLOT = 4 * SUBT;            // 16-byte patch pieces per thread and channel chunk
+  constexpr int SPT = NSLOT / 4;             // pieces requested / stored per tap
   constexpr int CCE = Frag<T>::BK;           // channels per chunk (64 bytes)
   constexpr int EV = 16 / (int)sizeof(T);
   constexpr int PITCH = CCE + EV;            // elements per LDS row (80 bytes)
   constexpr int NI = BN / 64;
   constexpr int B_CH = BN * 4 / 256;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-  T* patch = reinterpret_cast<T*>(smem_raw);                                  // [2][2*PATCH_MAX_POS][PITCH]
-  T* Bs = patch + 2 * 2 * PATCH_MAX_POS * PITCH;                              // [3][BN][PITCH]
-  int64_t* src_off = reinterpret_cast<int64_t*>(Bs + 3 * BN * PITCH);         // [2*PATCH_MAX_POS]
-  int64_t* out_off = src_off + 2 * PATCH_MAX_POS;                             // [256]
+  T* patch = reinterpret_cast<T*>(smem_raw);                                  // [2][SUBT*PATCH_MAX_POS][PITCH]
+  T* Bs = patch + 2 * SUBT * PATCH_MAX_POS * PITCH;                           // [3][BN][PITCH]
+  int64_t* src_off = reinterpret_cast<int64_t*>(Bs + 3 * BN * PITCH);         // [SUBT*PATCH_MAX_POS]
+  int64_t* out_off = src_off + SUBT * PATCH_MAX_POS;                          // [256]
   int* apos = reinterpret_cast<int*>(out_off + 256);                          // [256]
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1, g = lane >> 5, l32 = lane & 31;
   const int n0c = blockIdx.y * BN;
-  const int npos2 = 2 * a.NPOS;
+  const int npos2 = SUBT * a.NPOS;
   const int srcC = a.srcC, flip = a.flip, SC = a.SC;
 
   // ---- address tables ------------------------------------------------------------------------------------------
@@ -382,7 +398,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
     const int u = e / a.NPOS, rem = e - u * a.NPOS;
     const int ti = rem / (a.SR * a.SC), rr = rem - ti * (a.SR * a.SC);
     const int sy = rr / a.SC, sx = rr - sy * a.SC;
-    const int tile = 2 * blockIdx.x + u;
+    const int tile = SUBT * blockIdx.x + u;
     int64_t off = -1;
     if (tile < a.NT) {
       const int ci = tile % a.tiles_c, t2 = tile / a.tiles_c;
@@ -393,11 +409,11 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
     src_off[e] = off;
   }
   {
-    const int m2 = tid, u = m2 >> 7, m = m2 & 127;
-    const int tile = 2 * blockIdx.x + u;
+    const int m2 = tid, u = m2 / TPC, m = m2 - u * TPC;
+    const int tile = SUBT * blockIdx.x + u;
     int64_t off = -1;
     int ap = 0;
-    if (m < a.TP && tile < a.NT) {
+    if (m2 < ROWS && m < a.TP && tile < a.NT) {
       const int ti = m / (a.TR * a.TC), rr = m - ti * (a.TR * a.TC);
       const int tr = rr / a.TC, tc = rr - tr * a.TC;
       const int ci = tile % a.tiles_c, t2 = tile / a.tiles_c;
@@ -415,17 +431,17 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
   const int Kg = 9 * srcC;
 
   // ---- loaders ---------------------------------------------------------------------------------------------------
-  Chunk PR[8];  // patch chunks in flight (next channel chunk)
+  Chunk PR[NSLOT];  // patch chunks in flight (next channel chunk)
   // weight tiles in flight: one generation per tap, requested a whole channel chunk (nine steps) ahead
   // (a = rows 0-63, b = rows 64-127 of the tile)
   Chunk BRa[9], BRb[9];
   const int bvec = tid & 3, brow0 = tid >> 2;
   // patch pieces of this thread: slot sl covers the 16-byte piece idx = sl*256 + tid.  Loads are unconditional
   // (pieces outside the image read the tensor's first pixel) and are zeroed when written to LDS.
-  const T* pptr[8];
+  const T* pptr[NSLOT];
   unsigned pvalid = 0u, pstore = 0u;
 #pragma unroll
-  for (int sl = 0; sl < 8; ++sl) {
+  for (int sl = 0; sl < NSLOT; ++sl) {
     const int idx = sl * 256 + tid;
     const int pos = idx >> 2, v = idx & 3;
     int64_t off = 0;
@@ -441,7 +457,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
     const int idx = slot * 256 + tid;
     const int pos = idx >> 2, v = idx & 3;
     if ((pstore >> slot) & 1u)
-      *reinterpret_cast<Chunk*>(&patch[(buf * 2 * PATCH_MAX_POS + pos) * PITCH + v * EV]) = ((pvalid >> slot) & 1u) ? c : zero_chunk();
+      *reinterpret_cast<Chunk*>(&patch[(buf * SUBT * PATCH_MAX_POS + pos) * PITCH + v * EV]) = ((pvalid >> slot) & 1u) ? c : zero_chunk();
   };
   const T* wrow = wmat + (int64_t)(n0c + brow0) * Kg + bvec * EV;
   // weight tile of global step gs = chunk*9 + tap -> registers REG
@@ -461,23 +477,23 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
 
   // ---- prologue -----------------------------------------------------------------------------------------------
 #pragma unroll
-  for (int sl = 0; sl < 8; ++sl) PR[sl] = patch_load(sl, 0);
+  for (int sl = 0; sl < NSLOT; ++sl) PR[sl] = patch_load(sl, 0);
 #pragma unroll
   for (int t = 0; t < 9; ++t) B_LOAD(t, 0);
 #pragma unroll
-  for (int sl = 0; sl < 8; ++sl) patch_store(sl, 0, PR[sl]);
+  for (int sl = 0; sl < NSLOT; ++sl) patch_store(sl, 0, PR[sl]);
   B_STORE(0, 0);
   B_STORE(1, 1);
   __syncthreads();
 
-  int arow[4];  // LDS element offset of tap (0,0) for this lane's four 32-row groups
+  int arow[MI];  // LDS element offset of tap (0,0) for this lane's 32-row groups
 #pragma unroll
-  for (int i = 0; i < 4; ++i) arow[i] = apos[wm * 128 + i * 32 + l32] * PITCH + Frag<T>::lane_off(g);
+  for (int i = 0; i < MI; ++i) arow[i] = apos[wm * (32 * MI) + i * 32 + l32] * PITCH + Frag<T>::lane_off(g);
   const int bfrag = (wn * (BN / 2) + l32) * PITCH + Frag<T>::lane_off(g);  // this lane's row in a weight stage
 
-  v16f acc[4][NI];
+  v16f acc[MI][NI];
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < MI; ++i)
 #pragma unroll
     for (int j = 0; j < NI; ++j)
 #pragma unroll
@@ -488,9 +504,9 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
   // run under the MFMAs of step g and nothing waits on LDS latency.  Weight stage = step % 3; the weight tile of step
   // g+2 is written at the end of step g, the next chunk's patch during taps 4-7, so both are complete one barrier
   // before their first read.
-  Frag<T> fa[4], fb[NI];
+  Frag<T> fa[MI], fb[NI];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) fa[i].load(patch + arow[i]);
+  for (int i = 0; i < MI; ++i) fa[i].load(patch + arow[i]);
 #pragma unroll
   for (int j = 0; j < NI; ++j) fb[j].load(&Bs[bfrag + j * 32 * PITCH]);
 
@@ -498,8 +514,8 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
   auto chunk_body = [&](auto LAST, int chunk) {
     constexpr bool last = decltype(LAST)::value != 0;
     const int pbuf = chunk & 1;
-    const T* pcur = patch + pbuf * 2 * PATCH_MAX_POS * PITCH;
-    const T* pnxt = patch + (pbuf ^ 1) * 2 * PATCH_MAX_POS * PITCH;
+    const T* pcur = patch + pbuf * SUBT * PATCH_MAX_POS * PITCH;
+    const T* pnxt = patch + (pbuf ^ 1) * SUBT * PATCH_MAX_POS * PITCH;
 #pragma unroll
     for (int t = 0; t < 9; ++t) {
       // where the next step reads its operands
@@ -510,18 +526,21 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
       const T* bn_ = &Bs[((t + 1) % 3) * BN * PITCH + bfrag];
       // requests: the weight tile this tap will need in the next chunk, two pieces of the next patch during taps 0-3
       if (!last) B_LOAD(t, chunk + 1);
-      if (!last && t < 4) { PR[2 * t] = patch_load(2 * t, chunk + 1); PR[2 * t + 1] = patch_load(2 * t + 1, chunk + 1); }
+      if (!last && t < 4) {
+#pragma unroll
+        for (int q = 0; q < SPT; ++q) PR[SPT * t + q] = patch_load(SPT * t + q, chunk + 1);
+      }
       // first halves
 #pragma unroll
       for (int st = 0; st < Frag<T>::HALF_STEPS; ++st)
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < MI; ++i)
 #pragma unroll
           for (int j = 0; j < NI; ++j) Frag<T>::mma_half(fa[i], fb[j], acc[i][j], 0, st);
       __builtin_amdgcn_sched_barrier(0);
       if (has_next) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) fa[i].load_lo(pn + arow[i] + tapoff_n);
+        for (int i = 0; i < MI; ++i) fa[i].load_lo(pn + arow[i] + tapoff_n);
 #pragma unroll
         for (int j = 0; j < NI; ++j) fb[j].load_lo(bn_ + j * 32 * PITCH);
       }
@@ -530,19 +549,22 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
 #pragma unroll
       for (int st = 0; st < Frag<T>::HALF_STEPS; ++st)
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < MI; ++i)
 #pragma unroll
           for (int j = 0; j < NI; ++j) Frag<T>::mma_half(fa[i], fb[j], acc[i][j], 1, st);
       __builtin_amdgcn_sched_barrier(0);
       if (has_next) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) fa[i].load_hi(pn + arow[i] + tapoff_n);
+        for (int i = 0; i < MI; ++i) fa[i].load_hi(pn + arow[i] + tapoff_n);
 #pragma unroll
         for (int j = 0; j < NI; ++j) fb[j].load_hi(bn_ + j * 32 * PITCH);
       }
       // parked data goes to LDS: weight tile of step g+2, patch pieces requested four taps ago
       if (t + 2 < 9) B_STORE(t + 2, (t + 2) % 3) else if (!last) B_STORE(t + 2 - 9, (t + 2) % 3)
-      if (!last && t >= 4 && t < 8) { patch_store(2 * (t - 4), pbuf ^ 1, PR[2 * (t - 4)]); patch_store(2 * (t - 4) + 1, pbuf ^ 1, PR[2 * (t - 4) + 1]); }
+      if (!last && t >= 4 && t < 8) {
+#pragma unroll
+        for (int q = 0; q < SPT; ++q) patch_store(SPT * (t - 4) + q, pbuf ^ 1, PR[SPT * (t - 4) + q]);
+      }
       __syncthreads();
     }
   };
@@ -550,9 +572,9 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
   chunk_body(IC<1>{}, nchunks - 1);
 
   // ---- epilogue ---------------------------------------------------------------------------------------------------
-  // The accumulators go through LDS (the patch buffers are free now), one 128-pixel sub-tile at a time as fp32
-  // [row][BN + 4], so that every lane then handles 8 consecutive channels of one pixel: bias / residual addend / ReLU
-  // in fp32, one rounding, one 16-byte (8-byte for fp32: two) store; a wavefront writes whole rows.
+  // The accumulators go through LDS (the patch buffers are free now), the rows of one wavefront pair at a time, as
+  // fp32 [row][BN + 4], so that every lane then handles 8 consecutive channels of one pixel: bias / residual addend /
+  // ReLU in fp32, one rounding, one 16-byte (fp32: two) store; a wavefront writes whole rows.
   {
     float* ep = reinterpret_cast<float*>(smem_raw);
     constexpr int EP_PITCH = BN + 4;
@@ -561,7 +583,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
       __syncthreads();
       if (wm == u) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < MI; ++i)
 #pragma unroll
           for (int j = 0; j < NI; ++j)
 #pragma unroll
@@ -570,12 +592,13 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
       }
       __syncthreads();
       constexpr int GROUPS = BN / 8;              // 8-channel groups per row
-      constexpr int PER_THREAD = 128 * GROUPS / 256;
+      constexpr int PER_THREAD = 32 * MI * GROUPS / 256;
+      static_assert(PER_THREAD >= 1, "epilogue pass smaller than the block");
 #pragma unroll
       for (int it = 0; it < PER_THREAD; ++it) {
         const int id = it * 256 + tid;
         const int row = id / GROUPS, c8 = (id - row * GROUPS) * 8;
-        const int64_t ro = out_off[u * 128 + row];
+        const int64_t ro = out_off[u * (32 * MI) + row];
         if (ro >= 0) {
           const v4f x0 = *reinterpret_cast<const v4f*>(&ep[row * EP_PITCH + c8]);
           const v4f x1 = *reinterpret_cast<const v4f*>(&ep[row * EP_PITCH + c8 + 4]);
@@ -605,16 +628,17 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
 #undef B_LOAD
 #undef B_STORE
 
-template <class T> constexpr size_t patch_smem_bytes(int bn) {
-  return (size_t)(2 * 2 * PATCH_MAX_POS + 3 * bn) * (Frag<T>::BK + 16 / sizeof(T)) * sizeof(T) + 2 * PATCH_MAX_POS * 8 + 256 * 8 +
-         256 * 4;
+template <class T> constexpr size_t patch_smem_bytes(int bn, int subt) {
+  return (size_t)(2 * subt * PATCH_MAX_POS + 3 * bn) * (Frag<T>::BK + 16 / sizeof(T)) * sizeof(T) + subt * PATCH_MAX_POS * 8 +
+         256 * 8 + 256 * 4;
 }
 
-// tile geometry of the patch kernel for a (dstH x dstW) pixel grid gathered with a 3x3 window; false if it does not fit
-static bool patch_geometry(int N, int dstH, int dstW, PatchArgs& a) {
-  int tc = dstW < 128 ? dstW : 128;
-  int tr = 128 / tc; if (tr > dstH) tr = dstH; if (tr < 1) tr = 1;
-  int ti = (tr == dstH && tc == dstW) ? 128 / (dstH * dstW) : 1;
+// tile geometry of the patch kernel for a (dstH x dstW) pixel grid gathered with a 3x3 window and sub-tiles of up to
+// `cap` pixels; false if it does not fit
+static bool patch_geometry(int N, int dstH, int dstW, int cap, PatchArgs& a) {
+  int tc = dstW < cap ? dstW : cap;
+  int tr = cap / tc; if (tr > dstH) tr = dstH; if (tr < 1) tr = 1;
+  int ti = (tr == dstH && tc == dstW) ? cap / (dstH * dstW) : 1;
   if (ti > N) ti = N; if (ti < 1) ti = 1;
   while (ti > 1 && ti * (tr + 2) * (tc + 2) > PATCH_MAX_POS) ti /= 2;
   while (tr > 1 && ti * (tr + 2) * (tc + 2) > PATCH_MAX_POS) --tr;
@@ -627,40 +651,73 @@ static bool patch_geometry(int N, int dstH, int dstW, PatchArgs& a) {
   return true;
 }
 
-// the patch kernel pays off when the tile rows are well used and there are enough blocks to fill the chip
-int g_patch_min_blocks = 96;  // tuning constant (shape-only rule; not part of the C ABI)
-static bool patch_ok(int dt, int N, int dstH, int dstW, int srcC, int Ng, int R, int S, int stride) {
+// Block shapes of the patch kernel, largest first: {MI, SUBT, widest BN}.  The first one that gives the chip
+// `g_patch_fill` blocks is taken, else the one with the most blocks if that reaches `g_patch_min_blocks`
+// (shape-only rule, so the choice is the same on every run).
+struct PatchShape { int mi, subt, bn; };
+int g_patch_min_blocks = 96;   // tuning constants (not part of the C ABI)
+int g_patch_fill = 200;
+int g_patch_shapes = 0xf;      // bit i: candidate i allowed
+static bool patch_pick(int dt, int N, int dstH, int dstW, int srcC, int Ng, int R, int S, int stride, PatchShape& shape,
+                       PatchArgs& geo) {
   if (R != 3 || S != 3 || stride != 1) return false;
   if (srcC % (dt == DT_F32 ? 16 : 32) != 0 || Ng % 64 != 0) return false;
-  PatchArgs a{};
-  if (!patch_geometry(N, dstH, dstW, a)) return false;
-  if (a.TP < 96) return false;
-  const int64_t blocks = (int64_t)((a.NT + 1) / 2) * (Ng / (Ng % 128 == 0 ? 128 : 64));
-  return blocks >= g_patch_min_blocks;
+  const int wide = Ng % 128 == 0 ? 128 : 64;
+  const PatchShape cand[4] = {{4, 2, wide}, {2, 1, wide}, {2, 1, 64}, {1, 1, 64}};
+  int best = -1;
+  int64_t best_blocks = 0;
+  PatchArgs best_geo{};
+  for (int i = 0; i < 4; ++i) {
+    if (!((g_patch_shapes >> i) & 1)) continue;
+    if (i == 2 && wide == 64) continue;  // same as candidate 1
+    const int cap = 64 * cand[i].mi / cand[i].subt;
+    PatchArgs a{};
+    if (!patch_geometry(N, dstH, dstW, cap, a)) continue;
+    if (a.TP * 4 < cap * 3) continue;  // tile rows poorly used
+    if (a.NPOS * 2 > a.TP * 5) continue;  // mostly halo (2x2 images): the staged patch costs more than it saves
+    const int64_t blocks = (int64_t)((a.NT + cand[i].subt - 1) / cand[i].subt) * (Ng / cand[i].bn);
+    if (blocks > best_blocks) { best = i; best_blocks = blocks; best_geo = a; }
+    if (blocks >= g_patch_fill) break;
+  }
+  if (best < 0 || best_blocks < g_patch_min_blocks) return false;
+  shape = cand[best];
+  geo = best_geo;
+  return true;
+}
+
+template <class T, int BN, int MI, int SUBT>
+static void launch_patch_v(hipStream_t st, const void* src, const void* wmat, const float* bias, const void* addend, void* out,
+                           const PatchArgs& a) {
+  dim3 grid((a.NT + SUBT - 1) / SUBT, a.Ng / BN), block(256);
+  constexpr size_t sm = patch_smem_bytes<T>(BN, SUBT);
+  static bool attr_done = false;
+  if (!attr_done) {
+    (void)hipFuncSetAttribute((const void*)conv3x3_patch_kernel<T, BN, MI, SUBT>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sm);
+    attr_done = true;
+  }
+  hipLaunchKernelGGL((conv3x3_patch_kernel<T, BN, MI, SUBT>), grid, block, sm, st, (const T*)src, (const T*)wmat, bias,
+                     (const T*)addend, (T*)out, a);
 }
 
 template <class T>
 static void launch_patch_t(hipStream_t st, const void* src, const void* wmat, const float* bias, const void* addend, void* out,
-                           PatchArgs a) {
-  const bool wide = a.Ng % 128 == 0;
-  dim3 grid((a.NT + 1) / 2, a.Ng / (wide ? 128 : 64)), block(256);
-  static bool attr_done[2] = {false, false};
-  if (wide) {
-    const size_t sm = patch_smem_bytes<T>(128);
-    if (!attr_done[0]) { (void)hipFuncSetAttribute((const void*)conv3x3_patch_kernel<T, 128>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sm); attr_done[0] = true; }
-    hipLaunchKernelGGL((conv3x3_patch_kernel<T, 128>), grid, block, sm, st, (const T*)src, (const T*)wmat, bias, (const T*)addend, (T*)out, a);
+                           const PatchShape& v, const PatchArgs& a) {
+  if (v.mi == 4) {
+    if (v.bn == 128) launch_patch_v<T, 128, 4, 2>(st, src, wmat, bias, addend, out, a);
+    else launch_patch_v<T, 64, 4, 2>(st, src, wmat, bias, addend, out, a);
+  } else if (v.mi == 2) {
+    if (v.bn == 128) launch_patch_v<T, 128, 2, 1>(st, src, wmat, bias, addend, out, a);
+    else launch_patch_v<T, 64, 2, 1>(st, src, wmat, bias, addend, out, a);
   } else {
-    const size_t sm = patch_smem_bytes<T>(64);
-    if (!attr_done[1]) { (void)hipFuncSetAttribute((const void*)conv3x3_patch_kernel<T, 64>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sm); attr_done[1] = true; }
-    hipLaunchKernelGGL((conv3x3_patch_kernel<T, 64>), grid, block, sm, st, (const T*)src, (const T*)wmat, bias, (const T*)addend, (T*)out, a);
+    launch_patch_v<T, 64, 1, 1>(st, src, wmat, bias, addend, out, a);
   }
 }
 
 static void launch_patch(hipStream_t st, int dt, const void* src, const void* wmat, const float* bias, const void* addend, void* out,
-                         const PatchArgs& a) {
-  if (dt == DT_F32) launch_patch_t<float>(st, src, wmat, bias, addend, out, a);
-  else if (dt == DT_BF16) launch_patch_t<bf16_t>(st, src, wmat, bias, addend, out, a);
-  else launch_patch_t<f16_t>(st, src, wmat, bias, addend, out, a);
+                         const PatchShape& v, const PatchArgs& a) {
+  if (dt == DT_F32) launch_patch_t<float>(st, src, wmat, bias, addend, out, v, a);
+  else if (dt == DT_BF16) launch_patch_t<bf16_t>(st, src, wmat, bias, addend, out, v, a);
+  else launch_patch_t<f16_t>(st, src, wmat, bias, addend, out, v, a);
 }
 
 template <class T>
@@ -683,6 +740,9 @@ __global__ void __launch_bounds__(256) splitk_epilogue_kernel(const float* __res
   store_f32<T, 4>(out + i, r);
 }
 
+int g_igemm_spread = 1;                         // tuning switch (not part of the C ABI)
+constexpr size_t kSpreadLds = 84 * 1024;        // more than half of the 160 KB of LDS per CU
+
 // rows per block: 256 when that still gives every CU two blocks, else 128 (from the shape only)
 static int igemm_bm(int64_t M, int Ng) {
   const int64_t cols = Ng / (Ng % 128 == 0 ? 128 : 64);
@@ -698,17 +758,21 @@ static void launch_igemm_t(hipStream_t st, const void* src, const void* wmat, co
   const bool wide = a.Ng % 128 == 0;
   const int bm = splits > 1 ? 128 : igemm_bm(a.M, a.Ng);
   dim3 grid(ceil_div(a.M, bm), a.Ng / (wide ? 128 : 64), splits), block(256);
+  // A grid of at most one block per CU asks for more than half of a CU's LDS, so that no CU takes two blocks
+  // while another idles.
+  const bool spread = g_igemm_spread && (int64_t)grid.x * grid.y * grid.z <= 256;
 #define IGEMM_LAUNCH(BM_, BN_, SPLIT_)                                                                                   \
   {                                                                                                                      \
     constexpr size_t sm_ = igemm_smem_bytes<T, BM_, BN_>();                                                              \
+    constexpr size_t big_ = sm_ > kSpreadLds ? sm_ : kSpreadLds;                                                         \
     static bool attr_ = false;                                                                                           \
     if (!attr_) {                                                                                                        \
       (void)hipFuncSetAttribute((const void*)conv_igemm_kernel<T, BM_, BN_, MODE, SPLIT_>,                               \
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)sm_);                                   \
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)big_);                                  \
       attr_ = true;                                                                                                      \
     }                                                                                                                    \
-    hipLaunchKernelGGL((conv_igemm_kernel<T, BM_, BN_, MODE, SPLIT_>), grid, block, sm_, st, (const T*)src,              \
-                       (const T*)wmat, bias, (const T*)addend, (T*)out, partial, a);                                     \
+    hipLaunchKernelGGL((conv_igemm_kernel<T, BM_, BN_, MODE, SPLIT_>), grid, block, spread ? big_ : sm_, st,             \
+                       (const T*)src, (const T*)wmat, bias, (const T*)addend, (T*)out, partial, a);                      \
   }
   if (splits > 1) {
     if (wide) IGEMM_LAUNCH(128, 128, true) else IGEMM_LAUNCH(128, 64, true)
@@ -743,11 +807,13 @@ static int igemm_splits(int dt, int64_t M, int Ng, int Kg) {
   return (int)(s < 1 ? 1 : s);
 }
 int conv_mfma_fwd_splits(int dt, const ConvGeom& g) {
-  if (patch_ok(dt, g.N, g.P, g.Q, g.C, g.K, g.R, g.S, g.stride)) return 1;
+  PatchShape v; PatchArgs pa{};
+  if (patch_pick(dt, g.N, g.P, g.Q, g.C, g.K, g.R, g.S, g.stride, v, pa)) return 1;
   return igemm_splits(dt, (int64_t)g.N * g.P * g.Q, g.K, g.R * g.S * g.C);
 }
 int conv_mfma_dgrad_splits(int dt, const ConvGeom& g) {
-  if (patch_ok(dt, g.N, g.H, g.W, g.K, g.C, g.R, g.S, g.stride)) return 1;
+  PatchShape v; PatchArgs pa{};
+  if (patch_pick(dt, g.N, g.H, g.W, g.K, g.C, g.R, g.S, g.stride, v, pa)) return 1;
   return igemm_splits(dt, (int64_t)g.N * g.H * g.W, g.C, g.R * g.S * g.K);
 }
 
@@ -762,12 +828,11 @@ bool conv_mfma_dgrad_ok(int dt, const ConvGeom& g) {
 
 void launch_conv_fwd_mfma(hipStream_t st, int dt, const void* x, const void* w, const float* bias, void* out,
                           float* partial, int splits, const ConvGeom& g, int relu) {
-  if (patch_ok(dt, g.N, g.P, g.Q, g.C, g.K, g.R, g.S, g.stride)) {
-    PatchArgs pa{};
-    patch_geometry(g.N, g.P, g.Q, pa);
+  PatchShape pv; PatchArgs pa{};
+  if (patch_pick(dt, g.N, g.P, g.Q, g.C, g.K, g.R, g.S, g.stride, pv, pa)) {
     pa.N = g.N; pa.srcH = g.H; pa.srcW = g.W; pa.srcC = g.C; pa.dstH = g.P; pa.dstW = g.Q; pa.Ng = g.K;
     pa.pad = g.pad; pa.flip = 0; pa.relu = relu;
-    launch_patch(st, dt, x, w, bias, nullptr, out, pa);
+    launch_patch(st, dt, x, w, bias, nullptr, out, pv, pa);
     return;
   }
   IGemmArgs a{g.H, g.W, g.C, g.P, g.Q, g.N * g.P * g.Q, g.K, g.R * g.S * g.C, g.R, g.S, g.stride, g.pad, relu, 0};
@@ -777,12 +842,11 @@ void launch_conv_fwd_mfma(hipStream_t st, int dt, const void* x, const void* w, 
 // wt: the (C_in, kh, kw, C_out) transpose of the weights, in the compute type
 void launch_conv_dgrad_mfma(hipStream_t st, int dt, const void* dz, const void* wt, const void* addend, void* dx,
                             float* partial, int splits, const ConvGeom& g) {
-  if (patch_ok(dt, g.N, g.H, g.W, g.K, g.C, g.R, g.S, g.stride)) {
-    PatchArgs pa{};
-    patch_geometry(g.N, g.H, g.W, pa);
+  PatchShape pv; PatchArgs pa{};
+  if (patch_pick(dt, g.N, g.H, g.W, g.K, g.C, g.R, g.S, g.stride, pv, pa)) {
     pa.N = g.N; pa.srcH = g.P; pa.srcW = g.Q; pa.srcC = g.K; pa.dstH = g.H; pa.dstW = g.W; pa.Ng = g.C;
     pa.pad = g.R - 1 - g.pad; pa.flip = 1; pa.relu = 0;
-    launch_patch(st, dt, dz, wt, nullptr, addend, dx, pa);
+    launch_patch(st, dt, dz, wt, nullptr, addend, dx, pv, pa);
     return;
   }
   IGemmArgs a{g.P, g.Q, g.K, g.H, g.W, g.N * g.H * g.W, g.C, g.R * g.S * g.K, g.R, g.S, g.stride, g.pad, 0, 0};
@@ -1006,11 +1070,12 @@ __global__ void __launch_bounds__(256) conv_wgrad_kernel(const T* __restrict__ x
   if (n > 2) gload(IC<0>{}, 2);
   __syncthreads();
   if (n > 0) { load_half(0, 0); load_half(1, 0); }
-  auto body = [&](auto G, int j, int stage) {
+  auto body = [&](auto G, auto TAILC, int j, int stage) {
     constexpr int p = decltype(G)::value;  // = j & 1: this generation holds tile j+2
+    constexpr bool TAIL = decltype(TAILC)::value != 0;  // 0: steady state without range checks
     const int nstage = stage == 2 ? 0 : stage + 1;
-    const bool has_next = j + 1 < n;
-    if (j + 3 < n) gload(IC<1 - p>{}, j + 3);
+    const bool has_next = TAIL ? j + 1 < n : true;
+    if (!TAIL || j + 3 < n) gload(IC<1 - p>{}, j + 3);
     mma_half(0);
     __builtin_amdgcn_sched_barrier(0);
     if (has_next) load_half(0, nstage);
@@ -1018,16 +1083,22 @@ __global__ void __launch_bounds__(256) conv_wgrad_kernel(const T* __restrict__ x
     mma_half(1);
     __builtin_amdgcn_sched_barrier(0);
     if (has_next) load_half(1, nstage);
-    if (j + 2 < n) sstore(G, stage == 0 ? 2 : stage - 1);
+    if (!TAIL || j + 2 < n) sstore(G, stage == 0 ? 2 : stage - 1);
     __syncthreads();
   };
   {
-    int stage = 0;
-    for (int j = 0; j < n; j += 2) {
-      body(IC<0>{}, j, stage);
+    int stage = 0, j = 0;
+    for (; j + 4 < n; j += 2) {
+      body(IC<0>{}, IC<0>{}, j, stage);
+      stage = stage == 2 ? 0 : stage + 1;
+      body(IC<1>{}, IC<0>{}, j + 1, stage);
+      stage = stage == 2 ? 0 : stage + 1;
+    }
+    for (; j < n; j += 2) {
+      body(IC<0>{}, IC<1>{}, j, stage);
       stage = stage == 2 ? 0 : stage + 1;
       if (j + 1 < n) {
-        body(IC<1>{}, j + 1, stage);
+        body(IC<1>{}, IC<1>{}, j + 1, stage);
         stage = stage == 2 ? 0 : stage + 1;
       }
     }

@@ -73,6 +73,11 @@ LAYER_NETS = {
     "patch_128_at16": (128, 16, 96, [W.conv(128, 128), W.conv(128, 128), W.gap_linear_ce(128, 10)]),
     "patch_ragged_20": (64, 20, 48, [W.conv(64, 64), W.conv(64, 128), W.conv(128, 64, pad=0), W.gap_linear_ce(64, 10)]),
     "patch_block_256_at8": (256, 8, 192, [W.basic_block(256, 256), W.gap_linear_ce(256, 10)]),
+    # batches at which the shape-only rule takes the larger block shapes of that kernel (128 pixel rows per
+    # wavefront pair with 128 or 64 channels, and 64 rows per pair with 128 channels)
+    "patch_wide_128_at16": (128, 16, 208, [W.conv(128, 128), W.conv(128, 128), W.gap_linear_ce(128, 10)]),
+    "patch_half_128_at16": (128, 16, 104, [W.conv(128, 128), W.conv(128, 128), W.gap_linear_ce(128, 10)]),
+    "patch_wide_64_at32": (64, 32, 52, [W.conv(64, 64), W.conv(64, 64), W.gap_linear_ce(64, 10)]),
 }
 
 
