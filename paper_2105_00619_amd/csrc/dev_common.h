@@ -39,6 +39,18 @@ __device__ __forceinline__ void store_f32(T* p, const float (&in)[V]) {
   *reinterpret_cast<Vec<T, V>*>(p) = t;
 }
 
+// 16 bytes held in registers between a global load and an LDS store (a plain vector type: arrays of it stay in
+// registers across loop back-edges)
+typedef __attribute__((ext_vector_type(4))) uint32_t Chunk;
+__device__ __forceinline__ Chunk zero_chunk() { Chunk c = {0u, 0u, 0u, 0u}; return c; }
+
+// floor(m / d) by multiplication, exact for m * d < 2^48
+struct FastDiv {
+  uint64_t magic; uint32_t d;
+  __device__ __forceinline__ uint32_t div(uint32_t m) const { return (uint32_t)(((uint64_t)m * magic) >> 48); }
+};
+inline FastDiv make_fastdiv(uint32_t d) { FastDiv f; f.d = d; f.magic = (((uint64_t)1 << 48) + d - 1) / d; return f; }
+
 // The BatchNorm affine map; the same instruction sequence in forward and backward so that the
 // ReLU mask rebuilt in backward equals the one applied in forward, bit for bit.
 __device__ __forceinline__ float bn_affine(float z, float scale, float shift) { return __fmaf_rn(z, scale, shift); }

@@ -152,74 +152,151 @@ __global__ void __launch_bounds__(256) conv_fwd_smallc_kernel(const T* __restric
   store_f32<T, 8>(out + m * g.K + kg * 8, acc);
 }
 
-// weight gradient for few input channels: a block reduces a fixed chunk of pixels; thread (k, ti) accumulates
-// dw[k][i] for i = ti, ti+4, ...; dz and the input patches of 64 pixels at a time are staged in LDS as fp32
+// Weight gradient for few input channels (the network stem):  dw[k][e] = sum over pixels of dz[px][k] * col[px][e],
+// e = (tap, c) < 36, k <= 64.  HBM-bound on reading dz once.  A block reduces a fixed chunk of pixels in tiles of 64:
+// the dz tile [64][64] and the im2col tile [64][R*S*C] are staged in LDS as fp32 (two stages; the next tile's global
+// loads are issued before the MFMAs of the current one).  Each wavefront multiplies 16 of the 64 pixels with fp32
+// 32x32x2 MFMAs (rows k, columns e); the four partial sums are added in wavefront order through LDS.
 template <class T>
 __global__ void __launch_bounds__(256) conv_wgrad_smallc_kernel(const T* __restrict__ x, const T* __restrict__ dz,
-                                                                float* __restrict__ partial, ConvGeom g, int chunk) {
-  __shared__ float dzs[64 * 65];
-  __shared__ float xs[64 * (SMALLC_MAX + 1)];
-  const int rsc = g.R * g.S * g.C;
-  const int tk = threadIdx.x & 63, ti = threadIdx.x >> 6;
-  const int64_t pixels = (int64_t)g.N * g.P * g.Q;
-  const int64_t m0 = (int64_t)blockIdx.x * chunk;
-  const int64_t m1 = m0 + chunk < pixels ? m0 + chunk : pixels;
-  float acc[SMALLC_MAX / 4];
+                                                                float* __restrict__ partial, ConvGeom g, int chunk,
+                                                                FastDiv divQ, FastDiv divPQ) {
+  typedef __attribute__((ext_vector_type(16))) float v16f;
+  constexpr int DP = 68, XP = 37;                          // LDS row pitches in floats
+  constexpr int NX = (64 * SMALLC_MAX + 255) / 256;        // im2col elements per thread and tile
+  constexpr int EV = 16 / (int)sizeof(T), CPP = 64 / EV;   // elements per 16-byte chunk, chunks per dz row
+  constexpr int DCH = 64 * CPP / 256;                      // dz chunks per thread and tile
+  __shared__ __attribute__((aligned(16))) float dzs[2][64 * DP];
+  __shared__ float xs[2][64 * XP];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hg = lane >> 5, l32 = lane & 31;
+  const int K = g.K, C = g.C, H = g.H, W = g.W, rsc = g.R * g.S * g.C, cstride = g.stride;
+  const int pixels = g.N * g.P * g.Q;
+  const int m0 = blockIdx.x * chunk;
+  const int m1 = m0 + chunk < pixels ? m0 + chunk : pixels;
+  const int nt = m1 > m0 ? (m1 - m0 + 63) / 64 : 0;
+
+  // tile-independent part of this thread's im2col elements: pixel row, filter offset, channel
+  int xpx[NX], xdy[NX], xdx[NX], xc[NX], xdst[NX];
 #pragma unroll
-  for (int j = 0; j < SMALLC_MAX / 4; ++j) acc[j] = 0.f;
-  for (int64_t mt = m0; mt < m1; mt += 64) {
-    // all global loads of the sub-tile are issued before the first LDS store (fixed trip counts, unrolled)
-    float vd[16], vx[(64 * SMALLC_MAX + 255) / 256];
+  for (int it = 0; it < NX; ++it) {
+    const int i = tid + it * 256;
+    const bool on = i < 64 * rsc;
+    const int px = on ? i / rsc : 0, e = on ? i - px * rsc : 0;
+    const int c = e % C, tap = e / C, s = tap % g.S, r = tap / g.S;
+    xpx[it] = on ? px : -1; xdy[it] = r - g.pad; xdx[it] = s - g.pad; xc[it] = c; xdst[it] = px * XP + e;
+  }
+  Chunk rd[DCH];
+  float rx[NX];
+  unsigned dmask = 0u, xmask = 0u;
+  // loads are unconditional (clamped addresses); what lies outside is zeroed when written to LDS
+  auto gload = [&](int t) {
+    const int mt = m0 + t * 64;
+    unsigned dm = 0u, xm = 0u;
 #pragma unroll
-    for (int it = 0; it < 16; ++it) {
-      const int i = threadIdx.x + it * 256;
-      const int px = i / g.K, k = i - px * g.K;
-      vd[it] = (i < 64 * g.K && mt + px < m1) ? to_f32(dz[(mt + px) * g.K + k]) : 0.f;
+    for (int i = 0; i < DCH; ++i) {
+      const int id = tid + i * 256, px = id / CPP, kv = id - px * CPP;
+      const bool ok = mt + px < m1 && kv * EV < K;
+      rd[i] = *reinterpret_cast<const Chunk*>(dz + (int64_t)(ok ? mt + px : m0) * K + (ok ? kv * EV : 0));
+      dm |= ok ? (1u << i) : 0u;
     }
 #pragma unroll
-    for (int it = 0; it < (64 * SMALLC_MAX + 255) / 256; ++it) {
-      const int i = threadIdx.x + it * 256;
-      const int px = i / rsc, e = i - px * rsc;
-      float v = 0.f;
-      const int64_t m = mt + px;
-      if (i < 64 * rsc && m < m1) {
-        const int c = e % g.C, tap = e / g.C, s = tap % g.S, r = tap / g.S;
-        const int q = (int)(m % g.Q);
-        const int64_t t = m / g.Q;
-        const int p = (int)(t % g.P), n = (int)(t / g.P);
-        const int ih = p * g.stride + r - g.pad, iw = q * g.stride + s - g.pad;
-        if (ih >= 0 && ih < g.H && iw >= 0 && iw < g.W) v = to_f32(x[(((int64_t)n * g.H + ih) * g.W + iw) * g.C + c]);
+    for (int it = 0; it < NX; ++it) {
+      const int m = mt + xpx[it];
+      bool ok = xpx[it] >= 0 && m < m1;
+      const uint32_t mm = ok ? (uint32_t)m : (uint32_t)m0;
+      const uint32_t n_ = divPQ.div(mm), rem = mm - n_ * divPQ.d;
+      const uint32_t p_ = divQ.div(rem), q_ = rem - p_ * divQ.d;
+      const int ih = (int)p_ * cstride + xdy[it], iw = (int)q_ * cstride + xdx[it];
+      ok = ok && ih >= 0 && ih < H && iw >= 0 && iw < W;
+      const int64_t off = ok ? (((int64_t)n_ * H + ih) * W + iw) * C + xc[it] : 0;
+      rx[it] = to_f32(x[off]);
+      xm |= ok ? (1u << it) : 0u;
+    }
+    dmask = dm; xmask = xm;
+  };
+  auto sstore = [&](int stage) {
+#pragma unroll
+    for (int i = 0; i < DCH; ++i) {
+      const int id = tid + i * 256, px = id / CPP, kv = id - px * CPP;
+      const Chunk c = ((dmask >> i) & 1u) ? rd[i] : zero_chunk();
+      float* dst = &dzs[stage][px * DP + kv * EV];
+      if constexpr (sizeof(T) == 4) {
+        *reinterpret_cast<Chunk*>(dst) = c;
+      } else {
+        const Vec<T, EV> v = __builtin_bit_cast(Vec<T, EV>, c);
+        float f[EV];
+#pragma unroll
+        for (int k = 0; k < EV; ++k) f[k] = to_f32(v.v[k]);
+#pragma unroll
+        for (int k = 0; k < EV; k += 4) {
+          typedef __attribute__((ext_vector_type(4))) float v4f;
+          v4f o = {f[k], f[k + 1], f[k + 2], f[k + 3]};
+          *reinterpret_cast<v4f*>(dst + k) = o;
+        }
       }
-      vx[it] = v;
     }
 #pragma unroll
-    for (int it = 0; it < 16; ++it) {
-      const int i = threadIdx.x + it * 256;
-      const int px = i / g.K, k = i - px * g.K;
-      if (i < 64 * g.K) dzs[px * 65 + k] = vd[it];
-    }
+    for (int it = 0; it < NX; ++it)
+      if (xpx[it] >= 0) xs[stage][xdst[it]] = ((xmask >> it) & 1u) ? rx[it] : 0.f;
+  };
+
+  v16f acc[2][2];
 #pragma unroll
-    for (int it = 0; it < (64 * SMALLC_MAX + 255) / 256; ++it) {
-      const int i = threadIdx.x + it * 256;
-      const int px = i / rsc, e = i - px * rsc;
-      if (i < 64 * rsc) xs[px * (SMALLC_MAX + 1) + e] = vx[it];
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+  const bool two_m = K > 32, two_n = rsc > 32;
+  const int e0 = l32 < rsc ? l32 : rsc - 1, e1 = 32 + l32 < rsc ? 32 + l32 : rsc - 1;
+  const float z0 = l32 < rsc ? 1.f : 0.f, z1 = 32 + l32 < rsc ? 1.f : 0.f;
+
+  if (nt > 0) { gload(0); sstore(0); }
+  __syncthreads();
+  for (int t = 0; t < nt; ++t) {
+    const int stage = t & 1;
+    if (t + 1 < nt) gload(t + 1);
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int px = 16 * wave + 8 * hg + u;
+      const float a0 = dzs[stage][px * DP + l32];
+      const float b0 = xs[stage][px * XP + e0] * z0;
+      acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
+      float a1 = 0.f;
+      if (two_m) {
+        a1 = dzs[stage][px * DP + 32 + l32];
+        acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
+      }
+      if (two_n) {
+        const float b1 = xs[stage][px * XP + e1] * z1;
+        acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
+        if (two_m) acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
+      }
     }
+    if (t + 1 < nt) sstore(stage ^ 1);
     __syncthreads();
-    if (tk < g.K) {
-#pragma unroll 4
-      for (int px = 0; px < 64; ++px) {
-        const float d = dzs[px * 65 + tk];
+  }
+
+  // the four wavefronts' sums, added in wavefront order: red[k][e], pitch 65
+  float* red = &dzs[0][0];
+#pragma unroll 1
+  for (int w = 0; w < 4; ++w) {
+    if (wave == w) {
 #pragma unroll
-        for (int j = 0; j < SMALLC_MAX / 4; ++j)
-          if (ti + 4 * j < rsc) acc[j] = __fmaf_rn(d, xs[px * (SMALLC_MAX + 1) + ti + 4 * j], acc[j]);
-      }
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) {
+            const int idx = (i * 32 + 8 * (e >> 2) + 4 * hg + (e & 3)) * 65 + j * 32 + l32;
+            red[idx] = w == 0 ? acc[i][j][e] : red[idx] + acc[i][j][e];
+          }
     }
     __syncthreads();
   }
-  if (tk < g.K) {
-#pragma unroll
-    for (int j = 0; j < SMALLC_MAX / 4; ++j)
-      if (ti + 4 * j < rsc) partial[((int64_t)blockIdx.x * g.K + tk) * rsc + ti + 4 * j] = acc[j];
+  for (int o = tid; o < K * rsc; o += 256) {
+    const int k = o / rsc, e = o - k * rsc;
+    partial[((int64_t)blockIdx.x * K + k) * rsc + e] = red[k * 65 + e];
   }
 }
 
@@ -236,7 +313,10 @@ __global__ void __launch_bounds__(256) wave_reduce_kernel(const float* __restric
 }
 
 bool conv_smallc_fwd_ok(const ConvGeom& g) { return g.C <= 4 && g.R == 3 && g.S == 3 && g.K % 8 == 0; }
-bool conv_smallc_wgrad_ok(const ConvGeom& g) { return g.C <= 4 && g.R * g.S * g.C <= SMALLC_MAX && g.K <= 64; }
+bool conv_smallc_wgrad_ok(const ConvGeom& g) {
+  return g.C <= 4 && g.R * g.S * g.C <= SMALLC_MAX && g.K <= 64 && g.K % 8 == 0 && (int64_t)g.N * g.P * g.Q < (1 << 24) &&
+         (int64_t)g.N * g.H * g.W * g.C < ((int64_t)1 << 31);
+}
 int conv_smallc_wgrad_splits(const ConvGeom& g) {
   const int64_t pixels = (int64_t)g.N * g.P * g.Q;
   int64_t b = (pixels + 255) / 256;
@@ -270,9 +350,10 @@ void launch_conv_wgrad_smallc(hipStream_t st, int dt, const void* x, const void*
   chunk = (chunk + 63) / 64 * 64;
   float* dst = splits > 1 ? partial : dw;
   dim3 grid(splits), block(256);
-  if (dt == DT_F32) hipLaunchKernelGGL(conv_wgrad_smallc_kernel<float>, grid, block, 0, st, (const float*)x, (const float*)dz, dst, g, chunk);
-  else if (dt == DT_BF16) hipLaunchKernelGGL(conv_wgrad_smallc_kernel<bf16_t>, grid, block, 0, st, (const bf16_t*)x, (const bf16_t*)dz, dst, g, chunk);
-  else hipLaunchKernelGGL(conv_wgrad_smallc_kernel<f16_t>, grid, block, 0, st, (const f16_t*)x, (const f16_t*)dz, dst, g, chunk);
+  const FastDiv dq = make_fastdiv((uint32_t)g.Q), dpq = make_fastdiv((uint32_t)(g.P * g.Q));
+  if (dt == DT_F32) hipLaunchKernelGGL(conv_wgrad_smallc_kernel<float>, grid, block, 0, st, (const float*)x, (const float*)dz, dst, g, chunk, dq, dpq);
+  else if (dt == DT_BF16) hipLaunchKernelGGL(conv_wgrad_smallc_kernel<bf16_t>, grid, block, 0, st, (const bf16_t*)x, (const bf16_t*)dz, dst, g, chunk, dq, dpq);
+  else hipLaunchKernelGGL(conv_wgrad_smallc_kernel<f16_t>, grid, block, 0, st, (const f16_t*)x, (const f16_t*)dz, dst, g, chunk, dq, dpq);
   if (splits > 1) {
     const int64_t n = (int64_t)g.K * g.R * g.S * g.C;
     hipLaunchKernelGGL(wave_reduce_kernel, dim3(ceil_div(n, 4)), dim3(256), 0, st, partial, dw, n, splits);

@@ -25,8 +25,6 @@ typedef __attribute__((ext_vector_type(8))) _Float16 v8h;
 typedef __attribute__((ext_vector_type(4))) float v4f;
 
 // 16 bytes in flight between global memory and LDS: a first-class vector value, never a stack object
-typedef __attribute__((ext_vector_type(4))) uint32_t Chunk;
-__device__ __forceinline__ Chunk zero_chunk() { Chunk c = {0u, 0u, 0u, 0u}; return c; }
 
 enum { IG_FWD = 0, IG_DGRAD = 1 };
 
@@ -882,12 +880,6 @@ void launch_weight_transpose(hipStream_t st, int dt, const float* w, void* wt, i
 // reduction elements.  The tiles are stored in LDS exactly as loaded (16-byte chunks, [pixel][channel]); fp32 lanes
 // read them with a stride, 16-bit lanes use the transposing LDS read of gfx950 (ds_read_b64_tr_b16).
 // ------------------------------------------------------------------------------------------------------------
-struct FastDiv {  // floor(m / d) for m * d < 2^48
-  uint64_t magic; uint32_t d;
-  __device__ __forceinline__ uint32_t div(uint32_t m) const { return (uint32_t)(((uint64_t)m * magic) >> 48); }
-};
-static FastDiv make_fastdiv(uint32_t d) { FastDiv f; f.d = d; f.magic = (((uint64_t)1 << 48) + d - 1) / d; return f; }
-
 struct WGradArgs {
   int H, W, C, K, R, S, stride, pad, P, Q;
   int pixels, chunk;  // chunk: pixels per blockIdx.z, a multiple of the depth tile

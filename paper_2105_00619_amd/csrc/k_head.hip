@@ -36,16 +36,20 @@ __global__ void __launch_bounds__(256) head_feat_kernel(const T* __restrict__ x,
   }
 }
 
-__global__ void linear_fwd_kernel(const float* __restrict__ feat, const float* __restrict__ w, const float* __restrict__ b,
-                                  float* __restrict__ logits, int N, int F, int J) {
-  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+// one wavefront per (sample, class): lanes stride over the features, then a fixed butterfly
+__global__ void __launch_bounds__(256) linear_fwd_kernel(const float* __restrict__ feat, const float* __restrict__ w,
+                                                         const float* __restrict__ b, float* __restrict__ logits, int N, int F,
+                                                         int J) {
+  const int i = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (i >= N * J) return;
-  const int n = i / J, j = i % J;
+  const int n = i / J, j = i % J, lane = threadIdx.x & 63;
   const float* fp = feat + (int64_t)n * F;
   const float* wp = w + (int64_t)j * F;
   float acc = 0.f;
-  for (int f = 0; f < F; ++f) acc = __fmaf_rn(fp[f], wp[f], acc);
-  logits[i] = acc + b[j];
+  for (int f = lane; f < F; f += 64) acc = __fmaf_rn(fp[f], wp[f], acc);
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) acc += __shfl_xor(acc, off, 64);
+  if (lane == 0) logits[i] = acc + b[j];
 }
 
 // per sample: loss_n = logsumexp(logits_n) - logits_n[y_n]; dlogits = (softmax - onehot) * gscale
@@ -83,18 +87,28 @@ __global__ void __launch_bounds__(256) loss_mean_kernel(const float* __restrict_
 }
 
 // dW[j][f] = sum_n dlogits[n][j] * feat[n][f] ; the extra column f == F is the bias gradient
-__global__ void linear_bwd_w_kernel(const float* __restrict__ dlogits, const float* __restrict__ feat, float* __restrict__ dw,
-                                    float* __restrict__ db, int N, int F, int J) {
-  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= (int64_t)J * (F + 1)) return;
-  const int j = (int)(i / (F + 1)), f = (int)(i % (F + 1));
+__global__ void __launch_bounds__(256) linear_bwd_w_kernel(const float* __restrict__ dlogits, const float* __restrict__ feat,
+                                                           float* __restrict__ dw, float* __restrict__ db, int N, int F, int J) {
+  // block = one class j and 64 consecutive features (feature index F stands for the bias); the four wavefronts take
+  // samples n = wave, wave + 4, ... and their sums are added in a fixed order
+  __shared__ float red[4][64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int j = blockIdx.y, f = blockIdx.x * 64 + lane;
+  const bool isw = f < F;
+  const float* fp = feat + (isw ? f : 0);
+  const float one = f == F ? 1.f : 0.f;
   float acc = 0.f;
-  if (f < F) {
-    for (int n = 0; n < N; ++n) acc = __fmaf_rn(dlogits[(int64_t)n * J + j], feat[(int64_t)n * F + f], acc);
-    dw[(int64_t)j * F + f] = acc;
-  } else {
-    for (int n = 0; n < N; ++n) acc += dlogits[(int64_t)n * J + j];
-    db[j] = acc;
+#pragma unroll 8
+  for (int n = wave; n < N; n += 4) {
+    const float v = isw ? fp[(int64_t)n * F] : one;
+    acc = __fmaf_rn(dlogits[(int64_t)n * J + j], v, acc);
+  }
+  red[wave][lane] = acc;
+  __syncthreads();
+  if (wave == 0) {
+    const float s = ((red[0][lane] + red[1][lane]) + red[2][lane]) + red[3][lane];
+    if (isw) dw[(int64_t)j * F + f] = s;
+    else if (f == F) db[j] = s;
   }
 }
 
@@ -124,14 +138,14 @@ void launch_head_fwd(hipStream_t st, int dt, const void* x, int N, int HW, int C
   if (dt == DT_F32) hipLaunchKernelGGL(head_feat_kernel<float>, dim3(N), dim3(256), 0, st, (const float*)x, feat, HW, C, gap);
   else if (dt == DT_BF16) hipLaunchKernelGGL(head_feat_kernel<bf16_t>, dim3(N), dim3(256), 0, st, (const bf16_t*)x, feat, HW, C, gap);
   else hipLaunchKernelGGL(head_feat_kernel<f16_t>, dim3(N), dim3(256), 0, st, (const f16_t*)x, feat, HW, C, gap);
-  hipLaunchKernelGGL(linear_fwd_kernel, dim3(ceil_div((int64_t)N * J, 128)), dim3(128), 0, st, feat, w, b, logits, N, F, J);
+  hipLaunchKernelGGL(linear_fwd_kernel, dim3(ceil_div((int64_t)N * J, 4)), dim3(256), 0, st, feat, w, b, logits, N, F, J);
   hipLaunchKernelGGL(softmax_ce_kernel, dim3(ceil_div(N, 64)), dim3(64), 0, st, logits, y, loss_n, dlogits, N, J, gscale, flags);
   hipLaunchKernelGGL(loss_mean_kernel, dim3(1), dim3(256), 0, st, loss_n, N, loss_out);
 }
 
 void launch_head_bwd(hipStream_t st, int dt, const float* feat, const float* dlogits, const float* w, int N, int HW, int C,
                      int gap, int F, int J, float* dw, float* db, float* dfeat, void* dx) {
-  hipLaunchKernelGGL(linear_bwd_w_kernel, dim3(ceil_div((int64_t)J * (F + 1), 128)), dim3(128), 0, st, dlogits, feat, dw, db, N, F, J);
+  hipLaunchKernelGGL(linear_bwd_w_kernel, dim3(ceil_div(F + 1, 64), J), dim3(256), 0, st, dlogits, feat, dw, db, N, F, J);
   if (!dx) return;
   hipLaunchKernelGGL(linear_bwd_x_kernel, dim3(ceil_div((int64_t)N * F, 128)), dim3(128), 0, st, dlogits, w, dfeat, N, F, J);
   const int64_t total = (int64_t)N * HW * C;
