@@ -1117,12 +1117,14 @@ bool conv_mfma_wgrad_ok(int dt, const ConvGeom& g) {
 }
 
 // number of pixel chunks, from the layer shape only
+int g_wgrad_blocks = 1024;  // tuning constant (not part of the C ABI)
 int conv_mfma_wgrad_splits(int dt, const ConvGeom& g) {
+  if (conv_wgrad3x3_ok(dt, g)) return conv_wgrad3x3_splits(dt, g);
   const int depth = dt == DT_F32 ? 16 : 32;
   const int bm = g.K % 128 == 0 ? 128 : 64, bn = g.C % 128 == 0 ? 128 : 64;
   const int64_t tiles = (int64_t)(g.K / bm) * (g.C / bn) * g.R * g.S;
   const int64_t pixels = (int64_t)g.N * g.P * g.Q;
-  int64_t want = (1024 + tiles - 1) / tiles;                       // aim at ~1024 blocks
+  int64_t want = (g_wgrad_blocks + tiles / 2) / tiles;             // aim at about that many blocks
   const int64_t most = (pixels + 4 * depth - 1) / (4 * depth);     // at least four depth tiles per chunk
   if (want > most) want = most;
   if (want > 64) want = 64;
@@ -1148,23 +1150,55 @@ static void launch_wgrad_t(hipStream_t st, const void* x, const void* dz, float*
   else hipLaunchKernelGGL((conv_wgrad_kernel<T, 64, 64>), grid, block, 0, st, (const T*)x, (const T*)dz, dst, a);
 }
 
-__global__ void wgrad_reduce_kernel(const float* __restrict__ partial, float* __restrict__ out, int64_t n, int splits) {
-  const int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
-  if (i >= n) return;
-  v4f acc = *reinterpret_cast<const v4f*>(partial + i);
-  for (int s = 1; s < splits; ++s) acc += *reinterpret_cast<const v4f*>(partial + (int64_t)s * n + i);
-  *reinterpret_cast<v4f*>(out + i) = acc;
+// out[i] = sum over pixel ranges s of partial[s][i], in a fixed order: G groups of threads each add the ranges
+// s = g, g + G, ... for the same four outputs, then the G sums are added in group order.  G grows with the number
+// of ranges so that small weight tensors with many ranges still fill the chip.
+template <int G>
+__global__ void __launch_bounds__(256) wgrad_reduce_kernel(const float* __restrict__ partial, float* __restrict__ out, int64_t n,
+                                                           int splits) {
+  constexpr int QB = 256 / G;  // output quads per block
+  __shared__ v4f red[G > 1 ? 256 : 1];
+  const int ql = threadIdx.x % QB, sg = threadIdx.x / QB;
+  const int64_t i = ((int64_t)blockIdx.x * QB + ql) * 4;
+  const bool on = i < n;
+  v4f acc = {0.f, 0.f, 0.f, 0.f};
+  if (on) {
+#pragma unroll 4
+    for (int s = sg; s < splits; s += G) acc += *reinterpret_cast<const v4f*>(partial + (int64_t)s * n + i);
+  }
+  if constexpr (G > 1) {
+    red[threadIdx.x] = acc;
+    __syncthreads();
+    if (sg == 0 && on) {
+      v4f t = red[ql];
+#pragma unroll
+      for (int g = 1; g < G; ++g) t += red[g * QB + ql];
+      *reinterpret_cast<v4f*>(out + i) = t;
+    }
+  } else {
+    if (on) *reinterpret_cast<v4f*>(out + i) = acc;
+  }
+}
+
+static void launch_wgrad_reduce(hipStream_t st, const float* partial, float* out, int64_t n, int splits) {
+  const int64_t quads = n / 4;  // n is a multiple of 4 (C % 64 == 0)
+  if (splits >= 64 || (splits >= 16 && quads < 65536))
+    hipLaunchKernelGGL(wgrad_reduce_kernel<16>, dim3(ceil_div(quads, 16)), dim3(256), 0, st, partial, out, n, splits);
+  else if (splits >= 8)
+    hipLaunchKernelGGL(wgrad_reduce_kernel<4>, dim3(ceil_div(quads, 64)), dim3(256), 0, st, partial, out, n, splits);
+  else
+    hipLaunchKernelGGL(wgrad_reduce_kernel<1>, dim3(ceil_div(quads, 256)), dim3(256), 0, st, partial, out, n, splits);
 }
 
 void launch_conv_wgrad_mfma(hipStream_t st, int dt, const void* x, const void* dz, float* dw, float* partial, int splits,
                             const ConvGeom& g) {
   float* dst = splits > 1 ? partial : dw;
-  if (dt == DT_F32) launch_wgrad_t<float>(st, x, dz, dst, splits, g);
+  if (conv_wgrad3x3_ok(dt, g)) launch_conv_wgrad3x3(st, dt, x, dz, dst, g);  // splits == conv_wgrad3x3_splits(dt, g)
+  else if (dt == DT_F32) launch_wgrad_t<float>(st, x, dz, dst, splits, g);
   else if (dt == DT_BF16) launch_wgrad_t<bf16_t>(st, x, dz, dst, splits, g);
   else launch_wgrad_t<f16_t>(st, x, dz, dst, splits, g);
   if (splits > 1) {
-    const int64_t n = (int64_t)g.K * g.R * g.S * g.C;  // a multiple of 4 (C % 64 == 0)
-    hipLaunchKernelGGL(wgrad_reduce_kernel, dim3(ceil_div(n / 4, 256)), dim3(256), 0, st, partial, dw, n, splits);
+    launch_wgrad_reduce(st, partial, dw, (int64_t)g.K * g.R * g.S * g.C, splits);
   }
 }
 
