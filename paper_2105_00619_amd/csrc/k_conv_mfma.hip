@@ -361,6 +361,7 @@ struct PatchArgs {
   int TI, TR, TC, SR, SC, NPOS, TP;
   int tiles_r, tiles_c, NT;
   int relu;
+  int chunks_per_split;      // channel chunks per blockIdx.z (all of them when the depth is not split)
 };
 
 constexpr int PATCH_MAX_POS = 256;  // positions per sub-tile
@@ -368,7 +369,7 @@ constexpr int PATCH_MAX_POS = 256;  // positions per sub-tile
 template <class T, int BN, int MI, int SUBT>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, MI == 4 ? 1 : 2)))
 conv3x3_patch_kernel(const T* __restrict__ src, const T* __restrict__ wmat, const float* __restrict__ bias,
-                     const T* __restrict__ addend, T* __restrict__ out, PatchArgs a) {
+                     const T* __restrict__ addend, T* __restrict__ out, float* __restrict__ partial, PatchArgs a) {
   constexpr int ROWS = 64 * MI;              // pixel rows of the block
   constexpr int TPC = ROWS / SUBT;           // rows (pixel capacity) per sub-tile
   constexpr int NSLOT = 4 * SUBT;            // 16-byte patch pieces per thread and channel chunk
@@ -425,7 +426,10 @@ conv3x3_patch_kernel(const T* __restrict__ src, const T* __restrict__ wmat, cons
   }
   __syncthreads();
 
-  const int nchunks = srcC / CCE;
+  // channel chunks of this block: all of them, or the range of blockIdx.z (raw sums go to `partial`, a second
+  // kernel adds the ranges in order and applies the epilogue)
+  const int cb = blockIdx.z * a.chunks_per_split;
+  const int ce = cb + a.chunks_per_split < srcC / CCE ? cb + a.chunks_per_split : srcC / CCE;
   const int Kg = 9 * srcC;
 
   // ---- loaders ---------------------------------------------------------------------------------------------------
@@ -475,9 +479,9 @@ conv3x3_patch_kernel(const T* __restrict__ src, const T* __restrict__ wmat, cons
 
   // ---- prologue -----------------------------------------------------------------------------------------------
 #pragma unroll
-  for (int sl = 0; sl < NSLOT; ++sl) PR[sl] = patch_load(sl, 0);
+  for (int sl = 0; sl < NSLOT; ++sl) PR[sl] = patch_load(sl, cb);
 #pragma unroll
-  for (int t = 0; t < 9; ++t) B_LOAD(t, 0);
+  for (int t = 0; t < 9; ++t) B_LOAD(t, cb);
 #pragma unroll
   for (int sl = 0; sl < NSLOT; ++sl) patch_store(sl, 0, PR[sl]);
   B_STORE(0, 0);
@@ -511,7 +515,7 @@ conv3x3_patch_kernel(const T* __restrict__ src, const T* __restrict__ wmat, cons
   // one channel chunk = nine taps; LAST = no chunk follows (no patch prefetch, weight requests stop at the end)
   auto chunk_body = [&](auto LAST, int chunk) {
     constexpr bool last = decltype(LAST)::value != 0;
-    const int pbuf = chunk & 1;
+    const int pbuf = (chunk - cb) & 1;
     const T* pcur = patch + pbuf * SUBT * PATCH_MAX_POS * PITCH;
     const T* pnxt = patch + (pbuf ^ 1) * SUBT * PATCH_MAX_POS * PITCH;
 #pragma unroll
@@ -566,8 +570,8 @@ conv3x3_patch_kernel(const T* __restrict__ src, const T* __restrict__ wmat, cons
       __syncthreads();
     }
   };
-  for (int chunk = 0; chunk + 1 < nchunks; ++chunk) chunk_body(IC<0>{}, chunk);
-  chunk_body(IC<1>{}, nchunks - 1);
+  for (int chunk = cb; chunk + 1 < ce; ++chunk) chunk_body(IC<0>{}, chunk);
+  chunk_body(IC<1>{}, ce - 1);
 
   // ---- epilogue ---------------------------------------------------------------------------------------------------
   // The accumulators go through LDS (the patch buffers are free now), the rows of one wavefront pair at a time, as
@@ -602,6 +606,12 @@ conv3x3_patch_kernel(const T* __restrict__ src, const T* __restrict__ wmat, cons
           const v4f x1 = *reinterpret_cast<const v4f*>(&ep[row * EP_PITCH + c8 + 4]);
           float v[8] = {x0[0], x0[1], x0[2], x0[3], x1[0], x1[1], x1[2], x1[3]};
           const int col = n0c + c8;
+          if (partial) {
+            float* dst = partial + (int64_t)blockIdx.z * ((int64_t)a.N * a.dstH * a.dstW * a.Ng) + ro + col;
+            *reinterpret_cast<v4f*>(dst) = x0;
+            *reinterpret_cast<v4f*>(dst + 4) = x1;
+            continue;
+          }
           if (bias) {
 #pragma unroll
             for (int k = 0; k < 8; ++k) v[k] += bias[col + k];
@@ -625,6 +635,26 @@ conv3x3_patch_kernel(const T* __restrict__ src, const T* __restrict__ wmat, cons
 
 #undef B_LOAD
 #undef B_STORE
+
+template <class T>
+__global__ void __launch_bounds__(256) splitk_epilogue_kernel(const float* __restrict__ partial, int splits, int64_t n, int Ng,
+                                                              const float* __restrict__ bias, const T* __restrict__ addend,
+                                                              T* __restrict__ out, int relu) {
+  const int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
+  if (i >= n) return;
+  v4f acc = *reinterpret_cast<const v4f*>(partial + i);
+  for (int z = 1; z < splits; ++z) acc += *reinterpret_cast<const v4f*>(partial + (int64_t)z * n + i);
+  const int col = (int)(i % Ng);
+  float r[4];
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    float v = acc[e];
+    if (bias) v += bias[col + e];
+    if (addend) v += to_f32(addend[i + e]);
+    r[e] = relu ? fmaxf(v, 0.f) : v;
+  }
+  store_f32<T, 4>(out + i, r);
+}
 
 template <class T> constexpr size_t patch_smem_bytes(int bn, int subt) {
   return (size_t)(2 * subt * PATCH_MAX_POS + 3 * bn) * (Frag<T>::BK + 16 / sizeof(T)) * sizeof(T) + subt * PATCH_MAX_POS * 8 +
@@ -652,16 +682,17 @@ static bool patch_geometry(int N, int dstH, int dstW, int cap, PatchArgs& a) {
 // Block shapes of the patch kernel, largest first: {MI, SUBT, widest BN}.  The first one that gives the chip
 // `g_patch_fill` blocks is taken, else the one with the most blocks if that reaches `g_patch_min_blocks`
 // (shape-only rule, so the choice is the same on every run).
-struct PatchShape { int mi, subt, bn; };
+struct PatchShape { int mi, subt, bn, splits; };
 int g_patch_min_blocks = 96;   // tuning constants (not part of the C ABI)
 int g_patch_fill = 200;
 int g_patch_shapes = 0xf;      // bit i: candidate i allowed
+int g_patch_split = 1;         // allow the depth split
 static bool patch_pick(int dt, int N, int dstH, int dstW, int srcC, int Ng, int R, int S, int stride, PatchShape& shape,
                        PatchArgs& geo) {
   if (R != 3 || S != 3 || stride != 1) return false;
   if (srcC % (dt == DT_F32 ? 16 : 32) != 0 || Ng % 64 != 0) return false;
   const int wide = Ng % 128 == 0 ? 128 : 64;
-  const PatchShape cand[4] = {{4, 2, wide}, {2, 1, wide}, {2, 1, 64}, {1, 1, 64}};
+  const PatchShape cand[4] = {{4, 2, wide, 1}, {2, 1, wide, 1}, {2, 1, 64, 1}, {1, 1, 64, 1}};
   int best = -1;
   int64_t best_blocks = 0;
   PatchArgs best_geo{};
@@ -680,13 +711,24 @@ static bool patch_pick(int dt, int N, int dstH, int dstW, int srcC, int Ng, int 
   if (best < 0 || best_blocks < g_patch_min_blocks) return false;
   shape = cand[best];
   geo = best_geo;
+  // still short of a block per CU: split the channel chunks over blockIdx.z (at least four chunks per range)
+  const int nchunks = srcC / (dt == DT_F32 ? 16 : 32);
+  int splits = 1;
+  if (g_patch_split && best_blocks < g_patch_fill) {
+    splits = (int)((256 + best_blocks - 1) / best_blocks);
+    if (splits > nchunks / 4) splits = nchunks / 4;
+    if (splits > 4) splits = 4;
+    if (splits < 1) splits = 1;
+  }
+  geo.chunks_per_split = (nchunks + splits - 1) / splits;
+  shape.splits = (nchunks + geo.chunks_per_split - 1) / geo.chunks_per_split;  // no empty ranges
   return true;
 }
 
 template <class T, int BN, int MI, int SUBT>
 static void launch_patch_v(hipStream_t st, const void* src, const void* wmat, const float* bias, const void* addend, void* out,
-                           const PatchArgs& a) {
-  dim3 grid((a.NT + SUBT - 1) / SUBT, a.Ng / BN), block(256);
+                           float* partial, int splits, const PatchArgs& a) {
+  dim3 grid((a.NT + SUBT - 1) / SUBT, a.Ng / BN, splits), block(256);
   constexpr size_t sm = patch_smem_bytes<T>(BN, SUBT);
   static bool attr_done = false;
   if (!attr_done) {
@@ -694,48 +736,34 @@ static void launch_patch_v(hipStream_t st, const void* src, const void* wmat, co
     attr_done = true;
   }
   hipLaunchKernelGGL((conv3x3_patch_kernel<T, BN, MI, SUBT>), grid, block, sm, st, (const T*)src, (const T*)wmat, bias,
-                     (const T*)addend, (T*)out, a);
+                     (const T*)addend, (T*)out, splits > 1 ? partial : (float*)nullptr, a);
 }
 
 template <class T>
 static void launch_patch_t(hipStream_t st, const void* src, const void* wmat, const float* bias, const void* addend, void* out,
-                           const PatchShape& v, const PatchArgs& a) {
+                           float* partial, const PatchShape& v, const PatchArgs& a) {
+  const int sp = v.splits;
   if (v.mi == 4) {
-    if (v.bn == 128) launch_patch_v<T, 128, 4, 2>(st, src, wmat, bias, addend, out, a);
-    else launch_patch_v<T, 64, 4, 2>(st, src, wmat, bias, addend, out, a);
+    if (v.bn == 128) launch_patch_v<T, 128, 4, 2>(st, src, wmat, bias, addend, out, partial, sp, a);
+    else launch_patch_v<T, 64, 4, 2>(st, src, wmat, bias, addend, out, partial, sp, a);
   } else if (v.mi == 2) {
-    if (v.bn == 128) launch_patch_v<T, 128, 2, 1>(st, src, wmat, bias, addend, out, a);
-    else launch_patch_v<T, 64, 2, 1>(st, src, wmat, bias, addend, out, a);
+    if (v.bn == 128) launch_patch_v<T, 128, 2, 1>(st, src, wmat, bias, addend, out, partial, sp, a);
+    else launch_patch_v<T, 64, 2, 1>(st, src, wmat, bias, addend, out, partial, sp, a);
   } else {
-    launch_patch_v<T, 64, 1, 1>(st, src, wmat, bias, addend, out, a);
+    launch_patch_v<T, 64, 1, 1>(st, src, wmat, bias, addend, out, partial, sp, a);
+  }
+  if (sp > 1) {
+    const int64_t n = (int64_t)a.N * a.dstH * a.dstW * a.Ng;  // a multiple of 4: Ng % 64 == 0
+    hipLaunchKernelGGL(splitk_epilogue_kernel<T>, dim3(ceil_div(n / 4, 256)), dim3(256), 0, st, partial, sp, n, a.Ng, bias,
+                       (const T*)addend, (T*)out, a.relu);
   }
 }
 
 static void launch_patch(hipStream_t st, int dt, const void* src, const void* wmat, const float* bias, const void* addend, void* out,
-                         const PatchShape& v, const PatchArgs& a) {
-  if (dt == DT_F32) launch_patch_t<float>(st, src, wmat, bias, addend, out, v, a);
-  else if (dt == DT_BF16) launch_patch_t<bf16_t>(st, src, wmat, bias, addend, out, v, a);
-  else launch_patch_t<f16_t>(st, src, wmat, bias, addend, out, v, a);
-}
-
-template <class T>
-__global__ void __launch_bounds__(256) splitk_epilogue_kernel(const float* __restrict__ partial, int splits, int64_t n, int Ng,
-                                                              const float* __restrict__ bias, const T* __restrict__ addend,
-                                                              T* __restrict__ out, int relu) {
-  const int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
-  if (i >= n) return;
-  v4f acc = *reinterpret_cast<const v4f*>(partial + i);
-  for (int z = 1; z < splits; ++z) acc += *reinterpret_cast<const v4f*>(partial + (int64_t)z * n + i);
-  const int col = (int)(i % Ng);
-  float r[4];
-#pragma unroll
-  for (int e = 0; e < 4; ++e) {
-    float v = acc[e];
-    if (bias) v += bias[col + e];
-    if (addend) v += to_f32(addend[i + e]);
-    r[e] = relu ? fmaxf(v, 0.f) : v;
-  }
-  store_f32<T, 4>(out + i, r);
+                         float* partial, const PatchShape& v, const PatchArgs& a) {
+  if (dt == DT_F32) launch_patch_t<float>(st, src, wmat, bias, addend, out, partial, v, a);
+  else if (dt == DT_BF16) launch_patch_t<bf16_t>(st, src, wmat, bias, addend, out, partial, v, a);
+  else launch_patch_t<f16_t>(st, src, wmat, bias, addend, out, partial, v, a);
 }
 
 int g_igemm_spread = 1;                         // tuning switch (not part of the C ABI)
@@ -806,12 +834,12 @@ static int igemm_splits(int dt, int64_t M, int Ng, int Kg) {
 }
 int conv_mfma_fwd_splits(int dt, const ConvGeom& g) {
   PatchShape v; PatchArgs pa{};
-  if (patch_pick(dt, g.N, g.P, g.Q, g.C, g.K, g.R, g.S, g.stride, v, pa)) return 1;
+  if (patch_pick(dt, g.N, g.P, g.Q, g.C, g.K, g.R, g.S, g.stride, v, pa)) return v.splits;
   return igemm_splits(dt, (int64_t)g.N * g.P * g.Q, g.K, g.R * g.S * g.C);
 }
 int conv_mfma_dgrad_splits(int dt, const ConvGeom& g) {
   PatchShape v; PatchArgs pa{};
-  if (patch_pick(dt, g.N, g.H, g.W, g.K, g.C, g.R, g.S, g.stride, v, pa)) return 1;
+  if (patch_pick(dt, g.N, g.H, g.W, g.K, g.C, g.R, g.S, g.stride, v, pa)) return v.splits;
   return igemm_splits(dt, (int64_t)g.N * g.H * g.W, g.C, g.R * g.S * g.K);
 }
 
@@ -830,7 +858,7 @@ void launch_conv_fwd_mfma(hipStream_t st, int dt, const void* x, const void* w, 
   if (patch_pick(dt, g.N, g.P, g.Q, g.C, g.K, g.R, g.S, g.stride, pv, pa)) {
     pa.N = g.N; pa.srcH = g.H; pa.srcW = g.W; pa.srcC = g.C; pa.dstH = g.P; pa.dstW = g.Q; pa.Ng = g.K;
     pa.pad = g.pad; pa.flip = 0; pa.relu = relu;
-    launch_patch(st, dt, x, w, bias, nullptr, out, pv, pa);
+    launch_patch(st, dt, x, w, bias, nullptr, out, partial, pv, pa);
     return;
   }
   IGemmArgs a{g.H, g.W, g.C, g.P, g.Q, g.N * g.P * g.Q, g.K, g.R * g.S * g.C, g.R, g.S, g.stride, g.pad, relu, 0};
@@ -844,7 +872,7 @@ void launch_conv_dgrad_mfma(hipStream_t st, int dt, const void* dz, const void* 
   if (patch_pick(dt, g.N, g.H, g.W, g.K, g.C, g.R, g.S, g.stride, pv, pa)) {
     pa.N = g.N; pa.srcH = g.P; pa.srcW = g.Q; pa.srcC = g.K; pa.dstH = g.H; pa.dstW = g.W; pa.Ng = g.C;
     pa.pad = g.R - 1 - g.pad; pa.flip = 1; pa.relu = 0;
-    launch_patch(st, dt, dz, wt, nullptr, addend, dx, pv, pa);
+    launch_patch(st, dt, dz, wt, nullptr, addend, dx, partial, pv, pa);
     return;
   }
   IGemmArgs a{g.P, g.Q, g.K, g.H, g.W, g.N * g.H * g.W, g.C, g.R * g.S * g.K, g.R, g.S, g.stride, g.pad, 0, 0};

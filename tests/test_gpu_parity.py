@@ -78,6 +78,8 @@ LAYER_NETS = {
     "patch_wide_128_at16": (128, 16, 208, [W.conv(128, 128), W.conv(128, 128), W.gap_linear_ce(128, 10)]),
     "patch_half_128_at16": (128, 16, 104, [W.conv(128, 128), W.conv(128, 128), W.gap_linear_ce(128, 10)]),
     "patch_wide_64_at32": (64, 32, 52, [W.conv(64, 64), W.conv(64, 64), W.gap_linear_ce(64, 10)]),
+    # few pixels, many channels: that kernel with its channel chunks split over two blocks
+    "patch_split_512_at4": (512, 4, 64, [W.conv(512, 512), W.conv(512, 512), W.gap_linear_ce(512, 10)]),
 }
 
 
