@@ -51,10 +51,13 @@ static int hip_fail(const optorch_seq_t* h, hipError_t e, const char* what) {
 
 // refresh the transposed weight copies the data-gradient GEMMs read (after every change of the master weights)
 static void refresh_transposed_weights(optorch_seq_t* h) {
+  std::vector<TransposeJob> jobs;
   for (const FOp& f : h->plan.fops)
     if (f.kind == F_CONV && f.dgrad_algo == ALGO_MFMA && h->plan.tensors[f.x].needs_grad)
-      launch_weight_transpose(h->stream, h->dt, (const float*)(h->pbase + h->off_w) + f.w_off,
-                              h->pbase + h->off_wt + (uint64_t)f.w_off * h->plan.esize, f.K, f.R * f.S, f.C);
+      jobs.push_back(TransposeJob{f.w_off, f.K, f.R * f.S, f.C, 0});
+  if (!jobs.empty())
+    launch_weight_transposes(h->stream, h->dt, (const float*)(h->pbase + h->off_w), h->pbase + h->off_wt, jobs.data(),
+                             (int)jobs.size());
 }
 
 extern "C" int optorch_seq_create(const optorch_unit_t* units, int32_t n_units, const optorch_seq_config_t* cfg,

@@ -117,17 +117,26 @@ template <class T, int C>
 __global__ void __launch_bounds__(256) conv_fwd_smallc_kernel(const T* __restrict__ x, const T* __restrict__ w,
                                                               const float* __restrict__ bias, T* __restrict__ out,
                                                               ConvGeom g, int relu) {
+  // block = 32 pixels x 64 output channels (blockIdx.y selects the group of 64); thread = one pixel x 8 channels,
+  // the 8 threads of a pixel next to each other so that a wavefront writes 8 whole rows of 64 channels
   constexpr int RSC = 9 * C;  // 3x3 filter
-  __shared__ float ws[8 * RSC];
-  const int kg = blockIdx.y;
-  for (int i = threadIdx.x; i < 8 * RSC; i += 256) ws[i] = to_f32(w[(int64_t)kg * 8 * RSC + i]);
+  __shared__ __attribute__((aligned(16))) float ws[RSC * 64];  // [e][channel]
+  const int kbase = blockIdx.y * 64;
+  const int kn = g.K - kbase < 64 ? g.K - kbase : 64;
+  for (int i = threadIdx.x; i < RSC * 64; i += 256) {
+    const int e = i >> 6, k = i & 63;
+    ws[i] = k < kn ? to_f32(w[(int64_t)(kbase + k) * RSC + e]) : 0.f;
+  }
   __syncthreads();
-  const int64_t m = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (m >= (int64_t)g.N * g.P * g.Q) return;
+  const int grp = threadIdx.x & 7;
+  const int64_t m = (int64_t)blockIdx.x * 32 + (threadIdx.x >> 3);
+  if (m >= (int64_t)g.N * g.P * g.Q || grp * 8 >= kn) return;
   const int q = (int)(m % g.Q);
   const int64_t t = m / g.Q;
   const int p = (int)(t % g.P), n = (int)(t / g.P);
-  float xin[RSC];
+  float acc[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) acc[j] = 0.f;
 #pragma unroll
   for (int r = 0; r < 3; ++r) {
     const int ih = p * g.stride + r - g.pad;
@@ -137,19 +146,21 @@ __global__ void __launch_bounds__(256) conv_fwd_smallc_kernel(const T* __restric
       const bool ok = ih >= 0 && ih < g.H && iw >= 0 && iw < g.W;
       const T* xp = x + (((int64_t)n * g.H + (ok ? ih : 0)) * g.W + (ok ? iw : 0)) * C;
 #pragma unroll
-      for (int c = 0; c < C; ++c) xin[(r * 3 + s) * C + c] = ok ? to_f32(xp[c]) : 0.f;
+      for (int c = 0; c < C; ++c) {
+        const float xv = ok ? to_f32(xp[c]) : 0.f;
+        const float* wp = &ws[((r * 3 + s) * C + c) * 64 + grp * 8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[j] = __fmaf_rn(xv, wp[j], acc[j]);
+      }
     }
   }
-  float acc[8];
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
-    float a = 0.f;
-#pragma unroll
-    for (int i = 0; i < RSC; ++i) a = __fmaf_rn(xin[i], ws[j * RSC + i], a);
-    if (bias) a += bias[kg * 8 + j];
+    float a = acc[j];
+    if (bias) a += bias[kbase + grp * 8 + j];
     acc[j] = relu ? fmaxf(a, 0.f) : a;
   }
-  store_f32<T, 8>(out + m * g.K + kg * 8, acc);
+  store_f32<T, 8>(out + m * g.K + kbase + grp * 8, acc);
 }
 
 // Weight gradient for few input channels (the network stem):  dw[k][e] = sum over pixels of dz[px][k] * col[px][e],
@@ -326,7 +337,7 @@ int conv_smallc_wgrad_splits(const ConvGeom& g) {
 template <class T>
 static void launch_fwd_smallc_t(hipStream_t st, const void* x, const void* w, const float* bias, void* out, const ConvGeom& g,
                                 int relu) {
-  dim3 grid(ceil_div((int64_t)g.N * g.P * g.Q, 256), g.K / 8), block(256);
+  dim3 grid(ceil_div((int64_t)g.N * g.P * g.Q, 32), ceil_div(g.K, 64)), block(256);
   switch (g.C) {
     case 1: hipLaunchKernelGGL((conv_fwd_smallc_kernel<T, 1>), grid, block, 0, st, (const T*)x, (const T*)w, bias, (T*)out, g, relu); break;
     case 2: hipLaunchKernelGGL((conv_fwd_smallc_kernel<T, 2>), grid, block, 0, st, (const T*)x, (const T*)w, bias, (T*)out, g, relu); break;

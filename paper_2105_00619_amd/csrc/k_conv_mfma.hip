@@ -879,25 +879,52 @@ void launch_conv_dgrad_mfma(hipStream_t st, int dt, const void* dz, const void* 
   launch_igemm<IG_DGRAD>(st, dt, dz, wt, nullptr, addend, dx, partial, splits, a);
 }
 
-// (C_out, R*S, C_in) fp32 master weights -> (C_in, R*S, C_out) in the compute type
+// (C_out, R*S, C_in) fp32 master weights -> (C_in, R*S, C_out) in the compute type, for all layers of a batch in one
+// launch: a block transposes one 32x32 (C_out x C_in) tile of one filter tap through LDS, so that both the reads
+// (along C_in) and the writes (along C_out) are contiguous.
 template <class T>
-__global__ void weight_transpose_kernel(const float* __restrict__ w, T* __restrict__ wt, int K, int RS, int C) {
-  const int64_t total = (int64_t)K * RS * C;
-  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= total) return;
-  const int k = (int)(i % K);
-  const int64_t t = i / K;
-  const int rs = (int)(t % RS);
-  const int c = (int)(t / RS);
-  wt[i] = from_f32<T>(w[((int64_t)k * RS + rs) * C + c]);
+__global__ void __launch_bounds__(256) weight_transpose_kernel(const float* __restrict__ wbase, T* __restrict__ wtbase,
+                                                               TransposeBatch b) {
+  __shared__ float tile[32][33];
+  int j = 0;
+  while (j + 1 < b.n && (int)blockIdx.x >= b.job[j + 1].first_block) ++j;
+  const TransposeJob jb = b.job[j];
+  const int tiles_k = (jb.K + 31) / 32, tiles_c = (jb.C + 31) / 32;
+  const int local = blockIdx.x - jb.first_block;
+  const int tc = local % tiles_c, t2 = local / tiles_c;
+  const int tk = t2 % tiles_k, rs = t2 / tiles_k;
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+  const float* w = wbase + jb.w_off;
+  T* wt = wtbase + jb.w_off;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int k = tk * 32 + ty + i * 8, c = tc * 32 + tx;
+    if (k < jb.K && c < jb.C) tile[ty + i * 8][tx] = w[((int64_t)k * jb.RS + rs) * jb.C + c];
+  }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int c = tc * 32 + ty + i * 8, k = tk * 32 + tx;
+    if (c < jb.C && k < jb.K) wt[((int64_t)c * jb.RS + rs) * jb.K + k] = from_f32<T>(tile[tx][ty + i * 8]);
+  }
 }
 
-void launch_weight_transpose(hipStream_t st, int dt, const float* w, void* wt, int K, int RS, int C) {
-  const int64_t total = (int64_t)K * RS * C;
-  dim3 grid(ceil_div(total, 256)), block(256);
-  if (dt == DT_F32) hipLaunchKernelGGL(weight_transpose_kernel<float>, grid, block, 0, st, w, (float*)wt, K, RS, C);
-  else if (dt == DT_BF16) hipLaunchKernelGGL(weight_transpose_kernel<bf16_t>, grid, block, 0, st, w, (bf16_t*)wt, K, RS, C);
-  else hipLaunchKernelGGL(weight_transpose_kernel<f16_t>, grid, block, 0, st, w, (f16_t*)wt, K, RS, C);
+// jobs: first_block is filled in here
+void launch_weight_transposes(hipStream_t st, int dt, const float* wbase, void* wtbase, const TransposeJob* jobs, int njobs) {
+  for (int j0 = 0; j0 < njobs; j0 += TransposeBatch::MAX_JOBS) {
+    TransposeBatch b{};
+    b.n = njobs - j0 < TransposeBatch::MAX_JOBS ? njobs - j0 : TransposeBatch::MAX_JOBS;
+    int blocks = 0;
+    for (int j = 0; j < b.n; ++j) {
+      b.job[j] = jobs[j0 + j];
+      b.job[j].first_block = blocks;
+      blocks += b.job[j].RS * ((b.job[j].K + 31) / 32) * ((b.job[j].C + 31) / 32);
+    }
+    if (blocks == 0) continue;
+    if (dt == DT_F32) hipLaunchKernelGGL(weight_transpose_kernel<float>, dim3(blocks), dim3(256), 0, st, wbase, (float*)wtbase, b);
+    else if (dt == DT_BF16) hipLaunchKernelGGL(weight_transpose_kernel<bf16_t>, dim3(blocks), dim3(256), 0, st, wbase, (bf16_t*)wtbase, b);
+    else hipLaunchKernelGGL(weight_transpose_kernel<f16_t>, dim3(blocks), dim3(256), 0, st, wbase, (f16_t*)wtbase, b);
+  }
 }
 
 // ------------------------------------------------------------------------------------------------------------

@@ -62,7 +62,11 @@ bool conv_mfma_wgrad_ok(int dt, const ConvGeom& g);
 int conv_mfma_wgrad_splits(int dt, const ConvGeom& g);
 void launch_conv_wgrad_mfma(hipStream_t st, int dt, const void* x, const void* dz, float* dw, float* partial, int splits,
                             const ConvGeom& g);
-void launch_weight_transpose(hipStream_t st, int dt, const float* w, void* wt, int K, int RS, int C);
+// Transposed weight copies for the data-gradient GEMMs, all layers in one launch (per 48 layers).  w_off: element
+// offset of the layer's weights in the flat parameter vector (the same offset is used in the transposed copy).
+struct TransposeJob { int64_t w_off; int K, RS, C, first_block; };
+struct TransposeBatch { static constexpr int MAX_JOBS = 48; TransposeJob job[MAX_JOBS]; int n; };
+void launch_weight_transposes(hipStream_t st, int dt, const float* wbase, void* wtbase, const TransposeJob* jobs, int njobs);
 
 void launch_step_init(hipStream_t st, int* flags);
 void launch_optim(hipStream_t st, int dt, float* w, float* v, const float* g, void* w16, float* gout, int64_t n, float lr,
