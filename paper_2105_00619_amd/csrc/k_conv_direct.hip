@@ -116,51 +116,86 @@ constexpr int SMALLC_MAX = 36;
 template <class T, int C>
 __global__ void __launch_bounds__(256) conv_fwd_smallc_kernel(const T* __restrict__ x, const T* __restrict__ w,
                                                               const float* __restrict__ bias, T* __restrict__ out,
-                                                              ConvGeom g, int relu) {
-  // block = 32 pixels x 64 output channels (blockIdx.y selects the group of 64); thread = one pixel x 8 channels,
-  // the 8 threads of a pixel next to each other so that a wavefront writes 8 whole rows of 64 channels
+                                                              ConvGeom g, int relu, FastDiv divQ, FastDiv divPQ) {
+  // block = 128 pixels x 64 output channels (blockIdx.y selects the group of 64); thread = 4 pixels x 8 channels,
+  // the 8 threads of a pixel next to each other so that a wavefront writes 8 whole rows of 64 channels, and every
+  // weight read from LDS serves four pixels.  The 8 threads of a pixel share the loading of its R*S*C inputs
+  // through LDS (vector-memory instructions, not bytes, bound this kernel otherwise).
   constexpr int RSC = 9 * C;  // 3x3 filter
-  __shared__ __attribute__((aligned(16))) float ws[RSC * 64];  // [e][channel]
+  constexpr int XP = (RSC + 3) / 4 * 4;
+  constexpr int PPT = 4;
+  __shared__ __attribute__((aligned(16))) float ws[RSC * 64];        // [e][channel]
+  __shared__ __attribute__((aligned(16))) float xs[32 * PPT * XP];   // [pixel of the block][e]
   const int kbase = blockIdx.y * 64;
   const int kn = g.K - kbase < 64 ? g.K - kbase : 64;
   for (int i = threadIdx.x; i < RSC * 64; i += 256) {
-    const int e = i >> 6, k = i & 63;
-    ws[i] = k < kn ? to_f32(w[(int64_t)(kbase + k) * RSC + e]) : 0.f;
+    const int k = i / RSC, e = i - k * RSC;  // consecutive threads read consecutive weights
+    ws[e * 64 + k] = k < kn ? to_f32(w[(kbase + k) * RSC + e]) : 0.f;
+  }
+  const int grp = threadIdx.x & 7, slot = threadIdx.x >> 3;
+  const int pixels = g.N * g.P * g.Q;  // < 2^24 (checked by the launcher), so 32-bit index arithmetic throughout
+  const int H = g.H, W = g.W, cstride = g.stride, pad = g.pad;
+  int m[PPT];
+  // this thread's input elements e = grp + 8u of each of its pixels: filter offsets and channel are pixel-independent
+  int er[(RSC + 7) / 8], es[(RSC + 7) / 8], ec[(RSC + 7) / 8];
+#pragma unroll
+  for (int u = 0; u < (RSC + 7) / 8; ++u) {
+    const int e = grp + 8 * u < RSC ? grp + 8 * u : RSC - 1;
+    const int tap = e / C;
+    ec[u] = e - tap * C; er[u] = tap / 3 - pad; es[u] = tap % 3 - pad;
+  }
+#pragma unroll
+  for (int i = 0; i < PPT; ++i) {
+    m[i] = blockIdx.x * (32 * PPT) + slot + 32 * i;
+    const uint32_t mm = m[i] < pixels ? (uint32_t)m[i] : 0u;
+    const uint32_t n = divPQ.div(mm), rem = mm - n * divPQ.d;
+    const uint32_t p = divQ.div(rem), q = rem - p * divQ.d;
+    const int ih0 = (int)p * cstride, iw0 = (int)q * cstride, nbase = (int)n * H;
+#pragma unroll
+    for (int u = 0; u < (RSC + 7) / 8; ++u) {
+      const int ih = ih0 + er[u], iw = iw0 + es[u];
+      const bool ok = ih >= 0 && ih < H && iw >= 0 && iw < W;
+      const float v = to_f32(x[ok ? ((nbase + ih) * W + iw) * C + ec[u] : 0]);
+      if (grp + 8 * u < RSC) xs[(slot + 32 * i) * XP + grp + 8 * u] = ok ? v : 0.f;
+    }
   }
   __syncthreads();
-  const int grp = threadIdx.x & 7;
-  const int64_t m = (int64_t)blockIdx.x * 32 + (threadIdx.x >> 3);
-  if (m >= (int64_t)g.N * g.P * g.Q || grp * 8 >= kn) return;
-  const int q = (int)(m % g.Q);
-  const int64_t t = m / g.Q;
-  const int p = (int)(t % g.P), n = (int)(t / g.P);
-  float acc[8];
+  float acc[PPT][8];
 #pragma unroll
-  for (int j = 0; j < 8; ++j) acc[j] = 0.f;
+  for (int i = 0; i < PPT; ++i)
 #pragma unroll
-  for (int r = 0; r < 3; ++r) {
-    const int ih = p * g.stride + r - g.pad;
+    for (int j = 0; j < 8; ++j) acc[i][j] = 0.f;
+  // one filter tap (C inputs) per iteration; not unrolled further: with all R*S*C steps visible the compiler
+  // hoists every LDS read to the top and parks the values in accumulation registers
+#pragma unroll 1
+  for (int tap = 0; tap < 9; ++tap) {
 #pragma unroll
-    for (int s = 0; s < 3; ++s) {
-      const int iw = q * g.stride + s - g.pad;
-      const bool ok = ih >= 0 && ih < g.H && iw >= 0 && iw < g.W;
-      const T* xp = x + (((int64_t)n * g.H + (ok ? ih : 0)) * g.W + (ok ? iw : 0)) * C;
+    for (int c = 0; c < C; ++c) {
+      const int e = tap * C + c;
+      const float* wp = &ws[e * 64 + grp * 8];
+      float wv[8];
 #pragma unroll
-      for (int c = 0; c < C; ++c) {
-        const float xv = ok ? to_f32(xp[c]) : 0.f;
-        const float* wp = &ws[((r * 3 + s) * C + c) * 64 + grp * 8];
+      for (int j = 0; j < 8; ++j) wv[j] = wp[j];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) acc[j] = __fmaf_rn(xv, wp[j], acc[j]);
+      for (int i = 0; i < PPT; ++i) {
+        const float xv = xs[(slot + 32 * i) * XP + e];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[i][j] = __fmaf_rn(xv, wv[j], acc[i][j]);
       }
     }
   }
+  if (grp * 8 >= kn) return;
 #pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    float a = acc[j];
-    if (bias) a += bias[kbase + grp * 8 + j];
-    acc[j] = relu ? fmaxf(a, 0.f) : a;
+  for (int i = 0; i < PPT; ++i) {
+    if (m[i] >= pixels) continue;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      float a = acc[i][j];
+      if (bias) a += bias[kbase + grp * 8 + j];
+      acc[i][j] = relu ? fmaxf(a, 0.f) : a;
+    }
+    store_f32<T, 8>(out + (int64_t)m[i] * g.K + kbase + grp * 8, acc[i]);
   }
-  store_f32<T, 8>(out + m * g.K + kbase + grp * 8, acc);
 }
 
 // Weight gradient for few input channels (the network stem):  dw[k][e] = sum over pixels of dz[px][k] * col[px][e],
@@ -323,7 +358,10 @@ __global__ void __launch_bounds__(256) wave_reduce_kernel(const float* __restric
   if ((threadIdx.x & 63) == 0) out[o] = v;
 }
 
-bool conv_smallc_fwd_ok(const ConvGeom& g) { return g.C <= 4 && g.R == 3 && g.S == 3 && g.K % 8 == 0; }
+bool conv_smallc_fwd_ok(const ConvGeom& g) {
+  return g.C <= 4 && g.R == 3 && g.S == 3 && g.K % 8 == 0 && (int64_t)g.N * g.P * g.Q < (1 << 24) &&
+         (int64_t)g.N * g.H * g.W * g.C < ((int64_t)1 << 31);
+}
 bool conv_smallc_wgrad_ok(const ConvGeom& g) {
   return g.C <= 4 && g.R * g.S * g.C <= SMALLC_MAX && g.K <= 64 && g.K % 8 == 0 && (int64_t)g.N * g.P * g.Q < (1 << 24) &&
          (int64_t)g.N * g.H * g.W * g.C < ((int64_t)1 << 31);
@@ -337,12 +375,13 @@ int conv_smallc_wgrad_splits(const ConvGeom& g) {
 template <class T>
 static void launch_fwd_smallc_t(hipStream_t st, const void* x, const void* w, const float* bias, void* out, const ConvGeom& g,
                                 int relu) {
-  dim3 grid(ceil_div((int64_t)g.N * g.P * g.Q, 32), ceil_div(g.K, 64)), block(256);
+  dim3 grid(ceil_div((int64_t)g.N * g.P * g.Q, 128), ceil_div(g.K, 64)), block(256);
+  const FastDiv dq = make_fastdiv((uint32_t)g.Q), dpq = make_fastdiv((uint32_t)(g.P * g.Q));
   switch (g.C) {
-    case 1: hipLaunchKernelGGL((conv_fwd_smallc_kernel<T, 1>), grid, block, 0, st, (const T*)x, (const T*)w, bias, (T*)out, g, relu); break;
-    case 2: hipLaunchKernelGGL((conv_fwd_smallc_kernel<T, 2>), grid, block, 0, st, (const T*)x, (const T*)w, bias, (T*)out, g, relu); break;
-    case 3: hipLaunchKernelGGL((conv_fwd_smallc_kernel<T, 3>), grid, block, 0, st, (const T*)x, (const T*)w, bias, (T*)out, g, relu); break;
-    default: hipLaunchKernelGGL((conv_fwd_smallc_kernel<T, 4>), grid, block, 0, st, (const T*)x, (const T*)w, bias, (T*)out, g, relu); break;
+    case 1: hipLaunchKernelGGL((conv_fwd_smallc_kernel<T, 1>), grid, block, 0, st, (const T*)x, (const T*)w, bias, (T*)out, g, relu, dq, dpq); break;
+    case 2: hipLaunchKernelGGL((conv_fwd_smallc_kernel<T, 2>), grid, block, 0, st, (const T*)x, (const T*)w, bias, (T*)out, g, relu, dq, dpq); break;
+    case 3: hipLaunchKernelGGL((conv_fwd_smallc_kernel<T, 3>), grid, block, 0, st, (const T*)x, (const T*)w, bias, (T*)out, g, relu, dq, dpq); break;
+    default: hipLaunchKernelGGL((conv_fwd_smallc_kernel<T, 4>), grid, block, 0, st, (const T*)x, (const T*)w, bias, (T*)out, g, relu, dq, dpq); break;
   }
 }
 
