@@ -362,6 +362,7 @@ struct PatchArgs {
   int tiles_r, tiles_c, NT;
   int relu;
   int chunks_per_split;      // channel chunks per blockIdx.z (all of them when the depth is not split)
+  int row_pitch;             // bytes between staged patch rows in LDS (>= SC * 80, padded against bank conflicts)
 };
 
 constexpr int PATCH_MAX_POS = 256;  // positions per sub-tile
@@ -391,6 +392,7 @@ conv3x3_patch_kernel(const T* __restrict__ src, const T* __restrict__ wmat, cons
   const int n0c = blockIdx.y * BN;
   const int npos2 = SUBT * a.NPOS;
   const int srcC = a.srcC, flip = a.flip, SC = a.SC;
+  const int RPE = a.row_pitch / (int)sizeof(T);  // elements between staged patch rows
 
   // ---- address tables ------------------------------------------------------------------------------------------
   for (int e = tid; e < npos2; e += 256) {
@@ -418,7 +420,7 @@ conv3x3_patch_kernel(const T* __restrict__ src, const T* __restrict__ wmat, cons
       const int ci = tile % a.tiles_c, t2 = tile / a.tiles_c;
       const int ri = t2 % a.tiles_r, ii = t2 / a.tiles_r;
       const int n = ii * a.TI + ti, p = ri * a.TR + tr, q = ci * a.TC + tc;
-      ap = u * a.NPOS + (ti * a.SR + tr) * a.SC + tc;
+      ap = ((u * a.TI + ti) * a.SR + tr) * RPE + tc * PITCH;  // LDS element offset of tap (0,0)
       if (n < a.N && p < a.dstH && q < a.dstW) off = (((int64_t)n * a.dstH + p) * a.dstW + q) * a.Ng;
     }
     out_off[m2] = off;
@@ -441,25 +443,28 @@ conv3x3_patch_kernel(const T* __restrict__ src, const T* __restrict__ wmat, cons
   // patch pieces of this thread: slot sl covers the 16-byte piece idx = sl*256 + tid.  Loads are unconditional
   // (pieces outside the image read the tensor's first pixel) and are zeroed when written to LDS.
   const T* pptr[NSLOT];
+  int pdst[NSLOT];  // LDS element offset of the piece within a patch buffer
   unsigned pvalid = 0u, pstore = 0u;
 #pragma unroll
   for (int sl = 0; sl < NSLOT; ++sl) {
     const int idx = sl * 256 + tid;
     const int pos = idx >> 2, v = idx & 3;
     int64_t off = 0;
+    int dst = 0;
     if (pos < npos2) {
       pstore |= 1u << sl;
       const int64_t o = src_off[pos];
       if (o >= 0) { off = o; pvalid |= 1u << sl; }
+      const int prow = pos / SC;
+      dst = prow * RPE + (pos - prow * SC) * PITCH + v * EV;
     }
     pptr[sl] = src + off + v * EV;
+    pdst[sl] = dst;
   }
   auto patch_load = [&](int slot, int chunk) { return *reinterpret_cast<const Chunk*>(pptr[slot] + chunk * CCE); };
   auto patch_store = [&](int slot, int buf, const Chunk& c) {
-    const int idx = slot * 256 + tid;
-    const int pos = idx >> 2, v = idx & 3;
     if ((pstore >> slot) & 1u)
-      *reinterpret_cast<Chunk*>(&patch[(buf * SUBT * PATCH_MAX_POS + pos) * PITCH + v * EV]) = ((pvalid >> slot) & 1u) ? c : zero_chunk();
+      *reinterpret_cast<Chunk*>(&patch[buf * SUBT * PATCH_MAX_POS * PITCH + pdst[slot]]) = ((pvalid >> slot) & 1u) ? c : zero_chunk();
   };
   const T* wrow = wmat + (int64_t)(n0c + brow0) * Kg + bvec * EV;
   // weight tile of global step gs = chunk*9 + tap -> registers REG
@@ -490,7 +495,7 @@ conv3x3_patch_kernel(const T* __restrict__ src, const T* __restrict__ wmat, cons
 
   int arow[MI];  // LDS element offset of tap (0,0) for this lane's 32-row groups
 #pragma unroll
-  for (int i = 0; i < MI; ++i) arow[i] = apos[wm * (32 * MI) + i * 32 + l32] * PITCH + Frag<T>::lane_off(g);
+  for (int i = 0; i < MI; ++i) arow[i] = apos[wm * (32 * MI) + i * 32 + l32] + Frag<T>::lane_off(g);
   const int bfrag = (wn * (BN / 2) + l32) * PITCH + Frag<T>::lane_off(g);  // this lane's row in a weight stage
 
   v16f acc[MI][NI];
@@ -524,7 +529,7 @@ conv3x3_patch_kernel(const T* __restrict__ src, const T* __restrict__ wmat, cons
       const bool has_next = !last || t + 1 < 9;
       const int tn = (t + 1) % 9;
       const T* pn = t + 1 < 9 ? pcur : pnxt;
-      const int tapoff_n = ((tn / 3) * SC + (tn % 3)) * PITCH;
+      const int tapoff_n = (tn / 3) * RPE + (tn % 3) * PITCH;
       const T* bn_ = &Bs[((t + 1) % 3) * BN * PITCH + bfrag];
       // requests: the weight tile this tap will need in the next chunk, two pieces of the next patch during taps 0-3
       if (!last) B_LOAD(t, chunk + 1);
@@ -679,6 +684,22 @@ static bool patch_geometry(int N, int dstH, int dstW, int cap, PatchArgs& a) {
   return true;
 }
 
+// Bytes between staged patch rows.  A lane group reads 16 bytes per lane at consecutive pixels: within a row of TC
+// pixels the 80-byte position pitch spreads them over the LDS banks, and the row pitch is padded so that the next
+// rows of the tile land on the banks the previous ones left free (TC = 8: 128 mod 256, TC = 4: 64, TC = 2: 32);
+// kept at SC * 80 when the padded rows would not fit the patch buffer.
+int g_patch_pad_rows = 1;  // tuning switch (not part of the C ABI)
+static int patch_row_pitch(const PatchArgs& a, int subt) {
+  const int base = a.SC * 80;
+  int want = -1;
+  if (a.TC == 8) want = 128; else if (a.TC == 4) want = 64; else if (a.TC == 2) want = 32;
+  if (want < 0 || !g_patch_pad_rows) return base;
+  int rp = base / 256 * 256 + want;
+  if (rp < base) rp += 256;
+  const int64_t rows = (int64_t)subt * a.TI * a.SR;
+  return rows * rp <= (int64_t)subt * PATCH_MAX_POS * 80 ? rp : base;
+}
+
 // Block shapes of the patch kernel, largest first: {MI, SUBT, widest BN}.  The first one that gives the chip
 // `g_patch_fill` blocks is taken, else the one with the most blocks if that reaches `g_patch_min_blocks`
 // (shape-only rule, so the choice is the same on every run).
@@ -720,6 +741,7 @@ static bool patch_pick(int dt, int N, int dstH, int dstW, int srcC, int Ng, int 
     if (splits > 4) splits = 4;
     if (splits < 1) splits = 1;
   }
+  geo.row_pitch = patch_row_pitch(geo, shape.subt);
   geo.chunks_per_split = (nchunks + splits - 1) / splits;
   shape.splits = (nchunks + geo.chunks_per_split - 1) / geo.chunks_per_split;  // no empty ranges
   return true;

@@ -53,21 +53,28 @@ __global__ void __launch_bounds__(256) linear_fwd_kernel(const float* __restrict
 }
 
 // per sample: loss_n = logsumexp(logits_n) - logits_n[y_n]; dlogits = (softmax - onehot) * gscale
-__global__ void softmax_ce_kernel(const float* __restrict__ logits, const int32_t* __restrict__ y, float* __restrict__ loss_n,
-                                  float* __restrict__ dlogits, int N, int J, float gscale, int* __restrict__ flags) {
-  const int n = blockIdx.x * blockDim.x + threadIdx.x;
+// one wavefront per sample; lanes stride over the classes, maxima and sums by a fixed butterfly
+__global__ void __launch_bounds__(256) softmax_ce_kernel(const float* __restrict__ logits, const int32_t* __restrict__ y,
+                                                         float* __restrict__ loss_n, float* __restrict__ dlogits, int N, int J,
+                                                         float gscale, int* __restrict__ flags) {
+  const int n = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (n >= N) return;
+  const int lane = threadIdx.x & 63;
   const float* lp = logits + (int64_t)n * J;
-  float mx = lp[0];
-  for (int j = 1; j < J; ++j) mx = fmaxf(mx, lp[j]);
+  float mx = -INFINITY;
+  for (int j = lane; j < J; j += 64) mx = fmaxf(mx, lp[j]);
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
   float se = 0.f;
-  for (int j = 0; j < J; ++j) se += expf(lp[j] - mx);
+  for (int j = lane; j < J; j += 64) se += expf(lp[j] - mx);
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) se += __shfl_xor(se, off, 64);
   const float lse = mx + logf(se);
   int lab = y[n];
-  if (lab < 0 || lab >= J) { atomicOr(flags + 1, 1); lab = 0; }
-  loss_n[n] = lse - lp[lab];
+  if (lab < 0 || lab >= J) { if (lane == 0) atomicOr(flags + 1, 1); lab = 0; }
+  if (lane == 0) loss_n[n] = lse - lp[lab];
   const float inv = 1.f / se;
-  for (int j = 0; j < J; ++j) {
+  for (int j = lane; j < J; j += 64) {
     const float pj = expf(lp[j] - mx) * inv;
     dlogits[(int64_t)n * J + j] = (pj - (j == lab ? 1.f : 0.f)) * gscale;
   }
@@ -139,7 +146,7 @@ void launch_head_fwd(hipStream_t st, int dt, const void* x, int N, int HW, int C
   else if (dt == DT_BF16) hipLaunchKernelGGL(head_feat_kernel<bf16_t>, dim3(N), dim3(256), 0, st, (const bf16_t*)x, feat, HW, C, gap);
   else hipLaunchKernelGGL(head_feat_kernel<f16_t>, dim3(N), dim3(256), 0, st, (const f16_t*)x, feat, HW, C, gap);
   hipLaunchKernelGGL(linear_fwd_kernel, dim3(ceil_div((int64_t)N * J, 4)), dim3(256), 0, st, feat, w, b, logits, N, F, J);
-  hipLaunchKernelGGL(softmax_ce_kernel, dim3(ceil_div(N, 64)), dim3(64), 0, st, logits, y, loss_n, dlogits, N, J, gscale, flags);
+  hipLaunchKernelGGL(softmax_ce_kernel, dim3(ceil_div(N, 4)), dim3(256), 0, st, logits, y, loss_n, dlogits, N, J, gscale, flags);
   hipLaunchKernelGGL(loss_mean_kernel, dim3(1), dim3(256), 0, st, loss_n, N, loss_out);
 }
 
