@@ -89,7 +89,15 @@ extern "C" int optorch_seq_create(const optorch_unit_t* units, int32_t n_units, 
         if (f.dgrad_algo == ALGO_MFMA) f.dgrad_splits = conv_mfma_dgrad_splits(dt, g);
         if (f.wgrad_algo == ALGO_MFMA) f.wgrad_splits = conv_mfma_wgrad_splits(dt, g);
         if (f.wgrad_algo == ALGO_SMALLC) f.wgrad_splits = conv_smallc_wgrad_splits(g);
+        if (f.has_bn && f.fwd_algo == ALGO_MFMA) f.stat_blocks = conv_mfma_fwd_stat_blocks(dt, g);
       }
+    // the BatchNorm statistics operation that follows such a convolution only runs its finishing kernel
+    for (size_t i = 0; i + 1 < p.fops.size(); ++i)
+      if (p.fops[i].kind == F_CONV && p.fops[i].stat_blocks > 0 && p.fops[i + 1].kind == F_BN_STATS &&
+          p.fops[i + 1].x == p.fops[i].out)
+        p.fops[i + 1].stat_blocks = p.fops[i].stat_blocks;
+      else if (p.fops[i].kind == F_CONV)
+        p.fops[i].stat_blocks = 0;
     ok = choose_segments(p) && build_schedule(p);
   }
   p.cfg.boundaries = nullptr;  // the copy dies with this call; seg_begin holds the result
@@ -231,7 +239,7 @@ void run_op(const Ctx& c, const SOp& s) {
     case S_CONV_FWD:
       if (f.fwd_algo == ALGO_MFMA)
         launch_conv_fwd_mfma(st, dt, c.at(s.in[0]), c.wc(f.w_off), f.has_bias ? c.w32(f.b_off) : nullptr, c.at(s.out[0]),
-                             (float*)c.at(s.out[1]), f.fwd_splits, geom(f), f.relu);
+                             (float*)c.at(s.out[1]), (float*)c.at(s.out[2]), f.fwd_splits, geom(f), f.relu);
       else if (f.fwd_algo == ALGO_SMALLC)
         launch_conv_fwd_smallc(st, dt, c.at(s.in[0]), c.wc(f.w_off), f.has_bias ? c.w32(f.b_off) : nullptr, c.at(s.out[0]),
                                geom(f), f.relu);
@@ -240,9 +248,14 @@ void run_op(const Ctx& c, const SOp& s) {
                                geom(f), f.relu);
       break;
     case S_BN_STATS:
-      launch_bn_stats(st, dt, c.at(s.in[0]), (int64_t)f.N * f.P * f.Q, f.C, f.red_blocks, (float*)c.at(s.out[1]), h->eps,
-                      h->bn_mom, c.w32(f.gamma_off), c.w32(f.beta_off), (float*)c.at(s.out[0]),
-                      (float*)(h->pbase + h->off_run) + f.rs_off);
+      if (s.in[1] >= 0)
+        launch_bn_stats_finalize(st, (const float*)c.at(s.in[1]), (int64_t)f.N * f.P * f.Q, f.C, f.stat_blocks, h->eps,
+                                 h->bn_mom, c.w32(f.gamma_off), c.w32(f.beta_off), (float*)c.at(s.out[0]),
+                                 (float*)(h->pbase + h->off_run) + f.rs_off);
+      else
+        launch_bn_stats(st, dt, c.at(s.in[0]), (int64_t)f.N * f.P * f.Q, f.C, f.red_blocks, (float*)c.at(s.out[1]), h->eps,
+                        h->bn_mom, c.w32(f.gamma_off), c.w32(f.beta_off), (float*)c.at(s.out[0]),
+                        (float*)(h->pbase + h->off_run) + f.rs_off);
       break;
     case S_BN_APPLY:
       launch_bn_apply(st, dt, c.at(s.in[0]), (const float*)c.at(s.in[1]), c.at(s.in[2]), c.at(s.out[0]),
@@ -323,7 +336,7 @@ void work_of(const optorch_seq_t* h, const SOp& s, double* flops, double* bytes)
     case S_CONV_FWD: *flops = 2 * out_px * wts; *bytes = e * (in_px * f.C + out_px * f.K + wts); break;
     case S_DGRAD: *flops = 2 * out_px * wts; *bytes = e * (in_px * f.C * (s.in[1] >= 0 ? 2 : 1) + out_px * f.K + wts); break;
     case S_WGRAD: *flops = 2 * out_px * wts; *bytes = e * (in_px * f.C + out_px * f.K) + 4 * wts; break;
-    case S_BN_STATS: *bytes = e * out_px * f.C; break;
+    case S_BN_STATS: *bytes = s.in[1] >= 0 ? 8.0 * f.stat_blocks * f.C : e * out_px * f.C; break;  // fused: only the block sums
     case S_BN_APPLY: *bytes = e * out_px * f.C * (s.in[2] >= 0 ? 3 : 2); break;
     case S_BN_BWD: *bytes = e * out_px * f.C * (2 + (s.in[3] >= 0 ? 1 : 0) + 3 + (s.in[3] >= 0 ? 1 : 0) + (s.out[1] >= 0 ? 1 : 0)); break;
     case S_POOL_FWD: *bytes = e * (in_px + out_px) * f.C; break;

@@ -124,7 +124,8 @@ template <class T, int BM, int BN> constexpr size_t igemm_smem_bytes() {
 template <class T, int BM, int BN, int MODE, bool SPLIT>
 __global__ void __launch_bounds__(256) conv_igemm_kernel(const T* __restrict__ src, const T* __restrict__ wmat,
                                                          const float* __restrict__ bias, const T* __restrict__ addend,
-                                                         T* __restrict__ out, float* __restrict__ partial, IGemmArgs a) {
+                                                         T* __restrict__ out, float* __restrict__ partial,
+                                                         float* __restrict__ stat_partial, IGemmArgs a) {
   constexpr int BK = Frag<T>::BK;
   constexpr int EV = 16 / (int)sizeof(T);   // elements per 16-byte chunk
   constexpr int PITCH = BK + EV;            // LDS row pitch in elements (80 bytes)
@@ -286,6 +287,7 @@ __global__ void __launch_bounds__(256) conv_igemm_kernel(const T* __restrict__ s
     float* ep = reinterpret_cast<float*>(smem_raw);
     constexpr int EP_PITCH = BN + 4;
     constexpr int HR = BM / 2;  // rows per pass
+    float ssum = 0.f, qsum = 0.f;  // per-channel sum and sum of squares of the values as stored (BatchNorm statistics)
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
       __syncthreads();
@@ -335,6 +337,32 @@ __global__ void __launch_bounds__(256) conv_igemm_kernel(const T* __restrict__ s
           }
         }
       }
+      if (!SPLIT && stat_partial) {  // thread = channel tid % BN, every (256 / BN)-th row
+        constexpr int NPART = 256 / BN;
+        const int sc = tid % BN;
+        const float bv = bias ? bias[n0 + sc] : 0.f;
+#pragma unroll 8
+        for (int r = tid / BN; r < HR; r += NPART) {
+          float v = ep[r * EP_PITCH + sc] + bv;
+          if (a.relu) v = fmaxf(v, 0.f);
+          v = to_f32(from_f32<T>(v));
+          v = m0 + u * HR + r < a.M ? v : 0.f;
+          ssum += v; qsum = __fmaf_rn(v, v, qsum);
+        }
+      }
+    }
+    if (!SPLIT && stat_partial) {  // the row groups of a channel are added in a fixed order
+      constexpr int NPART = 256 / BN;
+      __syncthreads();
+      ep[tid] = ssum; ep[256 + tid] = qsum;
+      __syncthreads();
+      if (tid < BN) {
+        float s0 = ep[tid], q0 = ep[256 + tid];
+#pragma unroll
+        for (int pt = 1; pt < NPART; ++pt) { s0 += ep[pt * BN + tid]; q0 += ep[256 + pt * BN + tid]; }
+        stat_partial[((int64_t)blockIdx.x * 2 + 0) * a.Ng + n0 + tid] = s0;
+        stat_partial[((int64_t)blockIdx.x * 2 + 1) * a.Ng + n0 + tid] = q0;
+      }
     }
   }
 }
@@ -370,7 +398,8 @@ constexpr int PATCH_MAX_POS = 256;  // positions per sub-tile
 template <class T, int BN, int MI, int SUBT>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, MI == 4 ? 1 : 2)))
 conv3x3_patch_kernel(const T* __restrict__ src, const T* __restrict__ wmat, const float* __restrict__ bias,
-                     const T* __restrict__ addend, T* __restrict__ out, float* __restrict__ partial, PatchArgs a) {
+                     const T* __restrict__ addend, T* __restrict__ out, float* __restrict__ partial,
+                     float* __restrict__ stat_partial, PatchArgs a) {
   constexpr int ROWS = 64 * MI;              // pixel rows of the block
   constexpr int TPC = ROWS / SUBT;           // rows (pixel capacity) per sub-tile
   constexpr int NSLOT = 4 * SUBT;            // 16-byte patch pieces per thread and channel chunk
@@ -585,6 +614,7 @@ conv3x3_patch_kernel(const T* __restrict__ src, const T* __restrict__ wmat, cons
   {
     float* ep = reinterpret_cast<float*>(smem_raw);
     constexpr int EP_PITCH = BN + 4;
+    float ssum = 0.f, qsum = 0.f;  // per-channel sum and sum of squares of the values as stored (BatchNorm statistics)
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
       __syncthreads();
@@ -633,6 +663,32 @@ conv3x3_patch_kernel(const T* __restrict__ src, const T* __restrict__ wmat, cons
           }
           store_f32<T, 8>(out + ro + col, v);
         }
+      }
+      if (stat_partial) {  // thread = channel tid % BN, every (256 / BN)-th row
+        constexpr int NPART = 256 / BN;
+        const int sc = tid % BN;
+        const float bv = bias ? bias[n0c + sc] : 0.f;
+#pragma unroll 8
+        for (int r = tid / BN; r < 32 * MI; r += NPART) {
+          float v = ep[r * EP_PITCH + sc] + bv;
+          if (a.relu) v = fmaxf(v, 0.f);
+          v = to_f32(from_f32<T>(v));
+          v = out_off[u * (32 * MI) + r] >= 0 ? v : 0.f;
+          ssum += v; qsum = __fmaf_rn(v, v, qsum);
+        }
+      }
+    }
+    if (stat_partial) {  // the row groups of a channel are added in a fixed order
+      constexpr int NPART = 256 / BN;
+      __syncthreads();
+      ep[tid] = ssum; ep[256 + tid] = qsum;
+      __syncthreads();
+      if (tid < BN) {
+        float s0 = ep[tid], q0 = ep[256 + tid];
+#pragma unroll
+        for (int pt = 1; pt < NPART; ++pt) { s0 += ep[pt * BN + tid]; q0 += ep[256 + pt * BN + tid]; }
+        stat_partial[((int64_t)blockIdx.x * 2 + 0) * a.Ng + n0c + tid] = s0;
+        stat_partial[((int64_t)blockIdx.x * 2 + 1) * a.Ng + n0c + tid] = q0;
       }
     }
   }
@@ -749,7 +805,7 @@ static bool patch_pick(int dt, int N, int dstH, int dstW, int srcC, int Ng, int 
 
 template <class T, int BN, int MI, int SUBT>
 static void launch_patch_v(hipStream_t st, const void* src, const void* wmat, const float* bias, const void* addend, void* out,
-                           float* partial, int splits, const PatchArgs& a) {
+                           float* partial, float* stat_partial, int splits, const PatchArgs& a) {
   dim3 grid((a.NT + SUBT - 1) / SUBT, a.Ng / BN, splits), block(256);
   constexpr size_t sm = patch_smem_bytes<T>(BN, SUBT);
   static bool attr_done = false;
@@ -758,21 +814,22 @@ static void launch_patch_v(hipStream_t st, const void* src, const void* wmat, co
     attr_done = true;
   }
   hipLaunchKernelGGL((conv3x3_patch_kernel<T, BN, MI, SUBT>), grid, block, sm, st, (const T*)src, (const T*)wmat, bias,
-                     (const T*)addend, (T*)out, splits > 1 ? partial : (float*)nullptr, a);
+                     (const T*)addend, (T*)out, splits > 1 ? partial : (float*)nullptr, splits > 1 ? (float*)nullptr : stat_partial,
+                     a);
 }
 
 template <class T>
 static void launch_patch_t(hipStream_t st, const void* src, const void* wmat, const float* bias, const void* addend, void* out,
-                           float* partial, const PatchShape& v, const PatchArgs& a) {
+                           float* partial, float* stat_partial, const PatchShape& v, const PatchArgs& a) {
   const int sp = v.splits;
   if (v.mi == 4) {
-    if (v.bn == 128) launch_patch_v<T, 128, 4, 2>(st, src, wmat, bias, addend, out, partial, sp, a);
-    else launch_patch_v<T, 64, 4, 2>(st, src, wmat, bias, addend, out, partial, sp, a);
+    if (v.bn == 128) launch_patch_v<T, 128, 4, 2>(st, src, wmat, bias, addend, out, partial, stat_partial, sp, a);
+    else launch_patch_v<T, 64, 4, 2>(st, src, wmat, bias, addend, out, partial, stat_partial, sp, a);
   } else if (v.mi == 2) {
-    if (v.bn == 128) launch_patch_v<T, 128, 2, 1>(st, src, wmat, bias, addend, out, partial, sp, a);
-    else launch_patch_v<T, 64, 2, 1>(st, src, wmat, bias, addend, out, partial, sp, a);
+    if (v.bn == 128) launch_patch_v<T, 128, 2, 1>(st, src, wmat, bias, addend, out, partial, stat_partial, sp, a);
+    else launch_patch_v<T, 64, 2, 1>(st, src, wmat, bias, addend, out, partial, stat_partial, sp, a);
   } else {
-    launch_patch_v<T, 64, 1, 1>(st, src, wmat, bias, addend, out, partial, sp, a);
+    launch_patch_v<T, 64, 1, 1>(st, src, wmat, bias, addend, out, partial, stat_partial, sp, a);
   }
   if (sp > 1) {
     const int64_t n = (int64_t)a.N * a.dstH * a.dstW * a.Ng;  // a multiple of 4: Ng % 64 == 0
@@ -782,10 +839,10 @@ static void launch_patch_t(hipStream_t st, const void* src, const void* wmat, co
 }
 
 static void launch_patch(hipStream_t st, int dt, const void* src, const void* wmat, const float* bias, const void* addend, void* out,
-                         float* partial, const PatchShape& v, const PatchArgs& a) {
-  if (dt == DT_F32) launch_patch_t<float>(st, src, wmat, bias, addend, out, partial, v, a);
-  else if (dt == DT_BF16) launch_patch_t<bf16_t>(st, src, wmat, bias, addend, out, partial, v, a);
-  else launch_patch_t<f16_t>(st, src, wmat, bias, addend, out, partial, v, a);
+                         float* partial, float* stat_partial, const PatchShape& v, const PatchArgs& a) {
+  if (dt == DT_F32) launch_patch_t<float>(st, src, wmat, bias, addend, out, partial, stat_partial, v, a);
+  else if (dt == DT_BF16) launch_patch_t<bf16_t>(st, src, wmat, bias, addend, out, partial, stat_partial, v, a);
+  else launch_patch_t<f16_t>(st, src, wmat, bias, addend, out, partial, stat_partial, v, a);
 }
 
 int g_igemm_spread = 1;                         // tuning switch (not part of the C ABI)
@@ -799,7 +856,7 @@ static int igemm_bm(int64_t M, int Ng) {
 
 template <class T, int MODE>
 static void launch_igemm_t(hipStream_t st, const void* src, const void* wmat, const float* bias, const void* addend, void* out,
-                           float* partial, int splits, const IGemmArgs& a0) {
+                           float* partial, float* stat_partial, int splits, const IGemmArgs& a0) {
   IGemmArgs a = a0;
   const int bk = Frag<T>::BK;
   a.kt_per_split = ceil_div(a.Kg / bk, splits);
@@ -820,7 +877,7 @@ static void launch_igemm_t(hipStream_t st, const void* src, const void* wmat, co
       attr_ = true;                                                                                                      \
     }                                                                                                                    \
     hipLaunchKernelGGL((conv_igemm_kernel<T, BM_, BN_, MODE, SPLIT_>), grid, block, spread ? big_ : sm_, st,             \
-                       (const T*)src, (const T*)wmat, bias, (const T*)addend, (T*)out, partial, a);                      \
+                       (const T*)src, (const T*)wmat, bias, (const T*)addend, (T*)out, partial, stat_partial, a);        \
   }
   if (splits > 1) {
     if (wide) IGEMM_LAUNCH(128, 128, true) else IGEMM_LAUNCH(128, 64, true)
@@ -837,10 +894,10 @@ static void launch_igemm_t(hipStream_t st, const void* src, const void* wmat, co
 
 template <int MODE>
 static void launch_igemm(hipStream_t st, int dt, const void* src, const void* wmat, const float* bias, const void* addend,
-                         void* out, float* partial, int splits, const IGemmArgs& a) {
-  if (dt == DT_F32) launch_igemm_t<float, MODE>(st, src, wmat, bias, addend, out, partial, splits, a);
-  else if (dt == DT_BF16) launch_igemm_t<bf16_t, MODE>(st, src, wmat, bias, addend, out, partial, splits, a);
-  else launch_igemm_t<f16_t, MODE>(st, src, wmat, bias, addend, out, partial, splits, a);
+                         void* out, float* partial, float* stat_partial, int splits, const IGemmArgs& a) {
+  if (dt == DT_F32) launch_igemm_t<float, MODE>(st, src, wmat, bias, addend, out, partial, stat_partial, splits, a);
+  else if (dt == DT_BF16) launch_igemm_t<bf16_t, MODE>(st, src, wmat, bias, addend, out, partial, stat_partial, splits, a);
+  else launch_igemm_t<f16_t, MODE>(st, src, wmat, bias, addend, out, partial, stat_partial, splits, a);
 }
 
 // depth splits of a GEMM with M rows, Ng columns and depth Kg: from the shape only
@@ -874,17 +931,30 @@ bool conv_mfma_dgrad_ok(int dt, const ConvGeom& g) {
   return g.K % bk == 0 && g.C % 64 == 0;
 }
 
+// Row blocks of the forward kernel when it can also produce the per-channel sums for BatchNorm (no depth split);
+// 0 otherwise.  From the layer shape only.
+int conv_mfma_fwd_stat_blocks(int dt, const ConvGeom& g) {
+  PatchShape pv; PatchArgs pa{};
+  if (patch_pick(dt, g.N, g.P, g.Q, g.C, g.K, g.R, g.S, g.stride, pv, pa))
+    return pv.splits > 1 ? 0 : (pa.NT + pv.subt - 1) / pv.subt;
+  const int64_t M = (int64_t)g.N * g.P * g.Q;
+  if (igemm_splits(dt, M, g.K, g.R * g.S * g.C) > 1) return 0;
+  return ceil_div(M, igemm_bm(M, g.K));
+}
+
+// stat_partial: null, or [conv_mfma_fwd_stat_blocks][2][C_out] floats receiving per-block sums and sums of squares
+// of the stored outputs
 void launch_conv_fwd_mfma(hipStream_t st, int dt, const void* x, const void* w, const float* bias, void* out,
-                          float* partial, int splits, const ConvGeom& g, int relu) {
+                          float* partial, float* stat_partial, int splits, const ConvGeom& g, int relu) {
   PatchShape pv; PatchArgs pa{};
   if (patch_pick(dt, g.N, g.P, g.Q, g.C, g.K, g.R, g.S, g.stride, pv, pa)) {
     pa.N = g.N; pa.srcH = g.H; pa.srcW = g.W; pa.srcC = g.C; pa.dstH = g.P; pa.dstW = g.Q; pa.Ng = g.K;
     pa.pad = g.pad; pa.flip = 0; pa.relu = relu;
-    launch_patch(st, dt, x, w, bias, nullptr, out, partial, pv, pa);
+    launch_patch(st, dt, x, w, bias, nullptr, out, partial, stat_partial, pv, pa);
     return;
   }
   IGemmArgs a{g.H, g.W, g.C, g.P, g.Q, g.N * g.P * g.Q, g.K, g.R * g.S * g.C, g.R, g.S, g.stride, g.pad, relu, 0};
-  launch_igemm<IG_FWD>(st, dt, x, w, bias, nullptr, out, partial, splits, a);
+  launch_igemm<IG_FWD>(st, dt, x, w, bias, nullptr, out, partial, stat_partial, splits, a);
 }
 
 // wt: the (C_in, kh, kw, C_out) transpose of the weights, in the compute type
@@ -894,11 +964,11 @@ void launch_conv_dgrad_mfma(hipStream_t st, int dt, const void* dz, const void* 
   if (patch_pick(dt, g.N, g.H, g.W, g.K, g.C, g.R, g.S, g.stride, pv, pa)) {
     pa.N = g.N; pa.srcH = g.P; pa.srcW = g.Q; pa.srcC = g.K; pa.dstH = g.H; pa.dstW = g.W; pa.Ng = g.C;
     pa.pad = g.R - 1 - g.pad; pa.flip = 1; pa.relu = 0;
-    launch_patch(st, dt, dz, wt, nullptr, addend, dx, partial, pv, pa);
+    launch_patch(st, dt, dz, wt, nullptr, addend, dx, partial, nullptr, pv, pa);
     return;
   }
   IGemmArgs a{g.P, g.Q, g.K, g.H, g.W, g.N * g.H * g.W, g.C, g.R * g.S * g.K, g.R, g.S, g.stride, g.pad, 0, 0};
-  launch_igemm<IG_DGRAD>(st, dt, dz, wt, nullptr, addend, dx, partial, splits, a);
+  launch_igemm<IG_DGRAD>(st, dt, dz, wt, nullptr, addend, dx, partial, nullptr, splits, a);
 }
 
 // (C_out, R*S, C_in) fp32 master weights -> (C_in, R*S, C_out) in the compute type, for all layers of a batch in one

@@ -343,6 +343,12 @@ void launch_bn_stats(hipStream_t st, int dt, const void* z, int64_t rows, int C,
                      eps, mom, gamma, beta, stats, running);
 }
 
+void launch_bn_stats_finalize(hipStream_t st, const float* partial, int64_t rows, int C, int nblk, float eps, float mom,
+                              const float* gamma, const float* beta, float* stats, float* running) {
+  hipLaunchKernelGGL(bn_stats_finalize_kernel, dim3(ceil_div(C, 4)), dim3(256), 0, st, partial, nblk, C, (double)rows,
+                     eps, mom, gamma, beta, stats, running);
+}
+
 void launch_bn_apply(hipStream_t st, int dt, const void* z, const float* stats, const void* skip, void* out, int64_t rows,
                      int C, int relu) {
 #define CALL(T, V)                                                                                                   \

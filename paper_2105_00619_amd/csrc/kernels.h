@@ -13,6 +13,9 @@ struct ConvGeom { int N, H, W, C, K, R, S, stride, pad, P, Q; };
 void launch_cast_in(hipStream_t st, int dt, const float* x, void* out, int64_t n);
 void launch_bn_stats(hipStream_t st, int dt, const void* z, int64_t rows, int C, int nblk, float* partial, float eps,
                      float mom, const float* gamma, const float* beta, float* stats, float* running);
+// the same from per-block sums a convolution already produced: partial [nblk][2][C]
+void launch_bn_stats_finalize(hipStream_t st, const float* partial, int64_t rows, int C, int nblk, float eps, float mom,
+                              const float* gamma, const float* beta, float* stats, float* running);
 void launch_bn_apply(hipStream_t st, int dt, const void* z, const float* stats, const void* skip, void* out, int64_t rows,
                      int C, int relu);
 void launch_bn_bwd(hipStream_t st, int dt, const void* da, const void* z, const void* aout, const float* stats, int64_t rows,
@@ -50,8 +53,9 @@ bool conv_mfma_dgrad_ok(int dt, const ConvGeom& g);
 int conv_mfma_fwd_splits(int dt, const ConvGeom& g);
 int conv_mfma_dgrad_splits(int dt, const ConvGeom& g);
 // partial: fp32 workspace of splits * (output elements) floats when splits > 1, else unused
+int conv_mfma_fwd_stat_blocks(int dt, const ConvGeom& g);
 void launch_conv_fwd_mfma(hipStream_t st, int dt, const void* x, const void* w, const float* bias, void* out,
-                          float* partial, int splits, const ConvGeom& g, int relu);
+                          float* partial, float* stat_partial, int splits, const ConvGeom& g, int relu);
 void launch_conv_dgrad_mfma(hipStream_t st, int dt, const void* dz, const void* wt, const void* addend, void* dx,
                             float* partial, int splits, const ConvGeom& g);
 // 3x3 stride-1 weight gradient with all nine taps per block (k_conv_wgrad3x3.hip); used by the MFMA launcher below

@@ -230,7 +230,9 @@ bool has_side_effect(SKind k) {
 struct Scheduler {
   Plan& p;
   std::vector<int> cur, grad;  // [LTensor] -> Inst id
-  explicit Scheduler(Plan& pl) : p(pl), cur(pl.tensors.size(), -1), grad(pl.tensors.size(), -1) {}
+  std::vector<int> stat_ws;    // [LTensor of a conv output] -> Inst id of the channel sums its forward kernel wrote
+  explicit Scheduler(Plan& pl)
+      : p(pl), cur(pl.tensors.size(), -1), grad(pl.tensors.size(), -1), stat_ws(pl.tensors.size(), -1) {}
 
   int new_inst(int logical, uint64_t bytes, bool fwd_value) {
     Inst i; i.logical = logical; i.bytes = bytes; i.fwd_value = fwd_value;
@@ -254,13 +256,18 @@ struct Scheduler {
         SOp& s = push(S_CONV_FWD, fi, phase, seg);
         s.in[0] = cur[f.x]; s.out[0] = value_inst(f.out);
         if (f.fwd_splits > 1) s.out[1] = new_inst(-1, (uint64_t)f.fwd_splits * f.N * f.P * f.Q * f.K * 4, false);
+        if (f.stat_blocks > 0 && phase != PH_REPLAY) {  // per-block channel sums for the BatchNorm that follows
+          s.out[2] = new_inst(-1, (uint64_t)f.stat_blocks * 2 * f.K * 4, false);
+          stat_ws[f.out] = s.out[2];
+        }
         break;
       }
       case F_BN_STATS: {
         if (phase == PH_REPLAY) break;  // the statistics of the first forward pass are kept and reused
         SOp& s = push(S_BN_STATS, fi, phase, seg);
         s.in[0] = cur[f.x]; s.out[0] = value_inst(f.stats);
-        s.out[1] = new_inst(-1, (uint64_t)f.red_blocks * 2 * f.C * 4, false);
+        if (f.stat_blocks > 0) s.in[1] = stat_ws[f.x];  // sums come from the convolution: only the finishing kernel runs
+        else s.out[1] = new_inst(-1, (uint64_t)f.red_blocks * 2 * f.C * 4, false);
         break;
       }
       case F_BN_APPLY: {
@@ -369,7 +376,7 @@ struct Scheduler {
 
 int launches_of(const SOp& op, const FOp& f) {
   switch (op.kind) {
-    case S_BN_STATS: return 2;
+    case S_BN_STATS: return f.stat_blocks > 0 ? 1 : 2;
     case S_HEAD_FWD: return 4;
     case S_HEAD_BWD: return op.out[0] >= 0 ? 4 : 2;
     case S_BN_BWD: return 3;

@@ -48,6 +48,8 @@ struct FOp {
   int wgrad_splits = 1;      // fixed by shape only: deterministic split of the pixel reduction
   int fwd_splits = 1, dgrad_splits = 1;  // fixed by shape only: deterministic split of the GEMM depth
   int red_blocks = 1;        // row blocks of the per-channel reductions (BN statistics, BN backward)
+  int stat_blocks = 0;       // > 0: the convolution's forward kernel also writes per-block channel sums for the
+                             // BatchNorm that follows (that many row blocks); set on the conv and on its F_BN_STATS
 };
 
 enum SKind {
