@@ -760,10 +760,11 @@ static int patch_row_pitch(const PatchArgs& a, int subt) {
 // `g_patch_fill` blocks is taken, else the one with the most blocks if that reaches `g_patch_min_blocks`
 // (shape-only rule, so the choice is the same on every run).
 struct PatchShape { int mi, subt, bn, splits; };
-int g_patch_min_blocks = 96;   // tuning constants (not part of the C ABI)
+int g_patch_min_blocks = 64;   // tuning constants (not part of the C ABI)
 int g_patch_fill = 200;
 int g_patch_shapes = 0xf;      // bit i: candidate i allowed
 int g_patch_split = 1;         // allow the depth split
+int g_patch_halo2 = 9;         // largest staged positions : pixels ratio, times two
 int g_patch_target_small = 512;  // blocks aimed at by the depth split for the smallest block shape in fp32
 static bool patch_pick(int dt, int N, int dstH, int dstW, int srcC, int Ng, int R, int S, int stride, PatchShape& shape,
                        PatchArgs& geo) {
@@ -781,7 +782,7 @@ static bool patch_pick(int dt, int N, int dstH, int dstW, int srcC, int Ng, int 
     PatchArgs a{};
     if (!patch_geometry(N, dstH, dstW, cap, a)) continue;
     if (a.TP * 4 < cap * 3) continue;  // tile rows poorly used
-    if (a.NPOS * 2 > a.TP * 5) continue;  // mostly halo (2x2 images): the staged patch costs more than it saves
+    if (a.NPOS * 2 > a.TP * g_patch_halo2) continue;  // mostly halo (2x2 images): the staged patch costs more than it saves
     const int64_t blocks = (int64_t)((a.NT + cand[i].subt - 1) / cand[i].subt) * (Ng / cand[i].bn);
     if (blocks > best_blocks) { best = i; best_blocks = blocks; best_geo = a; }
     if (blocks >= g_patch_fill) break;
