@@ -34,6 +34,12 @@ struct IGemmArgs {
   int M, Ng, Kg;          // GEMM sizes: rows (pixels), columns (channels), depth (R*S*srcC)
   int R, S, stride, pad, relu;
   int kt_per_split;       // depth tiles per blockIdx.z when the depth is split
+  // Data gradient of a stride-2 convolution by parity classes (cls = 1): blockIdx.z is the class (ph, pw) of the
+  // output pixel (h, w) = (2*hh + ph, 2*ww + pw); only the taps with (ph + pad - r) and (pw + pad - s) even reach
+  // that class, so each class is its own GEMM over its tap list.  dstH / dstW are then the class grid (fullH/2,
+  // fullW/2), M its pixel count, taps[c] the list (one byte per tap, r*S + s), ntaps[c] its length.
+  int cls, fullH, fullW;
+  int taps[4], ntaps[4];
 };
 
 template <class T> struct Frag;  // 32 bytes of one operand row, and the MFMAs that consume it
@@ -144,6 +150,9 @@ __global__ void __launch_bounds__(256) conv_igemm_kernel(const T* __restrict__ s
   const int vec = tid & 3, row0 = tid >> 2;  // this thread's chunk column and first row
 
   // pixel coordinates of this thread's A rows
+  const int cz = a.cls ? blockIdx.z : 0;              // parity class
+  const int cph = cz >> 1, cpw = cz & 1;
+  const int ctaps = a.cls ? a.taps[cz] : 0;
   int pn[A_CH], pa[A_CH], pb[A_CH];
 #pragma unroll
   for (int i = 0; i < A_CH; ++i) {
@@ -153,10 +162,11 @@ __global__ void __launch_bounds__(256) conv_igemm_kernel(const T* __restrict__ s
     const int t = mm / a.dstW;
     pa[i] = t % a.dstH;
     pn[i] = m < a.M ? t / a.dstH : -1;  // -1: row beyond the last pixel
+    if (a.cls) { pa[i] = 2 * pa[i] + cph; pb[i] = 2 * pb[i] + cpw; }
   }
   const T* brow[B_CH];
 #pragma unroll
-  for (int i = 0; i < B_CH; ++i) brow[i] = wmat + (int64_t)(n0 + row0 + i * 64) * Kg + vec * EV;
+  for (int i = 0; i < B_CH; ++i) brow[i] = wmat + (int64_t)(n0 + row0 + i * 64) * (a.R * a.S * srcC) + vec * EV;
 
   // Global loads are unconditional (addresses of out-of-image taps are clamped into the tensor) and the zeroing is
   // applied when the chunk is written to LDS: straight-line loads let the hardware keep several generations in flight.
@@ -165,8 +175,10 @@ __global__ void __launch_bounds__(256) conv_igemm_kernel(const T* __restrict__ s
   auto gload = [&, srcH, srcW, srcC, S_, stride, pad](auto P, int kt) {
     constexpr int p = decltype(P)::value;
     const int kk0 = kt * BK;
-    const int tap = kk0 / srcC, c0 = kk0 - tap * srcC;
+    const int tapi = kk0 / srcC, c0 = kk0 - tapi * srcC;
+    const int tap = a.cls ? (ctaps >> (8 * tapi)) & 0xff : tapi;  // filter tap r*S + s of this depth tile
     const int r = tap / S_, s = tap - r * S_;
+    const int kkw = tap * srcC + c0;                              // its depth offset in the weight rows
     unsigned m = 0u;
 #pragma unroll
     for (int i = 0; i < A_CH; ++i) {
@@ -187,7 +199,7 @@ __global__ void __launch_bounds__(256) conv_igemm_kernel(const T* __restrict__ s
     }
     okm[p] = m;
 #pragma unroll
-    for (int i = 0; i < B_CH; ++i) rb[p][i] = *reinterpret_cast<const Chunk*>(brow[i] + kk0);
+    for (int i = 0; i < B_CH; ++i) rb[p][i] = *reinterpret_cast<const Chunk*>(brow[i] + kkw);
   };
   auto sstore = [&](auto P, int stage) {  // register generation p -> LDS stage
     constexpr int p = decltype(P)::value;
@@ -208,7 +220,8 @@ __global__ void __launch_bounds__(256) conv_igemm_kernel(const T* __restrict__ s
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
   const int kt0 = SPLIT ? blockIdx.z * a.kt_per_split : 0;
-  const int kt1 = SPLIT ? (kt0 + a.kt_per_split < a.Kg / BK ? kt0 + a.kt_per_split : a.Kg / BK) : a.Kg / BK;
+  const int nkt = (a.cls ? a.ntaps[cz] * srcC : a.Kg) / BK;  // depth tiles of this GEMM
+  const int kt1 = SPLIT ? (kt0 + a.kt_per_split < nkt ? kt0 + a.kt_per_split : nkt) : nkt;
   const int n = kt1 > kt0 ? kt1 - kt0 : 0;
   // prologue: tiles 0 and 1 into LDS stages 0 and 1, tile 2 on its way in generation 0
   if (n > 0) { gload(IC<0>{}, kt0); sstore(IC<0>{}, 0); }
@@ -312,7 +325,13 @@ __global__ void __launch_bounds__(256) conv_igemm_kernel(const T* __restrict__ s
           const v4f x0 = *reinterpret_cast<const v4f*>(&ep[row * EP_PITCH + c8]);
           const v4f x1 = *reinterpret_cast<const v4f*>(&ep[row * EP_PITCH + c8 + 4]);
           const int col = n0 + c8;
-          const int64_t o = (int64_t)grow * a.Ng + col;
+          int64_t opix = grow;
+          if (a.cls) {  // class-local pixel -> pixel of the full grid
+            const int ww = grow % a.dstW, t2 = grow / a.dstW;
+            const int hh = t2 % a.dstH, nn = t2 / a.dstH;
+            opix = ((int64_t)nn * a.fullH + 2 * hh + cph) * a.fullW + 2 * ww + cpw;
+          }
+          const int64_t o = opix * a.Ng + col;
           if (SPLIT) {
             float* dst = partial + (int64_t)blockIdx.z * a.M * a.Ng + o;
             *reinterpret_cast<v4f*>(dst) = x0;
@@ -867,7 +886,7 @@ static void launch_igemm_t(hipStream_t st, const void* src, const void* wmat, co
   a.kt_per_split = ceil_div(a.Kg / bk, splits);
   const bool wide = a.Ng % 128 == 0;
   const int bm = splits > 1 ? 128 : igemm_bm(a.M, a.Ng);
-  dim3 grid(ceil_div(a.M, bm), a.Ng / (wide ? 128 : 64), splits), block(256);
+  dim3 grid(ceil_div(a.M, bm), a.Ng / (wide ? 128 : 64), a.cls ? 4 : splits), block(256);  // cls: never split
   // A grid of at most one block per CU asks for more than half of a CU's LDS, so that no CU takes two blocks
   // while another idles.
   const bool spread = g_igemm_spread && (int64_t)grid.x * grid.y * grid.z <= 256;
@@ -921,9 +940,15 @@ int conv_mfma_fwd_splits(int dt, const ConvGeom& g) {
   if (patch_pick(dt, g.N, g.P, g.Q, g.C, g.K, g.R, g.S, g.stride, v, pa)) return v.splits;
   return igemm_splits(dt, (int64_t)g.N * g.P * g.Q, g.K, g.R * g.S * g.C);
 }
+// stride 2, even image, at most 3x3: the data gradient runs as four parity-class GEMMs in one launch
+int g_dgrad_classes = 1;  // tuning switch (not part of the C ABI)
+static bool dgrad_by_classes(const ConvGeom& g) {
+  return g_dgrad_classes && g.stride == 2 && g.H % 2 == 0 && g.W % 2 == 0 && g.R <= 3 && g.S <= 3;
+}
 int conv_mfma_dgrad_splits(int dt, const ConvGeom& g) {
   PatchShape v; PatchArgs pa{};
   if (patch_pick(dt, g.N, g.H, g.W, g.K, g.C, g.R, g.S, g.stride, v, pa)) return v.splits;
+  if (dgrad_by_classes(g)) return 1;
   return igemm_splits(dt, (int64_t)g.N * g.H * g.W, g.C, g.R * g.S * g.K);
 }
 
@@ -973,6 +998,20 @@ void launch_conv_dgrad_mfma(hipStream_t st, int dt, const void* dz, const void* 
     return;
   }
   IGemmArgs a{g.P, g.Q, g.K, g.H, g.W, g.N * g.H * g.W, g.C, g.R * g.S * g.K, g.R, g.S, g.stride, g.pad, 0, 0};
+  if (dgrad_by_classes(g)) {
+    a.cls = 1; a.fullH = g.H; a.fullW = g.W;
+    a.dstH = g.H / 2; a.dstW = g.W / 2; a.M = g.N * a.dstH * a.dstW;
+    for (int c = 0; c < 4; ++c) {
+      const int ph = c >> 1, pw = c & 1;
+      a.taps[c] = 0; a.ntaps[c] = 0;
+      for (int r = 0; r < g.R; ++r)
+        for (int s2 = 0; s2 < g.S; ++s2)
+          if (((ph + g.pad - r) & 1) == 0 && ((pw + g.pad - s2) & 1) == 0)
+            a.taps[c] |= (r * g.S + s2) << (8 * a.ntaps[c]++);
+    }
+    launch_igemm<IG_DGRAD>(st, dt, dz, wt, nullptr, addend, dx, nullptr, nullptr, 1, a);
+    return;
+  }
   launch_igemm<IG_DGRAD>(st, dt, dz, wt, nullptr, addend, dx, partial, nullptr, splits, a);
 }
 
