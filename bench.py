@@ -108,6 +108,7 @@ def main():
     for _ in range(max(1, args.survey_steps)):
         tr.step(xd, yd, lr)
     survey = tr.profile_read()
+    entries = tr.profile_read_entries()
     tr.profile_enable(False)
     classes = {}
     for name, c in survey["classes"].items():
@@ -149,10 +150,28 @@ def main():
         achieved = dc["bytes"] / (dc["gpu_ms"] * 1e-3) / 1e9
         roof = {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": PEAK["hbm"], "unit": "GB/s",
                 "frac": achieved / PEAK["hbm"], "traffic": None}
+    # HBM bytes per launch from rocprofv3 FETCH_SIZE / WRITE_SIZE runs, if they were taken on these very kernels
+    from paper_2105_00619_amd import traffic as _traffic
+    meas = _traffic.lookup(wl.name, dom)
+    if meas is not None:
+        roof["traffic"] = meas["bytes_per_step"] / max(1.0, dc["entries"] / args.steps)
+        roof["traffic_algorithmic"] = dc["bytes"] / max(1, dc["entries"])
     roof["kernels"] = GROUP_KERNELS.get(dom, dom)
     roof["avg_launch_us"] = dc["gpu_ms"] * 1e3 / max(1, dc["entries"])  # per schedule entry (a split layer = 2 launches)
     roof["ms_per_step"] = dc["gpu_ms"] / args.steps
     roof["launches_timed"] = int(dc["entries"])
+
+    # convolution work per step: "model" = 3 x the forward pass (forward + data gradient + weight gradient of the
+    # network itself), "executed" adds the replayed forward of the checkpointed segments
+    fwd_flops = sum(e["flops"] for e in entries if e["kind"] == "conv_fwd" and e["phase"] in (0, 1)) / survey["steps"]
+    exe_flops = sum(e["flops"] for e in entries if e["kind"] in MFMA_CLASSES) / survey["steps"]
+    peak_key = {0: "mfma_f32", 1: "mfma_bf16", 2: "mfma_f16"}[wl.precision]
+    conv_work = {
+        "model_gflop_per_step": 3 * fwd_flops / 1e9, "executed_gflop_per_step": exe_flops / 1e9,
+        "model_tflops_over_step_time": 3 * fwd_flops / (ms * 1e-3) / 1e12,
+        "executed_tflops_over_step_time": exe_flops / (ms * 1e-3) / 1e12,
+        "model_frac_of_mfma_peak": 3 * fwd_flops / (ms * 1e-3) / 1e12 / PEAK[peak_key],
+    }
 
     out = {
         "metric": "train images/sec at fixed HBM activation budget; peak activation bytes; MFMA util",
@@ -164,7 +183,7 @@ def main():
         "loss": r["loss"], "peak_saved_bytes": r["peak_saved_bytes"], "peak_arena_bytes": r["peak_arena_bytes"],
         "activation_budget_bytes": wl.budget_bytes, "launches_per_step": tr.n_launches,
         "replay_launches_per_step": tr.n_replay_launches,
-        "roofline": roof, "kernel_classes_survey": classes,
+        "roofline": roof, "conv_work": conv_work, "kernel_classes_survey": classes,
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args.config, args.cpu_sample_batch or wl.batch)
