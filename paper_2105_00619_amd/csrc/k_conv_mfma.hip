@@ -716,24 +716,68 @@ conv3x3_patch_kernel(const T* __restrict__ src, const T* __restrict__ wmat, cons
 #undef B_LOAD
 #undef B_STORE
 
+// Sum of the depth ranges in order, then bias / residual addend / ReLU, one rounding, store.  A block covers 64 rows
+// x 64 channels (thread = 4 channels of every 16th row), so that it can also produce the per-channel sums of the
+// stored values for the BatchNorm that follows: stat_partial [ceil(M / 64)][2][Ng], or null.
+constexpr int SPLIT_EPI_ROWS = 64;
 template <class T>
-__global__ void __launch_bounds__(256) splitk_epilogue_kernel(const float* __restrict__ partial, int splits, int64_t n, int Ng,
+__global__ void __launch_bounds__(256) splitk_epilogue_kernel(const float* __restrict__ partial, int splits, int64_t M, int Ng,
                                                               const float* __restrict__ bias, const T* __restrict__ addend,
-                                                              T* __restrict__ out, int relu) {
-  const int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
-  if (i >= n) return;
-  v4f acc = *reinterpret_cast<const v4f*>(partial + i);
-  for (int z = 1; z < splits; ++z) acc += *reinterpret_cast<const v4f*>(partial + (int64_t)z * n + i);
-  const int col = (int)(i % Ng);
-  float r[4];
+                                                              T* __restrict__ out, float* __restrict__ stat_partial, int relu) {
+  __shared__ float red[2][16][64];
+  const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+  const int col = blockIdx.y * 64 + tx * 4;
+  const int64_t n = M * Ng;
+  float bv[4] = {0.f, 0.f, 0.f, 0.f};
+  if (bias) {
 #pragma unroll
-  for (int e = 0; e < 4; ++e) {
-    float v = acc[e];
-    if (bias) v += bias[col + e];
-    if (addend) v += to_f32(addend[i + e]);
-    r[e] = relu ? fmaxf(v, 0.f) : v;
+    for (int e = 0; e < 4; ++e) bv[e] = bias[col + e];
   }
-  store_f32<T, 4>(out + i, r);
+  float ss[4] = {0.f, 0.f, 0.f, 0.f}, qq[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int it = 0; it < SPLIT_EPI_ROWS / 16; ++it) {
+    const int64_t row = (int64_t)blockIdx.x * SPLIT_EPI_ROWS + it * 16 + ty;
+    if (row < M) {
+      const int64_t i = row * Ng + col;
+      v4f acc = *reinterpret_cast<const v4f*>(partial + i);
+      for (int z = 1; z < splits; ++z) acc += *reinterpret_cast<const v4f*>(partial + (int64_t)z * n + i);
+      float r[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        float v = acc[e] + bv[e];
+        if (addend) v += to_f32(addend[i + e]);
+        r[e] = relu ? fmaxf(v, 0.f) : v;
+      }
+      store_f32<T, 4>(out + i, r);
+      if (stat_partial) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float v = to_f32(from_f32<T>(r[e]));  // as stored
+          ss[e] += v; qq[e] = __fmaf_rn(v, v, qq[e]);
+        }
+      }
+    }
+  }
+  if (stat_partial) {  // the 16 row groups of a channel, added in a fixed order
+#pragma unroll
+    for (int e = 0; e < 4; ++e) { red[0][ty][tx * 4 + e] = ss[e]; red[1][ty][tx * 4 + e] = qq[e]; }
+    __syncthreads();
+    if (threadIdx.x < 128) {
+      const int which = threadIdx.x >> 6, c = threadIdx.x & 63;
+      float t = 0.f;
+#pragma unroll
+      for (int y = 0; y < 16; ++y) t += red[which][y][c];
+      stat_partial[((int64_t)blockIdx.x * 2 + which) * Ng + blockIdx.y * 64 + c] = t;
+    }
+  }
+}
+
+template <class T>
+static void launch_splitk_epilogue(hipStream_t st, const float* partial, int splits, int64_t M, int Ng, const float* bias,
+                                   const void* addend, void* out, float* stat_partial, int relu) {
+  dim3 grid(ceil_div(M, SPLIT_EPI_ROWS), Ng / 64);  // Ng % 64 == 0 for every MFMA convolution
+  hipLaunchKernelGGL(splitk_epilogue_kernel<T>, grid, dim3(256), 0, st, partial, splits, M, Ng, bias, (const T*)addend,
+                     (T*)out, stat_partial, relu);
 }
 
 template <class T> constexpr size_t patch_smem_bytes(int bn, int subt) {
@@ -855,11 +899,8 @@ static void launch_patch_t(hipStream_t st, const void* src, const void* wmat, co
   } else {
     launch_patch_v<T, 64, 1, 1>(st, src, wmat, bias, addend, out, partial, stat_partial, sp, a);
   }
-  if (sp > 1) {
-    const int64_t n = (int64_t)a.N * a.dstH * a.dstW * a.Ng;  // a multiple of 4: Ng % 64 == 0
-    hipLaunchKernelGGL(splitk_epilogue_kernel<T>, dim3(ceil_div(n / 4, 256)), dim3(256), 0, st, partial, sp, n, a.Ng, bias,
-                       (const T*)addend, (T*)out, a.relu);
-  }
+  if (sp > 1)
+    launch_splitk_epilogue<T>(st, partial, sp, (int64_t)a.N * a.dstH * a.dstW, a.Ng, bias, addend, out, stat_partial, a.relu);
 }
 
 static void launch_patch(hipStream_t st, int dt, const void* src, const void* wmat, const float* bias, const void* addend, void* out,
@@ -905,9 +946,7 @@ static void launch_igemm_t(hipStream_t st, const void* src, const void* wmat, co
   }
   if (splits > 1) {
     if (wide) IGEMM_LAUNCH(128, 128, true) else IGEMM_LAUNCH(128, 64, true)
-    const int64_t n = (int64_t)a.M * a.Ng;  // a multiple of 4: Ng % 64 == 0
-    hipLaunchKernelGGL(splitk_epilogue_kernel<T>, dim3(ceil_div(n / 4, 256)), dim3(256), 0, st, partial, splits, n, a.Ng, bias,
-                       (const T*)addend, (T*)out, a.relu);
+    launch_splitk_epilogue<T>(st, partial, splits, a.M, a.Ng, bias, addend, out, stat_partial, a.relu);
   } else if (bm == 256) {
     if (wide) IGEMM_LAUNCH(256, 128, false) else IGEMM_LAUNCH(256, 64, false)
   } else {
@@ -961,14 +1000,14 @@ bool conv_mfma_dgrad_ok(int dt, const ConvGeom& g) {
   return g.K % bk == 0 && g.C % 64 == 0;
 }
 
-// Row blocks of the forward kernel when it can also produce the per-channel sums for BatchNorm (no depth split);
-// 0 otherwise.  From the layer shape only.
+// Row blocks over which the forward path produces the per-channel sums for BatchNorm: the blocks of the convolution
+// kernel, or of the kernel that adds the depth ranges when the depth is split.  From the layer shape only.
 int conv_mfma_fwd_stat_blocks(int dt, const ConvGeom& g) {
   PatchShape pv; PatchArgs pa{};
-  if (patch_pick(dt, g.N, g.P, g.Q, g.C, g.K, g.R, g.S, g.stride, pv, pa))
-    return pv.splits > 1 ? 0 : (pa.NT + pv.subt - 1) / pv.subt;
   const int64_t M = (int64_t)g.N * g.P * g.Q;
-  if (igemm_splits(dt, M, g.K, g.R * g.S * g.C) > 1) return 0;
+  if (patch_pick(dt, g.N, g.P, g.Q, g.C, g.K, g.R, g.S, g.stride, pv, pa))
+    return pv.splits > 1 ? ceil_div(M, SPLIT_EPI_ROWS) : (pa.NT + pv.subt - 1) / pv.subt;
+  if (igemm_splits(dt, M, g.K, g.R * g.S * g.C) > 1) return ceil_div(M, SPLIT_EPI_ROWS);
   return ceil_div(M, igemm_bm(M, g.K));
 }
 
