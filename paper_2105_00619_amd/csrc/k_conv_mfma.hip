@@ -392,8 +392,8 @@ __global__ void __launch_bounds__(256) conv_igemm_kernel(const T* __restrict__ s
 // of nine times; only the 64-byte-deep weight tile changes from tap to tap.
 //   block = 256 threads = 4 wavefronts (2 x 2); block tile = 64*MI pixel rows x BN channels; a wavefront owns 32*MI
 //   rows and BN/2 channels: MI x (BN/64) MFMA 32x32 tiles.  The rows are SUBT pixel sub-tiles of 64*MI/SUBT pixels
-//   (TI images x TR rows x TC columns each, with their own halo).  Variants: (MI 4, SUBT 2) for large layers,
-//   (2, 1) and (1, 1) so that layers with few pixels still give every CU a block.
+//   (TI images x TR rows x TC columns each, with their own halo).  Instantiated: (MI 2, SUBT 1) with 128 or 64
+//   channels and (1, 1) with 64, all small enough in LDS for two blocks per CU.
 //   LDS: 2 patch buffers [SUBT*256 positions][80 B], 3 weight stages [BN][80 B], address tables.
 //   Pipeline (one barrier per tap): the weight tile of (chunk c+1, tap t) is requested before the MFMAs of (c, t)
 //   and parked in registers until the end of step (c+1, t-1); the next chunk's patch is requested during taps 0-3
@@ -824,8 +824,8 @@ static int patch_row_pitch(const PatchArgs& a, int subt) {
 // (shape-only rule, so the choice is the same on every run).
 struct PatchShape { int mi, subt, bn, splits; };
 int g_patch_min_blocks = 64;   // tuning constants (not part of the C ABI)
-int g_patch_fill = 200;
-int g_patch_shapes = 0xf;      // bit i: candidate i allowed
+int g_patch_fill = 512;
+int g_patch_shapes = 0x7;      // bit i: candidate i allowed
 int g_patch_split = 1;         // allow the depth split
 int g_patch_halo2 = 9;         // largest staged positions : pixels ratio, times two
 int g_patch_target_small = 512;  // blocks aimed at by the depth split for the smallest block shape in fp32
@@ -834,18 +834,21 @@ static bool patch_pick(int dt, int N, int dstH, int dstW, int srcC, int Ng, int 
   if (R != 3 || S != 3 || stride != 1) return false;
   if (srcC % (dt == DT_F32 ? 16 : 32) != 0 || Ng % 64 != 0) return false;
   const int wide = Ng % 128 == 0 ? 128 : 64;
-  const PatchShape cand[4] = {{4, 2, wide, 1}, {2, 1, wide, 1}, {2, 1, 64, 1}, {1, 1, 64, 1}};
+  // Candidates, largest first.  Two co-resident blocks per CU cover each other's prologue, barriers and epilogue, and
+  // measured better than one block of twice the size at every layer of the benchmark networks, so the first
+  // candidate that gives g_patch_fill (two per CU) blocks is taken, else the one with the most blocks.
+  const PatchShape cand[3] = {{2, 1, wide, 1}, {2, 1, 64, 1}, {1, 1, 64, 1}};
   int best = -1;
   int64_t best_blocks = 0;
   PatchArgs best_geo{};
-  for (int i = 0; i < 4; ++i) {
+  for (int i = 0; i < 3; ++i) {
     if (!((g_patch_shapes >> i) & 1)) continue;
-    if (i == 2 && wide == 64) continue;  // same as candidate 1
+    if (i == 1 && wide == 64) continue;  // same as candidate 0
     const int cap = 64 * cand[i].mi / cand[i].subt;
     PatchArgs a{};
     if (!patch_geometry(N, dstH, dstW, cap, a)) continue;
     if (a.TP * 4 < cap * 3) continue;  // tile rows poorly used
-    if (a.NPOS * 2 > a.TP * g_patch_halo2) continue;  // mostly halo (2x2 images): the staged patch costs more than it saves
+    if (a.NPOS * 2 > a.TP * g_patch_halo2) continue;  // almost only halo: the staged patch costs more than it saves
     const int64_t blocks = (int64_t)((a.NT + cand[i].subt - 1) / cand[i].subt) * (Ng / cand[i].bn);
     if (blocks > best_blocks) { best = i; best_blocks = blocks; best_geo = a; }
     if (blocks >= g_patch_fill) break;
@@ -859,7 +862,7 @@ static bool patch_pick(int dt, int N, int dstH, int dstW, int srcC, int Ng, int 
   // fp32, smallest shape (one MFMA tile per wavefront, a barrier every 8 MFMAs): two co-resident blocks per CU
   // cover each other's barrier and LDS waits, which is worth the partial sums (measured 96 -> 84 us on 512->512 at 4x4)
   const int target = (shape.mi == 1 && dt == DT_F32) ? g_patch_target_small : 256;
-  if (g_patch_split && (best_blocks < g_patch_fill || best_blocks < target)) {
+  if (g_patch_split && best_blocks < target) {
     splits = (int)((target + best_blocks - 1) / best_blocks);
     if (splits > nchunks / 4) splits = nchunks / 4;
     if (splits > 4) splits = 4;
@@ -890,10 +893,7 @@ template <class T>
 static void launch_patch_t(hipStream_t st, const void* src, const void* wmat, const float* bias, const void* addend, void* out,
                            float* partial, float* stat_partial, const PatchShape& v, const PatchArgs& a) {
   const int sp = v.splits;
-  if (v.mi == 4) {
-    if (v.bn == 128) launch_patch_v<T, 128, 4, 2>(st, src, wmat, bias, addend, out, partial, stat_partial, sp, a);
-    else launch_patch_v<T, 64, 4, 2>(st, src, wmat, bias, addend, out, partial, stat_partial, sp, a);
-  } else if (v.mi == 2) {
+  if (v.mi == 2) {
     if (v.bn == 128) launch_patch_v<T, 128, 2, 1>(st, src, wmat, bias, addend, out, partial, stat_partial, sp, a);
     else launch_patch_v<T, 64, 2, 1>(st, src, wmat, bias, addend, out, partial, stat_partial, sp, a);
   } else {
