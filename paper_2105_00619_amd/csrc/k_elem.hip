@@ -57,10 +57,8 @@ __global__ void __launch_bounds__(256) colreduce_kernel(RedArgs g) {
     const T* a = static_cast<const T*>(g.a);
     const T* z = static_cast<const T*>(g.z);
     const T* ao = static_cast<const T*>(g.aout);
-    for (int64_t r = r0 + ty; r < r1; r += TY) {
-      const int64_t off = r * g.C + c0;
-      float va[V];
-      load_f32<T, V>(a + off, va);
+    // one row's contribution, from values already in registers
+    auto accumulate = [&](const float (&va)[V], const float (&vz)[V], const float (&vo)[V]) {
       if (MODE == RED_STATS) {
 #pragma unroll
         for (int i = 0; i < V; ++i) { s0[i] += va[i]; s1[i] = __fmaf_rn(va[i], va[i], s1[i]); }
@@ -68,9 +66,6 @@ __global__ void __launch_bounds__(256) colreduce_kernel(RedArgs g) {
 #pragma unroll
         for (int i = 0; i < V; ++i) s0[i] += va[i];
       } else {
-        float vz[V], vo[V];
-        load_f32<T, V>(z + off, vz);
-        if (ao) load_f32<T, V>(ao + off, vo);
 #pragma unroll
         for (int i = 0; i < V; ++i) {
           bool on = true;
@@ -80,6 +75,33 @@ __global__ void __launch_bounds__(256) colreduce_kernel(RedArgs g) {
           s0[i] += dy; s1[i] = __fmaf_rn(dy, xh, s1[i]);
         }
       }
+    };
+    // four rows per trip while four remain: their loads are all issued before the first value is used, so a thread
+    // keeps 8-12 16-byte loads in flight; the rows are still added in the same order
+    int64_t r = r0 + ty;
+    for (; r + 3 * (int64_t)TY < r1; r += 4 * (int64_t)TY) {
+      float va[4][V], vz[4][V], vo[4][V];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int64_t off = (r + (int64_t)u * TY) * g.C + c0;
+        load_f32<T, V>(a + off, va[u]);
+        if (MODE == RED_BN_BWD) {
+          load_f32<T, V>(z + off, vz[u]);
+          if (ao) load_f32<T, V>(ao + off, vo[u]);
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) accumulate(va[u], vz[u], vo[u]);
+    }
+    for (; r < r1; r += TY) {
+      const int64_t off = r * g.C + c0;
+      float va[V], vz[V], vo[V];
+      load_f32<T, V>(a + off, va);
+      if (MODE == RED_BN_BWD) {
+        load_f32<T, V>(z + off, vz);
+        if (ao) load_f32<T, V>(ao + off, vo);
+      }
+      accumulate(va, vz, vo);
     }
   }
   const int W = TX * V;
