@@ -60,6 +60,8 @@ LAYER_NETS = {
     "c3x3_256_at8": (256, 8, 16, [W.conv(256, 256), W.conv(256, 256), W.gap_linear_ce(256, 10)]),
     "c3x3_512_at4": (512, 4, 32, [W.conv(512, 512), W.conv(512, 512), W.gap_linear_ce(512, 10)]),
     "stride2_64_128": (64, 32, 4, [W.conv(64, 64), W.conv(64, 128, stride=2), W.gap_linear_ce(128, 10)]),
+    # odd image size: the stride-2 data gradient cannot be split into parity classes and takes the masked-tap path
+    "stride2_odd_15": (64, 15, 4, [W.conv(64, 64), W.conv(64, 128, stride=2), W.gap_linear_ce(128, 10)]),
     "c1x1_256_64_256": (256, 16, 4, [W.conv(256, 64, ksize=1), W.conv(64, 256, ksize=1), W.gap_linear_ce(256, 10)]),
     "basic_64_128_s2": (64, 16, 8, [W.conv(64, 64), W.basic_block(64, 128, 2), W.basic_block(128, 128),
                                     W.gap_linear_ce(128, 10)]),
