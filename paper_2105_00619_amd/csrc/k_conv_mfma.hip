@@ -976,6 +976,7 @@ static int igemm_splits(int dt, int64_t M, int Ng, int Kg) {
 }
 int conv_mfma_fwd_splits(int dt, const ConvGeom& g) {
   PatchShape v; PatchArgs pa{};
+  if (conv_pointwise_fwd_ok(dt, g)) return 1;
   if (patch_pick(dt, g.N, g.P, g.Q, g.C, g.K, g.R, g.S, g.stride, v, pa)) return v.splits;
   return igemm_splits(dt, (int64_t)g.N * g.P * g.Q, g.K, g.R * g.S * g.C);
 }
@@ -986,6 +987,7 @@ static bool dgrad_by_classes(const ConvGeom& g) {
 }
 int conv_mfma_dgrad_splits(int dt, const ConvGeom& g) {
   PatchShape v; PatchArgs pa{};
+  if (conv_pointwise_dgrad_ok(dt, g)) return 1;
   if (patch_pick(dt, g.N, g.H, g.W, g.K, g.C, g.R, g.S, g.stride, v, pa)) return v.splits;
   if (dgrad_by_classes(g)) return 1;
   return igemm_splits(dt, (int64_t)g.N * g.H * g.W, g.C, g.R * g.S * g.K);
@@ -1005,6 +1007,7 @@ bool conv_mfma_dgrad_ok(int dt, const ConvGeom& g) {
 int conv_mfma_fwd_stat_blocks(int dt, const ConvGeom& g) {
   PatchShape pv; PatchArgs pa{};
   const int64_t M = (int64_t)g.N * g.P * g.Q;
+  if (conv_pointwise_fwd_ok(dt, g)) return conv_pointwise_stat_blocks(g);
   if (patch_pick(dt, g.N, g.P, g.Q, g.C, g.K, g.R, g.S, g.stride, pv, pa))
     return pv.splits > 1 ? ceil_div(M, SPLIT_EPI_ROWS) : (pa.NT + pv.subt - 1) / pv.subt;
   if (igemm_splits(dt, M, g.K, g.R * g.S * g.C) > 1) return ceil_div(M, SPLIT_EPI_ROWS);
@@ -1016,6 +1019,10 @@ int conv_mfma_fwd_stat_blocks(int dt, const ConvGeom& g) {
 void launch_conv_fwd_mfma(hipStream_t st, int dt, const void* x, const void* w, const float* bias, void* out,
                           float* partial, float* stat_partial, int splits, const ConvGeom& g, int relu) {
   PatchShape pv; PatchArgs pa{};
+  if (conv_pointwise_fwd_ok(dt, g)) {
+    launch_conv_fwd_pointwise(st, dt, x, w, bias, out, stat_partial, g, relu);
+    return;
+  }
   if (patch_pick(dt, g.N, g.P, g.Q, g.C, g.K, g.R, g.S, g.stride, pv, pa)) {
     pa.N = g.N; pa.srcH = g.H; pa.srcW = g.W; pa.srcC = g.C; pa.dstH = g.P; pa.dstW = g.Q; pa.Ng = g.K;
     pa.pad = g.pad; pa.flip = 0; pa.relu = relu;
@@ -1030,6 +1037,10 @@ void launch_conv_fwd_mfma(hipStream_t st, int dt, const void* x, const void* w, 
 void launch_conv_dgrad_mfma(hipStream_t st, int dt, const void* dz, const void* wt, const void* addend, void* dx,
                             float* partial, int splits, const ConvGeom& g) {
   PatchShape pv; PatchArgs pa{};
+  if (conv_pointwise_dgrad_ok(dt, g)) {
+    launch_conv_dgrad_pointwise(st, dt, dz, wt, addend, dx, g);
+    return;
+  }
   if (patch_pick(dt, g.N, g.H, g.W, g.K, g.C, g.R, g.S, g.stride, pv, pa)) {
     pa.N = g.N; pa.srcH = g.P; pa.srcW = g.Q; pa.srcC = g.K; pa.dstH = g.H; pa.dstW = g.W; pa.Ng = g.C;
     pa.pad = g.R - 1 - g.pad; pa.flip = 1; pa.relu = 0;

@@ -1,0 +1,322 @@
+// 1x1 convolutions in 16-bit storage as a plain GEMM on the matrix cores (gfx950):
+//   out[m][n] = sum_c X[row(m)][c] * W[n][c]      m = output pixel, n = output channel, c = input channel
+// The rows of X are whole pixels of the NHWC source (row(m) = m for stride 1; for a strided forward convolution the
+// pixel (2p, 2q) of the same image), W is the (C_out, C_in) weight matrix for forward and its (C_in, C_out) transpose
+// for the data gradient of a stride-1 layer.  These layers move far more bytes per flop than the 3x3 ones (depth 64 to
+// 2048 only), so the kernel is built to keep HBM busy rather than the matrix cores:
+//   * block = 256 threads = 4 wavefronts (2 x 2), tile 128 rows x BN channels (BN = 128 or 64), depth step 64 bytes;
+//     40 KB of LDS and at most 168 registers per lane, so three blocks share a CU and cover each other's load
+//     latency, barriers and epilogue;
+//   * global loads run two depth steps ahead in registers, LDS is double buffered, one barrier per step;
+//   * the column tiles of one row tile get consecutive slots of the same XCD (workgroups go to the 8 XCDs round-robin
+//     by index), so the X tile is fetched from HBM once and re-read from that XCD's L2;
+//   * epilogue through LDS: bias / residual addend / ReLU in fp32, one rounding, 16-byte stores of whole rows, and the
+//     per-block channel sums of the stored values for the BatchNorm that follows.
+#include "dev_common.h"
+#include "kernels.h"
+
+namespace oseq {
+namespace {
+
+typedef __attribute__((ext_vector_type(16))) float v16f;
+typedef __attribute__((ext_vector_type(8))) __bf16 v8bf;
+typedef __attribute__((ext_vector_type(8))) _Float16 v8h;
+typedef __attribute__((ext_vector_type(4))) float v4f;
+
+template <class T> struct Mma;
+template <> struct Mma<bf16_t> {
+  typedef v8bf V;
+  __device__ static __forceinline__ v16f run(V a, V b, v16f c) { return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0); }
+};
+template <> struct Mma<f16_t> {
+  typedef v8h V;
+  __device__ static __forceinline__ v16f run(V a, V b, v16f c) { return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0); }
+};
+
+struct PwArgs {
+  int64_t M;              // output pixels
+  int Ng, Kd;             // output channels, depth (input channels)
+  int MT, NT;             // row tiles, column tiles
+  int relu;
+  int stride;             // 1, or 2: row m = (n, p, q) reads source pixel (n, 2p, 2q)
+  int dstH, dstW, srcH, srcW;
+  FastDiv div_w, div_hw;  // by dstW and dstH * dstW
+};
+
+template <int V> struct IC { static constexpr int value = V; };
+
+constexpr int PW_BM = 128;
+constexpr int PW_BK = 32;              // elements per depth step (64 bytes)
+constexpr int PW_PITCH = PW_BK + 8;    // LDS row pitch in elements (80 bytes)
+
+template <int BN> constexpr size_t pw_smem_bytes() {
+  constexpr size_t stages = (size_t)2 * (PW_BM + BN) * PW_PITCH * 2;
+  constexpr size_t epi = (size_t)(PW_BM / 2) * (BN + 4) * 4;
+  return stages > epi ? stages : epi;
+}
+
+template <class T, int BN>
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3)))
+conv1x1_kernel(const T* __restrict__ X, const T* __restrict__ W, const float* __restrict__ bias, const T* __restrict__ addend,
+               T* __restrict__ out, float* __restrict__ stat_partial, PwArgs a) {
+  typedef typename Mma<T>::V FV;
+  constexpr int BM = PW_BM, BK = PW_BK, PITCH = PW_PITCH;
+  constexpr int MI = 2, NI = BN / 64;      // 32x32 MFMA tiles per wavefront
+  constexpr int A_CH = BM * 4 / 256;       // 16-byte chunks per thread and depth step
+  constexpr int B_CH = BN * 4 / 256;
+  constexpr int STAGE = (BM + BN) * PITCH;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  T* lds = reinterpret_cast<T*>(smem_raw);
+
+  // slot s of XCD x: column tile s % NT of row tile (s / NT) * 8 + x
+  const int b = blockIdx.x, xcd = b & 7, slot = b >> 3;
+  const int nt = slot % a.NT, mt = (slot / a.NT) * 8 + xcd;
+  if (mt >= a.MT) return;
+  const int64_t m0 = (int64_t)mt * BM;
+  const int n0 = nt * BN;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1, g = lane >> 5, l32 = lane & 31;
+  const int vec = tid & 3, row0 = tid >> 2;
+  const int Kd = a.Kd;
+
+  // Rows past the last pixel read row 0; their sums are never stored.
+  const T* arow[A_CH];
+#pragma unroll
+  for (int i = 0; i < A_CH; ++i) {
+    const int64_t m = m0 + row0 + i * 64;
+    int64_t r = m < a.M ? m : 0;
+    if (a.stride != 1) {
+      const uint32_t mm = (uint32_t)r;
+      const uint32_t n = a.div_hw.div(mm), rem = mm - n * a.div_hw.d;
+      const uint32_t p = a.div_w.div(rem), q = rem - p * a.div_w.d;
+      r = ((int64_t)n * a.srcH + p * a.stride) * a.srcW + q * a.stride;
+    }
+    arow[i] = X + r * Kd + vec * 8;
+  }
+  const T* brow[B_CH];
+#pragma unroll
+  for (int i = 0; i < B_CH; ++i) brow[i] = W + (int64_t)(n0 + row0 + i * 64) * Kd + vec * 8;
+
+  Chunk ra[2][A_CH], rb[2][B_CH];
+  auto gload = [&](auto P, int kt) {
+    constexpr int p = decltype(P)::value;
+#pragma unroll
+    for (int i = 0; i < A_CH; ++i) ra[p][i] = *reinterpret_cast<const Chunk*>(arow[i] + kt * BK);
+#pragma unroll
+    for (int i = 0; i < B_CH; ++i) rb[p][i] = *reinterpret_cast<const Chunk*>(brow[i] + kt * BK);
+  };
+  auto sstore = [&](auto P, int stage) {
+    constexpr int p = decltype(P)::value;
+    T* st = lds + stage * STAGE;
+#pragma unroll
+    for (int i = 0; i < A_CH; ++i) *reinterpret_cast<Chunk*>(&st[(row0 + i * 64) * PITCH + vec * 8]) = ra[p][i];
+#pragma unroll
+    for (int i = 0; i < B_CH; ++i) *reinterpret_cast<Chunk*>(&st[(BM + row0 + i * 64) * PITCH + vec * 8]) = rb[p][i];
+  };
+
+  v16f acc[MI][NI];
+#pragma unroll
+  for (int i = 0; i < MI; ++i)
+#pragma unroll
+    for (int j = 0; j < NI; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+  // lane group g owns depth elements [16g, 16g + 16) of a step; A and B pair the same indices, so the sum is the same
+  const int afrag = (wm * 64 + l32) * PITCH + g * 16;
+  const int bfrag = (BM + wn * (BN / 2) + l32) * PITCH + g * 16;
+  auto compute = [&](int stage) {
+    const T* st = lds + stage * STAGE;
+    FV fa[MI][2], fb[NI][2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+#pragma unroll
+      for (int i = 0; i < MI; ++i) fa[i][h] = *reinterpret_cast<const FV*>(st + afrag + i * 32 * PITCH + h * 8);
+#pragma unroll
+      for (int j = 0; j < NI; ++j) fb[j][h] = *reinterpret_cast<const FV*>(st + bfrag + j * 32 * PITCH + h * 8);
+    }
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+      for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NI; ++j) acc[i][j] = Mma<T>::run(fa[i][h], fb[j][h], acc[i][j]);
+  };
+
+  // Step j: the registers of generation j & 1 (tile j) go to LDS stage j & 1 and are refilled with tile j + 2; one
+  // barrier, then the MFMAs of tile j.  A stage is rewritten two steps later, after the barrier of the step between,
+  // which every wavefront passes only when it is done reading.  The steady loop is unconditional straight-line code;
+  // the last two steps (no refill) are peeled.
+  const int n = Kd / BK;  // >= 2
+  gload(IC<0>{}, 0);
+  gload(IC<1>{}, 1);
+  int j = 0;
+  for (; j + 3 < n; j += 2) {
+    sstore(IC<0>{}, 0); gload(IC<0>{}, j + 2); __syncthreads(); compute(0);
+    sstore(IC<1>{}, 1); gload(IC<1>{}, j + 3); __syncthreads(); compute(1);
+  }
+  if (j + 2 < n) {  // odd number of steps: three left
+    sstore(IC<0>{}, 0); gload(IC<0>{}, j + 2); __syncthreads(); compute(0);
+    sstore(IC<1>{}, 1); __syncthreads(); compute(1);
+    sstore(IC<0>{}, 0); __syncthreads(); compute(0);
+  } else {
+    sstore(IC<0>{}, 0); __syncthreads(); compute(0);
+    sstore(IC<1>{}, 1); __syncthreads(); compute(1);
+  }
+
+  // ---- epilogue: the rows of one wavefront pair at a time through LDS as fp32 [64][BN + 4] ---------------------------
+  float* ep = reinterpret_cast<float*>(smem_raw);
+  constexpr int EP_PITCH = BN + 4;
+  constexpr int GROUPS = BN / 8;                 // 8-channel groups per row
+  constexpr int PER_THREAD = 64 * GROUPS / 256;  // (row, group) items per thread and pass
+  constexpr int RSTEP = 256 / GROUPS;            // rows between a thread's items
+  const int c8 = (tid % GROUPS) * 8, erow = tid / GROUPS;
+  const int col = n0 + c8;
+  float bv[8];
+#pragma unroll
+  for (int k = 0; k < 8; ++k) bv[k] = bias ? bias[col + k] : 0.f;
+  float ssum = 0.f, qsum = 0.f;  // per-channel sum and sum of squares of the values as stored (BatchNorm statistics)
+#pragma unroll
+  for (int u = 0; u < 2; ++u) {
+    __syncthreads();
+    if (wm == u) {
+#pragma unroll
+      for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int jn = 0; jn < NI; ++jn)
+#pragma unroll
+          for (int e = 0; e < 16; ++e)
+            ep[(i * 32 + 8 * (e >> 2) + 4 * g + (e & 3)) * EP_PITCH + wn * (BN / 2) + jn * 32 + l32] = acc[i][jn][e];
+    }
+    __syncthreads();
+    // all addend loads first (rows past the end read the last row), then the arithmetic and the stores
+    Chunk ad[PER_THREAD];
+    if (addend) {
+#pragma unroll
+      for (int it = 0; it < PER_THREAD; ++it) {
+        const int64_t grow = m0 + u * 64 + erow + it * RSTEP;
+        ad[it] = *reinterpret_cast<const Chunk*>(addend + (grow < a.M ? grow : a.M - 1) * a.Ng + col);
+      }
+    }
+#pragma unroll
+    for (int it = 0; it < PER_THREAD; ++it) {
+      const int row = erow + it * RSTEP;
+      const int64_t grow = m0 + u * 64 + row;
+      const v4f x0 = *reinterpret_cast<const v4f*>(&ep[row * EP_PITCH + c8]);
+      const v4f x1 = *reinterpret_cast<const v4f*>(&ep[row * EP_PITCH + c8 + 4]);
+      float v[8] = {x0[0], x0[1], x0[2], x0[3], x1[0], x1[1], x1[2], x1[3]};
+#pragma unroll
+      for (int k = 0; k < 8; ++k) v[k] += bv[k];
+      if (addend) {
+        const Vec<T, 8> av = __builtin_bit_cast(Vec<T, 8>, ad[it]);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) v[k] += to_f32(av.v[k]);
+      }
+      if (a.relu) {
+#pragma unroll
+        for (int k = 0; k < 8; ++k) v[k] = fmaxf(v[k], 0.f);
+      }
+      if (grow < a.M) store_f32<T, 8>(out + grow * a.Ng + col, v);
+    }
+    if (stat_partial) {  // thread = channel tid % BN, every (256 / BN)-th row
+      constexpr int NPART = 256 / BN;
+      const int sc = tid % BN;
+      const float sb = bias ? bias[n0 + sc] : 0.f;
+#pragma unroll 8
+      for (int r = tid / BN; r < 64; r += NPART) {
+        float v = ep[r * EP_PITCH + sc] + sb;
+        if (a.relu) v = fmaxf(v, 0.f);
+        v = to_f32(from_f32<T>(v));
+        v = m0 + u * 64 + r < a.M ? v : 0.f;
+        ssum += v; qsum = __fmaf_rn(v, v, qsum);
+      }
+    }
+  }
+  if (stat_partial) {  // the row groups of a channel are added in a fixed order
+    constexpr int NPART = 256 / BN;
+    __syncthreads();
+    ep[tid] = ssum; ep[256 + tid] = qsum;
+    __syncthreads();
+    if (tid < BN) {
+      float s0 = ep[tid], q0 = ep[256 + tid];
+#pragma unroll
+      for (int pt = 1; pt < NPART; ++pt) { s0 += ep[pt * BN + tid]; q0 += ep[256 + pt * BN + tid]; }
+      stat_partial[((int64_t)mt * 2 + 0) * a.Ng + n0 + tid] = s0;
+      stat_partial[((int64_t)mt * 2 + 1) * a.Ng + n0 + tid] = q0;
+    }
+  }
+}
+
+template <class T, int BN>
+void launch_pw_v(hipStream_t st, const void* X, const void* W, const float* bias, const void* addend, void* out,
+                 float* stat_partial, const PwArgs& a) {
+  constexpr size_t sm = pw_smem_bytes<BN>();
+  static bool attr_done = false;
+  if (!attr_done) {
+    (void)hipFuncSetAttribute((const void*)conv1x1_kernel<T, BN>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sm);
+    attr_done = true;
+  }
+  const int grid = ((a.MT + 7) / 8) * 8 * a.NT;
+  hipLaunchKernelGGL((conv1x1_kernel<T, BN>), dim3(grid), dim3(256), sm, st, (const T*)X, (const T*)W, bias, (const T*)addend,
+                     (T*)out, stat_partial, a);
+}
+
+void launch_pw(hipStream_t st, int dt, const void* X, const void* W, const float* bias, const void* addend, void* out,
+               float* stat_partial, PwArgs a) {
+  const int bn = a.Ng % 128 == 0 ? 128 : 64;
+  a.MT = ceil_div(a.M, PW_BM);
+  a.NT = a.Ng / bn;
+  if (dt == DT_BF16) {
+    if (bn == 128) launch_pw_v<bf16_t, 128>(st, X, W, bias, addend, out, stat_partial, a);
+    else launch_pw_v<bf16_t, 64>(st, X, W, bias, addend, out, stat_partial, a);
+  } else {
+    if (bn == 128) launch_pw_v<f16_t, 128>(st, X, W, bias, addend, out, stat_partial, a);
+    else launch_pw_v<f16_t, 64>(st, X, W, bias, addend, out, stat_partial, a);
+  }
+}
+
+// shapes the kernel takes: 16-bit storage, depth a multiple of the step and at least two steps, and enough blocks
+// (below half a block per CU the depth-split GEMM fills the chip better)
+bool pw_shape_ok(int dt, int64_t M, int Ng, int Kd, int min_blocks) {
+  if (dt == DT_F32 || Kd % PW_BK != 0 || Kd < 2 * PW_BK || Ng % 64 != 0) return false;
+  if (M >= ((int64_t)1 << 31)) return false;
+  const int64_t blocks = (int64_t)ceil_div(M, PW_BM) * (Ng / (Ng % 128 == 0 ? 128 : 64));
+  return blocks >= min_blocks;
+}
+
+}  // namespace
+
+int g_pointwise = 1;               // tuning switches (not part of the C ABI)
+int g_pointwise_min_blocks = 128;
+
+bool conv_pointwise_fwd_ok(int dt, const ConvGeom& g) {
+  if (!g_pointwise || g.R != 1 || g.S != 1 || g.pad != 0 || (g.stride != 1 && g.stride != 2)) return false;
+  return pw_shape_ok(dt, (int64_t)g.N * g.P * g.Q, g.K, g.C, g_pointwise_min_blocks);
+}
+bool conv_pointwise_dgrad_ok(int dt, const ConvGeom& g) {
+  if (!g_pointwise || g.R != 1 || g.S != 1 || g.pad != 0 || g.stride != 1) return false;
+  return pw_shape_ok(dt, (int64_t)g.N * g.H * g.W, g.C, g.K, g_pointwise_min_blocks);
+}
+int conv_pointwise_stat_blocks(const ConvGeom& g) { return ceil_div((int64_t)g.N * g.P * g.Q, PW_BM); }
+
+void launch_conv_fwd_pointwise(hipStream_t st, int dt, const void* x, const void* w, const float* bias, void* out,
+                               float* stat_partial, const ConvGeom& g, int relu) {
+  PwArgs a{};
+  a.M = (int64_t)g.N * g.P * g.Q; a.Ng = g.K; a.Kd = g.C; a.relu = relu; a.stride = g.stride;
+  a.dstH = g.P; a.dstW = g.Q; a.srcH = g.H; a.srcW = g.W;
+  a.div_w = make_fastdiv((uint32_t)g.Q); a.div_hw = make_fastdiv((uint32_t)(g.P * g.Q));
+  launch_pw(st, dt, x, w, bias, nullptr, out, stat_partial, a);
+}
+
+// wt: the (C_in, C_out) transpose of the weights in the compute type
+void launch_conv_dgrad_pointwise(hipStream_t st, int dt, const void* dz, const void* wt, const void* addend, void* dx,
+                                 const ConvGeom& g) {
+  PwArgs a{};
+  a.M = (int64_t)g.N * g.H * g.W; a.Ng = g.C; a.Kd = g.K; a.relu = 0; a.stride = 1;
+  a.dstH = g.H; a.dstW = g.W; a.srcH = g.P; a.srcW = g.Q;
+  a.div_w = make_fastdiv((uint32_t)g.W); a.div_hw = make_fastdiv((uint32_t)(g.H * g.W));
+  launch_pw(st, dt, dz, wt, nullptr, addend, dx, nullptr, a);
+}
+
+}  // namespace oseq

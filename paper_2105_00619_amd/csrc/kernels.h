@@ -58,6 +58,14 @@ void launch_conv_fwd_mfma(hipStream_t st, int dt, const void* x, const void* w, 
                           float* partial, float* stat_partial, int splits, const ConvGeom& g, int relu);
 void launch_conv_dgrad_mfma(hipStream_t st, int dt, const void* dz, const void* wt, const void* addend, void* dx,
                             float* partial, int splits, const ConvGeom& g);
+// 1x1 convolutions in 16-bit storage as a streaming GEMM (k_conv_pointwise.hip); used by the MFMA launchers above
+bool conv_pointwise_fwd_ok(int dt, const ConvGeom& g);
+bool conv_pointwise_dgrad_ok(int dt, const ConvGeom& g);
+int conv_pointwise_stat_blocks(const ConvGeom& g);
+void launch_conv_fwd_pointwise(hipStream_t st, int dt, const void* x, const void* w, const float* bias, void* out,
+                               float* stat_partial, const ConvGeom& g, int relu);
+void launch_conv_dgrad_pointwise(hipStream_t st, int dt, const void* dz, const void* wt, const void* addend, void* dx,
+                                 const ConvGeom& g);
 // 3x3 stride-1 weight gradient with all nine taps per block (k_conv_wgrad3x3.hip); used by the MFMA launcher below
 bool conv_wgrad3x3_ok(int dt, const ConvGeom& g);
 int conv_wgrad3x3_splits(int dt, const ConvGeom& g);
