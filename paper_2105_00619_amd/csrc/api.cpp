@@ -95,7 +95,7 @@ extern "C" int optorch_seq_create(const optorch_unit_t* units, int32_t n_units, 
     for (size_t i = 0; i + 1 < p.fops.size(); ++i)
       if (p.fops[i].kind == F_CONV && p.fops[i].stat_blocks > 0 && p.fops[i + 1].kind == F_BN_STATS &&
           p.fops[i + 1].x == p.fops[i].out)
-        p.fops[i + 1].stat_blocks = p.fops[i].stat_blocks;
+        p.fops[i + 1].stat_blocks = p.fops[i].stat_blocks, p.fops[i].stat_fold = p.fops[i + 1].stat_fold = bn_stats_fold_rows(p.fops[i].stat_blocks);
       else if (p.fops[i].kind == F_CONV)
         p.fops[i].stat_blocks = 0;
     ok = choose_segments(p) && build_schedule(p);
@@ -249,7 +249,7 @@ void run_op(const Ctx& c, const SOp& s) {
       break;
     case S_BN_STATS:
       if (s.in[1] >= 0)
-        launch_bn_stats_finalize(st, (const float*)c.at(s.in[1]), (int64_t)f.N * f.P * f.Q, f.C, f.stat_blocks, h->eps,
+        launch_bn_stats_finalize(st, (float*)c.at(s.in[1]), (int64_t)f.N * f.P * f.Q, f.C, f.stat_blocks, h->eps,
                                  h->bn_mom, c.w32(f.gamma_off), c.w32(f.beta_off), (float*)c.at(s.out[0]),
                                  (float*)(h->pbase + h->off_run) + f.rs_off);
       else

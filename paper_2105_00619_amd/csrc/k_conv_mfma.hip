@@ -1358,17 +1358,26 @@ bool conv_mfma_wgrad_ok(int dt, const ConvGeom& g) {
 }
 
 // number of pixel chunks, from the layer shape only
-int g_wgrad_blocks = 1024;  // tuning constant (not part of the C ABI)
+// 1x1 layers have only (K / 128) * (C / 128) tiles, often one or two, and hundreds of thousands of pixels: they take
+// up to 256 pixel ranges and aim at two blocks per CU (measured on the 1x1 layers of ResNet-50 at batch 128, bf16:
+// 64->64 at 56x56 64 -> 23 us, 64->256 91 -> 56 us, 256->128 126 -> 75 us, all fifteen layers 995 -> 743 us)
+int g_wgrad_blocks = 1024;  // tuning constants (not part of the C ABI)
+int g_wgrad_max_splits = 64;
+int g_wgrad_blocks_1x1 = 512;
+int g_wgrad_max_splits_1x1 = 256;
 int conv_mfma_wgrad_splits(int dt, const ConvGeom& g) {
   if (conv_wgrad3x3_ok(dt, g)) return conv_wgrad3x3_splits(dt, g);
   const int depth = dt == DT_F32 ? 16 : 32;
   const int bm = g.K % 128 == 0 ? 128 : 64, bn = g.C % 128 == 0 ? 128 : 64;
   const int64_t tiles = (int64_t)(g.K / bm) * (g.C / bn) * g.R * g.S;
   const int64_t pixels = (int64_t)g.N * g.P * g.Q;
-  int64_t want = (g_wgrad_blocks + tiles / 2) / tiles;             // aim at about that many blocks
+  const bool pointwise = g.R * g.S == 1;
+  const int target = pointwise ? g_wgrad_blocks_1x1 : g_wgrad_blocks;
+  const int cap = pointwise ? g_wgrad_max_splits_1x1 : g_wgrad_max_splits;
+  int64_t want = (target + tiles / 2) / tiles;                     // aim at about that many blocks
   const int64_t most = (pixels + 4 * depth - 1) / (4 * depth);     // at least four depth tiles per chunk
   if (want > most) want = most;
-  if (want > 64) want = 64;
+  if (want > cap) want = cap;
   return (int)(want < 1 ? 1 : want);
 }
 

@@ -162,6 +162,46 @@ __device__ __forceinline__ void partial_sums(const float* __restrict__ partial, 
   q = wave_sum(q);
 }
 
+// Many row blocks (a convolution over a large batch writes one row of sums per 128 pixels): the rows are first added
+// in STAT_FOLD_ROWS fixed ranges, with coalesced reads (thread = channel, four rows in flight per block), so that the
+// finishing kernel, which walks a channel's column with one wavefront, has only that many rows left.
+constexpr int STAT_FOLD_ROWS = 64;
+constexpr int STAT_FOLD_MIN = 512;
+__global__ void __launch_bounds__(256) stat_fold_kernel(const float* __restrict__ partial, int nblk, int C, int rows_per_range,
+                                                        float* __restrict__ folded) {
+  __shared__ double red[2][4][64];
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  const int c = blockIdx.x * 64 + tx;
+  const int b0 = blockIdx.y * rows_per_range;
+  const int b1 = b0 + rows_per_range < nblk ? b0 + rows_per_range : nblk;
+  double s = 0.0, q = 0.0;
+  if (c < C) {
+    int b = b0 + ty;
+    for (; b + 12 < b1; b += 16) {  // four rows of this thread per trip, loads first
+      float vs[4], vq[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        vs[u] = partial[((int64_t)(b + 4 * u) * 2) * C + c];
+        vq[u] = partial[((int64_t)(b + 4 * u) * 2 + 1) * C + c];
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) { s += (double)vs[u]; q += (double)vq[u]; }
+    }
+    for (; b < b1; b += 4) {
+      s += (double)partial[((int64_t)b * 2) * C + c];
+      q += (double)partial[((int64_t)b * 2 + 1) * C + c];
+    }
+  }
+  red[0][ty][tx] = s; red[1][ty][tx] = q;
+  __syncthreads();
+  if (ty == 0 && c < C) {
+    const double ts = ((red[0][0][tx] + red[0][1][tx]) + red[0][2][tx]) + red[0][3][tx];
+    const double tq = ((red[1][0][tx] + red[1][1][tx]) + red[1][2][tx]) + red[1][3][tx];
+    folded[((int64_t)blockIdx.y * 2) * C + c] = (float)ts;
+    folded[((int64_t)blockIdx.y * 2 + 1) * C + c] = (float)tq;
+  }
+}
+
 __global__ void __launch_bounds__(256) bn_stats_finalize_kernel(const float* __restrict__ partial, int nblk, int C, double m,
                                                                 float eps, float mom, const float* __restrict__ gamma,
                                                                 const float* __restrict__ beta, float* __restrict__ stats,
@@ -365,8 +405,19 @@ void launch_bn_stats(hipStream_t st, int dt, const void* z, int64_t rows, int C,
                      eps, mom, gamma, beta, stats, running);
 }
 
-void launch_bn_stats_finalize(hipStream_t st, const float* partial, int64_t rows, int C, int nblk, float eps, float mom,
+int bn_stats_fold_rows(int nblk) { return nblk >= STAT_FOLD_MIN ? STAT_FOLD_ROWS : 0; }
+
+// partial: [nblk][2][C] block sums, followed by room for [bn_stats_fold_rows(nblk)][2][C] floats
+void launch_bn_stats_finalize(hipStream_t st, float* partial, int64_t rows, int C, int nblk, float eps, float mom,
                               const float* gamma, const float* beta, float* stats, float* running) {
+  if (bn_stats_fold_rows(nblk) > 0) {
+    float* folded = partial + (int64_t)nblk * 2 * C;
+    const int per = ceil_div(nblk, STAT_FOLD_ROWS);
+    const int ranges = ceil_div(nblk, per);  // no empty range
+    hipLaunchKernelGGL(stat_fold_kernel, dim3(ceil_div(C, 64), ranges), dim3(256), 0, st, partial, nblk, C, per, folded);
+    partial = folded;
+    nblk = ranges;
+  }
   hipLaunchKernelGGL(bn_stats_finalize_kernel, dim3(ceil_div(C, 4)), dim3(256), 0, st, partial, nblk, C, (double)rows,
                      eps, mom, gamma, beta, stats, running);
 }

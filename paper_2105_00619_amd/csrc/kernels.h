@@ -14,7 +14,10 @@ void launch_cast_in(hipStream_t st, int dt, const float* x, void* out, int64_t n
 void launch_bn_stats(hipStream_t st, int dt, const void* z, int64_t rows, int C, int nblk, float* partial, float eps,
                      float mom, const float* gamma, const float* beta, float* stats, float* running);
 // the same from per-block sums a convolution already produced: partial [nblk][2][C]
-void launch_bn_stats_finalize(hipStream_t st, const float* partial, int64_t rows, int C, int nblk, float eps, float mom,
+// (with many blocks the rows are first folded into bn_stats_fold_rows(nblk) rows, written behind the block sums:
+// partial has room for [nblk + bn_stats_fold_rows(nblk)][2][C] floats)
+int bn_stats_fold_rows(int nblk);
+void launch_bn_stats_finalize(hipStream_t st, float* partial, int64_t rows, int C, int nblk, float eps, float mom,
                               const float* gamma, const float* beta, float* stats, float* running);
 void launch_bn_apply(hipStream_t st, int dt, const void* z, const float* stats, const void* skip, void* out, int64_t rows,
                      int C, int relu);

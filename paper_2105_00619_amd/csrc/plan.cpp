@@ -257,7 +257,7 @@ struct Scheduler {
         s.in[0] = cur[f.x]; s.out[0] = value_inst(f.out);
         if (f.fwd_splits > 1) s.out[1] = new_inst(-1, (uint64_t)f.fwd_splits * f.N * f.P * f.Q * f.K * 4, false);
         if (f.stat_blocks > 0 && phase != PH_REPLAY) {  // per-block channel sums for the BatchNorm that follows
-          s.out[2] = new_inst(-1, (uint64_t)f.stat_blocks * 2 * f.K * 4, false);
+          s.out[2] = new_inst(-1, (uint64_t)(f.stat_blocks + f.stat_fold) * 2 * f.K * 4, false);
           stat_ws[f.out] = s.out[2];
         }
         break;
@@ -376,7 +376,7 @@ struct Scheduler {
 
 int launches_of(const SOp& op, const FOp& f) {
   switch (op.kind) {
-    case S_BN_STATS: return f.stat_blocks > 0 ? 1 : 2;
+    case S_BN_STATS: return f.stat_blocks > 0 ? (f.stat_fold > 0 ? 2 : 1) : 2;
     case S_HEAD_FWD: return 4;
     case S_HEAD_BWD: return op.out[0] >= 0 ? 4 : 2;
     case S_BN_BWD: return 3;

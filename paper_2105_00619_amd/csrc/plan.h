@@ -50,6 +50,7 @@ struct FOp {
   int red_blocks = 1;        // row blocks of the per-channel reductions (BN statistics, BN backward)
   int stat_blocks = 0;       // > 0: the convolution's forward kernel also writes per-block channel sums for the
                              // BatchNorm that follows (that many row blocks); set on the conv and on its F_BN_STATS
+  int stat_fold = 0;         // rows into which the finishing step first folds those block sums (0: none); extra workspace
 };
 
 enum SKind {
