@@ -2,7 +2,8 @@
 //   out[m][n] = sum_c X[row(m)][c] * W[n][c]      m = output pixel, n = output channel, c = input channel
 // The rows of X are whole pixels of the NHWC source (row(m) = m for stride 1; for a strided forward convolution the
 // pixel (2p, 2q) of the same image), W is the (C_out, C_in) weight matrix for forward and its (C_in, C_out) transpose
-// for the data gradient of a stride-1 layer.  These layers move far more bytes per flop than the 3x3 ones (depth 64 to
+// for the data gradient (of a stride-2 layer on an even image: the rows are the pixels of dz, each written to pixel
+// (2p, 2q) of dx, and the three other pixels of that 2x2 cell, which no filter tap reaches, are written as zero).  These layers move far more bytes per flop than the 3x3 ones (depth 64 to
 // 2048 only), so the kernel is built to keep HBM busy rather than the matrix cores:
 //   * block = 256 threads = 4 wavefronts (2 x 2), tile 128 rows x BN channels (BN = 128 or 64), depth step 64 bytes;
 //     40 KB of LDS and at most 168 registers per lane, so three blocks share a CU and cover each other's load
@@ -39,6 +40,8 @@ struct PwArgs {
   int MT, NT;             // row tiles, column tiles
   int relu;
   int stride;             // 1, or 2: row m = (n, p, q) reads source pixel (n, 2p, 2q)
+  int scatter;            // data gradient of a stride-2 layer: row m = (n, p, q) is written to pixel (n, 2p, 2q) of a
+                          // (2 dstH) x (2 dstW) image and its three neighbours get zero (plus the addend)
   int dstH, dstW, srcH, srcW;
   FastDiv div_w, div_hw;  // by dstW and dstH * dstW
 };
@@ -192,7 +195,7 @@ conv1x1_kernel(const T* __restrict__ X, const T* __restrict__ W, const float* __
     __syncthreads();
     // all addend loads first (rows past the end read the last row), then the arithmetic and the stores
     Chunk ad[PER_THREAD];
-    if (addend) {
+    if (addend && !a.scatter) {
 #pragma unroll
       for (int it = 0; it < PER_THREAD; ++it) {
         const int64_t grow = m0 + u * 64 + erow + it * RSTEP;
@@ -208,6 +211,30 @@ conv1x1_kernel(const T* __restrict__ X, const T* __restrict__ W, const float* __
       float v[8] = {x0[0], x0[1], x0[2], x0[3], x1[0], x1[1], x1[2], x1[3]};
 #pragma unroll
       for (int k = 0; k < 8; ++k) v[k] += bv[k];
+      if (a.scatter) {
+        if (grow < a.M) {
+          const uint32_t mm = (uint32_t)grow;
+          const uint32_t n = a.div_hw.div(mm), rem = mm - n * a.div_hw.d;
+          const uint32_t p = a.div_w.div(rem), q = rem - p * a.div_w.d;
+          const int fullW = 2 * a.dstW;
+          const int64_t o00 = ((int64_t)n * (2 * a.dstH) + 2 * p) * fullW + 2 * q;
+#pragma unroll
+          for (int sib = 0; sib < 4; ++sib) {
+            const int64_t off = (o00 + (sib >> 1) * fullW + (sib & 1)) * a.Ng + col;
+            float w8[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) w8[k] = sib == 0 ? v[k] : 0.f;
+            if (addend) {
+              float a8[8];
+              load_f32<T, 8>(addend + off, a8);
+#pragma unroll
+              for (int k = 0; k < 8; ++k) w8[k] += a8[k];
+            }
+            store_f32<T, 8>(out + off, w8);
+          }
+        }
+        continue;
+      }
       if (addend) {
         const Vec<T, 8> av = __builtin_bit_cast(Vec<T, 8>, ad[it]);
 #pragma unroll
@@ -295,7 +322,12 @@ bool conv_pointwise_fwd_ok(int dt, const ConvGeom& g) {
   return pw_shape_ok(dt, (int64_t)g.N * g.P * g.Q, g.K, g.C, g_pointwise_min_blocks);
 }
 bool conv_pointwise_dgrad_ok(int dt, const ConvGeom& g) {
-  if (!g_pointwise || g.R != 1 || g.S != 1 || g.pad != 0 || g.stride != 1) return false;
+  if (!g_pointwise || g.R != 1 || g.S != 1 || g.pad != 0) return false;
+  if (g.stride == 2) {  // rows = pixels of dz, each scattered to a 2x2 cell of dx
+    if (g.H != 2 * g.P || g.W != 2 * g.Q || (int64_t)g.N * g.H * g.W >= ((int64_t)1 << 31)) return false;
+    return pw_shape_ok(dt, (int64_t)g.N * g.P * g.Q, g.C, g.K, g_pointwise_min_blocks);
+  }
+  if (g.stride != 1) return false;
   return pw_shape_ok(dt, (int64_t)g.N * g.H * g.W, g.C, g.K, g_pointwise_min_blocks);
 }
 int conv_pointwise_stat_blocks(const ConvGeom& g) { return ceil_div((int64_t)g.N * g.P * g.Q, PW_BM); }
@@ -313,9 +345,11 @@ void launch_conv_fwd_pointwise(hipStream_t st, int dt, const void* x, const void
 void launch_conv_dgrad_pointwise(hipStream_t st, int dt, const void* dz, const void* wt, const void* addend, void* dx,
                                  const ConvGeom& g) {
   PwArgs a{};
-  a.M = (int64_t)g.N * g.H * g.W; a.Ng = g.C; a.Kd = g.K; a.relu = 0; a.stride = 1;
-  a.dstH = g.H; a.dstW = g.W; a.srcH = g.P; a.srcW = g.Q;
-  a.div_w = make_fastdiv((uint32_t)g.W); a.div_hw = make_fastdiv((uint32_t)(g.H * g.W));
+  a.Ng = g.C; a.Kd = g.K; a.relu = 0; a.stride = 1;
+  a.scatter = g.stride == 2;
+  a.dstH = a.scatter ? g.P : g.H; a.dstW = a.scatter ? g.Q : g.W; a.srcH = g.P; a.srcW = g.Q;
+  a.M = (int64_t)g.N * a.dstH * a.dstW;
+  a.div_w = make_fastdiv((uint32_t)a.dstW); a.div_hw = make_fastdiv((uint32_t)(a.dstH * a.dstW));
   launch_pw(st, dt, dz, wt, nullptr, addend, dx, nullptr, a);
 }
 

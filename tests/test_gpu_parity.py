@@ -84,13 +84,15 @@ LAYER_NETS = {
     "patch_split_512_at4": (512, 4, 64, [W.conv(512, 512), W.conv(512, 512), W.gap_linear_ce(512, 10)]),
     # 1x1 layers with enough pixels for the streaming GEMM kernel of the 16-bit modes: 128- and 64-channel column
     # tiles, a ragged last row tile (52 * 18 * 18 pixels), depths of 3 and 5 steps, a strided forward layer, a layer
-    # with bias and ReLU instead of BatchNorm, and bottleneck blocks (residual sums in the data gradient)
+    # with bias and ReLU instead of BatchNorm, and bottleneck blocks (residual sums in the data gradient, also of a
+    # strided shortcut layer, whose data gradient is scattered to every second pixel)
     "pointwise_64_256_64": (64, 16, 64, [W.conv(64, 256, ksize=1), W.conv(256, 64, ksize=1), W.gap_linear_ce(64, 10)]),
     "pointwise_ragged_18": (64, 18, 52, [W.conv(64, 128, ksize=1), W.conv(128, 64, ksize=1), W.gap_linear_ce(64, 10)]),
     "pointwise_depth_96": (96, 16, 64, [W.conv(96, 128, ksize=1), W.conv(128, 96, ksize=1), W.gap_linear_ce(96, 10)]),
     "pointwise_depth_160": (160, 16, 64, [W.conv(160, 128, ksize=1), W.conv(128, 128, ksize=1), W.gap_linear_ce(128, 10)]),
     "pointwise_stride2_bias": (64, 32, 64, [W.conv(64, 64, ksize=1), W.conv(64, 128, ksize=1, stride=2),
                                             W.conv(128, 128, ksize=1, bn=False), W.gap_linear_ce(128, 10)]),
+    "pointwise_bottleneck_s2": (64, 32, 64, [W.conv(64, 64, ksize=1), W.bottleneck(64, 256, 2), W.gap_linear_ce(256, 10)]),
     "pointwise_bottlenecks": (64, 16, 64, [W.conv(64, 64, ksize=1), W.bottleneck(64, 256, 1), W.bottleneck(256, 512, 2),
                                            W.gap_linear_ce(512, 10)]),
 }
