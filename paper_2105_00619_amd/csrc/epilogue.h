@@ -1,0 +1,136 @@
+// Store half of the convolution kernels' epilogue, shared by the GEMM-shaped kernels.
+//
+// The accumulators of HR block rows lie in LDS as fp32 [HR][BN + 4].  Every thread handles, for HR * (BN / 8) / 256
+// rows, 8 consecutive channels: bias / residual addend / ReLU in fp32, one rounding, one 16-byte (fp32: two) store,
+// and optionally adds what it stored to its per-channel sum and sum of squares (the BatchNorm statistics).
+//
+// Loads and stores share one in-order counter on this hardware, so a load issued after a store cannot be waited for
+// without waiting for the store.  Hence: all loads of a pass (bias, addends) are issued before its first store, and
+// the (bias, addend) combinations are separate straight-line code paths chosen by a uniform branch, so that the
+// common path without either contains no load at all and its stores are never waited for.
+#pragma once
+#include "dev_common.h"
+
+namespace oseq {
+
+typedef __attribute__((ext_vector_type(4))) float epi_v4f;
+
+// rowoff(row): element offset of block row `row`'s first channel in the output tensor, or -1 if the row is not stored
+template <class T, int BN, int HR, bool HB, bool HA, bool STAT, class RowOff>
+__device__ __forceinline__ void epi_store_rows(const float* ep, int tid, int n0, const float* __restrict__ bias,
+                                               const T* __restrict__ addend, T* __restrict__ out, int relu, RowOff rowoff,
+                                               float (&ss)[8], float (&qq)[8]) {
+  constexpr int EP_PITCH = BN + 4;
+  constexpr int GROUPS = BN / 8;                // 8-channel groups per row
+  constexpr int PER_THREAD = HR * GROUPS / 256; // rows per thread
+  constexpr int RG = 256 / GROUPS;              // rows between a thread's rows
+  static_assert(PER_THREAD >= 1, "fewer rows than the block covers");
+  const int c8 = (tid % GROUPS) * 8, erow = tid / GROUPS;
+  const int col = n0 + c8;
+  int64_t ro[PER_THREAD];
+#pragma unroll
+  for (int it = 0; it < PER_THREAD; ++it) ro[it] = rowoff(erow + it * RG);
+  float bv[8];
+  if (HB) {
+#pragma unroll
+    for (int k = 0; k < 8; ++k) bv[k] = bias[col + k];
+  }
+  Vec<T, 8> ad[PER_THREAD];
+  if (HA) {  // rows that are not stored read the tensor's first row
+#pragma unroll
+    for (int it = 0; it < PER_THREAD; ++it)
+      ad[it] = *reinterpret_cast<const Vec<T, 8>*>(addend + (ro[it] >= 0 ? ro[it] : 0) + col);
+  }
+  // straight-line code for all rows (only the store is predicated), so that the LDS reads of the later rows are issued
+  // while the earlier ones are converted
+#pragma unroll
+  for (int it = 0; it < PER_THREAD; ++it) {
+    const int row = erow + it * RG;
+    const epi_v4f x0 = *reinterpret_cast<const epi_v4f*>(&ep[row * EP_PITCH + c8]);
+    const epi_v4f x1 = *reinterpret_cast<const epi_v4f*>(&ep[row * EP_PITCH + c8 + 4]);
+    float v[8] = {x0[0], x0[1], x0[2], x0[3], x1[0], x1[1], x1[2], x1[3]};
+    if (HB) {
+#pragma unroll
+      for (int k = 0; k < 8; ++k) v[k] += bv[k];
+    }
+    if (HA) {
+#pragma unroll
+      for (int k = 0; k < 8; ++k) v[k] += to_f32(ad[it].v[k]);
+    }
+    if (relu) {
+#pragma unroll
+      for (int k = 0; k < 8; ++k) v[k] = fmaxf(v[k], 0.f);
+    }
+    Vec<T, 8> t;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) t.v[k] = from_f32<T>(v[k]);
+    if (ro[it] >= 0) *reinterpret_cast<Vec<T, 8>*>(out + ro[it] + col) = t;
+    if (STAT) {
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        const float r = ro[it] >= 0 ? to_f32(t.v[k]) : 0.f;
+        ss[k] += r; qq[k] = __fmaf_rn(r, r, qq[k]);
+      }
+    }
+  }
+}
+
+// The uniform choice of the code path.  CAN_BIAS / CAN_ADD: whether the calling kernel is ever given a bias / an
+// addend (forward kernels have no addend, data-gradient kernels no bias); the combinations that cannot occur are not
+// compiled, which keeps their registers out of the kernel.
+template <class T, int BN, int HR, bool CAN_BIAS, bool CAN_ADD, bool STAT, class RowOff>
+__device__ __forceinline__ void epi_store_pass(const float* ep, int tid, int n0, const float* __restrict__ bias,
+                                               const T* __restrict__ addend, T* __restrict__ out, int relu, RowOff rowoff,
+                                               float (&ss)[8], float (&qq)[8]) {
+  if (CAN_BIAS && bias) {
+    if (CAN_ADD && addend) epi_store_rows<T, BN, HR, true, CAN_ADD, STAT>(ep, tid, n0, bias, addend, out, relu, rowoff, ss, qq);
+    else epi_store_rows<T, BN, HR, true, false, STAT>(ep, tid, n0, bias, addend, out, relu, rowoff, ss, qq);
+  } else {
+    if (CAN_ADD && addend) epi_store_rows<T, BN, HR, false, true, STAT>(ep, tid, n0, bias, addend, out, relu, rowoff, ss, qq);
+    else epi_store_rows<T, BN, HR, false, false, STAT>(ep, tid, n0, bias, addend, out, relu, rowoff, ss, qq);
+  }
+}
+
+// raw fp32 sums of a depth range (no epilogue arithmetic): dst + rowoff(row) + channel
+template <int BN, int HR, class RowOff>
+__device__ __forceinline__ void epi_store_partial(const float* ep, int tid, int n0, float* __restrict__ dst, RowOff rowoff) {
+  constexpr int EP_PITCH = BN + 4;
+  constexpr int GROUPS = BN / 8;
+  constexpr int PER_THREAD = HR * GROUPS / 256;
+  constexpr int RG = 256 / GROUPS;
+  const int c8 = (tid % GROUPS) * 8, erow = tid / GROUPS;
+#pragma unroll
+  for (int it = 0; it < PER_THREAD; ++it) {
+    const int row = erow + it * RG;
+    const int64_t ro = rowoff(row);
+    if (ro < 0) continue;
+    const epi_v4f x0 = *reinterpret_cast<const epi_v4f*>(&ep[row * EP_PITCH + c8]);
+    const epi_v4f x1 = *reinterpret_cast<const epi_v4f*>(&ep[row * EP_PITCH + c8 + 4]);
+    *reinterpret_cast<epi_v4f*>(dst + ro + n0 + c8) = x0;
+    *reinterpret_cast<epi_v4f*>(dst + ro + n0 + c8 + 4) = x1;
+  }
+}
+
+// Per-block channel sums from the threads' sums: the 256 / (BN / 8) row groups of a channel are added in a fixed order
+// through LDS (red: 2 * (256 / (BN / 8)) * BN floats, free to overwrite; called by all 256 threads).
+// dst_sum / dst_sq: this block's rows of the [blocks][2][channels] array, at the block's first channel.
+template <int BN>
+__device__ __forceinline__ void epi_stat_combine(float* red, int tid, const float (&ss)[8], const float (&qq)[8],
+                                                 float* __restrict__ dst_sum, float* __restrict__ dst_sq) {
+  constexpr int GROUPS = BN / 8;
+  constexpr int RG = 256 / GROUPS;
+  const int c8 = (tid % GROUPS) * 8, erow = tid / GROUPS;
+  __syncthreads();
+#pragma unroll
+  for (int k = 0; k < 8; ++k) { red[erow * BN + c8 + k] = ss[k]; red[(RG + erow) * BN + c8 + k] = qq[k]; }
+  __syncthreads();
+  if (tid < BN) {
+    float s0 = red[tid], q0 = red[RG * BN + tid];
+#pragma unroll 8
+    for (int r = 1; r < RG; ++r) { s0 += red[r * BN + tid]; q0 += red[(RG + r) * BN + tid]; }
+    dst_sum[tid] = s0;
+    dst_sq[tid] = q0;
+  }
+}
+
+}  // namespace oseq

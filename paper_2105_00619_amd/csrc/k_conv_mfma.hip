@@ -15,6 +15,7 @@
 // Each lane keeps 32 bytes of every operand row per depth tile; global loads for tile t+1 are issued before the
 // MFMAs of tile t (register prefetch + two LDS buffers, one barrier per tile).
 #include "dev_common.h"
+#include "epilogue.h"
 #include "kernels.h"
 
 namespace oseq {
@@ -295,12 +296,15 @@ __global__ void __launch_bounds__(256) conv_igemm_kernel(const T* __restrict__ s
   }
 
   // epilogue through LDS, one half of the rows (the two wavefronts with the same wm) at a time, as fp32 [row][BN+4];
-  // then every lane handles 8 consecutive channels of one pixel: bias / addend / ReLU in fp32, one rounding, one store
+  // the store half (bias / addend / ReLU, rounding, stores, BatchNorm sums) is shared with the other kernels
   {
     float* ep = reinterpret_cast<float*>(smem_raw);
     constexpr int EP_PITCH = BN + 4;
     constexpr int HR = BM / 2;  // rows per pass
-    float ssum = 0.f, qsum = 0.f;  // per-channel sum and sum of squares of the values as stored (BatchNorm statistics)
+    constexpr bool STAT = MODE == IG_FWD && !SPLIT;
+    float ss[8], qq[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) { ss[k] = 0.f; qq[k] = 0.f; }
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
       __syncthreads();
@@ -314,75 +318,28 @@ __global__ void __launch_bounds__(256) conv_igemm_kernel(const T* __restrict__ s
               ep[(i * 32 + 8 * (e >> 2) + 4 * g + (e & 3)) * EP_PITCH + wn * (BN / 2) + jn * 32 + l32] = acc[i][jn][e];
       }
       __syncthreads();
-      constexpr int GROUPS = BN / 8;
-      constexpr int PER_THREAD = HR * GROUPS / 256;
-#pragma unroll
-      for (int it = 0; it < PER_THREAD; ++it) {
-        const int id = it * 256 + tid;
-        const int row = id / GROUPS, c8 = (id - row * GROUPS) * 8;
+      auto rowoff = [&](int row) -> int64_t {
         const int grow = m0 + u * HR + row;
-        if (grow < a.M) {
-          const v4f x0 = *reinterpret_cast<const v4f*>(&ep[row * EP_PITCH + c8]);
-          const v4f x1 = *reinterpret_cast<const v4f*>(&ep[row * EP_PITCH + c8 + 4]);
-          const int col = n0 + c8;
-          int64_t opix = grow;
-          if (a.cls) {  // class-local pixel -> pixel of the full grid
-            const int ww = grow % a.dstW, t2 = grow / a.dstW;
-            const int hh = t2 % a.dstH, nn = t2 / a.dstH;
-            opix = ((int64_t)nn * a.fullH + 2 * hh + cph) * a.fullW + 2 * ww + cpw;
-          }
-          const int64_t o = opix * a.Ng + col;
-          if (SPLIT) {
-            float* dst = partial + (int64_t)blockIdx.z * a.M * a.Ng + o;
-            *reinterpret_cast<v4f*>(dst) = x0;
-            *reinterpret_cast<v4f*>(dst + 4) = x1;
-          } else {
-            float v[8] = {x0[0], x0[1], x0[2], x0[3], x1[0], x1[1], x1[2], x1[3]};
-            if (bias) {
-#pragma unroll
-              for (int k = 0; k < 8; ++k) v[k] += bias[col + k];
-            }
-            if (addend) {
-              float ad[8];
-              load_f32<T, 8>(addend + o, ad);
-#pragma unroll
-              for (int k = 0; k < 8; ++k) v[k] += ad[k];
-            }
-            if (a.relu) {
-#pragma unroll
-              for (int k = 0; k < 8; ++k) v[k] = fmaxf(v[k], 0.f);
-            }
-            store_f32<T, 8>(out + o, v);
-          }
+        if (grow >= a.M) return -1;
+        int64_t opix = grow;
+        if (a.cls) {  // class-local pixel -> pixel of the full grid
+          const int ww = grow % a.dstW, t2 = grow / a.dstW;
+          const int hh = t2 % a.dstH, nn = t2 / a.dstH;
+          opix = ((int64_t)nn * a.fullH + 2 * hh + cph) * a.fullW + 2 * ww + cpw;
         }
-      }
-      if (!SPLIT && stat_partial) {  // thread = channel tid % BN, every (256 / BN)-th row
-        constexpr int NPART = 256 / BN;
-        const int sc = tid % BN;
-        const float bv = bias ? bias[n0 + sc] : 0.f;
-#pragma unroll 8
-        for (int r = tid / BN; r < HR; r += NPART) {
-          float v = ep[r * EP_PITCH + sc] + bv;
-          if (a.relu) v = fmaxf(v, 0.f);
-          v = to_f32(from_f32<T>(v));
-          v = m0 + u * HR + r < a.M ? v : 0.f;
-          ssum += v; qsum = __fmaf_rn(v, v, qsum);
-        }
+        return opix * a.Ng;
+      };
+      if (SPLIT) {
+        epi_store_partial<BN, HR>(ep, tid, n0, partial + (int64_t)blockIdx.z * a.M * a.Ng, rowoff);
+      } else if (STAT && stat_partial) {
+        epi_store_pass<T, BN, HR, MODE == IG_FWD, MODE == IG_DGRAD, true>(ep, tid, n0, bias, addend, out, a.relu, rowoff, ss, qq);
+      } else {
+        epi_store_pass<T, BN, HR, MODE == IG_FWD, MODE == IG_DGRAD, false>(ep, tid, n0, bias, addend, out, a.relu, rowoff, ss, qq);
       }
     }
-    if (!SPLIT && stat_partial) {  // the row groups of a channel are added in a fixed order
-      constexpr int NPART = 256 / BN;
-      __syncthreads();
-      ep[tid] = ssum; ep[256 + tid] = qsum;
-      __syncthreads();
-      if (tid < BN) {
-        float s0 = ep[tid], q0 = ep[256 + tid];
-#pragma unroll
-        for (int pt = 1; pt < NPART; ++pt) { s0 += ep[pt * BN + tid]; q0 += ep[256 + pt * BN + tid]; }
-        stat_partial[((int64_t)blockIdx.x * 2 + 0) * a.Ng + n0 + tid] = s0;
-        stat_partial[((int64_t)blockIdx.x * 2 + 1) * a.Ng + n0 + tid] = q0;
-      }
-    }
+    if (STAT && stat_partial)
+      epi_stat_combine<BN>(ep, tid, ss, qq, stat_partial + ((int64_t)blockIdx.x * 2 + 0) * a.Ng + n0,
+                           stat_partial + ((int64_t)blockIdx.x * 2 + 1) * a.Ng + n0);
   }
 }
 
@@ -414,7 +371,7 @@ struct PatchArgs {
 
 constexpr int PATCH_MAX_POS = 256;  // positions per sub-tile
 
-template <class T, int BN, int MI, int SUBT>
+template <class T, int BN, int MI, int SUBT, bool STAT>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, MI == 4 ? 1 : 2)))
 conv3x3_patch_kernel(const T* __restrict__ src, const T* __restrict__ wmat, const float* __restrict__ bias,
                      const T* __restrict__ addend, T* __restrict__ out, float* __restrict__ partial,
@@ -628,12 +585,15 @@ conv3x3_patch_kernel(const T* __restrict__ src, const T* __restrict__ wmat, cons
 
   // ---- epilogue ---------------------------------------------------------------------------------------------------
   // The accumulators go through LDS (the patch buffers are free now), the rows of one wavefront pair at a time, as
-  // fp32 [row][BN + 4], so that every lane then handles 8 consecutive channels of one pixel: bias / residual addend /
-  // ReLU in fp32, one rounding, one 16-byte (fp32: two) store; a wavefront writes whole rows.
+  // fp32 [row][BN + 4]; the store half (bias / addend / ReLU, rounding, stores of whole rows, BatchNorm sums of the
+  // stored values) is shared with the other kernels.
   {
     float* ep = reinterpret_cast<float*>(smem_raw);
     constexpr int EP_PITCH = BN + 4;
-    float ssum = 0.f, qsum = 0.f;  // per-channel sum and sum of squares of the values as stored (BatchNorm statistics)
+    constexpr int HR = 32 * MI;  // rows per pass
+    float ss[8], qq[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) { ss[k] = 0.f; qq[k] = 0.f; }
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
       __syncthreads();
@@ -647,69 +607,15 @@ conv3x3_patch_kernel(const T* __restrict__ src, const T* __restrict__ wmat, cons
               ep[(i * 32 + 8 * (e >> 2) + 4 * g + (e & 3)) * EP_PITCH + wn * (BN / 2) + j * 32 + l32] = acc[i][j][e];
       }
       __syncthreads();
-      constexpr int GROUPS = BN / 8;              // 8-channel groups per row
-      constexpr int PER_THREAD = 32 * MI * GROUPS / 256;
-      static_assert(PER_THREAD >= 1, "epilogue pass smaller than the block");
-#pragma unroll
-      for (int it = 0; it < PER_THREAD; ++it) {
-        const int id = it * 256 + tid;
-        const int row = id / GROUPS, c8 = (id - row * GROUPS) * 8;
-        const int64_t ro = out_off[u * (32 * MI) + row];
-        if (ro >= 0) {
-          const v4f x0 = *reinterpret_cast<const v4f*>(&ep[row * EP_PITCH + c8]);
-          const v4f x1 = *reinterpret_cast<const v4f*>(&ep[row * EP_PITCH + c8 + 4]);
-          float v[8] = {x0[0], x0[1], x0[2], x0[3], x1[0], x1[1], x1[2], x1[3]};
-          const int col = n0c + c8;
-          if (partial) {
-            float* dst = partial + (int64_t)blockIdx.z * ((int64_t)a.N * a.dstH * a.dstW * a.Ng) + ro + col;
-            *reinterpret_cast<v4f*>(dst) = x0;
-            *reinterpret_cast<v4f*>(dst + 4) = x1;
-            continue;
-          }
-          if (bias) {
-#pragma unroll
-            for (int k = 0; k < 8; ++k) v[k] += bias[col + k];
-          }
-          if (addend) {
-            float ad[8];
-            load_f32<T, 8>(addend + ro + col, ad);
-#pragma unroll
-            for (int k = 0; k < 8; ++k) v[k] += ad[k];
-          }
-          if (a.relu) {
-#pragma unroll
-            for (int k = 0; k < 8; ++k) v[k] = fmaxf(v[k], 0.f);
-          }
-          store_f32<T, 8>(out + ro + col, v);
-        }
-      }
-      if (stat_partial) {  // thread = channel tid % BN, every (256 / BN)-th row
-        constexpr int NPART = 256 / BN;
-        const int sc = tid % BN;
-        const float bv = bias ? bias[n0c + sc] : 0.f;
-#pragma unroll 8
-        for (int r = tid / BN; r < 32 * MI; r += NPART) {
-          float v = ep[r * EP_PITCH + sc] + bv;
-          if (a.relu) v = fmaxf(v, 0.f);
-          v = to_f32(from_f32<T>(v));
-          v = out_off[u * (32 * MI) + r] >= 0 ? v : 0.f;
-          ssum += v; qsum = __fmaf_rn(v, v, qsum);
-        }
-      }
+      auto rowoff = [&](int row) -> int64_t { return out_off[u * HR + row]; };
+      if (partial)
+        epi_store_partial<BN, HR>(ep, tid, n0c, partial + (int64_t)blockIdx.z * ((int64_t)a.N * a.dstH * a.dstW * a.Ng), rowoff);
+      else
+        epi_store_pass<T, BN, HR, true, !STAT, STAT>(ep, tid, n0c, bias, addend, out, a.relu, rowoff, ss, qq);
     }
-    if (stat_partial) {  // the row groups of a channel are added in a fixed order
-      constexpr int NPART = 256 / BN;
-      __syncthreads();
-      ep[tid] = ssum; ep[256 + tid] = qsum;
-      __syncthreads();
-      if (tid < BN) {
-        float s0 = ep[tid], q0 = ep[256 + tid];
-#pragma unroll
-        for (int pt = 1; pt < NPART; ++pt) { s0 += ep[pt * BN + tid]; q0 += ep[256 + pt * BN + tid]; }
-        stat_partial[((int64_t)blockIdx.x * 2 + 0) * a.Ng + n0c + tid] = s0;
-        stat_partial[((int64_t)blockIdx.x * 2 + 1) * a.Ng + n0c + tid] = q0;
-      }
-    }
+    if (STAT)
+      epi_stat_combine<BN>(ep, tid, ss, qq, stat_partial + ((int64_t)blockIdx.x * 2 + 0) * a.Ng + n0c,
+                           stat_partial + ((int64_t)blockIdx.x * 2 + 1) * a.Ng + n0c);
   }
 }
 
@@ -881,12 +787,18 @@ static void launch_patch_v(hipStream_t st, const void* src, const void* wmat, co
   constexpr size_t sm = patch_smem_bytes<T>(BN, SUBT);
   static bool attr_done = false;
   if (!attr_done) {
-    (void)hipFuncSetAttribute((const void*)conv3x3_patch_kernel<T, BN, MI, SUBT>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sm);
+    (void)hipFuncSetAttribute((const void*)conv3x3_patch_kernel<T, BN, MI, SUBT, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sm);
+    (void)hipFuncSetAttribute((const void*)conv3x3_patch_kernel<T, BN, MI, SUBT, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sm);
     attr_done = true;
   }
-  hipLaunchKernelGGL((conv3x3_patch_kernel<T, BN, MI, SUBT>), grid, block, sm, st, (const T*)src, (const T*)wmat, bias,
-                     (const T*)addend, (T*)out, splits > 1 ? partial : (float*)nullptr, splits > 1 ? (float*)nullptr : stat_partial,
-                     a);
+  // the variant that also adds up what it stores (BatchNorm statistics) is a separate instantiation, so that the
+  // plain one carries none of its registers
+  if (splits == 1 && stat_partial)
+    hipLaunchKernelGGL((conv3x3_patch_kernel<T, BN, MI, SUBT, true>), grid, block, sm, st, (const T*)src, (const T*)wmat, bias,
+                       (const T*)addend, (T*)out, (float*)nullptr, stat_partial, a);
+  else
+    hipLaunchKernelGGL((conv3x3_patch_kernel<T, BN, MI, SUBT, false>), grid, block, sm, st, (const T*)src, (const T*)wmat, bias,
+                       (const T*)addend, (T*)out, splits > 1 ? partial : (float*)nullptr, (float*)nullptr, a);
 }
 
 template <class T>

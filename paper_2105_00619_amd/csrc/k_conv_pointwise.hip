@@ -14,6 +14,7 @@
 //   * epilogue through LDS: bias / residual addend / ReLU in fp32, one rounding, 16-byte stores of whole rows, and the
 //     per-block channel sums of the stored values for the BatchNorm that follows.
 #include "dev_common.h"
+#include "epilogue.h"
 #include "kernels.h"
 
 namespace oseq {
@@ -58,7 +59,50 @@ template <int BN> constexpr size_t pw_smem_bytes() {
   return stages > epi ? stages : epi;
 }
 
+// Data gradient of a stride-2 layer: block row r (pixel (n, p, q) of dz) goes to pixel (n, 2p, 2q) of dx, and the three
+// other pixels of that 2x2 cell get zero; with an addend every one of the four adds its own addend values (all loads
+// of a row before its stores).
 template <class T, int BN>
+__device__ __forceinline__ void scatter_rows(const float* ep, int tid, int n0, int64_t mbase, const T* __restrict__ addend,
+                                             T* __restrict__ out, const PwArgs& a) {
+  constexpr int EP_PITCH = BN + 4;
+  constexpr int GROUPS = BN / 8;
+  constexpr int PER_THREAD = 64 * GROUPS / 256;
+  constexpr int RG = 256 / GROUPS;
+  const int c8 = (tid % GROUPS) * 8, erow = tid / GROUPS;
+  const int col = n0 + c8;
+  const int fullW = 2 * a.dstW;
+#pragma unroll
+  for (int it = 0; it < PER_THREAD; ++it) {
+    const int row = erow + it * RG;
+    const int64_t grow = mbase + row;
+    if (grow >= a.M) continue;
+    const uint32_t mm = (uint32_t)grow;
+    const uint32_t n = a.div_hw.div(mm), rem = mm - n * a.div_hw.d;
+    const uint32_t p = a.div_w.div(rem), q = rem - p * a.div_w.d;
+    const int64_t o00 = ((int64_t)n * (2 * a.dstH) + 2 * p) * fullW + 2 * q;
+    const v4f x0 = *reinterpret_cast<const v4f*>(&ep[row * EP_PITCH + c8]);
+    const v4f x1 = *reinterpret_cast<const v4f*>(&ep[row * EP_PITCH + c8 + 4]);
+    float w8[4][8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) { w8[0][k] = k < 4 ? x0[k] : x1[k - 4]; w8[1][k] = 0.f; w8[2][k] = 0.f; w8[3][k] = 0.f; }
+    if (addend) {
+      Vec<T, 8> ad[4];
+#pragma unroll
+      for (int sib = 0; sib < 4; ++sib)
+        ad[sib] = *reinterpret_cast<const Vec<T, 8>*>(addend + (o00 + (sib >> 1) * fullW + (sib & 1)) * a.Ng + col);
+#pragma unroll
+      for (int sib = 0; sib < 4; ++sib)
+#pragma unroll
+        for (int k = 0; k < 8; ++k) w8[sib][k] += to_f32(ad[sib].v[k]);
+    }
+#pragma unroll
+    for (int sib = 0; sib < 4; ++sib) store_f32<T, 8>(out + (o00 + (sib >> 1) * fullW + (sib & 1)) * a.Ng + col, w8[sib]);
+  }
+}
+
+// DGRAD: the data-gradient instantiation (addend and scatter, no bias / ReLU / sums); else the forward one
+template <class T, int BN, bool DGRAD>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3)))
 conv1x1_kernel(const T* __restrict__ X, const T* __restrict__ W, const float* __restrict__ bias, const T* __restrict__ addend,
                T* __restrict__ out, float* __restrict__ stat_partial, PwArgs a) {
@@ -168,18 +212,13 @@ conv1x1_kernel(const T* __restrict__ X, const T* __restrict__ W, const float* __
     sstore(IC<1>{}, 1); __syncthreads(); compute(1);
   }
 
-  // ---- epilogue: the rows of one wavefront pair at a time through LDS as fp32 [64][BN + 4] ---------------------------
+  // ---- epilogue: the rows of one wavefront pair at a time through LDS as fp32 [64][BN + 4]; the store half (bias /
+  // addend / ReLU, rounding, stores of whole rows, BatchNorm sums) is shared with the other kernels ----------------
   float* ep = reinterpret_cast<float*>(smem_raw);
   constexpr int EP_PITCH = BN + 4;
-  constexpr int GROUPS = BN / 8;                 // 8-channel groups per row
-  constexpr int PER_THREAD = 64 * GROUPS / 256;  // (row, group) items per thread and pass
-  constexpr int RSTEP = 256 / GROUPS;            // rows between a thread's items
-  const int c8 = (tid % GROUPS) * 8, erow = tid / GROUPS;
-  const int col = n0 + c8;
-  float bv[8];
+  float ss[8], qq[8];
 #pragma unroll
-  for (int k = 0; k < 8; ++k) bv[k] = bias ? bias[col + k] : 0.f;
-  float ssum = 0.f, qsum = 0.f;  // per-channel sum and sum of squares of the values as stored (BatchNorm statistics)
+  for (int k = 0; k < 8; ++k) { ss[k] = 0.f; qq[k] = 0.f; }
 #pragma unroll
   for (int u = 0; u < 2; ++u) {
     __syncthreads();
@@ -193,114 +232,56 @@ conv1x1_kernel(const T* __restrict__ X, const T* __restrict__ W, const float* __
             ep[(i * 32 + 8 * (e >> 2) + 4 * g + (e & 3)) * EP_PITCH + wn * (BN / 2) + jn * 32 + l32] = acc[i][jn][e];
     }
     __syncthreads();
-    // all addend loads first (rows past the end read the last row), then the arithmetic and the stores
-    Chunk ad[PER_THREAD];
-    if (addend && !a.scatter) {
-#pragma unroll
-      for (int it = 0; it < PER_THREAD; ++it) {
-        const int64_t grow = m0 + u * 64 + erow + it * RSTEP;
-        ad[it] = *reinterpret_cast<const Chunk*>(addend + (grow < a.M ? grow : a.M - 1) * a.Ng + col);
-      }
-    }
-#pragma unroll
-    for (int it = 0; it < PER_THREAD; ++it) {
-      const int row = erow + it * RSTEP;
+    auto rowoff = [&](int row) -> int64_t {
       const int64_t grow = m0 + u * 64 + row;
-      const v4f x0 = *reinterpret_cast<const v4f*>(&ep[row * EP_PITCH + c8]);
-      const v4f x1 = *reinterpret_cast<const v4f*>(&ep[row * EP_PITCH + c8 + 4]);
-      float v[8] = {x0[0], x0[1], x0[2], x0[3], x1[0], x1[1], x1[2], x1[3]};
-#pragma unroll
-      for (int k = 0; k < 8; ++k) v[k] += bv[k];
-      if (a.scatter) {
-        if (grow < a.M) {
-          const uint32_t mm = (uint32_t)grow;
-          const uint32_t n = a.div_hw.div(mm), rem = mm - n * a.div_hw.d;
-          const uint32_t p = a.div_w.div(rem), q = rem - p * a.div_w.d;
-          const int fullW = 2 * a.dstW;
-          const int64_t o00 = ((int64_t)n * (2 * a.dstH) + 2 * p) * fullW + 2 * q;
-#pragma unroll
-          for (int sib = 0; sib < 4; ++sib) {
-            const int64_t off = (o00 + (sib >> 1) * fullW + (sib & 1)) * a.Ng + col;
-            float w8[8];
-#pragma unroll
-            for (int k = 0; k < 8; ++k) w8[k] = sib == 0 ? v[k] : 0.f;
-            if (addend) {
-              float a8[8];
-              load_f32<T, 8>(addend + off, a8);
-#pragma unroll
-              for (int k = 0; k < 8; ++k) w8[k] += a8[k];
-            }
-            store_f32<T, 8>(out + off, w8);
-          }
-        }
-        continue;
-      }
-      if (addend) {
-        const Vec<T, 8> av = __builtin_bit_cast(Vec<T, 8>, ad[it]);
-#pragma unroll
-        for (int k = 0; k < 8; ++k) v[k] += to_f32(av.v[k]);
-      }
-      if (a.relu) {
-#pragma unroll
-        for (int k = 0; k < 8; ++k) v[k] = fmaxf(v[k], 0.f);
-      }
-      if (grow < a.M) store_f32<T, 8>(out + grow * a.Ng + col, v);
-    }
-    if (stat_partial) {  // thread = channel tid % BN, every (256 / BN)-th row
-      constexpr int NPART = 256 / BN;
-      const int sc = tid % BN;
-      const float sb = bias ? bias[n0 + sc] : 0.f;
-#pragma unroll 8
-      for (int r = tid / BN; r < 64; r += NPART) {
-        float v = ep[r * EP_PITCH + sc] + sb;
-        if (a.relu) v = fmaxf(v, 0.f);
-        v = to_f32(from_f32<T>(v));
-        v = m0 + u * 64 + r < a.M ? v : 0.f;
-        ssum += v; qsum = __fmaf_rn(v, v, qsum);
-      }
+      return grow < a.M ? grow * a.Ng : -1;
+    };
+    if (DGRAD) {
+      if (a.scatter) scatter_rows<T, BN>(ep, tid, n0, m0 + u * 64, addend, out, a);
+      else epi_store_pass<T, BN, 64, false, true, false>(ep, tid, n0, bias, addend, out, 0, rowoff, ss, qq);
+    } else {
+      if (stat_partial) epi_store_pass<T, BN, 64, true, false, true>(ep, tid, n0, bias, addend, out, a.relu, rowoff, ss, qq);
+      else epi_store_pass<T, BN, 64, true, false, false>(ep, tid, n0, bias, addend, out, a.relu, rowoff, ss, qq);
     }
   }
-  if (stat_partial) {  // the row groups of a channel are added in a fixed order
-    constexpr int NPART = 256 / BN;
-    __syncthreads();
-    ep[tid] = ssum; ep[256 + tid] = qsum;
-    __syncthreads();
-    if (tid < BN) {
-      float s0 = ep[tid], q0 = ep[256 + tid];
-#pragma unroll
-      for (int pt = 1; pt < NPART; ++pt) { s0 += ep[pt * BN + tid]; q0 += ep[256 + pt * BN + tid]; }
-      stat_partial[((int64_t)mt * 2 + 0) * a.Ng + n0 + tid] = s0;
-      stat_partial[((int64_t)mt * 2 + 1) * a.Ng + n0 + tid] = q0;
-    }
-  }
+  if (!DGRAD && stat_partial)
+    epi_stat_combine<BN>(ep, tid, ss, qq, stat_partial + ((int64_t)mt * 2 + 0) * a.Ng + n0,
+                         stat_partial + ((int64_t)mt * 2 + 1) * a.Ng + n0);
 }
 
-template <class T, int BN>
+template <class T, int BN, bool DGRAD>
 void launch_pw_v(hipStream_t st, const void* X, const void* W, const float* bias, const void* addend, void* out,
                  float* stat_partial, const PwArgs& a) {
   constexpr size_t sm = pw_smem_bytes<BN>();
   static bool attr_done = false;
   if (!attr_done) {
-    (void)hipFuncSetAttribute((const void*)conv1x1_kernel<T, BN>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sm);
+    (void)hipFuncSetAttribute((const void*)conv1x1_kernel<T, BN, DGRAD>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sm);
     attr_done = true;
   }
   const int grid = ((a.MT + 7) / 8) * 8 * a.NT;
-  hipLaunchKernelGGL((conv1x1_kernel<T, BN>), dim3(grid), dim3(256), sm, st, (const T*)X, (const T*)W, bias, (const T*)addend,
-                     (T*)out, stat_partial, a);
+  hipLaunchKernelGGL((conv1x1_kernel<T, BN, DGRAD>), dim3(grid), dim3(256), sm, st, (const T*)X, (const T*)W, bias,
+                     (const T*)addend, (T*)out, stat_partial, a);
 }
 
-void launch_pw(hipStream_t st, int dt, const void* X, const void* W, const float* bias, const void* addend, void* out,
-               float* stat_partial, PwArgs a) {
+template <class T>
+void launch_pw_t(hipStream_t st, bool dgrad, int bn, const void* X, const void* W, const float* bias, const void* addend,
+                 void* out, float* stat_partial, const PwArgs& a) {
+  if (dgrad) {
+    if (bn == 128) launch_pw_v<T, 128, true>(st, X, W, bias, addend, out, stat_partial, a);
+    else launch_pw_v<T, 64, true>(st, X, W, bias, addend, out, stat_partial, a);
+  } else {
+    if (bn == 128) launch_pw_v<T, 128, false>(st, X, W, bias, addend, out, stat_partial, a);
+    else launch_pw_v<T, 64, false>(st, X, W, bias, addend, out, stat_partial, a);
+  }
+}
+
+void launch_pw(hipStream_t st, int dt, bool dgrad, const void* X, const void* W, const float* bias, const void* addend,
+               void* out, float* stat_partial, PwArgs a) {
   const int bn = a.Ng % 128 == 0 ? 128 : 64;
   a.MT = ceil_div(a.M, PW_BM);
   a.NT = a.Ng / bn;
-  if (dt == DT_BF16) {
-    if (bn == 128) launch_pw_v<bf16_t, 128>(st, X, W, bias, addend, out, stat_partial, a);
-    else launch_pw_v<bf16_t, 64>(st, X, W, bias, addend, out, stat_partial, a);
-  } else {
-    if (bn == 128) launch_pw_v<f16_t, 128>(st, X, W, bias, addend, out, stat_partial, a);
-    else launch_pw_v<f16_t, 64>(st, X, W, bias, addend, out, stat_partial, a);
-  }
+  if (dt == DT_BF16) launch_pw_t<bf16_t>(st, dgrad, bn, X, W, bias, addend, out, stat_partial, a);
+  else launch_pw_t<f16_t>(st, dgrad, bn, X, W, bias, addend, out, stat_partial, a);
 }
 
 // shapes the kernel takes: 16-bit storage, depth a multiple of the step and at least two steps, and enough blocks
@@ -338,7 +319,7 @@ void launch_conv_fwd_pointwise(hipStream_t st, int dt, const void* x, const void
   a.M = (int64_t)g.N * g.P * g.Q; a.Ng = g.K; a.Kd = g.C; a.relu = relu; a.stride = g.stride;
   a.dstH = g.P; a.dstW = g.Q; a.srcH = g.H; a.srcW = g.W;
   a.div_w = make_fastdiv((uint32_t)g.Q); a.div_hw = make_fastdiv((uint32_t)(g.P * g.Q));
-  launch_pw(st, dt, x, w, bias, nullptr, out, stat_partial, a);
+  launch_pw(st, dt, false, x, w, bias, nullptr, out, stat_partial, a);
 }
 
 // wt: the (C_in, C_out) transpose of the weights in the compute type
@@ -350,7 +331,7 @@ void launch_conv_dgrad_pointwise(hipStream_t st, int dt, const void* dz, const v
   a.dstH = a.scatter ? g.P : g.H; a.dstW = a.scatter ? g.Q : g.W; a.srcH = g.P; a.srcW = g.Q;
   a.M = (int64_t)g.N * a.dstH * a.dstW;
   a.div_w = make_fastdiv((uint32_t)a.dstW); a.div_hw = make_fastdiv((uint32_t)(a.dstH * a.dstW));
-  launch_pw(st, dt, dz, wt, nullptr, addend, dx, nullptr, a);
+  launch_pw(st, dt, true, dz, wt, nullptr, addend, dx, nullptr, a);
 }
 
 }  // namespace oseq
