@@ -250,7 +250,18 @@ __global__ void __launch_bounds__(256) bias_finalize_kernel(const float* __restr
 }
 
 // ------------------------------------------------------------- BN apply -----
-template <class T, int V>
+// The backward apply kernel is tiled like the column reductions: a thread owns V consecutive channels, keeps their
+// per-channel constants in registers and walks the rows of its block (blockIdx.x) with stride TY, four rows per trip
+// with all loads of the trip issued before its first store (loads and stores share one in-order counter).  The
+// optional tensors are template parameters, so that each variant is straight-line code (also in the forward kernel).
+struct RowArgs {
+  int64_t rows;
+  int C, relu, rows_per_block;
+};
+
+// (the forward apply kernel, with one load and one store stream, measured faster as one group of V channels per
+// thread; its per-channel constants are fetched as whole vectors)
+template <class T, int V, bool SKIP>
 __global__ void __launch_bounds__(256) bn_apply_kernel(const T* __restrict__ z, const float* __restrict__ stats,
                                                        const T* __restrict__ skip, T* __restrict__ out, int64_t groups,
                                                        int C, int relu) {
@@ -259,45 +270,83 @@ __global__ void __launch_bounds__(256) bn_apply_kernel(const T* __restrict__ z, 
   const int CG = C / V;
   const int c0 = (int)(i % CG) * V;
   const int64_t off = i * V;
-  float vz[V], vs[V], vo[V];
+  float vz[V], vs[V], vo[V], scale[V], shift[V];
   load_f32<T, V>(z + off, vz);
-  if (skip) load_f32<T, V>(skip + off, vs);
+  if (SKIP) load_f32<T, V>(skip + off, vs);
+  load_f32<float, V>(stats + 2 * C + c0, scale);
+  load_f32<float, V>(stats + 3 * C + c0, shift);
 #pragma unroll
   for (int k = 0; k < V; ++k) {
-    float y = bn_affine(vz[k], stats[2 * C + c0 + k], stats[3 * C + c0 + k]);
-    if (skip) y = __fadd_rn(y, vs[k]);
+    float y = bn_affine(vz[k], scale[k], shift[k]);
+    if (SKIP) y = __fadd_rn(y, vs[k]);
     vo[k] = relu ? fmaxf(y, 0.f) : y;
   }
   store_f32<T, V>(out + off, vo);
 }
 
-template <class T, int V>
+// AOUT: the ReLU mask comes from the block output (a residual sum) instead of being rebuilt from z; DSKIP: the masked
+// gradient is also written out for the skip branch
+template <class T, int V, bool AOUT, bool DSKIP>
 __global__ void __launch_bounds__(256) bn_bwd_apply_kernel(const T* __restrict__ da, const T* __restrict__ z,
                                                            const T* __restrict__ aout, const float* __restrict__ stats,
                                                            const float* __restrict__ coef, T* __restrict__ dz,
-                                                           T* __restrict__ dskip, int64_t groups, int C, int relu) {
-  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= groups) return;
-  const int CG = C / V;
-  const int c0 = (int)(i % CG) * V;
-  const int64_t off = i * V;
-  float va[V], vz[V], vo[V], rz[V], rs[V];
-  load_f32<T, V>(da + off, va);
-  load_f32<T, V>(z + off, vz);
-  if (aout) load_f32<T, V>(aout + off, vo);
+                                                           T* __restrict__ dskip, RowArgs g) {
+  const int CG = g.C / V;
+  const int TX = CG < 256 ? CG : 256;
+  const int TY = 256 / TX;
+  const int tx = threadIdx.x % TX, ty = threadIdx.x / TX;
+  const int cg = blockIdx.y * TX + tx;
+  if (cg >= CG || ty >= TY) return;
+  const int c0 = cg * V;
+  float mean[V], rstd[V], scale[V], shift[V], cb[V], cg2[V];
 #pragma unroll
   for (int k = 0; k < V; ++k) {
     const int c = c0 + k;
-    const float mean = stats[c], rstd = stats[C + c], scale = stats[2 * C + c], shift = stats[3 * C + c];
-    bool on = true;
-    if (relu) on = aout ? (vo[k] > 0.f) : (bn_affine(vz[k], scale, shift) > 0.f);
-    const float dy = on ? va[k] : 0.f;
-    const float xh = (vz[k] - mean) * rstd;
-    rz[k] = scale * (dy - coef[c] - xh * coef[C + c]);
-    rs[k] = dy;
+    mean[k] = stats[c]; rstd[k] = stats[g.C + c]; scale[k] = stats[2 * g.C + c]; shift[k] = stats[3 * g.C + c];
+    cb[k] = coef[c]; cg2[k] = coef[g.C + c];
   }
-  store_f32<T, V>(dz + off, rz);
-  if (dskip) store_f32<T, V>(dskip + off, rs);
+  const int64_t r0 = (int64_t)blockIdx.x * g.rows_per_block;
+  const int64_t r1 = r0 + g.rows_per_block < g.rows ? r0 + g.rows_per_block : g.rows;
+  auto one = [&](const float (&va)[V], const float (&vz)[V], const float (&vo)[V], float (&rz)[V], float (&rs)[V]) {
+#pragma unroll
+    for (int k = 0; k < V; ++k) {
+      bool on = true;
+      if (g.relu) on = AOUT ? (vo[k] > 0.f) : (bn_affine(vz[k], scale[k], shift[k]) > 0.f);
+      const float dy = on ? va[k] : 0.f;
+      const float xh = (vz[k] - mean[k]) * rstd[k];
+      rz[k] = scale[k] * (dy - cb[k] - xh * cg2[k]);
+      rs[k] = dy;
+    }
+  };
+  int64_t r = r0 + ty;
+  for (; r + 3 * (int64_t)TY < r1; r += 4 * (int64_t)TY) {
+    float va[4][V], vz[4][V], vo[4][V], rz[4][V], rs[4][V];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int64_t off = (r + (int64_t)u * TY) * g.C + c0;
+      load_f32<T, V>(da + off, va[u]);
+      load_f32<T, V>(z + off, vz[u]);
+      if (AOUT) load_f32<T, V>(aout + off, vo[u]);
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) one(va[u], vz[u], vo[u], rz[u], rs[u]);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int64_t off = (r + (int64_t)u * TY) * g.C + c0;
+      store_f32<T, V>(dz + off, rz[u]);
+      if (DSKIP) store_f32<T, V>(dskip + off, rs[u]);
+    }
+  }
+  for (; r < r1; r += TY) {
+    const int64_t off = r * g.C + c0;
+    float va[V], vz[V], vo[V], rz[V], rs[V];
+    load_f32<T, V>(da + off, va);
+    load_f32<T, V>(z + off, vz);
+    if (AOUT) load_f32<T, V>(aout + off, vo);
+    one(va, vz, vo, rz, rs);
+    store_f32<T, V>(dz + off, rz);
+    if (DSKIP) store_f32<T, V>(dskip + off, rs);
+  }
 }
 
 template <class T, int V>
@@ -422,12 +471,27 @@ void launch_bn_stats_finalize(hipStream_t st, float* partial, int64_t rows, int 
                      eps, mom, gamma, beta, stats, running);
 }
 
+// Row blocks of the apply kernels: four rows per thread (one trip) when that still leaves about four blocks per CU, else
+// fewer (small tensors), from the shape only.
+static void row_tiling(int64_t rows, int C, int V, RowArgs& g, dim3& grid) {
+  const int CG = C / V;
+  const int TX = CG < 256 ? CG : 256;
+  const int TY = 256 / TX;
+  const int ytiles = ceil_div(CG, TX);
+  int per_thread = 4;
+  while (per_thread > 1 && (int64_t)ceil_div(rows, (int64_t)TY * per_thread) * ytiles < 1024) per_thread /= 2;
+  g.rows = rows; g.C = C; g.rows_per_block = TY * per_thread;
+  grid = dim3(ceil_div(rows, g.rows_per_block), ytiles);
+}
+
 void launch_bn_apply(hipStream_t st, int dt, const void* z, const float* stats, const void* skip, void* out, int64_t rows,
                      int C, int relu) {
-#define CALL(T, V)                                                                                                   \
-  { const int64_t groups = rows * (C / V);                                                                            \
-    hipLaunchKernelGGL((bn_apply_kernel<T, V>), dim3(ceil_div(groups, 256)), dim3(256), 0, st, (const T*)z, stats,    \
-                       (const T*)skip, (T*)out, groups, C, relu); }
+#define CALL(T, V)                                                                                                    \
+  { const int64_t groups = rows * (C / V);                                                                             \
+    if (skip) hipLaunchKernelGGL((bn_apply_kernel<T, V, true>), dim3(ceil_div(groups, 256)), dim3(256), 0, st,         \
+                                 (const T*)z, stats, (const T*)skip, (T*)out, groups, C, relu);                        \
+    else hipLaunchKernelGGL((bn_apply_kernel<T, V, false>), dim3(ceil_div(groups, 256)), dim3(256), 0, st,             \
+                            (const T*)z, stats, (const T*)skip, (T*)out, groups, C, relu); }
   DISPATCH_TV(dt, C, CALL);
 #undef CALL
 }
@@ -440,12 +504,16 @@ void launch_bn_bwd(hipStream_t st, int dt, const void* da, const void* z, const 
   float* coef = ws + (int64_t)nblk * 2 * C;
   hipLaunchKernelGGL(bn_bwd_finalize_kernel, dim3(ceil_div(C, 4)), dim3(256), 0, st, ws, nblk, C, (double)rows, dgamma,
                      dbeta, coef);
+#define APPLY(T, V, AO, DS)                                                                                             \
+  hipLaunchKernelGGL((bn_bwd_apply_kernel<T, V, AO, DS>), grid, dim3(256), 0, st, (const T*)da, (const T*)z,             \
+                     (const T*)aout, stats, coef, (T*)dz, (T*)dskip, ra)
 #define CALL(T, V)                                                                                                      \
-  { const int64_t groups = rows * (C / V);                                                                               \
-    hipLaunchKernelGGL((bn_bwd_apply_kernel<T, V>), dim3(ceil_div(groups, 256)), dim3(256), 0, st, (const T*)da,         \
-                       (const T*)z, (const T*)aout, stats, coef, (T*)dz, (T*)dskip, groups, C, relu); }
+  { RowArgs ra{}; dim3 grid; row_tiling(rows, C, V, ra, grid); ra.relu = relu;                                           \
+    if (aout) { if (dskip) APPLY(T, V, true, true); else APPLY(T, V, true, false); }                                     \
+    else { if (dskip) APPLY(T, V, false, true); else APPLY(T, V, false, false); } }
   DISPATCH_TV(dt, C, CALL);
 #undef CALL
+#undef APPLY
 }
 
 void launch_relu_bwd(hipStream_t st, int dt, const void* da, const void* a, void* dz, int64_t rows, int C) {
