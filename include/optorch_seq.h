@@ -137,10 +137,11 @@ int optorch_seq_step(optorch_seq_t* h, const float* x_dev, const int32_t* y_dev,
  * replay (recomputation) of non-last segments. */
 int optorch_seq_schedule_info(const optorch_seq_t* h, int32_t* n_launch_records, int32_t* n_replay_records);
 
-/* Per-kernel-class timing for roofline figures.  While enabled, optorch_seq_step brackets every schedule
- * entry with a pair of HIP events on the step's stream; nothing is read back until optorch_seq_profile_read.
+/* Per-kernel-class timing for roofline figures.  While enabled, every kernel launch of optorch_seq_step carries a
+ * start and a stop HIP event of its own (time stamps of the dispatch itself, i.e. the kernel's duration as a kernel
+ * trace reports it); nothing is read back until optorch_seq_profile_read.
  * Classes are indexed by optorch_kernel_class_t.  For each class the read returns, summed over all profiled
- * steps since the last enable: kernel launches, schedule entries, GPU milliseconds between the entry's two events,
+ * steps since the last enable: kernel launches, schedule entries, GPU milliseconds (sum of the launches' durations),
  * algorithmic FLOPs (convolutions: 2 x output pixels x C_out x kh x kw x C_in for each of forward, data gradient
  * and weight gradient; 0 for the memory-bound classes) and algorithmic HBM bytes (every operand read once, every
  * result written once, at the storage type).  All out pointers are host arrays of OPTORCH_N_KERNEL_CLASSES. */
@@ -150,9 +151,9 @@ typedef enum {
   OPTORCH_K_RELU_BIAS_BWD = 9, OPTORCH_K_OPTIMIZER = 10, OPTORCH_N_KERNEL_CLASSES = 11
 } optorch_kernel_class_t;
 int optorch_seq_profile_enable(optorch_seq_t* h, int32_t enable);
-/* Restricts the event pairs to the classes whose bit (1u << optorch_kernel_class_t) is set in class_mask; all
- * classes by default.  Events cost host and GPU front-end time, so timing one class perturbs a step far less
- * than timing all of them.  Takes effect from the next step; call optorch_seq_profile_enable to reset the sums. */
+/* Restricts the timing to the classes whose bit (1u << optorch_kernel_class_t) is set in class_mask; all
+ * classes by default.  A timed launch costs host and GPU front-end time (about 5 us), so timing one class
+ * perturbs a step far less than timing all of them.  Takes effect from the next step; call optorch_seq_profile_enable to reset the sums. */
 int optorch_seq_profile_select(optorch_seq_t* h, uint32_t class_mask);
 int optorch_seq_profile_read(optorch_seq_t* h, int32_t* steps, uint64_t* launches, uint64_t* entries, double* gpu_ms,
                              double* flops, double* bytes);

@@ -9,10 +9,15 @@
 #include <vector>
 
 #include "kernels.h"
+#include "launch.h"
 #include "optorch_seq.h"
 #include "plan.h"
 
 using namespace oseq;
+
+namespace oseq {
+thread_local LaunchTimer g_launch_timer;
+}
 
 struct optorch_seq {
   Plan plan;
@@ -27,9 +32,9 @@ struct optorch_seq {
   bool dynamic_scale = false;
   float* host_rb = nullptr;  // pinned read-back buffer: loss + flags
   mutable std::string err;
-  // profiling: event pairs per schedule entry, harvested on read
+  // profiling: an event pair per kernel launch of the timed entries, harvested on read
   bool profiling = false;
-  uint32_t prof_mask = 0xffffffffu;  // kernel classes whose entries are bracketed by events
+  uint32_t prof_mask = 0xffffffffu;  // kernel classes whose launches are timed
   std::vector<hipEvent_t> ev_pool;
   size_t ev_used = 0;
   std::vector<int> ev_class;  // class of pair i
@@ -357,6 +362,8 @@ hipEvent_t next_event(optorch_seq_t* h) {
   return h->ev_pool[h->ev_used++];
 }
 
+hipEvent_t next_event_cb(void* ctx) { return next_event(static_cast<optorch_seq_t*>(ctx)); }
+
 void harvest(optorch_seq_t* h) {
   for (size_t i = 0; i + 1 < h->ev_used; i += 2) {
     float ms = 0.f;
@@ -454,34 +461,34 @@ extern "C" int optorch_seq_step(optorch_seq_t* h, const float* x_dev, const int3
   for (size_t si = 0; si < h->plan.sched.size(); ++si) {
     const SOp& s = h->plan.sched[si];
     if (!s.live) continue;
-    hipEvent_t e0 = nullptr, e1 = nullptr;
-    if (prof && ((h->prof_mask >> class_of(s.kind)) & 1u) && (e0 = next_event(h)) && (e1 = next_event(h)))
-      (void)hipEventRecord(e0, st);
+    const bool timed = prof && ((h->prof_mask >> class_of(s.kind)) & 1u);
+    const size_t ev0 = h->ev_used;
+    if (timed) g_launch_timer = LaunchTimer{true, next_event_cb, h};  // every launch of the entry carries its own events
     run_op(c, s);
-    if (e1) {
-      (void)hipEventRecord(e1, st);
+    if (timed) {
+      g_launch_timer.on = false;
       const int k = class_of(s.kind);
       double fl, by;
       work_of(h, s, &fl, &by);
-      h->ev_class.push_back(k);
-      h->ev_entry.push_back((int)si);
-      h->prof_launches[k] += launches_of(s, h->plan.fops[s.fop]);
+      const size_t pairs = (h->ev_used - ev0) / 2;
+      for (size_t q = 0; q < pairs; ++q) { h->ev_class.push_back(k); h->ev_entry.push_back((int)si); }
+      h->prof_launches[k] += pairs;
       h->prof_entries[k] += 1; h->prof_flops[k] += fl; h->prof_bytes[k] += by;
     }
   }
   const int64_t P = (int64_t)h->plan.n_params;
   {
-    hipEvent_t e0 = nullptr, e1 = nullptr;
-    if (prof && ((h->prof_mask >> OPTORCH_K_OPTIMIZER) & 1u) && (e0 = next_event(h)) && (e1 = next_event(h)))
-      (void)hipEventRecord(e0, st);
+    const bool timed = prof && ((h->prof_mask >> OPTORCH_K_OPTIMIZER) & 1u);
+    const size_t ev0 = h->ev_used;
+    if (timed) g_launch_timer = LaunchTimer{true, next_event_cb, h};
     launch_optim(st, h->dt, c.w32(0), (float*)(h->pbase + h->off_v), c.g32(0), h->pbase + h->off_h, grads_dev, P, lr,
                  h->momentum, 1.f / h->scale, c.flags());
-    if (e1) {
-      (void)hipEventRecord(e1, st);
+    if (timed) {
+      g_launch_timer.on = false;
       const int k = OPTORCH_K_OPTIMIZER;
-      h->ev_class.push_back(k);
-      h->ev_entry.push_back(-1);
-      h->prof_launches[k] += 2; h->prof_entries[k] += 1;
+      const size_t pairs = (h->ev_used - ev0) / 2;
+      for (size_t q = 0; q < pairs; ++q) { h->ev_class.push_back(k); h->ev_entry.push_back(-1); }
+      h->prof_launches[k] += pairs; h->prof_entries[k] += 1;
       // read g (check), read g, w [, v], write w [, v] [, 16-bit copy] [, unscaled g]
       h->prof_bytes[k] += (double)P * (4 + 12 + (h->momentum != 0.f ? 8 : 0) + (h->dt != DT_F32 ? 2 : 0) + (grads_dev ? 4 : 0));
     }

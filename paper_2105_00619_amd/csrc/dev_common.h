@@ -4,6 +4,7 @@
 #include <stdint.h>
 
 #include "kernels.h"
+#include "launch.h"
 
 namespace oseq {
 

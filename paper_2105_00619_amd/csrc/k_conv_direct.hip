@@ -378,10 +378,10 @@ static void launch_fwd_smallc_t(hipStream_t st, const void* x, const void* w, co
   dim3 grid(ceil_div((int64_t)g.N * g.P * g.Q, 128), ceil_div(g.K, 64)), block(256);
   const FastDiv dq = make_fastdiv((uint32_t)g.Q), dpq = make_fastdiv((uint32_t)(g.P * g.Q));
   switch (g.C) {
-    case 1: hipLaunchKernelGGL((conv_fwd_smallc_kernel<T, 1>), grid, block, 0, st, (const T*)x, (const T*)w, bias, (T*)out, g, relu, dq, dpq); break;
-    case 2: hipLaunchKernelGGL((conv_fwd_smallc_kernel<T, 2>), grid, block, 0, st, (const T*)x, (const T*)w, bias, (T*)out, g, relu, dq, dpq); break;
-    case 3: hipLaunchKernelGGL((conv_fwd_smallc_kernel<T, 3>), grid, block, 0, st, (const T*)x, (const T*)w, bias, (T*)out, g, relu, dq, dpq); break;
-    default: hipLaunchKernelGGL((conv_fwd_smallc_kernel<T, 4>), grid, block, 0, st, (const T*)x, (const T*)w, bias, (T*)out, g, relu, dq, dpq); break;
+    case 1: OSEQ_LAUNCH((conv_fwd_smallc_kernel<T, 1>), grid, block, 0, st, (const T*)x, (const T*)w, bias, (T*)out, g, relu, dq, dpq); break;
+    case 2: OSEQ_LAUNCH((conv_fwd_smallc_kernel<T, 2>), grid, block, 0, st, (const T*)x, (const T*)w, bias, (T*)out, g, relu, dq, dpq); break;
+    case 3: OSEQ_LAUNCH((conv_fwd_smallc_kernel<T, 3>), grid, block, 0, st, (const T*)x, (const T*)w, bias, (T*)out, g, relu, dq, dpq); break;
+    default: OSEQ_LAUNCH((conv_fwd_smallc_kernel<T, 4>), grid, block, 0, st, (const T*)x, (const T*)w, bias, (T*)out, g, relu, dq, dpq); break;
   }
 }
 
@@ -401,12 +401,12 @@ void launch_conv_wgrad_smallc(hipStream_t st, int dt, const void* x, const void*
   float* dst = splits > 1 ? partial : dw;
   dim3 grid(splits), block(256);
   const FastDiv dq = make_fastdiv((uint32_t)g.Q), dpq = make_fastdiv((uint32_t)(g.P * g.Q));
-  if (dt == DT_F32) hipLaunchKernelGGL(conv_wgrad_smallc_kernel<float>, grid, block, 0, st, (const float*)x, (const float*)dz, dst, g, chunk, dq, dpq);
-  else if (dt == DT_BF16) hipLaunchKernelGGL(conv_wgrad_smallc_kernel<bf16_t>, grid, block, 0, st, (const bf16_t*)x, (const bf16_t*)dz, dst, g, chunk, dq, dpq);
-  else hipLaunchKernelGGL(conv_wgrad_smallc_kernel<f16_t>, grid, block, 0, st, (const f16_t*)x, (const f16_t*)dz, dst, g, chunk, dq, dpq);
+  if (dt == DT_F32) OSEQ_LAUNCH(conv_wgrad_smallc_kernel<float>, grid, block, 0, st, (const float*)x, (const float*)dz, dst, g, chunk, dq, dpq);
+  else if (dt == DT_BF16) OSEQ_LAUNCH(conv_wgrad_smallc_kernel<bf16_t>, grid, block, 0, st, (const bf16_t*)x, (const bf16_t*)dz, dst, g, chunk, dq, dpq);
+  else OSEQ_LAUNCH(conv_wgrad_smallc_kernel<f16_t>, grid, block, 0, st, (const f16_t*)x, (const f16_t*)dz, dst, g, chunk, dq, dpq);
   if (splits > 1) {
     const int64_t n = (int64_t)g.K * g.R * g.S * g.C;
-    hipLaunchKernelGGL(wave_reduce_kernel, dim3(ceil_div(n, 4)), dim3(256), 0, st, partial, dw, n, splits);
+    OSEQ_LAUNCH(wave_reduce_kernel, dim3(ceil_div(n, 4)), dim3(256), 0, st, partial, dw, n, splits);
   }
 }
 
@@ -414,18 +414,18 @@ void launch_conv_fwd_direct(hipStream_t st, int dt, const void* x, const void* w
                             const ConvGeom& g, int relu) {
   const int64_t total = (int64_t)g.N * g.P * g.Q * g.K;
   dim3 grid(ceil_div(total, 256)), block(256);
-  if (dt == DT_F32) hipLaunchKernelGGL(conv_fwd_direct_kernel<float>, grid, block, 0, st, (const float*)x, (const float*)w, bias, (float*)out, g, relu);
-  else if (dt == DT_BF16) hipLaunchKernelGGL(conv_fwd_direct_kernel<bf16_t>, grid, block, 0, st, (const bf16_t*)x, (const bf16_t*)w, bias, (bf16_t*)out, g, relu);
-  else hipLaunchKernelGGL(conv_fwd_direct_kernel<f16_t>, grid, block, 0, st, (const f16_t*)x, (const f16_t*)w, bias, (f16_t*)out, g, relu);
+  if (dt == DT_F32) OSEQ_LAUNCH(conv_fwd_direct_kernel<float>, grid, block, 0, st, (const float*)x, (const float*)w, bias, (float*)out, g, relu);
+  else if (dt == DT_BF16) OSEQ_LAUNCH(conv_fwd_direct_kernel<bf16_t>, grid, block, 0, st, (const bf16_t*)x, (const bf16_t*)w, bias, (bf16_t*)out, g, relu);
+  else OSEQ_LAUNCH(conv_fwd_direct_kernel<f16_t>, grid, block, 0, st, (const f16_t*)x, (const f16_t*)w, bias, (f16_t*)out, g, relu);
 }
 
 void launch_conv_dgrad_direct(hipStream_t st, int dt, const void* dz, const void* w, const void* addend, void* dx,
                               const ConvGeom& g) {
   const int64_t total = (int64_t)g.N * g.H * g.W * g.C;
   dim3 grid(ceil_div(total, 256)), block(256);
-  if (dt == DT_F32) hipLaunchKernelGGL(conv_dgrad_direct_kernel<float>, grid, block, 0, st, (const float*)dz, (const float*)w, (const float*)addend, (float*)dx, g);
-  else if (dt == DT_BF16) hipLaunchKernelGGL(conv_dgrad_direct_kernel<bf16_t>, grid, block, 0, st, (const bf16_t*)dz, (const bf16_t*)w, (const bf16_t*)addend, (bf16_t*)dx, g);
-  else hipLaunchKernelGGL(conv_dgrad_direct_kernel<f16_t>, grid, block, 0, st, (const f16_t*)dz, (const f16_t*)w, (const f16_t*)addend, (f16_t*)dx, g);
+  if (dt == DT_F32) OSEQ_LAUNCH(conv_dgrad_direct_kernel<float>, grid, block, 0, st, (const float*)dz, (const float*)w, (const float*)addend, (float*)dx, g);
+  else if (dt == DT_BF16) OSEQ_LAUNCH(conv_dgrad_direct_kernel<bf16_t>, grid, block, 0, st, (const bf16_t*)dz, (const bf16_t*)w, (const bf16_t*)addend, (bf16_t*)dx, g);
+  else OSEQ_LAUNCH(conv_dgrad_direct_kernel<f16_t>, grid, block, 0, st, (const f16_t*)dz, (const f16_t*)w, (const f16_t*)addend, (f16_t*)dx, g);
 }
 
 void launch_conv_wgrad_direct(hipStream_t st, int dt, const void* x, const void* dz, float* dw, float* partial, int splits,
@@ -435,11 +435,11 @@ void launch_conv_wgrad_direct(hipStream_t st, int dt, const void* x, const void*
   const int64_t chunk = (pixels + splits - 1) / splits;
   float* dst = splits > 1 ? partial : dw;
   dim3 grid(ceil_div(outputs, 256), splits), block(256);
-  if (dt == DT_F32) hipLaunchKernelGGL(conv_wgrad_direct_kernel<float>, grid, block, 0, st, (const float*)x, (const float*)dz, dst, g, chunk);
-  else if (dt == DT_BF16) hipLaunchKernelGGL(conv_wgrad_direct_kernel<bf16_t>, grid, block, 0, st, (const bf16_t*)x, (const bf16_t*)dz, dst, g, chunk);
-  else hipLaunchKernelGGL(conv_wgrad_direct_kernel<f16_t>, grid, block, 0, st, (const f16_t*)x, (const f16_t*)dz, dst, g, chunk);
+  if (dt == DT_F32) OSEQ_LAUNCH(conv_wgrad_direct_kernel<float>, grid, block, 0, st, (const float*)x, (const float*)dz, dst, g, chunk);
+  else if (dt == DT_BF16) OSEQ_LAUNCH(conv_wgrad_direct_kernel<bf16_t>, grid, block, 0, st, (const bf16_t*)x, (const bf16_t*)dz, dst, g, chunk);
+  else OSEQ_LAUNCH(conv_wgrad_direct_kernel<f16_t>, grid, block, 0, st, (const f16_t*)x, (const f16_t*)dz, dst, g, chunk);
   if (splits > 1)
-    hipLaunchKernelGGL(splitk_reduce_kernel, dim3(ceil_div(outputs, 256)), dim3(256), 0, st, partial, dw, outputs, splits);
+    OSEQ_LAUNCH(splitk_reduce_kernel, dim3(ceil_div(outputs, 256)), dim3(256), 0, st, partial, dw, outputs, splits);
 }
 
 }  // namespace oseq

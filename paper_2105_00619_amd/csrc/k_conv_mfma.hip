@@ -682,7 +682,7 @@ template <class T>
 static void launch_splitk_epilogue(hipStream_t st, const float* partial, int splits, int64_t M, int Ng, const float* bias,
                                    const void* addend, void* out, float* stat_partial, int relu) {
   dim3 grid(ceil_div(M, SPLIT_EPI_ROWS), Ng / 64);  // Ng % 64 == 0 for every MFMA convolution
-  hipLaunchKernelGGL(splitk_epilogue_kernel<T>, grid, dim3(256), 0, st, partial, splits, M, Ng, bias, (const T*)addend,
+  OSEQ_LAUNCH(splitk_epilogue_kernel<T>, grid, dim3(256), 0, st, partial, splits, M, Ng, bias, (const T*)addend,
                      (T*)out, stat_partial, relu);
 }
 
@@ -794,10 +794,10 @@ static void launch_patch_v(hipStream_t st, const void* src, const void* wmat, co
   // the variant that also adds up what it stores (BatchNorm statistics) is a separate instantiation, so that the
   // plain one carries none of its registers
   if (splits == 1 && stat_partial)
-    hipLaunchKernelGGL((conv3x3_patch_kernel<T, BN, MI, SUBT, true>), grid, block, sm, st, (const T*)src, (const T*)wmat, bias,
+    OSEQ_LAUNCH((conv3x3_patch_kernel<T, BN, MI, SUBT, true>), grid, block, sm, st, (const T*)src, (const T*)wmat, bias,
                        (const T*)addend, (T*)out, (float*)nullptr, stat_partial, a);
   else
-    hipLaunchKernelGGL((conv3x3_patch_kernel<T, BN, MI, SUBT, false>), grid, block, sm, st, (const T*)src, (const T*)wmat, bias,
+    OSEQ_LAUNCH((conv3x3_patch_kernel<T, BN, MI, SUBT, false>), grid, block, sm, st, (const T*)src, (const T*)wmat, bias,
                        (const T*)addend, (T*)out, splits > 1 ? partial : (float*)nullptr, (float*)nullptr, a);
 }
 
@@ -853,7 +853,7 @@ static void launch_igemm_t(hipStream_t st, const void* src, const void* wmat, co
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)big_);                                  \
       attr_ = true;                                                                                                      \
     }                                                                                                                    \
-    hipLaunchKernelGGL((conv_igemm_kernel<T, BM_, BN_, MODE, SPLIT_>), grid, block, spread ? big_ : sm_, st,             \
+    OSEQ_LAUNCH((conv_igemm_kernel<T, BM_, BN_, MODE, SPLIT_>), grid, block, spread ? big_ : sm_, st,             \
                        (const T*)src, (const T*)wmat, bias, (const T*)addend, (T*)out, partial, stat_partial, a);        \
   }
   if (splits > 1) {
@@ -1019,9 +1019,9 @@ void launch_weight_transposes(hipStream_t st, int dt, const float* wbase, void* 
       blocks += b.job[j].RS * ((b.job[j].K + 31) / 32) * ((b.job[j].C + 31) / 32);
     }
     if (blocks == 0) continue;
-    if (dt == DT_F32) hipLaunchKernelGGL(weight_transpose_kernel<float>, dim3(blocks), dim3(256), 0, st, wbase, (float*)wtbase, b);
-    else if (dt == DT_BF16) hipLaunchKernelGGL(weight_transpose_kernel<bf16_t>, dim3(blocks), dim3(256), 0, st, wbase, (bf16_t*)wtbase, b);
-    else hipLaunchKernelGGL(weight_transpose_kernel<f16_t>, dim3(blocks), dim3(256), 0, st, wbase, (f16_t*)wtbase, b);
+    if (dt == DT_F32) OSEQ_LAUNCH(weight_transpose_kernel<float>, dim3(blocks), dim3(256), 0, st, wbase, (float*)wtbase, b);
+    else if (dt == DT_BF16) OSEQ_LAUNCH(weight_transpose_kernel<bf16_t>, dim3(blocks), dim3(256), 0, st, wbase, (bf16_t*)wtbase, b);
+    else OSEQ_LAUNCH(weight_transpose_kernel<f16_t>, dim3(blocks), dim3(256), 0, st, wbase, (f16_t*)wtbase, b);
   }
 }
 
@@ -1306,10 +1306,10 @@ static void launch_wgrad_t(hipStream_t st, const void* x, const void* dz, float*
   const bool m128 = g.K % 128 == 0, n128 = g.C % 128 == 0;
   const int bm = m128 ? 128 : 64, bn = n128 ? 128 : 64;
   dim3 grid(g.K / bm, g.R * g.S * (g.C / bn), splits), block(256);
-  if (m128 && n128) hipLaunchKernelGGL((conv_wgrad_kernel<T, 128, 128>), grid, block, 0, st, (const T*)x, (const T*)dz, dst, a);
-  else if (m128) hipLaunchKernelGGL((conv_wgrad_kernel<T, 128, 64>), grid, block, 0, st, (const T*)x, (const T*)dz, dst, a);
-  else if (n128) hipLaunchKernelGGL((conv_wgrad_kernel<T, 64, 128>), grid, block, 0, st, (const T*)x, (const T*)dz, dst, a);
-  else hipLaunchKernelGGL((conv_wgrad_kernel<T, 64, 64>), grid, block, 0, st, (const T*)x, (const T*)dz, dst, a);
+  if (m128 && n128) OSEQ_LAUNCH((conv_wgrad_kernel<T, 128, 128>), grid, block, 0, st, (const T*)x, (const T*)dz, dst, a);
+  else if (m128) OSEQ_LAUNCH((conv_wgrad_kernel<T, 128, 64>), grid, block, 0, st, (const T*)x, (const T*)dz, dst, a);
+  else if (n128) OSEQ_LAUNCH((conv_wgrad_kernel<T, 64, 128>), grid, block, 0, st, (const T*)x, (const T*)dz, dst, a);
+  else OSEQ_LAUNCH((conv_wgrad_kernel<T, 64, 64>), grid, block, 0, st, (const T*)x, (const T*)dz, dst, a);
 }
 
 // out[i] = sum over pixel ranges s of partial[s][i], in a fixed order: G groups of threads each add the ranges
@@ -1345,11 +1345,11 @@ __global__ void __launch_bounds__(256) wgrad_reduce_kernel(const float* __restri
 static void launch_wgrad_reduce(hipStream_t st, const float* partial, float* out, int64_t n, int splits) {
   const int64_t quads = n / 4;  // n is a multiple of 4 (C % 64 == 0)
   if (splits >= 64 || (splits >= 16 && quads < 65536))
-    hipLaunchKernelGGL(wgrad_reduce_kernel<16>, dim3(ceil_div(quads, 16)), dim3(256), 0, st, partial, out, n, splits);
+    OSEQ_LAUNCH(wgrad_reduce_kernel<16>, dim3(ceil_div(quads, 16)), dim3(256), 0, st, partial, out, n, splits);
   else if (splits >= 8)
-    hipLaunchKernelGGL(wgrad_reduce_kernel<4>, dim3(ceil_div(quads, 64)), dim3(256), 0, st, partial, out, n, splits);
+    OSEQ_LAUNCH(wgrad_reduce_kernel<4>, dim3(ceil_div(quads, 64)), dim3(256), 0, st, partial, out, n, splits);
   else
-    hipLaunchKernelGGL(wgrad_reduce_kernel<1>, dim3(ceil_div(quads, 256)), dim3(256), 0, st, partial, out, n, splits);
+    OSEQ_LAUNCH(wgrad_reduce_kernel<1>, dim3(ceil_div(quads, 256)), dim3(256), 0, st, partial, out, n, splits);
 }
 
 void launch_conv_wgrad_mfma(hipStream_t st, int dt, const void* x, const void* dz, float* dw, float* partial, int splits,

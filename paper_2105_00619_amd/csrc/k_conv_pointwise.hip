@@ -259,7 +259,7 @@ void launch_pw_v(hipStream_t st, const void* X, const void* W, const float* bias
     attr_done = true;
   }
   const int grid = ((a.MT + 7) / 8) * 8 * a.NT;
-  hipLaunchKernelGGL((conv1x1_kernel<T, BN, DGRAD>), dim3(grid), dim3(256), sm, st, (const T*)X, (const T*)W, bias,
+  OSEQ_LAUNCH((conv1x1_kernel<T, BN, DGRAD>), dim3(grid), dim3(256), sm, st, (const T*)X, (const T*)W, bias,
                      (const T*)addend, (T*)out, stat_partial, a);
 }
 

@@ -312,7 +312,7 @@ void launch_w9(hipStream_t st, const void* x, const void* dz, float* dst, const 
     attr_done = true;
   }
   dim3 grid(pl.a.K / (64 * MI), pl.a.C / 64, pl.splits), block(256);
-  hipLaunchKernelGGL((conv_wgrad3x3_kernel<T, MI>), grid, block, sm, st, (const T*)x, (const T*)dz, dst, pl.a);
+  OSEQ_LAUNCH((conv_wgrad3x3_kernel<T, MI>), grid, block, sm, st, (const T*)x, (const T*)dz, dst, pl.a);
 }
 
 }  // namespace

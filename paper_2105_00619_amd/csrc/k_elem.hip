@@ -132,8 +132,8 @@ static void launch_colreduce_t(hipStream_t st, const RedArgs& g0) {
   g.rows_per_block = ceil_div(g.rows, g.nblk);
   dim3 grid(g.nblk, ceil_div(CG, TX));
   const size_t sm = (size_t)2 * TY * TX * V * sizeof(float);
-  if (V == vmax) hipLaunchKernelGGL((colreduce_kernel<T, 16 / sizeof(T), MODE>), grid, dim3(256), sm, st, g);
-  else hipLaunchKernelGGL((colreduce_kernel<T, 1, MODE>), grid, dim3(256), sm, st, g);
+  if (V == vmax) OSEQ_LAUNCH((colreduce_kernel<T, 16 / sizeof(T), MODE>), grid, dim3(256), sm, st, g);
+  else OSEQ_LAUNCH((colreduce_kernel<T, 1, MODE>), grid, dim3(256), sm, st, g);
 }
 
 template <int MODE>
@@ -441,16 +441,16 @@ __global__ void __launch_bounds__(256) maxpool_bwd_kernel(const T* __restrict__ 
 
 void launch_cast_in(hipStream_t st, int dt, const float* x, void* out, int64_t n) {
   const int blocks = (int)((n + 255) / 256 < 4096 ? (n + 255) / 256 : 4096);
-  if (dt == DT_F32) hipLaunchKernelGGL(cast_in_kernel<float>, dim3(blocks), dim3(256), 0, st, x, (float*)out, n);
-  else if (dt == DT_BF16) hipLaunchKernelGGL(cast_in_kernel<bf16_t>, dim3(blocks), dim3(256), 0, st, x, (bf16_t*)out, n);
-  else hipLaunchKernelGGL(cast_in_kernel<f16_t>, dim3(blocks), dim3(256), 0, st, x, (f16_t*)out, n);
+  if (dt == DT_F32) OSEQ_LAUNCH(cast_in_kernel<float>, dim3(blocks), dim3(256), 0, st, x, (float*)out, n);
+  else if (dt == DT_BF16) OSEQ_LAUNCH(cast_in_kernel<bf16_t>, dim3(blocks), dim3(256), 0, st, x, (bf16_t*)out, n);
+  else OSEQ_LAUNCH(cast_in_kernel<f16_t>, dim3(blocks), dim3(256), 0, st, x, (f16_t*)out, n);
 }
 
 void launch_bn_stats(hipStream_t st, int dt, const void* z, int64_t rows, int C, int nblk, float* partial, float eps,
                      float mom, const float* gamma, const float* beta, float* stats, float* running) {
   RedArgs g{}; g.a = z; g.partial = partial; g.rows = rows; g.C = C; g.nblk = nblk;
   launch_colreduce<RED_STATS>(st, dt, g);
-  hipLaunchKernelGGL(bn_stats_finalize_kernel, dim3(ceil_div(C, 4)), dim3(256), 0, st, partial, nblk, C, (double)rows,
+  OSEQ_LAUNCH(bn_stats_finalize_kernel, dim3(ceil_div(C, 4)), dim3(256), 0, st, partial, nblk, C, (double)rows,
                      eps, mom, gamma, beta, stats, running);
 }
 
@@ -463,11 +463,11 @@ void launch_bn_stats_finalize(hipStream_t st, float* partial, int64_t rows, int 
     float* folded = partial + (int64_t)nblk * 2 * C;
     const int per = ceil_div(nblk, STAT_FOLD_ROWS);
     const int ranges = ceil_div(nblk, per);  // no empty range
-    hipLaunchKernelGGL(stat_fold_kernel, dim3(ceil_div(C, 64), ranges), dim3(256), 0, st, partial, nblk, C, per, folded);
+    OSEQ_LAUNCH(stat_fold_kernel, dim3(ceil_div(C, 64), ranges), dim3(256), 0, st, partial, nblk, C, per, folded);
     partial = folded;
     nblk = ranges;
   }
-  hipLaunchKernelGGL(bn_stats_finalize_kernel, dim3(ceil_div(C, 4)), dim3(256), 0, st, partial, nblk, C, (double)rows,
+  OSEQ_LAUNCH(bn_stats_finalize_kernel, dim3(ceil_div(C, 4)), dim3(256), 0, st, partial, nblk, C, (double)rows,
                      eps, mom, gamma, beta, stats, running);
 }
 
@@ -488,9 +488,9 @@ void launch_bn_apply(hipStream_t st, int dt, const void* z, const float* stats, 
                      int C, int relu) {
 #define CALL(T, V)                                                                                                    \
   { const int64_t groups = rows * (C / V);                                                                             \
-    if (skip) hipLaunchKernelGGL((bn_apply_kernel<T, V, true>), dim3(ceil_div(groups, 256)), dim3(256), 0, st,         \
+    if (skip) OSEQ_LAUNCH((bn_apply_kernel<T, V, true>), dim3(ceil_div(groups, 256)), dim3(256), 0, st,         \
                                  (const T*)z, stats, (const T*)skip, (T*)out, groups, C, relu);                        \
-    else hipLaunchKernelGGL((bn_apply_kernel<T, V, false>), dim3(ceil_div(groups, 256)), dim3(256), 0, st,             \
+    else OSEQ_LAUNCH((bn_apply_kernel<T, V, false>), dim3(ceil_div(groups, 256)), dim3(256), 0, st,             \
                             (const T*)z, stats, (const T*)skip, (T*)out, groups, C, relu); }
   DISPATCH_TV(dt, C, CALL);
 #undef CALL
@@ -502,10 +502,10 @@ void launch_bn_bwd(hipStream_t st, int dt, const void* da, const void* z, const 
   g.nblk = nblk;
   launch_colreduce<RED_BN_BWD>(st, dt, g);
   float* coef = ws + (int64_t)nblk * 2 * C;
-  hipLaunchKernelGGL(bn_bwd_finalize_kernel, dim3(ceil_div(C, 4)), dim3(256), 0, st, ws, nblk, C, (double)rows, dgamma,
+  OSEQ_LAUNCH(bn_bwd_finalize_kernel, dim3(ceil_div(C, 4)), dim3(256), 0, st, ws, nblk, C, (double)rows, dgamma,
                      dbeta, coef);
 #define APPLY(T, V, AO, DS)                                                                                             \
-  hipLaunchKernelGGL((bn_bwd_apply_kernel<T, V, AO, DS>), grid, dim3(256), 0, st, (const T*)da, (const T*)z,             \
+  OSEQ_LAUNCH((bn_bwd_apply_kernel<T, V, AO, DS>), grid, dim3(256), 0, st, (const T*)da, (const T*)z,             \
                      (const T*)aout, stats, coef, (T*)dz, (T*)dskip, ra)
 #define CALL(T, V)                                                                                                      \
   { RowArgs ra{}; dim3 grid; row_tiling(rows, C, V, ra, grid); ra.relu = relu;                                           \
@@ -519,7 +519,7 @@ void launch_bn_bwd(hipStream_t st, int dt, const void* da, const void* z, const 
 void launch_relu_bwd(hipStream_t st, int dt, const void* da, const void* a, void* dz, int64_t rows, int C) {
 #define CALL(T, V)                                                                                                  \
   { const int64_t groups = rows * (C / V);                                                                           \
-    hipLaunchKernelGGL((relu_bwd_kernel<T, V>), dim3(ceil_div(groups, 256)), dim3(256), 0, st, (const T*)da,         \
+    OSEQ_LAUNCH((relu_bwd_kernel<T, V>), dim3(ceil_div(groups, 256)), dim3(256), 0, st, (const T*)da,         \
                        (const T*)a, (T*)dz, groups); }
   DISPATCH_TV(dt, C, CALL);
 #undef CALL
@@ -528,14 +528,14 @@ void launch_relu_bwd(hipStream_t st, int dt, const void* da, const void* a, void
 void launch_bias_grad(hipStream_t st, int dt, const void* dz, int64_t rows, int C, int nblk, float* partial, float* dbias) {
   RedArgs g{}; g.a = dz; g.partial = partial; g.rows = rows; g.C = C; g.nblk = nblk;
   launch_colreduce<RED_BIAS>(st, dt, g);
-  hipLaunchKernelGGL(bias_finalize_kernel, dim3(ceil_div(C, 4)), dim3(256), 0, st, partial, nblk, C, dbias);
+  OSEQ_LAUNCH(bias_finalize_kernel, dim3(ceil_div(C, 4)), dim3(256), 0, st, partial, nblk, C, dbias);
 }
 
 void launch_maxpool_fwd(hipStream_t st, int dt, const void* x, void* y, int N, int H, int W, int C) {
   const int P = H / 2, Q = W / 2;
 #define CALL(T, V)                                                                                                  \
   { const int64_t total = (int64_t)N * P * Q * (C / V);                                                              \
-    hipLaunchKernelGGL((maxpool_fwd_kernel<T, V>), dim3(ceil_div(total, 256)), dim3(256), 0, st, (const T*)x, (T*)y, \
+    OSEQ_LAUNCH((maxpool_fwd_kernel<T, V>), dim3(ceil_div(total, 256)), dim3(256), 0, st, (const T*)x, (T*)y, \
                        N, H, W, C, P, Q); }
   DISPATCH_TV(dt, C, CALL);
 #undef CALL
@@ -545,7 +545,7 @@ void launch_maxpool_bwd(hipStream_t st, int dt, const void* x, const void* dy, v
   const int P = H / 2, Q = W / 2;
 #define CALL(T, V)                                                                                                  \
   { const int64_t total = (int64_t)N * H * W * (C / V);                                                              \
-    hipLaunchKernelGGL((maxpool_bwd_kernel<T, V>), dim3(ceil_div(total, 256)), dim3(256), 0, st, (const T*)x,        \
+    OSEQ_LAUNCH((maxpool_bwd_kernel<T, V>), dim3(ceil_div(total, 256)), dim3(256), 0, st, (const T*)x,        \
                        (const T*)dy, (T*)dx, N, H, W, C, P, Q); }
   DISPATCH_TV(dt, C, CALL);
 #undef CALL

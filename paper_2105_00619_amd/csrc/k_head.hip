@@ -142,23 +142,23 @@ __global__ void head_feat_bwd_kernel(const float* __restrict__ dfeat, T* __restr
 void launch_head_fwd(hipStream_t st, int dt, const void* x, int N, int HW, int C, int gap, int F, int J, const float* w,
                      const float* b, const int32_t* y, float gscale, float* feat, float* logits, float* dlogits,
                      float* loss_n, float* loss_out, int* flags) {
-  if (dt == DT_F32) hipLaunchKernelGGL(head_feat_kernel<float>, dim3(N), dim3(256), 0, st, (const float*)x, feat, HW, C, gap);
-  else if (dt == DT_BF16) hipLaunchKernelGGL(head_feat_kernel<bf16_t>, dim3(N), dim3(256), 0, st, (const bf16_t*)x, feat, HW, C, gap);
-  else hipLaunchKernelGGL(head_feat_kernel<f16_t>, dim3(N), dim3(256), 0, st, (const f16_t*)x, feat, HW, C, gap);
-  hipLaunchKernelGGL(linear_fwd_kernel, dim3(ceil_div((int64_t)N * J, 4)), dim3(256), 0, st, feat, w, b, logits, N, F, J);
-  hipLaunchKernelGGL(softmax_ce_kernel, dim3(ceil_div(N, 4)), dim3(256), 0, st, logits, y, loss_n, dlogits, N, J, gscale, flags);
-  hipLaunchKernelGGL(loss_mean_kernel, dim3(1), dim3(256), 0, st, loss_n, N, loss_out);
+  if (dt == DT_F32) OSEQ_LAUNCH(head_feat_kernel<float>, dim3(N), dim3(256), 0, st, (const float*)x, feat, HW, C, gap);
+  else if (dt == DT_BF16) OSEQ_LAUNCH(head_feat_kernel<bf16_t>, dim3(N), dim3(256), 0, st, (const bf16_t*)x, feat, HW, C, gap);
+  else OSEQ_LAUNCH(head_feat_kernel<f16_t>, dim3(N), dim3(256), 0, st, (const f16_t*)x, feat, HW, C, gap);
+  OSEQ_LAUNCH(linear_fwd_kernel, dim3(ceil_div((int64_t)N * J, 4)), dim3(256), 0, st, feat, w, b, logits, N, F, J);
+  OSEQ_LAUNCH(softmax_ce_kernel, dim3(ceil_div(N, 4)), dim3(256), 0, st, logits, y, loss_n, dlogits, N, J, gscale, flags);
+  OSEQ_LAUNCH(loss_mean_kernel, dim3(1), dim3(256), 0, st, loss_n, N, loss_out);
 }
 
 void launch_head_bwd(hipStream_t st, int dt, const float* feat, const float* dlogits, const float* w, int N, int HW, int C,
                      int gap, int F, int J, float* dw, float* db, float* dfeat, void* dx) {
-  hipLaunchKernelGGL(linear_bwd_w_kernel, dim3(ceil_div(F + 1, 64), J), dim3(256), 0, st, dlogits, feat, dw, db, N, F, J);
+  OSEQ_LAUNCH(linear_bwd_w_kernel, dim3(ceil_div(F + 1, 64), J), dim3(256), 0, st, dlogits, feat, dw, db, N, F, J);
   if (!dx) return;
-  hipLaunchKernelGGL(linear_bwd_x_kernel, dim3(ceil_div((int64_t)N * F, 128)), dim3(128), 0, st, dlogits, w, dfeat, N, F, J);
+  OSEQ_LAUNCH(linear_bwd_x_kernel, dim3(ceil_div((int64_t)N * F, 128)), dim3(128), 0, st, dlogits, w, dfeat, N, F, J);
   const int64_t total = (int64_t)N * HW * C;
-  if (dt == DT_F32) hipLaunchKernelGGL(head_feat_bwd_kernel<float>, dim3(ceil_div(total, 256)), dim3(256), 0, st, dfeat, (float*)dx, total, HW, C, gap);
-  else if (dt == DT_BF16) hipLaunchKernelGGL(head_feat_bwd_kernel<bf16_t>, dim3(ceil_div(total, 256)), dim3(256), 0, st, dfeat, (bf16_t*)dx, total, HW, C, gap);
-  else hipLaunchKernelGGL(head_feat_bwd_kernel<f16_t>, dim3(ceil_div(total, 256)), dim3(256), 0, st, dfeat, (f16_t*)dx, total, HW, C, gap);
+  if (dt == DT_F32) OSEQ_LAUNCH(head_feat_bwd_kernel<float>, dim3(ceil_div(total, 256)), dim3(256), 0, st, dfeat, (float*)dx, total, HW, C, gap);
+  else if (dt == DT_BF16) OSEQ_LAUNCH(head_feat_bwd_kernel<bf16_t>, dim3(ceil_div(total, 256)), dim3(256), 0, st, dfeat, (bf16_t*)dx, total, HW, C, gap);
+  else OSEQ_LAUNCH(head_feat_bwd_kernel<f16_t>, dim3(ceil_div(total, 256)), dim3(256), 0, st, dfeat, (f16_t*)dx, total, HW, C, gap);
 }
 
 }  // namespace oseq

@@ -62,23 +62,23 @@ __global__ void fill_kernel(float* p, int64_t n, float v) {
 
 static int grid_for(int64_t n) { int64_t b = (n + 255) / 256; return (int)(b < 1 ? 1 : (b > 8192 ? 8192 : b)); }
 
-void launch_step_init(hipStream_t st, int* flags) { hipLaunchKernelGGL(step_init_kernel, dim3(1), dim3(64), 0, st, flags); }
+void launch_step_init(hipStream_t st, int* flags) { OSEQ_LAUNCH(step_init_kernel, dim3(1), dim3(64), 0, st, flags); }
 
 void launch_optim(hipStream_t st, int dt, float* w, float* v, const float* g, void* w16, float* gout, int64_t n, float lr,
                   float mom, float inv_scale, int* flags) {
-  hipLaunchKernelGGL(optim_check_kernel, dim3(grid_for(n)), dim3(256), 0, st, g, n, flags);
-  if (dt == DT_F32) hipLaunchKernelGGL((optim_update_kernel<float, false>), dim3(grid_for(n)), dim3(256), 0, st, w, v, g, (float*)nullptr, gout, n, lr, mom, inv_scale, flags);
-  else if (dt == DT_BF16) hipLaunchKernelGGL((optim_update_kernel<bf16_t, true>), dim3(grid_for(n)), dim3(256), 0, st, w, v, g, (bf16_t*)w16, gout, n, lr, mom, inv_scale, flags);
-  else hipLaunchKernelGGL((optim_update_kernel<f16_t, true>), dim3(grid_for(n)), dim3(256), 0, st, w, v, g, (f16_t*)w16, gout, n, lr, mom, inv_scale, flags);
+  OSEQ_LAUNCH(optim_check_kernel, dim3(grid_for(n)), dim3(256), 0, st, g, n, flags);
+  if (dt == DT_F32) OSEQ_LAUNCH((optim_update_kernel<float, false>), dim3(grid_for(n)), dim3(256), 0, st, w, v, g, (float*)nullptr, gout, n, lr, mom, inv_scale, flags);
+  else if (dt == DT_BF16) OSEQ_LAUNCH((optim_update_kernel<bf16_t, true>), dim3(grid_for(n)), dim3(256), 0, st, w, v, g, (bf16_t*)w16, gout, n, lr, mom, inv_scale, flags);
+  else OSEQ_LAUNCH((optim_update_kernel<f16_t, true>), dim3(grid_for(n)), dim3(256), 0, st, w, v, g, (f16_t*)w16, gout, n, lr, mom, inv_scale, flags);
 }
 
 void launch_cast_params(hipStream_t st, int dt, const float* w, void* w16, int64_t n) {
-  if (dt == DT_BF16) hipLaunchKernelGGL(cast_params_kernel<bf16_t>, dim3(grid_for(n)), dim3(256), 0, st, w, (bf16_t*)w16, n);
-  else if (dt == DT_F16) hipLaunchKernelGGL(cast_params_kernel<f16_t>, dim3(grid_for(n)), dim3(256), 0, st, w, (f16_t*)w16, n);
+  if (dt == DT_BF16) OSEQ_LAUNCH(cast_params_kernel<bf16_t>, dim3(grid_for(n)), dim3(256), 0, st, w, (bf16_t*)w16, n);
+  else if (dt == DT_F16) OSEQ_LAUNCH(cast_params_kernel<f16_t>, dim3(grid_for(n)), dim3(256), 0, st, w, (f16_t*)w16, n);
 }
 
 void launch_fill(hipStream_t st, float* p, int64_t n, float v) {
-  if (n > 0) hipLaunchKernelGGL(fill_kernel, dim3(grid_for(n)), dim3(256), 0, st, p, n, v);
+  if (n > 0) OSEQ_LAUNCH(fill_kernel, dim3(grid_for(n)), dim3(256), 0, st, p, n, v);
 }
 
 }  // namespace oseq
