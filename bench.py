@@ -70,7 +70,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--config", type=int, default=2, help="benchmark configuration 1..5 (default: VGG-11-BN fp32, k=4)")
+    ap.add_argument("--config", type=int, default=2, help="benchmark configuration 1..6 (default 2: VGG-11-BN fp32, k=4)")
     ap.add_argument("--k", type=int, default=None, help="override the number of segments")
     ap.add_argument("--batch", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -187,7 +187,7 @@ def main():
         "value": wl.batch / (ms * 1e-3), "unit": "images/sec", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": DTYPE_NAME[wl.precision], "data": "synthetic",
-        "config": {"workload": wl.name, "batch": wl.batch, "k_segments": k, "image": "32x32x3 NHWC",
+        "config": {"workload": wl.name, "batch": wl.batch, "k_segments": k, "image": "%dx%dx%d NHWC" % (wl.height, wl.width, wl.channels),
                    "boundaries": tr.boundaries, "plan_mode": wl.plan_mode, "momentum": wl.momentum},
         "loss": r["loss"], "peak_saved_bytes": r["peak_saved_bytes"], "peak_arena_bytes": r["peak_arena_bytes"],
         "activation_budget_bytes": wl.budget_bytes, "launches_per_step": tr.n_launches,

@@ -7,33 +7,30 @@
 namespace oseq {
 
 // feat[n][f]: GAP -> mean over H*W of channel f ; flatten -> x[n][f]
+// GAP: block (n, g) owns 64 channels of image n; its four wavefronts take every fourth pixel (eight loads in flight
+// per lane) and their sums are added in wavefront order.
 template <class T>
 __global__ void __launch_bounds__(256) head_feat_kernel(const T* __restrict__ x, float* __restrict__ feat, int HW, int C,
                                                         int gap) {
-  __shared__ float sm[256];
+  __shared__ float sm[4][64];
   const int n = blockIdx.x;
   if (!gap) {
     const int64_t F = (int64_t)HW * C;
-    for (int64_t i = threadIdx.x; i < F; i += 256) feat[n * F + i] = to_f32(x[n * F + i]);
+    for (int64_t i = (int64_t)blockIdx.y * 256 + threadIdx.x; i < F; i += (int64_t)gridDim.y * 256)
+      feat[n * F + i] = to_f32(x[n * F + i]);
     return;
   }
-  const int TX = C < 256 ? C : 256;
-  const int TY = 256 / TX;
-  const int tx = threadIdx.x % TX, ty = threadIdx.x / TX;
-  for (int cb = 0; cb < C; cb += TX) {
-    const int c = cb + tx;
-    float s = 0.f;
-    if (ty < TY && c < C)
-      for (int p = ty; p < HW; p += TY) s += to_f32(x[((int64_t)n * HW + p) * C + c]);
-    sm[threadIdx.x] = s;
-    __syncthreads();
-    if (ty == 0 && c < C) {
-      float t = 0.f;
-      for (int y = 0; y < TY; ++y) t += sm[y * TX + tx];
-      feat[(int64_t)n * C + c] = t / (float)HW;
-    }
-    __syncthreads();
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  const int c = blockIdx.y * 64 + tx;
+  float s = 0.f;
+  if (c < C) {
+    const T* col = x + (int64_t)n * HW * C + c;
+#pragma unroll 8
+    for (int p = ty; p < HW; p += 4) s += to_f32(col[(int64_t)p * C]);
   }
+  sm[ty][tx] = s;
+  __syncthreads();
+  if (ty == 0 && c < C) feat[(int64_t)n * C + c] = (((sm[0][tx] + sm[1][tx]) + sm[2][tx]) + sm[3][tx]) / (float)HW;
 }
 
 // one wavefront per (sample, class): lanes stride over the features, then a fixed butterfly
@@ -139,12 +136,52 @@ __global__ void head_feat_bwd_kernel(const float* __restrict__ dfeat, T* __restr
   dx[i] = from_f32<T>(dfeat[n * C + c] / (float)HW);
 }
 
+// GAP backward for channel counts that are a multiple of V: block (chunk of rows, image n); a thread owns V channels,
+// reads their gradient once and writes it to every TY-th pixel of the block's rows (16-byte stores, no divisions
+// per element)
+template <class T, int V>
+__global__ void __launch_bounds__(256) gap_bwd_rows_kernel(const float* __restrict__ dfeat, T* __restrict__ dx, int HW, int C,
+                                                           int rows_per_block) {
+  const int CG = C / V;
+  const int TX = CG < 256 ? CG : 256;
+  const int TY = 256 / TX;
+  const int tx = threadIdx.x % TX, ty = threadIdx.x / TX;
+  const int n = blockIdx.y;
+  const int p0 = blockIdx.x * rows_per_block;
+  const int p1 = p0 + rows_per_block < HW ? p0 + rows_per_block : HW;
+  if (ty >= TY) return;
+  for (int cg = tx; cg < CG; cg += TX) {
+    float v[V];
+#pragma unroll
+    for (int k = 0; k < V; ++k) v[k] = dfeat[(int64_t)n * C + cg * V + k] / (float)HW;
+    Vec<T, V> t;
+#pragma unroll
+    for (int k = 0; k < V; ++k) t.v[k] = from_f32<T>(v[k]);
+    T* base = dx + ((int64_t)n * HW) * C + cg * V;
+    for (int p = p0 + ty; p < p1; p += TY) *reinterpret_cast<Vec<T, V>*>(base + (int64_t)p * C) = t;
+  }
+}
+
+template <class T>
+static void launch_feat_bwd(hipStream_t st, const float* dfeat, void* dx, int N, int HW, int C, int gap) {
+  constexpr int V = 16 / (int)sizeof(T);
+  const int64_t total = (int64_t)N * HW * C;
+  if (gap && C % V == 0 && HW >= 64) {
+    const int rows_per_block = 64;
+    OSEQ_LAUNCH((gap_bwd_rows_kernel<T, V>), dim3(ceil_div(HW, rows_per_block), N), dim3(256), 0, st, dfeat, (T*)dx, HW, C,
+                rows_per_block);
+  } else {
+    OSEQ_LAUNCH(head_feat_bwd_kernel<T>, dim3(ceil_div(total, 256)), dim3(256), 0, st, dfeat, (T*)dx, total, HW, C, gap);
+  }
+}
+
 void launch_head_fwd(hipStream_t st, int dt, const void* x, int N, int HW, int C, int gap, int F, int J, const float* w,
                      const float* b, const int32_t* y, float gscale, float* feat, float* logits, float* dlogits,
                      float* loss_n, float* loss_out, int* flags) {
-  if (dt == DT_F32) OSEQ_LAUNCH(head_feat_kernel<float>, dim3(N), dim3(256), 0, st, (const float*)x, feat, HW, C, gap);
-  else if (dt == DT_BF16) OSEQ_LAUNCH(head_feat_kernel<bf16_t>, dim3(N), dim3(256), 0, st, (const bf16_t*)x, feat, HW, C, gap);
-  else OSEQ_LAUNCH(head_feat_kernel<f16_t>, dim3(N), dim3(256), 0, st, (const f16_t*)x, feat, HW, C, gap);
+  const dim3 feat_grid(N, gap ? ceil_div(C, 64) : 1);
+  if (dt == DT_F32) OSEQ_LAUNCH(head_feat_kernel<float>, feat_grid, dim3(256), 0, st, (const float*)x, feat, HW, C, gap);
+  else if (dt == DT_BF16) OSEQ_LAUNCH(head_feat_kernel<bf16_t>, feat_grid, dim3(256), 0, st, (const bf16_t*)x, feat, HW, C, gap);
+  else OSEQ_LAUNCH(head_feat_kernel<f16_t>, feat_grid, dim3(256), 0, st, (const f16_t*)x, feat, HW, C, gap);
   OSEQ_LAUNCH(linear_fwd_kernel, dim3(ceil_div((int64_t)N * J, 4)), dim3(256), 0, st, feat, w, b, logits, N, F, J);
   OSEQ_LAUNCH(softmax_ce_kernel, dim3(ceil_div(N, 4)), dim3(256), 0, st, logits, y, loss_n, dlogits, N, J, gscale, flags);
   OSEQ_LAUNCH(loss_mean_kernel, dim3(1), dim3(256), 0, st, loss_n, N, loss_out);
@@ -155,10 +192,9 @@ void launch_head_bwd(hipStream_t st, int dt, const float* feat, const float* dlo
   OSEQ_LAUNCH(linear_bwd_w_kernel, dim3(ceil_div(F + 1, 64), J), dim3(256), 0, st, dlogits, feat, dw, db, N, F, J);
   if (!dx) return;
   OSEQ_LAUNCH(linear_bwd_x_kernel, dim3(ceil_div((int64_t)N * F, 128)), dim3(128), 0, st, dlogits, w, dfeat, N, F, J);
-  const int64_t total = (int64_t)N * HW * C;
-  if (dt == DT_F32) OSEQ_LAUNCH(head_feat_bwd_kernel<float>, dim3(ceil_div(total, 256)), dim3(256), 0, st, dfeat, (float*)dx, total, HW, C, gap);
-  else if (dt == DT_BF16) OSEQ_LAUNCH(head_feat_bwd_kernel<bf16_t>, dim3(ceil_div(total, 256)), dim3(256), 0, st, dfeat, (bf16_t*)dx, total, HW, C, gap);
-  else OSEQ_LAUNCH(head_feat_bwd_kernel<f16_t>, dim3(ceil_div(total, 256)), dim3(256), 0, st, dfeat, (f16_t*)dx, total, HW, C, gap);
+  if (dt == DT_F32) launch_feat_bwd<float>(st, dfeat, dx, N, HW, C, gap);
+  else if (dt == DT_BF16) launch_feat_bwd<bf16_t>(st, dfeat, dx, N, HW, C, gap);
+  else launch_feat_bwd<f16_t>(st, dfeat, dx, N, HW, C, gap);
 }
 
 }  // namespace oseq

@@ -144,8 +144,10 @@ class Workload:
     seed: int = MASTER_SEED
 
 
-def config(index: int, batch: int | None = None) -> Workload:
-    """The five benchmark configurations (index 1..5); `batch` overrides the size."""
+def config(index: int, batch: int | None = None, size: int | None = None) -> Workload:
+    """The five benchmark configurations (index 1..5) and, as index 6, the shape of the paper's memory experiment
+    (Section "Sequential-checkpoint training": 16 images of 512 x 512 x 3 through ResNet-18): large images, tiny
+    batch.  `batch` overrides the batch size, `size` the image height and width."""
     if index == 1:
         w = Workload("tiny_cnn_fp32_k2", tuple(tiny_cnn(10)), 8, 32, 32, 3, 10, FP32, 2, 0.0, 1.0, "uniform")
     elif index == 2:
@@ -159,10 +161,15 @@ def config(index: int, batch: int | None = None) -> Workload:
     elif index == 5:
         w = Workload("resnet152_bf16_k7", tuple(resnet_bottleneck([3, 8, 36, 3], 100)), 4096, 32, 32, 3, 100,
                      BF16, 7, 0.0, 1.0, "gauss", budget_bytes=32 << 30, plan_mode=1)
+    elif index == 6:
+        w = Workload("resnet18_fp32_k4_512px", tuple(resnet_basic([2, 2, 2, 2], 10)), 16, 512, 512, 3, 10,
+                     FP32, 4, 0.0, 1.0, "gauss")
     else:
-        raise ValueError("config index must be 1..5")
+        raise ValueError("config index must be 1..6")
     if batch is not None:
         w = Workload(**{**w.__dict__, "batch": int(batch)})
+    if size is not None:
+        w = Workload(**{**w.__dict__, "height": int(size), "width": int(size)})
     return Workload(**{**w.__dict__, "seed": MASTER_SEED + index})
 
 

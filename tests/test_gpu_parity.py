@@ -167,6 +167,21 @@ def test_deep_configs_reduced_batch(index, batch, fp32_too):
     assert info["n_replay_launches"] > 0
 
 
+def test_large_image_config_reduced_size():
+    """The large-image workload (ResNet-18 on 512 x 512 images, batch 16) at 64 x 64 and batch 2: the same network
+    with image sizes that are not the 32 x 32 of the other configurations (rows of 64, 32, 16 and 8 pixels)."""
+    wl = W.config(6, batch=2, size=64)
+    p, x, y = W.make_batch(wl, perturb=True)
+    r, info = gpu_step(wl.units, p, x, y, precision=W.FP32, k=wl.k_segments, classes=wl.classes)
+    loss, n_inv = assert_parity_fp32(wl.units, 64, 64, p, x, y, r["grads"], 1e-4, wl.name + " at 64 x 64", max_inverted=48)
+    print("%s at 64 x 64: %d near-kink ReLU decisions taken the other way" % (wl.name, n_inv))
+    assert abs(r["loss"] - loss) <= 1e-4 * abs(loss)
+    assert info["n_replay_launches"] > 0
+    one, info1 = gpu_step(wl.units, p, x, y, precision=W.FP32, k=1, classes=wl.classes)
+    assert np.array_equal(one["grads"], r["grads"])
+    assert info["planned_peak_saved_bytes"] < 0.6 * info1["planned_peak_saved_bytes"]
+
+
 @pytest.mark.parametrize("name,precision,ks", [
     ("bottleneck", W.FP32, (1, 2, 3, 5)), ("bottleneck", W.BF16, (1, 3)), ("basic_projection", W.FP16, (1, 2, 4)),
     ("maxpool_flatten", W.FP32, (1, 3, 5)), ("plain_conv_stack", W.FP32, (1, 2, 3))])

@@ -40,6 +40,20 @@ def test_param_counts_match_generator_layout():
         assert _plan(idx, activation_budget_bytes=0).param_count == W.param_count(w.units, w.height, w.width)
 
 
+def test_large_image_config_plans_and_shrinks_with_k():
+    # ResNet-18 on 16 images of 512 x 512 (the shape of the paper's memory experiment): 16 x the pixels of a
+    # 32 x 32 batch of 256 per image; the plan must hold 64-bit sizes and k = 4 must cut the saved bytes
+    w = W.config(6)
+    assert (w.batch, w.height, w.width) == (16, 512, 512)
+    p1 = _plan(6, k_segments=1)
+    p4 = _plan(6)
+    assert p1.param_count == W.param_count(w.units, w.height, w.width)
+    # stem output alone: 16 x 512 x 512 x 64 fp32 = 1 GiB
+    assert p1.planned_peak_saved_bytes > 16 * (1 << 30) and p1.act_arena_bytes >= p1.planned_peak_saved_bytes
+    assert p4.planned_peak_saved_bytes < 0.5 * p1.planned_peak_saved_bytes
+    assert p4.n_replay_launches > 0 and p1.n_replay_launches == 0
+
+
 def test_config2_all_stored_bytes_match_the_analytic_count():
     # VGG-11-BN, fp32, batch 128, every activation stored: the input, per conv the pre-BN output Z, the post-ReLU
     # output A and the four per-channel BN vectors, per pool its output (the last pool's output feeds only the head,
