@@ -254,6 +254,26 @@ def test_momentum_two_steps_match_oracle_update():
         assert np.linalg.norm(o["params"] - w) <= 1e-5 * np.linalg.norm(w)
 
 
+def test_training_loop_tracks_oracle_over_25_steps():
+    """A short training run on one batch (momentum 0.9, three segments): weights after every step against the float64
+    oracle's own training loop, and the loss must fall.  fp32 rounding differences compound from step to step, so
+    the bound widens with the step count."""
+    from oracle import seqnet_oracle as O
+    units, classes = NETS["basic_projection"]
+    p, x, y = _inputs(units, 6, 12, 12, classes)
+    steps = 25
+    outs, _ = gpu_step(units, p, x, y, precision=W.FP32, k=3, classes=classes, lr=0.02, momentum=0.9, steps=steps)
+    w, v = p.astype(np.float64), np.zeros(p.size)
+    losses = []
+    for i, o in enumerate(outs):
+        loss, _, w, v = O.train_step(units, w, v, x, y, 0.02, 0.9)
+        losses.append(loss)
+        assert abs(o["loss"] - loss) <= 1e-4 * (i + 1) * max(1.0, abs(loss)), (i, o["loss"], loss)
+        assert np.linalg.norm(o["params"] - w) <= 2e-6 * (i + 1) * np.linalg.norm(w), i
+        assert not o["skipped"]
+    assert losses[-1] < 0.7 * losses[0] and outs[-1]["loss"] < 0.7 * outs[0]["loss"]
+
+
 def test_label_out_of_range_is_an_error():
     from paper_2105_00619_amd.binding import OptorchError
     units, classes = NETS["conv_bn_relu"]
