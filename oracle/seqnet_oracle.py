@@ -45,6 +45,12 @@ the end.  Everything between two stored tensors (contractions, BatchNorm
 statistics and sums, the loss head, parameter gradients) stays in float64.  With
 storage=None the hooks are the identity and the function is the plain definition.
 
+Inference mode.  BatchNorm keeps running estimates of each channel's mean and variance (exponential averages of the
+batch mean and of the unbiased batch variance, momentum 0.1, started at 0 and 1) and `predict` evaluates the network
+with those in place of the batch statistics: y = gamma * (z - running_mean) / sqrt(running_var + eps) + beta.  The
+paper trains and then evaluates its networks (Section "Sequential-checkpoint training", accuracy after ten epochs)
+with a framework's BatchNorm; these are that layer's standard definitions.
+
 Pins (tests/test_oracle_pins.py): central finite differences on every layer
 kind, closed forms of the loss and the update, BatchNorm orthogonality
 invariants, reduction of 1x1 conv to a matrix product, agreement with
@@ -133,6 +139,18 @@ def batchnorm_forward(z, gamma, beta, eps=BN_EPS):
     return gamma * xhat + beta, (xhat, rstd)
 
 
+def batchnorm_eval(z, gamma, beta, running_mean, running_var, eps=BN_EPS):
+    """Inference-mode BatchNorm: the running estimates take the place of the batch statistics."""
+    return gamma * (z - running_mean) / np.sqrt(running_var + eps) + beta
+
+
+def batchnorm_running_update(running_mean, running_var, batch_mean, batch_var_biased, count, momentum=0.1):
+    """Exponential averages of the batch mean and of the unbiased batch variance (count = batch * H * W)."""
+    unbiased = batch_var_biased * count / (count - 1) if count > 1 else batch_var_biased
+    return ((1.0 - momentum) * running_mean + momentum * batch_mean,
+            (1.0 - momentum) * running_var + momentum * unbiased)
+
+
 def batchnorm_backward(dy, cache, gamma):
     xhat, rstd = cache
     m = dy.shape[0] * dy.shape[1] * dy.shape[2]
@@ -212,6 +230,8 @@ class _Params:
         self.relu_count = 0           # ReLU layers are numbered in forward order
         self.flips = flips or {}      # {relu number: (flat indices, decisions forced there)}
         self.kink_tau, self.kinks = kink_tau, []
+        self.moments = {}             # {flat offset of a BatchNorm's gamma: (batch mean, biased variance, count)}
+        self.running = None           # inference mode: {flat offset of gamma: (running mean, running variance)}
 
     def take(self, shape):
         n = int(np.prod(shape))
@@ -233,7 +253,13 @@ def _cbr_forward(x, pr, cin, cout, k, stride, pad, bn, relu, bias, skip=None):
         gamma, beta = pr.take((cout,)), pr.take((cout,))
         shift_off = pr.off - cout
         z = q(z)  # the convolution output is a stored tensor; statistics are taken from what is stored
-        y, cache["bn_cache"] = batchnorm_forward(z, gamma, beta)
+        if pr.running is not None:
+            y = batchnorm_eval(z, gamma, beta, *pr.running[shift_off - cout])
+        else:
+            y, cache["bn_cache"] = batchnorm_forward(z, gamma, beta)
+            mean = z.mean(axis=(0, 1, 2))
+            pr.moments[shift_off - cout] = (mean, ((z - mean) ** 2).mean(axis=(0, 1, 2)),
+                                            z.shape[0] * z.shape[1] * z.shape[2])
         cache["gamma"] = gamma
     if skip is not None:
         y = y + skip
@@ -404,3 +430,69 @@ def train_step(units, params, velocity, x, y, lr, momentum, dtype=np.float64):
     loss, g = loss_and_grads(units, params, x, y, dtype)
     w, v = sgd_momentum_step(np.asarray(params, dtype), np.asarray(velocity, dtype), g, lr, momentum)
     return loss, g, w, v
+
+
+
+# ------------------------------------------------- running statistics, inference ------
+def _forward_logits(units, pr, a):
+    for u in units[:-1]:
+        a, _ = _unit_forward(u, a, pr)
+    head = units[-1]
+    if head.kind == GAP_LINEAR_CE:
+        feat = a.mean(axis=(1, 2))
+    elif head.kind == FLATTEN_LINEAR_CE:
+        feat = a.reshape(a.shape[0], -1)
+    else:
+        raise ValueError("the last unit must be a loss head")
+    wl = pr.take((head.cout, feat.shape[1]))
+    bl = pr.take((head.cout,))
+    return feat @ wl.T + bl
+
+
+def initial_running_stats(units, params, x_shape):
+    """Flat vector of running statistics before the first step: per BatchNorm, in parameter-layout order, C zeros
+    (mean) then C ones (variance)."""
+    moments = batch_moments(units, params, np.zeros(x_shape))
+    return np.concatenate([np.concatenate([np.zeros_like(m[0]), np.ones_like(m[1])]) for m in moments]) \
+        if moments else np.zeros(0)
+
+
+def batch_moments(units, params, x, dtype=np.float64, storage=None):
+    """Per BatchNorm, in parameter-layout order: (batch mean, biased batch variance, count) of its input on x."""
+    q = _quantizer(storage)
+    pr = _Params(np.asarray(params, dtype=dtype), q)
+    _forward_logits(units, pr, q(np.asarray(x, dtype=dtype)))
+    return [pr.moments[k] for k in sorted(pr.moments)]
+
+
+def update_running_stats(running, moments, momentum=0.1):
+    """One training step's update of the flat running-statistics vector from that step's batch moments."""
+    out, off = [], 0
+    for mean, var, count in moments:
+        c = mean.size
+        rm, rv = batchnorm_running_update(running[off:off + c], running[off + c:off + 2 * c], mean, var, count, momentum)
+        out += [rm, rv]
+        off += 2 * c
+    return np.concatenate(out) if out else np.zeros(0)
+
+
+def predict(units, params, running, x, dtype=np.float64, storage=None):
+    """Logits of the network in inference mode: BatchNorm uses the running statistics `running` (flat, layout as in
+    initial_running_stats); storage as in loss_and_grads."""
+    q = _quantizer(storage)
+    params = np.asarray(params, dtype=dtype)
+    # the keys (flat offsets of the gammas, ascending) are those a batch-mode pass records
+    keys = sorted(_moment_keys(units, params, np.asarray(x).shape))
+    pr = _Params(params, q)
+    pr.running, off = {}, 0
+    for k, c in keys:
+        pr.running[k] = (np.asarray(running[off:off + c], dtype), np.asarray(running[off + c:off + 2 * c], dtype))
+        off += 2 * c
+    return _forward_logits(units, pr, q(np.asarray(x, dtype=dtype)))
+
+
+def _moment_keys(units, params, x_shape):
+    pr = _Params(params)
+    _forward_logits(units, pr, np.zeros((1,) + tuple(x_shape[1:]), dtype=params.dtype))
+    return [(k, v[0].size) for k, v in pr.moments.items()]
+

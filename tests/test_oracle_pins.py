@@ -303,3 +303,73 @@ def test_kink_listing_and_decision_flips():
     # the gradient change is linear in the upstream gradient (scale invariance)
     _, g4 = O.loss_and_grads(units, p, x, y, flips={rid: ([idx], [not dec])}, loss_scale=4.0)
     assert np.allclose(g4, g2, rtol=1e-12, atol=1e-15)
+
+
+# ------------------------------------------------ inference mode and running statistics ------
+def test_running_update_hand_computed():
+    # one channel holding 1, 2, 3, 4: mean 2.5, biased variance 1.25, unbiased 5/3;
+    # from (0, 1) with momentum 0.1: mean 0.25, variance 0.9 + 0.1 * 5/3
+    rm, rv = O.batchnorm_running_update(np.zeros(1), np.ones(1), np.array([2.5]), np.array([1.25]), 4, 0.1)
+    assert rm[0] == pytest.approx(0.25, abs=1e-15) and rv[0] == pytest.approx(0.9 + 1.0 / 6.0, abs=1e-15)
+    # a single value has no unbiased variance: the biased one (0) is used
+    rm, rv = O.batchnorm_running_update(np.zeros(1), np.ones(1), np.array([3.0]), np.array([0.0]), 1, 0.5)
+    assert rm[0] == 1.5 and rv[0] == 0.5
+
+
+def test_batchnorm_eval_reduces_to_training_forward_and_to_the_affine_map():
+    rng = np.random.default_rng(3)
+    z = rng.normal(size=(3, 4, 5, 6)) * 2 + 1
+    gamma, beta = rng.normal(size=6), rng.normal(size=6)
+    mean = z.mean(axis=(0, 1, 2))
+    var = z.var(axis=(0, 1, 2))  # numpy's biased variance
+    train, _ = O.batchnorm_forward(z, gamma, beta)
+    assert np.allclose(O.batchnorm_eval(z, gamma, beta, mean, var), train, rtol=0, atol=1e-12)
+    # running mean 0 and variance 1 - eps: y = gamma * z + beta exactly
+    y = O.batchnorm_eval(z, gamma, beta, np.zeros(6), np.full(6, 1.0 - O.BN_EPS))
+    assert np.allclose(y, gamma * z + beta, rtol=0, atol=1e-12)
+
+
+def test_predict_against_an_independent_evaluation():
+    """conv 3x3 (scipy correlate) -> BatchNorm with given running statistics -> ReLU -> mean over pixels -> linear."""
+    rng = np.random.default_rng(5)
+    units = [W.conv(2, 3), W.gap_linear_ce(3, 4)]
+    n = W.param_count(units, 6, 6)
+    p = rng.normal(size=n)
+    x = rng.normal(size=(2, 6, 6, 2))
+    running = np.concatenate([rng.normal(size=3), rng.uniform(0.5, 2.0, size=3)])
+    w = p[:54].reshape(3, 3, 3, 2)
+    gamma, beta = p[54:57], p[57:60]
+    wl, bl = p[60:72].reshape(4, 3), p[72:76]
+    feat = np.zeros((2, 3))
+    for i in range(2):
+        for k in range(3):
+            z = sum(correlate2d(np.pad(x[i, :, :, c], 1), w[k, :, :, c], mode="valid") for c in range(2))
+            a = np.maximum(gamma[k] * (z - running[k]) / math.sqrt(running[3 + k] + O.BN_EPS) + beta[k], 0.0)
+            feat[i, k] = a.mean()
+    assert np.allclose(O.predict(units, p, running, x), feat @ wl.T + bl, rtol=0, atol=1e-12)
+
+
+def test_running_statistics_follow_the_parameter_layout_order():
+    """In a block with a projection shortcut the shortcut's BatchNorm comes last in the layout although its forward
+    runs before the block's last convolution: its moments are those of a 1x1 strided convolution of the block input."""
+    rng = np.random.default_rng(7)
+    units = [W.basic_block(4, 8, 2), W.gap_linear_ce(8, 3)]
+    layout = W.param_layout(units, 6, 6)
+    p = rng.normal(size=W.param_count(units, 6, 6)) * 0.3
+    x = rng.normal(size=(3, 6, 6, 4))
+    moments = O.batch_moments(units, p, x)
+    assert len(moments) == 3 and [m[2] for m in moments] == [27, 27, 27]
+    names = [e[0] for e in layout]
+    first_sc = names.index("u0.sc.w")  # the shortcut's weight follows both main-path layers
+    assert first_sc > names.index("u0.c2.beta")
+    wsc_off = sum(int(np.prod(layout[i][1])) for i in range(first_sc))
+    wsc = p[wsc_off:wsc_off + 8 * 4].reshape(8, 4)
+    z = x[:, ::2, ::2, :] @ wsc.T  # 1x1 convolution, stride 2, no padding
+    assert np.allclose(moments[2][0], z.mean(axis=(0, 1, 2)), rtol=0, atol=1e-12)
+    assert np.allclose(moments[2][1], z.var(axis=(0, 1, 2)), rtol=0, atol=1e-12)
+    # and the flat vector is (mean, variance) per BatchNorm in that order, starting from zeros and ones
+    r0 = O.initial_running_stats(units, p, x.shape)
+    assert r0.size == 2 * (8 + 8 + 8) and np.array_equal(r0[:8], np.zeros(8)) and np.array_equal(r0[8:16], np.ones(8))
+    r1 = O.update_running_stats(r0, moments, 0.1)
+    assert np.allclose(r1[32:40], 0.1 * z.mean(axis=(0, 1, 2)), rtol=0, atol=1e-12)
+    assert np.allclose(r1[40:48], 0.9 + 0.1 * z.var(axis=(0, 1, 2)) * 27 / 26, rtol=0, atol=1e-12)
