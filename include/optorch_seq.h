@@ -133,6 +133,24 @@ int optorch_seq_step(optorch_seq_t* h, const float* x_dev, const int32_t* y_dev,
                      float* loss_out, float* grads_dev, uint64_t* peak_saved_bytes,
                      uint64_t* peak_arena_bytes, float* loss_scale_out, int32_t* step_skipped);
 
+/* Inference with the network as it stands (the counterpart of training-mode BatchNorm; the paper evaluates its
+ * trained networks, Section "Sequential-checkpoint training"): the forward pass of every segment, nothing kept, with
+ * each BatchNorm using its running mean and variance instead of the batch statistics, up to the logits.
+ *   x_dev       device: batch x height x width x channels fp32, NHWC (the batch size of create)
+ *   logits_dev  device: receives batch x num_classes fp32
+ * Runs on the bound stream and returns after it has finished.  Uses the activation arena: not concurrently with
+ * optorch_seq_step on the same handle.  Errors as optorch_seq_step. */
+int optorch_seq_predict(optorch_seq_t* h, const float* x_dev, float* logits_dev);
+
+/* The BatchNorm running statistics: for every BatchNorm in parameter order, C running means then C running
+ * variances (fp32).  They start at 0 and 1 (optorch_seq_set_params) and every optorch_seq_step moves them by
+ * bn_momentum towards the batch mean and the unbiased batch variance, also on a step that is then skipped for a
+ * non-finite gradient (the forward pass has run by then).
+ *   dst       host or device (is_device), or NULL to query the size only
+ *   capacity  floats dst can hold; OPTORCH_E_INVALID if fewer than *count
+ *   count     host or NULL: receives the number of floats */
+int optorch_seq_running_stats(const optorch_seq_t* h, float* dst, uint64_t capacity, uint64_t* count, int32_t is_device);
+
 /* Number of kernel launches in one step's static schedule, and how many of them belong to the
  * replay (recomputation) of non-last segments. */
 int optorch_seq_schedule_info(const optorch_seq_t* h, int32_t* n_launch_records, int32_t* n_replay_records);

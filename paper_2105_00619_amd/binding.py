@@ -20,7 +20,7 @@ OK, E_INVALID, E_BUDGET, E_HIP, E_ORDER = 0, -1, -2, -3, -4
 SYMBOLS = (
     "optorch_seq_create", "optorch_seq_query", "optorch_seq_bind", "optorch_seq_set_params",
     "optorch_seq_get_params", "optorch_seq_step", "optorch_seq_schedule_info", "optorch_seq_last_error",
-    "optorch_seq_destroy", "optorch_seq_profile_enable", "optorch_seq_profile_select", "optorch_seq_profile_read", "optorch_seq_profile_read_entries",
+    "optorch_seq_destroy", "optorch_seq_predict", "optorch_seq_running_stats", "optorch_seq_profile_enable", "optorch_seq_profile_select", "optorch_seq_profile_read", "optorch_seq_profile_read_entries",
 )
 
 KERNEL_CLASSES = ("cast_in", "conv_fwd", "conv_dgrad", "conv_wgrad", "bn_stats", "bn_apply", "bn_bwd", "pool", "head",
@@ -71,6 +71,10 @@ def load_library() -> C.CDLL:
                                      C.POINTER(C.c_uint64), C.POINTER(C.c_uint64), C.POINTER(C.c_float),
                                      C.POINTER(C.c_int32)]
     lib.optorch_seq_step.restype = C.c_int
+    lib.optorch_seq_predict.argtypes = [H, C.c_void_p, C.c_void_p]
+    lib.optorch_seq_predict.restype = C.c_int
+    lib.optorch_seq_running_stats.argtypes = [H, C.c_void_p, C.c_uint64, C.POINTER(C.c_uint64), C.c_int32]
+    lib.optorch_seq_running_stats.restype = C.c_int
     lib.optorch_seq_schedule_info.argtypes = [H, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
     lib.optorch_seq_schedule_info.restype = C.c_int
     lib.optorch_seq_profile_enable.argtypes = [H, C.c_int32]
@@ -130,6 +134,7 @@ class SeqPlan:
             raise OptorchError(rc, msg)
         self.k_segments = k_segments
         self.batch, self.height, self.width, self.channels = batch, height, width, channels
+        self.num_classes = num_classes
         pc, pb, ab, ps = C.c_uint64(), C.c_uint64(), C.c_uint64(), C.c_uint64()
         bo = (C.c_int32 * max(1, k_segments - 1))()
         self._check(self.lib.optorch_seq_query(self.handle, C.byref(pc), C.byref(pb), C.byref(ab), C.byref(ps), bo))
@@ -219,6 +224,24 @@ class SeqTrainer(SeqPlan):
                                               C.byref(scale), C.byref(skipped)))
         return {"loss": loss.value, "peak_saved_bytes": ps.value, "peak_arena_bytes": pa.value,
                 "loss_scale": scale.value, "skipped": bool(skipped.value)}
+
+    def predict(self, x):
+        """Inference-mode logits (running BatchNorm statistics): cuda float32 tensor batch x num_classes."""
+        torch = self.torch
+        assert x.is_cuda and x.dtype == torch.float32 and x.is_contiguous()
+        assert tuple(x.shape) == (self.batch, self.height, self.width, self.channels)
+        out = torch.empty((self.batch, self.num_classes), dtype=torch.float32, device=self.device)
+        self._check(self.lib.optorch_seq_predict(self.handle, x.data_ptr(), out.data_ptr()))
+        return out
+
+    def running_stats(self) -> np.ndarray:
+        """Per BatchNorm in parameter order: C running means, then C running variances."""
+        n = C.c_uint64()
+        self._check(self.lib.optorch_seq_running_stats(self.handle, None, 0, C.byref(n), 0))
+        out = np.empty(n.value, dtype=np.float32)
+        if n.value:
+            self._check(self.lib.optorch_seq_running_stats(self.handle, out.ctypes.data, out.size, C.byref(n), 0))
+        return out
 
     def profile_enable(self, enable: bool = True):
         self._check(self.lib.optorch_seq_profile_enable(self.handle, 1 if enable else 0))

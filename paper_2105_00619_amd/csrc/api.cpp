@@ -446,6 +446,63 @@ extern "C" int optorch_seq_profile_read_entries(optorch_seq_t* h, int32_t capaci
   return OPTORCH_OK;
 }
 
+// Inference: the forward entries of the schedule (all segments without keeping, then the last segment), with the
+// BatchNorm constants taken from the running statistics and the head stopped at the logits.  The arena offsets of
+// those entries are valid on their own: the entries run in schedule order and the plan never lets two live tensors
+// overlap.
+extern "C" int optorch_seq_predict(optorch_seq_t* h, const float* x_dev, float* logits_dev) {
+  if (!h) return OPTORCH_E_INVALID;
+  if (!h->bound || !h->params_set) return set_err(h, OPTORCH_E_ORDER, "predict before bind/set_params");
+  if (!x_dev || !logits_dev) return set_err(h, OPTORCH_E_INVALID, "null pointer");
+  Ctx c{h, x_dev, nullptr};
+  hipStream_t st = h->stream;
+  const int dt = h->dt;
+  for (const SOp& s : h->plan.sched) {
+    if (!s.live || (s.phase != PH_FWD_NOSAVE && s.phase != PH_FWD_LAST)) continue;
+    const FOp& f = h->plan.fops[s.fop];
+    switch (s.kind) {
+      case S_BN_STATS:
+        launch_bn_eval_stats(st, (const float*)(h->pbase + h->off_run) + f.rs_off, c.w32(f.gamma_off), c.w32(f.beta_off),
+                             h->eps, f.C, (float*)c.at(s.out[0]));
+        break;
+      case S_CONV_FWD: {  // as in training, without the per-block channel sums
+        SOp t = s;
+        t.out[2] = -1;
+        run_op(c, t);
+        break;
+      }
+      case S_HEAD_FWD: {
+        launch_head_logits(st, dt, c.at(s.in[0]), f.N, f.H * f.W, f.C, f.gap, f.feat_dim, f.classes, c.w32(f.w_off),
+                           c.w32(f.b_off), (float*)c.at(s.out[0]), (float*)c.at(s.out[1]));
+        hipError_t e = hipMemcpyAsync(logits_dev, c.at(s.out[1]), (size_t)f.N * f.classes * 4, hipMemcpyDeviceToDevice, st);
+        if (e != hipSuccess) return hip_fail(h, e, "hipMemcpyAsync(logits)");
+        break;
+      }
+      default:
+        run_op(c, s);
+    }
+  }
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return hip_fail(h, e, "kernel launch");
+  e = hipStreamSynchronize(st);
+  if (e != hipSuccess) return hip_fail(h, e, "hipStreamSynchronize");
+  return OPTORCH_OK;
+}
+
+extern "C" int optorch_seq_running_stats(const optorch_seq_t* h, float* dst, uint64_t capacity, uint64_t* count,
+                                         int32_t is_device) {
+  if (!h) return OPTORCH_E_INVALID;
+  if (count) *count = h->plan.n_running;
+  if (!dst) return OPTORCH_OK;  // size query
+  if (!h->bound || !h->params_set) return set_err(h, OPTORCH_E_ORDER, "running_stats before bind/set_params");
+  if (capacity < h->plan.n_running) return set_err(h, OPTORCH_E_INVALID, "running_stats: buffer too small");
+  hipError_t e = hipStreamSynchronize(h->stream);
+  if (e == hipSuccess && h->plan.n_running)
+    e = hipMemcpy(dst, h->pbase + h->off_run, h->plan.n_running * 4, is_device ? hipMemcpyDeviceToDevice : hipMemcpyDeviceToHost);
+  if (e != hipSuccess) return hip_fail(h, e, "hipMemcpy(running statistics)");
+  return OPTORCH_OK;
+}
+
 extern "C" int optorch_seq_step(optorch_seq_t* h, const float* x_dev, const int32_t* y_dev, float lr, float* loss_out,
                                 float* grads_dev, uint64_t* peak_saved_bytes, uint64_t* peak_arena_bytes,
                                 float* loss_scale_out, int32_t* step_skipped) {

@@ -226,6 +226,20 @@ __global__ void __launch_bounds__(256) bn_stats_finalize_kernel(const float* __r
   }
 }
 
+// inference mode: the same four per-channel constants from the running mean and variance
+__global__ void __launch_bounds__(256) bn_eval_stats_kernel(const float* __restrict__ running, const float* __restrict__ gamma,
+                                                            const float* __restrict__ beta, float eps, int C,
+                                                            float* __restrict__ stats) {
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  if (c >= C) return;
+  const double mean = (double)running[c];
+  const double rstd = 1.0 / sqrt((double)running[C + c] + (double)eps);
+  stats[c] = (float)mean;
+  stats[C + c] = (float)rstd;
+  stats[2 * C + c] = (float)((double)gamma[c] * rstd);
+  stats[3 * C + c] = (float)((double)beta[c] - mean * (double)gamma[c] * rstd);
+}
+
 __global__ void __launch_bounds__(256) bn_bwd_finalize_kernel(const float* __restrict__ partial, int nblk, int C, double m,
                                                               float* __restrict__ dgamma, float* __restrict__ dbeta,
                                                               float* __restrict__ coef) {
@@ -482,6 +496,11 @@ static void row_tiling(int64_t rows, int C, int V, RowArgs& g, dim3& grid) {
   while (per_thread > 1 && (int64_t)ceil_div(rows, (int64_t)TY * per_thread) * ytiles < 1024) per_thread /= 2;
   g.rows = rows; g.C = C; g.rows_per_block = TY * per_thread;
   grid = dim3(ceil_div(rows, g.rows_per_block), ytiles);
+}
+
+void launch_bn_eval_stats(hipStream_t st, const float* running, const float* gamma, const float* beta, float eps, int C,
+                          float* stats) {
+  OSEQ_LAUNCH(bn_eval_stats_kernel, dim3(ceil_div(C, 256)), dim3(256), 0, st, running, gamma, beta, eps, C, stats);
 }
 
 void launch_bn_apply(hipStream_t st, int dt, const void* z, const float* stats, const void* skip, void* out, int64_t rows,

@@ -175,14 +175,19 @@ static void launch_feat_bwd(hipStream_t st, const float* dfeat, void* dx, int N,
   }
 }
 
-void launch_head_fwd(hipStream_t st, int dt, const void* x, int N, int HW, int C, int gap, int F, int J, const float* w,
-                     const float* b, const int32_t* y, float gscale, float* feat, float* logits, float* dlogits,
-                     float* loss_n, float* loss_out, int* flags) {
+void launch_head_logits(hipStream_t st, int dt, const void* x, int N, int HW, int C, int gap, int F, int J, const float* w,
+                        const float* b, float* feat, float* logits) {
   const dim3 feat_grid(N, gap ? ceil_div(C, 64) : 1);
   if (dt == DT_F32) OSEQ_LAUNCH(head_feat_kernel<float>, feat_grid, dim3(256), 0, st, (const float*)x, feat, HW, C, gap);
   else if (dt == DT_BF16) OSEQ_LAUNCH(head_feat_kernel<bf16_t>, feat_grid, dim3(256), 0, st, (const bf16_t*)x, feat, HW, C, gap);
   else OSEQ_LAUNCH(head_feat_kernel<f16_t>, feat_grid, dim3(256), 0, st, (const f16_t*)x, feat, HW, C, gap);
   OSEQ_LAUNCH(linear_fwd_kernel, dim3(ceil_div((int64_t)N * J, 4)), dim3(256), 0, st, feat, w, b, logits, N, F, J);
+}
+
+void launch_head_fwd(hipStream_t st, int dt, const void* x, int N, int HW, int C, int gap, int F, int J, const float* w,
+                     const float* b, const int32_t* y, float gscale, float* feat, float* logits, float* dlogits,
+                     float* loss_n, float* loss_out, int* flags) {
+  launch_head_logits(st, dt, x, N, HW, C, gap, F, J, w, b, feat, logits);
   OSEQ_LAUNCH(softmax_ce_kernel, dim3(ceil_div(N, 4)), dim3(256), 0, st, logits, y, loss_n, dlogits, N, J, gscale, flags);
   OSEQ_LAUNCH(loss_mean_kernel, dim3(1), dim3(256), 0, st, loss_n, N, loss_out);
 }

@@ -19,6 +19,9 @@ void launch_bn_stats(hipStream_t st, int dt, const void* z, int64_t rows, int C,
 int bn_stats_fold_rows(int nblk);
 void launch_bn_stats_finalize(hipStream_t st, float* partial, int64_t rows, int C, int nblk, float eps, float mom,
                               const float* gamma, const float* beta, float* stats, float* running);
+// inference mode: (mean, rstd, scale, shift) from the running statistics [2][C] instead of the batch
+void launch_bn_eval_stats(hipStream_t st, const float* running, const float* gamma, const float* beta, float eps, int C,
+                          float* stats);
 void launch_bn_apply(hipStream_t st, int dt, const void* z, const float* stats, const void* skip, void* out, int64_t rows,
                      int C, int relu);
 void launch_bn_bwd(hipStream_t st, int dt, const void* da, const void* z, const void* aout, const float* stats, int64_t rows,
@@ -31,6 +34,9 @@ void launch_maxpool_bwd(hipStream_t st, int dt, const void* x, const void* dy, v
 void launch_head_fwd(hipStream_t st, int dt, const void* x, int N, int HW, int C, int gap, int F, int J, const float* w,
                      const float* b, const int32_t* y, float gscale, float* feat, float* logits, float* dlogits,
                      float* loss_n, float* loss_out, int* flags);
+// forward of the head up to the logits (no loss): inference
+void launch_head_logits(hipStream_t st, int dt, const void* x, int N, int HW, int C, int gap, int F, int J, const float* w,
+                        const float* b, float* feat, float* logits);
 void launch_head_bwd(hipStream_t st, int dt, const float* feat, const float* dlogits, const float* w, int N, int HW, int C,
                      int gap, int F, int J, float* dw, float* db, float* dfeat, void* dx);
 

@@ -7,7 +7,7 @@ from paper_2105_00619_amd import workloads as W
 TOL = {W.FP32: 1e-4, W.BF16: 2e-2, W.FP16: 2e-2}  # relative L2 per gradient tensor
 
 
-def gpu_step(units, params, x, y, *, precision, k, classes, lr=0.01, momentum=0.0, steps=1, **kw):
+def gpu_step(units, params, x, y, *, precision, k, classes, lr=0.01, momentum=0.0, steps=1, predict_x=None, **kw):
     import torch
     from paper_2105_00619_amd.binding import SeqTrainer
     b, h, w, c = x.shape
@@ -22,6 +22,9 @@ def gpu_step(units, params, x, y, *, precision, k, classes, lr=0.01, momentum=0.
         r = t.step(xd, yd, lr, gd)
         r["grads"] = gd.cpu().numpy().copy()
         r["params"] = t.get_params()
+        if predict_x is not None:  # inference-mode logits on predict_x and the running statistics after this step
+            r["running"] = t.running_stats()
+            r["logits"] = t.predict(torch.from_numpy(np.ascontiguousarray(predict_x, dtype=np.float32)).cuda()).cpu().numpy()
         outs.append(r)
     info = {"planned_peak_saved_bytes": t.planned_peak_saved_bytes, "act_arena_bytes": t.act_arena_bytes,
             "boundaries": t.boundaries, "n_launches": t.n_launches, "n_replay_launches": t.n_replay_launches}

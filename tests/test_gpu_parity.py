@@ -274,6 +274,47 @@ def test_training_loop_tracks_oracle_over_25_steps():
     assert losses[-1] < 0.7 * losses[0] and outs[-1]["loss"] < 0.7 * outs[0]["loss"]
 
 
+@pytest.mark.parametrize("name", ["conv_bn_relu", "basic_projection", "bottleneck", "maxpool_flatten"])
+@pytest.mark.parametrize("precision", [W.FP32, W.BF16, W.FP16])
+def test_running_statistics_and_inference_match_oracle(name, precision):
+    """Three training steps, then inference on other images: the running BatchNorm statistics after every step
+    against the oracle's update from its own batch moments at the same weights, and the inference-mode logits
+    against the oracle's inference forward at the library's weights and running statistics."""
+    from oracle import seqnet_oracle as O
+    from tests.gpu_util import STORAGE
+    units, classes = NETS[name]
+    p, x, y = _inputs(units, 6, 12, 12, classes)
+    _, x2, _ = _inputs(units, 6, 12, 12, classes, seed=77)
+    outs, _ = gpu_step(units, p, x, y, precision=precision, k=2, classes=classes, lr=0.05, momentum=0.9, steps=3,
+                       predict_x=x2, loss_scale_init=_scale(precision))
+    tol = TOL[precision]
+    w = p.astype(np.float64)
+    running = O.initial_running_stats(units, w, x.shape)
+    for i, o in enumerate(outs):
+        assert not o["skipped"]
+        # the step's forward ran at the weights before its update
+        running = O.update_running_stats(running, O.batch_moments(units, w, x, storage=STORAGE[precision]), 0.1)
+        assert o["running"].size == running.size
+        assert np.linalg.norm(o["running"] - running) <= tol * np.linalg.norm(running), (i, name)
+        w = o["params"].astype(np.float64)
+        ref = O.predict(units, w, o["running"].astype(np.float64), x2, storage=STORAGE[precision])
+        assert np.linalg.norm(o["logits"] - ref) <= tol * max(1.0, np.linalg.norm(ref)), (i, name)
+        running = o["running"].astype(np.float64)  # errors are not carried from step to step
+
+
+def test_inference_at_benchmark_size_matches_oracle():
+    """Inference on the benchmark network at its full batch after one training step (fp32 mode)."""
+    from oracle import seqnet_oracle as O
+    wl = W.config(2)
+    p, x, y = W.make_batch(wl)
+    r, _ = gpu_step(wl.units, p, x, y, precision=W.FP32, k=wl.k_segments, classes=wl.classes, predict_x=x[::-1].copy())
+    ref = O.predict(wl.units, r["params"].astype(np.float64), r["running"].astype(np.float64), x[::-1])
+    assert np.linalg.norm(r["logits"] - ref) <= 1e-4 * np.linalg.norm(ref)
+    moments = O.batch_moments(wl.units, p.astype(np.float64), x)
+    run = O.update_running_stats(O.initial_running_stats(wl.units, p.astype(np.float64), x.shape), moments, 0.1)
+    assert np.linalg.norm(r["running"] - run) <= 1e-5 * np.linalg.norm(run)
+
+
 def test_label_out_of_range_is_an_error():
     from paper_2105_00619_amd.binding import OptorchError
     units, classes = NETS["conv_bn_relu"]
