@@ -22,6 +22,8 @@
 
 namespace oseq {
 
+int g_w9_wide_min = 8;  // tuning constant (not part of the C ABI): fewest sub-tiles per block for 128-channel blocks
+
 namespace {
 
 typedef __attribute__((ext_vector_type(16))) float v16f;
@@ -289,18 +291,24 @@ bool w9_plan(int dt, const ConvGeom& g, W9Plan& pl) {
   if (!w9_geometry(g.N, g.P, g.Q, cap, maxpos, a)) return false;
   if (a.TP * 2 < cap) return false;  // short sub-tiles: too little work between barriers
   a.N = g.N; a.H = g.H; a.W = g.W; a.C = g.C; a.K = g.K; a.P = g.P; a.Q = g.Q; a.pad = g.pad;
-  // 16-bit: 128 output channels per block when possible (fewer operand fetches per MFMA); fp32: 64
-  const int mi = (dt != DT_F32 && g.K % 128 == 0) ? 2 : 1;
-  const int64_t tiles = (int64_t)(g.K / (64 * mi)) * (g.C / 64);
-  int64_t s = tiles >= 256 ? 1 : (256 + tiles / 2) / tiles;  // about one block per CU
-  if (s > a.NT) s = a.NT;
-  if (s > 256) s = 256;
-  if (s < 1) s = 1;
-  a.tiles_per_split = (int)((a.NT + s - 1) / s);
-  s = (a.NT + a.tiles_per_split - 1) / a.tiles_per_split;  // no empty ranges
-  if (tiles * s < 128) return false;  // too few blocks for the chip: one tap per block does better
-  pl.a = a; pl.mi = mi; pl.splits = (int)s;
-  return true;
+  // fp32: 64 output channels per block.  16-bit: 128 when possible (fewer operand fetches per MFMA), unless the blocks
+  // would then get fewer than g_w9_wide_min sub-tiles each: a block's accumulators (9 taps x 64*MI x 64 floats) are
+  // written out once per pixel range and read again by the reduction, and with few sub-tiles per range that traffic
+  // outweighs the operand reuse (128->128 at 16x16, batch 256, bf16: 55 -> 49 us with 64; batch 1024: 132 vs 140 us).
+  for (int mi = (dt != DT_F32 && g.K % 128 == 0) ? 2 : 1; mi >= 1; --mi) {
+    const int64_t tiles = (int64_t)(g.K / (64 * mi)) * (g.C / 64);
+    int64_t s = tiles >= 256 ? 1 : (256 + tiles / 2) / tiles;  // about one block per CU
+    if (s > a.NT) s = a.NT;
+    if (s > 256) s = 256;
+    if (s < 1) s = 1;
+    a.tiles_per_split = (int)((a.NT + s - 1) / s);
+    s = (a.NT + a.tiles_per_split - 1) / a.tiles_per_split;  // no empty ranges
+    if (mi == 2 && a.tiles_per_split < g_w9_wide_min) continue;
+    if (tiles * s < 128) return false;  // too few blocks for the chip: one tap per block does better
+    pl.a = a; pl.mi = mi; pl.splits = (int)s;
+    return true;
+  }
+  return false;
 }
 
 template <class T, int MI>
