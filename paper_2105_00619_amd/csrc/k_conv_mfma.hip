@@ -14,6 +14,8 @@
 // 64 bytes per row (16 fp32 / 32 half elements, so one depth tile never straddles a filter tap when C_src % BK == 0).
 // Each lane keeps 32 bytes of every operand row per depth tile; global loads for tile t+1 are issued before the
 // MFMAs of tile t (register prefetch + two LDS buffers, one barrier per tile).
+#include <algorithm>
+
 #include "dev_common.h"
 #include "epilogue.h"
 #include "kernels.h"
@@ -367,12 +369,13 @@ struct PatchArgs {
   int relu;
   int chunks_per_split;      // channel chunks per blockIdx.z (all of them when the depth is not split)
   int row_pitch;             // bytes between staged patch rows in LDS (>= SC * 80, padded against bank conflicts)
+  int patch_elems;           // elements of one staged patch buffer (its rows times row_pitch, rounded up to 16 bytes)
 };
 
 constexpr int PATCH_MAX_POS = 256;  // positions per sub-tile
 
 template <class T, int BN, int MI, int SUBT, bool STAT>
-__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, MI == 4 ? 1 : 2)))
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(BN == 64 ? 3 : 1, BN == 64 ? 3 : 2)))
 conv3x3_patch_kernel(const T* __restrict__ src, const T* __restrict__ wmat, const float* __restrict__ bias,
                      const T* __restrict__ addend, T* __restrict__ out, float* __restrict__ partial,
                      float* __restrict__ stat_partial, PatchArgs a) {
@@ -386,8 +389,9 @@ conv3x3_patch_kernel(const T* __restrict__ src, const T* __restrict__ wmat, cons
   constexpr int NI = BN / 64;
   constexpr int B_CH = BN * 4 / 256;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-  T* patch = reinterpret_cast<T*>(smem_raw);                                  // [2][SUBT*PATCH_MAX_POS][PITCH]
-  T* Bs = patch + 2 * SUBT * PATCH_MAX_POS * PITCH;                           // [3][BN][PITCH]
+  const int PBUF = a.patch_elems;                                             // one patch buffer, sized for this layer
+  T* patch = reinterpret_cast<T*>(smem_raw);                                  // [2][PBUF]
+  T* Bs = patch + 2 * PBUF;                                                   // [3][BN][PITCH]
   int64_t* src_off = reinterpret_cast<int64_t*>(Bs + 3 * BN * PITCH);         // [SUBT*PATCH_MAX_POS]
   int64_t* out_off = src_off + SUBT * PATCH_MAX_POS;                          // [256]
   int* apos = reinterpret_cast<int*>(out_off + 256);                          // [256]
@@ -469,7 +473,7 @@ conv3x3_patch_kernel(const T* __restrict__ src, const T* __restrict__ wmat, cons
   auto patch_load = [&](int slot, int chunk) { return *reinterpret_cast<const Chunk*>(pptr[slot] + chunk * CCE); };
   auto patch_store = [&](int slot, int buf, const Chunk& c) {
     if ((pstore >> slot) & 1u)
-      *reinterpret_cast<Chunk*>(&patch[buf * SUBT * PATCH_MAX_POS * PITCH + pdst[slot]]) = ((pvalid >> slot) & 1u) ? c : zero_chunk();
+      *reinterpret_cast<Chunk*>(&patch[buf * PBUF + pdst[slot]]) = ((pvalid >> slot) & 1u) ? c : zero_chunk();
   };
   const T* wrow = wmat + (int64_t)(n0c + brow0) * Kg + bvec * EV;
   // weight tile of global step gs = chunk*9 + tap -> registers REG
@@ -526,8 +530,8 @@ conv3x3_patch_kernel(const T* __restrict__ src, const T* __restrict__ wmat, cons
   auto chunk_body = [&](auto LAST, int chunk) {
     constexpr bool last = decltype(LAST)::value != 0;
     const int pbuf = (chunk - cb) & 1;
-    const T* pcur = patch + pbuf * SUBT * PATCH_MAX_POS * PITCH;
-    const T* pnxt = patch + (pbuf ^ 1) * SUBT * PATCH_MAX_POS * PITCH;
+    const T* pcur = patch + pbuf * PBUF;
+    const T* pnxt = patch + (pbuf ^ 1) * PBUF;
 #pragma unroll
     for (int t = 0; t < 9; ++t) {
       // where the next step reads its operands
@@ -686,9 +690,13 @@ static void launch_splitk_epilogue(hipStream_t st, const float* partial, int spl
                      (T*)out, stat_partial, relu);
 }
 
-template <class T> constexpr size_t patch_smem_bytes(int bn, int subt) {
-  return (size_t)(2 * subt * PATCH_MAX_POS + 3 * bn) * (Frag<T>::BK + 16 / sizeof(T)) * sizeof(T) + subt * PATCH_MAX_POS * 8 +
+// LDS of the patch kernel: two patch buffers of patch_elems elements, three weight stages, the address tables
+template <class T> constexpr size_t patch_smem_bytes(int bn, int subt, int64_t patch_elems) {
+  return (size_t)(2 * patch_elems + 3 * bn * (Frag<T>::BK + 16 / sizeof(T))) * sizeof(T) + subt * PATCH_MAX_POS * 8 +
          256 * 8 + 256 * 4;
+}
+template <class T> constexpr size_t patch_smem_max(int bn, int subt) {
+  return patch_smem_bytes<T>(bn, subt, (int64_t)subt * PATCH_MAX_POS * (Frag<T>::BK + 16 / sizeof(T)));
 }
 
 // tile geometry of the patch kernel for a (dstH x dstW) pixel grid gathered with a 3x3 window and sub-tiles of up to
@@ -782,13 +790,25 @@ static bool patch_pick(int dt, int N, int dstH, int dstW, int srcC, int Ng, int 
 
 template <class T, int BN, int MI, int SUBT>
 static void launch_patch_v(hipStream_t st, const void* src, const void* wmat, const float* bias, const void* addend, void* out,
-                           float* partial, float* stat_partial, int splits, const PatchArgs& a) {
+                           float* partial, float* stat_partial, int splits, const PatchArgs& a_in) {
+  PatchArgs a = a_in;
   dim3 grid((a.NT + SUBT - 1) / SUBT, a.Ng / BN, splits), block(256);
-  constexpr size_t sm = patch_smem_bytes<T>(BN, SUBT);
+  // The patch buffers are sized for this layer's tile (its staged rows times the row pitch), not for the largest one,
+  // so that the 64-channel shapes fit three blocks per CU on most layers.  The epilogue reuses the buffers and the
+  // weight stages: they must hold its fp32 tile and the 16 KB of the channel-sum combine.
+  constexpr size_t sm_max = patch_smem_max<T>(BN, SUBT);
+  constexpr int64_t PITCH_E = Frag<T>::BK + 16 / sizeof(T);
+  const int64_t epi_bytes = std::max<int64_t>((int64_t)32 * MI * (BN + 4) * 4, 16384);
+  int64_t pe = ((int64_t)SUBT * a.TI * a.SR * a.row_pitch + 15) / 16 * 16 / (int64_t)sizeof(T);
+  const int64_t need = (epi_bytes - (int64_t)3 * BN * PITCH_E * (int64_t)sizeof(T) + 1) / 2;  // bytes per buffer
+  if (pe * (int64_t)sizeof(T) < need) pe = (need + 15) / 16 * 16 / (int64_t)sizeof(T);
+  if (pe > (int64_t)SUBT * PATCH_MAX_POS * PITCH_E) pe = (int64_t)SUBT * PATCH_MAX_POS * PITCH_E;
+  a.patch_elems = (int)pe;
+  const size_t sm = patch_smem_bytes<T>(BN, SUBT, pe);
   static bool attr_done = false;
   if (!attr_done) {
-    (void)hipFuncSetAttribute((const void*)conv3x3_patch_kernel<T, BN, MI, SUBT, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sm);
-    (void)hipFuncSetAttribute((const void*)conv3x3_patch_kernel<T, BN, MI, SUBT, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sm);
+    (void)hipFuncSetAttribute((const void*)conv3x3_patch_kernel<T, BN, MI, SUBT, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sm_max);
+    (void)hipFuncSetAttribute((const void*)conv3x3_patch_kernel<T, BN, MI, SUBT, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sm_max);
     attr_done = true;
   }
   // the variant that also adds up what it stores (BatchNorm statistics) is a separate instantiation, so that the
