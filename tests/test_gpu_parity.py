@@ -167,6 +167,66 @@ def test_deep_configs_reduced_batch(index, batch, fp32_too):
     assert info["n_replay_launches"] > 0
 
 
+def test_config3_full_size_bf16():
+    """ResNet-18 in bf16 at the benchmark's batch (256) and segments (k = 4): gradients bit-identical to k = 1, and
+    against the oracle by the same criterion as at reduced batch (as close to float64 as the oracle's own 16-bit
+    storage emulation is)."""
+    from tests.gpu_util import conditioned_tolerance, tensor_errors
+    wl = W.config(3)
+    p, x, y = W.make_batch(wl, perturb=True)
+    r, info = gpu_step(wl.units, p, x, y, precision=wl.precision, k=wl.k_segments, classes=wl.classes)
+    one, info1 = gpu_step(wl.units, p, x, y, precision=wl.precision, k=1, classes=wl.classes)
+    assert np.array_equal(r["grads"], one["grads"]) and r["loss"] == one["loss"]
+    assert info["planned_peak_saved_bytes"] < 0.5 * info1["planned_peak_saved_bytes"]
+    assert r["peak_saved_bytes"] == info["planned_peak_saved_bytes"] and info["n_replay_launches"] > 0
+    loss64, g64 = oracle_step(wl.units, p, x, y)
+    _, o16 = oracle_step(wl.units, p, x, y, wl.precision, 1.0)
+    tol16 = conditioned_tolerance(wl.units, 32, 32, g64, o16, 2e-2, factor=1.5)
+    e16 = tensor_errors(wl.units, 32, 32, r["grads"], g64)
+    assert all(e16[k] <= tol16[k] for k in e16), max((e16[k] / tol16[k], k) for k in e16)
+    assert abs(r["loss"] - loss64) <= 2e-2 * abs(loss64)
+
+
+def test_config4_full_size_fp16_invariants():
+    """ResNet-50 in fp16 at the benchmark's batch (512) and segments (k = 8), dynamic loss scale from 2^16: what holds
+    at any size -- gradients bit-identical to k = 1 and from run to run, observed peaks equal to the planned ones,
+    less than a third of the all-stored bytes."""
+    wl = W.config(4)
+    p, x, y = W.make_batch(wl, perturb=True)
+    kw = dict(precision=wl.precision, classes=wl.classes, loss_scale_init=wl.loss_scale_init)
+    a, ia = gpu_step(wl.units, p, x, y, k=wl.k_segments, **kw)
+    b, _ = gpu_step(wl.units, p, x, y, k=wl.k_segments, **kw)
+    one, i1 = gpu_step(wl.units, p, x, y, k=1, **kw)
+    assert a["skipped"] == b["skipped"] == one["skipped"]
+    assert np.array_equal(a["grads"], b["grads"]) and np.array_equal(a["grads"], one["grads"]) and a["loss"] == one["loss"]
+    assert np.isfinite(a["loss"])
+    assert a["peak_saved_bytes"] == ia["planned_peak_saved_bytes"] and a["peak_arena_bytes"] == ia["act_arena_bytes"]
+    assert ia["planned_peak_saved_bytes"] < i1["planned_peak_saved_bytes"] / 3
+
+
+def test_config5_full_size_runs_within_its_budget():
+    """ResNet-152 in bf16, batch 4096, k = 7 under the 32 GiB activation budget (all stored it would need 142 GiB):
+    the step runs inside the planned arena, twice with identical results."""
+    import torch
+    from paper_2105_00619_amd.binding import SeqTrainer
+    wl = W.config(5)
+    tr = SeqTrainer.from_workload(wl)
+    assert tr.act_arena_bytes <= wl.budget_bytes
+    p, x, y = W.make_batch(wl)
+    xd, yd = torch.from_numpy(x).cuda(), torch.from_numpy(y).cuda()
+    gd = torch.empty(tr.param_count, dtype=torch.float32, device="cuda")
+    out = []
+    for _ in range(2):
+        tr.set_params(p)
+        r = tr.step(xd, yd, 0.01, gd)
+        out.append((r["loss"], gd.clone()))
+        assert not r["skipped"] and np.isfinite(r["loss"])
+        assert r["peak_arena_bytes"] == tr.act_arena_bytes and r["peak_saved_bytes"] == tr.planned_peak_saved_bytes
+    assert out[0][0] == out[1][0] and torch.equal(out[0][1], out[1][1])
+    assert bool(torch.isfinite(out[0][1]).all())
+    tr.close()
+
+
 def test_large_image_config_reduced_size():
     """The large-image workload (ResNet-18 on 512 x 512 images, batch 16) at 64 x 64 and batch 2: the same network
     with image sizes that are not the 32 x 32 of the other configurations (rows of 64, 32, 16 and 8 pixels)."""
