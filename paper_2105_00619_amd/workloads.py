@@ -279,6 +279,16 @@ def make_images(batch, height, width, channels, seed=MASTER_SEED, pixels="gauss"
     return x.astype(np.float32)
 
 
+def make_pixels_u8(batch, height, width, channels, seed=MASTER_SEED, pixels="gauss") -> np.ndarray:
+    """NHWC uint8 images: the 8-bit pixels of a colour image (per-channel N(128, 64^2) clipped to 0..255, or uniform
+    over 0..255); stand-ins for the 8-bit images of a dataset such as CIFAR."""
+    g = _rng(seed, 5)
+    if pixels == "uniform":
+        return g.integers(0, 256, size=(batch, height, width, channels), dtype=np.uint8)
+    x = np.rint(np.clip(128.0 + 64.0 * g.standard_normal((batch, height, width, channels)), 0.0, 255.0))
+    return x.astype(np.uint8)
+
+
 def make_labels(batch, classes, seed=MASTER_SEED) -> np.ndarray:
     return _rng(seed, 2).integers(0, classes, size=batch).astype(np.int32)
 
