@@ -65,6 +65,91 @@ def cpu_baseline(config_index, sample_batch, min_seconds=12.0):
             "sample": "%d float64 training steps of the same network on batch %d (%.1f s)" % (steps, sample_batch, dt)}
 
 
+def dataflow_cpu_baseline(z, n_pos, min_seconds=10.0):
+    """The data-flow oracle as it stands (exact Python integers) on a bounded sample: whole groups of z images."""
+    import numpy as np
+    from oracle import dataflow_oracle as D
+    from paper_2105_00619_amd import workloads as W
+    X = W.make_pixels_u8(z, 32, 32, 3, seed=W.MASTER_SEED).reshape(z, -1)[:, :n_pos]
+    groups = 0
+    t0 = time.perf_counter()
+    while True:
+        words = D.to_words(D.encode(X), D.words_needed(z, 8))
+        D.decode_normalized(words[None], z, z, 3, [1 / 255.0] * 3, [0.0] * 3)
+        groups += 1
+        dt = time.perf_counter() - t0
+        if dt >= min_seconds:
+            break
+    return {"value": groups * z / dt, "unit": "images/sec", "cores": 1, "kind": "oracle",
+            "sample": "%d groups of %d images of 32x32x3 encoded and decoded with normalisation in exact integers (%.1f s)"
+                      % (groups, z, dt)}
+
+
+def dataflow_main(args):
+    """--path dataflow: one step = Encode of an epoch-sized set of 8-bit images in groups of 16, then the decode layer
+    (Decode + normalisation + cast to bf16) over all of it; both kernels are bound by HBM traffic."""
+    import numpy as np
+    import torch
+    from paper_2105_00619_amd import binding as B
+    from paper_2105_00619_amd import workloads as W
+    if not os.path.exists(B.LIB_PATH):
+        import __graft_entry__
+        __graft_entry__.build()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    batch, h, w, c, z = args.batch or 50000, 32, 32, 3, 16
+    n_pos = h * w * c
+    g = torch.Generator(device="cuda").manual_seed(W.MASTER_SEED)
+    x = torch.randint(0, 256, (batch, n_pos), dtype=torch.uint8, device="cuda", generator=g)
+    words = B.encoded_words(z)
+    a = torch.empty((-(-batch // z), n_pos, words), dtype=torch.int64, device="cuda")
+    out = torch.empty((batch, n_pos), dtype=torch.bfloat16, device="cuda")
+    xb = torch.empty_like(x)
+    scale, shift = [1 / (255 * 0.25)] * 3, [-0.5 / 0.25] * 3
+    ops = {
+        "encode_kernel": (lambda: B.encode(x, z, out=a), batch * n_pos * 2.0),
+        "decode_kernel<bf16>": (lambda: B.decode_normalized(a, batch, n_pos, z, c, scale, shift, W.BF16, out=out), batch * n_pos * 3.0),
+        "decode_kernel<u8>": (lambda: B.decode(a, batch, n_pos, z, out=xb), batch * n_pos * 2.0),
+    }
+    per_kernel = {}
+    for name, (fn, nbytes) in ops.items():
+        for _ in range(args.warmup):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(args.steps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / args.steps
+        per_kernel[name] = {"avg_launch_us": us, "bytes_per_launch": nbytes, "gb_per_s": nbytes / us / 1e3}
+    assert bool((xb == x).all()), "decode(encode(x)) != x"
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        B.encode(x, z, out=a)
+        B.decode_normalized(a, batch, n_pos, z, c, scale, shift, W.BF16, out=out)
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / args.steps
+    dom = "decode_kernel<bf16>"
+    line = {
+        "metric": "images/sec", "value": batch / dt, "unit": "images/sec", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": dt * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u8", "data": "synthetic",
+        "config": {"workload": "dataflow_encode_decode_%dx32x32x3_z16" % batch, "images": batch, "image": "32x32x3 uint8",
+                   "images_per_group": z, "step": "Encode, then Decode + normalisation + cast to bf16"},
+        "roofline": {"bound": "hbm", "achieved": per_kernel[dom]["gb_per_s"], "peak": PEAK["hbm"], "unit": "GB/s",
+                     "frac": per_kernel[dom]["gb_per_s"] / PEAK["hbm"], "traffic": None, "kernel": dom,
+                     "avg_launch_us": per_kernel[dom]["avg_launch_us"],
+                     "algorithmic_bytes_per_launch": per_kernel[dom]["bytes_per_launch"],
+                     "timing": "HIP events on the launch stream around %d back-to-back launches" % args.steps},
+        "kernels": per_kernel,
+    }
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = dataflow_cpu_baseline(z, n_pos)
+    print(json.dumps(line))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -78,10 +163,16 @@ def main():
     ap.add_argument("--survey-steps", type=int, default=5, help="untimed steps with every kernel class event-timed")
     ap.add_argument("--timed-every", type=int, default=4,
                     help="steps of the timed region whose dominant-class launches carry events: every n-th")
+    ap.add_argument("--path", choices=("train", "dataflow"), default="train",
+                    help="train: the checkpointed training step (default); dataflow: image Encode + decode layer")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: the step has no inter-GPU path (run with --gpus 1)", file=sys.stderr)
         sys.exit(2)
+
+    if args.path == "dataflow":
+        dataflow_main(args)
+        return
 
     import numpy as np
     import torch

@@ -133,6 +133,18 @@ int optorch_seq_step(optorch_seq_t* h, const float* x_dev, const int32_t* y_dev,
                      float* loss_out, float* grads_dev, uint64_t* peak_saved_bytes,
                      uint64_t* peak_arena_bytes, float* loss_scale_out, int32_t* step_skipped);
 
+/* optorch_seq_step on a batch that arrives encoded (paper, Section "Image Data-flow Optimization": the network's
+ * first layer decodes).  a_dev is the batch in the form optorch_encode of optorch_dataflow.h produces for groups of z
+ * images of height x width x channels 8-bit pixels: device, uint64 [ceil(batch / z)][height * width * channels][words].
+ * The step's first kernel is Algorithm "Decode" fused with pixel * scale[c] + shift[c] (fp32, one fused multiply-add)
+ * and the cast to the storage type; it takes the place of the cast of an fp32 batch, and everything after it is
+ * optorch_seq_step.  scale_host / shift_host: `channels` floats each, host memory, read during the call; the
+ * network's input must have at most 16 channels; 1 <= z <= 16.  Other arguments and errors as optorch_seq_step. */
+int optorch_seq_step_encoded(optorch_seq_t* h, const uint64_t* a_dev, int32_t z, const float* scale_host,
+                             const float* shift_host, const int32_t* y_dev, float lr, float* loss_out,
+                             float* grads_dev, uint64_t* peak_saved_bytes, uint64_t* peak_arena_bytes,
+                             float* loss_scale_out, int32_t* step_skipped);
+
 /* Inference with the network as it stands (the counterpart of training-mode BatchNorm; the paper evaluates its
  * trained networks, Section "Sequential-checkpoint training"): the forward pass of every segment, nothing kept, with
  * each BatchNorm using its running mean and variance instead of the batch statistics, up to the logits.

@@ -21,6 +21,9 @@ SYMBOLS = (
     "optorch_seq_create", "optorch_seq_query", "optorch_seq_bind", "optorch_seq_set_params",
     "optorch_seq_get_params", "optorch_seq_step", "optorch_seq_schedule_info", "optorch_seq_last_error",
     "optorch_seq_destroy", "optorch_seq_predict", "optorch_seq_running_stats", "optorch_seq_profile_enable", "optorch_seq_profile_select", "optorch_seq_profile_read", "optorch_seq_profile_read_entries",
+    "optorch_seq_step_encoded",
+    "optorch_encoded_words", "optorch_encode", "optorch_decode", "optorch_decode_normalized", "optorch_encode_lossless",
+    "optorch_decode_lossless", "optorch_dataflow_last_error",
 )
 
 KERNEL_CLASSES = ("cast_in", "conv_fwd", "conv_dgrad", "conv_wgrad", "bn_stats", "bn_apply", "bn_bwd", "pool", "head",
@@ -71,6 +74,25 @@ def load_library() -> C.CDLL:
                                      C.POINTER(C.c_uint64), C.POINTER(C.c_uint64), C.POINTER(C.c_float),
                                      C.POINTER(C.c_int32)]
     lib.optorch_seq_step.restype = C.c_int
+    lib.optorch_seq_step_encoded.argtypes = [H, C.c_void_p, C.c_int32, C.POINTER(C.c_float), C.POINTER(C.c_float), C.c_void_p,
+                                             C.c_float, C.POINTER(C.c_float), C.c_void_p, C.POINTER(C.c_uint64),
+                                             C.POINTER(C.c_uint64), C.POINTER(C.c_float), C.POINTER(C.c_int32)]
+    lib.optorch_seq_step_encoded.restype = C.c_int
+    lib.optorch_encoded_words.argtypes = [C.c_int32, C.c_int32]
+    lib.optorch_encoded_words.restype = C.c_int32
+    lib.optorch_encode.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p]
+    lib.optorch_encode.restype = C.c_int
+    lib.optorch_decode.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p]
+    lib.optorch_decode.restype = C.c_int
+    lib.optorch_decode_normalized.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_int32, C.c_int32, C.POINTER(C.c_float),
+                                              C.POINTER(C.c_float), C.c_int32, C.c_void_p, C.c_void_p]
+    lib.optorch_decode_normalized.restype = C.c_int
+    lib.optorch_encode_lossless.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.optorch_encode_lossless.restype = C.c_int
+    lib.optorch_decode_lossless.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p]
+    lib.optorch_decode_lossless.restype = C.c_int
+    lib.optorch_dataflow_last_error.argtypes = []
+    lib.optorch_dataflow_last_error.restype = C.c_char_p
     lib.optorch_seq_predict.argtypes = [H, C.c_void_p, C.c_void_p]
     lib.optorch_seq_predict.restype = C.c_int
     lib.optorch_seq_running_stats.argtypes = [H, C.c_void_p, C.c_uint64, C.POINTER(C.c_uint64), C.c_int32]
@@ -225,6 +247,26 @@ class SeqTrainer(SeqPlan):
         return {"loss": loss.value, "peak_saved_bytes": ps.value, "peak_arena_bytes": pa.value,
                 "loss_scale": scale.value, "skipped": bool(skipped.value)}
 
+    def step_encoded(self, a, z: int, scale, shift, y, lr: float, grads=None) -> dict:
+        """`step` on a batch in encoded form: a = `encode(pixels, z)` of the batch's 8-bit pixels; the decode layer maps
+        every pixel to pixel * scale[c] + shift[c] (`channels` floats each)."""
+        torch = self.torch
+        words = encoded_words(z)
+        groups = -(-self.batch // z)
+        assert a.is_cuda and a.dtype == torch.int64 and a.is_contiguous()
+        assert a.numel() == groups * self.height * self.width * self.channels * words
+        assert y.is_cuda and y.dtype == torch.int32 and y.numel() == self.batch
+        if grads is not None:
+            assert grads.is_cuda and grads.dtype == torch.float32 and grads.numel() == self.param_count
+        sc, sh = _float_array(scale, self.channels), _float_array(shift, self.channels)
+        loss, lscale, skipped = C.c_float(), C.c_float(), C.c_int32()
+        ps, pa = C.c_uint64(), C.c_uint64()
+        self._check(self.lib.optorch_seq_step_encoded(self.handle, a.data_ptr(), z, sc, sh, y.data_ptr(), lr, C.byref(loss),
+                                                      grads.data_ptr() if grads is not None else None, C.byref(ps),
+                                                      C.byref(pa), C.byref(lscale), C.byref(skipped)))
+        return {"loss": loss.value, "peak_saved_bytes": ps.value, "peak_arena_bytes": pa.value,
+                "loss_scale": lscale.value, "skipped": bool(skipped.value)}
+
     def predict(self, x):
         """Inference-mode logits (running BatchNorm statistics): cuda float32 tensor batch x num_classes."""
         torch = self.torch
@@ -273,3 +315,103 @@ class SeqTrainer(SeqPlan):
         self._check(self.lib.optorch_seq_profile_read_entries(self.handle, cap, C.byref(n), kind, unit, phase, ms, fl, by))
         return [{"kind": KERNEL_CLASSES[kind[i]], "unit": unit[i], "phase": phase[i], "gpu_ms": ms[i], "flops": fl[i],
                  "bytes": by[i]} for i in range(min(n.value, cap))]
+
+
+# ---- image data-flow (optorch_dataflow.h): tensors allocated through torch, kernels on torch's current stream ----------
+# Encoded words are unsigned 64-bit; torch carries them as int64 tensors of the same bits.
+
+def _float_array(values, n: int):
+    v = [float(t) for t in values]
+    if len(v) != n:
+        raise ValueError("expected %d values, got %d" % (n, len(v)))
+    return (C.c_float * n)(*v)
+
+
+def _df_check(rc: int):
+    if rc != OK:
+        raise OptorchError(rc, (load_library().optorch_dataflow_last_error() or b"").decode())
+
+
+def _stream(torch):
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def encoded_words(z: int, lossless: bool = False) -> int:
+    """64-bit words per position for groups of z images; raises for z outside the form's range."""
+    n = load_library().optorch_encoded_words(z, 1 if lossless else 0)
+    if n == 0:
+        raise OptorchError(E_INVALID, "images per group must be 1..%d, got %d" % (32 if lossless else 16, z))
+    return n
+
+
+def _batch_shape(x):
+    batch = x.shape[0]
+    n_pos = 1
+    for d in x.shape[1:]:
+        n_pos *= d
+    return batch, n_pos
+
+
+def encode(x, z: int, out=None):
+    """Algorithm "Encode": x cuda uint8 [batch, ...] -> cuda int64 [ceil(batch / z), n_pos, words]."""
+    import torch
+    assert x.is_cuda and x.dtype == torch.uint8 and x.is_contiguous()
+    batch, n_pos = _batch_shape(x)
+    words = encoded_words(z)
+    if out is None:
+        out = torch.empty((-(-batch // z), n_pos, words), dtype=torch.int64, device=x.device)
+    assert out.is_cuda and out.dtype == torch.int64 and out.is_contiguous() and out.numel() == -(-batch // z) * n_pos * words
+    _df_check(load_library().optorch_encode(x.data_ptr(), batch, n_pos, z, out.data_ptr(), _stream(torch)))
+    return out
+
+
+def decode(a, batch: int, n_pos: int, z: int, out=None):
+    """Algorithm "Decode": the inverse of `encode`; returns cuda uint8 [batch, n_pos]."""
+    import torch
+    words = encoded_words(z)
+    assert a.is_cuda and a.dtype == torch.int64 and a.is_contiguous() and a.numel() == -(-batch // z) * n_pos * words
+    if out is None:
+        out = torch.empty((batch, n_pos), dtype=torch.uint8, device=a.device)
+    assert out.is_cuda and out.dtype == torch.uint8 and out.is_contiguous() and out.numel() == batch * n_pos
+    _df_check(load_library().optorch_decode(a.data_ptr(), batch, n_pos, z, out.data_ptr(), _stream(torch)))
+    return out
+
+
+def decode_normalized(a, batch: int, n_pos: int, z: int, channels: int, scale, shift, precision: int, out=None):
+    """Decode fused with pixel * scale[c] + shift[c] and the cast: cuda [batch, n_pos] in fp32 / bf16 / fp16."""
+    import torch
+    words = encoded_words(z)
+    assert a.is_cuda and a.dtype == torch.int64 and a.is_contiguous() and a.numel() == -(-batch // z) * n_pos * words
+    dtype = {0: torch.float32, 1: torch.bfloat16, 2: torch.float16}[precision]
+    if out is None:
+        out = torch.empty((batch, n_pos), dtype=dtype, device=a.device)
+    assert out.is_cuda and out.dtype == dtype and out.is_contiguous() and out.numel() == batch * n_pos
+    _df_check(load_library().optorch_decode_normalized(a.data_ptr(), batch, n_pos, z, channels, _float_array(scale, channels),
+                                                       _float_array(shift, channels), precision, out.data_ptr(),
+                                                       _stream(torch)))
+    return out
+
+
+def encode_lossless(x, z: int):
+    """Algorithm "Loss-less Forced Encoding": x cuda uint8 [batch, ...] -> (cuda int64 [G, n_pos, words], cuda int32 [G, n_pos])."""
+    import torch
+    assert x.is_cuda and x.dtype == torch.uint8 and x.is_contiguous()
+    batch, n_pos = _batch_shape(x)
+    words = encoded_words(z, True)
+    groups = -(-batch // z)
+    a = torch.empty((groups, n_pos, words), dtype=torch.int64, device=x.device)
+    o = torch.empty((groups, n_pos), dtype=torch.int32, device=x.device)
+    _df_check(load_library().optorch_encode_lossless(x.data_ptr(), batch, n_pos, z, a.data_ptr(), o.data_ptr(), _stream(torch)))
+    return a, o
+
+
+def decode_lossless(a, o, batch: int, n_pos: int, z: int):
+    """The inverse of `encode_lossless`; returns cuda uint8 [batch, n_pos]."""
+    import torch
+    words = encoded_words(z, True)
+    groups = -(-batch // z)
+    assert a.is_cuda and a.dtype == torch.int64 and a.is_contiguous() and a.numel() == groups * n_pos * words
+    assert o.is_cuda and o.dtype == torch.int32 and o.is_contiguous() and o.numel() == groups * n_pos
+    out = torch.empty((batch, n_pos), dtype=torch.uint8, device=a.device)
+    _df_check(load_library().optorch_decode_lossless(a.data_ptr(), o.data_ptr(), batch, n_pos, z, out.data_ptr(), _stream(torch)))
+    return out

@@ -26,7 +26,8 @@ struct optorch_seq {
   hipStream_t stream = nullptr;
   uint64_t off_w = 0, off_v = 0, off_g = 0, off_h = 0, off_wt = 0, off_run = 0, off_scal = 0, param_arena_bytes = 0;
   bool bound = false, params_set = false;
-  int dt = 0;
+  bool x_encoded = false;  // the current step's batch came in encoded form
+  int dt = 0, in_channels = 0;
   float scale = 1.f, scale_init = 1.f, growth = 2.f, backoff = 0.5f, eps = 1e-5f, bn_mom = 0.1f, momentum = 0.f;
   int growth_interval = 0, clean = 0;
   bool dynamic_scale = false;
@@ -114,6 +115,7 @@ extern "C" int optorch_seq_create(const optorch_unit_t* units, int32_t n_units, 
     return OPTORCH_E_BUDGET;
   }
   h->dt = cfg->precision;
+  h->in_channels = cfg->channels;
   h->eps = cfg->bn_eps > 0 ? cfg->bn_eps : 1e-5f;
   h->bn_mom = cfg->bn_momentum > 0 ? cfg->bn_momentum : 0.1f;
   h->momentum = cfg->momentum;
@@ -220,6 +222,8 @@ namespace {
 struct Ctx {
   optorch_seq_t* h;
   const float* x; const int32_t* y;
+  // the batch in encoded form instead of x (groups of xz images, Algorithm "Encode"), with the input normalisation
+  const uint64_t* xa = nullptr; int xz = 0; const float* xscale = nullptr; const float* xshift = nullptr;
   void* at(int inst) const { return inst < 0 ? nullptr : (void*)(h->abase + h->plan.insts[inst].offset); }
   float* w32(int64_t off) const { return (float*)(h->pbase + h->off_w) + off; }
   float* g32(int64_t off) const { return (float*)(h->pbase + h->off_g) + off; }
@@ -239,7 +243,10 @@ void run_op(const Ctx& c, const SOp& s) {
   const int dt = h->dt;
   switch (s.kind) {
     case S_CAST_IN:
-      launch_cast_in(st, dt, c.x, c.at(s.out[0]), (int64_t)f.N * f.H * f.W * f.C);
+      if (c.xa)  // the decode layer as the first kernel of the step
+        launch_decode_cast(st, dt, c.xa, f.N, (int64_t)f.H * f.W * f.C, c.xz, f.C, c.xscale, c.xshift, c.at(s.out[0]));
+      else
+        launch_cast_in(st, dt, c.x, c.at(s.out[0]), (int64_t)f.N * f.H * f.W * f.C);
       break;
     case S_CONV_FWD:
       if (f.fwd_algo == ALGO_MFMA)
@@ -337,7 +344,7 @@ void work_of(const optorch_seq_t* h, const SOp& s, double* flops, double* bytes)
   const double wts = (double)f.K * f.R * f.S * f.C;
   *flops = 0; *bytes = 0;
   switch (s.kind) {
-    case S_CAST_IN: *bytes = in_px * f.C * (4 + e); break;
+    case S_CAST_IN: *bytes = in_px * f.C * ((h->x_encoded ? 1 : 4) + e); break;  // an encoded batch: one byte per pixel
     case S_CONV_FWD: *flops = 2 * out_px * wts; *bytes = e * (in_px * f.C + out_px * f.K + wts); break;
     case S_DGRAD: *flops = 2 * out_px * wts; *bytes = e * (in_px * f.C * (s.in[1] >= 0 ? 2 : 1) + out_px * f.K + wts); break;
     case S_WGRAD: *flops = 2 * out_px * wts; *bytes = e * (in_px * f.C + out_px * f.K) + 4 * wts; break;
@@ -503,14 +510,9 @@ extern "C" int optorch_seq_running_stats(const optorch_seq_t* h, float* dst, uin
   return OPTORCH_OK;
 }
 
-extern "C" int optorch_seq_step(optorch_seq_t* h, const float* x_dev, const int32_t* y_dev, float lr, float* loss_out,
-                                float* grads_dev, uint64_t* peak_saved_bytes, uint64_t* peak_arena_bytes,
-                                float* loss_scale_out, int32_t* step_skipped) {
-  if (!h) return OPTORCH_E_INVALID;
-  if (!h->bound || !h->params_set) return set_err(h, OPTORCH_E_ORDER, "step before bind/set_params");
-  if (!x_dev || !y_dev) return set_err(h, OPTORCH_E_INVALID, "null input pointer");
-  if (!std::isfinite(lr)) return set_err(h, OPTORCH_E_INVALID, "learning rate is not finite");
-  Ctx c{h, x_dev, y_dev};
+// one training step on the batch that c describes
+static int step_run(optorch_seq_t* h, const Ctx& c, float lr, float* loss_out, float* grads_dev, uint64_t* peak_saved_bytes,
+                    uint64_t* peak_arena_bytes, float* loss_scale_out, int32_t* step_skipped) {
   hipStream_t st = h->stream;
   launch_step_init(st, c.flags());
   const bool prof = h->profiling;
@@ -574,6 +576,35 @@ extern "C" int optorch_seq_step(optorch_seq_t* h, const float* x_dev, const int3
   if (loss_scale_out) *loss_scale_out = h->scale;
   if (step_skipped) *step_skipped = skipped ? 1 : 0;
   return OPTORCH_OK;
+}
+
+extern "C" int optorch_seq_step(optorch_seq_t* h, const float* x_dev, const int32_t* y_dev, float lr, float* loss_out,
+                                float* grads_dev, uint64_t* peak_saved_bytes, uint64_t* peak_arena_bytes,
+                                float* loss_scale_out, int32_t* step_skipped) {
+  if (!h) return OPTORCH_E_INVALID;
+  if (!h->bound || !h->params_set) return set_err(h, OPTORCH_E_ORDER, "step before bind/set_params");
+  if (!x_dev || !y_dev) return set_err(h, OPTORCH_E_INVALID, "null input pointer");
+  if (!std::isfinite(lr)) return set_err(h, OPTORCH_E_INVALID, "learning rate is not finite");
+  Ctx c{h, x_dev, y_dev};
+  h->x_encoded = false;
+  return step_run(h, c, lr, loss_out, grads_dev, peak_saved_bytes, peak_arena_bytes, loss_scale_out, step_skipped);
+}
+
+extern "C" int optorch_seq_step_encoded(optorch_seq_t* h, const uint64_t* a_dev, int32_t z, const float* scale_host,
+                                        const float* shift_host, const int32_t* y_dev, float lr, float* loss_out,
+                                        float* grads_dev, uint64_t* peak_saved_bytes, uint64_t* peak_arena_bytes,
+                                        float* loss_scale_out, int32_t* step_skipped) {
+  if (!h) return OPTORCH_E_INVALID;
+  if (!h->bound || !h->params_set) return set_err(h, OPTORCH_E_ORDER, "step before bind/set_params");
+  if (!a_dev || !y_dev || !scale_host || !shift_host) return set_err(h, OPTORCH_E_INVALID, "null input pointer");
+  if (z < 1 || z > 16) return set_err(h, OPTORCH_E_INVALID, "images per group must be 1..16");
+  if (h->in_channels < 1 || h->in_channels > 16)
+    return set_err(h, OPTORCH_E_INVALID, "an encoded batch needs a network input of 1..16 channels");
+  if (!std::isfinite(lr)) return set_err(h, OPTORCH_E_INVALID, "learning rate is not finite");
+  Ctx c{h, nullptr, y_dev};
+  c.xa = a_dev; c.xz = z; c.xscale = scale_host; c.xshift = shift_host;
+  h->x_encoded = true;
+  return step_run(h, c, lr, loss_out, grads_dev, peak_saved_bytes, peak_arena_bytes, loss_scale_out, step_skipped);
 }
 
 extern "C" const char* optorch_seq_last_error(const optorch_seq_t* h) { return h ? h->err.c_str() : g_create_error.c_str(); }

@@ -95,4 +95,13 @@ void launch_optim(hipStream_t st, int dt, float* w, float* v, const float* g, vo
 void launch_cast_params(hipStream_t st, int dt, const float* w, void* w16, int64_t n);
 void launch_fill(hipStream_t st, float* p, int64_t n, float v);
 
+// Image data-flow (x uint8 [B][P]; a uint64 [ceil(B / z)][P][words]; o uint32 [ceil(B / z)][P]); z and the pointers
+// are validated by the callers.  scale / shift: host arrays of `channels` (<= 16) floats.
+void launch_encode(hipStream_t st, const uint8_t* x, int64_t B, int64_t P, int z, uint64_t* a);
+void launch_decode(hipStream_t st, const uint64_t* a, int64_t B, int64_t P, int z, uint8_t* x);
+void launch_decode_cast(hipStream_t st, int dt, const uint64_t* a, int64_t B, int64_t P, int z, int channels,
+                        const float* scale, const float* shift, void* out);
+void launch_encode_lossless(hipStream_t st, const uint8_t* x, int64_t B, int64_t P, int z, uint64_t* a, uint32_t* o);
+void launch_decode_lossless(hipStream_t st, const uint64_t* a, const uint32_t* o, int64_t B, int64_t P, int z, uint8_t* x);
+
 }  // namespace oseq

@@ -21,9 +21,13 @@ def _built():
 
 
 def test_library_exports_every_declared_symbol():
-    header = open(os.path.join(ROOT, "include", "optorch_seq.h")).read()
-    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
-    declared = set(re.findall(r"\b(optorch_seq_\w+)\s*\(", header))
+    declared = set()
+    for name in sorted(os.listdir(os.path.join(ROOT, "include"))):
+        if not name.endswith(".h"):
+            continue
+        header = open(os.path.join(ROOT, "include", name)).read()
+        header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+        declared |= set(re.findall(r"\b(optorch_\w+)\s*\(", header))
     assert declared and declared == set(binding.SYMBOLS)
     lib = ctypes.CDLL(binding.LIB_PATH)
     for name in declared:
@@ -131,3 +135,20 @@ def test_invalid_arguments_are_rejected(units, kw):
     with pytest.raises(OptorchError) as e:
         SeqPlan(units, **args)
     assert e.value.code == binding.E_INVALID and str(e.value)
+
+
+def test_dataflow_argument_checks_need_no_gpu():
+    lib = binding.load_library()
+    assert [lib.optorch_encoded_words(z, 0) for z in (0, 1, 8, 9, 16, 17)] == [0, 1, 1, 2, 2, 0]
+    assert [lib.optorch_encoded_words(z, 1) for z in (0, 1, 9, 10, 18, 19, 27, 28, 32, 33)] == [0, 1, 1, 2, 2, 3, 3, 4, 4, 0]
+    buf = ctypes.create_string_buffer(64)
+    addr = ctypes.addressof(buf)
+    assert lib.optorch_encode(addr, 4, 8, 0, addr, None) == binding.E_INVALID
+    assert b"1..16" in lib.optorch_dataflow_last_error()
+    assert lib.optorch_encode(addr, -1, 8, 4, addr, None) == binding.E_INVALID
+    assert lib.optorch_encode(None, 4, 8, 4, addr, None) == binding.E_INVALID
+    assert lib.optorch_encode_lossless(addr, 4, 8, 33, addr, addr, None) == binding.E_INVALID
+    assert lib.optorch_decode_normalized(addr, 4, 8, 4, 17, None, None, 0, addr, None) == binding.E_INVALID
+    # an empty batch is a success that launches nothing
+    assert lib.optorch_encode(None, 0, 8, 4, None, None) == binding.OK
+    assert lib.optorch_decode_lossless(None, None, 4, 0, 4, None, None) == binding.OK
