@@ -352,7 +352,8 @@ __global__ void __launch_bounds__(256) conv_igemm_kernel(const T* __restrict__ s
 //   block = 256 threads = 4 wavefronts (2 x 2); block tile = 64*MI pixel rows x BN channels; a wavefront owns 32*MI
 //   rows and BN/2 channels: MI x (BN/64) MFMA 32x32 tiles.  The rows are SUBT pixel sub-tiles of 64*MI/SUBT pixels
 //   (TI images x TR rows x TC columns each, with their own halo).  Instantiated: (MI 2, SUBT 1) with 128 or 64
-//   channels and (1, 1) with 64, all small enough in LDS for two blocks per CU.
+//   channels and (1, 1) with 64; two blocks share a CU, three with 64 channels (registers capped, patch
+//   buffers sized for the layer's tile).
 //   LDS: 2 patch buffers [SUBT*256 positions][80 B], 3 weight stages [BN][80 B], address tables.
 //   Pipeline (one barrier per tap): the weight tile of (chunk c+1, tap t) is requested before the MFMAs of (c, t)
 //   and parked in registers until the end of step (c+1, t-1); the next chunk's patch is requested during taps 0-3

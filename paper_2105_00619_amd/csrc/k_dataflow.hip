@@ -3,8 +3,8 @@
 //
 // With base 256 the number of a position is, in memory, the bytes of its images side by side: image i of a group is
 // byte i of the position's little-endian words.  Encode and Decode are therefore byte transposes between
-// [image][position] and [position][image], bound by HBM traffic.  One block handles 2048 positions of one group: a
-// thread reads 8 consecutive positions of every image with one 8-byte load (a wavefront reads 512 contiguous bytes
+// [image][position] and [position][image], bound by HBM traffic.  One block handles 2048 positions of one group (1024
+// where that fills an image's last block better): a thread reads 8 consecutive positions of every image with one 8-byte load (a wavefront reads 512 contiguous bytes
 // per image), transposes 8 x 8 bytes with byte permutes, and the words travel through LDS so that the other side is
 // accessed as 16 contiguous bytes per lane as well.  Decode can apply pixel * scale[c] + shift[c] and the cast to the
 // network's storage type on the way out, which makes it the first layer of a network.
@@ -17,9 +17,11 @@
 
 namespace oseq {
 
+int g_df_threads = 0;  // tuning constant (not part of the C ABI): 0 = chosen from the image size
+
 namespace {
 
-constexpr int DF_TILE = 2048;  // positions per block: 256 threads x 8
+constexpr int DF_POS = 8;  // positions per thread; a block of n threads (256, or 128 for short images) handles 8 n positions
 
 struct DfNorm { float scale[16]; float shift[16]; int channels; };
 
@@ -59,10 +61,11 @@ template <int W>
 __global__ __launch_bounds__(256) void encode_kernel(const uint8_t* __restrict__ x, uint4* __restrict__ a4, int z, int64_t P,
                                                      int64_t B, int tiles) {
   __shared__ uint4 buf[df_lds_chunks<W>()];
-  const int tid = threadIdx.x;
+  const int tid = threadIdx.x, nthr = blockDim.x;
+  const int tile_pos = nthr * DF_POS;
   const int64_t g = blockIdx.x / tiles;
   const int tile = blockIdx.x % tiles;
-  const int64_t p0 = (int64_t)tile * DF_TILE + tid * 8;
+  const int64_t p0 = (int64_t)tile * tile_pos + tid * 8;
   const int64_t n0 = g * z;
   const int zg = (int)((B - n0) < (int64_t)z ? (B - n0) : (int64_t)z);
   uint32_t lo[8 * W], hi[8 * W];
@@ -83,11 +86,11 @@ __global__ __launch_bounds__(256) void encode_kernel(const uint8_t* __restrict__
     for (int c = 0; c < 8; ++c) buf[df_slot(tid * 8 + c)] = make_uint4(wlo[0][c], whi[0][c], wlo[W - 1][c], whi[W - 1][c]);
   }
   __syncthreads();
-  uint4* dst = a4 + (g * P * W) / 2 + (int64_t)tile * (1024 * W);
+  uint4* dst = a4 + (g * P * W) / 2 + (int64_t)tile * (tile_pos / 2 * W);
 #pragma unroll
   for (int m = 0; m < 4 * W; ++m) {
-    const int q = tid + 256 * m;
-    const int64_t pos = (int64_t)tile * DF_TILE + (W == 1 ? 2 * q : q);
+    const int q = tid + nthr * m;
+    const int64_t pos = (int64_t)tile * tile_pos + (W == 1 ? 2 * q : q);
     if (pos < P) dst[q] = buf[df_slot(q)];
   }
 }
@@ -115,23 +118,24 @@ __global__ __launch_bounds__(256) void decode_kernel(const uint4* __restrict__ a
   constexpr bool RAW = sizeof(T) == 1;
   __shared__ uint4 buf[df_lds_chunks<W>()];
   __shared__ float s_scale[16], s_shift[16];
-  const int tid = threadIdx.x;
+  const int tid = threadIdx.x, nthr = blockDim.x;
+  const int tile_pos = nthr * DF_POS;
   const int64_t g = blockIdx.x / tiles;
   const int tile = blockIdx.x % tiles;
-  const int64_t p0 = (int64_t)tile * DF_TILE + tid * 8;
+  const int64_t p0 = (int64_t)tile * tile_pos + tid * 8;
   const int64_t n0 = g * z;
   const int zg = (int)((B - n0) < (int64_t)z ? (B - n0) : (int64_t)z);
-  const uint4* src = a4 + (g * P * W) / 2 + (int64_t)tile * (1024 * W);
+  const uint4* src = a4 + (g * P * W) / 2 + (int64_t)tile * (tile_pos / 2 * W);
   uint4 ch[4 * W];
 #pragma unroll
   for (int m = 0; m < 4 * W; ++m) {
-    const int q = tid + 256 * m;
-    const int64_t pos = (int64_t)tile * DF_TILE + (W == 1 ? 2 * q : q);
+    const int q = tid + nthr * m;
+    const int64_t pos = (int64_t)tile * tile_pos + (W == 1 ? 2 * q : q);
     ch[m] = make_uint4(0u, 0u, 0u, 0u);
     if (pos < P) ch[m] = src[q];
   }
 #pragma unroll
-  for (int m = 0; m < 4 * W; ++m) buf[df_slot(tid + 256 * m)] = ch[m];
+  for (int m = 0; m < 4 * W; ++m) buf[df_slot(tid + nthr * m)] = ch[m];
   if (!RAW && tid < 16) { s_scale[tid] = nm.scale[tid]; s_shift[tid] = nm.shift[tid]; }
   __syncthreads();
   if (p0 >= P) return;
@@ -321,6 +325,14 @@ __global__ __launch_bounds__(256) void decode_lossless_kernel(const uint64_t* __
   }
 }
 
+// 256 threads per block, or 128 where that leaves fewer idle threads in an image's last block (a 32 x 32 x 3 image is
+// one and a half blocks of 256 threads, and three full ones of 128)
+int df_threads(int64_t P) {
+  if (g_df_threads == 128 || g_df_threads == 256) return g_df_threads;
+  const int64_t idle256 = (P + 2047) / 2048 * 2048 - P, idle128 = (P + 1023) / 1024 * 1024 - P;
+  return idle128 < idle256 ? 128 : 256;
+}
+
 bool aligned(const void* p, size_t n) { return (reinterpret_cast<uintptr_t>(p) & (n - 1)) == 0; }
 
 DfNorm make_norm(int channels, const float* scale, const float* shift) {
@@ -335,8 +347,9 @@ void launch_decode_t(hipStream_t st, const uint64_t* a, int64_t B, int64_t P, in
   const int64_t G = (B + z - 1) / z;
   const int W = (z + 7) / 8;
   if (P % 8 == 0 && aligned(a, 16) && aligned(out, sizeof(T) == 1 ? 8 : 16)) {
-    const int tiles = (int)((P + DF_TILE - 1) / DF_TILE);
-    const dim3 grid((unsigned)(G * tiles)), block(256);
+    const int nthr = df_threads(P);
+    const int tiles = (int)((P + nthr * DF_POS - 1) / (nthr * DF_POS));
+    const dim3 grid((unsigned)(G * tiles)), block(nthr);
     if (W == 1) OSEQ_LAUNCH((decode_kernel<1, T>), grid, block, 0, st, (const uint4*)a, out, z, P, B, tiles, nm);
     else OSEQ_LAUNCH((decode_kernel<2, T>), grid, block, 0, st, (const uint4*)a, out, z, P, B, tiles, nm);
   } else {
@@ -354,8 +367,9 @@ void launch_encode(hipStream_t st, const uint8_t* x, int64_t B, int64_t P, int z
   const int64_t G = (B + z - 1) / z;
   const int W = (z + 7) / 8;
   if (P % 8 == 0 && aligned(x, 8) && aligned(a, 16)) {
-    const int tiles = (int)((P + DF_TILE - 1) / DF_TILE);
-    const dim3 grid((unsigned)(G * tiles)), block(256);
+    const int nthr = df_threads(P);
+    const int tiles = (int)((P + nthr * DF_POS - 1) / (nthr * DF_POS));
+    const dim3 grid((unsigned)(G * tiles)), block(nthr);
     if (W == 1) OSEQ_LAUNCH(encode_kernel<1>, grid, block, 0, st, x, (uint4*)a, z, P, B, tiles);
     else OSEQ_LAUNCH(encode_kernel<2>, grid, block, 0, st, x, (uint4*)a, z, P, B, tiles);
   } else {

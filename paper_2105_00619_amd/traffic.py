@@ -11,6 +11,10 @@ the same two runs of `copy` below, a plain device copy of known size, whose read
         --fetch out/f/*counter_collection.csv --write out/w/*counter_collection.csv \
         --cal-fetch out/cf/*counter_collection.csv --cal-write out/cw/*counter_collection.csv
 
+The data-flow benchmark (`bench.py --path dataflow`) is counted the same way, with `--path dataflow` added to the two
+bench.py commands and `ingest --workload dataflow_encode_decode_50000x32x32x3_z16 --per-launch ...`: its figures are
+bytes per kernel launch.
+
 `ingest` writes traffic.json next to this file together with a hash of the kernel sources; `lookup` (used by
 bench.py) returns the figure only while that hash still matches, i.e. while the kernels are the ones measured.
 (--steps is the number of training steps the benchmark run executed: warm-up + survey + timed.)
@@ -37,6 +41,14 @@ GROUP_KERNELS = {
 }
 
 
+# the data-flow benchmark's kernels (the bf16 instantiation appears under its mangled name in the counter files)
+DATAFLOW_KERNELS = {
+    "encode_kernel": ("encode_kernel<",),
+    "decode_kernel<bf16>": ("decode_kernelILi1EDF16b", "decode_kernelILi2EDF16b", "decode_kernel<1, __bf16>", "decode_kernel<2, __bf16>"),
+    "decode_kernel<u8>": ("decode_kernel<1, unsigned char>", "decode_kernel<2, unsigned char>"),
+}
+
+
 def source_hash() -> str:
     h = hashlib.sha1()
     for f in sorted(glob.glob(os.path.join(HERE, "csrc", "*"))):
@@ -57,14 +69,18 @@ def lookup(workload: str, group: str):
     return rec.get("groups", {}).get(group)
 
 
-def _sum_counter(path: str, counter: str, fragments) -> float:
-    """Sum of a counter (KiB) over the dispatches whose kernel name contains one of the fragments."""
-    total = 0.0
+def _sum_counter(path: str, counter: str, fragments, count=None) -> float:
+    """Sum of a counter (KiB) over the dispatches whose kernel name contains one of the fragments (count: a list that
+    receives the number of such dispatches)."""
+    total, n = 0.0, 0
     for r in csv.DictReader(open(path)):
         if r["Counter_Name"] != counter:
             continue
         if any(f in r["Kernel_Name"] for f in fragments):
             total += float(r["Counter_Value"])
+            n += 1
+    if count is not None:
+        count.append(n)
     return total
 
 
@@ -90,10 +106,20 @@ def ingest(args) -> None:
         sys.exit("no copy kernel found in the calibration runs")
     ff, fw = want_kib / cal_f, want_kib / cal_w  # true KiB per counted KiB
     groups = {}
-    for g, frags in GROUP_KERNELS.items():
-        fetch = _sum_counter(args.fetch, "FETCH_SIZE", frags) * ff * 1024.0 / args.steps
-        write = _sum_counter(args.write, "WRITE_SIZE", frags) * fw * 1024.0 / args.steps
-        groups[g] = {"fetch_bytes_per_step": fetch, "write_bytes_per_step": write, "bytes_per_step": fetch + write}
+    if args.per_launch:
+        for g, frags in DATAFLOW_KERNELS.items():
+            nf, nw = [], []
+            fetch = _sum_counter(args.fetch, "FETCH_SIZE", frags, nf) * ff * 1024.0
+            write = _sum_counter(args.write, "WRITE_SIZE", frags, nw) * fw * 1024.0
+            if not nf[0] or not nw[0]:
+                sys.exit("no dispatch of %s in the counter files" % g)
+            groups[g] = {"fetch_bytes_per_launch": fetch / nf[0], "write_bytes_per_launch": write / nw[0],
+                         "bytes_per_launch": fetch / nf[0] + write / nw[0]}
+    else:
+        for g, frags in GROUP_KERNELS.items():
+            fetch = _sum_counter(args.fetch, "FETCH_SIZE", frags) * ff * 1024.0 / args.steps
+            write = _sum_counter(args.write, "WRITE_SIZE", frags) * fw * 1024.0 / args.steps
+            groups[g] = {"fetch_bytes_per_step": fetch, "write_bytes_per_step": write, "bytes_per_step": fetch + write}
     d = json.load(open(STORE)) if os.path.exists(STORE) else {}
     d[args.workload] = {"source_hash": source_hash(), "steps_counted": args.steps,
                         "calibration": {"fetch_factor": ff, "write_factor": fw, "copy_mib": COPY_MIB, "reps": COPY_REPS},
@@ -109,7 +135,8 @@ def main() -> None:
     ing = sub.add_parser("ingest")
     for a in ("--fetch", "--write", "--cal-fetch", "--cal-write", "--workload"):
         ing.add_argument(a, required=True)
-    ing.add_argument("--steps", type=int, required=True)
+    ing.add_argument("--steps", type=int, default=1)
+    ing.add_argument("--per-launch", action="store_true", help="the data-flow kernels: bytes per kernel launch")
     args = ap.parse_args()
     if args.cmd == "copy":
         copy()
