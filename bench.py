@@ -167,6 +167,8 @@ def main():
     ap.add_argument("--survey-steps", type=int, default=5, help="untimed steps with every kernel class event-timed")
     ap.add_argument("--timed-every", type=int, default=4,
                     help="steps of the timed region whose dominant-class launches carry events: every n-th")
+    ap.add_argument("--storage-mode", type=int, default=0,
+                    help="0: keep Z and A of every conv-BN-ReLU (default); 1: keep Z only, rebuild A in backward")
     ap.add_argument("--path", choices=("train", "dataflow"), default="train",
                     help="train: the checkpointed training step (default); dataflow: image Encode + decode layer")
     args = ap.parse_args()
@@ -189,7 +191,7 @@ def main():
 
     wl = W.config(args.config, batch=args.batch)
     k = args.k if args.k is not None else wl.k_segments
-    tr = SeqTrainer.from_workload(wl, k_segments=k)
+    tr = SeqTrainer.from_workload(wl, k_segments=k, storage_mode=args.storage_mode)
     p, x, y = W.make_batch(wl)
     tr.set_params(p)
     xd, yd = torch.from_numpy(x).cuda(), torch.from_numpy(y).cuda()
@@ -282,7 +284,7 @@ def main():
         "value": wl.batch / (ms * 1e-3), "unit": "images/sec", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": DTYPE_NAME[wl.precision], "data": "synthetic",
-        "config": {"workload": wl.name, "batch": wl.batch, "k_segments": k, "image": "%dx%dx%d NHWC" % (wl.height, wl.width, wl.channels),
+        "config": {"workload": wl.name, "batch": wl.batch, "k_segments": k, "storage_mode": args.storage_mode, "image": "%dx%dx%d NHWC" % (wl.height, wl.width, wl.channels),
                    "boundaries": tr.boundaries, "plan_mode": wl.plan_mode, "momentum": wl.momentum},
         "loss": r["loss"], "peak_saved_bytes": r["peak_saved_bytes"], "peak_arena_bytes": r["peak_arena_bytes"],
         "activation_budget_bytes": wl.budget_bytes, "launches_per_step": tr.n_launches,

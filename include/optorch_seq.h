@@ -83,6 +83,12 @@ typedef struct {
   float scale_growth;              /* <= 0 selects 2                                              */
   float scale_backoff;             /* <= 0 selects 0.5                                            */
   int32_t growth_interval;         /* <= 0 selects 2000 (fp16) or "never" (fp32, bf16)            */
+  int32_t storage_mode;            /* what a conv-BatchNorm-ReLU keeps for backward: 0 = its pre-
+                                      normalisation output Z and its activation A; 1 = Z only where
+                                      A = ReLU(BN(Z)) has no skip connection added: backward rebuilds
+                                      such an A with one elementwise pass right before its first use
+                                      (fewer saved bytes, one more pass over Z per layer; gradients
+                                      bit-identical to mode 0)                                     */
 } optorch_seq_config_t;
 
 /* Plans the step on the host: expands units into kernels, chooses segment boundaries,

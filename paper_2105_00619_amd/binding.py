@@ -42,7 +42,7 @@ class optorch_seq_config_t(C.Structure):
         ("channels", C.c_int32), ("num_classes", C.c_int32), ("activation_budget_bytes", C.c_uint64),
         ("momentum", C.c_float), ("bn_eps", C.c_float), ("bn_momentum", C.c_float),
         ("loss_scale_init", C.c_float), ("scale_growth", C.c_float), ("scale_backoff", C.c_float),
-        ("growth_interval", C.c_int32),
+        ("growth_interval", C.c_int32), ("storage_mode", C.c_int32),
     ]
 
 
@@ -131,7 +131,7 @@ class SeqPlan:
                  channels: int, num_classes: int, boundaries: Optional[Sequence[int]] = None, plan_mode: int = 0,
                  activation_budget_bytes: int = 0, momentum: float = 0.0, bn_eps: float = 0.0, bn_momentum: float = 0.0,
                  loss_scale_init: float = 0.0, scale_growth: float = 0.0, scale_backoff: float = 0.0,
-                 growth_interval: int = 0):
+                 growth_interval: int = 0, storage_mode: int = 0):
         self.lib = load_library()
         self.handle = C.c_void_p()
         arr = (optorch_unit_t * len(units))()
@@ -149,6 +149,7 @@ class SeqPlan:
         cfg.momentum, cfg.bn_eps, cfg.bn_momentum = momentum, bn_eps, bn_momentum
         cfg.loss_scale_init, cfg.scale_growth, cfg.scale_backoff = loss_scale_init, scale_growth, scale_backoff
         cfg.growth_interval = growth_interval
+        cfg.storage_mode = storage_mode
         rc = self.lib.optorch_seq_create(arr, len(units), C.byref(cfg), C.byref(self.handle))
         if rc != OK:
             msg = self.lib.optorch_seq_last_error(None).decode()

@@ -231,8 +231,14 @@ struct Scheduler {
   Plan& p;
   std::vector<int> cur, grad;  // [LTensor] -> Inst id
   std::vector<int> stat_ws;    // [LTensor of a conv output] -> Inst id of the channel sums its forward kernel wrote
+  std::vector<int> bn_apply_of;  // [LTensor] -> the F_BN_APPLY operation that produces it, or -1
+  std::vector<char> rebuilt;     // [LTensor] backward has already rebuilt it (storage mode 1)
   explicit Scheduler(Plan& pl)
-      : p(pl), cur(pl.tensors.size(), -1), grad(pl.tensors.size(), -1), stat_ws(pl.tensors.size(), -1) {}
+      : p(pl), cur(pl.tensors.size(), -1), grad(pl.tensors.size(), -1), stat_ws(pl.tensors.size(), -1),
+        bn_apply_of(pl.tensors.size(), -1), rebuilt(pl.tensors.size(), 0) {
+    for (size_t fi = 0; fi < pl.fops.size(); ++fi)
+      if (pl.fops[fi].kind == F_BN_APPLY) bn_apply_of[pl.fops[fi].out] = (int)fi;
+  }
 
   int new_inst(int logical, uint64_t bytes, bool fwd_value) {
     Inst i; i.logical = logical; i.bytes = bytes; i.fwd_value = fwd_value;
@@ -287,6 +293,22 @@ struct Scheduler {
     }
   }
 
+  // The instance of forward tensor t that a backward operation of segment `seg` reads.  Storage mode 1: an
+  // activation A = ReLU(BN(Z)) without a skip connection, produced inside this segment, is not kept from the forward
+  // pass; the first backward operation that needs it has it rebuilt from Z and the kept statistics by the same
+  // elementwise kernel (hence the same bits), as a transient of the backward pass.
+  int backward_input(int t, int seg) {
+    const int fa = bn_apply_of[t];
+    if (p.cfg.storage_mode != 1 || fa < 0 || rebuilt[t]) return cur[t];
+    const FOp& f = p.fops[fa];
+    if (f.skip >= 0 || f.unit < p.seg_begin[seg] || f.unit >= p.seg_begin[seg + 1]) return cur[t];
+    SOp& s = push(S_BN_APPLY, fa, PH_BWD, seg);
+    s.in[0] = cur[f.x]; s.in[1] = cur[f.stats];
+    s.out[0] = cur[t] = new_inst(t, p.tensors[t].bytes, false);
+    rebuilt[t] = 1;
+    return cur[t];
+  }
+
   bool emit_fop_backward(int fi, int seg) {
     const FOp& f = p.fops[fi];
     switch (f.kind) {
@@ -326,8 +348,9 @@ struct Scheduler {
           s.out[0] = new_inst(-1, (uint64_t)f.red_blocks * 2 * f.K * 4, false);
         }
         {
+          const int xin = backward_input(f.x, seg);
           SOp& s = push(S_WGRAD, fi, PH_BWD, seg);
-          s.in[0] = cur[f.x]; s.in[1] = g;
+          s.in[0] = xin; s.in[1] = g;
           if (f.wgrad_splits > 1)
             s.out[0] = new_inst(-1, (uint64_t)f.wgrad_splits * f.K * f.R * f.S * f.C * 4, false);
         }
@@ -343,8 +366,9 @@ struct Scheduler {
         if (grad[f.out] < 0) { p.error = "internal: pool output has no gradient"; return false; }
         if (!p.tensors[f.x].needs_grad) return true;
         if (grad[f.x] >= 0) { p.error = "internal: pool input already has a gradient"; return false; }
+        const int xin = backward_input(f.x, seg);
         SOp& s = push(S_POOL_BWD, fi, PH_BWD, seg);
-        s.in[0] = cur[f.x]; s.in[1] = grad[f.out];
+        s.in[0] = xin; s.in[1] = grad[f.out];
         s.out[0] = grad_inst(f.x); grad[f.x] = s.out[0];
         return true;
       }
@@ -396,6 +420,7 @@ bool build_graph(Plan& p) {
     return false;
   }
   if (c.precision < 0 || c.precision > 2) { p.error = "precision must be 0 (fp32), 1 (bf16) or 2 (fp16)"; return false; }
+  if (c.storage_mode < 0 || c.storage_mode > 1) { p.error = "storage_mode must be 0 or 1"; return false; }
   if ((int64_t)c.batch * c.height * c.width * 2048 > (int64_t)1 << 40) { p.error = "batch too large"; return false; }
   Builder b(p);
   return b.run();

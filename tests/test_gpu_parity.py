@@ -260,6 +260,47 @@ def test_k_segments_bit_identical_to_k1(name, precision, ks):
             assert np.array_equal(ref["params"], r["params"])
 
 
+@pytest.mark.parametrize("name,precision,ks", [
+    ("conv_bn_relu", W.FP32, (1, 2)), ("bottleneck", W.FP32, (1, 3)), ("bottleneck", W.BF16, (2,)),
+    ("basic_projection", W.FP16, (1, 4)), ("maxpool_flatten", W.FP32, (1, 3)), ("ragged_channels", W.BF16, (2,)),
+    ("stride2_conv", W.FP32, (1,))])
+def test_storage_mode_1_is_bit_identical_and_keeps_less(name, precision, ks):
+    # activations rebuilt in backward from the kept pre-normalisation outputs: same bits, fewer saved bytes
+    units, classes = NETS[name]
+    b_, h_, w_ = 6, 13, 10  # the shape of test_small_nets_match_oracle
+    p, x, y = _inputs(units, b_, h_, w_, classes)
+    loss, g = oracle_step(units, p, x, y, precision, _scale(precision))
+    for k in ks:
+        a, ia = gpu_step(units, p, x, y, precision=precision, k=k, classes=classes, loss_scale_init=_scale(precision))
+        b, ib = gpu_step(units, p, x, y, precision=precision, k=k, classes=classes, loss_scale_init=_scale(precision),
+                         storage_mode=1)
+        assert np.array_equal(a["grads"], b["grads"]) and a["loss"] == b["loss"]
+        assert np.array_equal(a["params"], b["params"])
+        # (an activation that is a segment's kept input cannot be rebuilt: with every unit its own segment nothing is saved)
+        assert b["peak_saved_bytes"] == ib["planned_peak_saved_bytes"] <= ia["planned_peak_saved_bytes"]
+        if k == 1:
+            assert ib["planned_peak_saved_bytes"] < ia["planned_peak_saved_bytes"]
+        assert b["peak_arena_bytes"] == ib["act_arena_bytes"]
+        assert_parity(units, h_, w_, b["grads"], g, TOL[precision], "%s storage_mode 1 k=%d" % (name, k))
+
+
+def test_storage_mode_1_at_benchmark_size():
+    wl = W.config(2)
+    p, x, y = W.make_batch(wl)
+    a, ia = gpu_step(wl.units, p, x, y, precision=wl.precision, k=wl.k_segments, classes=wl.classes, plan_mode=wl.plan_mode)
+    b, ib = gpu_step(wl.units, p, x, y, precision=wl.precision, k=wl.k_segments, classes=wl.classes, plan_mode=wl.plan_mode,
+                     storage_mode=1)
+    assert np.array_equal(a["grads"], b["grads"]) and a["loss"] == b["loss"]
+    assert b["peak_saved_bytes"] == ib["planned_peak_saved_bytes"] < 0.7 * ia["planned_peak_saved_bytes"]
+    wl = W.config(3)
+    p, x, y = W.make_batch(wl)
+    a, ia = gpu_step(wl.units, p, x, y, precision=wl.precision, k=wl.k_segments, classes=wl.classes, plan_mode=wl.plan_mode)
+    b, ib = gpu_step(wl.units, p, x, y, precision=wl.precision, k=wl.k_segments, classes=wl.classes, plan_mode=wl.plan_mode,
+                     storage_mode=1)
+    assert np.array_equal(a["grads"], b["grads"]) and a["loss"] == b["loss"]
+    assert b["peak_saved_bytes"] == ib["planned_peak_saved_bytes"] < 0.85 * ia["planned_peak_saved_bytes"]
+
+
 def test_run_to_run_determinism_and_peak_shrinks_with_k():
     wl = W.config(3, batch=8)
     p, x, y = W.make_batch(wl)

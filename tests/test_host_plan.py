@@ -79,6 +79,33 @@ def test_config2_all_stored_bytes_match_the_analytic_count():
     assert p.n_replay_launches == 0
 
 
+def test_storage_mode_1_keeps_z_only_analytic_count():
+    # the same network with storage_mode 1: per conv only Z and the BN vectors are kept (A is rebuilt in backward), the
+    # pools' outputs and the input stay
+    b, e = 128, 4
+    h, total, c = 32, b * 32 * 32 * 3 * e, 3
+    widths = [64, "M", 128, "M", 256, 256, "M", 512, 512, "M", 512, 512, "M"]
+    for i, wd in enumerate(widths):
+        if wd == "M":
+            h //= 2
+            if i != len(widths) - 1:
+                total += b * h * h * c * e
+        else:
+            c = wd
+            total += b * h * h * c * e + 4 * c * 4
+    total += b * 512 * 4 + b * 10 * 4
+    p0, p1 = _plan(2, k_segments=1), _plan(2, k_segments=1, storage_mode=1)
+    assert p1.planned_peak_saved_bytes == total < p0.planned_peak_saved_bytes
+    assert p1.n_launches == p0.n_launches + 8  # one rebuilding pass per conv-BN-ReLU
+    # ResNet-152 shape of config 5: the published Z-only figures of the byte model (87.5 GiB all stored)
+    q = _plan(5, k_segments=1, storage_mode=1, activation_budget_bytes=0)
+    assert abs(q.planned_peak_saved_bytes / 2 ** 30 - 87.5) < 0.05
+    for idx in (3, 4, 6):
+        a, bb = _plan(idx, activation_budget_bytes=0), _plan(idx, activation_budget_bytes=0, storage_mode=1)
+        assert bb.planned_peak_saved_bytes < 0.9 * a.planned_peak_saved_bytes
+        assert bb.act_arena_bytes < a.act_arena_bytes
+
+
 def test_peak_shrinks_with_segments_and_plan_is_reproducible():
     p1, p4, p4b = _plan(2, k_segments=1), _plan(2, k_segments=4), _plan(2, k_segments=4)
     assert p4.boundaries == [3, 6, 9] == p4b.boundaries
@@ -128,6 +155,7 @@ def test_config5_budget_needs_the_byte_aware_plan():
     ([W.conv(3, 8), W.gap_linear_ce(8, 10)], {"k_segments": 3}),                     # more segments than units
     ([W.conv(3, 8), W.conv(8, 8), W.gap_linear_ce(8, 10)], {"k_segments": 2, "boundaries": [0]}),  # bad boundary
     ([W.conv(3, 8), W.gap_linear_ce(8, 10)], {"precision": 7}),
+    ([W.conv(3, 8), W.gap_linear_ce(8, 10)], {"storage_mode": 2}),
 ])
 def test_invalid_arguments_are_rejected(units, kw):
     args = dict(k_segments=1, precision=W.FP32, batch=4, height=8, width=8, channels=3, num_classes=10)
