@@ -67,7 +67,9 @@ typedef struct {
 } optorch_unit_t;
 
 typedef struct {
-  int32_t k_segments;              /* >= 1; 1 = every activation stored (no recomputation)       */
+  int32_t k_segments;              /* >= 1; 1 = every activation stored (no recomputation);
+                                      0 = chosen by create: the fewest segments whose planned
+                                      activation arena fits activation_budget_bytes                */
   const int32_t* boundaries;       /* NULL: the planner chooses; else k-1 ascending unit indices,
                                       segment j starts at unit boundaries[j-1]                    */
   int32_t plan_mode;               /* 0 = equal unit count (remainder joins the last segment),
@@ -88,7 +90,9 @@ typedef struct {
                                       A = ReLU(BN(Z)) has no skip connection added: backward rebuilds
                                       such an A with one elementwise pass right before its first use
                                       (fewer saved bytes, one more pass over Z per layer; gradients
-                                      bit-identical to mode 0)                                     */
+                                      bit-identical to mode 0); -1 = chosen by create: 0 if the arena
+                                      then fits activation_budget_bytes, else 1 (tried before a
+                                      further segment, which costs more time)                      */
 } optorch_seq_config_t;
 
 /* Plans the step on the host: expands units into kernels, chooses segment boundaries,
@@ -168,6 +172,10 @@ int optorch_seq_predict(optorch_seq_t* h, const float* x_dev, float* logits_dev)
  *   capacity  floats dst can hold; OPTORCH_E_INVALID if fewer than *count
  *   count     host or NULL: receives the number of floats */
 int optorch_seq_running_stats(const optorch_seq_t* h, float* dst, uint64_t capacity, uint64_t* count, int32_t is_device);
+
+/* The plan create settled on: number of segments and storage mode (the configuration's values unless they asked
+ * for the automatic choice).  optorch_seq_query's boundaries_out then has *k_segments - 1 entries. */
+int optorch_seq_plan_info(const optorch_seq_t* h, int32_t* k_segments, int32_t* storage_mode);
 
 /* Number of kernel launches in one step's static schedule, and how many of them belong to the
  * replay (recomputation) of non-last segments. */

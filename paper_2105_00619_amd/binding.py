@@ -21,7 +21,7 @@ SYMBOLS = (
     "optorch_seq_create", "optorch_seq_query", "optorch_seq_bind", "optorch_seq_set_params",
     "optorch_seq_get_params", "optorch_seq_step", "optorch_seq_schedule_info", "optorch_seq_last_error",
     "optorch_seq_destroy", "optorch_seq_predict", "optorch_seq_running_stats", "optorch_seq_profile_enable", "optorch_seq_profile_select", "optorch_seq_profile_read", "optorch_seq_profile_read_entries",
-    "optorch_seq_step_encoded",
+    "optorch_seq_step_encoded", "optorch_seq_plan_info",
     "optorch_encoded_words", "optorch_encode", "optorch_decode", "optorch_decode_normalized", "optorch_encode_lossless",
     "optorch_decode_lossless", "optorch_dataflow_last_error",
 )
@@ -97,6 +97,8 @@ def load_library() -> C.CDLL:
     lib.optorch_seq_predict.restype = C.c_int
     lib.optorch_seq_running_stats.argtypes = [H, C.c_void_p, C.c_uint64, C.POINTER(C.c_uint64), C.c_int32]
     lib.optorch_seq_running_stats.restype = C.c_int
+    lib.optorch_seq_plan_info.argtypes = [H, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
+    lib.optorch_seq_plan_info.restype = C.c_int
     lib.optorch_seq_schedule_info.argtypes = [H, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
     lib.optorch_seq_schedule_info.restype = C.c_int
     lib.optorch_seq_profile_enable.argtypes = [H, C.c_int32]
@@ -155,7 +157,10 @@ class SeqPlan:
             msg = self.lib.optorch_seq_last_error(None).decode()
             self.handle = C.c_void_p()
             raise OptorchError(rc, msg)
-        self.k_segments = k_segments
+        kk, sm = C.c_int32(), C.c_int32()
+        self._check(self.lib.optorch_seq_plan_info(self.handle, C.byref(kk), C.byref(sm)))
+        k_segments = kk.value  # the plan's choice when 0 was asked for
+        self.k_segments, self.storage_mode = k_segments, sm.value
         self.batch, self.height, self.width, self.channels = batch, height, width, channels
         self.num_classes = num_classes
         pc, pb, ab, ps = C.c_uint64(), C.c_uint64(), C.c_uint64(), C.c_uint64()

@@ -75,6 +75,7 @@ extern "C" int optorch_seq_create(const optorch_unit_t* units, int32_t n_units, 
   Plan& p = h->plan;
   p.units.assign(units, units + n_units);
   p.cfg = *cfg;
+  if (p.cfg.storage_mode == -1) p.cfg.storage_mode = 0;  // chosen below
   std::vector<int32_t> bcopy;
   if (cfg->boundaries && cfg->k_segments > 1) {
     bcopy.assign(cfg->boundaries, cfg->boundaries + (cfg->k_segments - 1));
@@ -104,7 +105,28 @@ extern "C" int optorch_seq_create(const optorch_unit_t* units, int32_t n_units, 
         p.fops[i + 1].stat_blocks = p.fops[i].stat_blocks, p.fops[i].stat_fold = p.fops[i + 1].stat_fold = bn_stats_fold_rows(p.fops[i].stat_blocks);
       else if (p.fops[i].kind == F_CONV)
         p.fops[i].stat_blocks = 0;
-    ok = choose_segments(p) && build_schedule(p);
+    // k_segments 0 and storage_mode -1 leave the choice to the plan: the cheapest candidate in step time whose
+    // arena fits the budget -- fewest segments first (each further segment replays more of the forward pass),
+    // and at equal segments keeping activations before rebuilding them
+    const bool auto_k = cfg->k_segments == 0, auto_mode = cfg->storage_mode == -1;
+    if (auto_k && cfg->boundaries) { p.error = "explicit boundaries need k_segments"; ok = false; }
+    const int k_lo = auto_k ? 1 : cfg->k_segments, k_hi = auto_k ? n_units : cfg->k_segments;
+    bool fits = false;
+    uint64_t least = ~0ull;  // smallest arena among the candidates tried
+    for (int k = k_lo; ok && !fits && k <= k_hi; ++k)
+      for (int mode = auto_mode ? 0 : cfg->storage_mode; ok && !fits && mode <= (auto_mode ? 1 : cfg->storage_mode); ++mode) {
+        p.cfg.k_segments = k;
+        p.cfg.storage_mode = mode;
+        ok = choose_segments(p) && build_schedule(p);
+        fits = ok && (!cfg->activation_budget_bytes || p.arena_bytes <= cfg->activation_budget_bytes);
+        if (ok && p.arena_bytes < least) least = p.arena_bytes;
+      }
+    if (ok && !fits && (auto_k || auto_mode)) {
+      g_create_error = "no plan fits the budget of " + std::to_string(cfg->activation_budget_bytes) +
+                       " bytes: the smallest activation arena among the candidates is " + std::to_string(least) + " bytes";
+      delete h;
+      return OPTORCH_E_BUDGET;
+    }
   }
   p.cfg.boundaries = nullptr;  // the copy dies with this call; seg_begin holds the result
   if (!ok) { g_create_error = p.error; delete h; return OPTORCH_E_INVALID; }
@@ -148,6 +170,13 @@ extern "C" int optorch_seq_query(const optorch_seq_t* h, uint64_t* param_count, 
   if (planned_peak_saved_bytes) *planned_peak_saved_bytes = h->plan.peak_saved_bytes;
   if (boundaries_out)
     for (size_t j = 1; j + 1 < h->plan.seg_begin.size(); ++j) boundaries_out[j - 1] = h->plan.seg_begin[j];
+  return OPTORCH_OK;
+}
+
+extern "C" int optorch_seq_plan_info(const optorch_seq_t* h, int32_t* k_segments, int32_t* storage_mode) {
+  if (!h) return OPTORCH_E_INVALID;
+  if (k_segments) *k_segments = (int32_t)h->plan.seg_begin.size() - 1;
+  if (storage_mode) *storage_mode = h->plan.cfg.storage_mode;
   return OPTORCH_OK;
 }
 

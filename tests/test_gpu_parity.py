@@ -284,6 +284,19 @@ def test_storage_mode_1_is_bit_identical_and_keeps_less(name, precision, ks):
         assert_parity(units, h_, w_, b["grads"], g, TOL[precision], "%s storage_mode 1 k=%d" % (name, k))
 
 
+def test_plan_chosen_under_a_budget_runs_and_matches_all_stored():
+    from paper_2105_00619_amd.binding import SeqPlan
+    units, classes = NETS["bottleneck"]
+    p, x, y = _inputs(units, 6, 12, 12, classes)
+    kw = dict(precision=W.BF16, batch=6, height=12, width=12, channels=3, num_classes=classes)
+    full = SeqPlan(units, k_segments=1, **kw).act_arena_bytes
+    budget = int(0.7 * full)
+    ref, _ = gpu_step(units, p, x, y, precision=W.BF16, k=1, classes=classes)
+    r, info = gpu_step(units, p, x, y, precision=W.BF16, k=0, classes=classes, storage_mode=-1, activation_budget_bytes=budget)
+    assert info["act_arena_bytes"] <= budget and r["peak_arena_bytes"] == info["act_arena_bytes"]
+    assert np.array_equal(ref["grads"], r["grads"]) and ref["loss"] == r["loss"]
+
+
 def test_storage_mode_1_at_benchmark_size():
     wl = W.config(2)
     p, x, y = W.make_batch(wl)

@@ -106,6 +106,33 @@ def test_storage_mode_1_keeps_z_only_analytic_count():
         assert bb.act_arena_bytes < a.act_arena_bytes
 
 
+def test_automatic_choice_of_segments_and_storage_mode_under_a_budget():
+    # k_segments 0 / storage_mode -1: fewest segments first, keeping activations before rebuilding them
+    w = W.config(5)
+    fixed = {k: _plan(5, k_segments=k, activation_budget_bytes=0).act_arena_bytes for k in (1, 2, 3, 4)}
+    p = SeqPlan.from_workload(w, k_segments=0, storage_mode=-1)  # the configuration's 32 GiB
+    assert (p.k_segments, p.storage_mode) == (4, 0) and len(p.boundaries) == 3
+    assert p.act_arena_bytes == fixed[4] <= 32 * 2 ** 30 < fixed[3]
+    p = SeqPlan.from_workload(w, k_segments=0, storage_mode=-1, activation_budget_bytes=0)
+    assert (p.k_segments, p.storage_mode, p.act_arena_bytes) == (1, 0, fixed[1])
+    # rebuilding activations is tried before a further segment
+    v = W.config(2)
+    a0 = _plan(2, k_segments=1, activation_budget_bytes=0).act_arena_bytes
+    a1 = _plan(2, k_segments=1, storage_mode=1, activation_budget_bytes=0).act_arena_bytes
+    p = SeqPlan.from_workload(v, k_segments=0, storage_mode=-1, activation_budget_bytes=(a0 + a1) // 2)
+    assert (p.k_segments, p.storage_mode, p.act_arena_bytes) == (1, 1, a1)
+    p = SeqPlan.from_workload(v, k_segments=0, storage_mode=0, activation_budget_bytes=(a0 + a1) // 2)
+    assert p.k_segments > 1 and p.storage_mode == 0 and p.act_arena_bytes <= (a0 + a1) // 2
+    p = SeqPlan.from_workload(v, k_segments=4, storage_mode=-1, activation_budget_bytes=0)
+    assert (p.k_segments, p.storage_mode) == (4, 0)
+    with pytest.raises(OptorchError) as e:
+        SeqPlan.from_workload(v, k_segments=0, storage_mode=-1, activation_budget_bytes=2 ** 20)
+    assert e.value.code == binding.E_BUDGET and "smallest" in str(e.value)
+    with pytest.raises(OptorchError) as e:
+        SeqPlan.from_workload(v, k_segments=0, boundaries=[3])
+    assert e.value.code == binding.E_INVALID
+
+
 def test_peak_shrinks_with_segments_and_plan_is_reproducible():
     p1, p4, p4b = _plan(2, k_segments=1), _plan(2, k_segments=4), _plan(2, k_segments=4)
     assert p4.boundaries == [3, 6, 9] == p4b.boundaries
