@@ -164,6 +164,11 @@ int optorch_seq_step_encoded(optorch_seq_t* h, const uint64_t* a_dev, int32_t z,
  * optorch_seq_step on the same handle.  Errors as optorch_seq_step. */
 int optorch_seq_predict(optorch_seq_t* h, const float* x_dev, float* logits_dev);
 
+/* optorch_seq_predict on a batch in encoded form; a_dev, z, scale_host and shift_host as for
+ * optorch_seq_step_encoded. */
+int optorch_seq_predict_encoded(optorch_seq_t* h, const uint64_t* a_dev, int32_t z, const float* scale_host,
+                                const float* shift_host, float* logits_dev);
+
 /* The BatchNorm running statistics: for every BatchNorm in parameter order, C running means then C running
  * variances (fp32).  They start at 0 and 1 (optorch_seq_set_params) and every optorch_seq_step moves them by
  * bn_momentum towards the batch mean and the unbiased batch variance, also on a step that is then skipped for a

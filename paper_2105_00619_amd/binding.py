@@ -21,7 +21,7 @@ SYMBOLS = (
     "optorch_seq_create", "optorch_seq_query", "optorch_seq_bind", "optorch_seq_set_params",
     "optorch_seq_get_params", "optorch_seq_step", "optorch_seq_schedule_info", "optorch_seq_last_error",
     "optorch_seq_destroy", "optorch_seq_predict", "optorch_seq_running_stats", "optorch_seq_profile_enable", "optorch_seq_profile_select", "optorch_seq_profile_read", "optorch_seq_profile_read_entries",
-    "optorch_seq_step_encoded", "optorch_seq_plan_info",
+    "optorch_seq_step_encoded", "optorch_seq_predict_encoded", "optorch_seq_plan_info",
     "optorch_encoded_words", "optorch_encode", "optorch_decode", "optorch_decode_normalized", "optorch_encode_lossless",
     "optorch_decode_lossless", "optorch_dataflow_last_error",
 )
@@ -78,6 +78,8 @@ def load_library() -> C.CDLL:
                                              C.c_float, C.POINTER(C.c_float), C.c_void_p, C.POINTER(C.c_uint64),
                                              C.POINTER(C.c_uint64), C.POINTER(C.c_float), C.POINTER(C.c_int32)]
     lib.optorch_seq_step_encoded.restype = C.c_int
+    lib.optorch_seq_predict_encoded.argtypes = [H, C.c_void_p, C.c_int32, C.POINTER(C.c_float), C.POINTER(C.c_float), C.c_void_p]
+    lib.optorch_seq_predict_encoded.restype = C.c_int
     lib.optorch_encoded_words.argtypes = [C.c_int32, C.c_int32]
     lib.optorch_encoded_words.restype = C.c_int32
     lib.optorch_encode.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p]
@@ -280,6 +282,17 @@ class SeqTrainer(SeqPlan):
         assert tuple(x.shape) == (self.batch, self.height, self.width, self.channels)
         out = torch.empty((self.batch, self.num_classes), dtype=torch.float32, device=self.device)
         self._check(self.lib.optorch_seq_predict(self.handle, x.data_ptr(), out.data_ptr()))
+        return out
+
+    def predict_encoded(self, a, z: int, scale, shift):
+        """`predict` on a batch in encoded form (see `step_encoded`)."""
+        torch = self.torch
+        groups = -(-self.batch // z)
+        assert a.is_cuda and a.dtype == torch.int64 and a.is_contiguous()
+        assert a.numel() == groups * self.height * self.width * self.channels * encoded_words(z)
+        out = torch.empty((self.batch, self.num_classes), dtype=torch.float32, device=self.device)
+        self._check(self.lib.optorch_seq_predict_encoded(self.handle, a.data_ptr(), z, _float_array(scale, self.channels),
+                                                         _float_array(shift, self.channels), out.data_ptr()))
         return out
 
     def running_stats(self) -> np.ndarray:

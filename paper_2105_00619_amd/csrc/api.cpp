@@ -485,12 +485,8 @@ extern "C" int optorch_seq_profile_read_entries(optorch_seq_t* h, int32_t capaci
 // Inference: the forward entries of the schedule (all segments without keeping, then the last segment), with the
 // BatchNorm constants taken from the running statistics and the head stopped at the logits.  The arena offsets of
 // those entries are valid on their own: the entries run in schedule order and the plan never lets two live tensors
-// overlap.
-extern "C" int optorch_seq_predict(optorch_seq_t* h, const float* x_dev, float* logits_dev) {
-  if (!h) return OPTORCH_E_INVALID;
-  if (!h->bound || !h->params_set) return set_err(h, OPTORCH_E_ORDER, "predict before bind/set_params");
-  if (!x_dev || !logits_dev) return set_err(h, OPTORCH_E_INVALID, "null pointer");
-  Ctx c{h, x_dev, nullptr};
+// overlap.  c describes the batch (fp32 or encoded).
+static int predict_run(optorch_seq_t* h, const Ctx& c, float* logits_dev) {
   hipStream_t st = h->stream;
   const int dt = h->dt;
   for (const SOp& s : h->plan.sched) {
@@ -523,6 +519,27 @@ extern "C" int optorch_seq_predict(optorch_seq_t* h, const float* x_dev, float* 
   e = hipStreamSynchronize(st);
   if (e != hipSuccess) return hip_fail(h, e, "hipStreamSynchronize");
   return OPTORCH_OK;
+}
+
+extern "C" int optorch_seq_predict(optorch_seq_t* h, const float* x_dev, float* logits_dev) {
+  if (!h) return OPTORCH_E_INVALID;
+  if (!h->bound || !h->params_set) return set_err(h, OPTORCH_E_ORDER, "predict before bind/set_params");
+  if (!x_dev || !logits_dev) return set_err(h, OPTORCH_E_INVALID, "null pointer");
+  Ctx c{h, x_dev, nullptr};
+  return predict_run(h, c, logits_dev);
+}
+
+extern "C" int optorch_seq_predict_encoded(optorch_seq_t* h, const uint64_t* a_dev, int32_t z, const float* scale_host,
+                                           const float* shift_host, float* logits_dev) {
+  if (!h) return OPTORCH_E_INVALID;
+  if (!h->bound || !h->params_set) return set_err(h, OPTORCH_E_ORDER, "predict before bind/set_params");
+  if (!a_dev || !logits_dev || !scale_host || !shift_host) return set_err(h, OPTORCH_E_INVALID, "null pointer");
+  if (z < 1 || z > 16) return set_err(h, OPTORCH_E_INVALID, "images per group must be 1..16");
+  if (h->in_channels < 1 || h->in_channels > 16)
+    return set_err(h, OPTORCH_E_INVALID, "an encoded batch needs a network input of 1..16 channels");
+  Ctx c{h, nullptr, nullptr};
+  c.xa = a_dev; c.xz = z; c.xscale = scale_host; c.xshift = shift_host;
+  return predict_run(h, c, logits_dev);
 }
 
 extern "C" int optorch_seq_running_stats(const optorch_seq_t* h, float* dst, uint64_t capacity, uint64_t* count,

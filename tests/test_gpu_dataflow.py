@@ -192,4 +192,8 @@ def test_step_on_an_encoded_batch_matches_oracle_and_the_plain_step(precision):
     r2 = t.step(xf, yd, 0.0, gd)
     assert r2["loss"] == r["loss"]
     assert np.array_equal(gd.cpu().numpy(), g_enc)
+    # inference on the encoded batch = inference on the decode layer's output
+    la = t.predict_encoded(_dev_words(words), z, scale, shift)
+    lb = t.predict(xf)
+    assert bool((la == lb).all()) and bool(torch.isfinite(la).all())
     t.close()
