@@ -53,14 +53,14 @@ __device__ __forceinline__ void t8x8(const uint32_t* ilo, const uint32_t* ihi, u
 // 128-byte pieces and the lane-contiguous accesses are both free of bank conflicts
 __device__ __forceinline__ int df_slot(int q) { return q + (q >> 4); }
 
-template <int W>
-constexpr int df_lds_chunks() { return 1024 * W + 64 * W; }
+// dynamic LDS of a block of nthr threads: its 4 W chunks per thread plus the padding slots
+inline size_t df_lds_bytes(int W, int nthr) { return (size_t)(nthr * 4 * W + nthr * 4 * W / 16) * 16; }
 
 // ---- Encode: x [B][P] bytes -> a [G][P][W] words ---------------------------------------------------------------
 template <int W>
 __global__ __launch_bounds__(256) void encode_kernel(const uint8_t* __restrict__ x, uint4* __restrict__ a4, int z, int64_t P,
                                                      int64_t B, int tiles) {
-  __shared__ uint4 buf[df_lds_chunks<W>()];
+  extern __shared__ uint4 buf[];
   const int tid = threadIdx.x, nthr = blockDim.x;
   const int tile_pos = nthr * DF_POS;
   const int64_t g = blockIdx.x / tiles;
@@ -116,7 +116,7 @@ template <int W, class T>
 __global__ __launch_bounds__(256) void decode_kernel(const uint4* __restrict__ a4, T* __restrict__ out, int z, int64_t P,
                                                      int64_t B, int tiles, DfNorm nm) {
   constexpr bool RAW = sizeof(T) == 1;
-  __shared__ uint4 buf[df_lds_chunks<W>()];
+  extern __shared__ uint4 buf[];
   __shared__ float s_scale[16], s_shift[16];
   const int tid = threadIdx.x, nthr = blockDim.x;
   const int tile_pos = nthr * DF_POS;
@@ -350,8 +350,8 @@ void launch_decode_t(hipStream_t st, const uint64_t* a, int64_t B, int64_t P, in
     const int nthr = df_threads(P);
     const int tiles = (int)((P + nthr * DF_POS - 1) / (nthr * DF_POS));
     const dim3 grid((unsigned)(G * tiles)), block(nthr);
-    if (W == 1) OSEQ_LAUNCH((decode_kernel<1, T>), grid, block, 0, st, (const uint4*)a, out, z, P, B, tiles, nm);
-    else OSEQ_LAUNCH((decode_kernel<2, T>), grid, block, 0, st, (const uint4*)a, out, z, P, B, tiles, nm);
+    if (W == 1) OSEQ_LAUNCH((decode_kernel<1, T>), grid, block, df_lds_bytes(1, nthr), st, (const uint4*)a, out, z, P, B, tiles, nm);
+    else OSEQ_LAUNCH((decode_kernel<2, T>), grid, block, df_lds_bytes(2, nthr), st, (const uint4*)a, out, z, P, B, tiles, nm);
   } else {
     const int64_t total = G * P;
     const dim3 grid((unsigned)((total + 255) / 256)), block(256);
@@ -370,8 +370,8 @@ void launch_encode(hipStream_t st, const uint8_t* x, int64_t B, int64_t P, int z
     const int nthr = df_threads(P);
     const int tiles = (int)((P + nthr * DF_POS - 1) / (nthr * DF_POS));
     const dim3 grid((unsigned)(G * tiles)), block(nthr);
-    if (W == 1) OSEQ_LAUNCH(encode_kernel<1>, grid, block, 0, st, x, (uint4*)a, z, P, B, tiles);
-    else OSEQ_LAUNCH(encode_kernel<2>, grid, block, 0, st, x, (uint4*)a, z, P, B, tiles);
+    if (W == 1) OSEQ_LAUNCH(encode_kernel<1>, grid, block, df_lds_bytes(1, nthr), st, x, (uint4*)a, z, P, B, tiles);
+    else OSEQ_LAUNCH(encode_kernel<2>, grid, block, df_lds_bytes(2, nthr), st, x, (uint4*)a, z, P, B, tiles);
   } else {
     const int64_t total = G * P;
     const dim3 grid((unsigned)((total + 255) / 256)), block(256);
