@@ -357,6 +357,45 @@ def test_loss_scale_grows_after_clean_interval():
     assert not any(o["skipped"] for o in outs)
 
 
+def test_loss_scale_dynamics_over_thousands_of_steps():
+    # fp16 with the default rule (start 2^16, x2 after 2000 clean steps, x1/2 and skip on a non-finite gradient): the
+    # scale keeps doubling until the scaled gradients leave the fp16 range, then the rule holds it one or two
+    # doublings below that.  Every transition must follow the rule given the step's own skip flag, skipped steps leave
+    # the weights alone, and training goes on underneath (the loss falls).
+    import torch
+    from paper_2105_00619_amd.binding import SeqTrainer
+    units, classes = NETS["conv_bn_relu"]
+    b, h, w = 8, 8, 8
+    p, x, y = _inputs(units, b, h, w, classes)
+    interval, steps = 50, 4000
+    t = SeqTrainer(units, k_segments=2, precision=W.FP16, batch=b, height=h, width=w, channels=3, num_classes=classes,
+                   momentum=0.9, growth_interval=interval)
+    t.set_params(p)
+    xd, yd = torch.from_numpy(x).cuda(), torch.from_numpy(y).cuda()
+    scale, clean, skips, first_loss, last = 65536.0, 0, 0, None, None
+    prev_params = None
+    for i in range(steps):
+        r = t.step(xd, yd, 0.02)
+        if r["skipped"]:
+            scale, clean, skips = scale * 0.5, 0, skips + 1
+            if skips <= 3:  # (reading the weights back every step would dominate the test)
+                assert prev_params is not None and np.array_equal(t.get_params(), prev_params)
+        else:
+            clean += 1
+            if clean == interval:
+                scale, clean = scale * 2.0, 0
+            if first_loss is None:
+                first_loss = r["loss"]
+            last = r["loss"]
+        assert r["loss_scale"] == scale, "step %d: scale %g, rule says %g" % (i, r["loss_scale"], scale)
+        if skips < 3:
+            prev_params = t.get_params()
+    assert skips >= 2, "the scale never reached the fp16 range limit"
+    assert skips <= steps // interval, "more skipped steps than the rule can cause"
+    assert last < 0.5 * first_loss and np.isfinite(t.get_params()).all()
+    t.close()
+
+
 def test_momentum_two_steps_match_oracle_update():
     from oracle import seqnet_oracle as O
     units, classes = NETS["conv_bn_relu"]
