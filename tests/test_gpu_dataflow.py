@@ -123,6 +123,36 @@ def test_lossless_encode_and_decode_match_oracle(z, batch, n_pos):
     assert np.array_equal(x.cpu().numpy(), X)
 
 
+def test_random_shapes_match_oracle():
+    # seeded random (group size, batch, positions): tile tails, ragged groups and both kernel families in many mixes
+    from paper_2105_00619_amd import binding as B
+    torch = _torch()
+    rng = np.random.default_rng(20210500619)
+    for case in range(48):
+        lossless = case % 3 == 2
+        z = int(rng.integers(1, 33 if lossless else 17))
+        batch = int(rng.integers(1, 3 * z + 2))
+        n_pos = int(rng.choice([int(rng.integers(1, 64)), 8 * int(rng.integers(1, 400)), 4 * int(rng.integers(1, 600)),
+                                int(rng.integers(1, 3000))]))
+        X = rng.integers(0, 256, size=(batch, n_pos), dtype=np.uint8)
+        xd = torch.from_numpy(X).cuda()
+        what = "case %d: z=%d batch=%d n_pos=%d lossless=%d" % (case, z, batch, n_pos, lossless)
+        if lossless:
+            ref_a, ref_o = D.encode_lossless_batch_words(X, z)
+            a, o = B.encode_lossless(xd, z)
+            assert np.array_equal(_u64(a), ref_a) and np.array_equal(o.cpu().numpy().view(np.uint32), ref_o), what
+            assert np.array_equal(B.decode_lossless(a, o, batch, n_pos, z).cpu().numpy(), X), what
+        else:
+            ref = D.encode_batch_words(X, z)
+            a = B.encode(xd, z)
+            assert np.array_equal(_u64(a), ref), what
+            assert np.array_equal(B.decode(a, batch, n_pos, z).cpu().numpy(), X), what
+            sc, sh = rng.uniform(0.001, 0.02, 1).astype(np.float32), rng.uniform(-2, 2, 1).astype(np.float32)
+            got = B.decode_normalized(a, batch, n_pos, z, 1, sc, sh, W.FP32).cpu().numpy()
+            want = D.decode_normalized(ref, z, batch, 1, sc, sh)
+            assert np.all(np.abs(got - want) <= REL[W.FP32] * np.abs(want) + 2.0 ** -22), what
+
+
 def test_empty_batch_and_argument_errors():
     from paper_2105_00619_amd import binding as B
     torch = _torch()
