@@ -371,6 +371,7 @@ struct PatchArgs {
   int chunks_per_split;      // channel chunks per blockIdx.z (all of them when the depth is not split)
   int row_pitch;             // bytes between staged patch rows in LDS (>= SC * 80, padded against bank conflicts)
   int patch_elems;           // elements of one staged patch buffer (its rows times row_pitch, rounded up to 16 bytes)
+  int xcd_group;             // 1: blocks are renumbered so that the row tiles of one weight slice run on one XCD
 };
 
 constexpr int PATCH_MAX_POS = 256;  // positions per sub-tile
@@ -399,7 +400,18 @@ conv3x3_patch_kernel(const T* __restrict__ src, const T* __restrict__ wmat, cons
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1, g = lane >> 5, l32 = lane & 31;
-  const int n0c = blockIdx.y * BN;
+  // Block coordinates: (row tile, channel block, depth range).  Workgroups go to the 8 XCDs round-robin by their
+  // linear index, and every XCD has an L2 of its own.  With large weights and few pixels the row tiles of one
+  // (channel block, depth range) all read the same weight slice: renumbered, they run on one XCD, which then fetches
+  // the slice once instead of all eight doing so.  Needs (channel blocks x depth ranges) % 8 == 0 (launcher).
+  int bx = blockIdx.x, by = blockIdx.y, bz = blockIdx.z;
+  if (a.xcd_group) {
+    const unsigned lin = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
+    const unsigned xcd = lin & 7u, slot = lin >> 3;
+    const unsigned grp = (slot / gridDim.x) * 8u + xcd;  // index of the (channel block, depth range) pair
+    bx = (int)(slot % gridDim.x); by = (int)(grp % gridDim.y); bz = (int)(grp / gridDim.y);
+  }
+  const int n0c = by * BN;
   const int npos2 = SUBT * a.NPOS;
   const int srcC = a.srcC, flip = a.flip, SC = a.SC;
   const int RPE = a.row_pitch / (int)sizeof(T);  // elements between staged patch rows
@@ -409,7 +421,7 @@ conv3x3_patch_kernel(const T* __restrict__ src, const T* __restrict__ wmat, cons
     const int u = e / a.NPOS, rem = e - u * a.NPOS;
     const int ti = rem / (a.SR * a.SC), rr = rem - ti * (a.SR * a.SC);
     const int sy = rr / a.SC, sx = rr - sy * a.SC;
-    const int tile = SUBT * blockIdx.x + u;
+    const int tile = SUBT * bx + u;
     int64_t off = -1;
     if (tile < a.NT) {
       const int ci = tile % a.tiles_c, t2 = tile / a.tiles_c;
@@ -421,7 +433,7 @@ conv3x3_patch_kernel(const T* __restrict__ src, const T* __restrict__ wmat, cons
   }
   {
     const int m2 = tid, u = m2 / TPC, m = m2 - u * TPC;
-    const int tile = SUBT * blockIdx.x + u;
+    const int tile = SUBT * bx + u;
     int64_t off = -1;
     int ap = 0;
     if (m2 < ROWS && m < a.TP && tile < a.NT) {
@@ -440,7 +452,7 @@ conv3x3_patch_kernel(const T* __restrict__ src, const T* __restrict__ wmat, cons
 
   // channel chunks of this block: all of them, or the range of blockIdx.z (raw sums go to `partial`, a second
   // kernel adds the ranges in order and applies the epilogue)
-  const int cb = blockIdx.z * a.chunks_per_split;
+  const int cb = bz * a.chunks_per_split;
   const int ce = cb + a.chunks_per_split < srcC / CCE ? cb + a.chunks_per_split : srcC / CCE;
   const int Kg = 9 * srcC;
 
@@ -614,13 +626,13 @@ conv3x3_patch_kernel(const T* __restrict__ src, const T* __restrict__ wmat, cons
       __syncthreads();
       auto rowoff = [&](int row) -> int64_t { return out_off[u * HR + row]; };
       if (partial)
-        epi_store_partial<BN, HR>(ep, tid, n0c, partial + (int64_t)blockIdx.z * ((int64_t)a.N * a.dstH * a.dstW * a.Ng), rowoff);
+        epi_store_partial<BN, HR>(ep, tid, n0c, partial + (int64_t)bz * ((int64_t)a.N * a.dstH * a.dstW * a.Ng), rowoff);
       else
         epi_store_pass<T, BN, HR, true, !STAT, STAT>(ep, tid, n0c, bias, addend, out, a.relu, rowoff, ss, qq);
     }
     if (STAT)
-      epi_stat_combine<BN>(ep, tid, ss, qq, stat_partial + ((int64_t)blockIdx.x * 2 + 0) * a.Ng + n0c,
-                           stat_partial + ((int64_t)blockIdx.x * 2 + 1) * a.Ng + n0c);
+      epi_stat_combine<BN>(ep, tid, ss, qq, stat_partial + ((int64_t)bx * 2 + 0) * a.Ng + n0c,
+                           stat_partial + ((int64_t)bx * 2 + 1) * a.Ng + n0c);
   }
 }
 
@@ -744,6 +756,8 @@ int g_patch_shapes = 0x7;      // bit i: candidate i allowed
 int g_patch_split = 1;         // allow the depth split
 int g_patch_halo2 = 9;         // largest staged positions : pixels ratio, times two
 int g_patch_target_small = 512;  // blocks aimed at by the depth split for the smallest block shape in fp32
+int64_t g_patch_xcd_wbytes = 4 << 20;  // XCD grouping of the blocks: least weight bytes (0: never) ...
+int g_patch_xcd_rows = 16;              // ... and most row tiles
 static bool patch_pick(int dt, int N, int dstH, int dstW, int srcC, int Ng, int R, int S, int stride, PatchShape& shape,
                        PatchArgs& geo) {
   if (R != 3 || S != 3 || stride != 1) return false;
@@ -805,6 +819,9 @@ static void launch_patch_v(hipStream_t st, const void* src, const void* wmat, co
   if (pe * (int64_t)sizeof(T) < need) pe = (need + 15) / 16 * 16 / (int64_t)sizeof(T);
   if (pe > (int64_t)SUBT * PATCH_MAX_POS * PITCH_E) pe = (int64_t)SUBT * PATCH_MAX_POS * PITCH_E;
   a.patch_elems = (int)pe;
+  // from the shape only: weights of at least g_patch_xcd_wbytes that at most g_patch_xcd_rows row tiles share
+  a.xcd_group = g_patch_xcd_wbytes > 0 && (int64_t)9 * a.srcC * a.Ng * (int64_t)sizeof(T) >= g_patch_xcd_wbytes &&
+                (int)grid.x <= g_patch_xcd_rows && (grid.y * grid.z) % 8 == 0;
   const size_t sm = patch_smem_bytes<T>(BN, SUBT, pe);
   static bool attr_done = false;
   if (!attr_done) {
