@@ -171,7 +171,7 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", type=int, default=2, help="benchmark configuration 1..6 (default 2: VGG-11-BN fp32, k=4)")
-    ap.add_argument("--k", type=int, default=None, help="override the number of segments")
+    ap.add_argument("--k", type=int, default=None, help="override the number of segments (0: the fewest that fit the workload's activation budget)")
     ap.add_argument("--batch", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-batch", type=int, default=None, help="default: the workload's batch")
@@ -179,7 +179,7 @@ def main():
     ap.add_argument("--timed-every", type=int, default=4,
                     help="steps of the timed region whose dominant-class launches carry events: every n-th")
     ap.add_argument("--storage-mode", type=int, default=0,
-                    help="0: keep Z and A of every conv-BN-ReLU (default); 1: keep Z only, rebuild A in backward")
+                    help="0: keep Z and A of every conv-BN-ReLU (default); 1: keep Z only, rebuild A in backward; -1: 1 only if 0 does not fit the budget")
     ap.add_argument("--path", choices=("train", "dataflow"), default="train",
                     help="train: the checkpointed training step (default); dataflow: image Encode + decode layer")
     args = ap.parse_args()
@@ -295,7 +295,7 @@ def main():
         "value": wl.batch / (ms * 1e-3), "unit": "images/sec", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": DTYPE_NAME[wl.precision], "data": "synthetic",
-        "config": {"workload": wl.name, "batch": wl.batch, "k_segments": k, "storage_mode": args.storage_mode, "image": "%dx%dx%d NHWC" % (wl.height, wl.width, wl.channels),
+        "config": {"workload": wl.name, "batch": wl.batch, "k_segments": tr.k_segments, "storage_mode": tr.storage_mode, "image": "%dx%dx%d NHWC" % (wl.height, wl.width, wl.channels),
                    "boundaries": tr.boundaries, "plan_mode": wl.plan_mode, "momentum": wl.momentum},
         "loss": r["loss"], "peak_saved_bytes": r["peak_saved_bytes"], "peak_arena_bytes": r["peak_arena_bytes"],
         "activation_budget_bytes": wl.budget_bytes, "launches_per_step": tr.n_launches,
