@@ -49,12 +49,22 @@ DATAFLOW_KERNELS = {
 }
 
 
-def source_hash() -> str:
+DATAFLOW_SOURCES = ("k_dataflow.hip", "dataflow.cpp", "dev_common.h", "launch.h", "kernels.h")
+
+
+def source_hash(workload: str = "") -> str:
+    """Hash of the sources a workload's kernels are built from: the data-flow files for the data-flow benchmark, all
+    the others (and the shared headers) for a training workload."""
+    dataflow = workload.startswith("dataflow")
     h = hashlib.sha1()
     for f in sorted(glob.glob(os.path.join(HERE, "csrc", "*"))):
-        if f.endswith((".hip", ".h", ".cpp")):
-            h.update(os.path.basename(f).encode())
-            h.update(open(f, "rb").read())
+        name = os.path.basename(f)
+        if not name.endswith((".hip", ".h", ".cpp")):
+            continue
+        if dataflow != (name in DATAFLOW_SOURCES) and name not in ("dev_common.h", "launch.h", "kernels.h"):
+            continue
+        h.update(name.encode())
+        h.update(open(f, "rb").read())
     return h.hexdigest()
 
 
@@ -64,7 +74,7 @@ def lookup(workload: str, group: str):
         return None
     d = json.load(open(STORE))
     rec = d.get(workload)
-    if not rec or rec.get("source_hash") != source_hash():
+    if not rec or rec.get("source_hash") != source_hash(workload):
         return None
     return rec.get("groups", {}).get(group)
 
@@ -121,7 +131,7 @@ def ingest(args) -> None:
             write = _sum_counter(args.write, "WRITE_SIZE", frags) * fw * 1024.0 / args.steps
             groups[g] = {"fetch_bytes_per_step": fetch, "write_bytes_per_step": write, "bytes_per_step": fetch + write}
     d = json.load(open(STORE)) if os.path.exists(STORE) else {}
-    d[args.workload] = {"source_hash": source_hash(), "steps_counted": args.steps,
+    d[args.workload] = {"source_hash": source_hash(args.workload), "steps_counted": args.steps,
                         "calibration": {"fetch_factor": ff, "write_factor": fw, "copy_mib": COPY_MIB, "reps": COPY_REPS},
                         "groups": groups}
     json.dump(d, open(STORE, "w"), indent=1, sort_keys=True)
