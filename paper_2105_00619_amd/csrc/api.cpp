@@ -299,8 +299,12 @@ void run_op(const Ctx& c, const SOp& s) {
                         (float*)(h->pbase + h->off_run) + f.rs_off);
       break;
     case S_BN_APPLY:
-      launch_bn_apply(st, dt, c.at(s.in[0]), (const float*)c.at(s.in[1]), c.at(s.in[2]), c.at(s.out[0]),
-                      (int64_t)f.N * f.P * f.Q, f.C, f.relu);
+      if (s.out[1] >= 0)  // with the 2x2 max-pool that follows
+        launch_bn_apply_pool(st, dt, c.at(s.in[0]), (const float*)c.at(s.in[1]), c.at(s.out[0]), c.at(s.out[1]), f.N, f.P,
+                             f.Q, f.C, f.relu);
+      else
+        launch_bn_apply(st, dt, c.at(s.in[0]), (const float*)c.at(s.in[1]), c.at(s.in[2]), c.at(s.out[0]),
+                        (int64_t)f.N * f.P * f.Q, f.C, f.relu);
       break;
     case S_POOL_FWD:
       launch_maxpool_fwd(st, dt, c.at(s.in[0]), c.at(s.out[0]), f.N, f.H, f.W, f.C);
@@ -378,7 +382,10 @@ void work_of(const optorch_seq_t* h, const SOp& s, double* flops, double* bytes)
     case S_DGRAD: *flops = 2 * out_px * wts; *bytes = e * (in_px * f.C * (s.in[1] >= 0 ? 2 : 1) + out_px * f.K + wts); break;
     case S_WGRAD: *flops = 2 * out_px * wts; *bytes = e * (in_px * f.C + out_px * f.K) + 4 * wts; break;
     case S_BN_STATS: *bytes = s.in[1] >= 0 ? 8.0 * f.stat_blocks * f.C : e * out_px * f.C; break;  // fused: only the block sums
-    case S_BN_APPLY: *bytes = e * out_px * f.C * (s.in[2] >= 0 ? 3 : 2); break;
+    case S_BN_APPLY:
+      if (s.out[1] >= 0) *bytes = e * out_px * f.C * (1.0 + (s.out[0] >= 0 ? 1.0 : 0.0) + 0.25);  // z, [a], pooled
+      else *bytes = e * out_px * f.C * (s.in[2] >= 0 ? 3 : 2);
+      break;
     case S_BN_BWD: *bytes = e * out_px * f.C * (2 + (s.in[3] >= 0 ? 1 : 0) + 3 + (s.in[3] >= 0 ? 1 : 0) + (s.out[1] >= 0 ? 1 : 0)); break;
     case S_POOL_FWD: *bytes = e * (in_px + out_px) * f.C; break;
     case S_POOL_BWD: *bytes = e * (2 * in_px + out_px) * f.C; break;

@@ -298,6 +298,46 @@ __global__ void __launch_bounds__(256) bn_apply_kernel(const T* __restrict__ z, 
   store_f32<T, V>(out + off, vo);
 }
 
+// BatchNorm apply (+ReLU) and the 2x2 max-pool that follows it in one pass over z: a thread owns one pooled position
+// of V channels, i.e. the four activations of its window.  The activations are rounded to the storage type before the
+// maximum is taken, as the separate pooling kernel finds them in memory, so the result is the same bits.  WRITE_A:
+// the activations themselves are also kept (they are when backward needs them).
+template <class T, int V, bool WRITE_A>
+__global__ void __launch_bounds__(256) bn_apply_pool_kernel(const T* __restrict__ z, const float* __restrict__ stats,
+                                                            T* __restrict__ a, T* __restrict__ y, int N, int H, int W, int C,
+                                                            int relu) {
+  const int CG = C / V, P = H / 2, Q = W / 2;
+  const int64_t total = (int64_t)N * P * Q * CG;
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= total) return;
+  const int cg = (int)(i % CG);
+  int64_t t = i / CG;
+  const int q = (int)(t % Q); t /= Q;
+  const int pp = (int)(t % P);
+  const int n = (int)(t / P);
+  const int c0 = cg * V;
+  const int64_t base = (((int64_t)n * H + 2 * pp) * W + 2 * q) * C + c0;
+  const int64_t offs[4] = {0, (int64_t)C, (int64_t)W * C, (int64_t)W * C + C};
+  float vz[4][V], scale[V], shift[V];
+#pragma unroll
+  for (int u = 0; u < 4; ++u) load_f32<T, V>(z + base + offs[u], vz[u]);
+  load_f32<float, V>(stats + 2 * C + c0, scale);
+  load_f32<float, V>(stats + 3 * C + c0, shift);
+  float m[V];
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    float va[V];
+#pragma unroll
+    for (int k = 0; k < V; ++k) {
+      const float yv = bn_affine(vz[u][k], scale[k], shift[k]);
+      va[k] = to_f32(from_f32<T>(relu ? fmaxf(yv, 0.f) : yv));
+      m[k] = (u == 0 || va[k] > m[k]) ? va[k] : m[k];
+    }
+    if (WRITE_A) store_f32<T, V>(a + base + offs[u], va);
+  }
+  store_f32<T, V>(y + i * V, m);
+}
+
 // AOUT: the ReLU mask comes from the block output (a residual sum) instead of being rebuilt from z; DSKIP: the masked
 // gradient is also written out for the skip branch
 template <class T, int V, bool AOUT, bool DSKIP>
@@ -511,6 +551,18 @@ void launch_bn_apply(hipStream_t st, int dt, const void* z, const float* stats, 
                                  (const T*)z, stats, (const T*)skip, (T*)out, groups, C, relu);                        \
     else OSEQ_LAUNCH((bn_apply_kernel<T, V, false>), dim3(ceil_div(groups, 256)), dim3(256), 0, st,             \
                             (const T*)z, stats, (const T*)skip, (T*)out, groups, C, relu); }
+  DISPATCH_TV(dt, C, CALL);
+#undef CALL
+}
+
+void launch_bn_apply_pool(hipStream_t st, int dt, const void* z, const float* stats, void* a, void* y, int N, int H, int W,
+                          int C, int relu) {
+#define CALL(T, V)                                                                                                     \
+  { const int64_t total = (int64_t)N * (H / 2) * (W / 2) * (C / V);                                                     \
+    if (a) OSEQ_LAUNCH((bn_apply_pool_kernel<T, V, true>), dim3(ceil_div(total, 256)), dim3(256), 0, st, (const T*)z,   \
+                       stats, (T*)a, (T*)y, N, H, W, C, relu);                                                          \
+    else OSEQ_LAUNCH((bn_apply_pool_kernel<T, V, false>), dim3(ceil_div(total, 256)), dim3(256), 0, st, (const T*)z,    \
+                     stats, (T*)a, (T*)y, N, H, W, C, relu); }
   DISPATCH_TV(dt, C, CALL);
 #undef CALL
 }

@@ -24,6 +24,10 @@ void launch_bn_eval_stats(hipStream_t st, const float* running, const float* gam
                           float* stats);
 void launch_bn_apply(hipStream_t st, int dt, const void* z, const float* stats, const void* skip, void* out, int64_t rows,
                      int C, int relu);
+// BatchNorm apply and the 2x2 max-pool behind it in one pass (H, W even): z [N][H][W][C] -> a (may be null: not kept)
+// and y [N][H/2][W/2][C]
+void launch_bn_apply_pool(hipStream_t st, int dt, const void* z, const float* stats, void* a, void* y, int N, int H, int W,
+                          int C, int relu);
 void launch_bn_bwd(hipStream_t st, int dt, const void* da, const void* z, const void* aout, const float* stats, int64_t rows,
                    int C, int relu, int nblk, float* ws, float* dgamma, float* dbeta, void* dz, void* dskip);
 void launch_relu_bwd(hipStream_t st, int dt, const void* da, const void* a, void* dz, int64_t rows, int C);

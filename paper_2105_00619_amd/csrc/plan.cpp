@@ -254,6 +254,18 @@ struct Scheduler {
     return p.sched.back();
   }
 
+  // Is forward operation fi a 2x2 max-pool that the BatchNorm apply right in front of it computes as well?  Both must
+  // lie in segment `seg` (a pool that opens a segment is replayed from the segment's kept input), the apply must add
+  // no skip connection, and the map must have even sides.
+  bool pool_fused(int fi, int seg) const {
+    if (fi < 1 || fi >= (int)p.fops.size()) return false;
+    const FOp& pool = p.fops[fi];
+    const FOp& ap = p.fops[fi - 1];
+    if (pool.kind != F_POOL || ap.kind != F_BN_APPLY || pool.x != ap.out || ap.skip >= 0) return false;
+    if (ap.P % 2 != 0 || ap.Q % 2 != 0) return false;
+    return ap.unit >= p.seg_begin[seg] && pool.unit < p.seg_begin[seg + 1];
+  }
+
   void emit_fop_forward(int fi, int phase, int seg) {
     const FOp& f = p.fops[fi];
     switch (f.kind) {
@@ -280,9 +292,14 @@ struct Scheduler {
         SOp& s = push(S_BN_APPLY, fi, phase, seg);
         s.in[0] = cur[f.x]; s.in[1] = cur[f.stats]; s.in[2] = f.skip >= 0 ? cur[f.skip] : -1;
         s.out[0] = value_inst(f.out);
+        if (pool_fused(fi + 1, seg)) s.out[1] = value_inst(p.fops[fi + 1].out);  // the same kernel also pools
         break;
       }
-      case F_POOL: { SOp& s = push(S_POOL_FWD, fi, phase, seg); s.in[0] = cur[f.x]; s.out[0] = value_inst(f.out); break; }
+      case F_POOL: {
+        if (pool_fused(fi, seg)) break;  // done by the BatchNorm apply in front of it
+        SOp& s = push(S_POOL_FWD, fi, phase, seg); s.in[0] = cur[f.x]; s.out[0] = value_inst(f.out);
+        break;
+      }
       case F_HEAD: {
         SOp& s = push(S_HEAD_FWD, fi, phase, seg);
         s.in[0] = cur[f.x];
@@ -437,6 +454,10 @@ bool build_schedule(Plan& p) {
     bool live = has_side_effect(op.kind);
     for (int o : op.out) if (o >= 0 && uses[o] > 0) live = true;
     op.live = live;
+    if (live && op.kind == S_BN_APPLY && op.out[1] >= 0) {  // apply + pool: an output nobody reads is not written
+      if (uses[op.out[0]] == 0) op.out[0] = -1;
+      else if (uses[op.out[1]] == 0) op.out[1] = -1;
+    }
     if (live) for (int x : op.in) if (x >= 0) ++uses[x];
   }
   // lifetimes
