@@ -133,6 +133,18 @@ def test_automatic_choice_of_segments_and_storage_mode_under_a_budget():
     assert e.value.code == binding.E_INVALID
 
 
+def test_pool_is_computed_by_the_apply_kernel_unless_it_opens_a_segment():
+    # VGG-11-BN has 5 max-pools, each behind a conv-BN-ReLU.  All stored: every pool is done by the BatchNorm apply in
+    # front of it (100 launches as separate kernels, 95 fused).  Equal-count k = 4 puts boundaries at units 3, 6, 9, all
+    # three of them pools: those open a segment, are replayed from its kept input and stay kernels of their own.
+    assert _plan(2, k_segments=1).n_launches == 95
+    p = _plan(2, k_segments=4)
+    assert p.boundaries == [3, 6, 9] and (p.n_launches, p.n_replay_launches) == (111, 13)
+    # boundaries behind the pools instead: every pool is fused again, in the first pass and in the replay
+    q = _plan(2, k_segments=4, boundaries=[4, 7, 10])
+    assert (q.n_launches, q.n_replay_launches) == (109, 14)
+
+
 def test_peak_shrinks_with_segments_and_plan_is_reproducible():
     p1, p4, p4b = _plan(2, k_segments=1), _plan(2, k_segments=4), _plan(2, k_segments=4)
     assert p4.boundaries == [3, 6, 9] == p4b.boundaries
