@@ -1,0 +1,76 @@
+"""The static plan checked from outside the library: tests/plan_check.cpp is built with the planner's own source under
+AddressSanitizer and UBSan (host code only) and walks the schedule of every benchmark network at several k and both
+storage modes: reads only of live tensors, no overlap of live tensors in the arena, peaks and launch counts as
+reported.  (Kernel choices are left at their defaults there; they change split workspaces, not the walk.)"""
+import os
+import shutil
+import subprocess
+
+import pytest
+
+from paper_2105_00619_amd import workloads as W
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+CSRC = os.path.join(ROOT, "paper_2105_00619_amd", "csrc")
+
+
+@pytest.fixture(scope="module")
+def checker(tmp_path_factory):
+    cxx = shutil.which("g++") or shutil.which("c++")
+    if cxx is None:
+        pytest.skip("no host C++ compiler")
+    exe = str(tmp_path_factory.mktemp("plan_check") / "plan_check")
+    cmd = [cxx, "-std=c++17", "-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=all",
+           "-I", os.path.join(ROOT, "include"), "-I", CSRC,
+           os.path.join(ROOT, "tests", "plan_check.cpp"), os.path.join(CSRC, "plan.cpp"), "-o", exe]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+    return exe
+
+
+def _run(exe, units, k, plan_mode, precision, batch, h, w, c, classes, storage_mode):
+    lines = ["%d %d %d %d %d %d %d %d %d %d" % (k, plan_mode, precision, batch, h, w, c, classes, storage_mode, len(units))]
+    for u in units:
+        lines.append("%d %d %d %d %d %d %d %d %d" % (u.kind, u.cin, u.cout, u.ksize, u.stride, u.pad, u.has_bn, u.has_relu,
+                                                    u.has_bias))
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=1")
+    r = subprocess.run([exe], input="\n".join(lines) + "\n", capture_output=True, text=True, env=env)
+    assert r.returncode == 0 and r.stdout.startswith("ok "), (r.stdout + r.stderr)[-2000:]
+    _, arena, saved, launches = r.stdout.split()
+    return int(arena), int(saved), int(launches)
+
+
+@pytest.mark.parametrize("index", [1, 2, 3, 4, 5, 6])
+def test_benchmark_networks_plan_validly(checker, index):
+    wl = W.config(index)
+    n = len(wl.units)
+    ks = sorted({1, 2, wl.k_segments, min(n, wl.k_segments + 3), n})
+    seen = {}
+    for k in ks:
+        for plan_mode in (0, 1):
+            for storage_mode in (0, 1):
+                arena, saved, launches = _run(checker, wl.units, k, plan_mode, wl.precision, wl.batch, wl.height, wl.width,
+                                              wl.channels, wl.classes, storage_mode)
+                assert 0 < saved <= arena
+                seen[(k, plan_mode, storage_mode)] = (arena, saved)
+    for k in ks:
+        for plan_mode in (0, 1):
+            assert seen[(k, plan_mode, 1)][1] <= seen[(k, plan_mode, 0)][1]  # keeping Z only never keeps more
+    # the byte-aware plan never keeps more than the equal-count plan
+    for k in ks:
+        assert seen[(k, 1, 0)][1] <= seen[(k, 0, 0)][1]
+
+
+def test_small_odd_networks_plan_validly(checker):
+    nets = [
+        [W.conv(3, 5), W.conv(5, 7, stride=2), W.maxpool(), W.conv(7, 6, ksize=1), W.gap_linear_ce(6, 3)],
+        [W.conv(3, 8, bn=False), W.maxpool(), W.conv(8, 8, bn=True, relu=False, bias=True), W.maxpool(), W.flatten_linear_ce(8, 4)],
+        [W.conv(3, 8), W.basic_block(8, 16, 2), W.basic_block(16, 16), W.bottleneck(16, 32, 2), W.gap_linear_ce(32, 5)],
+    ]
+    sizes = [(3, 13, 10), (2, 8, 8), (4, 12, 12)]
+    classes = [3, 4, 5]
+    for units, (b, h, w), cl in zip(nets, sizes, classes):
+        for k in range(1, len(units) + 1):
+            for storage_mode in (0, 1):
+                for precision in (W.FP32, W.BF16):
+                    _run(checker, units, k, k % 2, precision, b, h, w, 3, cl, storage_mode)
