@@ -178,6 +178,9 @@ def main():
     ap.add_argument("--survey-steps", type=int, default=5, help="untimed steps with every kernel class event-timed")
     ap.add_argument("--timed-every", type=int, default=4,
                     help="steps of the timed region whose dominant-class launches carry events: every n-th")
+    ap.add_argument("--plan-mode", type=int, default=None,
+                    help="override the workload's way of choosing segment boundaries: 0 equal unit count, 1 least peak "
+                         "of saved bytes, 2 least recomputation within that peak or within the budget")
     ap.add_argument("--storage-mode", type=int, default=0,
                     help="0: keep Z and A of every conv-BN-ReLU (default); 1: keep Z only, rebuild A in backward; -1: 1 only if 0 does not fit the budget")
     ap.add_argument("--path", choices=("train", "dataflow"), default="train",
@@ -202,7 +205,8 @@ def main():
 
     wl = W.config(args.config, batch=args.batch)
     k = args.k if args.k is not None else wl.k_segments
-    tr = SeqTrainer.from_workload(wl, k_segments=k, storage_mode=args.storage_mode)
+    plan_mode = wl.plan_mode if args.plan_mode is None else args.plan_mode
+    tr = SeqTrainer.from_workload(wl, k_segments=k, storage_mode=args.storage_mode, plan_mode=plan_mode)
     p, x, y = W.make_batch(wl)
     tr.set_params(p)
     xd, yd = torch.from_numpy(x).cuda(), torch.from_numpy(y).cuda()
@@ -296,7 +300,7 @@ def main():
         "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": DTYPE_NAME[wl.precision], "data": "synthetic",
         "config": {"workload": wl.name, "batch": wl.batch, "k_segments": tr.k_segments, "storage_mode": tr.storage_mode, "image": "%dx%dx%d NHWC" % (wl.height, wl.width, wl.channels),
-                   "boundaries": tr.boundaries, "plan_mode": wl.plan_mode, "momentum": wl.momentum},
+                   "boundaries": tr.boundaries, "plan_mode": plan_mode, "momentum": wl.momentum},
         "loss": r["loss"], "peak_saved_bytes": r["peak_saved_bytes"], "peak_arena_bytes": r["peak_arena_bytes"],
         "activation_budget_bytes": wl.budget_bytes, "launches_per_step": tr.n_launches,
         "replay_launches_per_step": tr.n_replay_launches,

@@ -73,7 +73,10 @@ typedef struct {
   const int32_t* boundaries;       /* NULL: the planner chooses; else k-1 ascending unit indices,
                                       segment j starts at unit boundaries[j-1]                    */
   int32_t plan_mode;               /* 0 = equal unit count (remainder joins the last segment),
-                                      1 = minimise peak saved bytes over contiguous partitions    */
+                                      1 = minimise peak saved bytes over contiguous partitions,
+                                      2 = least recomputation (the last segment is not replayed)
+                                          among the partitions within the minimum peak of mode 1,
+                                          or within activation_budget_bytes when that is set       */
   int32_t precision;               /* optorch_precision_t                                         */
   int32_t batch, height, width, channels, num_classes;
   uint64_t activation_budget_bytes; /* 0 = unlimited; create fails with OPTORCH_E_BUDGET if the

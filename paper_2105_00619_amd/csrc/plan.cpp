@@ -544,7 +544,7 @@ bool choose_segments(Plan& p) {
     p.seg_begin.push_back(nu);
     return true;
   }
-  if (p.cfg.plan_mode != 1) { p.error = "plan_mode must be 0 or 1"; return false; }
+  if (p.cfg.plan_mode != 1 && p.cfg.plan_mode != 2) { p.error = "plan_mode must be 0, 1 or 2"; return false; }
   // min-peak: per-unit byte model from the all-stored schedule, then the smallest threshold T for which a
   // partition into k segments exists with  sum_{i<=j} checkpoint_i + saved_j <= T  for every j.
   Plan all = p;
@@ -587,6 +587,80 @@ bool choose_segments(Plan& p) {
   }
   if (!feasible(lo, &best)) { p.error = "internal: min-peak planner found no partition"; return false; }
   p.seg_begin = best;
+  if (p.cfg.plan_mode == 1) return true;
+
+  // plan_mode 2: least recomputation.  The last segment is never replayed, so among the partitions whose modelled
+  // peak stays within a threshold the one with the cheapest replay (the forward pass of all segments but the last,
+  // from a rough per-unit time estimate) is taken.  The threshold is the minimum peak found above; with a budget it
+  // starts at the budget instead and is lowered until the schedule built for the partition fits the budget.
+  std::vector<double> cost(nu, 0.0), cpre(nu + 1, 0.0);
+  {
+    const double rate = p.cfg.precision == OPTORCH_FP32 ? 9e13 : 4.5e14, bw = 4e12, launch = 4e-6, e = (double)p.esize;
+    for (const FOp& f : p.fops) {
+      if (f.unit < 0) continue;
+      const double in_px = (double)f.N * f.H * f.W, out_px = (double)f.N * f.P * f.Q;
+      double t = launch;
+      if (f.kind == F_CONV) {
+        const double w = (double)f.K * f.R * f.S * f.C;
+        t += 2.0 * out_px * w / rate + e * (in_px * f.C + out_px * f.K + w) / bw;
+      } else if (f.kind == F_BN_APPLY) {
+        t += e * out_px * f.C * (f.skip >= 0 ? 3 : 2) / bw;
+      } else if (f.kind == F_POOL) {
+        t += e * in_px * f.C * 1.25 / bw;
+      }
+      cost[f.unit] += t;
+    }
+    for (int u = 0; u < nu; ++u) cpre[u + 1] = cpre[u] + cost[u];
+  }
+  struct St { uint64_t ck; double cost; int from_s, from_i; };
+  auto cheapest = [&](uint64_t T, std::vector<int>* cuts) {
+    // per (segments used, units covered): the states no other state beats in both checkpoint bytes and replay cost
+    std::vector<std::vector<std::vector<St>>> S(k + 1, std::vector<std::vector<St>>(nu + 1));
+    S[0][0].push_back(St{0, 0.0, -1, -1});
+    for (int j = 1; j <= k; ++j)
+      for (int e = j; e <= nu - (k - j); ++e) {
+        if (j == k && e != nu) continue;
+        std::vector<St> cand;
+        for (int s0 = j - 1; s0 < e; ++s0)
+          for (size_t i = 0; i < S[j - 1][s0].size(); ++i) {
+            const St& st = S[j - 1][s0][i];
+            const uint64_t c = st.ck + ck[s0];
+            if (c + (pre[e] - pre[s0]) > T) continue;
+            cand.push_back(St{c, st.cost + (e == nu ? 0.0 : cpre[e] - cpre[s0]), s0, (int)i});
+          }
+        std::sort(cand.begin(), cand.end(), [](const St& a, const St& b) { return a.ck != b.ck ? a.ck < b.ck : a.cost < b.cost; });
+        double least = 1e300;
+        for (const St& c : cand)
+          if (c.cost < least) { S[j][e].push_back(c); least = c.cost; }
+      }
+    if (S[k][nu].empty()) return false;
+    size_t bi = 0;
+    for (size_t i = 1; i < S[k][nu].size(); ++i)
+      if (S[k][nu][i].cost < S[k][nu][bi].cost) bi = i;
+    cuts->assign(k + 1, 0);
+    int e = nu; size_t idx = bi;
+    for (int j = k; j >= 1; --j) {
+      (*cuts)[j] = e;
+      const St& st = S[j][e][idx];
+      e = st.from_s; idx = (size_t)st.from_i;
+    }
+    return true;
+  };
+  const uint64_t budget = p.cfg.activation_budget_bytes;
+  uint64_t T = budget > lo ? budget : lo;
+  for (int attempt = 0; attempt < 24; ++attempt) {
+    std::vector<int> cuts;
+    if (!cheapest(T, &cuts)) break;
+    if (!budget) { p.seg_begin = cuts; return true; }
+    Plan trial = p;
+    trial.cfg.boundaries = nullptr;
+    trial.seg_begin = cuts;
+    if (!build_schedule(trial)) { p.error = trial.error; return false; }
+    if (trial.arena_bytes <= budget) { p.seg_begin = cuts; return true; }
+    if (T == lo) break;
+    T = std::max<uint64_t>(lo, T - T / 16);
+  }
+  p.seg_begin = best;  // nothing cheaper fits: the minimum-peak partition
   return true;
 }
 

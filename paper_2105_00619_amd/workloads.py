@@ -140,7 +140,8 @@ class Workload:
     loss_scale_init: float
     pixels: str  # "uniform" or "gauss"
     budget_bytes: int = 0
-    plan_mode: int = 0
+    plan_mode: int = 0  # how segment boundaries are chosen: 0 equal unit count, 1 least peak of saved bytes, 2 least
+    #                     recomputation within that peak (or within budget_bytes); the benchmark networks use 2
     seed: int = MASTER_SEED
 
 
@@ -151,19 +152,19 @@ def config(index: int, batch: int | None = None, size: int | None = None) -> Wor
     if index == 1:
         w = Workload("tiny_cnn_fp32_k2", tuple(tiny_cnn(10)), 8, 32, 32, 3, 10, FP32, 2, 0.0, 1.0, "uniform")
     elif index == 2:
-        w = Workload("vgg11_bn_fp32_k4", tuple(vgg11_bn(10)), 128, 32, 32, 3, 10, FP32, 4, 0.0, 1.0, "gauss")
+        w = Workload("vgg11_bn_fp32_k4", tuple(vgg11_bn(10)), 128, 32, 32, 3, 10, FP32, 4, 0.0, 1.0, "gauss", plan_mode=2)
     elif index == 3:
         w = Workload("resnet18_bf16_k4", tuple(resnet_basic([2, 2, 2, 2], 100)), 256, 32, 32, 3, 100,
-                     BF16, 4, 0.9, 1.0, "gauss")
+                     BF16, 4, 0.9, 1.0, "gauss", plan_mode=2)
     elif index == 4:
         w = Workload("resnet50_fp16_k8", tuple(resnet_bottleneck([3, 4, 6, 3], 100)), 512, 32, 32, 3, 100,
-                     FP16, 8, 0.0, 65536.0, "gauss")
+                     FP16, 8, 0.0, 65536.0, "gauss", plan_mode=2)
     elif index == 5:
         w = Workload("resnet152_bf16_k7", tuple(resnet_bottleneck([3, 8, 36, 3], 100)), 4096, 32, 32, 3, 100,
-                     BF16, 7, 0.0, 1.0, "gauss", budget_bytes=32 << 30, plan_mode=1)
+                     BF16, 7, 0.0, 1.0, "gauss", budget_bytes=32 << 30, plan_mode=2)
     elif index == 6:
         w = Workload("resnet18_fp32_k4_512px", tuple(resnet_basic([2, 2, 2, 2], 10)), 16, 512, 512, 3, 10,
-                     FP32, 4, 0.0, 1.0, "gauss")
+                     FP32, 4, 0.0, 1.0, "gauss", plan_mode=2)
     else:
         raise ValueError("config index must be 1..6")
     if batch is not None:

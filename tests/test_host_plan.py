@@ -138,7 +138,7 @@ def test_pool_is_computed_by_the_apply_kernel_unless_it_opens_a_segment():
     # front of it (100 launches as separate kernels, 95 fused).  Equal-count k = 4 puts boundaries at units 3, 6, 9, all
     # three of them pools: those open a segment, are replayed from its kept input and stay kernels of their own.
     assert _plan(2, k_segments=1).n_launches == 95
-    p = _plan(2, k_segments=4)
+    p = _plan(2, k_segments=4, plan_mode=0)
     assert p.boundaries == [3, 6, 9] and (p.n_launches, p.n_replay_launches) == (111, 13)
     # boundaries behind the pools instead: every pool is fused again, in the first pass and in the replay
     q = _plan(2, k_segments=4, boundaries=[4, 7, 10])
@@ -146,7 +146,7 @@ def test_pool_is_computed_by_the_apply_kernel_unless_it_opens_a_segment():
 
 
 def test_peak_shrinks_with_segments_and_plan_is_reproducible():
-    p1, p4, p4b = _plan(2, k_segments=1), _plan(2, k_segments=4), _plan(2, k_segments=4)
+    p1, p4, p4b = _plan(2, k_segments=1), _plan(2, k_segments=4, plan_mode=0), _plan(2, k_segments=4, plan_mode=0)
     assert p4.boundaries == [3, 6, 9] == p4b.boundaries
     assert p4.planned_peak_saved_bytes < 0.6 * p1.planned_peak_saved_bytes
     assert (p4.act_arena_bytes, p4.planned_peak_saved_bytes) == (p4b.act_arena_bytes, p4b.planned_peak_saved_bytes)
@@ -155,6 +155,19 @@ def test_peak_shrinks_with_segments_and_plan_is_reproducible():
     # the byte-aware plan is never worse than the equal-count plan
     pm = _plan(2, k_segments=4, plan_mode=1)
     assert pm.planned_peak_saved_bytes <= p4.planned_peak_saved_bytes
+    # least recomputation within the least peak: the last segment (never replayed) takes every unit it can, so the
+    # replay is shorter than under either other mode and nothing more is kept
+    pt = _plan(2, k_segments=4, plan_mode=2)
+    assert pt.boundaries == [2, 4, 5] == _plan(2).boundaries  # the benchmark configuration's own mode
+    assert pt.planned_peak_saved_bytes <= pm.planned_peak_saved_bytes
+    assert pt.n_replay_launches < min(pm.n_replay_launches, p4.n_replay_launches)
+    for idx in (3, 4, 6):
+        a, b, c = _plan(idx, plan_mode=0), _plan(idx, plan_mode=1), _plan(idx, plan_mode=2)
+        assert c.planned_peak_saved_bytes <= a.planned_peak_saved_bytes
+        assert c.n_replay_launches <= min(a.n_replay_launches, b.n_replay_launches)
+    # under a budget the same mode spends the budget on a longer last segment
+    t5, m5 = _plan(5, plan_mode=2), _plan(5, plan_mode=1)
+    assert m5.act_arena_bytes < t5.act_arena_bytes <= 32 << 30 and t5.n_replay_launches < m5.n_replay_launches
     # 16-bit storage halves the activation bytes of the same plan (BN vectors and the fp32 head aside)
     ph = _plan(2, k_segments=1, precision=W.BF16)
     assert 0.49 < ph.planned_peak_saved_bytes / p1.planned_peak_saved_bytes < 0.51
@@ -173,7 +186,7 @@ def test_min_peak_plan_checkpoints_at_the_narrow_layer():
 
 def test_config5_budget_needs_the_byte_aware_plan():
     w = W.config(5)
-    ok = SeqPlan.from_workload(w)  # min-peak plan, 32 GiB budget
+    ok = SeqPlan.from_workload(w, plan_mode=1)  # min-peak plan, 32 GiB budget
     assert ok.act_arena_bytes <= 32 << 30
     with pytest.raises(OptorchError) as e:
         SeqPlan.from_workload(w, plan_mode=0)  # equal count does not fit
