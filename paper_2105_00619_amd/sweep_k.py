@@ -1,6 +1,6 @@
 """Step time and activation memory as a function of the number of segments k (the method's trade-off).
 
-    python3 -m paper_2105_00619_amd.sweep_k --config 2 [--plan-mode 0|1] [--steps 20]
+    python3 -m paper_2105_00619_amd.sweep_k --config 2 [--plan-mode 0|1|2] [--steps 20]
 
 Prints one line per k: ms per step, planned peak of saved activations, arena high-water mark, and both relative
 to k = 1 (all activations stored, no recomputation).
@@ -12,7 +12,7 @@ import time
 def main() -> None:
     ap = argparse.ArgumentParser()
     ap.add_argument("--config", type=int, default=2)
-    ap.add_argument("--plan-mode", type=int, default=None, help="0 equal count, 1 min peak bytes (default: the config's)")
+    ap.add_argument("--plan-mode", type=int, default=None, help="0 equal count, 1 least peak bytes, 2 least recomputation within that peak (default: the config's)")
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--batch", type=int, default=None)
