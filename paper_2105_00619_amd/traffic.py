@@ -49,19 +49,22 @@ DATAFLOW_KERNELS = {
 }
 
 
-DATAFLOW_SOURCES = ("k_dataflow.hip", "dataflow.cpp", "dev_common.h", "launch.h", "kernels.h")
+DATAFLOW_ONLY = ("k_dataflow.hip", "dataflow.cpp")          # sources of the data-flow kernels alone
+SHARED = ("dev_common.h", "launch.h")                         # device helpers both kinds of kernels are built from
 
 
 def source_hash(workload: str = "") -> str:
-    """Hash of the sources a workload's kernels are built from: the data-flow files for the data-flow benchmark, all
-    the others (and the shared headers) for a training workload."""
+    """Hash of the sources a workload's kernels are built from: the data-flow files and the shared device helpers for
+    the data-flow benchmark; everything but the data-flow files for a training workload."""
     dataflow = workload.startswith("dataflow")
     h = hashlib.sha1()
     for f in sorted(glob.glob(os.path.join(HERE, "csrc", "*"))):
         name = os.path.basename(f)
         if not name.endswith((".hip", ".h", ".cpp")):
             continue
-        if dataflow != (name in DATAFLOW_SOURCES) and name not in ("dev_common.h", "launch.h", "kernels.h"):
+        if dataflow and name not in DATAFLOW_ONLY + SHARED:
+            continue
+        if not dataflow and name in DATAFLOW_ONLY:
             continue
         h.update(name.encode())
         h.update(open(f, "rb").read())
