@@ -319,6 +319,11 @@ void run_op(const Ctx& c, const SOp& s) {
                       f.gap, f.feat_dim, f.classes, c.g32(f.w_off), c.g32(f.b_off), (float*)c.at(s.out[1]), c.at(s.out[0]));
       break;
     case S_BN_BWD:
+      if (s.variant == 1) {  // in[0] is the gradient of the max-pool behind the activation
+        launch_bn_bwd_pool(st, dt, c.at(s.in[0]), c.at(s.in[1]), (const float*)c.at(s.in[2]), f.N, f.P, f.Q, f.C, f.relu,
+                           f.red_blocks, (float*)c.at(s.out[2]), c.g32(f.gamma_off), c.g32(f.beta_off), c.at(s.out[0]));
+        break;
+      }
       launch_bn_bwd(st, dt, c.at(s.in[0]), c.at(s.in[1]), c.at(s.in[3]), (const float*)c.at(s.in[2]),
                     (int64_t)f.N * f.P * f.Q, f.C, f.relu, f.red_blocks, (float*)c.at(s.out[2]), c.g32(f.gamma_off),
                     c.g32(f.beta_off), c.at(s.out[0]), c.at(s.out[1]));
@@ -386,7 +391,10 @@ void work_of(const optorch_seq_t* h, const SOp& s, double* flops, double* bytes)
       if (s.out[1] >= 0) *bytes = e * out_px * f.C * (1.0 + (s.out[0] >= 0 ? 1.0 : 0.0) + 0.25);  // z, [a], pooled
       else *bytes = e * out_px * f.C * (s.in[2] >= 0 ? 3 : 2);
       break;
-    case S_BN_BWD: *bytes = e * out_px * f.C * (2 + (s.in[3] >= 0 ? 1 : 0) + 3 + (s.in[3] >= 0 ? 1 : 0) + (s.out[1] >= 0 ? 1 : 0)); break;
+    case S_BN_BWD:
+      if (s.variant == 1) { *bytes = e * out_px * f.C * (2 * 1.25 + 1); break; }  // twice (z, pooled gradient), dz
+      *bytes = e * out_px * f.C * (2 + (s.in[3] >= 0 ? 1 : 0) + 3 + (s.in[3] >= 0 ? 1 : 0) + (s.out[1] >= 0 ? 1 : 0));
+      break;
     case S_POOL_FWD: *bytes = e * (in_px + out_px) * f.C; break;
     case S_POOL_BWD: *bytes = e * (2 * in_px + out_px) * f.C; break;
     case S_RELU_BWD: *bytes = e * 3 * out_px * f.K; break;

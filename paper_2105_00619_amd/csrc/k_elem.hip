@@ -403,6 +403,139 @@ __global__ void __launch_bounds__(256) bn_bwd_apply_kernel(const T* __restrict__
   }
 }
 
+// ---- BatchNorm(+ReLU) backward through the 2x2 max-pool behind it ---------------------------------------------
+// The pool's backward, the gradient it would write (dA, full resolution) and the activation it would read are all
+// skipped: a thread owns one pooled position of V channels, reads the four z of its window and the pooled gradient,
+// rebuilds the four activations as the forward kernel computed them (rounded to the storage type), finds the first
+// maximum in scan order, and so knows dA at its four positions.  Two kernels with the same tiling: the per-channel
+// sums (as colreduce: row blocks of pooled positions, partial [nblk][2][C]) and, after the finishing kernel, dz.
+struct PoolBwdArgs {
+  int64_t rows;  // pooled positions N * P * Q
+  int C, relu, rows_per_block, W, Q, PQ, HW;  // full-resolution width, pooled width, pooled / full positions per image
+};
+
+template <class T, int V>
+__device__ __forceinline__ void pool_window_grad(const T* __restrict__ z, const T* __restrict__ dy, int64_t r, int c0,
+                                                 const PoolBwdArgs& g, const float (&scale)[V], const float (&shift)[V],
+                                                 float (&vz)[4][V], float (&dyv)[4][V], int64_t (&off)[4]) {
+  const int64_t n = r / g.PQ;
+  const int rem = (int)(r - n * g.PQ);
+  const int p = rem / g.Q, q = rem - p * g.Q;
+  off[0] = ((n * g.HW + (int64_t)(2 * p) * g.W + 2 * q)) * g.C + c0;
+  off[1] = off[0] + g.C; off[2] = off[0] + (int64_t)g.W * g.C; off[3] = off[2] + g.C;
+  float gy[V];
+#pragma unroll
+  for (int u = 0; u < 4; ++u) load_f32<T, V>(z + off[u], vz[u]);
+  load_f32<T, V>(dy + r * g.C + c0, gy);
+#pragma unroll
+  for (int k = 0; k < V; ++k) {
+    float y[4], m = 0.f;
+    int arg = 0;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      y[u] = bn_affine(vz[u][k], scale[k], shift[k]);
+      const float a = to_f32(from_f32<T>(g.relu ? fmaxf(y[u], 0.f) : y[u]));
+      if (u == 0 || a > m) { m = a; arg = u; }
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const bool on = !g.relu || y[u] > 0.f;
+      dyv[u][k] = (arg == u && on) ? gy[k] : 0.f;
+    }
+  }
+}
+
+template <class T, int V>
+__global__ void __launch_bounds__(256) bn_bwd_pool_reduce_kernel(const T* __restrict__ dy, const T* __restrict__ z,
+                                                                 const float* __restrict__ stats, float* __restrict__ partial,
+                                                                 PoolBwdArgs g) {
+  extern __shared__ float smem[];  // [2][TY][TX*V]
+  const int CG = g.C / V;
+  const int TX = CG < 256 ? CG : 256;
+  const int TY = 256 / TX;
+  const int tx = threadIdx.x % TX, ty = threadIdx.x / TX;
+  const int cg = blockIdx.y * TX + tx;
+  const bool active = cg < CG && ty < TY;
+  const int c0 = cg * V;
+  float s0[V], s1[V];
+#pragma unroll
+  for (int i = 0; i < V; ++i) s0[i] = s1[i] = 0.f;
+  if (active) {
+    float mean[V], rstd[V], scale[V], shift[V];
+#pragma unroll
+    for (int i = 0; i < V; ++i) {
+      mean[i] = stats[c0 + i]; rstd[i] = stats[g.C + c0 + i];
+      scale[i] = stats[2 * g.C + c0 + i]; shift[i] = stats[3 * g.C + c0 + i];
+    }
+    const int64_t r0 = (int64_t)blockIdx.x * g.rows_per_block;
+    const int64_t r1 = r0 + g.rows_per_block < g.rows ? r0 + g.rows_per_block : g.rows;
+    for (int64_t r = r0 + ty; r < r1; r += TY) {
+      float vz[4][V], dyv[4][V];
+      int64_t off[4];
+      pool_window_grad<T, V>(z, dy, r, c0, g, scale, shift, vz, dyv, off);
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int i = 0; i < V; ++i) {
+          const float xh = (vz[u][i] - mean[i]) * rstd[i];
+          s0[i] += dyv[u][i]; s1[i] = __fmaf_rn(dyv[u][i], xh, s1[i]);
+        }
+    }
+  }
+  const int W = TX * V;
+  if (active) {
+#pragma unroll
+    for (int i = 0; i < V; ++i) { smem[ty * W + tx * V + i] = s0[i]; smem[(TY + ty) * W + tx * V + i] = s1[i]; }
+  }
+  __syncthreads();
+  if (active && ty == 0) {
+#pragma unroll
+    for (int i = 0; i < V; ++i) {
+      float t0 = 0.f, t1 = 0.f;
+      for (int y = 0; y < TY; ++y) { t0 += smem[y * W + tx * V + i]; t1 += smem[(TY + y) * W + tx * V + i]; }
+      partial[((int64_t)blockIdx.x * 2 + 0) * g.C + c0 + i] = t0;
+      partial[((int64_t)blockIdx.x * 2 + 1) * g.C + c0 + i] = t1;
+    }
+  }
+}
+
+template <class T, int V>
+__global__ void __launch_bounds__(256) bn_bwd_pool_apply_kernel(const T* __restrict__ dy, const T* __restrict__ z,
+                                                                const float* __restrict__ stats, const float* __restrict__ coef,
+                                                                T* __restrict__ dz, PoolBwdArgs g) {
+  const int CG = g.C / V;
+  const int TX = CG < 256 ? CG : 256;
+  const int TY = 256 / TX;
+  const int tx = threadIdx.x % TX, ty = threadIdx.x / TX;
+  const int cg = blockIdx.y * TX + tx;
+  if (cg >= CG || ty >= TY) return;
+  const int c0 = cg * V;
+  float mean[V], rstd[V], scale[V], shift[V], cb[V], cg2[V];
+#pragma unroll
+  for (int k = 0; k < V; ++k) {
+    const int c = c0 + k;
+    mean[k] = stats[c]; rstd[k] = stats[g.C + c]; scale[k] = stats[2 * g.C + c]; shift[k] = stats[3 * g.C + c];
+    cb[k] = coef[c]; cg2[k] = coef[g.C + c];
+  }
+  const int64_t r0 = (int64_t)blockIdx.x * g.rows_per_block;
+  const int64_t r1 = r0 + g.rows_per_block < g.rows ? r0 + g.rows_per_block : g.rows;
+  for (int64_t r = r0 + ty; r < r1; r += TY) {
+    float vz[4][V], dyv[4][V];
+    int64_t off[4];
+    pool_window_grad<T, V>(z, dy, r, c0, g, scale, shift, vz, dyv, off);
+    float rz[4][V];
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+      for (int k = 0; k < V; ++k) {
+        const float xh = (vz[u][k] - mean[k]) * rstd[k];
+        rz[u][k] = scale[k] * (dyv[u][k] - cb[k] - xh * cg2[k]);
+      }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) store_f32<T, V>(dz + off[u], rz[u]);
+  }
+}
+
 template <class T, int V>
 __global__ void __launch_bounds__(256) relu_bwd_kernel(const T* __restrict__ da, const T* __restrict__ a,
                                                        T* __restrict__ dz, int64_t groups) {
@@ -585,6 +718,29 @@ void launch_bn_bwd(hipStream_t st, int dt, const void* da, const void* z, const 
   DISPATCH_TV(dt, C, CALL);
 #undef CALL
 #undef APPLY
+}
+
+// BatchNorm(+ReLU) backward where dy is the gradient of the 2x2 max-pool behind the activation: z [N][H][W][C] (H, W
+// even), dy [N][H/2][W/2][C]; ws as for launch_bn_bwd
+void launch_bn_bwd_pool(hipStream_t st, int dt, const void* dy, const void* z, const float* stats, int N, int H, int W, int C,
+                        int relu, int nblk, float* ws, float* dgamma, float* dbeta, void* dz) {
+  PoolBwdArgs g{};
+  g.rows = (int64_t)N * (H / 2) * (W / 2); g.C = C; g.relu = relu; g.W = W; g.Q = W / 2; g.PQ = (H / 2) * (W / 2); g.HW = H * W;
+  float* coef = ws + (int64_t)nblk * 2 * C;
+#define CALL(T, V)                                                                                                       \
+  { const int CG = C / V, TX = CG < 256 ? CG : 256, TY = 256 / TX, ytiles = ceil_div(CG, TX);                              \
+    PoolBwdArgs gr = g; gr.rows_per_block = ceil_div(g.rows, nblk);                                                        \
+    OSEQ_LAUNCH((bn_bwd_pool_reduce_kernel<T, V>), dim3(nblk, ytiles), dim3(256), (size_t)2 * TY * TX * V * sizeof(float), \
+                st, (const T*)dy, (const T*)z, stats, ws, gr);                                                             \
+    OSEQ_LAUNCH(bn_bwd_finalize_kernel, dim3(ceil_div(C, 4)), dim3(256), 0, st, ws, nblk, C, (double)N * H * W, dgamma,    \
+                dbeta, coef);                                                                                              \
+    PoolBwdArgs ga = g; int per = 2;                                                                                       \
+    while (per > 1 && (int64_t)ceil_div(g.rows, (int64_t)TY * per) * ytiles < 1024) per /= 2;                              \
+    ga.rows_per_block = TY * per;                                                                                          \
+    OSEQ_LAUNCH((bn_bwd_pool_apply_kernel<T, V>), dim3(ceil_div(g.rows, ga.rows_per_block), ytiles), dim3(256), 0, st,     \
+                (const T*)dy, (const T*)z, stats, coef, (T*)dz, ga); }
+  DISPATCH_TV(dt, C, CALL);
+#undef CALL
 }
 
 void launch_relu_bwd(hipStream_t st, int dt, const void* da, const void* a, void* dz, int64_t rows, int C) {

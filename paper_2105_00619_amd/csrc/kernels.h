@@ -30,6 +30,10 @@ void launch_bn_apply_pool(hipStream_t st, int dt, const void* z, const float* st
                           int C, int relu);
 void launch_bn_bwd(hipStream_t st, int dt, const void* da, const void* z, const void* aout, const float* stats, int64_t rows,
                    int C, int relu, int nblk, float* ws, float* dgamma, float* dbeta, void* dz, void* dskip);
+// the same where dy is the gradient of the 2x2 max-pool that follows the activation ([N][H/2][W/2][C]; H, W even): the
+// pool's own backward pass is not run
+void launch_bn_bwd_pool(hipStream_t st, int dt, const void* dy, const void* z, const float* stats, int N, int H, int W, int C,
+                        int relu, int nblk, float* ws, float* dgamma, float* dbeta, void* dz);
 void launch_relu_bwd(hipStream_t st, int dt, const void* da, const void* a, void* dz, int64_t rows, int C);
 void launch_bias_grad(hipStream_t st, int dt, const void* dz, int64_t rows, int C, int nblk, float* partial, float* dbias);
 void launch_maxpool_fwd(hipStream_t st, int dt, const void* x, void* y, int N, int H, int W, int C);

@@ -233,11 +233,30 @@ struct Scheduler {
   std::vector<int> stat_ws;    // [LTensor of a conv output] -> Inst id of the channel sums its forward kernel wrote
   std::vector<int> bn_apply_of;  // [LTensor] -> the F_BN_APPLY operation that produces it, or -1
   std::vector<char> rebuilt;     // [LTensor] backward has already rebuilt it (storage mode 1)
+  std::vector<int> readers;      // [LTensor] -> number of forward operations that read it
+  std::vector<int> via_pool;     // [LTensor] -> Inst id of the gradient of the max-pool output behind it, when the
+                                 //              pool's backward is left to the BatchNorm backward in front of it
   explicit Scheduler(Plan& pl)
       : p(pl), cur(pl.tensors.size(), -1), grad(pl.tensors.size(), -1), stat_ws(pl.tensors.size(), -1),
-        bn_apply_of(pl.tensors.size(), -1), rebuilt(pl.tensors.size(), 0) {
-    for (size_t fi = 0; fi < pl.fops.size(); ++fi)
-      if (pl.fops[fi].kind == F_BN_APPLY) bn_apply_of[pl.fops[fi].out] = (int)fi;
+        bn_apply_of(pl.tensors.size(), -1), rebuilt(pl.tensors.size(), 0), readers(pl.tensors.size(), 0),
+        via_pool(pl.tensors.size(), -1) {
+    for (size_t fi = 0; fi < pl.fops.size(); ++fi) {
+      const FOp& f = pl.fops[fi];
+      if (f.kind == F_BN_APPLY) bn_apply_of[f.out] = (int)fi;
+      if (f.x >= 0) ++readers[f.x];
+      if (f.skip >= 0) ++readers[f.skip];
+    }
+  }
+
+  // Is forward operation fi a 2x2 max-pool whose backward the BatchNorm backward in front of it does as well?  The
+  // activation between them must be read by nothing else; the rule looks at the network only (never at the segments),
+  // so the sums of that BatchNorm backward are added in the same order for every k.
+  bool pool_bwd_fused(int fi) const {
+    if (fi < 1) return false;
+    const FOp& pool = p.fops[fi];
+    const FOp& ap = p.fops[fi - 1];
+    if (pool.kind != F_POOL || ap.kind != F_BN_APPLY || pool.x != ap.out || ap.skip >= 0) return false;
+    return ap.P % 2 == 0 && ap.Q % 2 == 0 && readers[ap.out] == 1 && p.tensors[ap.out].needs_grad;
   }
 
   int new_inst(int logical, uint64_t bytes, bool fwd_value) {
@@ -338,10 +357,13 @@ struct Scheduler {
         return true;
       }
       case F_BN_APPLY: {
-        if (grad[f.out] < 0) { p.error = "internal: BN output has no gradient"; return false; }
+        int gin = grad[f.out], variant = 0;
+        if (gin < 0 && via_pool[f.out] >= 0) { gin = via_pool[f.out]; variant = 1; }  // through the pool behind it
+        if (gin < 0) { p.error = "internal: BN output has no gradient"; return false; }
         if (f.skip >= 0 && !f.relu) { p.error = "skip connection without ReLU is not supported"; return false; }
         SOp& s = push(S_BN_BWD, fi, PH_BWD, seg);
-        s.in[0] = grad[f.out]; s.in[1] = cur[f.x]; s.in[2] = cur[f.stats];
+        s.variant = variant;
+        s.in[0] = gin; s.in[1] = cur[f.x]; s.in[2] = cur[f.stats];
         s.in[3] = (f.skip >= 0) ? cur[f.out] : -1;
         s.out[0] = grad_inst(f.x); grad[f.x] = s.out[0];
         if (f.skip >= 0 && p.tensors[f.skip].needs_grad) {
@@ -383,6 +405,7 @@ struct Scheduler {
         if (grad[f.out] < 0) { p.error = "internal: pool output has no gradient"; return false; }
         if (!p.tensors[f.x].needs_grad) return true;
         if (grad[f.x] >= 0) { p.error = "internal: pool input already has a gradient"; return false; }
+        if (pool_bwd_fused(fi)) { via_pool[f.x] = grad[f.out]; return true; }
         const int xin = backward_input(f.x, seg);
         SOp& s = push(S_POOL_BWD, fi, PH_BWD, seg);
         s.in[0] = xin; s.in[1] = grad[f.out];

