@@ -227,3 +227,29 @@ def test_dataflow_argument_checks_need_no_gpu():
     # an empty batch is a success that launches nothing
     assert lib.optorch_encode(None, 0, 8, 4, None, None) == binding.OK
     assert lib.optorch_decode_lossless(None, None, 4, 0, 4, None, None) == binding.OK
+
+
+def test_planner_against_brute_force_on_small_networks():
+    # every partition of two small networks, planned for real: plan mode 2 must find the least peak of saved bytes (its
+    # byte model is not the schedule itself: 1 % of slack) with the least replay among the partitions that keep no
+    # more than it does; plan mode 1 only promises a peak close to the least
+    import itertools
+    nets = [
+        ([W.conv(3, 16), W.maxpool(), W.conv(16, 32), W.maxpool(), W.conv(32, 64), W.conv(64, 64), W.maxpool(),
+          W.gap_linear_ce(64, 10)], W.FP32),
+        ([W.conv(3, 16), W.basic_block(16, 16), W.basic_block(16, 32, 2), W.basic_block(32, 32), W.basic_block(32, 64, 2),
+          W.bottleneck(64, 128, 2), W.gap_linear_ce(128, 10)], W.BF16),
+    ]
+    for units, precision in nets:
+        kw = dict(batch=16, height=32, width=32, channels=3, num_classes=10, precision=precision)
+        for k in (2, 3, 4):
+            rows = []
+            for b in itertools.combinations(range(1, len(units)), k - 1):
+                p = SeqPlan(units, k_segments=k, boundaries=list(b), **kw)
+                rows.append((p.planned_peak_saved_bytes, p.n_replay_launches))
+            least = min(r[0] for r in rows)
+            m1 = SeqPlan(units, k_segments=k, plan_mode=1, **kw)
+            m2 = SeqPlan(units, k_segments=k, plan_mode=2, **kw)
+            assert m2.planned_peak_saved_bytes <= 1.01 * least
+            assert m2.n_replay_launches <= min(r[1] for r in rows if r[0] <= m2.planned_peak_saved_bytes)
+            assert m1.planned_peak_saved_bytes <= 1.15 * least
