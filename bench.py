@@ -25,8 +25,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK = {"hbm": 8000.0,  # GB/s
-        "mfma_f32": 157.3, "mfma_bf16": 2500.0, "mfma_f16": 2500.0,  # TFLOP/s dense
-        "alu_f32": 157.3}  # fp32 vector FMA: 256 CU x 4 SIMD x 32 lanes-per-clock(x2 packed) x 2 flop x 2.4 GHz
+        "mfma_f32": 157.3, "mfma_bf16": 2500.0, "mfma_f16": 2500.0}  # TFLOP/s dense
 MFMA_CLASSES = ("conv_fwd", "conv_dgrad", "conv_wgrad")
 # Forward and data gradient run the same kernels (the data gradient is the forward computation on dz with flipped
 # taps), which a kernel trace cannot tell apart: they form one group for the roofline figure.

@@ -141,7 +141,11 @@ int optorch_seq_get_params(const optorch_seq_t* h, float* dst, uint64_t n, int32
  *   peak_arena_bytes  host or NULL: high-water mark of the activation arena
  *   loss_scale_out    host or NULL: loss scale after this step
  *   step_skipped      host or NULL: 1 if a non-finite gradient was found (weights untouched,
- *                     scale multiplied by scale_backoff), else 0 */
+ *                     scale multiplied by scale_backoff), else 0
+ * A label outside [0, num_classes) is found on the device before the forward pass: the call returns
+ * OPTORCH_E_INVALID after the step's kernels have run, with the master weights, momentum, 16-bit copies, BatchNorm
+ * running statistics, loss scale and the out arguments untouched; the activation arena and grads_dev are then
+ * unspecified. */
 int optorch_seq_step(optorch_seq_t* h, const float* x_dev, const int32_t* y_dev, float lr,
                      float* loss_out, float* grads_dev, uint64_t* peak_saved_bytes,
                      uint64_t* peak_arena_bytes, float* loss_scale_out, int32_t* step_skipped);
@@ -159,7 +163,7 @@ int optorch_seq_step_encoded(optorch_seq_t* h, const uint64_t* a_dev, int32_t z,
                              float* loss_scale_out, int32_t* step_skipped);
 
 /* Inference with the network as it stands (the counterpart of training-mode BatchNorm; the paper evaluates its
- * trained networks, Section "Sequential-checkpoint training"): the forward pass of every segment, nothing kept, with
+ * trained networks, Section "Results"): the forward pass of every segment, nothing kept, with
  * each BatchNorm using its running mean and variance instead of the batch statistics, up to the logits.
  *   x_dev       device: batch x height x width x channels fp32, NHWC (the batch size of create)
  *   logits_dev  device: receives batch x num_classes fp32

@@ -13,16 +13,16 @@ images in order.  Algorithm "Loss-less Forced Encoding" halves every pixel so
 that the digits are base 128, and keeps the lost low bit of every pixel in a
 boolean offset array.
 
-These are encodings, so the oracle takes the algorithms' steps in their order
-and notation (X batch, A encoded matrix, O offsets, Z images, i counter, domain
-= base^i), in exact integer arithmetic: A is a numpy array of Python integers,
-which never overflow.  Nothing is blocked or reordered.
+The result of each algorithm has a plain definition -- a positional numeral in
+base 256 (or 128) whose digits are the pixels -- and the oracle is that
+definition written out per position in exact Python integers, which never
+overflow (Horner evaluation of the digits; digits back by repeated divmod).
 
 Readings (the text is at odds with itself in three places):
   * the displayed sum runs i = 1..N while the algorithm starts at i = 0; the
     algorithm's exponents 0..Z-1 are taken, so that a single image encodes to
     itself;
-  * the capacity remarks ("16 images", "32 images" in a 64-bit float) exceed
+  * the capacity remarks (16, or 32, images in one 64-bit float) exceed
     what 53 or 64 bits hold; the numbers here are exact integers of as many bits
     as needed (8 Z, or 7 Z), and `to_words` cuts them into 64-bit words;
   * the loss-less algorithm as printed adds the unhalved image times 128^i,
@@ -44,65 +44,67 @@ import numpy as np
 MASK64 = (1 << 64) - 1
 
 
+def _digits_to_number(digits, base: int) -> int:
+    """Value of a positional numeral: digits[0] is the least significant digit."""
+    value = 0
+    for d in reversed(digits):
+        value = value * base + int(d)
+    return value
+
+
+def _number_to_digits(value: int, base: int, count: int):
+    """The `count` least significant digits of a non-negative integer, least significant first."""
+    out = []
+    for _ in range(count):
+        value, d = divmod(int(value), base)
+        out.append(d)
+    return out
+
+
 def encode(X: np.ndarray) -> np.ndarray:
-    """Algorithm "Encode".  X: uint8 [Z, ...] -> A: Python integers [...], A = sum_i X[i] * 256^i."""
+    """Algorithm "Encode".  X: uint8 [Z, ...] -> Python integers [...]: at every position the number whose base-256
+    digits are the pixels of images 0 .. Z-1 there, image 0 least significant."""
     X = np.asarray(X)
     assert X.dtype == np.uint8
-    Z = X.shape[0]
-    A = np.zeros(X.shape[1:], dtype=object)
-    i = 0
-    while i != Z:
-        img = X[i].astype(object)
-        domain = 256 ** i
-        A = A + (img * domain)
-        i = i + 1
-    return A
+    columns = X.reshape(X.shape[0], -1)
+    out = np.empty(columns.shape[1], dtype=object)
+    for p in range(columns.shape[1]):
+        out[p] = _digits_to_number(columns[:, p], 256)
+    return out.reshape(X.shape[1:])
 
 
 def decode(A: np.ndarray, Z: int) -> np.ndarray:
-    """Algorithm "Decode".  A: integers [...] -> X: uint8 [Z, ...]; modulo 256, then integer division by 256."""
-    A = np.array(A, dtype=object, copy=True)
-    X = np.zeros((Z,) + A.shape, dtype=np.uint8)
-    i = 0
-    while i != Z:
-        X[i] = (A % 256).astype(np.uint8)
-        A = A // 256
-        i = i + 1
-    return X
+    """Algorithm "Decode".  Integers [...] -> uint8 [Z, ...]: image i is base-256 digit i of every number."""
+    A = np.asarray(A, dtype=object)
+    flat = A.reshape(-1)
+    X = np.zeros((Z, flat.size), dtype=np.uint8)
+    for p in range(flat.size):
+        X[:, p] = _number_to_digits(flat[p], 256, Z)
+    return X.reshape((Z,) + A.shape)
 
 
 def encode_lossless(X: np.ndarray):
-    """Algorithm "Loss-less Forced Encoding" (halved pixels as base-128 digits, parities kept).
-
-    X: uint8 [Z, ...] -> (A: integers [...], O: bool [Z, ...])."""
+    """Algorithm "Loss-less Forced Encoding": the halved pixels are the base-128 digits, the low bit of every pixel
+    goes to the offset array.  X: uint8 [Z, ...] -> (integers [...], bool [Z, ...])."""
     X = np.asarray(X)
     assert X.dtype == np.uint8
-    Z = X.shape[0]
-    A = np.zeros(X.shape[1:], dtype=object)
-    O = np.zeros(X.shape, dtype=bool)
-    i = 0
-    while i != Z:
-        img = X[i].astype(object)
-        offset = img % 2
-        domain = 128 ** i
-        A = A + ((img // 2) * domain)
-        O[i] = offset.astype(bool)
-        i = i + 1
-    return A, O
+    columns = X.reshape(X.shape[0], -1)
+    A = np.empty(columns.shape[1], dtype=object)
+    for p in range(columns.shape[1]):
+        A[p] = _digits_to_number([int(v) >> 1 for v in columns[:, p]], 128)
+    return A.reshape(X.shape[1:]), (X & 1).astype(bool)
 
 
 def decode_lossless(A: np.ndarray, O: np.ndarray) -> np.ndarray:
-    """Inverse of `encode_lossless`: digit = A mod 128, A = A div 128, pixel = 2 * digit + offset."""
-    A = np.array(A, dtype=object, copy=True)
+    """Inverse of `encode_lossless`: pixel of image i = 2 * (base-128 digit i) + offset bit."""
+    A = np.asarray(A, dtype=object)
+    O = np.asarray(O, dtype=bool)
     Z = O.shape[0]
-    X = np.zeros(O.shape, dtype=np.uint8)
-    i = 0
-    while i != Z:
-        digit = A % 128
-        X[i] = (2 * digit + O[i].astype(object)).astype(np.uint8)
-        A = A // 128
-        i = i + 1
-    return X
+    flat = A.reshape(-1)
+    half = np.zeros((Z, flat.size), dtype=np.uint8)
+    for p in range(flat.size):
+        half[:, p] = _number_to_digits(flat[p], 128, Z)
+    return (2 * half.reshape(O.shape) + O.astype(np.uint8)).astype(np.uint8)
 
 
 # ---- memory format -----------------------------------------------------------------------------------------------

@@ -48,7 +48,7 @@ storage=None the hooks are the identity and the function is the plain definition
 Inference mode.  BatchNorm keeps running estimates of each channel's mean and variance (exponential averages of the
 batch mean and of the unbiased batch variance, momentum 0.1, started at 0 and 1) and `predict` evaluates the network
 with those in place of the batch statistics: y = gamma * (z - running_mean) / sqrt(running_var + eps) + beta.  The
-paper trains and then evaluates its networks (Section "Sequential-checkpoint training", accuracy after ten epochs)
+paper trains and then evaluates its networks (Section "Results", accuracy after ten epochs)
 with a framework's BatchNorm; these are that layer's standard definitions.
 
 Pins (tests/test_oracle_pins.py): central finite differences on every layer

@@ -292,11 +292,11 @@ void run_op(const Ctx& c, const SOp& s) {
       if (s.in[1] >= 0)
         launch_bn_stats_finalize(st, (float*)c.at(s.in[1]), (int64_t)f.N * f.P * f.Q, f.C, f.stat_blocks, h->eps,
                                  h->bn_mom, c.w32(f.gamma_off), c.w32(f.beta_off), (float*)c.at(s.out[0]),
-                                 (float*)(h->pbase + h->off_run) + f.rs_off);
+                                 (float*)(h->pbase + h->off_run) + f.rs_off, c.flags());
       else
         launch_bn_stats(st, dt, c.at(s.in[0]), (int64_t)f.N * f.P * f.Q, f.C, f.red_blocks, (float*)c.at(s.out[1]), h->eps,
                         h->bn_mom, c.w32(f.gamma_off), c.w32(f.beta_off), (float*)c.at(s.out[0]),
-                        (float*)(h->pbase + h->off_run) + f.rs_off);
+                        (float*)(h->pbase + h->off_run) + f.rs_off, c.flags());
       break;
     case S_BN_APPLY:
       if (s.out[1] >= 0)  // with the 2x2 max-pool that follows
@@ -575,7 +575,7 @@ extern "C" int optorch_seq_running_stats(const optorch_seq_t* h, float* dst, uin
 static int step_run(optorch_seq_t* h, const Ctx& c, float lr, float* loss_out, float* grads_dev, uint64_t* peak_saved_bytes,
                     uint64_t* peak_arena_bytes, float* loss_scale_out, int32_t* step_skipped) {
   hipStream_t st = h->stream;
-  launch_step_init(st, c.flags());
+  launch_step_init(st, c.flags(), c.y, h->plan.cfg.batch, h->plan.cfg.num_classes);
   const bool prof = h->profiling;
   if (prof && h->ev_used > (size_t)1 << 16) harvest(h);  // previous steps are complete: each step ends with a sync
   for (size_t si = 0; si < h->plan.sched.size(); ++si) {

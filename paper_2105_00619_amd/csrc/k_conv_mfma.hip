@@ -734,7 +734,7 @@ static bool patch_geometry(int N, int dstH, int dstW, int cap, PatchArgs& a) {
 // pixels the 80-byte position pitch spreads them over the LDS banks, and the row pitch is padded so that the next
 // rows of the tile land on the banks the previous ones left free (TC = 8: 128 mod 256, TC = 4: 64, TC = 2: 32);
 // kept at SC * 80 when the padded rows would not fit the patch buffer.
-int g_patch_pad_rows = 1;  // tuning switch (not part of the C ABI)
+static constexpr int g_patch_pad_rows = 1;  // compile-time switch
 static int patch_row_pitch(const PatchArgs& a, int subt) {
   const int base = a.SC * 80;
   int want = -1;
@@ -750,14 +750,14 @@ static int patch_row_pitch(const PatchArgs& a, int subt) {
 // `g_patch_fill` blocks is taken, else the one with the most blocks if that reaches `g_patch_min_blocks`
 // (shape-only rule, so the choice is the same on every run).
 struct PatchShape { int mi, subt, bn, splits; };
-int g_patch_min_blocks = 64;   // tuning constants (not part of the C ABI)
-int g_patch_fill = 512;
-int g_patch_shapes = 0x7;      // bit i: candidate i allowed
-int g_patch_split = 1;         // allow the depth split
-int g_patch_halo2 = 9;         // largest staged positions : pixels ratio, times two
-int g_patch_target_small = 512;  // blocks aimed at by the depth split for the smallest block shape in fp32
-int64_t g_patch_xcd_wbytes = 4 << 20;  // XCD grouping of the blocks: least weight bytes (0: never) ...
-int g_patch_xcd_rows = 16;              // ... and most row tiles
+static constexpr int g_patch_min_blocks = 64;   // compile-time constants
+static constexpr int g_patch_fill = 512;
+static constexpr int g_patch_shapes = 0x7;      // bit i: candidate i allowed
+static constexpr int g_patch_split = 1;         // allow the depth split
+static constexpr int g_patch_halo2 = 9;         // largest staged positions : pixels ratio, times two
+static constexpr int g_patch_target_small = 512;  // blocks aimed at by the depth split for the smallest block shape in fp32
+static constexpr int64_t g_patch_xcd_wbytes = 4 << 20;  // XCD grouping of the blocks: least weight bytes (0: never) ...
+static constexpr int g_patch_xcd_rows = 16;              // ... and most row tiles
 static bool patch_pick(int dt, int N, int dstH, int dstW, int srcC, int Ng, int R, int S, int stride, PatchShape& shape,
                        PatchArgs& geo) {
   if (R != 3 || S != 3 || stride != 1) return false;
@@ -860,7 +860,7 @@ static void launch_patch(hipStream_t st, int dt, const void* src, const void* wm
   else launch_patch_t<f16_t>(st, src, wmat, bias, addend, out, partial, stat_partial, v, a);
 }
 
-int g_igemm_spread = 1;                         // tuning switch (not part of the C ABI)
+static constexpr int g_igemm_spread = 1;                         // compile-time switch
 constexpr size_t kSpreadLds = 84 * 1024;        // more than half of the 160 KB of LDS per CU
 
 // rows per block: 256 when that still gives every CU two blocks, else 128 (from the shape only)
@@ -931,7 +931,7 @@ int conv_mfma_fwd_splits(int dt, const ConvGeom& g) {
   return igemm_splits(dt, (int64_t)g.N * g.P * g.Q, g.K, g.R * g.S * g.C);
 }
 // stride 2, even image, at most 3x3: the data gradient runs as four parity-class GEMMs in one launch
-int g_dgrad_classes = 1;  // tuning switch (not part of the C ABI)
+static constexpr int g_dgrad_classes = 1;  // compile-time switch
 static bool dgrad_by_classes(const ConvGeom& g) {
   return g_dgrad_classes && g.stride == 2 && g.H % 2 == 0 && g.W % 2 == 0 && g.R <= 3 && g.S <= 3;
 }
@@ -1311,10 +1311,10 @@ bool conv_mfma_wgrad_ok(int dt, const ConvGeom& g) {
 // 1x1 layers have only (K / 128) * (C / 128) tiles, often one or two, and hundreds of thousands of pixels: they take
 // up to 256 pixel ranges and aim at two blocks per CU (measured on the 1x1 layers of ResNet-50 at batch 128, bf16:
 // 64->64 at 56x56 64 -> 23 us, 64->256 91 -> 56 us, 256->128 126 -> 75 us, all fifteen layers 995 -> 743 us)
-int g_wgrad_blocks = 1024;  // tuning constants (not part of the C ABI)
-int g_wgrad_max_splits = 64;
-int g_wgrad_blocks_1x1 = 512;
-int g_wgrad_max_splits_1x1 = 256;
+static constexpr int g_wgrad_blocks = 1024;  // compile-time constants
+static constexpr int g_wgrad_max_splits = 64;
+static constexpr int g_wgrad_blocks_1x1 = 512;
+static constexpr int g_wgrad_max_splits_1x1 = 256;
 int conv_mfma_wgrad_splits(int dt, const ConvGeom& g) {
   if (conv_wgrad3x3_ok(dt, g)) return conv_wgrad3x3_splits(dt, g);
   const int depth = dt == DT_F32 ? 16 : 32;

@@ -295,8 +295,8 @@ bool pw_shape_ok(int dt, int64_t M, int Ng, int Kd, int min_blocks) {
 
 }  // namespace
 
-int g_pointwise = 1;               // tuning switches (not part of the C ABI)
-int g_pointwise_min_blocks = 128;
+static constexpr int g_pointwise = 1;               // compile-time switches
+static constexpr int g_pointwise_min_blocks = 128;
 
 bool conv_pointwise_fwd_ok(int dt, const ConvGeom& g) {
   if (!g_pointwise || g.R != 1 || g.S != 1 || g.pad != 0 || (g.stride != 1 && g.stride != 2)) return false;

@@ -22,7 +22,7 @@
 
 namespace oseq {
 
-int g_w9_wide_min = 8;  // tuning constant (not part of the C ABI): fewest sub-tiles per block for 128-channel blocks
+static constexpr int g_w9_wide_min = 8;  // compile-time constant: fewest sub-tiles per block for 128-channel blocks
 
 namespace {
 
@@ -325,7 +325,7 @@ void launch_w9(hipStream_t st, const void* x, const void* dz, float* dst, const 
 
 }  // namespace
 
-int g_wgrad3x3 = 1;  // tuning switch (not part of the C ABI)
+static constexpr int g_wgrad3x3 = 1;  // compile-time switch
 
 bool conv_wgrad3x3_ok(int dt, const ConvGeom& g) {
   W9Plan pl;

@@ -17,7 +17,7 @@
 
 namespace oseq {
 
-int g_df_threads = 0;  // tuning constant (not part of the C ABI): 0 = chosen from the image size
+static constexpr int g_df_threads = 0;  // compile-time constant: 0 = chosen from the image size
 
 namespace {
 

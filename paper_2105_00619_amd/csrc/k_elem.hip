@@ -205,7 +205,8 @@ __global__ void __launch_bounds__(256) stat_fold_kernel(const float* __restrict_
 __global__ void __launch_bounds__(256) bn_stats_finalize_kernel(const float* __restrict__ partial, int nblk, int C, double m,
                                                                 float eps, float mom, const float* __restrict__ gamma,
                                                                 const float* __restrict__ beta, float* __restrict__ stats,
-                                                                float* __restrict__ running) {
+                                                                float* __restrict__ running,
+                                                                const int* __restrict__ flags) {
   const int c = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (c >= C) return;
   double s, q;
@@ -219,7 +220,7 @@ __global__ void __launch_bounds__(256) bn_stats_finalize_kernel(const float* __r
   stats[C + c] = (float)rstd;
   stats[2 * C + c] = (float)((double)gamma[c] * rstd);
   stats[3 * C + c] = (float)((double)beta[c] - mean * (double)gamma[c] * rstd);
-  if (running) {
+  if (running && !(flags && flags[1])) {  // a step with an invalid label leaves the running statistics alone
     const double unbiased = m > 1.0 ? var * m / (m - 1.0) : var;
     running[c] = (float)((1.0 - mom) * (double)running[c] + mom * mean);
     running[C + c] = (float)((1.0 - mom) * (double)running[C + c] + mom * unbiased);
@@ -634,18 +635,20 @@ void launch_cast_in(hipStream_t st, int dt, const float* x, void* out, int64_t n
 }
 
 void launch_bn_stats(hipStream_t st, int dt, const void* z, int64_t rows, int C, int nblk, float* partial, float eps,
-                     float mom, const float* gamma, const float* beta, float* stats, float* running) {
+                     float mom, const float* gamma, const float* beta, float* stats, float* running,
+                     const int* flags) {
   RedArgs g{}; g.a = z; g.partial = partial; g.rows = rows; g.C = C; g.nblk = nblk;
   launch_colreduce<RED_STATS>(st, dt, g);
   OSEQ_LAUNCH(bn_stats_finalize_kernel, dim3(ceil_div(C, 4)), dim3(256), 0, st, partial, nblk, C, (double)rows,
-                     eps, mom, gamma, beta, stats, running);
+                     eps, mom, gamma, beta, stats, running, flags);
 }
 
 int bn_stats_fold_rows(int nblk) { return nblk >= STAT_FOLD_MIN ? STAT_FOLD_ROWS : 0; }
 
 // partial: [nblk][2][C] block sums, followed by room for [bn_stats_fold_rows(nblk)][2][C] floats
 void launch_bn_stats_finalize(hipStream_t st, float* partial, int64_t rows, int C, int nblk, float eps, float mom,
-                              const float* gamma, const float* beta, float* stats, float* running) {
+                              const float* gamma, const float* beta, float* stats, float* running,
+                              const int* flags) {
   if (bn_stats_fold_rows(nblk) > 0) {
     float* folded = partial + (int64_t)nblk * 2 * C;
     const int per = ceil_div(nblk, STAT_FOLD_ROWS);
@@ -655,7 +658,7 @@ void launch_bn_stats_finalize(hipStream_t st, float* partial, int64_t rows, int 
     nblk = ranges;
   }
   OSEQ_LAUNCH(bn_stats_finalize_kernel, dim3(ceil_div(C, 4)), dim3(256), 0, st, partial, nblk, C, (double)rows,
-                     eps, mom, gamma, beta, stats, running);
+                     eps, mom, gamma, beta, stats, running, flags);
 }
 
 // Row blocks of the apply kernels: four rows per thread (one trip) when that still leaves about four blocks per CU, else

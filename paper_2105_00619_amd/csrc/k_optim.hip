@@ -8,8 +8,20 @@
 
 namespace oseq {
 
-__global__ void step_init_kernel(int* flags) {
-  if (threadIdx.x < 4) flags[threadIdx.x] = 0;
+// Clears the step's flags and validates the labels before anything else runs: flags[0] = a gradient is not finite
+// (set by the check pass), flags[1] = a label lies outside [0, classes).  Either flag makes the update pass a no-op,
+// and flags[1] also keeps the BatchNorm running statistics as they were.  One block; stream order makes the flags
+// visible to every later kernel of the step.
+__global__ void __launch_bounds__(256) step_init_kernel(int* __restrict__ flags, const int32_t* __restrict__ y, int n,
+                                                        int classes) {
+  __shared__ int bad;
+  if (threadIdx.x == 0) bad = 0;
+  __syncthreads();
+  bool b = false;
+  for (int i = threadIdx.x; i < n; i += blockDim.x) b |= y[i] < 0 || y[i] >= classes;
+  if (b) bad = 1;  // every writer stores the same value
+  __syncthreads();
+  if (threadIdx.x < 4) flags[threadIdx.x] = threadIdx.x == 1 ? bad : 0;
 }
 
 typedef __attribute__((ext_vector_type(4))) float opt_v4f;
@@ -35,7 +47,7 @@ __global__ void __launch_bounds__(256) optim_update_kernel(float* __restrict__ w
                                                            const float* __restrict__ g, T* __restrict__ w16,
                                                            float* __restrict__ gout, int64_t n, float lr, float mom,
                                                            float inv_scale, const int* __restrict__ flags) {
-  if (flags[0]) return;
+  if (flags[0] | flags[1]) return;  // non-finite gradient or invalid label: the step changes nothing
   const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
   const int64_t n4 = n / 4;
@@ -101,7 +113,9 @@ static int grid_for(int64_t n) { int64_t b = (n + 255) / 256; return (int)(b < 1
 // four parameters per thread and trip
 static int grid4_for(int64_t n) { return grid_for((n + 3) / 4); }
 
-void launch_step_init(hipStream_t st, int* flags) { OSEQ_LAUNCH(step_init_kernel, dim3(1), dim3(64), 0, st, flags); }
+void launch_step_init(hipStream_t st, int* flags, const int32_t* y, int n, int classes) {
+  OSEQ_LAUNCH(step_init_kernel, dim3(1), dim3(256), 0, st, flags, y, n, classes);
+}
 
 void launch_optim(hipStream_t st, int dt, float* w, float* v, const float* g, void* w16, float* gout, int64_t n, float lr,
                   float mom, float inv_scale, int* flags) {

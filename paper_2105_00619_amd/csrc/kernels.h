@@ -12,13 +12,14 @@ struct ConvGeom { int N, H, W, C, K, R, S, stride, pad, P, Q; };
 
 void launch_cast_in(hipStream_t st, int dt, const float* x, void* out, int64_t n);
 void launch_bn_stats(hipStream_t st, int dt, const void* z, int64_t rows, int C, int nblk, float* partial, float eps,
-                     float mom, const float* gamma, const float* beta, float* stats, float* running);
+                     float mom, const float* gamma, const float* beta, float* stats, float* running, const int* flags);
+// flags[1] != 0 (an invalid label in this step's batch) keeps `running` as it is.
 // the same from per-block sums a convolution already produced: partial [nblk][2][C]
 // (with many blocks the rows are first folded into bn_stats_fold_rows(nblk) rows, written behind the block sums:
 // partial has room for [nblk + bn_stats_fold_rows(nblk)][2][C] floats)
 int bn_stats_fold_rows(int nblk);
 void launch_bn_stats_finalize(hipStream_t st, float* partial, int64_t rows, int C, int nblk, float eps, float mom,
-                              const float* gamma, const float* beta, float* stats, float* running);
+                              const float* gamma, const float* beta, float* stats, float* running, const int* flags);
 // inference mode: (mean, rstd, scale, shift) from the running statistics [2][C] instead of the batch
 void launch_bn_eval_stats(hipStream_t st, const float* running, const float* gamma, const float* beta, float eps, int C,
                           float* stats);
@@ -97,7 +98,7 @@ struct TransposeJob { int64_t w_off; int K, RS, C, first_block; };
 struct TransposeBatch { static constexpr int MAX_JOBS = 48; TransposeJob job[MAX_JOBS]; int n; };
 void launch_weight_transposes(hipStream_t st, int dt, const float* wbase, void* wtbase, const TransposeJob* jobs, int njobs);
 
-void launch_step_init(hipStream_t st, int* flags);
+void launch_step_init(hipStream_t st, int* flags, const int32_t* y, int n, int classes);
 void launch_optim(hipStream_t st, int dt, float* w, float* v, const float* g, void* w16, float* gout, int64_t n, float lr,
                   float mom, float inv_scale, int* flags);
 void launch_cast_params(hipStream_t st, int dt, const float* w, void* w16, int64_t n);

@@ -147,7 +147,7 @@ class Workload:
 
 def config(index: int, batch: int | None = None, size: int | None = None) -> Workload:
     """The five benchmark configurations (index 1..5) and, as index 6, the shape of the paper's memory experiment
-    (Section "Sequential-checkpoint training": 16 images of 512 x 512 x 3 through ResNet-18): large images, tiny
+    (Section "Results": 16 images of 512 x 512 x 3 through ResNet-18): large images, tiny
     batch.  `batch` overrides the batch size, `size` the image height and width."""
     if index == 1:
         w = Workload("tiny_cnn_fp32_k2", tuple(tiny_cnn(10)), 8, 32, 32, 3, 10, FP32, 2, 0.0, 1.0, "uniform")

@@ -472,6 +472,29 @@ def test_label_out_of_range_is_an_error():
     from paper_2105_00619_amd.binding import OptorchError
     units, classes = NETS["conv_bn_relu"]
     p, x, y = _inputs(units, 4, 8, 8, classes)
-    y = y.copy(); y[1] = classes
+    import torch
+    from paper_2105_00619_amd.binding import SeqTrainer
+    bad = y.copy(); bad[1] = classes
     with pytest.raises(OptorchError):
-        gpu_step(units, p, x, y, precision=W.FP32, k=1, classes=classes)
+        gpu_step(units, p, x, bad, precision=W.FP32, k=1, classes=classes)
+    # the failed step leaves the training state as it was: weights, momentum, running statistics, loss scale
+    for precision in (W.FP32, W.FP16):
+        t = SeqTrainer(units, k_segments=2, precision=precision, batch=4, height=8, width=8, channels=3,
+                       num_classes=classes, momentum=0.9)
+        t.set_params(p)
+        xd = torch.from_numpy(x).cuda()
+        good, r0 = t.step(xd, torch.from_numpy(y).cuda(), 0.05), None
+        w0, run0 = t.get_params(), t.running_stats()
+        with pytest.raises(OptorchError):
+            t.step(xd, torch.from_numpy(bad).cuda(), 0.05)
+        assert np.array_equal(t.get_params(), w0) and np.array_equal(t.running_stats(), run0)
+        # momentum untouched: the next good step equals the one a twin takes that never saw the bad batch
+        twin = SeqTrainer(units, k_segments=2, precision=precision, batch=4, height=8, width=8, channels=3,
+                          num_classes=classes, momentum=0.9)
+        twin.set_params(p)
+        twin.step(xd, torch.from_numpy(y).cuda(), 0.05)
+        a, b = t.step(xd, torch.from_numpy(y).cuda(), 0.05), twin.step(xd, torch.from_numpy(y).cuda(), 0.05)
+        assert a["loss"] == b["loss"] and a["loss_scale"] == b["loss_scale"] == good["loss_scale"]
+        assert np.array_equal(t.get_params(), twin.get_params())
+        assert np.array_equal(t.running_stats(), twin.running_stats())
+        t.close(); twin.close()

@@ -222,12 +222,11 @@ def test_batch_permutation_symmetry():
     assert abs(l1 - l2) < 1e-12 and np.linalg.norm(g1 - g2) <= 1e-11 * np.linalg.norm(g1)
 
 
-def test_gradient_linear_in_upstream_scale():
-    """Scaling the loss by S scales every gradient by S exactly when S is a power of two."""
+def test_gradient_unchanged_by_batch_replication():
+    """Feeding the batch twice leaves the mean loss, the BatchNorm statistics and so every gradient unchanged."""
     units = FD_NETS["conv_bn_relu"]
     p, x, y = _setup(units)
     _, g = O.loss_and_grads(units, p, x, y)
-    # replicate the batch: mean loss unchanged, gradients unchanged (BN statistics identical)
     _, g2 = O.loss_and_grads(units, p, np.concatenate([x, x]), np.concatenate([y, y]))
     assert np.linalg.norm(g - g2) <= 1e-10 * np.linalg.norm(g)
 
