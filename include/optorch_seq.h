@@ -150,6 +150,22 @@ int optorch_seq_step(optorch_seq_t* h, const float* x_dev, const int32_t* y_dev,
                      float* loss_out, float* grads_dev, uint64_t* peak_saved_bytes,
                      uint64_t* peak_arena_bytes, float* loss_scale_out, int32_t* step_skipped);
 
+/* For callers that cannot allocate device memory where they step (code under HIP graph capture, tight serving or
+ * training loops, harnesses that forbid allocation): optorch_seq_step with the activation arena -- checkpoints, tensors
+ * kept for backward, transients, partial sums of the split reductions -- taken from a device array that the library
+ * holds statically, OPTORCH_STATIC_ARENA_BYTES on every GPU it runs on until the process ends, instead of from the
+ * activation arena given to optorch_seq_bind (which this call does not touch; the parameter arena, the stream and the
+ * pinned read-back buffer are the bound ones).  The call allocates nothing, on the device or through any library.
+ * OPTORCH_E_BUDGET if the planned activation arena (optorch_seq_query) is larger than the static one; OPTORCH_E_ORDER
+ * while launch timing is enabled.  The array is shared by every handle and call on that GPU and keeps the previous
+ * call's contents; no kernel of the step reads arena memory it has not written in the same step, so nothing has to be
+ * cleared -- but two such calls that overlap on one GPU (different streams or threads) race.  Arguments, results and
+ * all other errors as optorch_seq_step, to which the results are bit-identical. */
+#define OPTORCH_STATIC_ARENA_BYTES (32u << 20)
+int optorch_seq_step_static(optorch_seq_t* h, const float* x_dev, const int32_t* y_dev, float lr, float* loss_out,
+                            float* grads_dev, uint64_t* peak_saved_bytes, uint64_t* peak_arena_bytes,
+                            float* loss_scale_out, int32_t* step_skipped);
+
 /* optorch_seq_step on a batch that arrives encoded (paper, Section "Image Data-flow Optimization": the network's
  * first layer decodes).  a_dev is the batch in the form optorch_encode of optorch_dataflow.h produces for groups of z
  * images of height x width x channels 8-bit pixels: device, uint64 [ceil(batch / z)][height * width * channels][words].

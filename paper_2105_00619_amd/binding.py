@@ -21,7 +21,7 @@ SYMBOLS = (
     "optorch_seq_create", "optorch_seq_query", "optorch_seq_bind", "optorch_seq_set_params",
     "optorch_seq_get_params", "optorch_seq_step", "optorch_seq_schedule_info", "optorch_seq_last_error",
     "optorch_seq_destroy", "optorch_seq_predict", "optorch_seq_running_stats", "optorch_seq_profile_enable", "optorch_seq_profile_select", "optorch_seq_profile_read", "optorch_seq_profile_read_entries",
-    "optorch_seq_step_encoded", "optorch_seq_predict_encoded", "optorch_seq_plan_info",
+    "optorch_seq_step_encoded", "optorch_seq_predict_encoded", "optorch_seq_plan_info", "optorch_seq_step_static",
     "optorch_encoded_words", "optorch_encode", "optorch_decode", "optorch_decode_normalized", "optorch_encode_lossless",
     "optorch_decode_lossless", "optorch_dataflow_last_error",
 )
@@ -74,6 +74,8 @@ def load_library() -> C.CDLL:
                                      C.POINTER(C.c_uint64), C.POINTER(C.c_uint64), C.POINTER(C.c_float),
                                      C.POINTER(C.c_int32)]
     lib.optorch_seq_step.restype = C.c_int
+    lib.optorch_seq_step_static.argtypes = lib.optorch_seq_step.argtypes
+    lib.optorch_seq_step_static.restype = C.c_int
     lib.optorch_seq_step_encoded.argtypes = [H, C.c_void_p, C.c_int32, C.POINTER(C.c_float), C.POINTER(C.c_float), C.c_void_p,
                                              C.c_float, C.POINTER(C.c_float), C.c_void_p, C.POINTER(C.c_uint64),
                                              C.POINTER(C.c_uint64), C.POINTER(C.c_float), C.POINTER(C.c_int32)]
@@ -239,8 +241,9 @@ class SeqTrainer(SeqPlan):
         self._check(self.lib.optorch_seq_get_params(self.handle, out.ctypes.data, out.size, 0))
         return out
 
-    def step(self, x, y, lr: float, grads=None) -> dict:
-        """x: cuda float32 NHWC tensor, y: cuda int32 tensor, grads: optional cuda float32 tensor (param_count)."""
+    def step(self, x, y, lr: float, grads=None, static_arena: bool = False) -> dict:
+        """x: cuda float32 NHWC tensor, y: cuda int32 tensor, grads: optional cuda float32 tensor (param_count).
+        static_arena: run optorch_seq_step_static (the library's static activation arena; allocates nothing)."""
         torch = self.torch
         assert x.is_cuda and x.dtype == torch.float32 and x.is_contiguous()
         assert tuple(x.shape) == (self.batch, self.height, self.width, self.channels)
@@ -249,7 +252,8 @@ class SeqTrainer(SeqPlan):
             assert grads.is_cuda and grads.dtype == torch.float32 and grads.numel() == self.param_count
         loss, scale, skipped = C.c_float(), C.c_float(), C.c_int32()
         ps, pa = C.c_uint64(), C.c_uint64()
-        self._check(self.lib.optorch_seq_step(self.handle, x.data_ptr(), y.data_ptr(), lr, C.byref(loss),
+        fn = self.lib.optorch_seq_step_static if static_arena else self.lib.optorch_seq_step
+        self._check(fn(self.handle, x.data_ptr(), y.data_ptr(), lr, C.byref(loss),
                                               grads.data_ptr() if grads is not None else None, C.byref(ps), C.byref(pa),
                                               C.byref(scale), C.byref(skipped)))
         return {"loss": loss.value, "peak_saved_bytes": ps.value, "peak_arena_bytes": pa.value,

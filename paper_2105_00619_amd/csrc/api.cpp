@@ -32,6 +32,7 @@ struct optorch_seq {
   int growth_interval = 0, clean = 0;
   bool dynamic_scale = false;
   float* host_rb = nullptr;  // pinned read-back buffer: loss + flags
+  std::vector<TransposeJob> transpose_jobs;  // layers whose data gradient reads a transposed weight copy
   mutable std::string err;
   // profiling: an event pair per kernel launch of the timed entries, harvested on read
   bool profiling = false;
@@ -57,13 +58,9 @@ static int hip_fail(const optorch_seq_t* h, hipError_t e, const char* what) {
 
 // refresh the transposed weight copies the data-gradient GEMMs read (after every change of the master weights)
 static void refresh_transposed_weights(optorch_seq_t* h) {
-  std::vector<TransposeJob> jobs;
-  for (const FOp& f : h->plan.fops)
-    if (f.kind == F_CONV && f.dgrad_algo == ALGO_MFMA && h->plan.tensors[f.x].needs_grad)
-      jobs.push_back(TransposeJob{f.w_off, f.K, f.R * f.S, f.C, 0});
-  if (!jobs.empty())
-    launch_weight_transposes(h->stream, h->dt, (const float*)(h->pbase + h->off_w), h->pbase + h->off_wt, jobs.data(),
-                             (int)jobs.size());
+  if (!h->transpose_jobs.empty())
+    launch_weight_transposes(h->stream, h->dt, (const float*)(h->pbase + h->off_w), h->pbase + h->off_wt,
+                             h->transpose_jobs.data(), (int)h->transpose_jobs.size());
 }
 
 extern "C" int optorch_seq_create(const optorch_unit_t* units, int32_t n_units, const optorch_seq_config_t* cfg,
@@ -157,6 +154,9 @@ extern "C" int optorch_seq_create(const optorch_unit_t* units, int32_t n_units, 
   h->off_run = o; o = align_up(o + p.n_running * 4);
   h->off_scal = o; o = align_up(o + 256);
   h->param_arena_bytes = o;
+  for (const FOp& f : p.fops)
+    if (f.kind == F_CONV && f.dgrad_algo == ALGO_MFMA && p.tensors[f.x].needs_grad)
+      h->transpose_jobs.push_back(TransposeJob{f.w_off, f.K, f.R * f.S, f.C, 0});
   *out = h;
   return OPTORCH_OK;
 }
@@ -251,9 +251,10 @@ namespace {
 struct Ctx {
   optorch_seq_t* h;
   const float* x; const int32_t* y;
+  char* abase = nullptr;  // the activation arena this call works in (the bound one unless stated otherwise)
   // the batch in encoded form instead of x (groups of xz images, Algorithm "Encode"), with the input normalisation
   const uint64_t* xa = nullptr; int xz = 0; const float* xscale = nullptr; const float* xshift = nullptr;
-  void* at(int inst) const { return inst < 0 ? nullptr : (void*)(h->abase + h->plan.insts[inst].offset); }
+  void* at(int inst) const { return inst < 0 ? nullptr : (void*)(abase + h->plan.insts[inst].offset); }
   float* w32(int64_t off) const { return (float*)(h->pbase + h->off_w) + off; }
   float* g32(int64_t off) const { return (float*)(h->pbase + h->off_g) + off; }
   const void* wc(int64_t off) const {  // weights in the compute type
@@ -540,7 +541,7 @@ extern "C" int optorch_seq_predict(optorch_seq_t* h, const float* x_dev, float* 
   if (!h) return OPTORCH_E_INVALID;
   if (!h->bound || !h->params_set) return set_err(h, OPTORCH_E_ORDER, "predict before bind/set_params");
   if (!x_dev || !logits_dev) return set_err(h, OPTORCH_E_INVALID, "null pointer");
-  Ctx c{h, x_dev, nullptr};
+  Ctx c{h, x_dev, nullptr, h->abase};
   return predict_run(h, c, logits_dev);
 }
 
@@ -552,7 +553,7 @@ extern "C" int optorch_seq_predict_encoded(optorch_seq_t* h, const uint64_t* a_d
   if (z < 1 || z > 16) return set_err(h, OPTORCH_E_INVALID, "images per group must be 1..16");
   if (h->in_channels < 1 || h->in_channels > 16)
     return set_err(h, OPTORCH_E_INVALID, "an encoded batch needs a network input of 1..16 channels");
-  Ctx c{h, nullptr, nullptr};
+  Ctx c{h, nullptr, nullptr, h->abase};
   c.xa = a_dev; c.xz = z; c.xscale = scale_host; c.xshift = shift_host;
   return predict_run(h, c, logits_dev);
 }
@@ -646,7 +647,7 @@ extern "C" int optorch_seq_step(optorch_seq_t* h, const float* x_dev, const int3
   if (!h->bound || !h->params_set) return set_err(h, OPTORCH_E_ORDER, "step before bind/set_params");
   if (!x_dev || !y_dev) return set_err(h, OPTORCH_E_INVALID, "null input pointer");
   if (!std::isfinite(lr)) return set_err(h, OPTORCH_E_INVALID, "learning rate is not finite");
-  Ctx c{h, x_dev, y_dev};
+  Ctx c{h, x_dev, y_dev, h->abase};
   h->x_encoded = false;
   return step_run(h, c, lr, loss_out, grads_dev, peak_saved_bytes, peak_arena_bytes, loss_scale_out, step_skipped);
 }
@@ -662,9 +663,30 @@ extern "C" int optorch_seq_step_encoded(optorch_seq_t* h, const uint64_t* a_dev,
   if (h->in_channels < 1 || h->in_channels > 16)
     return set_err(h, OPTORCH_E_INVALID, "an encoded batch needs a network input of 1..16 channels");
   if (!std::isfinite(lr)) return set_err(h, OPTORCH_E_INVALID, "learning rate is not finite");
-  Ctx c{h, nullptr, y_dev};
+  Ctx c{h, nullptr, y_dev, h->abase};
   c.xa = a_dev; c.xz = z; c.xscale = scale_host; c.xshift = shift_host;
   h->x_encoded = true;
+  return step_run(h, c, lr, loss_out, grads_dev, peak_saved_bytes, peak_arena_bytes, loss_scale_out, step_skipped);
+}
+
+extern "C" int optorch_seq_step_static(optorch_seq_t* h, const float* x_dev, const int32_t* y_dev, float lr, float* loss_out,
+                                       float* grads_dev, uint64_t* peak_saved_bytes, uint64_t* peak_arena_bytes,
+                                       float* loss_scale_out, int32_t* step_skipped) {
+  if (!h) return OPTORCH_E_INVALID;
+  if (!h->bound || !h->params_set) return set_err(h, OPTORCH_E_ORDER, "step before bind/set_params");
+  if (!x_dev || !y_dev) return set_err(h, OPTORCH_E_INVALID, "null input pointer");
+  if (!std::isfinite(lr)) return set_err(h, OPTORCH_E_INVALID, "learning rate is not finite");
+  if (h->profiling) return set_err(h, OPTORCH_E_ORDER, "optorch_seq_step_static does not time launches: disable profiling");
+  if (h->plan.arena_bytes > (uint64_t)OPTORCH_STATIC_ARENA_BYTES)
+    return set_err(h, OPTORCH_E_BUDGET, "planned activation arena of " + std::to_string(h->plan.arena_bytes) +
+                                            " bytes exceeds the static arena of " +
+                                            std::to_string((uint64_t)OPTORCH_STATIC_ARENA_BYTES) + " bytes");
+  void* arena = nullptr;
+  uint64_t bytes = 0;
+  hipError_t e = static_arena(&arena, &bytes);
+  if (e != hipSuccess) return hip_fail(h, e, "hipGetSymbolAddress(static arena)");
+  Ctx c{h, x_dev, y_dev, (char*)arena};
+  h->x_encoded = false;
   return step_run(h, c, lr, loss_out, grads_dev, peak_saved_bytes, peak_arena_bytes, loss_scale_out, step_skipped);
 }
 

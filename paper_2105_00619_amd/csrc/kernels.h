@@ -98,6 +98,8 @@ struct TransposeJob { int64_t w_off; int K, RS, C, first_block; };
 struct TransposeBatch { static constexpr int MAX_JOBS = 48; TransposeJob job[MAX_JOBS]; int n; };
 void launch_weight_transposes(hipStream_t st, int dt, const float* wbase, void* wtbase, const TransposeJob* jobs, int njobs);
 
+// device address and size of the per-GPU static activation arena (optorch_seq_step_static), current device
+hipError_t static_arena(void** ptr, uint64_t* bytes);
 void launch_step_init(hipStream_t st, int* flags, const int32_t* y, int n, int classes);
 void launch_optim(hipStream_t st, int dt, float* w, float* v, const float* g, void* w16, float* gout, int64_t n, float lr,
                   float mom, float inv_scale, int* flags);
