@@ -192,6 +192,21 @@ int optorch_seq_predict(optorch_seq_t* h, const float* x_dev, float* logits_dev)
 int optorch_seq_predict_encoded(optorch_seq_t* h, const uint64_t* a_dev, int32_t z, const float* scale_host,
                                 const float* shift_host, float* logits_dev);
 
+/* Inspection of the forward pass (for parity tests unit by unit; not part of a training loop): runs the forward
+ * entries of the step's static schedule on x_dev exactly as optorch_seq_step runs them (batch statistics in every
+ * BatchNorm, the segments' keep / discard rules, the same kernels and launch shapes), stops after the entry that writes
+ * the output activation of body unit `unit`, and converts that tensor from the storage type to fp32 into out_dev.
+ * Changes no training state: weights, momentum, running statistics and loss scale are untouched.  Allocates nothing;
+ * uses the bound activation arena (not concurrently with a step) and returns after the stream has finished.
+ *   out_dev     device, or NULL to query *count and shape_nhwc only
+ *   capacity    floats out_dev can hold; OPTORCH_E_INVALID if fewer than *count
+ *   count       host or NULL: elements of the unit's output
+ *   shape_nhwc  host int32[4] or NULL: batch, height, width, channels of the unit's output
+ * OPTORCH_E_INVALID also if the plan fuses the unit's output into the next unit so that it is never written (a
+ * convolution whose activation is only read by the max-pool behind it). */
+int optorch_seq_debug_unit_output(optorch_seq_t* h, const float* x_dev, int32_t unit, float* out_dev, uint64_t capacity,
+                                  uint64_t* count, int32_t* shape_nhwc);
+
 /* The BatchNorm running statistics: for every BatchNorm in parameter order, C running means then C running
  * variances (fp32).  They start at 0 and 1 (optorch_seq_set_params) and every optorch_seq_step moves them by
  * bn_momentum towards the batch mean and the unbiased batch variance, also on a step that is then skipped for a

@@ -37,13 +37,20 @@ tap; nothing is blocked, fused or reordered.
 Storage emulation (optional).  A ReLU mask is an integer decision taken by a
 floating-point comparison, and a 16-bit pipeline takes it on 16-bit values.  So
 that both sides take it in the same precision, `loss_and_grads(storage="bf16" |
-"fp16", loss_scale=S)` rounds (to nearest even) every tensor the mixed-precision
-pipeline keeps in 16 bits -- the input image, the convolution weights, each
-convolution output, each BatchNorm/ReLU output, and each activation gradient --
-and multiplies the loss gradient by S, dividing the parameter gradients by S at
-the end.  Everything between two stored tensors (contractions, BatchNorm
-statistics and sums, the loss head, parameter gradients) stays in float64.  With
-storage=None the hooks are the identity and the function is the plain definition.
+"fp16", loss_scale=S)` follows the mixed-precision recipe (Section
+"Mixed-precision training": 16-bit storage, 32-bit arithmetic) as "every tensor
+kept in 16 bits is rounded to nearest even exactly once, when it is stored":
+the input image, the 16-bit copy of each convolution weight, each convolution
+output in front of a BatchNorm (the statistics are then those of the stored
+values), each unit's and each layer's output activation, and each activation
+gradient (the gradient entering the network body, the gradient behind each
+BatchNorm, and the gradient w.r.t. each layer's input; where two paths meet, the
+sum is the stored tensor).  The loss gradient is multiplied by S and the
+parameter gradients divided by S at the end.  Everything between two stored
+tensors (contractions, BatchNorm statistics and sums, the loss head, parameter
+gradients) stays in float64.  With storage=None the hooks are the identity and
+the function is the plain definition.  The placement of the rounding points is
+pinned by worked examples (tests/golden/mixed_precision_worked.txt).
 
 Inference mode.  BatchNorm keeps running estimates of each channel's mean and variance (exponential averages of the
 batch mean and of the unbiased batch variance, momentum 0.1, started at 0 and 1) and `predict` evaluates the network
@@ -346,7 +353,7 @@ def _unit_backward(cache, da, grads):
     local.reverse()  # conv1, conv2, [conv3]
     if csc is not None:
         dsc, _ = _cbr_backward(dskip, csc, local)  # appended last = layout order
-        d = q(d + q(dsc))  # the shortcut's data gradient is stored first, the main path's is added to it
+        d = q(d + dsc)  # the gradient w.r.t. the block's input is one stored tensor: the sum, rounded once
     else:
         d = q(d + dskip)
     grads.append([g for layer in local for g in layer])
@@ -364,6 +371,9 @@ def loss_and_grads(units, params, x, y, dtype=np.float64, return_trace=False, st
     x      : (B, H, W, C) images;  y : (B,) integer labels
     storage, loss_scale : 16-bit storage emulation, see the module docstring; the returned
              gradients are unscaled (non-finite if a stored value overflowed)
+    return_trace : a third return value holds the stored tensors: {"input": the batch as stored, "units": the
+             output of every body unit, "logits", "d_units": the gradient w.r.t. the input of every unit (entry i
+             for unit i; the last entry is the gradient entering the body from the head), scaled by loss_scale}
     kink_tau : if given, a third return value lists the ReLU decisions whose pre-activation lies within
              kink_tau x rms of zero -- decisions a finite-precision evaluation may legitimately take the
              other way -- as (relu number, flat index into that layer's output, flat index of the gradient
@@ -377,12 +387,13 @@ def loss_and_grads(units, params, x, y, dtype=np.float64, return_trace=False, st
     a = q(np.asarray(x, dtype=dtype))
     y = np.asarray(y).astype(np.int64)
     pr = _Params(params, q, flips, kink_tau)
-    caches, trace = [], []
+    caches = []
+    trace = {"input": a, "units": [], "d_units": []}
     for u in units[:-1]:
         a, c = _unit_forward(u, a, pr)
         caches.append(c)
         if return_trace:
-            trace.append(a)
+            trace["units"].append(a)
     head = units[-1]
     if head.kind == GAP_LINEAR_CE:
         feat = a.mean(axis=(1, 2))
@@ -396,6 +407,7 @@ def loss_and_grads(units, params, x, y, dtype=np.float64, return_trace=False, st
         raise ValueError("parameter vector has %d entries, network needs %d" % (params.size, pr.off))
     logits = feat @ wl.T + bl
     loss, prob = softmax_ce_forward(logits, y)
+    trace["logits"] = logits
 
     dlogits = softmax_ce_backward(prob, y) * loss_scale
     dwl = dlogits.T @ feat
@@ -407,10 +419,12 @@ def loss_and_grads(units, params, x, y, dtype=np.float64, return_trace=False, st
     else:
         da = dfeat.reshape(a.shape)
     da = q(da)
+    trace["d_units"].append(da)
     grads_rev = [[dwl, dbl]]
     for c in reversed(caches):
         before = len(grads_rev)
         da = _unit_backward(c, da, grads_rev)
+        trace["d_units"].append(da)
         if len(grads_rev) == before:
             grads_rev.append([])
     flat = [np.ravel(g) for unit_g in reversed(grads_rev) for g in unit_g]
@@ -419,6 +433,7 @@ def loss_and_grads(units, params, x, y, dtype=np.float64, return_trace=False, st
     if loss_scale != 1.0:
         grad = grad / loss_scale
     if return_trace:
+        trace["d_units"].reverse()  # d_units[i]: gradient w.r.t. the input of unit i, as stored (scaled by loss_scale)
         return float(loss), grad, trace
     if kink_tau is not None:
         return float(loss), grad, pr.kinks
@@ -447,6 +462,24 @@ def _forward_logits(units, pr, a):
     wl = pr.take((head.cout, feat.shape[1]))
     bl = pr.take((head.cout,))
     return feat @ wl.T + bl
+
+
+def forward_trace(units, params, x, dtype=np.float64, storage=None):
+    """The training-mode forward pass alone (batch statistics in every BatchNorm): {"input": the batch as stored,
+    "units": the output of every body unit, "logits"}; storage as in loss_and_grads."""
+    q = _quantizer(storage)
+    pr = _Params(np.asarray(params, dtype=dtype), q)
+    a = q(np.asarray(x, dtype=dtype))
+    trace = {"input": a, "units": []}
+    for u in units[:-1]:
+        a, _ = _unit_forward(u, a, pr)
+        trace["units"].append(a)
+    head = units[-1]
+    feat = a.mean(axis=(1, 2)) if head.kind == GAP_LINEAR_CE else a.reshape(a.shape[0], -1)
+    wl = pr.take((head.cout, feat.shape[1]))
+    bl = pr.take((head.cout,))
+    trace["logits"] = feat @ wl.T + bl
+    return trace
 
 
 def initial_running_stats(units, params, x_shape):

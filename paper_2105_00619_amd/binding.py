@@ -21,7 +21,7 @@ SYMBOLS = (
     "optorch_seq_create", "optorch_seq_query", "optorch_seq_bind", "optorch_seq_set_params",
     "optorch_seq_get_params", "optorch_seq_step", "optorch_seq_schedule_info", "optorch_seq_last_error",
     "optorch_seq_destroy", "optorch_seq_predict", "optorch_seq_running_stats", "optorch_seq_profile_enable", "optorch_seq_profile_select", "optorch_seq_profile_read", "optorch_seq_profile_read_entries",
-    "optorch_seq_step_encoded", "optorch_seq_predict_encoded", "optorch_seq_plan_info", "optorch_seq_step_static",
+    "optorch_seq_step_encoded", "optorch_seq_predict_encoded", "optorch_seq_plan_info", "optorch_seq_step_static", "optorch_seq_debug_unit_output",
     "optorch_encoded_words", "optorch_encode", "optorch_decode", "optorch_decode_normalized", "optorch_encode_lossless",
     "optorch_decode_lossless", "optorch_dataflow_last_error",
 )
@@ -76,6 +76,9 @@ def load_library() -> C.CDLL:
     lib.optorch_seq_step.restype = C.c_int
     lib.optorch_seq_step_static.argtypes = lib.optorch_seq_step.argtypes
     lib.optorch_seq_step_static.restype = C.c_int
+    lib.optorch_seq_debug_unit_output.argtypes = [H, C.c_void_p, C.c_int32, C.c_void_p, C.c_uint64, C.POINTER(C.c_uint64),
+                                                  C.POINTER(C.c_int32)]
+    lib.optorch_seq_debug_unit_output.restype = C.c_int
     lib.optorch_seq_step_encoded.argtypes = [H, C.c_void_p, C.c_int32, C.POINTER(C.c_float), C.POINTER(C.c_float), C.c_void_p,
                                              C.c_float, C.POINTER(C.c_float), C.c_void_p, C.POINTER(C.c_uint64),
                                              C.POINTER(C.c_uint64), C.POINTER(C.c_float), C.POINTER(C.c_int32)]
@@ -204,20 +207,41 @@ class SeqPlan:
 class SeqTrainer(SeqPlan):
     """A bound plan: device arenas allocated through torch, steps run on torch's current stream."""
 
-    def __init__(self, units, *, device="cuda:0", **kw):
+    GUARD_BYTE = 0xA5
+
+    def __init__(self, units, *, device="cuda:0", guard_bytes: int = 0, **kw):
+        """guard_bytes > 0: each arena is allocated with that many bytes of a fixed pattern in front of and behind the
+        bytes lent to the library, and `guards_intact()` checks that no kernel wrote outside them."""
         import torch
         super().__init__(units, **kw)
         self.torch = torch
         self.device = torch.device(device)
         if not torch.cuda.is_available():
             raise RuntimeError("no GPU visible: the training step only runs on the HIP path")
-        self.param_arena = torch.empty(self.param_arena_bytes + 256, dtype=torch.uint8, device=self.device)
-        self.act_arena = torch.empty(self.act_arena_bytes + 256, dtype=torch.uint8, device=self.device)
+        self.guard_bytes = g = (int(guard_bytes) + 255) // 256 * 256
+        self._arenas = []
+        ptrs = []
+        for nbytes in (self.param_arena_bytes, self.act_arena_bytes):
+            buf = torch.empty(nbytes + 2 * g + 256, dtype=torch.uint8, device=self.device)
+            start = (buf.data_ptr() + 255) // 256 * 256 - buf.data_ptr() + g  # offset of the lent bytes inside buf
+            if g:
+                buf[:start].fill_(self.GUARD_BYTE)
+                buf[start + nbytes:].fill_(self.GUARD_BYTE)
+            self._arenas.append((buf, start, nbytes))
+            ptrs.append(buf.data_ptr() + start)
+        self.param_arena, self.act_arena = self._arenas[0][0], self._arenas[1][0]
         self.stream = torch.cuda.current_stream(self.device)
-        pa = (self.param_arena.data_ptr() + 255) // 256 * 256
-        aa = (self.act_arena.data_ptr() + 255) // 256 * 256
-        self._check(self.lib.optorch_seq_bind(self.handle, pa, self.param_arena_bytes, aa, self.act_arena_bytes,
+        self._check(self.lib.optorch_seq_bind(self.handle, ptrs[0], self.param_arena_bytes, ptrs[1], self.act_arena_bytes,
                                               self.stream.cuda_stream))
+
+    def guards_intact(self) -> bool:
+        """True if every guard byte around both arenas still holds the pattern (needs guard_bytes > 0)."""
+        assert self.guard_bytes > 0, "the trainer was created without guard bands"
+        self.torch.cuda.synchronize(self.device)
+        for buf, start, nbytes in self._arenas:
+            if not bool((buf[:start] == self.GUARD_BYTE).all()) or not bool((buf[start + nbytes:] == self.GUARD_BYTE).all()):
+                return False
+        return True
 
     @classmethod
     def from_workload(cls, w, device="cuda:0", **override):
@@ -297,6 +321,18 @@ class SeqTrainer(SeqPlan):
         out = torch.empty((self.batch, self.num_classes), dtype=torch.float32, device=self.device)
         self._check(self.lib.optorch_seq_predict_encoded(self.handle, a.data_ptr(), z, _float_array(scale, self.channels),
                                                          _float_array(shift, self.channels), out.data_ptr()))
+        return out
+
+    def unit_output(self, x, unit: int):
+        """The output activation of body unit `unit` in a training-mode forward pass on x: cuda float32 NHWC tensor
+        (optorch_seq_debug_unit_output)."""
+        torch = self.torch
+        assert x.is_cuda and x.dtype == torch.float32 and x.is_contiguous()
+        n, shape = C.c_uint64(), (C.c_int32 * 4)()
+        self._check(self.lib.optorch_seq_debug_unit_output(self.handle, None, unit, None, 0, C.byref(n), shape))
+        out = torch.empty(tuple(shape), dtype=torch.float32, device=self.device)
+        self._check(self.lib.optorch_seq_debug_unit_output(self.handle, x.data_ptr(), unit, out.data_ptr(), n.value,
+                                                           C.byref(n), shape))
         return out
 
     def running_stats(self) -> np.ndarray:

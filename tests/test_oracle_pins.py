@@ -372,3 +372,87 @@ def test_running_statistics_follow_the_parameter_layout_order():
     r1 = O.update_running_stats(r0, moments, 0.1)
     assert np.allclose(r1[32:40], 0.1 * z.mean(axis=(0, 1, 2)), rtol=0, atol=1e-12)
     assert np.allclose(r1[40:48], 0.9 + 0.1 * z.var(axis=(0, 1, 2)) * 27 / 26, rtol=0, atol=1e-12)
+
+
+# ------------------------------------------------ 16-bit storage: where the roundings fall ------
+def _worked_examples():
+    import os
+    path = os.path.join(os.path.dirname(__file__), "golden", "mixed_precision_worked.txt")
+    out, cur = {}, None
+    for line in open(path):
+        line = line.split("#")[0].strip()
+        if not line:
+            continue
+        if line.startswith("["):
+            cur = out.setdefault(line.strip("[]"), {})
+            continue
+        name, vals = [t.strip() for t in line.split("=")]
+        cur[name] = np.array([float(v) for v in vals.split()])
+    return out
+
+
+WORKED_NETS = {
+    "A": ([W.conv(1, 1, ksize=1, bn=False, relu=True, bias=True), W.conv(1, 1, ksize=1, bn=False, relu=False, bias=True),
+           W.gap_linear_ce(1, 2)], (1, 1, 2, 1)),
+    "B": ([W.conv(2, 1, ksize=1, bn=True, relu=True, bias=False), W.gap_linear_ce(1, 2)], (2, 1, 2, 2)),
+}
+
+
+@pytest.mark.parametrize("name", sorted(WORKED_NETS))
+def test_bf16_storage_matches_the_worked_examples(name):
+    """Paper, Section "Mixed-precision training", read as one rounding per stored tensor: the stored intermediates and
+    the gradients of two networks small enough to work by hand (tests/golden/mixed_precision_worked.txt)."""
+    ex = _worked_examples()[name]
+    units, shape = WORKED_NETS[name]
+    x = ex["x"].reshape(shape)
+    y = ex["label"].astype(np.int64)
+    loss, g, tr = O.loss_and_grads(units, ex["params"], x, y, storage="bf16", loss_scale=float(ex["loss_scale"][0]),
+                                   return_trace=True)
+    tol = dict(rtol=1e-13, atol=1e-15)
+    assert np.allclose(tr["input"].ravel(), ex["input_stored"], **tol)
+    for i in range(len(units) - 1):
+        assert np.allclose(tr["units"][i].ravel(), ex["unit%d_out" % i], **tol), i
+    assert np.allclose(tr["logits"].ravel(), ex["logits"], rtol=1e-13, atol=1e-15)
+    assert abs(loss - ex["loss"][0]) < 1e-14
+    for i in range(len(units)):
+        if "d_unit%d_in" % i in ex:
+            assert np.allclose(tr["d_units"][i].ravel(), ex["d_unit%d_in" % i], **tol), i
+    assert np.allclose(g, ex["grads"], rtol=1e-12, atol=1e-15)
+    # a missing or an extra rounding anywhere moves these numbers by 1e-4 or more: the plain evaluation is that far away
+    _, g_plain = O.loss_and_grads(units, ex["params"], x, y)
+    assert np.abs(g_plain - ex["grads"]).max() > 1e-4
+
+
+def test_maxpool_on_odd_maps():
+    """2x2 max-pool on a 7 x 5 map: the last row and column belong to no window.  Forward against a loop over
+    windows, backward against finite differences through a network that pools a 7 x 5 map twice."""
+    rng = np.random.default_rng(3)
+    x = rng.normal(size=(2, 7, 5, 3))
+    out, arg = O.maxpool2_forward(x)
+    assert out.shape == (2, 3, 2, 3)
+    for n in range(2):
+        for i in range(3):
+            for j in range(2):
+                for c in range(3):
+                    win = x[n, 2 * i:2 * i + 2, 2 * j:2 * j + 2, c]
+                    assert out[n, i, j, c] == win.max() and arg[n, i, j, c] == int(np.argmax(win.ravel()))
+    dy = rng.normal(size=out.shape)
+    dx = O.maxpool2_backward(dy, arg, x.shape)
+    assert np.all(dx[:, 6, :, :] == 0) and np.all(dx[:, :, 4, :] == 0)
+    assert np.isclose(dx.sum(), dy.sum()) and np.count_nonzero(dx) == dy.size
+    # ties go to the first maximum in scan order
+    t = np.zeros((1, 2, 2, 1)); t[0, 0, 1, 0] = t[0, 1, 0, 0] = 1.0
+    assert O.maxpool2_forward(t)[1][0, 0, 0, 0] == 1
+    units = [W.conv(3, 4), W.maxpool(), W.conv(4, 4), W.maxpool(), W.flatten_linear_ce(4, 5)]
+    p, xi, yi = _setup(units, b=3, h=7, w=5)
+    _fd_check(units, p, xi, yi)
+
+
+def test_forward_trace_is_the_forward_half_of_loss_and_grads():
+    units = FD_NETS["basic_block_projection"][:-1] + [W.maxpool(), W.gap_linear_ce(8, 5)]
+    p, x, y = _setup(units, b=3, h=8, w=8)
+    for storage in (None, "bf16", "fp16"):
+        _, _, t = O.loss_and_grads(units, p, x, y, return_trace=True, storage=storage)
+        f = O.forward_trace(units, p, x, storage=storage)
+        assert len(f["units"]) == len(units) - 1
+        assert all(np.array_equal(a, b) for a, b in zip(t["units"], f["units"])) and np.array_equal(t["logits"], f["logits"])
