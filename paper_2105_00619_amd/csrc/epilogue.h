@@ -1,7 +1,7 @@
 // Store half of the convolution kernels' epilogue, shared by the GEMM-shaped kernels.
 //
-// The accumulators of HR block rows lie in LDS as fp32 [HR][BN + 4].  Every thread handles, for HR * (BN / 8) / 256
-// rows, 8 consecutive channels: bias / residual addend / ReLU in fp32, one rounding, one 16-byte (fp32: two) store,
+// The accumulators of HR block rows lie in LDS as fp32 [HR][BN + 4].  Every one of the block's NT threads (256 unless
+// the _nt form is used) handles, for HR * (BN / 8) / NT rows, 8 consecutive channels: bias / residual addend / ReLU in fp32, one rounding, one 16-byte (fp32: two) store,
 // and optionally adds what it stored to its per-channel sum and sum of squares (the BatchNorm statistics).
 //
 // Loads and stores share one in-order counter on this hardware, so a load issued after a store cannot be waited for
@@ -16,14 +16,14 @@ namespace oseq {
 typedef __attribute__((ext_vector_type(4))) float epi_v4f;
 
 // rowoff(row): element offset of block row `row`'s first channel in the output tensor, or -1 if the row is not stored
-template <class T, int BN, int HR, bool HB, bool HA, bool STAT, class RowOff>
-__device__ __forceinline__ void epi_store_rows(const float* ep, int tid, int n0, const float* __restrict__ bias,
+template <int NT, class T, int BN, int HR, bool HB, bool HA, bool STAT, class RowOff>
+__device__ __forceinline__ void epi_store_rows_nt(const float* ep, int tid, int n0, const float* __restrict__ bias,
                                                const T* __restrict__ addend, T* __restrict__ out, int relu, RowOff rowoff,
                                                float (&ss)[8], float (&qq)[8]) {
   constexpr int EP_PITCH = BN + 4;
   constexpr int GROUPS = BN / 8;                // 8-channel groups per row
-  constexpr int PER_THREAD = HR * GROUPS / 256; // rows per thread
-  constexpr int RG = 256 / GROUPS;              // rows between a thread's rows
+  constexpr int PER_THREAD = HR * GROUPS / NT;  // rows per thread
+  constexpr int RG = NT / GROUPS;               // rows between a thread's rows
   static_assert(PER_THREAD >= 1, "fewer rows than the block covers");
   const int c8 = (tid % GROUPS) * 8, erow = tid / GROUPS;
   const int col = n0 + c8;
@@ -78,17 +78,23 @@ __device__ __forceinline__ void epi_store_rows(const float* ep, int tid, int n0,
 // The uniform choice of the code path.  CAN_BIAS / CAN_ADD: whether the calling kernel is ever given a bias / an
 // addend (forward kernels have no addend, data-gradient kernels no bias); the combinations that cannot occur are not
 // compiled, which keeps their registers out of the kernel.
+template <int NT, class T, int BN, int HR, bool CAN_BIAS, bool CAN_ADD, bool STAT, class RowOff>
+__device__ __forceinline__ void epi_store_pass_nt(const float* ep, int tid, int n0, const float* __restrict__ bias,
+                                                  const T* __restrict__ addend, T* __restrict__ out, int relu, RowOff rowoff,
+                                                  float (&ss)[8], float (&qq)[8]) {
+  if (CAN_BIAS && bias) {
+    if (CAN_ADD && addend) epi_store_rows_nt<NT, T, BN, HR, true, CAN_ADD, STAT>(ep, tid, n0, bias, addend, out, relu, rowoff, ss, qq);
+    else epi_store_rows_nt<NT, T, BN, HR, true, false, STAT>(ep, tid, n0, bias, addend, out, relu, rowoff, ss, qq);
+  } else {
+    if (CAN_ADD && addend) epi_store_rows_nt<NT, T, BN, HR, false, true, STAT>(ep, tid, n0, bias, addend, out, relu, rowoff, ss, qq);
+    else epi_store_rows_nt<NT, T, BN, HR, false, false, STAT>(ep, tid, n0, bias, addend, out, relu, rowoff, ss, qq);
+  }
+}
 template <class T, int BN, int HR, bool CAN_BIAS, bool CAN_ADD, bool STAT, class RowOff>
 __device__ __forceinline__ void epi_store_pass(const float* ep, int tid, int n0, const float* __restrict__ bias,
                                                const T* __restrict__ addend, T* __restrict__ out, int relu, RowOff rowoff,
                                                float (&ss)[8], float (&qq)[8]) {
-  if (CAN_BIAS && bias) {
-    if (CAN_ADD && addend) epi_store_rows<T, BN, HR, true, CAN_ADD, STAT>(ep, tid, n0, bias, addend, out, relu, rowoff, ss, qq);
-    else epi_store_rows<T, BN, HR, true, false, STAT>(ep, tid, n0, bias, addend, out, relu, rowoff, ss, qq);
-  } else {
-    if (CAN_ADD && addend) epi_store_rows<T, BN, HR, false, true, STAT>(ep, tid, n0, bias, addend, out, relu, rowoff, ss, qq);
-    else epi_store_rows<T, BN, HR, false, false, STAT>(ep, tid, n0, bias, addend, out, relu, rowoff, ss, qq);
-  }
+  epi_store_pass_nt<256, T, BN, HR, CAN_BIAS, CAN_ADD, STAT>(ep, tid, n0, bias, addend, out, relu, rowoff, ss, qq);
 }
 
 // raw fp32 sums of a depth range (no epilogue arithmetic): dst + rowoff(row) + channel
@@ -111,14 +117,14 @@ __device__ __forceinline__ void epi_store_partial(const float* ep, int tid, int 
   }
 }
 
-// Per-block channel sums from the threads' sums: the 256 / (BN / 8) row groups of a channel are added in a fixed order
-// through LDS (red: 2 * (256 / (BN / 8)) * BN floats, free to overwrite; called by all 256 threads).
+// Per-block channel sums from the threads' sums: the NT / (BN / 8) row groups of a channel are added in a fixed order
+// through LDS (red: 2 * (NT / (BN / 8)) * BN floats, free to overwrite; called by all NT threads).
 // dst_sum / dst_sq: this block's rows of the [blocks][2][channels] array, at the block's first channel.
-template <int BN>
-__device__ __forceinline__ void epi_stat_combine(float* red, int tid, const float (&ss)[8], const float (&qq)[8],
-                                                 float* __restrict__ dst_sum, float* __restrict__ dst_sq) {
+template <int NT, int BN>
+__device__ __forceinline__ void epi_stat_combine_nt(float* red, int tid, const float (&ss)[8], const float (&qq)[8],
+                                                    float* __restrict__ dst_sum, float* __restrict__ dst_sq) {
   constexpr int GROUPS = BN / 8;
-  constexpr int RG = 256 / GROUPS;
+  constexpr int RG = NT / GROUPS;
   const int c8 = (tid % GROUPS) * 8, erow = tid / GROUPS;
   __syncthreads();
 #pragma unroll
@@ -131,6 +137,11 @@ __device__ __forceinline__ void epi_stat_combine(float* red, int tid, const floa
     dst_sum[tid] = s0;
     dst_sq[tid] = q0;
   }
+}
+template <int BN>
+__device__ __forceinline__ void epi_stat_combine(float* red, int tid, const float (&ss)[8], const float (&qq)[8],
+                                                 float* __restrict__ dst_sum, float* __restrict__ dst_sq) {
+  epi_stat_combine_nt<256, BN>(red, tid, ss, qq, dst_sum, dst_sq);
 }
 
 }  // namespace oseq

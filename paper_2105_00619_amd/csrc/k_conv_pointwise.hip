@@ -249,6 +249,179 @@ conv1x1_kernel(const T* __restrict__ X, const T* __restrict__ W, const float* __
                          stat_partial + ((int64_t)mt * 2 + 1) * a.Ng + n0);
 }
 
+// The same GEMM with a 256 x 256 tile for layers with many pixels (stride 1, no scatter).  Operand tiles travel from L2
+// to the CUs at about 10 TB/s over the whole chip, and a block of this kernel family moves (BM + BN) * depth elements
+// for BM * BN results: with 128 x 128 tiles a layer of the bottleneck networks at batch 4096 moves 2.1 GB that way and
+// cannot finish faster than ~210 us, whatever HBM and the matrix cores could do; 256 x 256 tiles halve that.  512
+// threads = 8 wavefronts (2 x 4), wave tile 128 x 64 (MI = 4, NI = 2: six operand reads from LDS per eight MFMAs instead of
+// four per four), 80 KB of LDS: one block per CU, two wavefronts per SIMD.  A layer with 256 output channels reads its
+// activations exactly once.  The column tiles of a row tile again take consecutive slots of one XCD.  Measured at
+// 262 144 pixels, bf16: 1024 -> 256 channels 222 -> 184 us, its data gradient 213 -> 170 us, 256 -> 1024 channels
+// 300 -> 265 us; tiles of 128 x 256 and 256 x 128 with two blocks per CU lie between (195-202 us on the first).
+constexpr int PWL_BM = 256, PWL_BN = 256;
+
+template <int BM, int BN> constexpr size_t pwl_smem_bytes() {
+  constexpr size_t stages = (size_t)2 * (BM + BN) * PW_PITCH * 2;
+  constexpr size_t epi = (size_t)64 * (BN + 4) * 4;
+  return stages > epi ? stages : epi;
+}
+
+// BM x BN tile, WGM x WGN wavefronts (wave tile BM / WGM x BN / WGN, at least 64 rows)
+template <class T, bool DGRAD, int BM, int BN, int WGM, int WGN>
+__global__ void __launch_bounds__(64 * WGM * WGN) __attribute__((amdgpu_waves_per_eu(2, 2)))
+conv1x1_large_kernel(const T* __restrict__ X, const T* __restrict__ W, const float* __restrict__ bias,
+                     const T* __restrict__ addend, T* __restrict__ out, float* __restrict__ stat_partial, PwArgs a) {
+  typedef typename Mma<T>::V FV;
+  constexpr int NT = 64 * WGM * WGN, BK = PW_BK, PITCH = PW_PITCH;
+  constexpr int WTM = BM / WGM, WTN = BN / WGN;       // wave tile
+  constexpr int MI = WTM / 32, NI = WTN / 32;
+  static_assert(WTM >= 64 && WTM % 64 == 0, "the epilogue moves 64 rows of one wavefront row at a time");
+  constexpr int A_CH = BM * 4 / NT;        // 16-byte chunks per thread and depth step
+  constexpr int B_CH = BN * 4 / NT;
+  constexpr int RSTEP = NT / 4;            // rows between a thread's chunks
+  constexpr int STAGE = (BM + BN) * PITCH;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  T* lds = reinterpret_cast<T*>(smem_raw);
+
+  // slot s of XCD x: column tile s % NT of row tile (s / NT) * 8 + x
+  const int b = blockIdx.x, xcd = b & 7, slot = b >> 3;
+  const int nt = slot % a.NT, mt = (slot / a.NT) * 8 + xcd;
+  if (mt >= a.MT) return;
+  const int64_t m0 = (int64_t)mt * BM;
+  const int n0 = nt * BN;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WGN, wn = wave % WGN, g = lane >> 5, l32 = lane & 31;
+  const int vec = tid & 3, row0 = tid >> 2;
+  const int Kd = a.Kd;
+
+  // Rows past the last pixel read row 0; they are never stored and add nothing to the sums.
+  const T* arow[A_CH];
+#pragma unroll
+  for (int i = 0; i < A_CH; ++i) {
+    const int64_t m = m0 + row0 + i * RSTEP;
+    arow[i] = X + (m < a.M ? m : 0) * Kd + vec * 8;
+  }
+  const T* brow[B_CH];
+#pragma unroll
+  for (int i = 0; i < B_CH; ++i) brow[i] = W + (int64_t)(n0 + row0 + i * RSTEP) * Kd + vec * 8;
+
+  Chunk ra[2][A_CH], rb[2][B_CH];
+  auto gload = [&](auto P, int kt) {
+    constexpr int p = decltype(P)::value;
+#pragma unroll
+    for (int i = 0; i < A_CH; ++i) ra[p][i] = *reinterpret_cast<const Chunk*>(arow[i] + kt * BK);
+#pragma unroll
+    for (int i = 0; i < B_CH; ++i) rb[p][i] = *reinterpret_cast<const Chunk*>(brow[i] + kt * BK);
+  };
+  auto sstore = [&](auto P, int stage) {
+    constexpr int p = decltype(P)::value;
+    T* st = lds + stage * STAGE;
+#pragma unroll
+    for (int i = 0; i < A_CH; ++i) *reinterpret_cast<Chunk*>(&st[(row0 + i * RSTEP) * PITCH + vec * 8]) = ra[p][i];
+#pragma unroll
+    for (int i = 0; i < B_CH; ++i) *reinterpret_cast<Chunk*>(&st[(BM + row0 + i * RSTEP) * PITCH + vec * 8]) = rb[p][i];
+  };
+
+  v16f acc[MI][NI];
+#pragma unroll
+  for (int i = 0; i < MI; ++i)
+#pragma unroll
+    for (int j = 0; j < NI; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+  const int afrag = (wm * WTM + l32) * PITCH + g * 16;
+  const int bfrag = (BM + wn * WTN + l32) * PITCH + g * 16;
+  auto compute = [&](int stage) {
+    const T* st = lds + stage * STAGE;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      FV fa[MI], fb[NI];
+#pragma unroll
+      for (int i = 0; i < MI; ++i) fa[i] = *reinterpret_cast<const FV*>(st + afrag + i * 32 * PITCH + h * 8);
+#pragma unroll
+      for (int j = 0; j < NI; ++j) fb[j] = *reinterpret_cast<const FV*>(st + bfrag + j * 32 * PITCH + h * 8);
+#pragma unroll
+      for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NI; ++j) acc[i][j] = Mma<T>::run(fa[i], fb[j], acc[i][j]);
+    }
+  };
+
+  // The two-generation pipeline of conv1x1_kernel as one uniform loop (an even number of depth steps): the last two
+  // refills load the last tile again (the same addresses, just read) and are never used -- peeled steps without the
+  // loads cost this kernel, which holds 128 accumulator registers, a few hundred spilled registers per thread.  (Four
+  // tiles in flight instead of two changed nothing: 187 against 184 us on 1024 -> 256 channels at 262 144 pixels.)
+  const int n = Kd / BK;  // even, >= 2
+  gload(IC<0>{}, 0);
+  gload(IC<1>{}, 1);
+  for (int j = 0; j < n; j += 2) {
+    const int t2 = j + 2 < n ? j + 2 : n - 1, t3 = j + 3 < n ? j + 3 : n - 1;
+    sstore(IC<0>{}, 0); gload(IC<0>{}, t2); __syncthreads(); compute(0);
+    sstore(IC<1>{}, 1); gload(IC<1>{}, t3); __syncthreads(); compute(1);
+  }
+
+  // ---- epilogue: 64 rows at a time through LDS as fp32 [64][BN + 4] (the rows of the four wavefronts with wm = pass / 2,
+  // their 32-row tiles 2 * (pass & 1) and + 1), stored by all 512 threads ------------------------------------------------
+  float* ep = reinterpret_cast<float*>(smem_raw);
+  constexpr int EP_PITCH = BN + 4;
+  float ss[8], qq[8];
+#pragma unroll
+  for (int k = 0; k < 8; ++k) { ss[k] = 0.f; qq[k] = 0.f; }
+#pragma unroll
+  for (int pass = 0; pass < BM / 64; ++pass) {
+    __syncthreads();
+    if (wm == pass * 64 / WTM) {
+#pragma unroll
+      for (int ii = 0; ii < 2; ++ii)
+#pragma unroll
+        for (int jn = 0; jn < NI; ++jn)
+#pragma unroll
+          for (int e = 0; e < 16; ++e)
+            ep[(ii * 32 + 8 * (e >> 2) + 4 * g + (e & 3)) * EP_PITCH + wn * WTN + jn * 32 + l32] =
+                acc[(pass * 64 % WTM) / 32 + ii][jn][e];
+    }
+    __syncthreads();
+    auto rowoff = [&](int row) -> int64_t {
+      const int64_t grow = m0 + pass * 64 + row;
+      return grow < a.M ? grow * a.Ng : -1;
+    };
+    if (DGRAD) {
+      epi_store_pass_nt<NT, T, BN, 64, false, true, false>(ep, tid, n0, bias, addend, out, 0, rowoff, ss, qq);
+    } else {
+      if (stat_partial) epi_store_pass_nt<NT, T, BN, 64, true, false, true>(ep, tid, n0, bias, addend, out, a.relu, rowoff, ss, qq);
+      else epi_store_pass_nt<NT, T, BN, 64, true, false, false>(ep, tid, n0, bias, addend, out, a.relu, rowoff, ss, qq);
+    }
+  }
+  if (!DGRAD && stat_partial)
+    epi_stat_combine_nt<NT, BN>(ep, tid, ss, qq, stat_partial + ((int64_t)mt * 2 + 0) * a.Ng + n0,
+                                stat_partial + ((int64_t)mt * 2 + 1) * a.Ng + n0);
+}
+
+template <class T, bool DGRAD, int BM, int BN, int WGM, int WGN>
+void launch_pw_large(hipStream_t st, const void* X, const void* W, const float* bias, const void* addend, void* out,
+                     float* stat_partial, PwArgs a) {
+  constexpr size_t sm = pwl_smem_bytes<BM, BN>();
+  static bool attr_done = false;
+  if (!attr_done) {
+    (void)hipFuncSetAttribute((const void*)conv1x1_large_kernel<T, DGRAD, BM, BN, WGM, WGN>,
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)sm);
+    attr_done = true;
+  }
+  a.MT = ceil_div(a.M, BM);
+  a.NT = a.Ng / BN;
+  const int grid = ((a.MT + 7) / 8) * 8 * a.NT;
+  OSEQ_LAUNCH((conv1x1_large_kernel<T, DGRAD, BM, BN, WGM, WGN>), dim3(grid), dim3(64 * WGM * WGN), sm, st, (const T*)X,
+              (const T*)W, bias, (const T*)addend, (T*)out, stat_partial, a);
+}
+
+// The 256 x 256 tile is taken when the layer still gives every CU two blocks of it (from the shape only).
+bool pw_large_ok(int64_t M, int Ng, int Kd, int stride, bool scatter) {
+  if (stride != 1 || scatter || Ng % PWL_BN != 0 || Kd % (2 * PW_BK) != 0) return false;
+  return (int64_t)ceil_div(M, PWL_BM) * (Ng / PWL_BN) >= 512;
+}
+
 template <class T, int BN, bool DGRAD>
 void launch_pw_v(hipStream_t st, const void* X, const void* W, const float* bias, const void* addend, void* out,
                  float* stat_partial, const PwArgs& a) {
@@ -277,6 +450,18 @@ void launch_pw_t(hipStream_t st, bool dgrad, int bn, const void* X, const void* 
 
 void launch_pw(hipStream_t st, int dt, bool dgrad, const void* X, const void* W, const float* bias, const void* addend,
                void* out, float* stat_partial, PwArgs a) {
+  // (a data gradient that adds a residual stays with the small tile: one block per CU has nobody to cover the latency
+  // of the addend loads in its epilogue -- 332 against 313 us on 256 -> 1024 channels at 262 144 pixels)
+  if (pw_large_ok(a.M, a.Ng, a.Kd, a.stride, a.scatter != 0) && !(dgrad && addend)) {
+    if (dt == DT_BF16) {
+      if (dgrad) launch_pw_large<bf16_t, true, PWL_BM, PWL_BN, 2, 4>(st, X, W, bias, addend, out, stat_partial, a);
+      else launch_pw_large<bf16_t, false, PWL_BM, PWL_BN, 2, 4>(st, X, W, bias, addend, out, stat_partial, a);
+    } else {
+      if (dgrad) launch_pw_large<f16_t, true, PWL_BM, PWL_BN, 2, 4>(st, X, W, bias, addend, out, stat_partial, a);
+      else launch_pw_large<f16_t, false, PWL_BM, PWL_BN, 2, 4>(st, X, W, bias, addend, out, stat_partial, a);
+    }
+    return;
+  }
   const int bn = a.Ng % 128 == 0 ? 128 : 64;
   a.MT = ceil_div(a.M, PW_BM);
   a.NT = a.Ng / bn;
@@ -311,7 +496,10 @@ bool conv_pointwise_dgrad_ok(int dt, const ConvGeom& g) {
   if (g.stride != 1) return false;
   return pw_shape_ok(dt, (int64_t)g.N * g.H * g.W, g.C, g.K, g_pointwise_min_blocks);
 }
-int conv_pointwise_stat_blocks(const ConvGeom& g) { return ceil_div((int64_t)g.N * g.P * g.Q, PW_BM); }
+int conv_pointwise_stat_blocks(const ConvGeom& g) {
+  const int64_t M = (int64_t)g.N * g.P * g.Q;
+  return ceil_div(M, pw_large_ok(M, g.K, g.C, g.stride, false) ? PWL_BM : PW_BM);
+}
 
 void launch_conv_fwd_pointwise(hipStream_t st, int dt, const void* x, const void* w, const float* bias, void* out,
                                float* stat_partial, const ConvGeom& g, int relu) {

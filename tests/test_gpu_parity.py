@@ -93,6 +93,10 @@ LAYER_NETS = {
     "pointwise_stride2_bias": (64, 32, 64, [W.conv(64, 64, ksize=1), W.conv(64, 128, ksize=1, stride=2),
                                             W.conv(128, 128, ksize=1, bn=False), W.gap_linear_ce(128, 10)]),
     "pointwise_bottleneck_s2": (64, 32, 64, [W.conv(64, 64, ksize=1), W.bottleneck(64, 256, 2), W.gap_linear_ce(256, 10)]),
+    # enough pixels for the 256 x 256 tile of that kernel (515 row tiles, the last one ragged): forward with and without
+    # BatchNorm sums, data gradient with 256 channels
+    "pointwise_large_tile": (64, 33, 121, [W.conv(64, 256, ksize=1), W.conv(256, 256, ksize=1), W.conv(256, 256, ksize=1, bn=False),
+                                           W.gap_linear_ce(256, 10)]),
     "pointwise_bottlenecks": (64, 16, 64, [W.conv(64, 64, ksize=1), W.bottleneck(64, 256, 1), W.bottleneck(256, 512, 2),
                                            W.gap_linear_ce(512, 10)]),
 }
@@ -102,6 +106,8 @@ LAYER_NETS = {
 @pytest.mark.parametrize("precision", [W.FP32, W.BF16, W.FP16])
 def test_layers_at_benchmark_shapes_match_oracle(name, precision):
     cin, hw, b, units = LAYER_NETS[name]
+    if precision == W.FP32 and name == "pointwise_large_tile":
+        pytest.skip("the 256 x 256 tile exists in the 16-bit modes only")
     p, x, y = _inputs(units, b, hw, hw, 10, seed=9, channels=cin)
     r, info = gpu_step(units, p, x, y, precision=precision, k=2, classes=10, loss_scale_init=_scale(precision))
     assert not r["skipped"]
@@ -136,6 +142,7 @@ SINGLE_CONVS = {
     "c1x1_2048_512_at2": (2048, 512, 1, 1, 2, 32),
     "c1x1_s2_256_512": (256, 512, 1, 2, 16, 32),
     "c1x1_s2_64_128": (64, 128, 1, 2, 32, 16),
+    "c1x1_256_256_large_tile": (256, 256, 1, 1, 33, 121),
 }
 
 
