@@ -10,8 +10,11 @@
 // this reads dz once instead of nine times and x about twice instead of nine times, which is what bounds the
 // 16-bit kernel (the path from L2 to LDS), and it leaves nine MFMAs per operand fetch.
 //
-//   block = 4 wavefronts (2 x 2): wavefront (wm, wn) owns k rows [wm*32*MI, +32*MI) and c columns [wn*32, +32) of
-//   every tap: MI x 9 accumulator tiles of 32x32.
+//   block = WGM x 2 wavefronts: wavefront (wm, wn) owns k rows [wm*32*MI, +32*MI) and c columns [wn*32, +32) of
+//   every tap: MI x 9 accumulator tiles of 32x32.  64 output channels: 2 x 2 wavefronts, one per SIMD.  128 output
+//   channels (16-bit modes): 4 x 2 wavefronts with MI = 1, two per SIMD (144 accumulator registers each), so that one
+//   wavefront's LDS reads and address arithmetic run under the other's MFMAs: 256 -> 256 channels at 8 x 8, batch
+//   4096, bf16: 481 us with 2 x 2 wavefronts of MI = 2, 326 us with 4 x 2 (the one-tap-per-block kernel: 479 us).
 //   fp32: MFMA 32x32x2, lanes read single floats of the pixel-major tiles (channel = lane).
 //   16-bit: MFMA 32x32x16, operands come from the transposing LDS read (ds_read_b64_tr_b16), whose per-lane row
 //   addresses make the tap shift a plain change of address.
@@ -22,7 +25,7 @@
 
 namespace oseq {
 
-static constexpr int g_w9_wide_min = 8;  // compile-time constant: fewest sub-tiles per block for 128-channel blocks
+static constexpr int g_w9_wide_min = 4;  // compile-time constant: fewest sub-tiles per block for 128-channel blocks
 
 namespace {
 
@@ -44,10 +47,11 @@ template <> struct W9Cfg<float> { static constexpr int CAP = 64, MAXPOS = 144; }
 template <> struct W9Cfg<bf16_t> { static constexpr int CAP = 128, MAXPOS = 256; };
 template <> struct W9Cfg<f16_t> { static constexpr int CAP = 128, MAXPOS = 256; };
 
-template <class T, int MI> struct W9Lds {
+// WGM wavefront rows of 32 * MI output channels each (2 wavefront columns of 32 input channels): 64 * WGM threads
+template <class T, int MI, int WGM> struct W9Lds {
   static constexpr bool F32 = sizeof(T) == 4;
   static constexpr int CAP = W9Cfg<T>::CAP, MAXPOS = W9Cfg<T>::MAXPOS;
-  static constexpr int BMK = 64 * MI;
+  static constexpr int BMK = 32 * MI * WGM;
   static constexpr int PX = F32 ? 64 : 80;          // elements per staged x position (16-bit: 32 bytes of padding)
   static constexpr int PK = F32 ? BMK : BMK + 16;   // elements per staged dz pixel
   static constexpr int XS = MAXPOS * PX, DS = CAP * PK, STAGE = XS + DS;
@@ -74,16 +78,17 @@ __device__ __forceinline__ typename V8<T>::type tr_read8(const T* p0, const T* p
   return __builtin_bit_cast(typename V8<T>::type, r);
 }
 
-template <class T, int MI>
-__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
+template <class T, int MI, int WGM>
+__global__ void __launch_bounds__(128 * WGM) __attribute__((amdgpu_waves_per_eu(WGM / 2, WGM / 2)))
 conv_wgrad3x3_kernel(const T* __restrict__ x, const T* __restrict__ dz, float* __restrict__ out, W9Args a) {
-  typedef W9Lds<T, MI> L;
+  typedef W9Lds<T, MI, WGM> L;
   constexpr bool F32 = L::F32;
+  constexpr int NTH = 128 * WGM;                          // threads
   constexpr int CAP = L::CAP, MAXPOS = L::MAXPOS, BMK = L::BMK, PX = L::PX, PK = L::PK;
   constexpr int EV = 16 / (int)sizeof(T);
   constexpr int XCP = 64 / EV, DCP = BMK / EV;            // 16-byte chunks per x position / dz pixel
-  constexpr int XSLOTS = (MAXPOS * XCP + 255) / 256;      // chunks per thread and sub-tile
-  constexpr int DSLOTS = CAP * DCP / 256;
+  constexpr int XSLOTS = (MAXPOS * XCP + NTH - 1) / NTH;  // chunks per thread and sub-tile
+  constexpr int DSLOTS = CAP * DCP / NTH;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   T* lds = reinterpret_cast<T*>(smem_raw);
   int* apos = reinterpret_cast<int*>(lds + 2 * L::STAGE);
@@ -98,7 +103,7 @@ conv_wgrad3x3_kernel(const T* __restrict__ x, const T* __restrict__ dz, float* _
   const int nst = t1 > t0 ? t1 - t0 : 0;
 
   // position of tap (0,0) in the staged x tile for every pixel of a sub-tile (the same for all sub-tiles)
-  for (int m = tid; m < CAP; m += 256) {
+  for (int m = tid; m < CAP; m += NTH) {
     int ap = 0;
     if (m < TP) {
       const int ti = m / (TR * TC), rr = m - ti * (TR * TC);
@@ -112,7 +117,7 @@ conv_wgrad3x3_kernel(const T* __restrict__ x, const T* __restrict__ dz, float* _
   int xinfo[XSLOTS], dinfo[DSLOTS];
 #pragma unroll
   for (int sl = 0; sl < XSLOTS; ++sl) {
-    const int idx = sl * 256 + tid, pos = idx / XCP;
+    const int idx = sl * NTH + tid, pos = idx / XCP;
     int info = -1;
     if (pos < NPOS) {
       const int ti = pos / (a.SR * SC), rr = pos - ti * (a.SR * SC);
@@ -123,7 +128,7 @@ conv_wgrad3x3_kernel(const T* __restrict__ x, const T* __restrict__ dz, float* _
   }
 #pragma unroll
   for (int sl = 0; sl < DSLOTS; ++sl) {
-    const int idx = sl * 256 + tid, m = idx / DCP;
+    const int idx = sl * NTH + tid, m = idx / DCP;
     int info = -1;
     if (m < TP) {
       const int ti = m / (TR * TC), rr = m - ti * (TR * TC);
@@ -146,7 +151,7 @@ conv_wgrad3x3_kernel(const T* __restrict__ x, const T* __restrict__ dz, float* _
       const int info = xinfo[sl];
       const int n = nb + (info >> 20), y = yb - pad + ((info >> 10) & 1023), xx = xb - pad + (info & 1023);
       const bool ok = info >= 0 && n < N && y >= 0 && y < H && xx >= 0 && xx < W;
-      const int v = (sl * 256 + tid) % XCP;
+      const int v = (sl * NTH + tid) % XCP;
       const int64_t off = ok ? (((int64_t)n * H + y) * W + xx) * C : 0;
       xr[sl] = *reinterpret_cast<const Chunk*>(x + off + c0 + v * EV);
       xm |= ok ? (1u << sl) : 0u;
@@ -156,7 +161,7 @@ conv_wgrad3x3_kernel(const T* __restrict__ x, const T* __restrict__ dz, float* _
       const int info = dinfo[sl];
       const int n = nb + (info >> 20), p = yb + ((info >> 10) & 1023), q = xb + (info & 1023);
       const bool ok = info >= 0 && n < N && p < P && q < Q;
-      const int v = (sl * 256 + tid) % DCP;
+      const int v = (sl * NTH + tid) % DCP;
       const int64_t off = ok ? (((int64_t)n * P + p) * Q + q) * K : 0;
       dr[sl] = *reinterpret_cast<const Chunk*>(dz + off + k0 + v * EV);
       dm |= ok ? (1u << sl) : 0u;
@@ -168,12 +173,12 @@ conv_wgrad3x3_kernel(const T* __restrict__ x, const T* __restrict__ dz, float* _
     T* ds = xs + L::XS;
 #pragma unroll
     for (int sl = 0; sl < XSLOTS; ++sl) {
-      const int idx = sl * 256 + tid, pos = idx / XCP, v = idx - pos * XCP;
+      const int idx = sl * NTH + tid, pos = idx / XCP, v = idx - pos * XCP;
       if (pos < MAXPOS) *reinterpret_cast<Chunk*>(&xs[pos * PX + v * EV]) = ((xok >> sl) & 1u) ? xr[sl] : zero_chunk();
     }
 #pragma unroll
     for (int sl = 0; sl < DSLOTS; ++sl) {
-      const int idx = sl * 256 + tid, m = idx / DCP, v = idx - m * DCP;
+      const int idx = sl * NTH + tid, m = idx / DCP, v = idx - m * DCP;
       *reinterpret_cast<Chunk*>(&ds[m * PK + v * EV]) = ((dok >> sl) & 1u) ? dr[sl] : zero_chunk();
     }
   };
@@ -284,7 +289,7 @@ bool w9_geometry(int N, int P, int Q, int cap, int maxpos, W9Args& a) {
 struct W9Plan { W9Args a; int mi, splits; };
 bool w9_plan(int dt, const ConvGeom& g, W9Plan& pl) {
   if (g.R != 3 || g.S != 3 || g.stride != 1 || g.C % 64 != 0 || g.K % 64 != 0) return false;
-  if (g.N >= 2048 || g.H >= 1024 || g.W >= 1024) return false;  // packed (image, row, column) fields
+  if (g.H >= 1024 || g.W >= 1024) return false;  // packed (image within the sub-tile, row, column) fields
   const int cap = dt == DT_F32 ? W9Cfg<float>::CAP : W9Cfg<bf16_t>::CAP;
   const int maxpos = dt == DT_F32 ? W9Cfg<float>::MAXPOS : W9Cfg<bf16_t>::MAXPOS;
   W9Args a{};
@@ -294,7 +299,9 @@ bool w9_plan(int dt, const ConvGeom& g, W9Plan& pl) {
   // fp32: 64 output channels per block.  16-bit: 128 when possible (fewer operand fetches per MFMA), unless the blocks
   // would then get fewer than g_w9_wide_min sub-tiles each: a block's accumulators (9 taps x 64*MI x 64 floats) are
   // written out once per pixel range and read again by the reduction, and with few sub-tiles per range that traffic
-  // outweighs the operand reuse (128->128 at 16x16, batch 256, bf16: 55 -> 49 us with 64; batch 1024: 132 vs 140 us).
+  // outweighs the operand reuse (128->128 at 16x16, batch 256, bf16: 49.6 us with 64-channel blocks, 48.1 with
+  // 128-channel blocks of four sub-tiles each).  At that size the 75 MB of partial sums written and read back are most
+  // of the time: 19 GFLOP would take 8 us at the matrix cores' peak.
   for (int mi = (dt != DT_F32 && g.K % 128 == 0) ? 2 : 1; mi >= 1; --mi) {
     const int64_t tiles = (int64_t)(g.K / (64 * mi)) * (g.C / 64);
     int64_t s = tiles >= 256 ? 1 : (256 + tiles / 2) / tiles;  // about one block per CU
@@ -311,16 +318,16 @@ bool w9_plan(int dt, const ConvGeom& g, W9Plan& pl) {
   return false;
 }
 
-template <class T, int MI>
+template <class T, int MI, int WGM>
 void launch_w9(hipStream_t st, const void* x, const void* dz, float* dst, const W9Plan& pl) {
-  constexpr size_t sm = W9Lds<T, MI>::bytes;
+  constexpr size_t sm = W9Lds<T, MI, WGM>::bytes;
   static bool attr_done = false;
   if (!attr_done) {
-    (void)hipFuncSetAttribute((const void*)conv_wgrad3x3_kernel<T, MI>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sm);
+    (void)hipFuncSetAttribute((const void*)conv_wgrad3x3_kernel<T, MI, WGM>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sm);
     attr_done = true;
   }
-  dim3 grid(pl.a.K / (64 * MI), pl.a.C / 64, pl.splits), block(256);
-  OSEQ_LAUNCH((conv_wgrad3x3_kernel<T, MI>), grid, block, sm, st, (const T*)x, (const T*)dz, dst, pl.a);
+  dim3 grid(pl.a.K / (32 * MI * WGM), pl.a.C / 64, pl.splits), block(128 * WGM);
+  OSEQ_LAUNCH((conv_wgrad3x3_kernel<T, MI, WGM>), grid, block, sm, st, (const T*)x, (const T*)dz, dst, pl.a);
 }
 
 }  // namespace
@@ -341,9 +348,10 @@ int conv_wgrad3x3_splits(int dt, const ConvGeom& g) {
 void launch_conv_wgrad3x3(hipStream_t st, int dt, const void* x, const void* dz, float* dst, const ConvGeom& g) {
   W9Plan pl;
   if (!w9_plan(dt, g, pl)) return;
-  if (dt == DT_F32) launch_w9<float, 1>(st, x, dz, dst, pl);
-  else if (dt == DT_BF16) { if (pl.mi == 2) launch_w9<bf16_t, 2>(st, x, dz, dst, pl); else launch_w9<bf16_t, 1>(st, x, dz, dst, pl); }
-  else { if (pl.mi == 2) launch_w9<f16_t, 2>(st, x, dz, dst, pl); else launch_w9<f16_t, 1>(st, x, dz, dst, pl); }
+  // 128 output channels per block in the 16-bit modes: four wavefront rows of 32 channels (eight wavefronts, two per SIMD)
+  if (dt == DT_F32) launch_w9<float, 1, 2>(st, x, dz, dst, pl);
+  else if (dt == DT_BF16) { if (pl.mi == 2) launch_w9<bf16_t, 1, 4>(st, x, dz, dst, pl); else launch_w9<bf16_t, 1, 2>(st, x, dz, dst, pl); }
+  else { if (pl.mi == 2) launch_w9<f16_t, 1, 4>(st, x, dz, dst, pl); else launch_w9<f16_t, 1, 2>(st, x, dz, dst, pl); }
 }
 
 }  // namespace oseq
