@@ -1102,21 +1102,32 @@ __device__ __forceinline__ v8s tr_read8(const T* p0, const T* p1) {
   return r;
 }
 
-template <class T, int BM, int BN>
-__global__ void __launch_bounds__(256) conv_wgrad_kernel(const T* __restrict__ x, const T* __restrict__ dz,
-                                                         float* __restrict__ out, WGradArgs a) {
+// WGM x WGN wavefronts (wave tile BM / WGM x BN / WGN); the 256 x 256 tile of the 1x1 layers with many pixels runs 2 x 4
+// wavefronts, two per SIMD, one block per CU: every operand element then crosses from L2 to a CU half as often as with
+// 128 x 128 tiles (a 1024 x 256 weight gradient over 262 144 pixels moves 1.07 GB instead of 2.1 GB that way).
+template <class T, int BM, int BN, int WGM>
+constexpr size_t wgrad_lds_bytes() {
+  return (size_t)3 * (sizeof(T) == 4 ? 16 : 32) * (BM + BN + 2 * (sizeof(T) == 4 ? 4 : 16)) * sizeof(T);
+}
+
+template <class T, int BM, int BN, int WGM = 2, int WGN = 2>
+__global__ void __launch_bounds__(64 * WGM * WGN) conv_wgrad_kernel(const T* __restrict__ x, const T* __restrict__ dz,
+                                                                    float* __restrict__ out, WGradArgs a) {
   constexpr bool F32 = sizeof(T) == 4;
   constexpr int DEPTH = F32 ? 16 : 32;
-  constexpr int MI = BM / 64, NI = BN / 64;
+  constexpr int NT = 64 * WGM * WGN;
+  constexpr int WTM = BM / WGM, WTN = BN / WGN;
+  constexpr int MI = WTM / 32, NI = WTN / 32;
   // one LDS stage, pixel-major exactly as loaded: [DEPTH][BM + pad] then [DEPTH][BN + pad] (pad: 4 floats / 16 halves)
   constexpr int PADE = F32 ? 4 : 16;
   constexpr int A_ELEMS = DEPTH * (BM + PADE);
   constexpr int B_ELEMS = DEPTH * (BN + PADE);
   constexpr int STAGE = A_ELEMS + B_ELEMS;
-  __shared__ __attribute__((aligned(16))) T lds[3 * STAGE];
+  extern __shared__ __attribute__((aligned(16))) unsigned char wgrad_smem[];
+  T* lds = reinterpret_cast<T*>(wgrad_smem);
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1, g = lane >> 5, l32 = lane & 31;
+  const int wm = wave / WGN, wn = wave % WGN, g = lane >> 5, l32 = lane & 31;
   const int k0 = blockIdx.x * BM;
   const int ctiles = a.C / BN;
   const int tap = blockIdx.y / ctiles, c0 = (blockIdx.y - tap * ctiles) * BN;
@@ -1129,7 +1140,8 @@ __global__ void __launch_bounds__(256) conv_wgrad_kernel(const T* __restrict__ x
 
   // staging: 16-byte chunks, rows = pixels (EV elements per chunk)
   constexpr int EV = 16 / (int)sizeof(T);
-  constexpr int A_CH32 = DEPTH * (BM / EV) / 256, B_CH32 = DEPTH * (BN / EV) / 256;
+  constexpr int A_CH32 = DEPTH * (BM / EV) / NT, B_CH32 = DEPTH * (BN / EV) / NT;
+  static_assert(A_CH32 >= 1 && B_CH32 >= 1, "tile too small for the block");
   Chunk ra[2][A_CH32], rb[2][B_CH32];
   unsigned va[2] = {0u, 0u}, vb[2] = {0u, 0u};  // validity bits of the pieces in flight, per generation
 
@@ -1147,7 +1159,7 @@ __global__ void __launch_bounds__(256) conv_wgrad_kernel(const T* __restrict__ x
     unsigned ma = 0u, mb = 0u;
 #pragma unroll
     for (int i = 0; i < A_CH32; ++i) {
-      const int id = tid + i * 256, px = id / (BM / EV), kv = id % (BM / EV);
+      const int id = tid + i * NT, px = id / (BM / EV), kv = id % (BM / EV);
       const int m = mt + px;
       const bool ok = m < mend;
       ra[p][i] = *reinterpret_cast<const Chunk*>(dz + (int64_t)(ok ? m : mbeg) * K + k0 + kv * EV);
@@ -1155,7 +1167,7 @@ __global__ void __launch_bounds__(256) conv_wgrad_kernel(const T* __restrict__ x
     }
 #pragma unroll
     for (int i = 0; i < B_CH32; ++i) {
-      const int id = tid + i * 256, px = id / (BN / EV), cv = id % (BN / EV);
+      const int id = tid + i * NT, px = id / (BN / EV), cv = id % (BN / EV);
       const int m = mt + px;
       const int mm = m < mend ? m : mbeg;
       const uint32_t n_ = divPQ.div((uint32_t)mm), rem = (uint32_t)mm - n_ * divPQ.d;
@@ -1173,12 +1185,12 @@ __global__ void __launch_bounds__(256) conv_wgrad_kernel(const T* __restrict__ x
     T* sb = sa + A_ELEMS;
 #pragma unroll
     for (int i = 0; i < A_CH32; ++i) {
-      const int id = tid + i * 256, px = id / (BM / EV), kv = id % (BM / EV);
+      const int id = tid + i * NT, px = id / (BM / EV), kv = id % (BM / EV);
       *reinterpret_cast<Chunk*>(&sa[px * (BM + PADE) + kv * EV]) = ((va[p] >> i) & 1u) ? ra[p][i] : zero_chunk();
     }
 #pragma unroll
     for (int i = 0; i < B_CH32; ++i) {
-      const int id = tid + i * 256, px = id / (BN / EV), cv = id % (BN / EV);
+      const int id = tid + i * NT, px = id / (BN / EV), cv = id % (BN / EV);
       *reinterpret_cast<Chunk*>(&sb[px * (BN + PADE) + cv * EV]) = ((vb[p] >> i) & 1u) ? rb[p][i] : zero_chunk();
     }
   };
@@ -1194,7 +1206,7 @@ __global__ void __launch_bounds__(256) conv_wgrad_kernel(const T* __restrict__ x
   // operand registers: fp32 8 scalars per 32-row tile (pixels g*8 .. g*8+7 of the depth tile), 16-bit a 32-byte slice
   float fa32[F32 ? MI : 1][8], fb32[F32 ? NI : 1][8];
   Frag<T> fa[F32 ? 1 : MI], fb[F32 ? 1 : NI];
-  const int acol = wm * (BM / 2) + l32, bcol = wn * (BN / 2) + l32;
+  const int acol = wm * WTM + l32, bcol = wn * WTN + l32;
   auto load_half = [&](int half, int stage) {
     const T* sa = lds + stage * STAGE;
     const T* sb = sa + A_ELEMS;
@@ -1218,13 +1230,13 @@ __global__ void __launch_bounds__(256) conv_wgrad_kernel(const T* __restrict__ x
       const int coff = (l32 & 16) + 4 * (r16 & 3);
 #pragma unroll
       for (int i = 0; i < MI; ++i) {
-        const T* pp = sa + kbase * (BM + PADE) + wm * (BM / 2) + i * 32 + coff;
+        const T* pp = sa + kbase * (BM + PADE) + wm * WTM + i * 32 + coff;
         const v8s v = tr_read8(pp, pp + 4 * (BM + PADE));
         if (half == 0) fa[i].lo = __builtin_bit_cast(decltype(fa[i].lo), v); else fa[i].hi = __builtin_bit_cast(decltype(fa[i].hi), v);
       }
 #pragma unroll
       for (int j = 0; j < NI; ++j) {
-        const T* pp = sb + kbase * (BN + PADE) + wn * (BN / 2) + j * 32 + coff;
+        const T* pp = sb + kbase * (BN + PADE) + wn * WTN + j * 32 + coff;
         const v8s v = tr_read8(pp, pp + 4 * (BN + PADE));
         if (half == 0) fb[j].lo = __builtin_bit_cast(decltype(fb[j].lo), v); else fb[j].hi = __builtin_bit_cast(decltype(fb[j].hi), v);
       }
@@ -1293,10 +1305,10 @@ __global__ void __launch_bounds__(256) conv_wgrad_kernel(const T* __restrict__ x
   for (int i = 0; i < MI; ++i)
 #pragma unroll
     for (int j = 0; j < NI; ++j) {
-      const int c = c0 + wn * (BN / 2) + j * 32 + l32;
+      const int c = c0 + wn * WTN + j * 32 + l32;
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
-        const int k = k0 + wm * (BM / 2) + i * 32 + 8 * (e >> 2) + 4 * g + (e & 3);
+        const int k = k0 + wm * WTM + i * 32 + 8 * (e >> 2) + 4 * g + (e & 3);
         dst[((int64_t)k * a.R * a.S + tap) * C + c] = acc[i][j][e];
       }
     }
@@ -1315,8 +1327,24 @@ static constexpr int g_wgrad_blocks = 1024;  // compile-time constants
 static constexpr int g_wgrad_max_splits = 64;
 static constexpr int g_wgrad_blocks_1x1 = 512;
 static constexpr int g_wgrad_max_splits_1x1 = 256;
+// 1x1 layers in the 16-bit modes whose channel counts are multiples of 256 and that have at least 64 K pixels take the
+// 256 x 256 tile: one block per CU (256 blocks), every pixel range at least 16 depth tiles long
+static bool wgrad_large_ok(int dt, const ConvGeom& g) {
+  return dt != DT_F32 && g.R * g.S == 1 && g.K % 256 == 0 && g.C % 256 == 0 && (int64_t)g.N * g.P * g.Q >= 65536;
+}
+static int wgrad_large_splits(const ConvGeom& g) {
+  const int64_t tiles = (int64_t)(g.K / 256) * (g.C / 256);
+  const int64_t pixels = (int64_t)g.N * g.P * g.Q;
+  int64_t want = tiles >= 256 ? 1 : (256 + tiles / 2) / tiles;
+  const int64_t most = pixels / (16 * 32);
+  if (want > most) want = most;
+  if (want > 256) want = 256;
+  return (int)(want < 1 ? 1 : want);
+}
+
 int conv_mfma_wgrad_splits(int dt, const ConvGeom& g) {
   if (conv_wgrad3x3_ok(dt, g)) return conv_wgrad3x3_splits(dt, g);
+  if (wgrad_large_ok(dt, g)) return wgrad_large_splits(g);
   const int depth = dt == DT_F32 ? 16 : 32;
   const int bm = g.K % 128 == 0 ? 128 : 64, bn = g.C % 128 == 0 ? 128 : 64;
   const int64_t tiles = (int64_t)(g.K / bm) * (g.C / bn) * g.R * g.S;
@@ -1341,13 +1369,26 @@ static void launch_wgrad_t(hipStream_t st, const void* x, const void* dz, float*
   a.chunk = (chunk + depth - 1) / depth * depth;
   a.divQ = make_fastdiv((uint32_t)g.Q);
   a.divPQ = make_fastdiv((uint32_t)(g.P * g.Q));
+  if constexpr (sizeof(T) == 2) {
+    if (wgrad_large_ok(DT_BF16, g)) {
+      constexpr size_t sm = wgrad_lds_bytes<T, 256, 256, 2>();
+      static bool attr_done = false;
+      if (!attr_done) {
+        (void)hipFuncSetAttribute((const void*)conv_wgrad_kernel<T, 256, 256, 2, 4>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sm);
+        attr_done = true;
+      }
+      OSEQ_LAUNCH((conv_wgrad_kernel<T, 256, 256, 2, 4>), dim3(g.K / 256, g.C / 256, splits), dim3(512), sm, st, (const T*)x,
+                  (const T*)dz, dst, a);
+      return;
+    }
+  }
   const bool m128 = g.K % 128 == 0, n128 = g.C % 128 == 0;
   const int bm = m128 ? 128 : 64, bn = n128 ? 128 : 64;
   dim3 grid(g.K / bm, g.R * g.S * (g.C / bn), splits), block(256);
-  if (m128 && n128) OSEQ_LAUNCH((conv_wgrad_kernel<T, 128, 128>), grid, block, 0, st, (const T*)x, (const T*)dz, dst, a);
-  else if (m128) OSEQ_LAUNCH((conv_wgrad_kernel<T, 128, 64>), grid, block, 0, st, (const T*)x, (const T*)dz, dst, a);
-  else if (n128) OSEQ_LAUNCH((conv_wgrad_kernel<T, 64, 128>), grid, block, 0, st, (const T*)x, (const T*)dz, dst, a);
-  else OSEQ_LAUNCH((conv_wgrad_kernel<T, 64, 64>), grid, block, 0, st, (const T*)x, (const T*)dz, dst, a);
+  if (m128 && n128) OSEQ_LAUNCH((conv_wgrad_kernel<T, 128, 128>), grid, block, (wgrad_lds_bytes<T, 128, 128, 2>()), st, (const T*)x, (const T*)dz, dst, a);
+  else if (m128) OSEQ_LAUNCH((conv_wgrad_kernel<T, 128, 64>), grid, block, (wgrad_lds_bytes<T, 128, 64, 2>()), st, (const T*)x, (const T*)dz, dst, a);
+  else if (n128) OSEQ_LAUNCH((conv_wgrad_kernel<T, 64, 128>), grid, block, (wgrad_lds_bytes<T, 64, 128, 2>()), st, (const T*)x, (const T*)dz, dst, a);
+  else OSEQ_LAUNCH((conv_wgrad_kernel<T, 64, 64>), grid, block, (wgrad_lds_bytes<T, 64, 64, 2>()), st, (const T*)x, (const T*)dz, dst, a);
 }
 
 // out[i] = sum over pixel ranges s of partial[s][i], in a fixed order: G groups of threads each add the ranges
