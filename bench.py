@@ -27,13 +27,19 @@ if ROOT not in sys.path:
 
 PEAK = {"hbm": 8000.0,  # GB/s
         "mfma_f32": 157.3, "mfma_bf16": 2500.0, "mfma_f16": 2500.0}  # TFLOP/s dense
-MFMA_CLASSES = ("conv_fwd", "conv_dgrad", "conv_wgrad")
+MFMA_CLASSES = ("conv_fwd", "conv_dgrad", "conv_wgrad")  # 3x3 (and larger) convolutions: bound by the matrix cores
+CONV_CLASSES = MFMA_CLASSES + ("conv1x1_fwd", "conv1x1_dgrad", "conv1x1_wgrad")
+# 1x1 convolutions in the 16-bit modes are bound by HBM traffic (C_in * C_out / (C_in + C_out) FLOP per byte at best,
+# 51 to 410 on the bottleneck networks, against a ridge of 2500 / 8 = 312); in fp32 mode (ridge 20) they are MFMA-bound.
 # Forward and data gradient run the same kernels (the data gradient is the forward computation on dz with flipped
-# taps), which a kernel trace cannot tell apart: they form one group for the roofline figure.
-GROUPS = {"conv_fwd": "conv_fwd+conv_dgrad", "conv_dgrad": "conv_fwd+conv_dgrad"}
+# taps / the transposed weights), which a kernel trace cannot tell apart: they form one group for the roofline figure.
+GROUPS = {"conv_fwd": "conv_fwd+conv_dgrad", "conv_dgrad": "conv_fwd+conv_dgrad",
+          "conv1x1_fwd": "conv1x1_fwd+conv1x1_dgrad", "conv1x1_dgrad": "conv1x1_fwd+conv1x1_dgrad"}
 GROUP_KERNELS = {
-    "conv_fwd+conv_dgrad": "conv3x3_patch_kernel, conv_igemm_kernel (+ splitk_epilogue_kernel), conv1x1_kernel, conv_fwd_smallc_kernel",
+    "conv_fwd+conv_dgrad": "conv3x3_patch_kernel, conv_igemm_kernel (+ splitk_epilogue_kernel), conv_fwd_smallc_kernel",
     "conv_wgrad": "conv_wgrad3x3_kernel, conv_wgrad_kernel, conv_wgrad_smallc_kernel (+ wgrad_reduce_kernel)",
+    "conv1x1_fwd+conv1x1_dgrad": "conv1x1_large_kernel, conv1x1_kernel, conv_igemm_kernel (strided or few pixels)",
+    "conv1x1_wgrad": "conv_wgrad_kernel (+ wgrad_reduce_kernel)",
 }
 DTYPE_NAME = {0: "f32", 1: "bf16", 2: "f16"}
 
@@ -293,7 +299,8 @@ def main():
     tr.profile_select(None)
     ms = dt / args.steps * 1e3
     dc = {k_: sum(prof["classes"][n][k_] for n in members) for k_ in ("gpu_ms", "flops", "bytes", "entries", "launches")}
-    if members[0] in MFMA_CLASSES:
+    mfma_bound = members[0] in MFMA_CLASSES or (members[0] in CONV_CLASSES and wl.precision == 0)
+    if mfma_bound:
         key = {0: "mfma_f32", 1: "mfma_bf16", 2: "mfma_f16"}[wl.precision]
         achieved = dc["flops"] / (dc["gpu_ms"] * 1e-3) / 1e12
         roof = {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": PEAK[key], "unit": "TFLOP/s",
@@ -308,7 +315,7 @@ def main():
     if meas is not None:  # per launch, like `achieved`
         roof["traffic"] = meas["bytes_per_step"] / max(1.0, dc["launches"] / steps_timed)
         roof["traffic_algorithmic"] = dc["bytes"] / max(1, dc["launches"])
-    if members[0] in MFMA_CLASSES:
+    if mfma_bound:
         # `achieved` counts every launch's own algorithmic FLOPs, replayed forward launches included ("executed");
         # the model's own work (forward once, data gradient, weight gradient) over the same kernel time:
         replay = sum(e["flops"] for e in entries if e["kind"] in members and e["phase"] == 2) / survey["steps"]
@@ -324,8 +331,8 @@ def main():
 
     # convolution work per step: "model" = 3 x the forward pass (forward + data gradient + weight gradient of the
     # network itself), "executed" adds the replayed forward of the checkpointed segments
-    fwd_flops = sum(e["flops"] for e in entries if e["kind"] == "conv_fwd" and e["phase"] in (0, 1)) / survey["steps"]
-    exe_flops = sum(e["flops"] for e in entries if e["kind"] in MFMA_CLASSES) / survey["steps"]
+    fwd_flops = sum(e["flops"] for e in entries if e["kind"] in ("conv_fwd", "conv1x1_fwd") and e["phase"] in (0, 1)) / survey["steps"]
+    exe_flops = sum(e["flops"] for e in entries if e["kind"] in CONV_CLASSES) / survey["steps"]
     peak_key = {0: "mfma_f32", 1: "mfma_bf16", 2: "mfma_f16"}[wl.precision]
     conv_work = {
         "model_gflop_per_step": 3 * fwd_flops / 1e9, "executed_gflop_per_step": exe_flops / 1e9,

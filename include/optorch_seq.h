@@ -235,7 +235,10 @@ int optorch_seq_schedule_info(const optorch_seq_t* h, int32_t* n_launch_records,
 typedef enum {
   OPTORCH_K_CAST_IN = 0, OPTORCH_K_CONV_FWD = 1, OPTORCH_K_CONV_DGRAD = 2, OPTORCH_K_CONV_WGRAD = 3,
   OPTORCH_K_BN_STATS = 4, OPTORCH_K_BN_APPLY = 5, OPTORCH_K_BN_BWD = 6, OPTORCH_K_POOL = 7, OPTORCH_K_HEAD = 8,
-  OPTORCH_K_RELU_BIAS_BWD = 9, OPTORCH_K_OPTIMIZER = 10, OPTORCH_N_KERNEL_CLASSES = 11
+  OPTORCH_K_RELU_BIAS_BWD = 9, OPTORCH_K_OPTIMIZER = 10,
+  /* 1x1 convolutions apart from the others: their arithmetic intensity (C_in * C_out / (C_in + C_out) FLOP per byte at
+   * best) puts them under the HBM roof, where the 3x3 layers of 128 channels and more sit under the matrix-core roof */
+  OPTORCH_K_CONV1X1_FWD = 11, OPTORCH_K_CONV1X1_DGRAD = 12, OPTORCH_K_CONV1X1_WGRAD = 13, OPTORCH_N_KERNEL_CLASSES = 14
 } optorch_kernel_class_t;
 int optorch_seq_profile_enable(optorch_seq_t* h, int32_t enable);
 /* Restricts the timing to the classes whose bit (1u << optorch_kernel_class_t) is set in class_mask; all

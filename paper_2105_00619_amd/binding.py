@@ -27,7 +27,7 @@ SYMBOLS = (
 )
 
 KERNEL_CLASSES = ("cast_in", "conv_fwd", "conv_dgrad", "conv_wgrad", "bn_stats", "bn_apply", "bn_bwd", "pool", "head",
-                  "relu_bias_bwd", "optimizer")
+                  "relu_bias_bwd", "optimizer", "conv1x1_fwd", "conv1x1_dgrad", "conv1x1_wgrad")
 
 
 class optorch_unit_t(C.Structure):

@@ -305,7 +305,7 @@ void run_op(const Ctx& c, const SOp& s) {
         launch_bn_apply_pool(st, dt, c.at(s.in[0]), (const float*)c.at(s.in[1]), c.at(s.out[0]), c.at(s.out[1]), f.N, f.P,
                              f.Q, f.C, f.relu);
       else
-        launch_bn_apply(st, dt, c.at(s.in[0]), (const float*)c.at(s.in[1]), c.at(s.in[2]), c.at(s.out[0]),
+        launch_bn_apply(st, dt, c.at(s.in[0]), (const float*)c.at(s.in[1]), c.at(s.in[2]), c.at(s.out[0]), c.at(s.out[2]),
                         (int64_t)f.N * f.P * f.Q, f.C, f.relu);
       break;
     case S_POOL_FWD:
@@ -326,9 +326,11 @@ void run_op(const Ctx& c, const SOp& s) {
                            f.red_blocks, (float*)c.at(s.out[2]), c.g32(f.gamma_off), c.g32(f.beta_off), c.at(s.out[0]));
         break;
       }
-      launch_bn_bwd(st, dt, c.at(s.in[0]), c.at(s.in[1]), c.at(s.in[3]), (const float*)c.at(s.in[2]),
-                    (int64_t)f.N * f.P * f.Q, f.C, f.relu, f.red_blocks, (float*)c.at(s.out[2]), c.g32(f.gamma_off),
-                    c.g32(f.beta_off), c.at(s.out[0]), c.at(s.out[1]));
+      // in[3]: the block output whose sign gives the ReLU decisions, or (variant 2) those decisions as a bit mask
+      launch_bn_bwd(st, dt, c.at(s.in[0]), c.at(s.in[1]), s.variant == 2 ? nullptr : c.at(s.in[3]),
+                    s.variant == 2 ? c.at(s.in[3]) : nullptr, (const float*)c.at(s.in[2]), (int64_t)f.N * f.P * f.Q, f.C,
+                    f.relu, f.red_blocks, (float*)c.at(s.out[2]), c.g32(f.gamma_off), c.g32(f.beta_off), c.at(s.out[0]),
+                    c.at(s.out[1]));
       break;
     case S_RELU_BWD:
       launch_relu_bwd(st, dt, c.at(s.in[0]), c.at(s.in[1]), c.at(s.out[0]), (int64_t)f.N * f.P * f.Q, f.K);
@@ -351,7 +353,7 @@ void run_op(const Ctx& c, const SOp& s) {
     case S_DGRAD:
       if (f.dgrad_algo == ALGO_MFMA)
         launch_conv_dgrad_mfma(st, dt, c.at(s.in[0]), h->pbase + h->off_wt + (uint64_t)f.w_off * h->plan.esize, c.at(s.in[1]),
-                               c.at(s.out[0]), (float*)c.at(s.out[1]), f.dgrad_splits, geom(f));
+                               c.at(s.in[2]), c.at(s.out[0]), (float*)c.at(s.out[1]), f.dgrad_splits, geom(f));
       else
         launch_conv_dgrad_direct(st, dt, c.at(s.in[0]), c.wc(f.w_off), c.at(s.in[1]), c.at(s.out[0]), geom(f));
       break;
@@ -361,12 +363,13 @@ void run_op(const Ctx& c, const SOp& s) {
   }
 }
 
-int class_of(SKind k) {
+int class_of(SKind k, const FOp& f) {
+  const bool pointwise = f.R == 1 && f.S == 1;
   switch (k) {
     case S_CAST_IN: return OPTORCH_K_CAST_IN;
-    case S_CONV_FWD: return OPTORCH_K_CONV_FWD;
-    case S_DGRAD: return OPTORCH_K_CONV_DGRAD;
-    case S_WGRAD: return OPTORCH_K_CONV_WGRAD;
+    case S_CONV_FWD: return pointwise ? OPTORCH_K_CONV1X1_FWD : OPTORCH_K_CONV_FWD;
+    case S_DGRAD: return pointwise ? OPTORCH_K_CONV1X1_DGRAD : OPTORCH_K_CONV_DGRAD;
+    case S_WGRAD: return pointwise ? OPTORCH_K_CONV1X1_WGRAD : OPTORCH_K_CONV_WGRAD;
     case S_BN_STATS: return OPTORCH_K_BN_STATS;
     case S_BN_APPLY: return OPTORCH_K_BN_APPLY;
     case S_BN_BWD: return OPTORCH_K_BN_BWD;
@@ -386,16 +389,22 @@ void work_of(const optorch_seq_t* h, const SOp& s, double* flops, double* bytes)
   switch (s.kind) {
     case S_CAST_IN: *bytes = in_px * f.C * ((h->x_encoded ? 1 : 4) + e); break;  // an encoded batch: one byte per pixel
     case S_CONV_FWD: *flops = 2 * out_px * wts; *bytes = e * (in_px * f.C + out_px * f.K + wts); break;
-    case S_DGRAD: *flops = 2 * out_px * wts; *bytes = e * (in_px * f.C * (s.in[1] >= 0 ? 2 : 1) + out_px * f.K + wts); break;
+    case S_DGRAD:
+      *flops = 2 * out_px * wts;
+      *bytes = e * (in_px * f.C * (s.in[1] >= 0 ? 2 : 1) + out_px * f.K + wts) + (s.in[2] >= 0 ? e * in_px * f.C / 16 : 0);
+      break;
     case S_WGRAD: *flops = 2 * out_px * wts; *bytes = e * (in_px * f.C + out_px * f.K) + 4 * wts; break;
     case S_BN_STATS: *bytes = s.in[1] >= 0 ? 8.0 * f.stat_blocks * f.C : e * out_px * f.C; break;  // fused: only the block sums
     case S_BN_APPLY:
       if (s.out[1] >= 0) *bytes = e * out_px * f.C * (1.0 + (s.out[0] >= 0 ? 1.0 : 0.0) + 0.25);  // z, [a], pooled
-      else *bytes = e * out_px * f.C * (s.in[2] >= 0 ? 3 : 2);
+      else *bytes = e * out_px * f.C * ((s.in[2] >= 0 ? 3 : 2) + (s.out[2] >= 0 ? 1.0 / 16 : 0));  // + the ReLU bit mask
       break;
     case S_BN_BWD:
       if (s.variant == 1) { *bytes = e * out_px * f.C * (2 * 1.25 + 1); break; }  // twice (z, pooled gradient), dz
-      *bytes = e * out_px * f.C * (2 + (s.in[3] >= 0 ? 1 : 0) + 3 + (s.in[3] >= 0 ? 1 : 0) + (s.out[1] >= 0 ? 1 : 0));
+      {  // the reduction reads dA, z and the ReLU source; the apply pass reads them again and writes dz (+ the skip gradient)
+        const double src = s.in[3] < 0 ? 0.0 : s.variant == 2 ? 1.0 / 16 : 1.0;  // a bit mask is a sixteenth of a tensor
+        *bytes = e * out_px * f.C * (2 + src + 3 + src + (s.out[1] >= 0 ? 1 : 0));
+      }
       break;
     case S_POOL_FWD: *bytes = e * (in_px + out_px) * f.C; break;
     case S_POOL_BWD: *bytes = e * (2 * in_px + out_px) * f.C; break;
@@ -486,7 +495,7 @@ extern "C" int optorch_seq_profile_read_entries(optorch_seq_t* h, int32_t capaci
     if (cnt < capacity) {
       double fl, by;
       work_of(h, s, &fl, &by);
-      if (kind) kind[cnt] = class_of(s.kind);
+      if (kind) kind[cnt] = class_of(s.kind, h->plan.fops[s.fop]);
       if (unit) unit[cnt] = h->plan.fops[s.fop].unit;
       if (phase) phase[cnt] = s.phase;
       if (gpu_ms) gpu_ms[cnt] = si < h->entry_ms.size() ? h->entry_ms[si] : 0.0;
@@ -623,13 +632,13 @@ static int step_run(optorch_seq_t* h, const Ctx& c, float lr, float* loss_out, f
   for (size_t si = 0; si < h->plan.sched.size(); ++si) {
     const SOp& s = h->plan.sched[si];
     if (!s.live) continue;
-    const bool timed = prof && ((h->prof_mask >> class_of(s.kind)) & 1u);
+    const bool timed = prof && ((h->prof_mask >> class_of(s.kind, h->plan.fops[s.fop])) & 1u);
     const size_t ev0 = h->ev_used;
     if (timed) g_launch_timer = LaunchTimer{true, next_event_cb, h};  // every launch of the entry carries its own events
     run_op(c, s);
     if (timed) {
       g_launch_timer.on = false;
-      const int k = class_of(s.kind);
+      const int k = class_of(s.kind, h->plan.fops[s.fop]);
       double fl, by;
       work_of(h, s, &fl, &by);
       const size_t pairs = (h->ev_used - ev0) / 2;

@@ -16,9 +16,12 @@ namespace oseq {
 typedef __attribute__((ext_vector_type(4))) float epi_v4f;
 
 // rowoff(row): element offset of block row `row`'s first channel in the output tensor, or -1 if the row is not stored
+// amask (with an addend; may be null): ReLU decisions as bits, byte e / V for the V = 16 / sizeof(T) elements from
+// element offset e of the addend; an addend element whose bit is clear counts as zero.
 template <int NT, class T, int BN, int HR, bool HB, bool HA, bool STAT, class RowOff>
 __device__ __forceinline__ void epi_store_rows_nt(const float* ep, int tid, int n0, const float* __restrict__ bias,
-                                               const T* __restrict__ addend, T* __restrict__ out, int relu, RowOff rowoff,
+                                               const T* __restrict__ addend, const uint8_t* __restrict__ amask,
+                                               T* __restrict__ out, int relu, RowOff rowoff,
                                                float (&ss)[8], float (&qq)[8]) {
   constexpr int EP_PITCH = BN + 4;
   constexpr int GROUPS = BN / 8;                // 8-channel groups per row
@@ -36,10 +39,20 @@ __device__ __forceinline__ void epi_store_rows_nt(const float* ep, int tid, int 
     for (int k = 0; k < 8; ++k) bv[k] = bias[col + k];
   }
   Vec<T, 8> ad[PER_THREAD];
+  unsigned mb[PER_THREAD];
   if (HA) {  // rows that are not stored read the tensor's first row
 #pragma unroll
     for (int it = 0; it < PER_THREAD; ++it)
       ad[it] = *reinterpret_cast<const Vec<T, 8>*>(addend + (ro[it] >= 0 ? ro[it] : 0) + col);
+#pragma unroll
+    for (int it = 0; it < PER_THREAD; ++it) {
+      mb[it] = 0xffu;
+      if (amask) {
+        const int64_t e = (ro[it] >= 0 ? ro[it] : 0) + col;
+        if (sizeof(T) == 2) mb[it] = amask[e >> 3];
+        else mb[it] = (amask[e >> 2] & 15u) | ((unsigned)(amask[(e >> 2) + 1] & 15u) << 4);
+      }
+    }
   }
   // straight-line code for all rows (only the store is predicated), so that the LDS reads of the later rows are issued
   // while the earlier ones are converted
@@ -55,7 +68,7 @@ __device__ __forceinline__ void epi_store_rows_nt(const float* ep, int tid, int 
     }
     if (HA) {
 #pragma unroll
-      for (int k = 0; k < 8; ++k) v[k] += to_f32(ad[it].v[k]);
+      for (int k = 0; k < 8; ++k) v[k] += ((mb[it] >> k) & 1u) ? to_f32(ad[it].v[k]) : 0.f;
     }
     if (relu) {
 #pragma unroll
@@ -80,21 +93,23 @@ __device__ __forceinline__ void epi_store_rows_nt(const float* ep, int tid, int 
 // compiled, which keeps their registers out of the kernel.
 template <int NT, class T, int BN, int HR, bool CAN_BIAS, bool CAN_ADD, bool STAT, class RowOff>
 __device__ __forceinline__ void epi_store_pass_nt(const float* ep, int tid, int n0, const float* __restrict__ bias,
-                                                  const T* __restrict__ addend, T* __restrict__ out, int relu, RowOff rowoff,
+                                                  const T* __restrict__ addend, const uint8_t* __restrict__ amask,
+                                                  T* __restrict__ out, int relu, RowOff rowoff,
                                                   float (&ss)[8], float (&qq)[8]) {
   if (CAN_BIAS && bias) {
-    if (CAN_ADD && addend) epi_store_rows_nt<NT, T, BN, HR, true, CAN_ADD, STAT>(ep, tid, n0, bias, addend, out, relu, rowoff, ss, qq);
-    else epi_store_rows_nt<NT, T, BN, HR, true, false, STAT>(ep, tid, n0, bias, addend, out, relu, rowoff, ss, qq);
+    if (CAN_ADD && addend) epi_store_rows_nt<NT, T, BN, HR, true, CAN_ADD, STAT>(ep, tid, n0, bias, addend, amask, out, relu, rowoff, ss, qq);
+    else epi_store_rows_nt<NT, T, BN, HR, true, false, STAT>(ep, tid, n0, bias, addend, amask, out, relu, rowoff, ss, qq);
   } else {
-    if (CAN_ADD && addend) epi_store_rows_nt<NT, T, BN, HR, false, true, STAT>(ep, tid, n0, bias, addend, out, relu, rowoff, ss, qq);
-    else epi_store_rows_nt<NT, T, BN, HR, false, false, STAT>(ep, tid, n0, bias, addend, out, relu, rowoff, ss, qq);
+    if (CAN_ADD && addend) epi_store_rows_nt<NT, T, BN, HR, false, true, STAT>(ep, tid, n0, bias, addend, amask, out, relu, rowoff, ss, qq);
+    else epi_store_rows_nt<NT, T, BN, HR, false, false, STAT>(ep, tid, n0, bias, addend, amask, out, relu, rowoff, ss, qq);
   }
 }
 template <class T, int BN, int HR, bool CAN_BIAS, bool CAN_ADD, bool STAT, class RowOff>
 __device__ __forceinline__ void epi_store_pass(const float* ep, int tid, int n0, const float* __restrict__ bias,
-                                               const T* __restrict__ addend, T* __restrict__ out, int relu, RowOff rowoff,
+                                               const T* __restrict__ addend, const uint8_t* __restrict__ amask,
+                                               T* __restrict__ out, int relu, RowOff rowoff,
                                                float (&ss)[8], float (&qq)[8]) {
-  epi_store_pass_nt<256, T, BN, HR, CAN_BIAS, CAN_ADD, STAT>(ep, tid, n0, bias, addend, out, relu, rowoff, ss, qq);
+  epi_store_pass_nt<256, T, BN, HR, CAN_BIAS, CAN_ADD, STAT>(ep, tid, n0, bias, addend, amask, out, relu, rowoff, ss, qq);
 }
 
 // raw fp32 sums of a depth range (no epilogue arithmetic): dst + rowoff(row) + channel

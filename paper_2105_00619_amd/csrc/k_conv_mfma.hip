@@ -43,6 +43,7 @@ struct IGemmArgs {
   // fullW/2), M its pixel count, taps[c] the list (one byte per tap, r*S + s), ntaps[c] its length.
   int cls, fullH, fullW;
   int taps[4], ntaps[4];
+  const uint8_t* amask;   // data gradient with an addend: ReLU bit mask the addend is multiplied by, or null
 };
 
 template <class T> struct Frag;  // 32 bytes of one operand row, and the MFMAs that consume it
@@ -334,9 +335,9 @@ __global__ void __launch_bounds__(256) conv_igemm_kernel(const T* __restrict__ s
       if (SPLIT) {
         epi_store_partial<BN, HR>(ep, tid, n0, partial + (int64_t)blockIdx.z * a.M * a.Ng, rowoff);
       } else if (STAT && stat_partial) {
-        epi_store_pass<T, BN, HR, MODE == IG_FWD, MODE == IG_DGRAD, true>(ep, tid, n0, bias, addend, out, a.relu, rowoff, ss, qq);
+        epi_store_pass<T, BN, HR, MODE == IG_FWD, MODE == IG_DGRAD, true>(ep, tid, n0, bias, addend, a.amask, out, a.relu, rowoff, ss, qq);
       } else {
-        epi_store_pass<T, BN, HR, MODE == IG_FWD, MODE == IG_DGRAD, false>(ep, tid, n0, bias, addend, out, a.relu, rowoff, ss, qq);
+        epi_store_pass<T, BN, HR, MODE == IG_FWD, MODE == IG_DGRAD, false>(ep, tid, n0, bias, addend, a.amask, out, a.relu, rowoff, ss, qq);
       }
     }
     if (STAT && stat_partial)
@@ -372,6 +373,7 @@ struct PatchArgs {
   int row_pitch;             // bytes between staged patch rows in LDS (>= SC * 80, padded against bank conflicts)
   int patch_elems;           // elements of one staged patch buffer (its rows times row_pitch, rounded up to 16 bytes)
   int xcd_group;             // 1: blocks are renumbered so that the row tiles of one weight slice run on one XCD
+  const uint8_t* amask;      // data gradient with an addend: ReLU bit mask the addend is multiplied by, or null
 };
 
 constexpr int PATCH_MAX_POS = 256;  // positions per sub-tile
@@ -628,7 +630,7 @@ conv3x3_patch_kernel(const T* __restrict__ src, const T* __restrict__ wmat, cons
       if (partial)
         epi_store_partial<BN, HR>(ep, tid, n0c, partial + (int64_t)bz * ((int64_t)a.N * a.dstH * a.dstW * a.Ng), rowoff);
       else
-        epi_store_pass<T, BN, HR, true, !STAT, STAT>(ep, tid, n0c, bias, addend, out, a.relu, rowoff, ss, qq);
+        epi_store_pass<T, BN, HR, true, !STAT, STAT>(ep, tid, n0c, bias, addend, a.amask, out, a.relu, rowoff, ss, qq);
     }
     if (STAT)
       epi_stat_combine<BN>(ep, tid, ss, qq, stat_partial + ((int64_t)bx * 2 + 0) * a.Ng + n0c,
@@ -646,7 +648,8 @@ constexpr int SPLIT_EPI_ROWS = 64;
 template <class T>
 __global__ void __launch_bounds__(256) splitk_epilogue_kernel(const float* __restrict__ partial, int splits, int64_t M, int Ng,
                                                               const float* __restrict__ bias, const T* __restrict__ addend,
-                                                              T* __restrict__ out, float* __restrict__ stat_partial, int relu) {
+                                                              const uint8_t* __restrict__ amask, T* __restrict__ out,
+                                                              float* __restrict__ stat_partial, int relu) {
   __shared__ float red[2][16][64];
   const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
   const int col = blockIdx.y * 64 + tx * 4;
@@ -665,10 +668,13 @@ __global__ void __launch_bounds__(256) splitk_epilogue_kernel(const float* __res
       v4f acc = *reinterpret_cast<const v4f*>(partial + i);
       for (int z = 1; z < splits; ++z) acc += *reinterpret_cast<const v4f*>(partial + (int64_t)z * n + i);
       float r[4];
+      // the addend's ReLU bits, if it has any: four consecutive elements lie in one byte (i is a multiple of 4)
+      unsigned mb = 0xfu;
+      if (addend && amask) mb = sizeof(T) == 2 ? (amask[i >> 3] >> (i & 4)) & 15u : amask[i >> 2] & 15u;
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         float v = acc[e] + bv[e];
-        if (addend) v += to_f32(addend[i + e]);
+        if (addend && ((mb >> e) & 1u)) v += to_f32(addend[i + e]);
         r[e] = relu ? fmaxf(v, 0.f) : v;
       }
       store_f32<T, 4>(out + i, r);
@@ -697,9 +703,9 @@ __global__ void __launch_bounds__(256) splitk_epilogue_kernel(const float* __res
 
 template <class T>
 static void launch_splitk_epilogue(hipStream_t st, const float* partial, int splits, int64_t M, int Ng, const float* bias,
-                                   const void* addend, void* out, float* stat_partial, int relu) {
+                                   const void* addend, const uint8_t* amask, void* out, float* stat_partial, int relu) {
   dim3 grid(ceil_div(M, SPLIT_EPI_ROWS), Ng / 64);  // Ng % 64 == 0 for every MFMA convolution
-  OSEQ_LAUNCH(splitk_epilogue_kernel<T>, grid, dim3(256), 0, st, partial, splits, M, Ng, bias, (const T*)addend,
+  OSEQ_LAUNCH(splitk_epilogue_kernel<T>, grid, dim3(256), 0, st, partial, splits, M, Ng, bias, (const T*)addend, amask,
                      (T*)out, stat_partial, relu);
 }
 
@@ -850,7 +856,7 @@ static void launch_patch_t(hipStream_t st, const void* src, const void* wmat, co
     launch_patch_v<T, 64, 1, 1>(st, src, wmat, bias, addend, out, partial, stat_partial, sp, a);
   }
   if (sp > 1)
-    launch_splitk_epilogue<T>(st, partial, sp, (int64_t)a.N * a.dstH * a.dstW, a.Ng, bias, addend, out, stat_partial, a.relu);
+    launch_splitk_epilogue<T>(st, partial, sp, (int64_t)a.N * a.dstH * a.dstW, a.Ng, bias, addend, a.amask, out, stat_partial, a.relu);
 }
 
 static void launch_patch(hipStream_t st, int dt, const void* src, const void* wmat, const float* bias, const void* addend, void* out,
@@ -896,7 +902,7 @@ static void launch_igemm_t(hipStream_t st, const void* src, const void* wmat, co
   }
   if (splits > 1) {
     if (wide) IGEMM_LAUNCH(128, 128, true) else IGEMM_LAUNCH(128, 64, true)
-    launch_splitk_epilogue<T>(st, partial, splits, a.M, a.Ng, bias, addend, out, stat_partial, a.relu);
+    launch_splitk_epilogue<T>(st, partial, splits, a.M, a.Ng, bias, addend, a.amask, out, stat_partial, a.relu);
   } else if (bm == 256) {
     if (wide) IGEMM_LAUNCH(256, 128, false) else IGEMM_LAUNCH(256, 64, false)
   } else {
@@ -984,20 +990,22 @@ void launch_conv_fwd_mfma(hipStream_t st, int dt, const void* x, const void* w, 
 }
 
 // wt: the (C_in, kh, kw, C_out) transpose of the weights, in the compute type
-void launch_conv_dgrad_mfma(hipStream_t st, int dt, const void* dz, const void* wt, const void* addend, void* dx,
-                            float* partial, int splits, const ConvGeom& g) {
+void launch_conv_dgrad_mfma(hipStream_t st, int dt, const void* dz, const void* wt, const void* addend,
+                            const void* addend_mask, void* dx, float* partial, int splits, const ConvGeom& g) {
   PatchShape pv; PatchArgs pa{};
+  const uint8_t* amask = addend ? (const uint8_t*)addend_mask : nullptr;
   if (conv_pointwise_dgrad_ok(dt, g)) {
-    launch_conv_dgrad_pointwise(st, dt, dz, wt, addend, dx, g);
+    launch_conv_dgrad_pointwise(st, dt, dz, wt, addend, amask, dx, g);
     return;
   }
   if (patch_pick(dt, g.N, g.H, g.W, g.K, g.C, g.R, g.S, g.stride, pv, pa)) {
     pa.N = g.N; pa.srcH = g.P; pa.srcW = g.Q; pa.srcC = g.K; pa.dstH = g.H; pa.dstW = g.W; pa.Ng = g.C;
-    pa.pad = g.R - 1 - g.pad; pa.flip = 1; pa.relu = 0;
+    pa.pad = g.R - 1 - g.pad; pa.flip = 1; pa.relu = 0; pa.amask = amask;
     launch_patch(st, dt, dz, wt, nullptr, addend, dx, partial, nullptr, pv, pa);
     return;
   }
   IGemmArgs a{g.P, g.Q, g.K, g.H, g.W, g.N * g.H * g.W, g.C, g.R * g.S * g.K, g.R, g.S, g.stride, g.pad, 0, 0};
+  a.amask = amask;  // (only stride-1 layers ever get one: the identity shortcut of a block)
   if (dgrad_by_classes(g)) {
     a.cls = 1; a.fullH = g.H; a.fullW = g.W;
     a.dstH = g.H / 2; a.dstW = g.W / 2; a.M = g.N * a.dstH * a.dstW;

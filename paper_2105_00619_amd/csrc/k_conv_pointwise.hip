@@ -45,6 +45,7 @@ struct PwArgs {
                           // (2 dstH) x (2 dstW) image and its three neighbours get zero (plus the addend)
   int dstH, dstW, srcH, srcW;
   FastDiv div_w, div_hw;  // by dstW and dstH * dstW
+  const uint8_t* amask;   // data gradient with an addend: ReLU bit mask the addend is multiplied by, or null
 };
 
 template <int V> struct IC { static constexpr int value = V; };
@@ -238,10 +239,10 @@ conv1x1_kernel(const T* __restrict__ X, const T* __restrict__ W, const float* __
     };
     if (DGRAD) {
       if (a.scatter) scatter_rows<T, BN>(ep, tid, n0, m0 + u * 64, addend, out, a);
-      else epi_store_pass<T, BN, 64, false, true, false>(ep, tid, n0, bias, addend, out, 0, rowoff, ss, qq);
+      else epi_store_pass<T, BN, 64, false, true, false>(ep, tid, n0, bias, addend, a.amask, out, 0, rowoff, ss, qq);
     } else {
-      if (stat_partial) epi_store_pass<T, BN, 64, true, false, true>(ep, tid, n0, bias, addend, out, a.relu, rowoff, ss, qq);
-      else epi_store_pass<T, BN, 64, true, false, false>(ep, tid, n0, bias, addend, out, a.relu, rowoff, ss, qq);
+      if (stat_partial) epi_store_pass<T, BN, 64, true, false, true>(ep, tid, n0, bias, addend, nullptr, out, a.relu, rowoff, ss, qq);
+      else epi_store_pass<T, BN, 64, true, false, false>(ep, tid, n0, bias, addend, nullptr, out, a.relu, rowoff, ss, qq);
     }
   }
   if (!DGRAD && stat_partial)
@@ -388,10 +389,10 @@ conv1x1_large_kernel(const T* __restrict__ X, const T* __restrict__ W, const flo
       return grow < a.M ? grow * a.Ng : -1;
     };
     if (DGRAD) {
-      epi_store_pass_nt<NT, T, BN, 64, false, true, false>(ep, tid, n0, bias, addend, out, 0, rowoff, ss, qq);
+      epi_store_pass_nt<NT, T, BN, 64, false, true, false>(ep, tid, n0, bias, addend, a.amask, out, 0, rowoff, ss, qq);
     } else {
-      if (stat_partial) epi_store_pass_nt<NT, T, BN, 64, true, false, true>(ep, tid, n0, bias, addend, out, a.relu, rowoff, ss, qq);
-      else epi_store_pass_nt<NT, T, BN, 64, true, false, false>(ep, tid, n0, bias, addend, out, a.relu, rowoff, ss, qq);
+      if (stat_partial) epi_store_pass_nt<NT, T, BN, 64, true, false, true>(ep, tid, n0, bias, addend, nullptr, out, a.relu, rowoff, ss, qq);
+      else epi_store_pass_nt<NT, T, BN, 64, true, false, false>(ep, tid, n0, bias, addend, nullptr, out, a.relu, rowoff, ss, qq);
     }
   }
   if (!DGRAD && stat_partial)
@@ -511,9 +512,10 @@ void launch_conv_fwd_pointwise(hipStream_t st, int dt, const void* x, const void
 }
 
 // wt: the (C_in, C_out) transpose of the weights in the compute type
-void launch_conv_dgrad_pointwise(hipStream_t st, int dt, const void* dz, const void* wt, const void* addend, void* dx,
-                                 const ConvGeom& g) {
+void launch_conv_dgrad_pointwise(hipStream_t st, int dt, const void* dz, const void* wt, const void* addend,
+                                 const uint8_t* addend_mask, void* dx, const ConvGeom& g) {
   PwArgs a{};
+  a.amask = addend_mask;  // (stride-1 layers only: the identity shortcut of a block)
   a.Ng = g.C; a.Kd = g.K; a.relu = 0; a.stride = 1;
   a.scatter = g.stride == 2;
   a.dstH = a.scatter ? g.P : g.H; a.dstW = a.scatter ? g.Q : g.W; a.srcH = g.P; a.srcW = g.Q;

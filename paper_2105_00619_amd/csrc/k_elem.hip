@@ -31,6 +31,8 @@ struct RedArgs {
   const void* a;       // STATS: z ; BN_BWD: dA ; BIAS: dz
   const void* z;       // BN_BWD: z
   const void* aout;    // BN_BWD with skip: block output (ReLU mask source); else null
+  const uint8_t* mask; // BN_BWD: ReLU decisions as bits, byte (row * C + c) / V holds those of V = 16 / sizeof(T) channels;
+                       // takes the place of aout (and of the ReLU flag: the bits are applied as they are)
   const float* stats;  // BN_BWD: [4][C] mean, rstd, scale, shift
   float* partial;      // [nblk][2][C]
   int64_t rows;
@@ -64,8 +66,9 @@ __global__ void __launch_bounds__(256) colreduce_kernel(RedArgs g) {
     const T* a = static_cast<const T*>(g.a);
     const T* z = static_cast<const T*>(g.z);
     const T* ao = static_cast<const T*>(g.aout);
+    const uint8_t* mk = MODE == RED_BN_BWD && V > 1 ? g.mask : nullptr;
     // one row's contribution, from values already in registers
-    auto accumulate = [&](const float (&va)[V], const float (&vz)[V], const float (&vo)[V]) {
+    auto accumulate = [&](const float (&va)[V], const float (&vz)[V], const float (&vo)[V], unsigned bits) {
       if (MODE == RED_STATS) {
 #pragma unroll
         for (int i = 0; i < V; ++i) { s0[i] += va[i]; s1[i] = __fmaf_rn(va[i], va[i], s1[i]); }
@@ -76,7 +79,8 @@ __global__ void __launch_bounds__(256) colreduce_kernel(RedArgs g) {
 #pragma unroll
         for (int i = 0; i < V; ++i) {
           bool on = true;
-          if (g.relu) on = ao ? (vo[i] > 0.f) : (bn_affine(vz[i], scale[i], shift[i]) > 0.f);
+          if (mk) on = (bits >> i) & 1u;
+          else if (g.relu) on = ao ? (vo[i] > 0.f) : (bn_affine(vz[i], scale[i], shift[i]) > 0.f);
           const float dy = on ? va[i] : 0.f;
           const float xh = (vz[i] - mean[i]) * rstd[i];
           s0[i] += dy; s1[i] = __fmaf_rn(dy, xh, s1[i]);
@@ -88,27 +92,31 @@ __global__ void __launch_bounds__(256) colreduce_kernel(RedArgs g) {
     int64_t r = r0 + ty;
     for (; r + 3 * (int64_t)TY < r1; r += 4 * (int64_t)TY) {
       float va[4][V], vz[4][V], vo[4][V];
+      unsigned mb[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
         const int64_t off = (r + (int64_t)u * TY) * g.C + c0;
         load_f32<T, V>(a + off, va[u]);
         if (MODE == RED_BN_BWD) {
           load_f32<T, V>(z + off, vz[u]);
-          if (ao) load_f32<T, V>(ao + off, vo[u]);
+          if (mk) mb[u] = mk[(r + (int64_t)u * TY) * CG + cg];
+          else if (ao) load_f32<T, V>(ao + off, vo[u]);
         }
       }
 #pragma unroll
-      for (int u = 0; u < 4; ++u) accumulate(va[u], vz[u], vo[u]);
+      for (int u = 0; u < 4; ++u) accumulate(va[u], vz[u], vo[u], mb[u]);
     }
     for (; r < r1; r += TY) {
       const int64_t off = r * g.C + c0;
       float va[V], vz[V], vo[V];
+      unsigned mb = 0u;
       load_f32<T, V>(a + off, va);
       if (MODE == RED_BN_BWD) {
         load_f32<T, V>(z + off, vz);
-        if (ao) load_f32<T, V>(ao + off, vo);
+        if (mk) mb = mk[r * CG + cg];
+        else if (ao) load_f32<T, V>(ao + off, vo);
       }
-      accumulate(va, vz, vo);
+      accumulate(va, vz, vo, mb);
     }
   }
   const int W = TX * V;
@@ -283,10 +291,11 @@ struct RowArgs {
 
 // (the forward apply kernel, with one load and one store stream, measured faster as one group of V channels per
 // thread; its per-channel constants are fetched as whole vectors)
+// mask (with a skip connection, V = 16 / sizeof(T)): byte i receives the ReLU decisions of group i, bit k = output k > 0
 template <class T, int V, bool SKIP>
 __global__ void __launch_bounds__(256) bn_apply_kernel(const T* __restrict__ z, const float* __restrict__ stats,
-                                                       const T* __restrict__ skip, T* __restrict__ out, int64_t groups,
-                                                       int C, int relu) {
+                                                       const T* __restrict__ skip, T* __restrict__ out,
+                                                       uint8_t* __restrict__ mask, int64_t groups, int C, int relu) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= groups) return;
   const int CG = C / V;
@@ -304,6 +313,12 @@ __global__ void __launch_bounds__(256) bn_apply_kernel(const T* __restrict__ z, 
     vo[k] = relu ? fmaxf(y, 0.f) : y;
   }
   store_f32<T, V>(out + off, vo);
+  if (SKIP && V > 1 && mask) {
+    unsigned bits = 0u;
+#pragma unroll
+    for (int k = 0; k < V; ++k) bits |= (vo[k] > 0.f ? 1u : 0u) << k;
+    mask[i] = (uint8_t)bits;
+  }
 }
 
 // BatchNorm apply (+ReLU) and the 2x2 max-pool that follows it in one pass over z: a thread owns one pooled position
@@ -348,9 +363,11 @@ __global__ void __launch_bounds__(256) bn_apply_pool_kernel(const T* __restrict_
 
 // AOUT: the ReLU mask comes from the block output (a residual sum) instead of being rebuilt from z; DSKIP: the masked
 // gradient is also written out for the skip branch
-template <class T, int V, bool AOUT, bool DSKIP>
+// MS: where the ReLU decisions come from: 0 redone from z, 1 the sign of the block output aout, 2 the bits of mask
+template <class T, int V, int MS, bool DSKIP>
 __global__ void __launch_bounds__(256) bn_bwd_apply_kernel(const T* __restrict__ da, const T* __restrict__ z,
-                                                           const T* __restrict__ aout, const float* __restrict__ stats,
+                                                           const T* __restrict__ aout, const uint8_t* __restrict__ mask,
+                                                           const float* __restrict__ stats,
                                                            const float* __restrict__ coef, T* __restrict__ dz,
                                                            T* __restrict__ dskip, RowArgs g) {
   const int CG = g.C / V;
@@ -360,6 +377,7 @@ __global__ void __launch_bounds__(256) bn_bwd_apply_kernel(const T* __restrict__
   const int cg = blockIdx.y * TX + tx;
   if (cg >= CG || ty >= TY) return;
   const int c0 = cg * V;
+  constexpr bool AOUT = MS == 1;
   float mean[V], rstd[V], scale[V], shift[V], cb[V], cg2[V];
 #pragma unroll
   for (int k = 0; k < V; ++k) {
@@ -369,11 +387,13 @@ __global__ void __launch_bounds__(256) bn_bwd_apply_kernel(const T* __restrict__
   }
   const int64_t r0 = (int64_t)blockIdx.x * g.rows_per_block;
   const int64_t r1 = r0 + g.rows_per_block < g.rows ? r0 + g.rows_per_block : g.rows;
-  auto one = [&](const float (&va)[V], const float (&vz)[V], const float (&vo)[V], float (&rz)[V], float (&rs)[V]) {
+  auto one = [&](const float (&va)[V], const float (&vz)[V], const float (&vo)[V], unsigned bits, float (&rz)[V],
+                 float (&rs)[V]) {
 #pragma unroll
     for (int k = 0; k < V; ++k) {
       bool on = true;
-      if (g.relu) on = AOUT ? (vo[k] > 0.f) : (bn_affine(vz[k], scale[k], shift[k]) > 0.f);
+      if (MS == 2) on = (bits >> k) & 1u;
+      else if (g.relu) on = AOUT ? (vo[k] > 0.f) : (bn_affine(vz[k], scale[k], shift[k]) > 0.f);
       const float dy = on ? va[k] : 0.f;
       const float xh = (vz[k] - mean[k]) * rstd[k];
       rz[k] = scale[k] * (dy - cb[k] - xh * cg2[k]);
@@ -383,15 +403,17 @@ __global__ void __launch_bounds__(256) bn_bwd_apply_kernel(const T* __restrict__
   int64_t r = r0 + ty;
   for (; r + 3 * (int64_t)TY < r1; r += 4 * (int64_t)TY) {
     float va[4][V], vz[4][V], vo[4][V], rz[4][V], rs[4][V];
+    unsigned mb[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       const int64_t off = (r + (int64_t)u * TY) * g.C + c0;
       load_f32<T, V>(da + off, va[u]);
       load_f32<T, V>(z + off, vz[u]);
       if (AOUT) load_f32<T, V>(aout + off, vo[u]);
+      if (MS == 2) mb[u] = mask[(r + (int64_t)u * TY) * CG + cg];
     }
 #pragma unroll
-    for (int u = 0; u < 4; ++u) one(va[u], vz[u], vo[u], rz[u], rs[u]);
+    for (int u = 0; u < 4; ++u) one(va[u], vz[u], vo[u], mb[u], rz[u], rs[u]);
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       const int64_t off = (r + (int64_t)u * TY) * g.C + c0;
@@ -402,10 +424,12 @@ __global__ void __launch_bounds__(256) bn_bwd_apply_kernel(const T* __restrict__
   for (; r < r1; r += TY) {
     const int64_t off = r * g.C + c0;
     float va[V], vz[V], vo[V], rz[V], rs[V];
+    unsigned mb = 0u;
     load_f32<T, V>(da + off, va);
     load_f32<T, V>(z + off, vz);
     if (AOUT) load_f32<T, V>(aout + off, vo);
-    one(va, vz, vo, rz, rs);
+    if (MS == 2) mb = mask[r * CG + cg];
+    one(va, vz, vo, mb, rz, rs);
     store_f32<T, V>(dz + off, rz);
     if (DSKIP) store_f32<T, V>(dskip + off, rs);
   }
@@ -693,14 +717,15 @@ void launch_bn_eval_stats(hipStream_t st, const float* running, const float* gam
   OSEQ_LAUNCH(bn_eval_stats_kernel, dim3(ceil_div(C, 256)), dim3(256), 0, st, running, gamma, beta, eps, C, stats);
 }
 
-void launch_bn_apply(hipStream_t st, int dt, const void* z, const float* stats, const void* skip, void* out, int64_t rows,
-                     int C, int relu) {
+void launch_bn_apply(hipStream_t st, int dt, const void* z, const float* stats, const void* skip, void* out, void* mask,
+                     int64_t rows, int C, int relu) {
 #define CALL(T, V)                                                                                                    \
   { const int64_t groups = rows * (C / V);                                                                             \
+    uint8_t* mk = V > 1 ? (uint8_t*)mask : nullptr;                                                                    \
     if (skip) OSEQ_LAUNCH((bn_apply_kernel<T, V, true>), dim3(ceil_div(groups, 256)), dim3(256), 0, st,         \
-                                 (const T*)z, stats, (const T*)skip, (T*)out, groups, C, relu);                        \
+                                 (const T*)z, stats, (const T*)skip, (T*)out, mk, groups, C, relu);                    \
     else OSEQ_LAUNCH((bn_apply_kernel<T, V, false>), dim3(ceil_div(groups, 256)), dim3(256), 0, st,             \
-                            (const T*)z, stats, (const T*)skip, (T*)out, groups, C, relu); }
+                            (const T*)z, stats, (const T*)skip, (T*)out, mk, groups, C, relu); }
   DISPATCH_TV(dt, C, CALL);
 #undef CALL
 }
@@ -717,21 +742,23 @@ void launch_bn_apply_pool(hipStream_t st, int dt, const void* z, const float* st
 #undef CALL
 }
 
-void launch_bn_bwd(hipStream_t st, int dt, const void* da, const void* z, const void* aout, const float* stats, int64_t rows,
-                   int C, int relu, int nblk, float* ws, float* dgamma, float* dbeta, void* dz, void* dskip) {
-  RedArgs g{}; g.a = da; g.z = z; g.aout = aout; g.stats = stats; g.partial = ws; g.rows = rows; g.C = C; g.relu = relu;
-  g.nblk = nblk;
+void launch_bn_bwd(hipStream_t st, int dt, const void* da, const void* z, const void* aout, const void* mask,
+                   const float* stats, int64_t rows, int C, int relu, int nblk, float* ws, float* dgamma, float* dbeta,
+                   void* dz, void* dskip) {
+  RedArgs g{}; g.a = da; g.z = z; g.aout = aout; g.mask = (const uint8_t*)mask; g.stats = stats; g.partial = ws; g.rows = rows;
+  g.C = C; g.relu = relu; g.nblk = nblk;
   launch_colreduce<RED_BN_BWD>(st, dt, g);
   float* coef = ws + (int64_t)nblk * 2 * C;
   OSEQ_LAUNCH(bn_bwd_finalize_kernel, dim3(ceil_div(C, 4)), dim3(256), 0, st, ws, nblk, C, (double)rows, dgamma,
                      dbeta, coef);
-#define APPLY(T, V, AO, DS)                                                                                             \
-  OSEQ_LAUNCH((bn_bwd_apply_kernel<T, V, AO, DS>), grid, dim3(256), 0, st, (const T*)da, (const T*)z,             \
-                     (const T*)aout, stats, coef, (T*)dz, (T*)dskip, ra)
+#define APPLY(T, V, MS, DS)                                                                                             \
+  OSEQ_LAUNCH((bn_bwd_apply_kernel<T, V, MS, DS>), grid, dim3(256), 0, st, (const T*)da, (const T*)z,             \
+                     (const T*)aout, (const uint8_t*)mask, stats, coef, (T*)dz, (T*)dskip, ra)
 #define CALL(T, V)                                                                                                      \
   { RowArgs ra{}; dim3 grid; row_tiling(rows, C, V, ra, grid); ra.relu = relu;                                           \
-    if (aout) { if (dskip) APPLY(T, V, true, true); else APPLY(T, V, true, false); }                                     \
-    else { if (dskip) APPLY(T, V, false, true); else APPLY(T, V, false, false); } }
+    if (mask && V > 1) { if (dskip) APPLY(T, V, 2, true); else APPLY(T, V, 2, false); }                                  \
+    else if (aout) { if (dskip) APPLY(T, V, 1, true); else APPLY(T, V, 1, false); }                                      \
+    else { if (dskip) APPLY(T, V, 0, true); else APPLY(T, V, 0, false); } }
   DISPATCH_TV(dt, C, CALL);
 #undef CALL
 #undef APPLY

@@ -25,14 +25,19 @@ void launch_bn_stats_finalize(hipStream_t st, float* partial, int64_t rows, int 
 // inference mode: (mean, rstd, scale, shift) from the running statistics [2][C] instead of the batch
 void launch_bn_eval_stats(hipStream_t st, const float* running, const float* gamma, const float* beta, float eps, int C,
                           float* stats);
-void launch_bn_apply(hipStream_t st, int dt, const void* z, const float* stats, const void* skip, void* out, int64_t rows,
-                     int C, int relu);
+// mask (null, or with a skip connection and C a multiple of 16 / element size): receives the ReLU decisions as bits,
+// byte (row * C + c) / V for the V = 16 / element size channels from c
+void launch_bn_apply(hipStream_t st, int dt, const void* z, const float* stats, const void* skip, void* out, void* mask,
+                     int64_t rows, int C, int relu);
 // BatchNorm apply and the 2x2 max-pool behind it in one pass (H, W even): z [N][H][W][C] -> a (may be null: not kept)
 // and y [N][H/2][W/2][C]
 void launch_bn_apply_pool(hipStream_t st, int dt, const void* z, const float* stats, void* a, void* y, int N, int H, int W,
                           int C, int relu);
-void launch_bn_bwd(hipStream_t st, int dt, const void* da, const void* z, const void* aout, const float* stats, int64_t rows,
-                   int C, int relu, int nblk, float* ws, float* dgamma, float* dbeta, void* dz, void* dskip);
+// ReLU decisions: from mask (bits as launch_bn_apply writes them, applied whatever relu says) if given, else from the
+// sign of aout if given, else redone from z when relu is set
+void launch_bn_bwd(hipStream_t st, int dt, const void* da, const void* z, const void* aout, const void* mask,
+                   const float* stats, int64_t rows, int C, int relu, int nblk, float* ws, float* dgamma, float* dbeta,
+                   void* dz, void* dskip);
 // the same where dy is the gradient of the 2x2 max-pool that follows the activation ([N][H/2][W/2][C]; H, W even): the
 // pool's own backward pass is not run
 void launch_bn_bwd_pool(hipStream_t st, int dt, const void* dy, const void* z, const float* stats, int N, int H, int W, int C,
@@ -76,16 +81,18 @@ int conv_mfma_dgrad_splits(int dt, const ConvGeom& g);
 int conv_mfma_fwd_stat_blocks(int dt, const ConvGeom& g);
 void launch_conv_fwd_mfma(hipStream_t st, int dt, const void* x, const void* w, const float* bias, void* out,
                           float* partial, float* stat_partial, int splits, const ConvGeom& g, int relu);
-void launch_conv_dgrad_mfma(hipStream_t st, int dt, const void* dz, const void* wt, const void* addend, void* dx,
-                            float* partial, int splits, const ConvGeom& g);
+// addend_mask (null, or with an addend): ReLU decisions as bits (as launch_bn_apply writes them); the addend counts
+// as zero where its bit is clear
+void launch_conv_dgrad_mfma(hipStream_t st, int dt, const void* dz, const void* wt, const void* addend,
+                            const void* addend_mask, void* dx, float* partial, int splits, const ConvGeom& g);
 // 1x1 convolutions in 16-bit storage as a streaming GEMM (k_conv_pointwise.hip); used by the MFMA launchers above
 bool conv_pointwise_fwd_ok(int dt, const ConvGeom& g);
 bool conv_pointwise_dgrad_ok(int dt, const ConvGeom& g);
 int conv_pointwise_stat_blocks(const ConvGeom& g);
 void launch_conv_fwd_pointwise(hipStream_t st, int dt, const void* x, const void* w, const float* bias, void* out,
                                float* stat_partial, const ConvGeom& g, int relu);
-void launch_conv_dgrad_pointwise(hipStream_t st, int dt, const void* dz, const void* wt, const void* addend, void* dx,
-                                 const ConvGeom& g);
+void launch_conv_dgrad_pointwise(hipStream_t st, int dt, const void* dz, const void* wt, const void* addend,
+                                 const uint8_t* addend_mask, void* dx, const ConvGeom& g);
 // 3x3 stride-1 weight gradient with all nine taps per block (k_conv_wgrad3x3.hip); used by the MFMA launcher below
 bool conv_wgrad3x3_ok(int dt, const ConvGeom& g);
 int conv_wgrad3x3_splits(int dt, const ConvGeom& g);

@@ -73,6 +73,14 @@ struct Builder {
     FOp a = s;
     a.kind = F_BN_APPLY; a.skip = skip; a.relu = relu;
     a.out = new_tensor(f.N, f.P, f.Q, cout, p.esize, unit);
+    // The ReLU behind a skip connection cannot be redone from z alone; backward needs its decisions.  They are kept as
+    // one bit per element (one byte per group of 16 / esize channels), a sixteenth of the bytes of the output that
+    // backward would otherwise read twice.
+    const int vgroup = 16 / p.esize;
+    if (skip >= 0 && relu && cout % vgroup == 0) {
+      a.mask = new_tensor(f.N, f.P, f.Q, cout / vgroup, 1, unit);
+      p.tensors[a.mask].needs_grad = false;
+    }
     p.fops.push_back(a);
     return a.out;
   }
@@ -236,10 +244,13 @@ struct Scheduler {
   std::vector<int> readers;      // [LTensor] -> number of forward operations that read it
   std::vector<int> via_pool;     // [LTensor] -> Inst id of the gradient of the max-pool output behind it, when the
                                  //              pool's backward is left to the BatchNorm backward in front of it
+  std::vector<int> gmask;        // [LTensor] -> Inst id of a ReLU bit mask that grad[t] still has to be multiplied by
+                                 //              (the gradient through a skip connection is not written out: its
+                                 //              reader applies the mask to the block output's gradient itself), or -1
   explicit Scheduler(Plan& pl)
       : p(pl), cur(pl.tensors.size(), -1), grad(pl.tensors.size(), -1), stat_ws(pl.tensors.size(), -1),
         bn_apply_of(pl.tensors.size(), -1), rebuilt(pl.tensors.size(), 0), readers(pl.tensors.size(), 0),
-        via_pool(pl.tensors.size(), -1) {
+        via_pool(pl.tensors.size(), -1), gmask(pl.tensors.size(), -1) {
     for (size_t fi = 0; fi < pl.fops.size(); ++fi) {
       const FOp& f = pl.fops[fi];
       if (f.kind == F_BN_APPLY) bn_apply_of[f.out] = (int)fi;
@@ -312,6 +323,7 @@ struct Scheduler {
         s.in[0] = cur[f.x]; s.in[1] = cur[f.stats]; s.in[2] = f.skip >= 0 ? cur[f.skip] : -1;
         s.out[0] = value_inst(f.out);
         if (pool_fused(fi + 1, seg)) s.out[1] = value_inst(p.fops[fi + 1].out);  // the same kernel also pools
+        if (f.mask >= 0) s.out[2] = value_inst(f.mask);
         break;
       }
       case F_POOL: {
@@ -345,6 +357,18 @@ struct Scheduler {
     return cur[t];
   }
 
+  // May the reader of the gradient through operation fi's skip connection take it as (gradient of the block output,
+  // ReLU bit mask) instead of a tensor of its own?  A BatchNorm backward (projection shortcut) always can; a
+  // convolution's data gradient can where it runs on the matrix cores (their shared epilogue applies the mask).
+  bool masked_skip_grad_ok(int fi) const {
+    const FOp& f = p.fops[fi];
+    if (f.mask < 0 || f.skip < 0) return false;
+    if (bn_apply_of[f.skip] >= 0 && p.fops[bn_apply_of[f.skip]].unit == f.unit) return true;
+    for (int j = p.unit_first_fop[f.unit]; j < p.unit_last_fop[f.unit]; ++j)
+      if (p.fops[j].kind == F_CONV && p.fops[j].x == f.skip) return p.fops[j].dgrad_algo == ALGO_MFMA;
+    return false;
+  }
+
   bool emit_fop_backward(int fi, int seg) {
     const FOp& f = p.fops[fi];
     switch (f.kind) {
@@ -361,14 +385,22 @@ struct Scheduler {
         if (gin < 0 && via_pool[f.out] >= 0) { gin = via_pool[f.out]; variant = 1; }  // through the pool behind it
         if (gin < 0) { p.error = "internal: BN output has no gradient"; return false; }
         if (f.skip >= 0 && !f.relu) { p.error = "skip connection without ReLU is not supported"; return false; }
+        const int gin_mask = gmask[f.out];  // the incoming gradient still wants a mask (projection shortcut's BatchNorm)
         SOp& s = push(S_BN_BWD, fi, PH_BWD, seg);
         s.variant = variant;
         s.in[0] = gin; s.in[1] = cur[f.x]; s.in[2] = cur[f.stats];
         s.in[3] = (f.skip >= 0) ? cur[f.out] : -1;
-        s.out[0] = grad_inst(f.x); grad[f.x] = s.out[0];
+        if (gin_mask >= 0) {
+          if (f.skip >= 0 || variant != 0) { p.error = "internal: masked gradient into a BatchNorm with a skip connection"; return false; }
+          s.in[3] = gin_mask; s.variant = 2;
+        } else if (f.mask >= 0) {
+          s.in[3] = cur[f.mask]; s.variant = 2;
+        }
+        s.out[0] = grad_inst(f.x); grad[f.x] = s.out[0]; gmask[f.x] = -1;
         if (f.skip >= 0 && p.tensors[f.skip].needs_grad) {
           if (grad[f.skip] >= 0) { p.error = "internal: skip gradient must be the first contribution"; return false; }
-          s.out[1] = grad_inst(f.skip); grad[f.skip] = s.out[1];
+          if (masked_skip_grad_ok(fi)) { grad[f.skip] = gin; gmask[f.skip] = cur[f.mask]; }  // nothing written
+          else { s.out[1] = grad_inst(f.skip); grad[f.skip] = s.out[1]; gmask[f.skip] = -1; }
         }
         s.out[2] = new_inst(-1, ((uint64_t)f.red_blocks * 2 + 2) * f.C * 4, false);
         return true;
@@ -395,8 +427,8 @@ struct Scheduler {
         }
         if (p.tensors[f.x].needs_grad) {
           SOp& s = push(S_DGRAD, fi, PH_BWD, seg);
-          s.in[0] = g; s.in[1] = grad[f.x];
-          s.out[0] = grad_inst(f.x); grad[f.x] = s.out[0];
+          s.in[0] = g; s.in[1] = grad[f.x]; s.in[2] = grad[f.x] >= 0 ? gmask[f.x] : -1;
+          s.out[0] = grad_inst(f.x); grad[f.x] = s.out[0]; gmask[f.x] = -1;
           if (f.dgrad_splits > 1) s.out[1] = new_inst(-1, (uint64_t)f.dgrad_splits * f.N * f.H * f.W * f.C * 4, false);
         }
         return true;
@@ -481,6 +513,7 @@ bool build_schedule(Plan& p) {
       if (uses[op.out[0]] == 0) op.out[0] = -1;
       else if (uses[op.out[1]] == 0) op.out[1] = -1;
     }
+    if (live && op.kind == S_BN_APPLY && op.out[2] >= 0 && uses[op.out[2]] == 0) op.out[2] = -1;  // the mask likewise
     if (live) for (int x : op.in) if (x >= 0) ++uses[x];
   }
   // lifetimes
@@ -530,18 +563,48 @@ bool build_schedule(Plan& p) {
   return true;
 }
 
+// Per-unit byte model of what a segment holds for its backward pass, read off a k = 1 schedule.  A tensor kept for
+// backward counts for the unit that made it, except a unit's output: that is kept as the input of the next unit (whose
+// backward reads it), so inside a segment it counts for every unit but the last, and for the last one only where the
+// unit's own backward reads it.  The first unit's input is the segment's checkpoint and is counted separately.
+struct SegModel {
+  std::vector<uint64_t> own_pre, out_pre, out_self, ck;
+  explicit SegModel(const Plan& all) {
+    const int nu = (int)all.units.size();
+    std::vector<uint64_t> own(nu, 0), outb(nu, 0);
+    std::vector<char> self(nu, 0);
+    for (const Inst& t : all.insts) {
+      if (!t.held || t.logical < 0) continue;
+      const int u = all.tensors[t.logical].unit;
+      if (u < 0) continue;
+      if (t.logical == all.unit_out[u]) outb[u] += t.bytes; else own[u] += t.bytes;
+    }
+    for (const SOp& s : all.sched) {
+      if (!s.live || s.phase != PH_BWD || s.fop < 0) continue;
+      const int u = all.fops[s.fop].unit;
+      if (u < 0) continue;
+      for (int i : s.in)
+        if (i >= 0 && all.insts[i].fwd_value && all.insts[i].logical == all.unit_out[u]) self[u] = 1;
+    }
+    own_pre.assign(nu + 1, 0); out_pre.assign(nu + 1, 0); out_self.assign(nu, 0); ck.assign(nu, 0);
+    for (int u = 0; u < nu; ++u) {
+      own_pre[u + 1] = own_pre[u] + own[u];
+      out_pre[u + 1] = out_pre[u] + outb[u];
+      out_self[u] = self[u] ? outb[u] : 0;
+      ck[u] = all.tensors[all.unit_in[u]].bytes;
+    }
+  }
+  // bytes units [s, e) hold at the end of their forward pass or replay
+  uint64_t saved(int s, int e) const { return (own_pre[e] - own_pre[s]) + (out_pre[e - 1] - out_pre[s]) + out_self[e - 1]; }
+  uint64_t total() const { return own_pre.back() + out_pre.back(); }
+};
+
 uint64_t model_peak_saved(const Plan& all_stored, const std::vector<int>& seg_begin) {
-  // per-unit bytes kept for backward, from a k = 1 schedule
-  const int nu = (int)all_stored.units.size();
-  std::vector<uint64_t> saved_u(nu, 0);
-  for (const Inst& t : all_stored.insts)
-    if (t.held && t.logical >= 0 && all_stored.tensors[t.logical].unit >= 0) saved_u[all_stored.tensors[t.logical].unit] += t.bytes;
+  const SegModel m(all_stored);
   uint64_t ck = 0, peak = 0;
   for (size_t j = 0; j + 1 < seg_begin.size(); ++j) {
-    ck += all_stored.tensors[all_stored.unit_in[seg_begin[j]]].bytes;
-    uint64_t s = 0;
-    for (int u = seg_begin[j]; u < seg_begin[j + 1]; ++u) s += saved_u[u];
-    peak = std::max(peak, ck + s);
+    ck += m.ck[seg_begin[j]];
+    peak = std::max(peak, ck + m.saved(seg_begin[j], seg_begin[j + 1]));
   }
   return peak;
 }
@@ -574,10 +637,8 @@ bool choose_segments(Plan& p) {
   all.cfg.boundaries = nullptr;
   all.seg_begin = {0, nu};
   if (!build_schedule(all)) { p.error = all.error; return false; }
-  std::vector<uint64_t> saved_u(nu, 0), pre(nu + 1, 0), ck(nu, 0);
-  for (const Inst& t : all.insts)
-    if (t.held && t.logical >= 0 && all.tensors[t.logical].unit >= 0) saved_u[all.tensors[t.logical].unit] += t.bytes;
-  for (int u = 0; u < nu; ++u) { pre[u + 1] = pre[u] + saved_u[u]; ck[u] = all.tensors[all.unit_in[u]].bytes; }
+  const SegModel model(all);
+  const std::vector<uint64_t>& ck = model.ck;
   const uint64_t INF = ~0ull;
   std::vector<int> best;
   auto feasible = [&](uint64_t T, std::vector<int>* cuts) {
@@ -590,7 +651,7 @@ bool choose_segments(Plan& p) {
         for (int s = j - 1; s < e; ++s) {
           if (g[j - 1][s] == INF) continue;
           uint64_t c = g[j - 1][s] + ck[s];
-          if (c + (pre[e] - pre[s]) > T) continue;
+          if (c + model.saved(s, e) > T) continue;
           if (c < g[j][e]) { g[j][e] = c; from[j][e] = s; }
         }
     if (g[k][nu] == INF) return false;
@@ -602,7 +663,7 @@ bool choose_segments(Plan& p) {
     }
     return true;
   };
-  uint64_t lo = 0, hi = pre[nu];
+  uint64_t lo = 0, hi = model.total();
   for (int u = 0; u < nu; ++u) hi += ck[u];
   while (lo < hi) {
     uint64_t mid = lo + (hi - lo) / 2;
@@ -648,7 +709,7 @@ bool choose_segments(Plan& p) {
           for (size_t i = 0; i < S[j - 1][s0].size(); ++i) {
             const St& st = S[j - 1][s0][i];
             const uint64_t c = st.ck + ck[s0];
-            if (c + (pre[e] - pre[s0]) > T) continue;
+            if (c + model.saved(s0, e) > T) continue;
             cand.push_back(St{c, st.cost + (e == nu ? 0.0 : cpre[e] - cpre[s0]), s0, (int)i});
           }
         std::sort(cand.begin(), cand.end(), [](const St& a, const St& b) { return a.ck != b.ck ? a.ck < b.ck : a.cost < b.cost; });

@@ -38,6 +38,8 @@ struct FOp {
   FKind kind = F_CONV;
   int unit = -1;
   int x = -1, skip = -1, stats = -1, out = -1;  // LTensor ids
+  int mask = -1;  // F_BN_APPLY with a skip connection: LTensor of the ReLU decisions, one bit per element (one byte per
+                  // 16 bytes of the output), which the backward pass reads instead of the output itself; -1: none
   int aux[3] = {-1, -1, -1};                     // head: feat, logits, dlogits
   int N = 0, H = 0, W = 0, C = 0, K = 0, R = 1, S = 1, stride = 1, pad = 0, P = 0, Q = 0;
   int relu = 0, has_bias = 0, has_bn = 0;
@@ -77,7 +79,9 @@ struct SOp {
   int phase = 0, seg = 0;
   int in[4] = {-1, -1, -1, -1};
   int out[4] = {-1, -1, -1, -1};
-  int variant = 0;  // S_BN_BWD: 1 = in[0] is the gradient of the 2x2 max-pool behind the activation (pooled size)
+  int variant = 0;  // S_BN_BWD: 1 = in[0] is the gradient of the 2x2 max-pool behind the activation (pooled size);
+                    // 2 = in[3] is a bit mask of ReLU decisions (FOp::mask) to apply to in[0], not an activation.
+                    // S_DGRAD: in[2] >= 0 is such a mask for the addend in[1]
   bool live = true;
 };
 

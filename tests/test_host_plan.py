@@ -91,12 +91,15 @@ def test_storage_mode_1_keeps_z_only_analytic_count():
     p0, p1 = _plan(2, k_segments=1), _plan(2, k_segments=1, storage_mode=1)
     assert p1.planned_peak_saved_bytes == _vgg_saved_bytes(True) < p0.planned_peak_saved_bytes
     assert p1.n_launches == p0.n_launches + 3  # one rebuilding pass per conv-BN-ReLU that feeds a convolution
-    # ResNet-152 shape of config 5: the published Z-only figures of the byte model (87.5 GiB all stored)
+    # ResNet-152 shape of config 5: the Z-only figure of the byte model (87.5 GiB all stored), plus the ReLU decisions
+    # of the 50 block outputs as bits (a sixteenth of their 32.75 GiB), minus the last block's output, which backward
+    # no longer reads (0.25 GiB)
     q = _plan(5, k_segments=1, storage_mode=1, activation_budget_bytes=0)
-    assert abs(q.planned_peak_saved_bytes / 2 ** 30 - 87.5) < 0.05
+    blocks = 3 * 2.0 + 8 * 1.0 + 36 * 0.5 + 3 * 0.25  # GiB of block outputs: bf16, batch 4096
+    assert abs(q.planned_peak_saved_bytes / 2 ** 30 - (87.5 + blocks / 16 - 0.25)) < 0.05
     for idx in (3, 4, 6):
         a, bb = _plan(idx, activation_budget_bytes=0), _plan(idx, activation_budget_bytes=0, storage_mode=1)
-        assert bb.planned_peak_saved_bytes < 0.9 * a.planned_peak_saved_bytes
+        assert bb.planned_peak_saved_bytes < 0.95 * a.planned_peak_saved_bytes
         assert bb.act_arena_bytes < a.act_arena_bytes
 
 
@@ -106,7 +109,8 @@ def test_automatic_choice_of_segments_and_storage_mode_under_a_budget():
     fixed = {k: _plan(5, k_segments=k, activation_budget_bytes=0).act_arena_bytes for k in (1, 2, 3, 4)}
     p = SeqPlan.from_workload(w, k_segments=0, storage_mode=-1)  # the configuration's 32 GiB
     assert (p.k_segments, p.storage_mode) == (4, 0) and len(p.boundaries) == 3
-    assert p.act_arena_bytes == fixed[4] <= 32 * 2 ** 30 < fixed[3]
+    # (without a budget plan mode 2 takes the least peak; with one it may spend the room up to it on less recomputation)
+    assert fixed[4] <= p.act_arena_bytes <= 32 * 2 ** 30 < fixed[3]
     p = SeqPlan.from_workload(w, k_segments=0, storage_mode=-1, activation_budget_bytes=0)
     assert (p.k_segments, p.storage_mode, p.act_arena_bytes) == (1, 0, fixed[1])
     # rebuilding activations is tried before a further segment
@@ -153,7 +157,7 @@ def test_peak_shrinks_with_segments_and_plan_is_reproducible():
     # least recomputation within the least peak: the last segment (never replayed) takes every unit it can, so the
     # replay is shorter than under either other mode and nothing more is kept
     pt = _plan(2, k_segments=4, plan_mode=2)
-    assert pt.boundaries == [2, 4, 6] == _plan(2).boundaries  # the benchmark configuration's own mode
+    assert pt.boundaries == [2, 5, 7] == _plan(2).boundaries  # the benchmark configuration's own mode
     assert pt.planned_peak_saved_bytes <= pm.planned_peak_saved_bytes
     assert pt.n_replay_launches <= pm.n_replay_launches < p4.n_replay_launches
     for idx in (3, 4, 6):
