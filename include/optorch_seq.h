@@ -95,7 +95,12 @@ typedef struct {
                                       (fewer saved bytes, one more pass over Z per layer; gradients
                                       bit-identical to mode 0); -1 = chosen by create: 0 if the arena
                                       then fits activation_budget_bytes, else 1 (tried before a
-                                      further segment, which costs more time)                      */
+                                      further segment, which costs more time).  In modes 0 and 1 an A
+                                      inside a unit whose only reader is a convolution that can apply
+                                      the BatchNorm itself while loading Z (16-bit 1x1 layers) is
+                                      never written at all, in forward or backward; 2 = as mode 0 but
+                                      every A is written and kept (same bits; the layout the other
+                                      modes are checked against)                                   */
 } optorch_seq_config_t;
 
 /* Plans the step on the host: expands units into kernels, chooses segment boundaries,

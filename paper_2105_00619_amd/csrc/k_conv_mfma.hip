@@ -972,11 +972,14 @@ int conv_mfma_fwd_stat_blocks(int dt, const ConvGeom& g) {
 
 // stat_partial: null, or [conv_mfma_fwd_stat_blocks][2][C_out] floats receiving per-block sums and sums of squares
 // of the stored outputs
+bool conv_fold_fwd_ok(int dt, const ConvGeom& g) { return conv_pointwise_fold_ok(dt, g); }
+
 void launch_conv_fwd_mfma(hipStream_t st, int dt, const void* x, const void* w, const float* bias, void* out,
-                          float* partial, float* stat_partial, int splits, const ConvGeom& g, int relu) {
+                          float* partial, float* stat_partial, int splits, const ConvGeom& g, int relu, const float* fold,
+                          int fold_relu) {
   PatchShape pv; PatchArgs pa{};
   if (conv_pointwise_fwd_ok(dt, g)) {
-    launch_conv_fwd_pointwise(st, dt, x, w, bias, out, stat_partial, g, relu);
+    launch_conv_fwd_pointwise(st, dt, x, w, bias, out, stat_partial, g, relu, fold, fold_relu);
     return;
   }
   if (patch_pick(dt, g.N, g.P, g.Q, g.C, g.K, g.R, g.S, g.stride, pv, pa)) {
@@ -1083,6 +1086,8 @@ struct WGradArgs {
   int H, W, C, K, R, S, stride, pad, P, Q;
   int pixels, chunk;  // chunk: pixels per blockIdx.z, a multiple of the depth tile
   FastDiv divQ, divPQ;
+  const float* fold;  // FOLD: x is the z of a BatchNorm, this its [4][C] statistics tensor; the pieces of x become the
+  int fold_relu;      // activation (scale, shift, ReLU if fold_relu, one rounding) on their way to LDS
 };
 
 template <class T> struct WFrag;
@@ -1118,7 +1123,7 @@ constexpr size_t wgrad_lds_bytes() {
   return (size_t)3 * (sizeof(T) == 4 ? 16 : 32) * (BM + BN + 2 * (sizeof(T) == 4 ? 4 : 16)) * sizeof(T);
 }
 
-template <class T, int BM, int BN, int WGM = 2, int WGN = 2>
+template <class T, int BM, int BN, int WGM = 2, int WGN = 2, bool FOLD = false>
 __global__ void __launch_bounds__(64 * WGM * WGN) conv_wgrad_kernel(const T* __restrict__ x, const T* __restrict__ dz,
                                                                     float* __restrict__ out, WGradArgs a) {
   constexpr bool F32 = sizeof(T) == 4;
@@ -1187,10 +1192,22 @@ __global__ void __launch_bounds__(64 * WGM * WGN) conv_wgrad_kernel(const T* __r
     }
     va[p] = ma; vb[p] = mb;
   };
+  // FOLD: a thread's pieces of x all cover the same EV channels, whose scale and shift it keeps in registers
+  static_assert(NT % (BN / EV) == 0, "a thread's pieces of x must share their channels");
+  float fsc[EV], fsh[EV];
+  if (FOLD) {
+    const int cv = tid % (BN / EV);
+    load_f32<float, EV>(a.fold + 2 * C + c0 + cv * EV, fsc);
+    load_f32<float, EV>(a.fold + 3 * C + c0 + cv * EV, fsh);
+  }
   auto sstore = [&](auto G, int stage) {
     constexpr int p = decltype(G)::value;
     T* sa = lds + stage * STAGE;
     T* sb = sa + A_ELEMS;
+    if (FOLD) {
+#pragma unroll
+      for (int i = 0; i < B_CH32; ++i) rb[p][i] = bn_fold_chunk<T>(rb[p][i], fsc, fsh, a.fold_relu);
+    }
 #pragma unroll
     for (int i = 0; i < A_CH32; ++i) {
       const int id = tid + i * NT, px = id / (BM / EV), kv = id % (BM / EV);
@@ -1367,8 +1384,9 @@ int conv_mfma_wgrad_splits(int dt, const ConvGeom& g) {
   return (int)(want < 1 ? 1 : want);
 }
 
-template <class T>
-static void launch_wgrad_t(hipStream_t st, const void* x, const void* dz, float* dst, int splits, const ConvGeom& g) {
+template <class T, bool FOLD>
+static void launch_wgrad_t(hipStream_t st, const void* x, const void* dz, float* dst, int splits, const ConvGeom& g,
+                           const float* fold, int fold_relu) {
   constexpr int depth = sizeof(T) == 4 ? 16 : 32;
   WGradArgs a;
   a.H = g.H; a.W = g.W; a.C = g.C; a.K = g.K; a.R = g.R; a.S = g.S; a.stride = g.stride; a.pad = g.pad; a.P = g.P; a.Q = g.Q;
@@ -1377,15 +1395,16 @@ static void launch_wgrad_t(hipStream_t st, const void* x, const void* dz, float*
   a.chunk = (chunk + depth - 1) / depth * depth;
   a.divQ = make_fastdiv((uint32_t)g.Q);
   a.divPQ = make_fastdiv((uint32_t)(g.P * g.Q));
+  a.fold = fold; a.fold_relu = fold_relu;
   if constexpr (sizeof(T) == 2) {
     if (wgrad_large_ok(DT_BF16, g)) {
       constexpr size_t sm = wgrad_lds_bytes<T, 256, 256, 2>();
       static bool attr_done = false;
       if (!attr_done) {
-        (void)hipFuncSetAttribute((const void*)conv_wgrad_kernel<T, 256, 256, 2, 4>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sm);
+        (void)hipFuncSetAttribute((const void*)conv_wgrad_kernel<T, 256, 256, 2, 4, FOLD>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sm);
         attr_done = true;
       }
-      OSEQ_LAUNCH((conv_wgrad_kernel<T, 256, 256, 2, 4>), dim3(g.K / 256, g.C / 256, splits), dim3(512), sm, st, (const T*)x,
+      OSEQ_LAUNCH((conv_wgrad_kernel<T, 256, 256, 2, 4, FOLD>), dim3(g.K / 256, g.C / 256, splits), dim3(512), sm, st, (const T*)x,
                   (const T*)dz, dst, a);
       return;
     }
@@ -1393,10 +1412,10 @@ static void launch_wgrad_t(hipStream_t st, const void* x, const void* dz, float*
   const bool m128 = g.K % 128 == 0, n128 = g.C % 128 == 0;
   const int bm = m128 ? 128 : 64, bn = n128 ? 128 : 64;
   dim3 grid(g.K / bm, g.R * g.S * (g.C / bn), splits), block(256);
-  if (m128 && n128) OSEQ_LAUNCH((conv_wgrad_kernel<T, 128, 128>), grid, block, (wgrad_lds_bytes<T, 128, 128, 2>()), st, (const T*)x, (const T*)dz, dst, a);
-  else if (m128) OSEQ_LAUNCH((conv_wgrad_kernel<T, 128, 64>), grid, block, (wgrad_lds_bytes<T, 128, 64, 2>()), st, (const T*)x, (const T*)dz, dst, a);
-  else if (n128) OSEQ_LAUNCH((conv_wgrad_kernel<T, 64, 128>), grid, block, (wgrad_lds_bytes<T, 64, 128, 2>()), st, (const T*)x, (const T*)dz, dst, a);
-  else OSEQ_LAUNCH((conv_wgrad_kernel<T, 64, 64>), grid, block, (wgrad_lds_bytes<T, 64, 64, 2>()), st, (const T*)x, (const T*)dz, dst, a);
+  if (m128 && n128) OSEQ_LAUNCH((conv_wgrad_kernel<T, 128, 128, 2, 2, FOLD>), grid, block, (wgrad_lds_bytes<T, 128, 128, 2>()), st, (const T*)x, (const T*)dz, dst, a);
+  else if (m128) OSEQ_LAUNCH((conv_wgrad_kernel<T, 128, 64, 2, 2, FOLD>), grid, block, (wgrad_lds_bytes<T, 128, 64, 2>()), st, (const T*)x, (const T*)dz, dst, a);
+  else if (n128) OSEQ_LAUNCH((conv_wgrad_kernel<T, 64, 128, 2, 2, FOLD>), grid, block, (wgrad_lds_bytes<T, 64, 128, 2>()), st, (const T*)x, (const T*)dz, dst, a);
+  else OSEQ_LAUNCH((conv_wgrad_kernel<T, 64, 64, 2, 2, FOLD>), grid, block, (wgrad_lds_bytes<T, 64, 64, 2>()), st, (const T*)x, (const T*)dz, dst, a);
 }
 
 // out[i] = sum over pixel ranges s of partial[s][i], in a fixed order: G groups of threads each add the ranges
@@ -1439,13 +1458,23 @@ static void launch_wgrad_reduce(hipStream_t st, const float* partial, float* out
     OSEQ_LAUNCH(wgrad_reduce_kernel<1>, dim3(ceil_div(quads, 256)), dim3(256), 0, st, partial, out, n, splits);
 }
 
+// the kernel of this file in a 16-bit mode (the all-taps 3x3 kernel reads its input as stored)
+bool conv_fold_wgrad_ok(int dt, const ConvGeom& g) {
+  return dt != DT_F32 && conv_mfma_wgrad_ok(dt, g) && !conv_wgrad3x3_ok(dt, g);
+}
+
 void launch_conv_wgrad_mfma(hipStream_t st, int dt, const void* x, const void* dz, float* dw, float* partial, int splits,
-                            const ConvGeom& g) {
+                            const ConvGeom& g, const float* fold, int fold_relu) {
   float* dst = splits > 1 ? partial : dw;
   if (conv_wgrad3x3_ok(dt, g)) launch_conv_wgrad3x3(st, dt, x, dz, dst, g);  // splits == conv_wgrad3x3_splits(dt, g)
-  else if (dt == DT_F32) launch_wgrad_t<float>(st, x, dz, dst, splits, g);
-  else if (dt == DT_BF16) launch_wgrad_t<bf16_t>(st, x, dz, dst, splits, g);
-  else launch_wgrad_t<f16_t>(st, x, dz, dst, splits, g);
+  else if (dt == DT_F32) launch_wgrad_t<float, false>(st, x, dz, dst, splits, g, nullptr, 0);
+  else if (dt == DT_BF16) {
+    if (fold) launch_wgrad_t<bf16_t, true>(st, x, dz, dst, splits, g, fold, fold_relu);
+    else launch_wgrad_t<bf16_t, false>(st, x, dz, dst, splits, g, nullptr, 0);
+  } else {
+    if (fold) launch_wgrad_t<f16_t, true>(st, x, dz, dst, splits, g, fold, fold_relu);
+    else launch_wgrad_t<f16_t, false>(st, x, dz, dst, splits, g, nullptr, 0);
+  }
   if (splits > 1) {
     launch_wgrad_reduce(st, partial, dw, (int64_t)g.K * g.R * g.S * g.C, splits);
   }

@@ -46,6 +46,8 @@ struct PwArgs {
   int dstH, dstW, srcH, srcW;
   FastDiv div_w, div_hw;  // by dstW and dstH * dstW
   const uint8_t* amask;   // data gradient with an addend: ReLU bit mask the addend is multiplied by, or null
+  const float* fold;      // forward: X is the z of a BatchNorm whose [4][Kd] statistics tensor this is; the rows are turned
+  int fold_relu;          //          into the activation (scale, shift, ReLU if fold_relu, one rounding) on their way to LDS
 };
 
 template <int V> struct IC { static constexpr int value = V; };
@@ -103,8 +105,9 @@ __device__ __forceinline__ void scatter_rows(const float* ep, int tid, int n0, i
 }
 
 // DGRAD: the data-gradient instantiation (addend and scatter, no bias / ReLU / sums); else the forward one
-template <class T, int BN, bool DGRAD>
-__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3)))
+// (FOLD needs some forty registers more: two blocks per CU instead of three)
+template <class T, int BN, bool DGRAD, bool FOLD = false>
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(FOLD ? 2 : 3, FOLD ? 2 : 3)))
 conv1x1_kernel(const T* __restrict__ X, const T* __restrict__ W, const float* __restrict__ bias, const T* __restrict__ addend,
                T* __restrict__ out, float* __restrict__ stat_partial, PwArgs a) {
   typedef typename Mma<T>::V FV;
@@ -154,9 +157,22 @@ conv1x1_kernel(const T* __restrict__ X, const T* __restrict__ W, const float* __
 #pragma unroll
     for (int i = 0; i < B_CH; ++i) rb[p][i] = *reinterpret_cast<const Chunk*>(brow[i] + kt * BK);
   };
-  auto sstore = [&](auto P, int stage) {
+  // FOLD: scale and shift of all Kd channels lie in LDS behind the stages; the pieces of tile kt become activations
+  float* ftab = reinterpret_cast<float*>(smem_raw + pw_smem_bytes<BN>());  // [2][Kd]
+  if (FOLD) {
+    for (int i = tid; i < Kd; i += 256) { ftab[i] = a.fold[2 * Kd + i]; ftab[Kd + i] = a.fold[3 * Kd + i]; }
+    __syncthreads();
+  }
+  auto sstore = [&](auto P, int stage, int kt) {
     constexpr int p = decltype(P)::value;
     T* st = lds + stage * STAGE;
+    if (FOLD) {
+      float sc[8], sh[8];
+      load_f32<float, 8>(ftab + kt * BK + vec * 8, sc);
+      load_f32<float, 8>(ftab + Kd + kt * BK + vec * 8, sh);
+#pragma unroll
+      for (int i = 0; i < A_CH; ++i) ra[p][i] = bn_fold_chunk<T>(ra[p][i], sc, sh, a.fold_relu);
+    }
 #pragma unroll
     for (int i = 0; i < A_CH; ++i) *reinterpret_cast<Chunk*>(&st[(row0 + i * 64) * PITCH + vec * 8]) = ra[p][i];
 #pragma unroll
@@ -201,16 +217,16 @@ conv1x1_kernel(const T* __restrict__ X, const T* __restrict__ W, const float* __
   gload(IC<1>{}, 1);
   int j = 0;
   for (; j + 3 < n; j += 2) {
-    sstore(IC<0>{}, 0); gload(IC<0>{}, j + 2); __syncthreads(); compute(0);
-    sstore(IC<1>{}, 1); gload(IC<1>{}, j + 3); __syncthreads(); compute(1);
+    sstore(IC<0>{}, 0, j); gload(IC<0>{}, j + 2); __syncthreads(); compute(0);
+    sstore(IC<1>{}, 1, j + 1); gload(IC<1>{}, j + 3); __syncthreads(); compute(1);
   }
   if (j + 2 < n) {  // odd number of steps: three left
-    sstore(IC<0>{}, 0); gload(IC<0>{}, j + 2); __syncthreads(); compute(0);
-    sstore(IC<1>{}, 1); __syncthreads(); compute(1);
-    sstore(IC<0>{}, 0); __syncthreads(); compute(0);
+    sstore(IC<0>{}, 0, j); gload(IC<0>{}, j + 2); __syncthreads(); compute(0);
+    sstore(IC<1>{}, 1, j + 1); __syncthreads(); compute(1);
+    sstore(IC<0>{}, 0, j + 2); __syncthreads(); compute(0);
   } else {
-    sstore(IC<0>{}, 0); __syncthreads(); compute(0);
-    sstore(IC<1>{}, 1); __syncthreads(); compute(1);
+    sstore(IC<0>{}, 0, j); __syncthreads(); compute(0);
+    sstore(IC<1>{}, 1, j + 1); __syncthreads(); compute(1);
   }
 
   // ---- epilogue: the rows of one wavefront pair at a time through LDS as fp32 [64][BN + 4]; the store half (bias /
@@ -268,7 +284,7 @@ template <int BM, int BN> constexpr size_t pwl_smem_bytes() {
 }
 
 // BM x BN tile, WGM x WGN wavefronts (wave tile BM / WGM x BN / WGN, at least 64 rows)
-template <class T, bool DGRAD, int BM, int BN, int WGM, int WGN>
+template <class T, bool DGRAD, int BM, int BN, int WGM, int WGN, bool FOLD = false>
 __global__ void __launch_bounds__(64 * WGM * WGN) __attribute__((amdgpu_waves_per_eu(2, 2)))
 conv1x1_large_kernel(const T* __restrict__ X, const T* __restrict__ W, const float* __restrict__ bias,
                      const T* __restrict__ addend, T* __restrict__ out, float* __restrict__ stat_partial, PwArgs a) {
@@ -315,9 +331,21 @@ conv1x1_large_kernel(const T* __restrict__ X, const T* __restrict__ W, const flo
 #pragma unroll
     for (int i = 0; i < B_CH; ++i) rb[p][i] = *reinterpret_cast<const Chunk*>(brow[i] + kt * BK);
   };
-  auto sstore = [&](auto P, int stage) {
+  float* ftab = reinterpret_cast<float*>(smem_raw + pwl_smem_bytes<BM, BN>());  // FOLD: [2][Kd] scale, shift
+  if (FOLD) {
+    for (int i = tid; i < Kd; i += NT) { ftab[i] = a.fold[2 * Kd + i]; ftab[Kd + i] = a.fold[3 * Kd + i]; }
+    __syncthreads();
+  }
+  auto sstore = [&](auto P, int stage, int kt) {
     constexpr int p = decltype(P)::value;
     T* st = lds + stage * STAGE;
+    if (FOLD) {
+      float sc[8], sh[8];
+      load_f32<float, 8>(ftab + kt * BK + vec * 8, sc);
+      load_f32<float, 8>(ftab + Kd + kt * BK + vec * 8, sh);
+#pragma unroll
+      for (int i = 0; i < A_CH; ++i) ra[p][i] = bn_fold_chunk<T>(ra[p][i], sc, sh, a.fold_relu);
+    }
 #pragma unroll
     for (int i = 0; i < A_CH; ++i) *reinterpret_cast<Chunk*>(&st[(row0 + i * RSTEP) * PITCH + vec * 8]) = ra[p][i];
 #pragma unroll
@@ -359,8 +387,8 @@ conv1x1_large_kernel(const T* __restrict__ X, const T* __restrict__ W, const flo
   gload(IC<1>{}, 1);
   for (int j = 0; j < n; j += 2) {
     const int t2 = j + 2 < n ? j + 2 : n - 1, t3 = j + 3 < n ? j + 3 : n - 1;
-    sstore(IC<0>{}, 0); gload(IC<0>{}, t2); __syncthreads(); compute(0);
-    sstore(IC<1>{}, 1); gload(IC<1>{}, t3); __syncthreads(); compute(1);
+    sstore(IC<0>{}, 0, j); gload(IC<0>{}, t2); __syncthreads(); compute(0);
+    sstore(IC<1>{}, 1, j + 1); gload(IC<1>{}, t3); __syncthreads(); compute(1);
   }
 
   // ---- epilogue: 64 rows at a time through LDS as fp32 [64][BN + 4] (the rows of the four wavefronts with wm = pass / 2,
@@ -400,21 +428,23 @@ conv1x1_large_kernel(const T* __restrict__ X, const T* __restrict__ W, const flo
                                 stat_partial + ((int64_t)mt * 2 + 1) * a.Ng + n0);
 }
 
-template <class T, bool DGRAD, int BM, int BN, int WGM, int WGN>
+constexpr int PW_FOLD_MAX_DEPTH = 1024;  // the scale / shift table of a folded BatchNorm takes 8 bytes of LDS per channel
+
+template <class T, bool DGRAD, int BM, int BN, int WGM, int WGN, bool FOLD>
 void launch_pw_large(hipStream_t st, const void* X, const void* W, const float* bias, const void* addend, void* out,
                      float* stat_partial, PwArgs a) {
   constexpr size_t sm = pwl_smem_bytes<BM, BN>();
   static bool attr_done = false;
   if (!attr_done) {
-    (void)hipFuncSetAttribute((const void*)conv1x1_large_kernel<T, DGRAD, BM, BN, WGM, WGN>,
-                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)sm);
+    (void)hipFuncSetAttribute((const void*)conv1x1_large_kernel<T, DGRAD, BM, BN, WGM, WGN, FOLD>,
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)(sm + (FOLD ? PW_FOLD_MAX_DEPTH * 8 : 0)));
     attr_done = true;
   }
   a.MT = ceil_div(a.M, BM);
   a.NT = a.Ng / BN;
   const int grid = ((a.MT + 7) / 8) * 8 * a.NT;
-  OSEQ_LAUNCH((conv1x1_large_kernel<T, DGRAD, BM, BN, WGM, WGN>), dim3(grid), dim3(64 * WGM * WGN), sm, st, (const T*)X,
-              (const T*)W, bias, (const T*)addend, (T*)out, stat_partial, a);
+  OSEQ_LAUNCH((conv1x1_large_kernel<T, DGRAD, BM, BN, WGM, WGN, FOLD>), dim3(grid), dim3(64 * WGM * WGN),
+              sm + (FOLD ? (size_t)a.Kd * 8 : 0), st, (const T*)X, (const T*)W, bias, (const T*)addend, (T*)out, stat_partial, a);
 }
 
 // The 256 x 256 tile is taken when the layer still gives every CU two blocks of it (from the shape only).
@@ -423,30 +453,42 @@ bool pw_large_ok(int64_t M, int Ng, int Kd, int stride, bool scatter) {
   return (int64_t)ceil_div(M, PWL_BM) * (Ng / PWL_BN) >= 512;
 }
 
-template <class T, int BN, bool DGRAD>
+template <class T, int BN, bool DGRAD, bool FOLD>
 void launch_pw_v(hipStream_t st, const void* X, const void* W, const float* bias, const void* addend, void* out,
                  float* stat_partial, const PwArgs& a) {
   constexpr size_t sm = pw_smem_bytes<BN>();
   static bool attr_done = false;
   if (!attr_done) {
-    (void)hipFuncSetAttribute((const void*)conv1x1_kernel<T, BN, DGRAD>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sm);
+    (void)hipFuncSetAttribute((const void*)conv1x1_kernel<T, BN, DGRAD, FOLD>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                              (int)(sm + (FOLD ? PW_FOLD_MAX_DEPTH * 8 : 0)));
     attr_done = true;
   }
   const int grid = ((a.MT + 7) / 8) * 8 * a.NT;
-  OSEQ_LAUNCH((conv1x1_kernel<T, BN, DGRAD>), dim3(grid), dim3(256), sm, st, (const T*)X, (const T*)W, bias,
-                     (const T*)addend, (T*)out, stat_partial, a);
+  OSEQ_LAUNCH((conv1x1_kernel<T, BN, DGRAD, FOLD>), dim3(grid), dim3(256), sm + (FOLD ? (size_t)a.Kd * 8 : 0), st,
+              (const T*)X, (const T*)W, bias, (const T*)addend, (T*)out, stat_partial, a);
 }
 
 template <class T>
 void launch_pw_t(hipStream_t st, bool dgrad, int bn, const void* X, const void* W, const float* bias, const void* addend,
                  void* out, float* stat_partial, const PwArgs& a) {
   if (dgrad) {
-    if (bn == 128) launch_pw_v<T, 128, true>(st, X, W, bias, addend, out, stat_partial, a);
-    else launch_pw_v<T, 64, true>(st, X, W, bias, addend, out, stat_partial, a);
+    if (bn == 128) launch_pw_v<T, 128, true, false>(st, X, W, bias, addend, out, stat_partial, a);
+    else launch_pw_v<T, 64, true, false>(st, X, W, bias, addend, out, stat_partial, a);
+  } else if (a.fold) {
+    if (bn == 128) launch_pw_v<T, 128, false, true>(st, X, W, bias, addend, out, stat_partial, a);
+    else launch_pw_v<T, 64, false, true>(st, X, W, bias, addend, out, stat_partial, a);
   } else {
-    if (bn == 128) launch_pw_v<T, 128, false>(st, X, W, bias, addend, out, stat_partial, a);
-    else launch_pw_v<T, 64, false>(st, X, W, bias, addend, out, stat_partial, a);
+    if (bn == 128) launch_pw_v<T, 128, false, false>(st, X, W, bias, addend, out, stat_partial, a);
+    else launch_pw_v<T, 64, false, false>(st, X, W, bias, addend, out, stat_partial, a);
   }
+}
+
+template <class T>
+void launch_pw_large_t(hipStream_t st, bool dgrad, const void* X, const void* W, const float* bias, const void* addend,
+                       void* out, float* stat_partial, const PwArgs& a) {
+  if (dgrad) launch_pw_large<T, true, PWL_BM, PWL_BN, 2, 4, false>(st, X, W, bias, addend, out, stat_partial, a);
+  else if (a.fold) launch_pw_large<T, false, PWL_BM, PWL_BN, 2, 4, true>(st, X, W, bias, addend, out, stat_partial, a);
+  else launch_pw_large<T, false, PWL_BM, PWL_BN, 2, 4, false>(st, X, W, bias, addend, out, stat_partial, a);
 }
 
 void launch_pw(hipStream_t st, int dt, bool dgrad, const void* X, const void* W, const float* bias, const void* addend,
@@ -454,13 +496,8 @@ void launch_pw(hipStream_t st, int dt, bool dgrad, const void* X, const void* W,
   // (a data gradient that adds a residual stays with the small tile: one block per CU has nobody to cover the latency
   // of the addend loads in its epilogue -- 332 against 313 us on 256 -> 1024 channels at 262 144 pixels)
   if (pw_large_ok(a.M, a.Ng, a.Kd, a.stride, a.scatter != 0) && !(dgrad && addend)) {
-    if (dt == DT_BF16) {
-      if (dgrad) launch_pw_large<bf16_t, true, PWL_BM, PWL_BN, 2, 4>(st, X, W, bias, addend, out, stat_partial, a);
-      else launch_pw_large<bf16_t, false, PWL_BM, PWL_BN, 2, 4>(st, X, W, bias, addend, out, stat_partial, a);
-    } else {
-      if (dgrad) launch_pw_large<f16_t, true, PWL_BM, PWL_BN, 2, 4>(st, X, W, bias, addend, out, stat_partial, a);
-      else launch_pw_large<f16_t, false, PWL_BM, PWL_BN, 2, 4>(st, X, W, bias, addend, out, stat_partial, a);
-    }
+    if (dt == DT_BF16) launch_pw_large_t<bf16_t>(st, dgrad, X, W, bias, addend, out, stat_partial, a);
+    else launch_pw_large_t<f16_t>(st, dgrad, X, W, bias, addend, out, stat_partial, a);
     return;
   }
   const int bn = a.Ng % 128 == 0 ? 128 : 64;
@@ -502,9 +539,14 @@ int conv_pointwise_stat_blocks(const ConvGeom& g) {
   return ceil_div(M, pw_large_ok(M, g.K, g.C, g.stride, false) ? PWL_BM : PW_BM);
 }
 
+// May the forward kernel take the z of a BatchNorm as its input and apply that BatchNorm (+ReLU) itself?
+bool conv_pointwise_fold_ok(int dt, const ConvGeom& g) { return conv_pointwise_fwd_ok(dt, g) && g.C <= PW_FOLD_MAX_DEPTH; }
+
+// fold: null, or the [4][C_in] statistics tensor of the BatchNorm whose z the tensor x is (see PwArgs::fold)
 void launch_conv_fwd_pointwise(hipStream_t st, int dt, const void* x, const void* w, const float* bias, void* out,
-                               float* stat_partial, const ConvGeom& g, int relu) {
+                               float* stat_partial, const ConvGeom& g, int relu, const float* fold, int fold_relu) {
   PwArgs a{};
+  a.fold = fold; a.fold_relu = fold_relu;
   a.M = (int64_t)g.N * g.P * g.Q; a.Ng = g.K; a.Kd = g.C; a.relu = relu; a.stride = g.stride;
   a.dstH = g.P; a.dstW = g.Q; a.srcH = g.H; a.srcW = g.W;
   a.div_w = make_fastdiv((uint32_t)g.Q); a.div_hw = make_fastdiv((uint32_t)(g.P * g.Q));

@@ -302,7 +302,9 @@ struct Scheduler {
       case F_CAST_IN: { SOp& s = push(S_CAST_IN, fi, phase, seg); s.out[0] = value_inst(f.out); break; }
       case F_CONV: {
         SOp& s = push(S_CONV_FWD, fi, phase, seg);
-        s.in[0] = cur[f.x]; s.out[0] = value_inst(f.out);
+        s.in[0] = cur[f.x];
+        if (f.fold_src >= 0) { s.in[0] = cur[p.fops[f.fold_src].x]; s.in[1] = cur[p.fops[f.fold_src].stats]; }
+        s.out[0] = value_inst(f.out);
         if (f.fwd_splits > 1) s.out[1] = new_inst(-1, (uint64_t)f.fwd_splits * f.N * f.P * f.Q * f.K * 4, false);
         if (f.stat_blocks > 0 && phase != PH_REPLAY) {  // per-block channel sums for the BatchNorm that follows
           s.out[2] = new_inst(-1, (uint64_t)(f.stat_blocks + f.stat_fold) * 2 * f.K * 4, false);
@@ -319,6 +321,7 @@ struct Scheduler {
         break;
       }
       case F_BN_APPLY: {
+        if (f.fold) break;  // done by the convolution that reads it
         SOp& s = push(S_BN_APPLY, fi, phase, seg);
         s.in[0] = cur[f.x]; s.in[1] = cur[f.stats]; s.in[2] = f.skip >= 0 ? cur[f.skip] : -1;
         s.out[0] = value_inst(f.out);
@@ -419,9 +422,10 @@ struct Scheduler {
           s.out[0] = new_inst(-1, (uint64_t)f.red_blocks * 2 * f.K * 4, false);
         }
         {
-          const int xin = backward_input(f.x, seg);
+          const int xin = f.fold_src >= 0 ? cur[p.fops[f.fold_src].x] : backward_input(f.x, seg);
           SOp& s = push(S_WGRAD, fi, PH_BWD, seg);
           s.in[0] = xin; s.in[1] = g;
+          if (f.fold_src >= 0) s.in[2] = cur[p.fops[f.fold_src].stats];
           if (f.wgrad_splits > 1)
             s.out[0] = new_inst(-1, (uint64_t)f.wgrad_splits * f.K * f.R * f.S * f.C * 4, false);
         }
@@ -492,7 +496,7 @@ bool build_graph(Plan& p) {
     return false;
   }
   if (c.precision < 0 || c.precision > 2) { p.error = "precision must be 0 (fp32), 1 (bf16) or 2 (fp16)"; return false; }
-  if (c.storage_mode < 0 || c.storage_mode > 1) { p.error = "storage_mode must be 0 or 1"; return false; }
+  if (c.storage_mode < 0 || c.storage_mode > 2) { p.error = "storage_mode must be 0, 1 or 2"; return false; }
   if ((int64_t)c.batch * c.height * c.width * 2048 > (int64_t)1 << 40) { p.error = "batch too large"; return false; }
   Builder b(p);
   return b.run();

@@ -40,6 +40,9 @@ struct FOp {
   int x = -1, skip = -1, stats = -1, out = -1;  // LTensor ids
   int mask = -1;  // F_BN_APPLY with a skip connection: LTensor of the ReLU decisions, one bit per element (one byte per
                   // 16 bytes of the output), which the backward pass reads instead of the output itself; -1: none
+  int fold = 0;       // F_BN_APPLY: 1 = never run; the one convolution that reads its output applies scale, shift and
+                      // ReLU to z while it stages its operand (forward and weight gradient), so the output is never stored
+  int fold_src = -1;  // F_CONV: the folded F_BN_APPLY operation its input comes from, or -1
   int aux[3] = {-1, -1, -1};                     // head: feat, logits, dlogits
   int N = 0, H = 0, W = 0, C = 0, K = 0, R = 1, S = 1, stride = 1, pad = 0, P = 0, Q = 0;
   int relu = 0, has_bias = 0, has_bn = 0;
@@ -82,6 +85,8 @@ struct SOp {
   int variant = 0;  // S_BN_BWD: 1 = in[0] is the gradient of the 2x2 max-pool behind the activation (pooled size);
                     // 2 = in[3] is a bit mask of ReLU decisions (FOp::mask) to apply to in[0], not an activation.
                     // S_DGRAD: in[2] >= 0 is such a mask for the addend in[1]
+                    // S_CONV_FWD with in[1] >= 0, S_WGRAD with in[2] >= 0: in[0] is the z of a folded BatchNorm apply
+                    // and that slot its statistics tensor (FOp::fold_src)
   bool live = true;
 };
 

@@ -516,6 +516,27 @@ def test_storage_mode_1_at_benchmark_size():
     assert ib["planned_peak_saved_bytes"] < 0.85 * ia["planned_peak_saved_bytes"]
 
 
+@pytest.mark.parametrize("idx,batch", [(4, None), (5, 32), (5, 256), (3, None)])
+def test_folded_batchnorm_is_bit_identical_to_written_activations(idx, batch):
+    # storage modes 0 and 1 never write an activation whose one reader, a 1x1 convolution in 16-bit storage, can apply
+    # the BatchNorm itself while it loads z (forward and weight gradient); mode 2 writes and keeps every activation.
+    # Same arithmetic, same rounding: every gradient bit must agree.  (Config 3 has no such layer: nothing changes.)
+    wl = W.config(idx, batch=batch) if batch else W.config(idx)
+    p, x, y = W.make_batch(wl)
+    kw = dict(precision=wl.precision, k=wl.k_segments, classes=wl.classes, plan_mode=wl.plan_mode)
+    a, ia = gpu_step(wl.units, p, x, y, storage_mode=2, **kw)
+    for mode in (0, 1):
+        b, ib = gpu_step(wl.units, p, x, y, storage_mode=mode, **kw)
+        assert np.array_equal(a["grads"], b["grads"]) and a["loss"] == b["loss"], (idx, batch, mode)
+        if idx == 3:
+            assert mode == 1 or ib["n_launches"] == ia["n_launches"]
+        else:
+            assert ib["n_launches"] < ia["n_launches"]
+            assert ib["planned_peak_saved_bytes"] < ia["planned_peak_saved_bytes"]
+    record(test="folded_batchnorm/%s/batch%d" % (wl.name, wl.batch), workload=wl.name, batch=wl.batch, launches_all_written=ia["n_launches"],
+           launches_folded=ib["n_launches"], saved_all_written=ia["planned_peak_saved_bytes"])
+
+
 def test_run_to_run_determinism_and_peak_shrinks_with_k():
     wl = W.config(3, batch=8)
     p, x, y = W.make_batch(wl)

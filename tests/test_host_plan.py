@@ -206,7 +206,7 @@ def test_config5_budget_needs_the_byte_aware_plan():
     ([W.conv(3, 8), W.gap_linear_ce(8, 10)], {"k_segments": 3}),                     # more segments than units
     ([W.conv(3, 8), W.conv(8, 8), W.gap_linear_ce(8, 10)], {"k_segments": 2, "boundaries": [0]}),  # bad boundary
     ([W.conv(3, 8), W.gap_linear_ce(8, 10)], {"precision": 7}),
-    ([W.conv(3, 8), W.gap_linear_ce(8, 10)], {"storage_mode": 2}),
+    ([W.conv(3, 8), W.gap_linear_ce(8, 10)], {"storage_mode": 3}),
 ])
 def test_invalid_arguments_are_rejected(units, kw):
     args = dict(k_segments=1, precision=W.FP32, batch=4, height=8, width=8, channels=3, num_classes=10)
