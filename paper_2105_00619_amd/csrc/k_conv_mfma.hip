@@ -16,6 +16,7 @@
 // MFMAs of tile t (register prefetch + two LDS buffers, one barrier per tile).
 #include <algorithm>
 
+#include "bn_fold.h"
 #include "dev_common.h"
 #include "epilogue.h"
 #include "kernels.h"

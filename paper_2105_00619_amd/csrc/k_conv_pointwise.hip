@@ -13,6 +13,7 @@
 //     by index), so the X tile is fetched from HBM once and re-read from that XCD's L2;
 //   * epilogue through LDS: bias / residual addend / ReLU in fp32, one rounding, 16-byte stores of whole rows, and the
 //     per-block channel sums of the stored values for the BatchNorm that follows.
+#include "bn_fold.h"
 #include "dev_common.h"
 #include "epilogue.h"
 #include "kernels.h"
