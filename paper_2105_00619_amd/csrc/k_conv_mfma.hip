@@ -375,11 +375,14 @@ struct PatchArgs {
   int patch_elems;           // elements of one staged patch buffer (its rows times row_pitch, rounded up to 16 bytes)
   int xcd_group;             // 1: blocks are renumbered so that the row tiles of one weight slice run on one XCD
   const uint8_t* amask;      // data gradient with an addend: ReLU bit mask the addend is multiplied by, or null
+  const float* fold;         // FOLD (forward): src is the z of a BatchNorm, this its [4][srcC] statistics tensor; the pieces
+  int fold_relu;             // of the patch become the activation (scale, shift, ReLU if fold_relu, one rounding) on
+                             // their way to LDS; positions outside the image stay zero
 };
 
 constexpr int PATCH_MAX_POS = 256;  // positions per sub-tile
 
-template <class T, int BN, int MI, int SUBT, bool STAT>
+template <class T, int BN, int MI, int SUBT, bool STAT, bool FOLD = false>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(BN == 64 ? 3 : 1, BN == 64 ? 3 : 2)))
 conv3x3_patch_kernel(const T* __restrict__ src, const T* __restrict__ wmat, const float* __restrict__ bias,
                      const T* __restrict__ addend, T* __restrict__ out, float* __restrict__ partial,
@@ -487,9 +490,22 @@ conv3x3_patch_kernel(const T* __restrict__ src, const T* __restrict__ wmat, cons
     pdst[sl] = dst;
   }
   auto patch_load = [&](int slot, int chunk) { return *reinterpret_cast<const Chunk*>(pptr[slot] + chunk * CCE); };
+  // FOLD: all pieces of a thread cover channels [(tid & 3) * EV, + EV) of the chunk; their scale and shift are
+  // requested with the first pieces of a chunk and used when the pieces are stored
+  float fsc[EV], fsh[EV];
+  auto fold_load = [&](int chunk) {
+    if (FOLD) {
+      const int c = chunk * CCE + (tid & 3) * EV;
+      load_f32<float, EV>(a.fold + 2 * srcC + c, fsc);
+      load_f32<float, EV>(a.fold + 3 * srcC + c, fsh);
+    }
+  };
   auto patch_store = [&](int slot, int buf, const Chunk& c) {
-    if ((pstore >> slot) & 1u)
-      *reinterpret_cast<Chunk*>(&patch[buf * PBUF + pdst[slot]]) = ((pvalid >> slot) & 1u) ? c : zero_chunk();
+    if ((pstore >> slot) & 1u) {
+      Chunk v = c;
+      if (FOLD) v = bn_fold_chunk<T>(c, fsc, fsh, a.fold_relu);
+      *reinterpret_cast<Chunk*>(&patch[buf * PBUF + pdst[slot]]) = ((pvalid >> slot) & 1u) ? v : zero_chunk();
+    }
   };
   const T* wrow = wmat + (int64_t)(n0c + brow0) * Kg + bvec * EV;
   // weight tile of global step gs = chunk*9 + tap -> registers REG
@@ -510,6 +526,7 @@ conv3x3_patch_kernel(const T* __restrict__ src, const T* __restrict__ wmat, cons
   // ---- prologue -----------------------------------------------------------------------------------------------
 #pragma unroll
   for (int sl = 0; sl < NSLOT; ++sl) PR[sl] = patch_load(sl, cb);
+  fold_load(cb);
 #pragma unroll
   for (int t = 0; t < 9; ++t) B_LOAD(t, cb);
 #pragma unroll
@@ -561,6 +578,7 @@ conv3x3_patch_kernel(const T* __restrict__ src, const T* __restrict__ wmat, cons
       if (!last && t < 4) {
 #pragma unroll
         for (int q = 0; q < SPT; ++q) PR[SPT * t + q] = patch_load(SPT * t + q, chunk + 1);
+        if (t == 0) fold_load(chunk + 1);
       }
       // first halves
 #pragma unroll
@@ -810,7 +828,7 @@ static bool patch_pick(int dt, int N, int dstH, int dstW, int srcC, int Ng, int 
   return true;
 }
 
-template <class T, int BN, int MI, int SUBT>
+template <class T, int BN, int MI, int SUBT, bool FOLD>
 static void launch_patch_v(hipStream_t st, const void* src, const void* wmat, const float* bias, const void* addend, void* out,
                            float* partial, float* stat_partial, int splits, const PatchArgs& a_in) {
   PatchArgs a = a_in;
@@ -832,17 +850,17 @@ static void launch_patch_v(hipStream_t st, const void* src, const void* wmat, co
   const size_t sm = patch_smem_bytes<T>(BN, SUBT, pe);
   static bool attr_done = false;
   if (!attr_done) {
-    (void)hipFuncSetAttribute((const void*)conv3x3_patch_kernel<T, BN, MI, SUBT, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sm_max);
-    (void)hipFuncSetAttribute((const void*)conv3x3_patch_kernel<T, BN, MI, SUBT, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sm_max);
+    (void)hipFuncSetAttribute((const void*)conv3x3_patch_kernel<T, BN, MI, SUBT, false, FOLD>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sm_max);
+    (void)hipFuncSetAttribute((const void*)conv3x3_patch_kernel<T, BN, MI, SUBT, true, FOLD>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sm_max);
     attr_done = true;
   }
   // the variant that also adds up what it stores (BatchNorm statistics) is a separate instantiation, so that the
   // plain one carries none of its registers
   if (splits == 1 && stat_partial)
-    OSEQ_LAUNCH((conv3x3_patch_kernel<T, BN, MI, SUBT, true>), grid, block, sm, st, (const T*)src, (const T*)wmat, bias,
+    OSEQ_LAUNCH((conv3x3_patch_kernel<T, BN, MI, SUBT, true, FOLD>), grid, block, sm, st, (const T*)src, (const T*)wmat, bias,
                        (const T*)addend, (T*)out, (float*)nullptr, stat_partial, a);
   else
-    OSEQ_LAUNCH((conv3x3_patch_kernel<T, BN, MI, SUBT, false>), grid, block, sm, st, (const T*)src, (const T*)wmat, bias,
+    OSEQ_LAUNCH((conv3x3_patch_kernel<T, BN, MI, SUBT, false, FOLD>), grid, block, sm, st, (const T*)src, (const T*)wmat, bias,
                        (const T*)addend, (T*)out, splits > 1 ? partial : (float*)nullptr, (float*)nullptr, a);
 }
 
@@ -850,11 +868,23 @@ template <class T>
 static void launch_patch_t(hipStream_t st, const void* src, const void* wmat, const float* bias, const void* addend, void* out,
                            float* partial, float* stat_partial, const PatchShape& v, const PatchArgs& a) {
   const int sp = v.splits;
-  if (v.mi == 2) {
-    if (v.bn == 128) launch_patch_v<T, 128, 2, 1>(st, src, wmat, bias, addend, out, partial, stat_partial, sp, a);
-    else launch_patch_v<T, 64, 2, 1>(st, src, wmat, bias, addend, out, partial, stat_partial, sp, a);
-  } else {
-    launch_patch_v<T, 64, 1, 1>(st, src, wmat, bias, addend, out, partial, stat_partial, sp, a);
+  if constexpr (sizeof(T) == 2) {
+    if (a.fold) {  // (16-bit modes only)
+      if (v.mi == 2) {
+        if (v.bn == 128) launch_patch_v<T, 128, 2, 1, true>(st, src, wmat, bias, addend, out, partial, stat_partial, sp, a);
+        else launch_patch_v<T, 64, 2, 1, true>(st, src, wmat, bias, addend, out, partial, stat_partial, sp, a);
+      } else {
+        launch_patch_v<T, 64, 1, 1, true>(st, src, wmat, bias, addend, out, partial, stat_partial, sp, a);
+      }
+    }
+  }
+  if (sizeof(T) != 2 || !a.fold) {
+    if (v.mi == 2) {
+      if (v.bn == 128) launch_patch_v<T, 128, 2, 1, false>(st, src, wmat, bias, addend, out, partial, stat_partial, sp, a);
+      else launch_patch_v<T, 64, 2, 1, false>(st, src, wmat, bias, addend, out, partial, stat_partial, sp, a);
+    } else {
+      launch_patch_v<T, 64, 1, 1, false>(st, src, wmat, bias, addend, out, partial, stat_partial, sp, a);
+    }
   }
   if (sp > 1)
     launch_splitk_epilogue<T>(st, partial, sp, (int64_t)a.N * a.dstH * a.dstW, a.Ng, bias, addend, a.amask, out, stat_partial, a.relu);
@@ -973,7 +1003,12 @@ int conv_mfma_fwd_stat_blocks(int dt, const ConvGeom& g) {
 
 // stat_partial: null, or [conv_mfma_fwd_stat_blocks][2][C_out] floats receiving per-block sums and sums of squares
 // of the stored outputs
-bool conv_fold_fwd_ok(int dt, const ConvGeom& g) { return conv_pointwise_fold_ok(dt, g); }
+// the 1x1 streaming kernels and, in the 16-bit modes, the 3x3 patch kernel
+bool conv_fold_fwd_ok(int dt, const ConvGeom& g) {
+  if (conv_pointwise_fwd_ok(dt, g)) return conv_pointwise_fold_ok(dt, g);
+  PatchShape pv; PatchArgs pa{};
+  return dt != DT_F32 && patch_pick(dt, g.N, g.P, g.Q, g.C, g.K, g.R, g.S, g.stride, pv, pa);
+}
 
 void launch_conv_fwd_mfma(hipStream_t st, int dt, const void* x, const void* w, const float* bias, void* out,
                           float* partial, float* stat_partial, int splits, const ConvGeom& g, int relu, const float* fold,
@@ -986,6 +1021,7 @@ void launch_conv_fwd_mfma(hipStream_t st, int dt, const void* x, const void* w, 
   if (patch_pick(dt, g.N, g.P, g.Q, g.C, g.K, g.R, g.S, g.stride, pv, pa)) {
     pa.N = g.N; pa.srcH = g.H; pa.srcW = g.W; pa.srcC = g.C; pa.dstH = g.P; pa.dstW = g.Q; pa.Ng = g.K;
     pa.pad = g.pad; pa.flip = 0; pa.relu = relu;
+    pa.fold = dt == DT_F32 ? nullptr : fold; pa.fold_relu = fold_relu;
     launch_patch(st, dt, x, w, bias, nullptr, out, partial, stat_partial, pv, pa);
     return;
   }
@@ -1089,6 +1125,8 @@ struct WGradArgs {
   FastDiv divQ, divPQ;
   const float* fold;  // FOLD: x is the z of a BatchNorm, this its [4][C] statistics tensor; the pieces of x become the
   int fold_relu;      // activation (scale, shift, ReLU if fold_relu, one rounding) on their way to LDS
+  int xcd_group;      // 1: the tiles of a pixel range share an XCD (see the kernel); ranges: the number of pixel ranges
+  int ranges;
 };
 
 template <class T> struct WFrag;
@@ -1142,11 +1180,25 @@ __global__ void __launch_bounds__(64 * WGM * WGN) conv_wgrad_kernel(const T* __r
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WGN, wn = wave % WGN, g = lane >> 5, l32 = lane & 31;
-  const int k0 = blockIdx.x * BM;
+  // Block coordinates: (output-channel tile, tap and input-channel tile, pixel range).  xcd_group (1x1 layers): the
+  // tiles of one pixel range all read the same rows of x and dz; workgroups go to the 8 XCDs round-robin by their linear
+  // index and every XCD has an L2 of its own, so the tiles of a range are renumbered onto one XCD, which then fetches
+  // those rows once.  The grid's z extent is the number of ranges rounded up to a multiple of 8.
+  int bx = blockIdx.x, by = blockIdx.y, bz = blockIdx.z;
+  if (a.xcd_group) {
+    const unsigned tiles = gridDim.x * gridDim.y;
+    const unsigned lin = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
+    const unsigned xcd = lin & 7u, slot = lin >> 3;
+    const unsigned tile = slot % tiles;
+    bz = (int)((slot / tiles) * 8u + xcd);
+    bx = (int)(tile % gridDim.x); by = (int)(tile / gridDim.x);
+    if (bz >= a.ranges) return;
+  }
+  const int k0 = bx * BM;
   const int ctiles = a.C / BN;
-  const int tap = blockIdx.y / ctiles, c0 = (blockIdx.y - tap * ctiles) * BN;
+  const int tap = by / ctiles, c0 = (by - tap * ctiles) * BN;
   const int r = tap / a.S, s = tap - r * a.S;
-  const int mbeg = blockIdx.z * a.chunk;
+  const int mbeg = bz * a.chunk;
   const int mend = mbeg + a.chunk < a.pixels ? mbeg + a.chunk : a.pixels;
   const int n = mend > mbeg ? (mend - mbeg + DEPTH - 1) / DEPTH : 0;
   const int K = a.K, C = a.C, H = a.H, W = a.W, P = a.P, Q = a.Q, cstride = a.stride, pad = a.pad;
@@ -1326,7 +1378,7 @@ __global__ void __launch_bounds__(64 * WGM * WGN) conv_wgrad_kernel(const T* __r
   }
 
   const int64_t outputs = (int64_t)K * a.R * a.S * C;
-  float* dst = out + (int64_t)blockIdx.z * outputs;
+  float* dst = out + (int64_t)bz * outputs;
 #pragma unroll
   for (int i = 0; i < MI; ++i)
 #pragma unroll
@@ -1397,6 +1449,9 @@ static void launch_wgrad_t(hipStream_t st, const void* x, const void* dz, float*
   a.divQ = make_fastdiv((uint32_t)g.Q);
   a.divPQ = make_fastdiv((uint32_t)(g.P * g.Q));
   a.fold = fold; a.fold_relu = fold_relu;
+  a.ranges = splits;
+  a.xcd_group = g.R * g.S == 1 && splits >= 8;
+  const int gz = a.xcd_group ? (splits + 7) / 8 * 8 : splits;
   if constexpr (sizeof(T) == 2) {
     if (wgrad_large_ok(DT_BF16, g)) {
       constexpr size_t sm = wgrad_lds_bytes<T, 256, 256, 2>();
@@ -1405,14 +1460,14 @@ static void launch_wgrad_t(hipStream_t st, const void* x, const void* dz, float*
         (void)hipFuncSetAttribute((const void*)conv_wgrad_kernel<T, 256, 256, 2, 4, FOLD>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sm);
         attr_done = true;
       }
-      OSEQ_LAUNCH((conv_wgrad_kernel<T, 256, 256, 2, 4, FOLD>), dim3(g.K / 256, g.C / 256, splits), dim3(512), sm, st, (const T*)x,
+      OSEQ_LAUNCH((conv_wgrad_kernel<T, 256, 256, 2, 4, FOLD>), dim3(g.K / 256, g.C / 256, gz), dim3(512), sm, st, (const T*)x,
                   (const T*)dz, dst, a);
       return;
     }
   }
   const bool m128 = g.K % 128 == 0, n128 = g.C % 128 == 0;
   const int bm = m128 ? 128 : 64, bn = n128 ? 128 : 64;
-  dim3 grid(g.K / bm, g.R * g.S * (g.C / bn), splits), block(256);
+  dim3 grid(g.K / bm, g.R * g.S * (g.C / bn), gz), block(256);
   if (m128 && n128) OSEQ_LAUNCH((conv_wgrad_kernel<T, 128, 128, 2, 2, FOLD>), grid, block, (wgrad_lds_bytes<T, 128, 128, 2>()), st, (const T*)x, (const T*)dz, dst, a);
   else if (m128) OSEQ_LAUNCH((conv_wgrad_kernel<T, 128, 64, 2, 2, FOLD>), grid, block, (wgrad_lds_bytes<T, 128, 64, 2>()), st, (const T*)x, (const T*)dz, dst, a);
   else if (n128) OSEQ_LAUNCH((conv_wgrad_kernel<T, 64, 128, 2, 2, FOLD>), grid, block, (wgrad_lds_bytes<T, 64, 128, 2>()), st, (const T*)x, (const T*)dz, dst, a);
@@ -1459,15 +1514,13 @@ static void launch_wgrad_reduce(hipStream_t st, const float* partial, float* out
     OSEQ_LAUNCH(wgrad_reduce_kernel<1>, dim3(ceil_div(quads, 256)), dim3(256), 0, st, partial, out, n, splits);
 }
 
-// the kernel of this file in a 16-bit mode (the all-taps 3x3 kernel reads its input as stored)
-bool conv_fold_wgrad_ok(int dt, const ConvGeom& g) {
-  return dt != DT_F32 && conv_mfma_wgrad_ok(dt, g) && !conv_wgrad3x3_ok(dt, g);
-}
+// the matrix-core kernels in the 16-bit modes
+bool conv_fold_wgrad_ok(int dt, const ConvGeom& g) { return dt != DT_F32 && conv_mfma_wgrad_ok(dt, g); }
 
 void launch_conv_wgrad_mfma(hipStream_t st, int dt, const void* x, const void* dz, float* dw, float* partial, int splits,
                             const ConvGeom& g, const float* fold, int fold_relu) {
   float* dst = splits > 1 ? partial : dw;
-  if (conv_wgrad3x3_ok(dt, g)) launch_conv_wgrad3x3(st, dt, x, dz, dst, g);  // splits == conv_wgrad3x3_splits(dt, g)
+  if (conv_wgrad3x3_ok(dt, g)) launch_conv_wgrad3x3(st, dt, x, dz, dst, g, fold, fold_relu);  // splits == conv_wgrad3x3_splits(dt, g)
   else if (dt == DT_F32) launch_wgrad_t<float, false>(st, x, dz, dst, splits, g, nullptr, 0);
   else if (dt == DT_BF16) {
     if (fold) launch_wgrad_t<bf16_t, true>(st, x, dz, dst, splits, g, fold, fold_relu);

@@ -20,6 +20,7 @@
 //   addresses make the tap shift a plain change of address.
 //   Two LDS stages; the global loads of the next sub-tile are issued before the MFMAs of the current one, parked
 //   in registers and written to the other stage afterwards: one barrier per sub-tile.
+#include "bn_fold.h"
 #include "dev_common.h"
 #include "kernels.h"
 
@@ -40,6 +41,8 @@ struct W9Args {
   int TI, TR, TC, SR, SC, NPOS, TP;  // sub-tile: images, rows, columns; staged rows / columns; positions; pixels
   int tiles_r, tiles_c, NT;          // sub-tiles per image rows / columns; in total
   int tiles_per_split;
+  const float* fold;  // FOLD: x is the z of a BatchNorm, this its [4][C] statistics tensor; the staged pieces of x become
+  int fold_relu;      // the activation (scale, shift, ReLU if fold_relu, one rounding); positions outside the image stay zero
 };
 
 template <class T> struct W9Cfg;
@@ -78,7 +81,7 @@ __device__ __forceinline__ typename V8<T>::type tr_read8(const T* p0, const T* p
   return __builtin_bit_cast(typename V8<T>::type, r);
 }
 
-template <class T, int MI, int WGM>
+template <class T, int MI, int WGM, bool FOLD = false>
 __global__ void __launch_bounds__(128 * WGM) __attribute__((amdgpu_waves_per_eu(WGM / 2, WGM / 2)))
 conv_wgrad3x3_kernel(const T* __restrict__ x, const T* __restrict__ dz, float* __restrict__ out, W9Args a) {
   typedef W9Lds<T, MI, WGM> L;
@@ -168,9 +171,20 @@ conv_wgrad3x3_kernel(const T* __restrict__ x, const T* __restrict__ dz, float* _
     }
     xok = xm; dok = dm;
   };
+  // FOLD: a thread's pieces of x all cover the same EV channels, whose scale and shift it keeps in registers
+  static_assert(NTH % XCP == 0, "a thread's pieces of x must share their channels");
+  float fsc[EV], fsh[EV];
+  if (FOLD) {
+    load_f32<float, EV>(a.fold + 2 * C + c0 + (tid % XCP) * EV, fsc);
+    load_f32<float, EV>(a.fold + 3 * C + c0 + (tid % XCP) * EV, fsh);
+  }
   auto sstore = [&](int stage) {
     T* xs = lds + stage * L::STAGE;
     T* ds = xs + L::XS;
+    if (FOLD) {
+#pragma unroll
+      for (int sl = 0; sl < XSLOTS; ++sl) xr[sl] = bn_fold_chunk<T>(xr[sl], fsc, fsh, a.fold_relu);
+    }
 #pragma unroll
     for (int sl = 0; sl < XSLOTS; ++sl) {
       const int idx = sl * NTH + tid, pos = idx / XCP, v = idx - pos * XCP;
@@ -318,16 +332,26 @@ bool w9_plan(int dt, const ConvGeom& g, W9Plan& pl) {
   return false;
 }
 
-template <class T, int MI, int WGM>
+template <class T, int MI, int WGM, bool FOLD>
 void launch_w9(hipStream_t st, const void* x, const void* dz, float* dst, const W9Plan& pl) {
   constexpr size_t sm = W9Lds<T, MI, WGM>::bytes;
   static bool attr_done = false;
   if (!attr_done) {
-    (void)hipFuncSetAttribute((const void*)conv_wgrad3x3_kernel<T, MI, WGM>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sm);
+    (void)hipFuncSetAttribute((const void*)conv_wgrad3x3_kernel<T, MI, WGM, FOLD>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sm);
     attr_done = true;
   }
   dim3 grid(pl.a.K / (32 * MI * WGM), pl.a.C / 64, pl.splits), block(128 * WGM);
-  OSEQ_LAUNCH((conv_wgrad3x3_kernel<T, MI, WGM>), grid, block, sm, st, (const T*)x, (const T*)dz, dst, pl.a);
+  OSEQ_LAUNCH((conv_wgrad3x3_kernel<T, MI, WGM, FOLD>), grid, block, sm, st, (const T*)x, (const T*)dz, dst, pl.a);
+}
+
+template <class T>
+void launch_w9_16(hipStream_t st, const void* x, const void* dz, float* dst, const W9Plan& pl) {
+  // 128 output channels per block: four wavefront rows of 32 channels (eight wavefronts, two per SIMD)
+  if (pl.a.fold) {
+    if (pl.mi == 2) launch_w9<T, 1, 4, true>(st, x, dz, dst, pl); else launch_w9<T, 1, 2, true>(st, x, dz, dst, pl);
+  } else {
+    if (pl.mi == 2) launch_w9<T, 1, 4, false>(st, x, dz, dst, pl); else launch_w9<T, 1, 2, false>(st, x, dz, dst, pl);
+  }
 }
 
 }  // namespace
@@ -344,14 +368,15 @@ int conv_wgrad3x3_splits(int dt, const ConvGeom& g) {
   return w9_plan(dt, g, pl) ? pl.splits : 1;
 }
 
-// dst: [splits][K][9][C] floats (dw itself when splits == 1)
-void launch_conv_wgrad3x3(hipStream_t st, int dt, const void* x, const void* dz, float* dst, const ConvGeom& g) {
+// dst: [splits][K][9][C] floats (dw itself when splits == 1); fold: see W9Args (16-bit modes only)
+void launch_conv_wgrad3x3(hipStream_t st, int dt, const void* x, const void* dz, float* dst, const ConvGeom& g,
+                          const float* fold, int fold_relu) {
   W9Plan pl;
   if (!w9_plan(dt, g, pl)) return;
-  // 128 output channels per block in the 16-bit modes: four wavefront rows of 32 channels (eight wavefronts, two per SIMD)
-  if (dt == DT_F32) launch_w9<float, 1, 2>(st, x, dz, dst, pl);
-  else if (dt == DT_BF16) { if (pl.mi == 2) launch_w9<bf16_t, 1, 4>(st, x, dz, dst, pl); else launch_w9<bf16_t, 1, 2>(st, x, dz, dst, pl); }
-  else { if (pl.mi == 2) launch_w9<f16_t, 1, 4>(st, x, dz, dst, pl); else launch_w9<f16_t, 1, 2>(st, x, dz, dst, pl); }
+  pl.a.fold = dt == DT_F32 ? nullptr : fold; pl.a.fold_relu = fold_relu;
+  if (dt == DT_F32) launch_w9<float, 1, 2, false>(st, x, dz, dst, pl);
+  else if (dt == DT_BF16) launch_w9_16<bf16_t>(st, x, dz, dst, pl);
+  else launch_w9_16<f16_t>(st, x, dz, dst, pl);
 }
 
 }  // namespace oseq

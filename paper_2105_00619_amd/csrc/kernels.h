@@ -104,7 +104,8 @@ void launch_conv_dgrad_pointwise(hipStream_t st, int dt, const void* dz, const v
 // 3x3 stride-1 weight gradient with all nine taps per block (k_conv_wgrad3x3.hip); used by the MFMA launcher below
 bool conv_wgrad3x3_ok(int dt, const ConvGeom& g);
 int conv_wgrad3x3_splits(int dt, const ConvGeom& g);
-void launch_conv_wgrad3x3(hipStream_t st, int dt, const void* x, const void* dz, float* dst, const ConvGeom& g);
+void launch_conv_wgrad3x3(hipStream_t st, int dt, const void* x, const void* dz, float* dst, const ConvGeom& g,
+                          const float* fold, int fold_relu);
 bool conv_mfma_wgrad_ok(int dt, const ConvGeom& g);
 int conv_mfma_wgrad_splits(int dt, const ConvGeom& g);
 void launch_conv_wgrad_mfma(hipStream_t st, int dt, const void* x, const void* dz, float* dw, float* partial, int splits,

@@ -513,14 +513,18 @@ def test_storage_mode_1_at_benchmark_size():
     b, ib = gpu_step(wl.units, p, x, y, precision=wl.precision, k=wl.k_segments, classes=wl.classes, plan_mode=wl.plan_mode,
                      storage_mode=1)
     assert np.array_equal(a["grads"], b["grads"]) and a["loss"] == b["loss"]
-    assert ib["planned_peak_saved_bytes"] < 0.85 * ia["planned_peak_saved_bytes"]
+    # (in this network every activation mode 1 could rebuild is already rebuilt by the convolution that reads it)
+    c, ic = gpu_step(wl.units, p, x, y, precision=wl.precision, k=wl.k_segments, classes=wl.classes, plan_mode=wl.plan_mode,
+                     storage_mode=2)
+    assert np.array_equal(a["grads"], c["grads"]) and a["loss"] == c["loss"]
+    assert ib["planned_peak_saved_bytes"] <= ia["planned_peak_saved_bytes"] < 0.85 * ic["planned_peak_saved_bytes"]
 
 
 @pytest.mark.parametrize("idx,batch", [(4, None), (5, 32), (5, 256), (3, None)])
 def test_folded_batchnorm_is_bit_identical_to_written_activations(idx, batch):
-    # storage modes 0 and 1 never write an activation whose one reader, a 1x1 convolution in 16-bit storage, can apply
-    # the BatchNorm itself while it loads z (forward and weight gradient); mode 2 writes and keeps every activation.
-    # Same arithmetic, same rounding: every gradient bit must agree.  (Config 3 has no such layer: nothing changes.)
+    # storage modes 0 and 1 never write an activation whose one reader, a stride-1 convolution in 16-bit storage, can
+    # apply the BatchNorm itself while it loads z (forward and weight gradient); mode 2 writes and keeps every
+    # activation.  Same arithmetic, same rounding: every gradient bit must agree.
     wl = W.config(idx, batch=batch) if batch else W.config(idx)
     p, x, y = W.make_batch(wl)
     kw = dict(precision=wl.precision, k=wl.k_segments, classes=wl.classes, plan_mode=wl.plan_mode)
@@ -528,11 +532,8 @@ def test_folded_batchnorm_is_bit_identical_to_written_activations(idx, batch):
     for mode in (0, 1):
         b, ib = gpu_step(wl.units, p, x, y, storage_mode=mode, **kw)
         assert np.array_equal(a["grads"], b["grads"]) and a["loss"] == b["loss"], (idx, batch, mode)
-        if idx == 3:
-            assert mode == 1 or ib["n_launches"] == ia["n_launches"]
-        else:
-            assert ib["n_launches"] < ia["n_launches"]
-            assert ib["planned_peak_saved_bytes"] < ia["planned_peak_saved_bytes"]
+        assert mode == 1 or ib["n_launches"] < ia["n_launches"]  # (mode 1 adds the passes that rebuild the other activations)
+        assert ib["planned_peak_saved_bytes"] < ia["planned_peak_saved_bytes"]
     record(test="folded_batchnorm/%s/batch%d" % (wl.name, wl.batch), workload=wl.name, batch=wl.batch, launches_all_written=ia["n_launches"],
            launches_folded=ib["n_launches"], saved_all_written=ia["planned_peak_saved_bytes"])
 
