@@ -309,7 +309,7 @@ def test_config2_full_size_fp32_matches_oracle():
     p, x, y = W.make_batch(wl)
     r, info = gpu_step(wl.units, p, x, y, precision=W.FP32, k=wl.k_segments, classes=wl.classes, plan_mode=wl.plan_mode)
     assert info["n_replay_launches"] > 0 and info["boundaries"] == [2, 5, 7]  # the plan bench.py times
-    loss, n_inverted = assert_parity_fp32(wl.units, 32, 32, p, x, y, r["grads"], 1e-4, wl.name, below_tol=2e-2)
+    loss, n_inverted = assert_parity_fp32(wl.units, 32, 32, p, x, y, r["grads"], 1e-4, wl.name)
     print("config 2 full size: %d near-kink ReLU decisions taken the other way" % n_inverted)
     assert abs(r["loss"] - loss) <= 1e-5 * max(1.0, abs(loss))
     # every plan and storage mode: the same bits, and no kernel leaves the arenas (guard bands checked in gpu_step)
