@@ -88,6 +88,54 @@ __device__ __forceinline__ void epi_store_rows_nt(const float* ep, int tid, int 
   }
 }
 
+// The residual-adding pass in two halves, for a kernel whose block owns its CU alone and therefore has nobody to cover
+// the latency of the addend loads: the addend pieces (and mask bytes) of a pass are requested one pass ahead
+// (epi_load_addend_nt), before the stores of the pass in between, and added later (epi_store_rows_pre_nt).  Loads
+// issued before stores can be waited for without waiting for those stores.
+template <int NT, class T, int BN, int HR, class RowOff>
+__device__ __forceinline__ void epi_load_addend_nt(int tid, int n0, const T* __restrict__ addend,
+                                                   const uint8_t* __restrict__ amask, RowOff rowoff,
+                                                   Vec<T, 8> (&ad)[HR * (BN / 8) / NT], unsigned (&mb)[HR * (BN / 8) / NT]) {
+  constexpr int GROUPS = BN / 8, PER_THREAD = HR * GROUPS / NT, RG = NT / GROUPS;
+  const int col = n0 + (tid % GROUPS) * 8, erow = tid / GROUPS;
+#pragma unroll
+  for (int it = 0; it < PER_THREAD; ++it) {
+    const int64_t ro = rowoff(erow + it * RG);
+    const int64_t e = (ro >= 0 ? ro : 0) + col;  // rows that are not stored read the tensor's first row
+    ad[it] = *reinterpret_cast<const Vec<T, 8>*>(addend + e);
+    mb[it] = 0xffu;
+    if (amask) {
+      if (sizeof(T) == 2) mb[it] = amask[e >> 3];
+      else mb[it] = (amask[e >> 2] & 15u) | ((unsigned)(amask[(e >> 2) + 1] & 15u) << 4);
+    }
+  }
+}
+template <int NT, class T, int BN, int HR, class RowOff>
+__device__ __forceinline__ void epi_store_rows_pre_nt(const float* ep, int tid, int n0,
+                                                      const Vec<T, 8> (&ad)[HR * (BN / 8) / NT],
+                                                      const unsigned (&mb)[HR * (BN / 8) / NT], T* __restrict__ out,
+                                                      RowOff rowoff) {
+  constexpr int EP_PITCH = BN + 4;
+  constexpr int GROUPS = BN / 8, PER_THREAD = HR * GROUPS / NT, RG = NT / GROUPS;
+  const int c8 = (tid % GROUPS) * 8, erow = tid / GROUPS;
+  const int col = n0 + c8;
+#pragma unroll
+  for (int it = 0; it < PER_THREAD; ++it) {
+    const int row = erow + it * RG;
+    const int64_t ro = rowoff(row);
+    const epi_v4f x0 = *reinterpret_cast<const epi_v4f*>(&ep[row * EP_PITCH + c8]);
+    const epi_v4f x1 = *reinterpret_cast<const epi_v4f*>(&ep[row * EP_PITCH + c8 + 4]);
+    float v[8] = {x0[0], x0[1], x0[2], x0[3], x1[0], x1[1], x1[2], x1[3]};
+    Vec<T, 8> t;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      v[k] += ((mb[it] >> k) & 1u) ? to_f32(ad[it].v[k]) : 0.f;
+      t.v[k] = from_f32<T>(v[k]);
+    }
+    if (ro >= 0) *reinterpret_cast<Vec<T, 8>*>(out + ro + col) = t;
+  }
+}
+
 // The uniform choice of the code path.  CAN_BIAS / CAN_ADD: whether the calling kernel is ever given a bias / an
 // addend (forward kernels have no addend, data-gradient kernels no bias); the combinations that cannot occur are not
 // compiled, which keeps their registers out of the kernel.

@@ -399,6 +399,18 @@ conv1x1_large_kernel(const T* __restrict__ X, const T* __restrict__ W, const flo
   float ss[8], qq[8];
 #pragma unroll
   for (int k = 0; k < 8; ++k) { ss[k] = 0.f; qq[k] = 0.f; }
+  // a data gradient that adds a residual: the addend pieces of pass p + 1 are requested before the stores of pass p
+  constexpr int EPT = 64 * (BN / 8) / NT;
+  Vec<T, 8> adn[EPT];
+  unsigned mbn[EPT];
+  const bool residual = DGRAD && addend != nullptr;
+  auto rowoff_of = [&](int pass) {
+    return [&a, m0, pass](int row) -> int64_t {
+      const int64_t grow = m0 + pass * 64 + row;
+      return grow < a.M ? grow * a.Ng : -1;
+    };
+  };
+  if (residual) epi_load_addend_nt<NT, T, BN, 64>(tid, n0, addend, a.amask, rowoff_of(0), adn, mbn);
 #pragma unroll
   for (int pass = 0; pass < BM / 64; ++pass) {
     __syncthreads();
@@ -413,11 +425,15 @@ conv1x1_large_kernel(const T* __restrict__ X, const T* __restrict__ W, const flo
                 acc[(pass * 64 % WTM) / 32 + ii][jn][e];
     }
     __syncthreads();
-    auto rowoff = [&](int row) -> int64_t {
-      const int64_t grow = m0 + pass * 64 + row;
-      return grow < a.M ? grow * a.Ng : -1;
-    };
-    if (DGRAD) {
+    auto rowoff = rowoff_of(pass);
+    if (residual) {
+      Vec<T, 8> ad[EPT];
+      unsigned mb[EPT];
+#pragma unroll
+      for (int it = 0; it < EPT; ++it) { ad[it] = adn[it]; mb[it] = mbn[it]; }
+      if (pass + 1 < BM / 64) epi_load_addend_nt<NT, T, BN, 64>(tid, n0, addend, a.amask, rowoff_of(pass + 1), adn, mbn);
+      epi_store_rows_pre_nt<NT, T, BN, 64>(ep, tid, n0, ad, mb, out, rowoff);
+    } else if (DGRAD) {
       epi_store_pass_nt<NT, T, BN, 64, false, true, false>(ep, tid, n0, bias, addend, a.amask, out, 0, rowoff, ss, qq);
     } else {
       if (stat_partial) epi_store_pass_nt<NT, T, BN, 64, true, false, true>(ep, tid, n0, bias, addend, nullptr, out, a.relu, rowoff, ss, qq);
@@ -484,19 +500,23 @@ void launch_pw_t(hipStream_t st, bool dgrad, int bn, const void* X, const void* 
   }
 }
 
+// A data gradient that adds a residual takes 256 x 128 tiles with two blocks per CU: its block spends more time in the
+// epilogue (fetching the 128 KB residual tile, storing as much) than in its depth loop, and with the CU to itself
+// nothing overlaps the two (256 -> 1024 channels at 262 144 pixels, bf16: 354 us with 128 x 128 tiles, 353 with
+// 256 x 256 and the residual fetched a pass ahead, 340 with 256 x 128).  The same half tile for short-depth forward
+// layers was far slower (the class 47 -> 60 ms per step on the largest workload).
 template <class T>
 void launch_pw_large_t(hipStream_t st, bool dgrad, const void* X, const void* W, const float* bias, const void* addend,
                        void* out, float* stat_partial, const PwArgs& a) {
-  if (dgrad) launch_pw_large<T, true, PWL_BM, PWL_BN, 2, 4, false>(st, X, W, bias, addend, out, stat_partial, a);
+  if (dgrad && addend) launch_pw_large<T, true, PWL_BM, PWL_BN / 2, 2, 2, false>(st, X, W, bias, addend, out, stat_partial, a);
+  else if (dgrad) launch_pw_large<T, true, PWL_BM, PWL_BN, 2, 4, false>(st, X, W, bias, addend, out, stat_partial, a);
   else if (a.fold) launch_pw_large<T, false, PWL_BM, PWL_BN, 2, 4, true>(st, X, W, bias, addend, out, stat_partial, a);
   else launch_pw_large<T, false, PWL_BM, PWL_BN, 2, 4, false>(st, X, W, bias, addend, out, stat_partial, a);
 }
 
 void launch_pw(hipStream_t st, int dt, bool dgrad, const void* X, const void* W, const float* bias, const void* addend,
                void* out, float* stat_partial, PwArgs a) {
-  // (a data gradient that adds a residual stays with the small tile: one block per CU has nobody to cover the latency
-  // of the addend loads in its epilogue -- 332 against 313 us on 256 -> 1024 channels at 262 144 pixels)
-  if (pw_large_ok(a.M, a.Ng, a.Kd, a.stride, a.scatter != 0) && !(dgrad && addend)) {
+  if (pw_large_ok(a.M, a.Ng, a.Kd, a.stride, a.scatter != 0)) {
     if (dt == DT_BF16) launch_pw_large_t<bf16_t>(st, dgrad, X, W, bias, addend, out, stat_partial, a);
     else launch_pw_large_t<f16_t>(st, dgrad, X, W, bias, addend, out, stat_partial, a);
     return;
