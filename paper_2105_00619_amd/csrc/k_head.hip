@@ -33,20 +33,49 @@ __global__ void __launch_bounds__(256) head_feat_kernel(const T* __restrict__ x,
   if (ty == 0 && c < C) feat[(int64_t)n * C + c] = (((sm[0][tx] + sm[1][tx]) + sm[2][tx]) + sm[3][tx]) / (float)HW;
 }
 
-// one wavefront per (sample, class): lanes stride over the features, then a fixed butterfly
+// logits[n][j] = b[j] + sum_f feat[n][f] * w[j][f]: lanes stride over the features, then a fixed butterfly, per (sample,
+// class).  A wavefront owns 8 samples x 8 classes, so that every feature and weight value it loads serves eight sums
+// (one wavefront per (sample, class) re-read the whole weight matrix per sample: 508 us at batch 4096, 2048 features).
+// With few samples the tiles are too few to fill the chip: then a wavefront keeps to one (sample, class).
+template <int LIN_TN, int LIN_TJ>
 __global__ void __launch_bounds__(256) linear_fwd_kernel(const float* __restrict__ feat, const float* __restrict__ w,
                                                          const float* __restrict__ b, float* __restrict__ logits, int N, int F,
                                                          int J) {
-  const int i = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (i >= N * J) return;
-  const int n = i / J, j = i % J, lane = threadIdx.x & 63;
-  const float* fp = feat + (int64_t)n * F;
-  const float* wp = w + (int64_t)j * F;
-  float acc = 0.f;
-  for (int f = lane; f < F; f += 64) acc = __fmaf_rn(fp[f], wp[f], acc);
+  const int jt = (J + LIN_TJ - 1) / LIN_TJ;
+  const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int n0 = (t / jt) * LIN_TN, j0 = (t % jt) * LIN_TJ, lane = threadIdx.x & 63;
+  if (n0 >= N) return;
+  const float* fp[LIN_TN];
+  const float* wp[LIN_TJ];
 #pragma unroll
-  for (int off = 32; off > 0; off >>= 1) acc += __shfl_xor(acc, off, 64);
-  if (lane == 0) logits[i] = acc + b[j];
+  for (int s = 0; s < LIN_TN; ++s) fp[s] = feat + (int64_t)(n0 + s < N ? n0 + s : n0) * F;
+#pragma unroll
+  for (int c = 0; c < LIN_TJ; ++c) wp[c] = w + (int64_t)(j0 + c < J ? j0 + c : j0) * F;
+  float acc[LIN_TN][LIN_TJ];
+#pragma unroll
+  for (int s = 0; s < LIN_TN; ++s)
+#pragma unroll
+    for (int c = 0; c < LIN_TJ; ++c) acc[s][c] = 0.f;
+  for (int f = lane; f < F; f += 64) {
+    float x[LIN_TN], v[LIN_TJ];
+#pragma unroll
+    for (int s = 0; s < LIN_TN; ++s) x[s] = fp[s][f];
+#pragma unroll
+    for (int c = 0; c < LIN_TJ; ++c) v[c] = wp[c][f];
+#pragma unroll
+    for (int s = 0; s < LIN_TN; ++s)
+#pragma unroll
+      for (int c = 0; c < LIN_TJ; ++c) acc[s][c] = __fmaf_rn(x[s], v[c], acc[s][c]);
+  }
+#pragma unroll
+  for (int s = 0; s < LIN_TN; ++s)
+#pragma unroll
+    for (int c = 0; c < LIN_TJ; ++c) {
+      float a = acc[s][c];
+#pragma unroll
+      for (int off = 32; off > 0; off >>= 1) a += __shfl_xor(a, off, 64);
+      if (lane == 0 && n0 + s < N && j0 + c < J) logits[(int64_t)(n0 + s) * J + j0 + c] = a + b[j0 + c];
+    }
 }
 
 // per sample: loss_n = logsumexp(logits_n) - logits_n[y_n]; dlogits = (softmax - onehot) * gscale
@@ -91,39 +120,68 @@ __global__ void __launch_bounds__(256) loss_mean_kernel(const float* __restrict_
 }
 
 // dW[j][f] = sum_n dlogits[n][j] * feat[n][f] ; the extra column f == F is the bias gradient
+// LBW_TJ: classes per block of the weight gradient (more when that still leaves a few blocks per CU)
+template <int LBW_TJ>
 __global__ void __launch_bounds__(256) linear_bwd_w_kernel(const float* __restrict__ dlogits, const float* __restrict__ feat,
                                                            float* __restrict__ dw, float* __restrict__ db, int N, int F, int J) {
-  // block = one class j and 64 consecutive features (feature index F stands for the bias); the four wavefronts take
-  // samples n = wave, wave + 4, ... and their sums are added in a fixed order
-  __shared__ float red[4][64];
+  // block = LBW_TJ classes and 64 consecutive features (feature index F stands for the bias); the four wavefronts take
+  // samples n = wave, wave + 4, ... and their sums are added in a fixed order.  (One class per block read the features
+  // once per class.)
+  __shared__ float red[LBW_TJ][4][64];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int j = blockIdx.y, f = blockIdx.x * 64 + lane;
+  const int j0 = blockIdx.y * LBW_TJ, f = blockIdx.x * 64 + lane;
   const bool isw = f < F;
   const float* fp = feat + (isw ? f : 0);
   const float one = f == F ? 1.f : 0.f;
-  float acc = 0.f;
+  float acc[LBW_TJ];
+#pragma unroll
+  for (int c = 0; c < LBW_TJ; ++c) acc[c] = 0.f;
+  int jc[LBW_TJ];
+#pragma unroll
+  for (int c = 0; c < LBW_TJ; ++c) jc[c] = j0 + c < J ? j0 + c : j0;
 #pragma unroll 8
   for (int n = wave; n < N; n += 4) {
     const float v = isw ? fp[(int64_t)n * F] : one;
-    acc = __fmaf_rn(dlogits[(int64_t)n * J + j], v, acc);
+    const float* dl = dlogits + (int64_t)n * J;
+#pragma unroll
+    for (int c = 0; c < LBW_TJ; ++c) acc[c] = __fmaf_rn(dl[jc[c]], v, acc[c]);
   }
-  red[wave][lane] = acc;
+#pragma unroll
+  for (int c = 0; c < LBW_TJ; ++c) red[c][wave][lane] = acc[c];
   __syncthreads();
   if (wave == 0) {
-    const float s = ((red[0][lane] + red[1][lane]) + red[2][lane]) + red[3][lane];
-    if (isw) dw[(int64_t)j * F + f] = s;
-    else if (f == F) db[j] = s;
+#pragma unroll
+    for (int c = 0; c < LBW_TJ; ++c) {
+      if (j0 + c >= J) break;
+      const float s = ((red[c][0][lane] + red[c][1][lane]) + red[c][2][lane]) + red[c][3][lane];
+      if (isw) dw[(int64_t)(j0 + c) * F + f] = s;
+      else if (f == F) db[j0 + c] = s;
+    }
   }
 }
 
-__global__ void linear_bwd_x_kernel(const float* __restrict__ dlogits, const float* __restrict__ w, float* __restrict__ dfeat,
-                                    int N, int F, int J) {
-  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= (int64_t)N * F) return;
-  const int n = (int)(i / F), f = (int)(i % F);
-  float acc = 0.f;
-  for (int j = 0; j < J; ++j) acc = __fmaf_rn(dlogits[(int64_t)n * J + j], w[(int64_t)j * F + f], acc);
-  dfeat[i] = acc;
+// dfeat[n][f] = sum_j dlogits[n][j] * w[j][f], classes in ascending order; a thread owns one feature of 8 samples, so a
+// weight value is loaded once per eight sums
+template <int LBX_TN>
+__global__ void __launch_bounds__(256) linear_bwd_x_kernel(const float* __restrict__ dlogits, const float* __restrict__ w,
+                                                           float* __restrict__ dfeat, int N, int F, int J) {
+  const int f = blockIdx.x * 256 + threadIdx.x;
+  const int n0 = blockIdx.y * LBX_TN;
+  if (f >= F) return;
+  const float* dl[LBX_TN];
+#pragma unroll
+  for (int s = 0; s < LBX_TN; ++s) dl[s] = dlogits + (int64_t)(n0 + s < N ? n0 + s : n0) * J;
+  float acc[LBX_TN];
+#pragma unroll
+  for (int s = 0; s < LBX_TN; ++s) acc[s] = 0.f;
+  for (int j = 0; j < J; ++j) {
+    const float v = w[(int64_t)j * F + f];
+#pragma unroll
+    for (int s = 0; s < LBX_TN; ++s) acc[s] = __fmaf_rn(dl[s][j], v, acc[s]);
+  }
+#pragma unroll
+  for (int s = 0; s < LBX_TN; ++s)
+    if (n0 + s < N) dfeat[(int64_t)(n0 + s) * F + f] = acc[s];
 }
 
 template <class T>
@@ -181,7 +239,11 @@ void launch_head_logits(hipStream_t st, int dt, const void* x, int N, int HW, in
   if (dt == DT_F32) OSEQ_LAUNCH(head_feat_kernel<float>, feat_grid, dim3(256), 0, st, (const float*)x, feat, HW, C, gap);
   else if (dt == DT_BF16) OSEQ_LAUNCH(head_feat_kernel<bf16_t>, feat_grid, dim3(256), 0, st, (const bf16_t*)x, feat, HW, C, gap);
   else OSEQ_LAUNCH(head_feat_kernel<f16_t>, feat_grid, dim3(256), 0, st, (const f16_t*)x, feat, HW, C, gap);
-  OSEQ_LAUNCH(linear_fwd_kernel, dim3(ceil_div((int64_t)N * J, 4)), dim3(256), 0, st, feat, w, b, logits, N, F, J);
+  if ((int64_t)ceil_div(N, 8) * ceil_div(J, 8) >= 2048)
+    OSEQ_LAUNCH((linear_fwd_kernel<8, 8>), dim3(ceil_div((int64_t)ceil_div(N, 8) * ceil_div(J, 8), 4)), dim3(256), 0, st, feat, w,
+                b, logits, N, F, J);
+  else
+    OSEQ_LAUNCH((linear_fwd_kernel<1, 1>), dim3(ceil_div((int64_t)N * J, 4)), dim3(256), 0, st, feat, w, b, logits, N, F, J);
 }
 
 void launch_head_fwd(hipStream_t st, int dt, const void* x, int N, int HW, int C, int gap, int F, int J, const float* w,
@@ -194,9 +256,16 @@ void launch_head_fwd(hipStream_t st, int dt, const void* x, int N, int HW, int C
 
 void launch_head_bwd(hipStream_t st, int dt, const float* feat, const float* dlogits, const float* w, int N, int HW, int C,
                      int gap, int F, int J, float* dw, float* db, float* dfeat, void* dx) {
-  OSEQ_LAUNCH(linear_bwd_w_kernel, dim3(ceil_div(F + 1, 64), J), dim3(256), 0, st, dlogits, feat, dw, db, N, F, J);
+  const int strips = ceil_div(F + 1, 64);
+  if ((int64_t)strips * ceil_div(J, 4) >= 512)
+    OSEQ_LAUNCH(linear_bwd_w_kernel<4>, dim3(strips, ceil_div(J, 4)), dim3(256), 0, st, dlogits, feat, dw, db, N, F, J);
+  else
+    OSEQ_LAUNCH(linear_bwd_w_kernel<1>, dim3(strips, J), dim3(256), 0, st, dlogits, feat, dw, db, N, F, J);
   if (!dx) return;
-  OSEQ_LAUNCH(linear_bwd_x_kernel, dim3(ceil_div((int64_t)N * F, 128)), dim3(128), 0, st, dlogits, w, dfeat, N, F, J);
+  if ((int64_t)ceil_div(F, 256) * ceil_div(N, 8) >= 512)
+    OSEQ_LAUNCH(linear_bwd_x_kernel<8>, dim3(ceil_div(F, 256), ceil_div(N, 8)), dim3(256), 0, st, dlogits, w, dfeat, N, F, J);
+  else
+    OSEQ_LAUNCH(linear_bwd_x_kernel<1>, dim3(ceil_div(F, 256), N), dim3(256), 0, st, dlogits, w, dfeat, N, F, J);
   if (dt == DT_F32) launch_feat_bwd<float>(st, dfeat, dx, N, HW, C, gap);
   else if (dt == DT_BF16) launch_feat_bwd<bf16_t>(st, dfeat, dx, N, HW, C, gap);
   else launch_feat_bwd<f16_t>(st, dfeat, dx, N, HW, C, gap);
