@@ -735,18 +735,46 @@ bool choose_segments(Plan& p) {
     return true;
   };
   const uint64_t budget = p.cfg.activation_budget_bytes;
-  uint64_t T = budget > lo ? budget : lo;
-  for (int attempt = 0; attempt < 24; ++attempt) {
+  if (!budget) {
     std::vector<int> cuts;
-    if (!cheapest(T, &cuts)) break;
-    if (!budget) { p.seg_begin = cuts; return true; }
+    if (cheapest(lo, &cuts)) { p.seg_begin = cuts; return true; }
+    p.seg_begin = best;
+    return true;
+  }
+  // With a budget: the modelled peak (saved tensors only) of a partition is below its arena (transients, alignment,
+  // fragmentation), so the threshold that just fits the budget is searched: lowered in sixteenths from the budget until
+  // the scheduled arena fits, then bisected between that threshold and the last one that did not.
+  auto fits = [&](uint64_t T, std::vector<int>* cuts, bool* error) {
+    *error = false;
+    if (!cheapest(T, cuts)) return false;
     Plan trial = p;
     trial.cfg.boundaries = nullptr;
-    trial.seg_begin = cuts;
-    if (!build_schedule(trial)) { p.error = trial.error; return false; }
-    if (trial.arena_bytes <= budget) { p.seg_begin = cuts; return true; }
+    trial.seg_begin = *cuts;
+    if (!build_schedule(trial)) { p.error = trial.error; *error = true; return false; }
+    return trial.arena_bytes <= budget;
+  };
+  uint64_t T = budget > lo ? budget : lo, too_big = 0;
+  std::vector<int> good;
+  uint64_t good_T = 0;
+  for (int attempt = 0; attempt < 24; ++attempt) {
+    std::vector<int> cuts;
+    bool error;
+    if (fits(T, &cuts, &error)) { good = cuts; good_T = T; break; }
+    if (error) return false;
+    too_big = T;
     if (T == lo) break;
     T = std::max<uint64_t>(lo, T - T / 16);
+  }
+  if (!good.empty()) {
+    for (int it = 0; it < 8 && too_big > good_T + (budget >> 10); ++it) {
+      const uint64_t mid = good_T + (too_big - good_T) / 2;
+      std::vector<int> cuts;
+      bool error;
+      if (fits(mid, &cuts, &error)) { good = cuts; good_T = mid; }
+      else { if (error) return false; too_big = mid; }
+    }
+    p.seg_begin = good;
+    return true;
   }
   p.seg_begin = best;  // nothing cheaper fits: the minimum-peak partition
   return true;
