@@ -2,6 +2,7 @@
 // kernels do not take: very few channels (the 3-channel stem, the tiny test networks).  NHWC activations,
 // (C_out, kh, kw, C_in) weights, fp32 accumulation in a fixed order.
 #include "dev_common.h"
+#include "epilogue.h"
 #include "kernels.h"
 
 namespace oseq {
@@ -198,6 +199,116 @@ __global__ void __launch_bounds__(256) conv_fwd_smallc_kernel(const T* __restric
   }
 }
 
+// The same layer in the 16-bit modes, with at most 32 products per output (3x3 on up to 3 channels) and output
+// channels in groups of 64: the plain-FMA kernel above is bound by its 27 x 64 multiply-adds per pixel on the vector
+// units (296 us for 4.2 M pixels, where writing the output takes 100), so the products go to the matrix cores as one
+// 32-deep MFMA step: the block gathers the patches of its 128 pixels into LDS as [pixel][32] in the storage type (depth
+// 27..31 zero), the 64 x 32 weight tile beside them, every wavefront multiplies 64 pixels x 32 channels with two
+// 32x32x16 MFMAs per 32 x 32 tile, and the shared epilogue rounds and stores whole rows.
+template <class T> struct StemMma;
+template <> struct StemMma<bf16_t> {
+  typedef __attribute__((ext_vector_type(8))) __bf16 V;
+  typedef __attribute__((ext_vector_type(16))) float A;
+  __device__ static __forceinline__ A run(V a, V b, A c) { return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0); }
+};
+template <> struct StemMma<f16_t> {
+  typedef __attribute__((ext_vector_type(8))) _Float16 V;
+  typedef __attribute__((ext_vector_type(16))) float A;
+  __device__ static __forceinline__ A run(V a, V b, A c) { return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0); }
+};
+
+template <class T, int C>
+__global__ void __launch_bounds__(256) conv_fwd_smallc_mfma_kernel(const T* __restrict__ x, const T* __restrict__ w,
+                                                                   const float* __restrict__ bias, T* __restrict__ out,
+                                                                   ConvGeom g, int relu, FastDiv divQ, FastDiv divPQ) {
+  typedef typename StemMma<T>::V FV;
+  typedef typename StemMma<T>::A v16f;
+  constexpr int RSC = 9 * C;       // <= 32
+  constexpr int PITCH = 40;        // elements per LDS row (80 bytes)
+  constexpr int PPT = 4;
+  static_assert(RSC <= 32, "one 32-deep step");
+  // 15 KB of operands, reused as the 17 KB epilogue tile: eight blocks (all 32 wavefronts) fit a CU, which is what hides
+  // the latency of the gather (a block is a dozen dependent-free 2-byte loads per thread, a barrier and a few MFMAs)
+  constexpr int EP_BYTES = 64 * (64 + 4) * 4, OP_BYTES = (64 + 128) * PITCH * (int)sizeof(T);
+  __shared__ __attribute__((aligned(16))) unsigned char smem[EP_BYTES > OP_BYTES ? EP_BYTES : OP_BYTES];
+  T* ws = reinterpret_cast<T*>(smem);                 // [channel][depth]
+  T* xs = ws + 64 * PITCH;                            // [pixel of the block][depth]
+  float* ep = reinterpret_cast<float*>(smem);         // epilogue tile (after the operands have been read)
+  const int tid = threadIdx.x;
+  const int kbase = blockIdx.y * 64;
+  for (int i = tid; i < 64 * 32; i += 256) {
+    const int k = i >> 5, e = i & 31;
+    ws[k * PITCH + e] = e < RSC ? w[(kbase + k) * RSC + e] : from_f32<T>(0.f);
+  }
+  const int grp = tid & 7, slot = tid >> 3;
+  const int pixels = g.N * g.P * g.Q;  // < 2^24 (checked by the launcher)
+  const int H = g.H, W = g.W, cstride = g.stride, pad = g.pad;
+  // this thread's depth elements e = grp + 8u of each of its four pixels
+  int er[4], es[4], ec[4];
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    const int e = grp + 8 * u < RSC ? grp + 8 * u : RSC - 1;
+    const int tap = e / C;
+    ec[u] = e - tap * C; er[u] = tap / 3 - pad; es[u] = tap % 3 - pad;
+  }
+#pragma unroll
+  for (int i = 0; i < PPT; ++i) {
+    const int m = blockIdx.x * (32 * PPT) + slot + 32 * i;
+    const uint32_t mm = m < pixels ? (uint32_t)m : 0u;
+    const uint32_t n = divPQ.div(mm), rem = mm - n * divPQ.d;
+    const uint32_t p = divQ.div(rem), q = rem - p * divQ.d;
+    const int ih0 = (int)p * cstride, iw0 = (int)q * cstride, nbase = (int)n * H;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int ih = ih0 + er[u], iw = iw0 + es[u];
+      const bool ok = ih >= 0 && ih < H && iw >= 0 && iw < W && grp + 8 * u < RSC;
+      const T v = x[ok ? ((nbase + ih) * W + iw) * C + ec[u] : 0];
+      xs[(slot + 32 * i) * PITCH + grp + 8 * u] = ok ? v : from_f32<T>(0.f);
+    }
+  }
+  __syncthreads();
+  // lane group g owns depth elements [16g, 16g + 16) of both operands (first MFMA: its first eight, second: the rest)
+  const int lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1, hg = lane >> 5, l32 = lane & 31;
+  const FV b0 = *reinterpret_cast<const FV*>(&ws[(wn * 32 + l32) * PITCH + hg * 16]);
+  const FV b1 = *reinterpret_cast<const FV*>(&ws[(wn * 32 + l32) * PITCH + hg * 16 + 8]);
+  v16f acc[2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const T* ap = &xs[(wm * 64 + i * 32 + l32) * PITCH + hg * 16];
+    const FV a0 = *reinterpret_cast<const FV*>(ap);
+    const FV a1 = *reinterpret_cast<const FV*>(ap + 8);
+    v16f c;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) c[e] = 0.f;
+    c = StemMma<T>::run(a0, b0, c);
+    acc[i] = StemMma<T>::run(a1, b1, c);
+  }
+  // epilogue: the 64 rows of one wavefront pair at a time through LDS as fp32 [64][64 + 4]
+  constexpr int EP_PITCH = 64 + 4;
+  float ss[8], qq[8];  // (channel sums: not used here)
+#pragma unroll
+  for (int k = 0; k < 8; ++k) { ss[k] = 0.f; qq[k] = 0.f; }
+#pragma unroll
+  for (int u = 0; u < 2; ++u) {
+    __syncthreads();
+    if (wm == u) {
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e)
+          ep[(i * 32 + 8 * (e >> 2) + 4 * hg + (e & 3)) * EP_PITCH + wn * 32 + l32] = acc[i][e];
+    }
+    __syncthreads();
+    auto rowoff = [&](int row) -> int64_t {
+      const int64_t m = (int64_t)blockIdx.x * 128 + u * 64 + row;
+      return m < pixels ? m * g.K : -1;
+    };
+    epi_store_pass<T, 64, 64, true, false, false>(ep, tid, kbase, bias, (const T*)nullptr, (const uint8_t*)nullptr, out, relu,
+                                                  rowoff, ss, qq);
+  }
+}
+
 // Weight gradient for few input channels (the network stem):  dw[k][e] = sum over pixels of dz[px][k] * col[px][e],
 // e = (tap, c) < 36, k <= 64.  HBM-bound on reading dz once.  A block reduces a fixed chunk of pixels in tiles of 64:
 // the dz tile [64][64] and the im2col tile [64][R*S*C] are staged in LDS as fp32 (two stages; the next tile's global
@@ -377,6 +488,16 @@ static void launch_fwd_smallc_t(hipStream_t st, const void* x, const void* w, co
                                 int relu) {
   dim3 grid(ceil_div((int64_t)g.N * g.P * g.Q, 128), ceil_div(g.K, 64)), block(256);
   const FastDiv dq = make_fastdiv((uint32_t)g.Q), dpq = make_fastdiv((uint32_t)(g.P * g.Q));
+  if constexpr (sizeof(T) == 2) {
+    if (g.K % 64 == 0 && g.C <= 3) {  // 16-bit modes: on the matrix cores
+      switch (g.C) {
+        case 1: OSEQ_LAUNCH((conv_fwd_smallc_mfma_kernel<T, 1>), grid, block, 0, st, (const T*)x, (const T*)w, bias, (T*)out, g, relu, dq, dpq); break;
+        case 2: OSEQ_LAUNCH((conv_fwd_smallc_mfma_kernel<T, 2>), grid, block, 0, st, (const T*)x, (const T*)w, bias, (T*)out, g, relu, dq, dpq); break;
+        default: OSEQ_LAUNCH((conv_fwd_smallc_mfma_kernel<T, 3>), grid, block, 0, st, (const T*)x, (const T*)w, bias, (T*)out, g, relu, dq, dpq); break;
+      }
+      return;
+    }
+  }
   switch (g.C) {
     case 1: OSEQ_LAUNCH((conv_fwd_smallc_kernel<T, 1>), grid, block, 0, st, (const T*)x, (const T*)w, bias, (T*)out, g, relu, dq, dpq); break;
     case 2: OSEQ_LAUNCH((conv_fwd_smallc_kernel<T, 2>), grid, block, 0, st, (const T*)x, (const T*)w, bias, (T*)out, g, relu, dq, dpq); break;
