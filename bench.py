@@ -38,7 +38,7 @@ GROUPS = {"conv_fwd": "conv_fwd+conv_dgrad", "conv_dgrad": "conv_fwd+conv_dgrad"
 GROUP_KERNELS = {
     "conv_fwd+conv_dgrad": "conv3x3_patch_kernel, conv_igemm_kernel (+ splitk_epilogue_kernel), conv_fwd_smallc_kernel",
     "conv_wgrad": "conv_wgrad3x3_kernel, conv_wgrad_kernel, conv_wgrad_smallc_kernel (+ wgrad_reduce_kernel)",
-    "conv1x1_fwd+conv1x1_dgrad": "conv1x1_large_kernel, conv1x1_kernel, conv_igemm_kernel (strided or few pixels)",
+    "conv1x1_fwd+conv1x1_dgrad": "conv1x1_ws_kernel, conv1x1_rows_kernel, conv1x1_large_kernel, conv1x1_kernel, conv_igemm_kernel (strided or few pixels)",
     "conv1x1_wgrad": "conv_wgrad_kernel (+ wgrad_reduce_kernel)",
 }
 DTYPE_NAME = {0: "f32", 1: "bf16", 2: "f16"}

@@ -445,6 +445,403 @@ conv1x1_large_kernel(const T* __restrict__ X, const T* __restrict__ W, const flo
                                 stat_partial + ((int64_t)mt * 2 + 1) * a.Ng + n0);
 }
 
+// Short-depth, wide layers (depth 64 to 256, two to four times as many output channels: the last convolution of a
+// bottleneck block and the data gradient of its first).  A tile of the kernels above spends a few depth steps between a start-up that
+// waits for HBM and an epilogue that stores 128 KB, and most of its instructions in that epilogue; and it fetches the
+// weight matrix from L2 again for every row tile, more bytes than HBM moves for these layers.  Two kernels for them:
+//
+// Data gradient (conv1x1_rows_kernel): a block keeps its 128 rows of dz, all of their depth, resident in LDS and walks
+// the column tiles (256 channels each) itself: dz is read from HBM exactly once and from L2 never; the weight tiles
+// stream through two LDS stages of 128 bytes of depth from registers two steps ahead, the stream running on across
+// the column tiles, so that the loads of the next tile's first steps (and the next residual pieces) are in flight
+// while this tile's results are stored.  512 threads = 8 wavefronts (2 x 4), wave tile 64 x 64.  Epilogue of a column
+// tile with a residual: 32 rows at a time through LDS as fp32, the masked residual added before the rounding; without
+// one: rounded on the accumulators where they are, the rounded values through LDS as [128][256 + 8] elements; 16-byte
+// stores of whole rows either way.
+constexpr int PWR_BM = 128, PWR_BN = 256, PWR_BK = 64;
+constexpr int PWR_PITCH = PWR_BK + 8;  // LDS row pitch of a weight stage in elements (144 bytes)
+
+template <int KD> constexpr size_t pwr_smem_bytes() {
+  return (size_t)2 * PWR_BN * PWR_PITCH * 2 + (size_t)PWR_BM * (KD + 8) * 2;
+}
+
+// sum of the two products of a pair of 16-bit values, added to c in fp32 (one instruction)
+template <class T> struct Dot2;
+template <> struct Dot2<bf16_t> {
+  typedef __attribute__((ext_vector_type(2))) __bf16 V;
+  __device__ static __forceinline__ float run(V a, V b, float c) { return __builtin_amdgcn_fdot2_f32_bf16(a, b, c, false); }
+};
+template <> struct Dot2<f16_t> {
+  typedef __attribute__((ext_vector_type(2))) _Float16 V;
+  __device__ static __forceinline__ float run(V a, V b, float c) { return __builtin_amdgcn_fdot2(a, b, c, false); }
+};
+
+template <class T, int KD>
+__global__ void __launch_bounds__(512)
+conv1x1_rows_kernel(const T* __restrict__ X, const T* __restrict__ W, const T* __restrict__ addend, T* __restrict__ out,
+                    PwArgs a) {
+  typedef typename Mma<T>::V FV;
+  constexpr int NT = 512, BM = PWR_BM, BN = PWR_BN, BK = PWR_BK, PITCH = PWR_PITCH, APITCH = KD + 8;
+  constexpr int WGN = 4, MI = 2, NI = 2;
+  constexpr int NS = KD / BK;          // depth steps per column tile (2 or 4)
+  constexpr int CPR = KD / 8;          // 16-byte chunks per row of X
+  constexpr int A_CH = BM * CPR / NT;  // of them per thread
+  constexpr int RPI = NT / CPR;        // rows between a thread's chunks
+  constexpr int B_CH = BN * (BK / 8) / NT;  // chunks per thread of a weight stage (4)
+  constexpr int BSTAGE = BN * PITCH;
+  constexpr int HR = 32;               // rows per pass of the residual-adding epilogue
+  constexpr int EPITCH = BN + 8;       // row pitch of the rounded tile
+  static_assert(NS == 2 || NS == 4, "depth 128 or 256");
+  static_assert((size_t)BM * EPITCH * 2 <= (size_t)2 * BSTAGE * 2, "the rounded tile lies over the weight stages");
+  static_assert((size_t)HR * (BN + 4) * 4 <= (size_t)2 * BSTAGE * 2, "so does the fp32 tile of the residual-adding epilogue");
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  T* bst = reinterpret_cast<T*>(smem_raw);
+  T* ares = bst + 2 * BSTAGE;
+  float* ep = reinterpret_cast<float*>(smem_raw);
+  T* stg = reinterpret_cast<T*>(smem_raw);
+
+  const int mt = blockIdx.x;
+  const int64_t m0 = (int64_t)mt * BM;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WGN, wn = wave % WGN, g = lane >> 5, l32 = lane & 31;
+  const int vec = tid & 7, row0 = tid >> 3;  // a weight stage: 8 chunks per row, 64 rows per sweep of the block
+  const int NP = a.Ng / BN, last = NP * NS - 1;
+
+  // weight stream: step t = depth step t % NS of column tile t / NS
+  const T* bbase = W + (int64_t)row0 * KD + vec * 8;
+  Chunk rb[2][B_CH];
+  auto gload = [&](auto P, int t) {
+    constexpr int p = decltype(P)::value;
+    const T* src = bbase + (int64_t)(t / NS) * BN * KD + (t % NS) * BK;
+#pragma unroll
+    for (int i = 0; i < B_CH; ++i) rb[p][i] = *reinterpret_cast<const Chunk*>(src + (int64_t)i * 64 * KD);
+  };
+  auto sstore = [&](auto P) {
+    constexpr int p = decltype(P)::value;
+    T* st = bst + p * BSTAGE;
+#pragma unroll
+    for (int i = 0; i < B_CH; ++i) *reinterpret_cast<Chunk*>(&st[(row0 + i * 64) * PITCH + vec * 8]) = rb[p][i];
+  };
+  gload(IC<0>{}, 0);
+  gload(IC<1>{}, 1);
+
+  // the block's rows of X, whole depth; rows past the last pixel read row 0 (never stored)
+  {
+    const int cc = tid % CPR, r0 = tid / CPR;
+    Chunk ra[A_CH];
+#pragma unroll
+    for (int i = 0; i < A_CH; ++i) {
+      const int64_t m = m0 + r0 + i * RPI;
+      ra[i] = *reinterpret_cast<const Chunk*>(X + (m < a.M ? m : 0) * KD + cc * 8);
+    }
+#pragma unroll
+    for (int i = 0; i < A_CH; ++i) *reinterpret_cast<Chunk*>(&ares[(r0 + i * RPI) * APITCH + cc * 8]) = ra[i];
+  }
+
+  v16f acc[MI][NI];
+  // lane group g owns depth elements [32 s + 16 g, + 16) of the two 32-element halves s of a step, 8 per MFMA
+  const int afrag = (wm * 64 + l32) * APITCH + g * 16;
+  const int bfrag = (wn * 64 + l32) * PITCH + g * 16;
+  auto compute = [&](int stage, int kt) {
+    const T* st = bst + stage * BSTAGE;
+    const T* ar = ares + kt * BK;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int ko = (q >> 1) * 32 + (q & 1) * 8;
+      FV fa[MI], fb[NI];
+#pragma unroll
+      for (int i = 0; i < MI; ++i) fa[i] = *reinterpret_cast<const FV*>(ar + afrag + i * 32 * APITCH + ko);
+#pragma unroll
+      for (int j = 0; j < NI; ++j) fb[j] = *reinterpret_cast<const FV*>(st + bfrag + j * 32 * PITCH + ko);
+#pragma unroll
+      for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NI; ++j) acc[i][j] = Mma<T>::run(fa[i], fb[j], acc[i][j]);
+    }
+  };
+
+  constexpr int EPT = HR * (BN / 8) / NT;
+  Vec<T, 8> adn[EPT];
+  unsigned mbn[EPT];
+  const bool residual = addend != nullptr;
+  auto rowoff_of = [&](int sp) {
+    return [&a, m0, sp](int row) -> int64_t {
+      const int64_t grow = m0 + sp * HR + row;
+      return grow < a.M ? grow * a.Ng : -1;
+    };
+  };
+  if (residual) epi_load_addend_nt<NT, T, BN, HR>(tid, 0, addend, a.amask, rowoff_of(0), adn, mbn);
+  const bool ragged = m0 + BM > a.M;
+
+  for (int ps = 0; ps < NP; ++ps) {
+    const int n0 = ps * BN;
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+      for (int j = 0; j < NI; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+    // A step stores its generation to LDS and refills it with the step two ahead (past the end: the last step again,
+    // never used); a stage is rewritten two steps later, after the barrier of the step between.
+#pragma unroll
+    for (int k2 = 0; k2 < NS; k2 += 2) {
+      const int t = ps * NS + k2;
+      sstore(IC<0>{}); gload(IC<0>{}, t + 2 < last ? t + 2 : last); __syncthreads(); compute(0, k2);
+      sstore(IC<1>{}); gload(IC<1>{}, t + 3 < last ? t + 3 : last); __syncthreads(); compute(1, k2 + 1);
+    }
+    __syncthreads();  // the weight stages are free: the epilogue tiles lie over them
+
+    if (residual) {
+      // ---- 32 rows at a time as fp32 [32][BN + 4]; the residual pieces of a pass are requested a pass ahead ----
+#pragma unroll
+      for (int sp = 0; sp < BM / HR; ++sp) {
+        if (sp) __syncthreads();
+        if (wm == sp / 2) {
+#pragma unroll
+          for (int jn = 0; jn < NI; ++jn)
+#pragma unroll
+            for (int e = 0; e < 16; ++e)
+              ep[(8 * (e >> 2) + 4 * g + (e & 3)) * (BN + 4) + wn * 64 + jn * 32 + l32] = acc[sp % 2][jn][e];
+        }
+        __syncthreads();
+        Vec<T, 8> ad[EPT];
+        unsigned mb[EPT];
+#pragma unroll
+        for (int it = 0; it < EPT; ++it) { ad[it] = adn[it]; mb[it] = mbn[it]; }
+        if (sp + 1 < BM / HR) epi_load_addend_nt<NT, T, BN, HR>(tid, n0, addend, a.amask, rowoff_of(sp + 1), adn, mbn);
+        else if (ps + 1 < NP) epi_load_addend_nt<NT, T, BN, HR>(tid, n0 + BN, addend, a.amask, rowoff_of(0), adn, mbn);
+        epi_store_rows_pre_nt<NT, T, BN, HR>(ep, tid, n0, ad, mb, out, rowoff_of(sp));
+      }
+    } else {
+      // ---- rounded in place (a lane holds pairs of consecutive rows of one channel), through LDS as [BM][EPITCH] ----
+#pragma unroll
+      for (int jn = 0; jn < NI; ++jn) {
+        const int cj = wn * 64 + jn * 32 + l32;
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+          for (int e = 0; e < 16; ++e)
+            stg[(wm * 64 + i * 32 + 8 * (e >> 2) + 4 * g + (e & 3)) * EPITCH + cj] = from_f32<T>(acc[i][jn][e]);
+      }
+      __syncthreads();
+      constexpr int SPT = BM * (BN / 8) / NT;  // 16-byte pieces per thread
+      const int c8 = (tid % (BN / 8)) * 8, erow = tid / (BN / 8);
+#pragma unroll
+      for (int it = 0; it < SPT; ++it) {
+        const int row = erow + it * (NT / (BN / 8));
+        const Chunk c = *reinterpret_cast<const Chunk*>(&stg[row * EPITCH + c8]);
+        if (!ragged || m0 + row < a.M) *reinterpret_cast<Chunk*>(out + (m0 + row) * a.Ng + n0 + c8) = c;
+      }
+    }
+    __syncthreads();  // the weight stages are free again
+  }
+}
+
+// Forward (conv1x1_ws_kernel), weights stationary: a block owns 256 output channels for its whole life -- every
+// wavefront keeps the weights of its 32 channels, all of their depth, in registers as MFMA operands (64 registers at
+// depth 256) -- and walks row tiles of 128 (depth 256: 64) pixels: a tile of X goes through LDS once (turned into
+// activations on the way if a BatchNorm is folded in) and is multiplied by all eight wavefronts (wave tile 128 x 32).
+// Per tile nothing but X crosses from L2 to the CU.  256 blocks, one per CU; the blocks that share row tiles (one per
+// 256 channels) take consecutive slots of one XCD and move through the tiles together.  The next tile of X is requested
+// before the MFMAs of the current one and waits in registers.  Epilogue: bias / ReLU / rounding on the accumulators
+// where they are (a lane holds pairs of consecutive rows of one channel: the BatchNorm sums of the rounded values are
+// two dot-product instructions per pair, kept in registers over all tiles, one row of block sums per block), the
+// rounded values through LDS, 16-byte stores of whole rows.
+constexpr int PWS_BN = 256, PWS_BLOCKS = 256;
+// rows per tile: at depth 256 the weights take 64 registers, and 128 rows (64 accumulator registers, 32 for the tile in
+// flight) no longer fit beside them
+constexpr int pws_bm(int kd) { return kd > 128 ? 64 : 128; }
+
+template <int KD> constexpr size_t pws_smem_bytes() {
+  return (size_t)pws_bm(KD) * (KD + 8) * 2 + (size_t)pws_bm(KD) * (PWS_BN + 8) * 2 + (size_t)2 * 2 * PWS_BN * 4 + (size_t)2 * KD * 4;
+}
+
+template <class T, bool FOLD, int KD>
+__global__ void __launch_bounds__(512)
+conv1x1_ws_kernel(const T* __restrict__ X, const T* __restrict__ W, const float* __restrict__ bias, T* __restrict__ out,
+                  float* __restrict__ stat_partial, PwArgs a) {
+  typedef typename Mma<T>::V FV;
+  typedef typename Dot2<T>::V T2;
+  constexpr int NT = 512, BM = pws_bm(KD), BN = PWS_BN, APITCH = KD + 8, EPITCH = BN + 8;
+  constexpr int MI = BM / 32, KC = KD / 16;  // 32-row tiles per wavefront, 16-deep MFMA steps
+  constexpr int CPR = KD / 8;          // 16-byte chunks per row of X
+  constexpr int A_CH = BM * CPR / NT;  // of them per thread
+  constexpr int RPI = NT / CPR;        // rows between a thread's chunks
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  T* abuf = reinterpret_cast<T*>(smem_raw);           // [BM][APITCH]: the tile of X
+  T* stg = abuf + BM * APITCH;                        // [BM][EPITCH]: the rounded results
+  float* red = reinterpret_cast<float*>(stg + BM * EPITCH);  // [2][2][BN]
+  float* ftab = red + 2 * 2 * BN;                     // FOLD: [2][KD] scale, shift
+
+  // slot s of XCD x: channel group s % NCG of row group (s / NCG) * 8 + x
+  const int NCG = a.Ng / BN, RGN = PWS_BLOCKS / NCG;
+  const int b = blockIdx.x, xcd = b & 7, slot = b >> 3;
+  const int cg = slot % NCG, rg = (slot / NCG) * 8 + xcd;
+  const int n0 = cg * BN;
+  const int MT = a.MT;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int g = lane >> 5, l32 = lane & 31;
+  const int cj = wave * 32 + l32;  // the lane's channel within the block's 256
+
+  // the lane's weights: lane group g owns depth elements [32 s + 16 g, + 16) of every 32, 8 per MFMA
+  FV fb[KC];
+  {
+    const T* wrow = W + (int64_t)(n0 + cj) * KD + g * 16;
+#pragma unroll
+    for (int q = 0; q < KC; ++q) fb[q] = *reinterpret_cast<const FV*>(wrow + (q >> 1) * 32 + (q & 1) * 8);
+  }
+  if (FOLD) {
+    for (int i = tid; i < KD; i += NT) { ftab[i] = a.fold[2 * KD + i]; ftab[KD + i] = a.fold[3 * KD + i]; }
+  }
+  const float bj = bias ? bias[n0 + cj] : 0.f;
+
+  const int cc = tid % CPR, r0 = tid / CPR;
+  Chunk ra[A_CH];
+  // rows past the last pixel read row 0 (never stored, nothing added to the sums)
+  auto gload = [&](int t) {
+#pragma unroll
+    for (int i = 0; i < A_CH; ++i) {
+      const int64_t m = (int64_t)t * BM + r0 + i * RPI;
+      ra[i] = *reinterpret_cast<const Chunk*>(X + (m < a.M ? m : 0) * KD + cc * 8);
+    }
+  };
+  const int afrag = l32 * APITCH + g * 16;
+  const int c8 = (tid % (BN / 8)) * 8, erow = tid / (BN / 8);
+  float S1 = 0.f, S2 = 0.f;
+  T2 one2;
+  one2[0] = from_f32<T>(1.f); one2[1] = from_f32<T>(1.f);
+
+  // `ra` -> LDS (as activations if a BatchNorm is folded in), then the request for the tile after it
+  auto stage_tile = [&](int tnext) {
+    if (FOLD) {
+      float sc[8], sh[8];
+      load_f32<float, 8>(ftab + cc * 8, sc);
+      load_f32<float, 8>(ftab + KD + cc * 8, sh);
+#pragma unroll
+      for (int i = 0; i < A_CH; ++i) ra[i] = bn_fold_chunk<T>(ra[i], sc, sh, a.fold_relu);
+    }
+#pragma unroll
+    for (int i = 0; i < A_CH; ++i) *reinterpret_cast<Chunk*>(&abuf[(r0 + i * RPI) * APITCH + cc * 8]) = ra[i];
+    if (tnext < MT) gload(tnext);
+  };
+
+  // Two barriers per row tile: the MFMAs of tile t and the rounding of its results into `stg` between them; then the
+  // stores of tile t from `stg` together with the staging of tile t + 1 into `abuf`.  Loads and stores share one
+  // in-order counter: the rows a tile waits for were requested before the stores of the tile before it.
+  int t = rg;  // < MT
+  gload(t);
+  if (FOLD) __syncthreads();  // the scale / shift table
+  stage_tile(t + RGN);
+  for (;;) {
+    __syncthreads();
+    v16f acc[MI];
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
+#pragma unroll
+    for (int q = 0; q < KC; ++q) {
+      FV fa[MI];
+#pragma unroll
+      for (int i = 0; i < MI; ++i)
+        fa[i] = *reinterpret_cast<const FV*>(abuf + afrag + i * 32 * APITCH + (q >> 1) * 32 + (q & 1) * 8);
+#pragma unroll
+      for (int i = 0; i < MI; ++i) acc[i] = Mma<T>::run(fa[i], fb[q], acc[i]);
+    }
+
+    const int64_t m0 = (int64_t)t * BM;
+    const bool ragged = m0 + BM > a.M;
+    float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+      for (int e = 0; e < 16; e += 2) {
+        const int r = i * 32 + 8 * (e >> 2) + 4 * g + (e & 3);  // and r + 1
+        float v0 = acc[i][e] + bj, v1 = acc[i][e + 1] + bj;
+        if (a.relu) { v0 = fmaxf(v0, 0.f); v1 = fmaxf(v1, 0.f); }
+        if (ragged) {  // rows past the last pixel count as zero
+          if (m0 + r >= a.M) v0 = 0.f;
+          if (m0 + r + 1 >= a.M) v1 = 0.f;
+        }
+        T2 p2;
+        p2[0] = from_f32<T>(v0); p2[1] = from_f32<T>(v1);
+        s1 = Dot2<T>::run(p2, one2, s1);
+        s2 = Dot2<T>::run(p2, p2, s2);
+        stg[r * EPITCH + cj] = p2[0];
+        stg[(r + 1) * EPITCH + cj] = p2[1];
+      }
+    S1 += s1; S2 += s2;
+    __syncthreads();
+#pragma unroll
+    for (int it = 0; it < BM * (BN / 8) / NT; ++it) {
+      const int row = erow + it * (NT / (BN / 8));
+      const Chunk c = *reinterpret_cast<const Chunk*>(&stg[row * EPITCH + c8]);
+      if (!ragged || m0 + row < a.M) *reinterpret_cast<Chunk*>(out + (m0 + row) * a.Ng + n0 + c8) = c;
+    }
+    t += RGN;
+    if (t >= MT) break;
+    stage_tile(t + RGN);
+  }
+  if (stat_partial) {  // the two lane groups of a channel in a fixed order
+    red[g * BN + cj] = S1;
+    red[(2 + g) * BN + cj] = S2;
+    __syncthreads();
+    if (tid < BN) {
+      stat_partial[((int64_t)rg * 2 + 0) * a.Ng + n0 + tid] = red[tid] + red[BN + tid];
+      stat_partial[((int64_t)rg * 2 + 1) * a.Ng + n0 + tid] = red[2 * BN + tid] + red[3 * BN + tid];
+    }
+  }
+}
+
+template <class T, bool FOLD, int KD>
+void launch_pw_ws(hipStream_t st, const void* X, const void* W, const float* bias, void* out, float* stat_partial, PwArgs a) {
+  constexpr size_t sm = pws_smem_bytes<KD>();
+  static bool attr_done = false;
+  if (!attr_done) {
+    (void)hipFuncSetAttribute((const void*)conv1x1_ws_kernel<T, FOLD, KD>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sm);
+    attr_done = true;
+  }
+  a.MT = ceil_div(a.M, pws_bm(KD));
+  a.NT = a.Ng / PWS_BN;
+  OSEQ_LAUNCH((conv1x1_ws_kernel<T, FOLD, KD>), dim3(PWS_BLOCKS), dim3(512), sm, st, (const T*)X, (const T*)W, bias, (T*)out,
+              stat_partial, a);
+}
+
+// from the shape only: depth 64, 128 or 256 and at least twice as many output channels; 1, 2, 4 ... 32 channel groups;
+// at least four row tiles per block
+bool pw_ws_ok(int64_t M, int Ng, int Kd, int stride) {
+  if (stride != 1 || (Kd != 64 && Kd != 128 && Kd != 256) || Ng % PWS_BN != 0 || Ng < 2 * Kd) return false;
+  const int ncg = Ng / PWS_BN;
+  if (ncg > 32 || (ncg & (ncg - 1)) != 0) return false;
+  return ceil_div(M, 128) >= 4 * (PWS_BLOCKS / ncg);
+}
+
+template <class T, int KD>
+void launch_pw_ws_t(hipStream_t st, const void* X, const void* W, const float* bias, void* out, float* stat_partial, const PwArgs& a) {
+  if (a.fold) launch_pw_ws<T, true, KD>(st, X, W, bias, out, stat_partial, a);
+  else launch_pw_ws<T, false, KD>(st, X, W, bias, out, stat_partial, a);
+}
+
+template <class T, int KD>
+void launch_pw_rows(hipStream_t st, const void* X, const void* W, const void* addend, void* out, PwArgs a) {
+  constexpr size_t sm = pwr_smem_bytes<KD>();
+  static bool attr_done = false;
+  if (!attr_done) {
+    (void)hipFuncSetAttribute((const void*)conv1x1_rows_kernel<T, KD>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sm);
+    attr_done = true;
+  }
+  a.MT = ceil_div(a.M, PWR_BM);
+  a.NT = a.Ng / PWR_BN;
+  OSEQ_LAUNCH((conv1x1_rows_kernel<T, KD>), dim3(a.MT), dim3(512), sm, st, (const T*)X, (const T*)W, (const T*)addend, (T*)out, a);
+}
+
+// from the shape only: at least two blocks per CU
+bool pw_rows_ok(int64_t M, int Ng, int Kd, int stride, bool scatter) {
+  if (stride != 1 || scatter || (Kd != 128 && Kd != 256) || Ng % PWR_BN != 0 || Ng < 2 * PWR_BN) return false;
+  return ceil_div(M, PWR_BM) >= 512;
+}
+
 constexpr int PW_FOLD_MAX_DEPTH = 1024;  // the scale / shift table of a folded BatchNorm takes 8 bytes of LDS per channel
 
 template <class T, bool DGRAD, int BM, int BN, int WGM, int WGN, bool FOLD>
@@ -516,6 +913,28 @@ void launch_pw_large_t(hipStream_t st, bool dgrad, const void* X, const void* W,
 
 void launch_pw(hipStream_t st, int dt, bool dgrad, const void* X, const void* W, const float* bias, const void* addend,
                void* out, float* stat_partial, PwArgs a) {
+  if (!dgrad && pw_ws_ok(a.M, a.Ng, a.Kd, a.stride)) {
+    if (dt == DT_BF16) {
+      if (a.Kd == 256) launch_pw_ws_t<bf16_t, 256>(st, X, W, bias, out, stat_partial, a);
+      else if (a.Kd == 128) launch_pw_ws_t<bf16_t, 128>(st, X, W, bias, out, stat_partial, a);
+      else launch_pw_ws_t<bf16_t, 64>(st, X, W, bias, out, stat_partial, a);
+    } else {
+      if (a.Kd == 256) launch_pw_ws_t<f16_t, 256>(st, X, W, bias, out, stat_partial, a);
+      else if (a.Kd == 128) launch_pw_ws_t<f16_t, 128>(st, X, W, bias, out, stat_partial, a);
+      else launch_pw_ws_t<f16_t, 64>(st, X, W, bias, out, stat_partial, a);
+    }
+    return;
+  }
+  if (dgrad && pw_rows_ok(a.M, a.Ng, a.Kd, a.stride, a.scatter != 0)) {
+    if (dt == DT_BF16) {
+      if (a.Kd == 256) launch_pw_rows<bf16_t, 256>(st, X, W, addend, out, a);
+      else launch_pw_rows<bf16_t, 128>(st, X, W, addend, out, a);
+    } else {
+      if (a.Kd == 256) launch_pw_rows<f16_t, 256>(st, X, W, addend, out, a);
+      else launch_pw_rows<f16_t, 128>(st, X, W, addend, out, a);
+    }
+    return;
+  }
   if (pw_large_ok(a.M, a.Ng, a.Kd, a.stride, a.scatter != 0)) {
     if (dt == DT_BF16) launch_pw_large_t<bf16_t>(st, dgrad, X, W, bias, addend, out, stat_partial, a);
     else launch_pw_large_t<f16_t>(st, dgrad, X, W, bias, addend, out, stat_partial, a);
@@ -557,6 +976,7 @@ bool conv_pointwise_dgrad_ok(int dt, const ConvGeom& g) {
 }
 int conv_pointwise_stat_blocks(const ConvGeom& g) {
   const int64_t M = (int64_t)g.N * g.P * g.Q;
+  if (pw_ws_ok(M, g.K, g.C, g.stride)) return PWS_BLOCKS / (g.K / PWS_BN);
   return ceil_div(M, pw_large_ok(M, g.K, g.C, g.stride, false) ? PWL_BM : PW_BM);
 }
 

@@ -36,7 +36,7 @@ COPY_REPS = 4
 GROUP_KERNELS = {
     "conv_fwd+conv_dgrad": ("conv3x3_patch_kernel", "conv_igemm_kernel", "splitk_epilogue_kernel", "conv_fwd_smallc_kernel",
                             "conv_fwd_direct_kernel", "conv_dgrad_direct_kernel"),
-    "conv1x1_fwd+conv1x1_dgrad": ("conv1x1_kernel", "conv1x1_large_kernel"),
+    "conv1x1_fwd+conv1x1_dgrad": ("conv1x1_kernel", "conv1x1_large_kernel", "conv1x1_ws_kernel", "conv1x1_rows_kernel"),
     # one kernel family serves the 1x1 and the other weight gradients: counted together
     "conv_wgrad": ("conv_wgrad3x3_kernel", "conv_wgrad_kernel", "conv_wgrad_smallc_kernel", "wgrad_reduce_kernel",
                    "wave_reduce_kernel", "conv_wgrad_direct_kernel", "splitk_reduce_kernel"),
