@@ -25,7 +25,8 @@ __global__ void cast_out_kernel(const T* __restrict__ x, float* __restrict__ out
 }
 
 // ----------------------------------------------------- column reductions ----
-enum { RED_STATS = 0, RED_BN_BWD = 1, RED_BIAS = 2 };
+// RED_BN_BWD: ReLU decisions redone from z (or none); _AOUT: from the sign of the block output; _MASK: from the bits
+enum { RED_STATS = 0, RED_BN_BWD = 1, RED_BIAS = 2, RED_BN_BWD_AOUT = 3, RED_BN_BWD_MASK = 4 };
 
 struct RedArgs {
   const void* a;       // STATS: z ; BN_BWD: dA ; BIAS: dz
@@ -52,12 +53,13 @@ __global__ void __launch_bounds__(256) colreduce_kernel(RedArgs g) {
   float s0[V], s1[V];
 #pragma unroll
   for (int i = 0; i < V; ++i) s0[i] = s1[i] = 0.f;
+  constexpr bool BWD = MODE == RED_BN_BWD || MODE == RED_BN_BWD_AOUT || MODE == RED_BN_BWD_MASK;
   float mean[V], rstd[V], scale[V], shift[V];
-  if (MODE == RED_BN_BWD && active) {
+  if (BWD && active) {
 #pragma unroll
     for (int i = 0; i < V; ++i) {
       mean[i] = g.stats[c0 + i]; rstd[i] = g.stats[g.C + c0 + i];
-      scale[i] = g.stats[2 * g.C + c0 + i]; shift[i] = g.stats[3 * g.C + c0 + i];
+      if (MODE == RED_BN_BWD) { scale[i] = g.stats[2 * g.C + c0 + i]; shift[i] = g.stats[3 * g.C + c0 + i]; }
     }
   }
   const int64_t r0 = (int64_t)blockIdx.x * g.rows_per_block;
@@ -65,8 +67,8 @@ __global__ void __launch_bounds__(256) colreduce_kernel(RedArgs g) {
   if (active) {
     const T* a = static_cast<const T*>(g.a);
     const T* z = static_cast<const T*>(g.z);
-    const T* ao = static_cast<const T*>(g.aout);
-    const uint8_t* mk = MODE == RED_BN_BWD && V > 1 ? g.mask : nullptr;
+    const T* ao = MODE == RED_BN_BWD_AOUT ? static_cast<const T*>(g.aout) : nullptr;
+    const uint8_t* mk = MODE == RED_BN_BWD_MASK ? g.mask : nullptr;
     // one row's contribution, from values already in registers
     auto accumulate = [&](const float (&va)[V], const float (&vz)[V], const float (&vo)[V], unsigned bits) {
       if (MODE == RED_STATS) {
@@ -79,8 +81,9 @@ __global__ void __launch_bounds__(256) colreduce_kernel(RedArgs g) {
 #pragma unroll
         for (int i = 0; i < V; ++i) {
           bool on = true;
-          if (mk) on = (bits >> i) & 1u;
-          else if (g.relu) on = ao ? (vo[i] > 0.f) : (bn_affine(vz[i], scale[i], shift[i]) > 0.f);
+          if (MODE == RED_BN_BWD_MASK) on = (bits >> i) & 1u;
+          else if (MODE == RED_BN_BWD_AOUT) { if (g.relu) on = vo[i] > 0.f; }
+          else if (g.relu) on = bn_affine(vz[i], scale[i], shift[i]) > 0.f;
           const float dy = on ? va[i] : 0.f;
           const float xh = (vz[i] - mean[i]) * rstd[i];
           s0[i] += dy; s1[i] = __fmaf_rn(dy, xh, s1[i]);
@@ -97,10 +100,10 @@ __global__ void __launch_bounds__(256) colreduce_kernel(RedArgs g) {
       for (int u = 0; u < 4; ++u) {
         const int64_t off = (r + (int64_t)u * TY) * g.C + c0;
         load_f32<T, V>(a + off, va[u]);
-        if (MODE == RED_BN_BWD) {
+        if (BWD) {
           load_f32<T, V>(z + off, vz[u]);
-          if (mk) mb[u] = mk[(r + (int64_t)u * TY) * CG + cg];
-          else if (ao) load_f32<T, V>(ao + off, vo[u]);
+          if (MODE == RED_BN_BWD_MASK) mb[u] = mk[(r + (int64_t)u * TY) * CG + cg];
+          else if (MODE == RED_BN_BWD_AOUT) load_f32<T, V>(ao + off, vo[u]);
         }
       }
 #pragma unroll
@@ -111,10 +114,10 @@ __global__ void __launch_bounds__(256) colreduce_kernel(RedArgs g) {
       float va[V], vz[V], vo[V];
       unsigned mb = 0u;
       load_f32<T, V>(a + off, va);
-      if (MODE == RED_BN_BWD) {
+      if (BWD) {
         load_f32<T, V>(z + off, vz);
-        if (mk) mb = mk[r * CG + cg];
-        else if (ao) load_f32<T, V>(ao + off, vo);
+        if (MODE == RED_BN_BWD_MASK) mb = mk[r * CG + cg];
+        else if (MODE == RED_BN_BWD_AOUT) load_f32<T, V>(ao + off, vo);
       }
       accumulate(va, vz, vo, mb);
     }
@@ -748,7 +751,11 @@ void launch_bn_bwd(hipStream_t st, int dt, const void* da, const void* z, const 
                    void* dz, void* dskip) {
   RedArgs g{}; g.a = da; g.z = z; g.aout = aout; g.mask = (const uint8_t*)mask; g.stats = stats; g.partial = ws; g.rows = rows;
   g.C = C; g.relu = relu; g.nblk = nblk;
-  launch_colreduce<RED_BN_BWD>(st, dt, g);
+  // the same choice of the ReLU decisions' source as the apply kernel below makes
+  const int vmax = dt == DT_F32 ? 4 : 8;
+  if (mask && C % vmax == 0) launch_colreduce<RED_BN_BWD_MASK>(st, dt, g);
+  else if (aout) launch_colreduce<RED_BN_BWD_AOUT>(st, dt, g);
+  else launch_colreduce<RED_BN_BWD>(st, dt, g);
   float* coef = ws + (int64_t)nblk * 2 * C;
   OSEQ_LAUNCH(bn_bwd_finalize_kernel, dim3(ceil_div(C, 4)), dim3(256), 0, st, ws, nblk, C, (double)rows, dgamma,
                      dbeta, coef);
