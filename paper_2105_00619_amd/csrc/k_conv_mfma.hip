@@ -900,8 +900,11 @@ static void launch_patch(hipStream_t st, int dt, const void* src, const void* wm
 static constexpr int g_igemm_spread = 1;                         // compile-time switch
 constexpr size_t kSpreadLds = 84 * 1024;        // more than half of the 160 KB of LDS per CU
 
-// rows per block: 256 when that still gives every CU two blocks, else 128 (from the shape only)
-static int igemm_bm(int64_t M, int Ng) {
+// rows per block (from the shape only): fp32 256 when that still gives every CU two blocks, else 128.  The 16-bit
+// instantiation with 256 rows needs 348 registers (one wavefront per SIMD); with 128 rows two blocks share a CU and
+// the strided 3x3 layers of the bottleneck network at batch 4096 take 551 / 520 us instead of 716 / 646.
+static int igemm_bm(int dt, int64_t M, int Ng) {
+  if (dt != DT_F32) return 128;
   const int64_t cols = Ng / (Ng % 128 == 0 ? 128 : 64);
   return ((M + 255) / 256) * cols >= 512 ? 256 : 128;
 }
@@ -913,7 +916,7 @@ static void launch_igemm_t(hipStream_t st, const void* src, const void* wmat, co
   const int bk = Frag<T>::BK;
   a.kt_per_split = ceil_div(a.Kg / bk, splits);
   const bool wide = a.Ng % 128 == 0;
-  const int bm = splits > 1 ? 128 : igemm_bm(a.M, a.Ng);
+  const int bm = splits > 1 ? 128 : igemm_bm(sizeof(T) == 4 ? DT_F32 : DT_BF16, a.M, a.Ng);
   dim3 grid(ceil_div(a.M, bm), a.Ng / (wide ? 128 : 64), a.cls ? 4 : splits), block(256);  // cls: never split
   // A grid of at most one block per CU asks for more than half of a CU's LDS, so that no CU takes two blocks
   // while another idles.
@@ -998,7 +1001,7 @@ int conv_mfma_fwd_stat_blocks(int dt, const ConvGeom& g) {
   if (patch_pick(dt, g.N, g.P, g.Q, g.C, g.K, g.R, g.S, g.stride, pv, pa))
     return pv.splits > 1 ? ceil_div(M, SPLIT_EPI_ROWS) : (pa.NT + pv.subt - 1) / pv.subt;
   if (igemm_splits(dt, M, g.K, g.R * g.S * g.C) > 1) return ceil_div(M, SPLIT_EPI_ROWS);
-  return ceil_div(M, igemm_bm(M, g.K));
+  return ceil_div(M, igemm_bm(dt, M, g.K));
 }
 
 // stat_partial: null, or [conv_mfma_fwd_stat_blocks][2][C_out] floats receiving per-block sums and sums of squares
