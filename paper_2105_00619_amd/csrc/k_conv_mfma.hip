@@ -148,7 +148,7 @@ __global__ void __launch_bounds__(256) conv_igemm_kernel(const T* __restrict__ s
   T* lds = reinterpret_cast<T*>(smem_raw);
 
   // kernel arguments used inside the loaders, as plain scalars
-  const int srcH = a.srcH, srcW = a.srcW, srcC = a.srcC, S_ = a.S, stride = a.stride, pad = a.pad, Kg = a.Kg;
+  const int srcH = a.srcH, srcW = a.srcW, srcC = a.srcC, S_ = a.S, stride = a.stride, pad = a.pad;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1, g = lane >> 5, l32 = lane & 31;
   const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
@@ -900,14 +900,10 @@ static void launch_patch(hipStream_t st, int dt, const void* src, const void* wm
 static constexpr int g_igemm_spread = 1;                         // compile-time switch
 constexpr size_t kSpreadLds = 84 * 1024;        // more than half of the 160 KB of LDS per CU
 
-// rows per block (from the shape only): fp32 256 when that still gives every CU two blocks, else 128.  The 16-bit
-// instantiation with 256 rows needs 348 registers (one wavefront per SIMD); with 128 rows two blocks share a CU and
-// the strided 3x3 layers of the bottleneck network at batch 4096 take 551 / 520 us instead of 716 / 646.
-static int igemm_bm(int dt, int64_t M, int Ng) {
-  if (dt != DT_F32) return 128;
-  const int64_t cols = Ng / (Ng % 128 == 0 ? 128 : 64);
-  return ((M + 255) / 256) * cols >= 512 ? 256 : 128;
-}
+// Rows per block.  A 256-row tile was tried for layers with many pixels: it needs 348-380 registers, so one wavefront
+// per SIMD, where two 128-row blocks share a CU; the strided 3x3 layers of the bottleneck network at batch 4096 (bf16)
+// take 716 / 646 us with it and 551 / 520 without, the fp32 network on 512 x 512 images 166.4 against 163.2 ms a step.
+constexpr int IGEMM_BM = 128;
 
 template <class T, int MODE>
 static void launch_igemm_t(hipStream_t st, const void* src, const void* wmat, const float* bias, const void* addend, void* out,
@@ -916,8 +912,7 @@ static void launch_igemm_t(hipStream_t st, const void* src, const void* wmat, co
   const int bk = Frag<T>::BK;
   a.kt_per_split = ceil_div(a.Kg / bk, splits);
   const bool wide = a.Ng % 128 == 0;
-  const int bm = splits > 1 ? 128 : igemm_bm(sizeof(T) == 4 ? DT_F32 : DT_BF16, a.M, a.Ng);
-  dim3 grid(ceil_div(a.M, bm), a.Ng / (wide ? 128 : 64), a.cls ? 4 : splits), block(256);  // cls: never split
+  dim3 grid(ceil_div(a.M, IGEMM_BM), a.Ng / (wide ? 128 : 64), a.cls ? 4 : splits), block(256);  // cls: never split
   // A grid of at most one block per CU asks for more than half of a CU's LDS, so that no CU takes two blocks
   // while another idles.
   const bool spread = g_igemm_spread && (int64_t)grid.x * grid.y * grid.z <= 256;
@@ -937,8 +932,6 @@ static void launch_igemm_t(hipStream_t st, const void* src, const void* wmat, co
   if (splits > 1) {
     if (wide) IGEMM_LAUNCH(128, 128, true) else IGEMM_LAUNCH(128, 64, true)
     launch_splitk_epilogue<T>(st, partial, splits, a.M, a.Ng, bias, addend, a.amask, out, stat_partial, a.relu);
-  } else if (bm == 256) {
-    if (wide) IGEMM_LAUNCH(256, 128, false) else IGEMM_LAUNCH(256, 64, false)
   } else {
     if (wide) IGEMM_LAUNCH(128, 128, false) else IGEMM_LAUNCH(128, 64, false)
   }
@@ -1001,7 +994,7 @@ int conv_mfma_fwd_stat_blocks(int dt, const ConvGeom& g) {
   if (patch_pick(dt, g.N, g.P, g.Q, g.C, g.K, g.R, g.S, g.stride, pv, pa))
     return pv.splits > 1 ? ceil_div(M, SPLIT_EPI_ROWS) : (pa.NT + pv.subt - 1) / pv.subt;
   if (igemm_splits(dt, M, g.K, g.R * g.S * g.C) > 1) return ceil_div(M, SPLIT_EPI_ROWS);
-  return ceil_div(M, igemm_bm(dt, M, g.K));
+  return ceil_div(M, IGEMM_BM);
 }
 
 // stat_partial: null, or [conv_mfma_fwd_stat_blocks][2][C_out] floats receiving per-block sums and sums of squares
@@ -1204,7 +1197,7 @@ __global__ void __launch_bounds__(64 * WGM * WGN) conv_wgrad_kernel(const T* __r
   const int mbeg = bz * a.chunk;
   const int mend = mbeg + a.chunk < a.pixels ? mbeg + a.chunk : a.pixels;
   const int n = mend > mbeg ? (mend - mbeg + DEPTH - 1) / DEPTH : 0;
-  const int K = a.K, C = a.C, H = a.H, W = a.W, P = a.P, Q = a.Q, cstride = a.stride, pad = a.pad;
+  const int K = a.K, C = a.C, H = a.H, W = a.W, cstride = a.stride, pad = a.pad;
   const FastDiv divQ = a.divQ, divPQ = a.divPQ;
 
   // staging: 16-byte chunks, rows = pixels (EV elements per chunk)
