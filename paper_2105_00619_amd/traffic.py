@@ -41,8 +41,9 @@ GROUP_KERNELS = {
     "conv_wgrad": ("conv_wgrad3x3_kernel", "conv_wgrad_kernel", "conv_wgrad_smallc_kernel", "wgrad_reduce_kernel",
                    "wave_reduce_kernel", "conv_wgrad_direct_kernel", "splitk_reduce_kernel"),
     "bn_apply": ("bn_apply_kernel", "bn_apply_pool_kernel"),
-    # the reduction pass (colreduce_kernel in its BatchNorm-backward mode, template argument 1) and the apply pass
-    "bn_bwd": ("bn_bwd_apply_kernel", "bn_bwd_finalize_kernel", "bn_bwd_pool", "ELi1EEEvNS_7RedArgsE", ", 1>(oseq::RedArgs)"),
+    # the reduction pass (colreduce_kernel in its BatchNorm-backward modes, template arguments 1, 3 and 4) and the apply pass
+    "bn_bwd": ("bn_bwd_apply_kernel", "bn_bwd_finalize_kernel", "bn_bwd_pool", "ELi1EEEvNS_7RedArgsE", "ELi3EEEvNS_7RedArgsE",
+               "ELi4EEEvNS_7RedArgsE", ", 1>(oseq::RedArgs)", ", 3>(oseq::RedArgs)", ", 4>(oseq::RedArgs)"),
 }
 
 

@@ -94,7 +94,8 @@ LAYER_NETS = {
                                             W.conv(128, 128, ksize=1, bn=False), W.gap_linear_ce(128, 10)]),
     "pointwise_bottleneck_s2": (64, 32, 64, [W.conv(64, 64, ksize=1), W.bottleneck(64, 256, 2), W.gap_linear_ce(256, 10)]),
     # enough pixels for the 256 x 256 tile of that kernel (515 row tiles, the last one ragged): forward with and without
-    # BatchNorm sums, data gradient with 256 channels
+    # BatchNorm sums, data gradient with 256 channels; the first layer (depth 64, 256 channels) takes the
+    # weights-stationary forward kernel with one channel group
     "pointwise_large_tile": (64, 33, 121, [W.conv(64, 256, ksize=1), W.conv(256, 256, ksize=1), W.conv(256, 256, ksize=1, bn=False),
                                            W.gap_linear_ce(256, 10)]),
     # short depth, wide output, 519 row tiles of 128 (the last one ragged): the kernel that keeps its rows resident --
