@@ -90,16 +90,19 @@ __global__ void __launch_bounds__(256) colreduce_kernel(RedArgs g) {
         }
       }
     };
-    // four rows per trip while four remain: their loads are all issued before the first value is used, so a thread
-    // keeps 8-12 16-byte loads in flight; the rows are still added in the same order
+    // RT rows per trip while RT remain: their loads are all issued before the first value is used; the rows are still
+    // added in the same order.  (Two tensors per row in the BatchNorm-backward modes: two rows per trip measured as
+    // well as four or a little better, with fewer registers.)
+    constexpr int RT = BWD ? 2 : 4;
     int64_t r = r0 + ty;
-    for (; r + 3 * (int64_t)TY < r1; r += 4 * (int64_t)TY) {
-      float va[4][V], vz[4][V], vo[4][V];
-      unsigned mb[4] = {0u, 0u, 0u, 0u};
+    for (; r + (RT - 1) * (int64_t)TY < r1; r += RT * (int64_t)TY) {
+      float va[RT][V], vz[RT][V], vo[RT][V];
+      unsigned mb[RT];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
+      for (int u = 0; u < RT; ++u) {
         const int64_t off = (r + (int64_t)u * TY) * g.C + c0;
         load_f32<T, V>(a + off, va[u]);
+        mb[u] = 0u;
         if (BWD) {
           load_f32<T, V>(z + off, vz[u]);
           if (MODE == RED_BN_BWD_MASK) mb[u] = mk[(r + (int64_t)u * TY) * CG + cg];
@@ -107,7 +110,7 @@ __global__ void __launch_bounds__(256) colreduce_kernel(RedArgs g) {
         }
       }
 #pragma unroll
-      for (int u = 0; u < 4; ++u) accumulate(va[u], vz[u], vo[u], mb[u]);
+      for (int u = 0; u < RT; ++u) accumulate(va[u], vz[u], vo[u], mb[u]);
     }
     for (; r < r1; r += TY) {
       const int64_t off = r * g.C + c0;
@@ -284,7 +287,7 @@ __global__ void __launch_bounds__(256) bias_finalize_kernel(const float* __restr
 
 // ------------------------------------------------------------- BN apply -----
 // The backward apply kernel is tiled like the column reductions: a thread owns V consecutive channels, keeps their
-// per-channel constants in registers and walks the rows of its block (blockIdx.x) with stride TY, four rows per trip
+// per-channel constants in registers and walks the rows of its block (blockIdx.x) with stride TY, two rows per trip
 // with all loads of the trip issued before its first store (loads and stores share one in-order counter).  The
 // optional tensors are template parameters, so that each variant is straight-line code (also in the forward kernel).
 struct RowArgs {
@@ -403,22 +406,25 @@ __global__ void __launch_bounds__(256) bn_bwd_apply_kernel(const T* __restrict__
       rs[k] = dy;
     }
   };
+  // two rows per trip, all loads before the stores (four rows: 575 against 544 us for the whole backward of a block
+  // output at 262 144 x 1024, bf16; one row: 550)
+  constexpr int RT = 2;
   int64_t r = r0 + ty;
-  for (; r + 3 * (int64_t)TY < r1; r += 4 * (int64_t)TY) {
-    float va[4][V], vz[4][V], vo[4][V], rz[4][V], rs[4][V];
-    unsigned mb[4] = {0u, 0u, 0u, 0u};
+  for (; r + (RT - 1) * (int64_t)TY < r1; r += RT * (int64_t)TY) {
+    float va[RT][V], vz[RT][V], vo[RT][V], rz[RT][V], rs[RT][V];
+    unsigned mb[RT];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
+    for (int u = 0; u < RT; ++u) {
       const int64_t off = (r + (int64_t)u * TY) * g.C + c0;
       load_f32<T, V>(da + off, va[u]);
       load_f32<T, V>(z + off, vz[u]);
       if (AOUT) load_f32<T, V>(aout + off, vo[u]);
-      if (MS == 2) mb[u] = mask[(r + (int64_t)u * TY) * CG + cg];
+      mb[u] = MS == 2 ? mask[(r + (int64_t)u * TY) * CG + cg] : 0u;
     }
 #pragma unroll
-    for (int u = 0; u < 4; ++u) one(va[u], vz[u], vo[u], mb[u], rz[u], rs[u]);
+    for (int u = 0; u < RT; ++u) one(va[u], vz[u], vo[u], mb[u], rz[u], rs[u]);
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
+    for (int u = 0; u < RT; ++u) {
       const int64_t off = (r + (int64_t)u * TY) * g.C + c0;
       store_f32<T, V>(dz + off, rz[u]);
       if (DSKIP) store_f32<T, V>(dskip + off, rs[u]);
@@ -702,8 +708,8 @@ void launch_bn_stats_finalize(hipStream_t st, float* partial, int64_t rows, int 
                      eps, mom, gamma, beta, stats, running, flags);
 }
 
-// Row blocks of the apply kernels: sixteen rows per thread (four trips of four; the per-channel constants are fetched
-// once per block: 64.2 -> 62.9 ms per step for the class on the largest workload against one trip) when that still
+// Row blocks of the apply kernels: sixteen rows per thread (the per-channel constants are fetched once per block:
+// 64.2 -> 62.9 ms per step for the class on the largest workload against four rows per thread) when that still
 // leaves about four blocks per CU, else fewer (small tensors), from the shape only.
 static void row_tiling(int64_t rows, int C, int V, RowArgs& g, dim3& grid) {
   const int CG = C / V;
