@@ -3,8 +3,11 @@
 // The rows of X are whole pixels of the NHWC source (row(m) = m for stride 1; for a strided forward convolution the
 // pixel (2p, 2q) of the same image), W is the (C_out, C_in) weight matrix for forward and its (C_in, C_out) transpose
 // for the data gradient (of a stride-2 layer on an even image: the rows are the pixels of dz, each written to pixel
-// (2p, 2q) of dx, and the three other pixels of that 2x2 cell, which no filter tap reaches, are written as zero).  These layers move far more bytes per flop than the 3x3 ones (depth 64 to
-// 2048 only), so the kernel is built to keep HBM busy rather than the matrix cores:
+// (2p, 2q) of dx, and the three other pixels of that 2x2 cell, which no filter tap reaches, are written as zero).
+// Four kernels: conv1x1_kernel (below), conv1x1_large_kernel (256 x 256 tiles for layers with many pixels),
+// conv1x1_ws_kernel and conv1x1_rows_kernel (forward and data gradient of the short-depth wide layers).  These layers
+// move far more bytes per flop than the 3x3 ones (depth 64 to 2048 only), so conv1x1_kernel is built to keep HBM busy
+// rather than the matrix cores:
 //   * block = 256 threads = 4 wavefronts (2 x 2), tile 128 rows x BN channels (BN = 128 or 64), depth step 64 bytes;
 //     40 KB of LDS and at most 168 registers per lane, so three blocks share a CU and cover each other's load
 //     latency, barriers and epilogue;
@@ -640,7 +643,8 @@ conv1x1_rows_kernel(const T* __restrict__ X, const T* __restrict__ W, const T* _
 // Forward (conv1x1_ws_kernel), weights stationary: a block owns 256 output channels for its whole life -- every
 // wavefront keeps the weights of its 32 channels, all of their depth, in registers as MFMA operands (64 registers at
 // depth 256) -- and walks row tiles of 128 (depth 256: 64) pixels: a tile of X goes through LDS once (turned into
-// activations on the way if a BatchNorm is folded in) and is multiplied by all eight wavefronts (wave tile 128 x 32).
+// activations on the way if a BatchNorm is folded in) and is multiplied by all eight wavefronts (wave tile 128 x 32,
+// or 64 x 32).
 // Per tile nothing but X crosses from L2 to the CU.  256 blocks, one per CU; the blocks that share row tiles (one per
 // 256 channels) take consecutive slots of one XCD and move through the tiles together.  The next tile of X is requested
 // before the MFMAs of the current one and waits in registers.  Epilogue: bias / ReLU / rounding on the accumulators
