@@ -458,7 +458,7 @@ conv1x1_large_kernel(const T* __restrict__ X, const T* __restrict__ W, const flo
 // stream through two LDS stages of 128 bytes of depth from registers two steps ahead, the stream running on across
 // the column tiles, so that the loads of the next tile's first steps (and the next residual pieces) are in flight
 // while this tile's results are stored.  512 threads = 8 wavefronts (2 x 4), wave tile 64 x 64.  Epilogue of a column
-// tile with a residual: 32 rows at a time through LDS as fp32, the masked residual added before the rounding; without
+// tile with a residual: 64 rows at a time through LDS as fp32, the masked residual added before the rounding; without
 // one: rounded on the accumulators where they are, the rounded values through LDS as [128][256 + 8] elements; 16-byte
 // stores of whole rows either way.
 constexpr int PWR_BM = 128, PWR_BN = 256, PWR_BK = 64;
@@ -492,7 +492,7 @@ conv1x1_rows_kernel(const T* __restrict__ X, const T* __restrict__ W, const T* _
   constexpr int RPI = NT / CPR;        // rows between a thread's chunks
   constexpr int B_CH = BN * (BK / 8) / NT;  // chunks per thread of a weight stage (4)
   constexpr int BSTAGE = BN * PITCH;
-  constexpr int HR = 32;               // rows per pass of the residual-adding epilogue
+  constexpr int HR = 64;               // rows per pass of the residual-adding epilogue (a wavefront row)
   constexpr int EPITCH = BN + 8;       // row pitch of the rounded tile
   static_assert(NS == 2 || NS == 4, "depth 128 or 256");
   static_assert((size_t)BM * EPITCH * 2 <= (size_t)2 * BSTAGE * 2, "the rounded tile lies over the weight stages");
@@ -595,16 +595,18 @@ conv1x1_rows_kernel(const T* __restrict__ X, const T* __restrict__ W, const T* _
     __syncthreads();  // the weight stages are free: the epilogue tiles lie over them
 
     if (residual) {
-      // ---- 32 rows at a time as fp32 [32][BN + 4]; the residual pieces of a pass are requested a pass ahead ----
+      // ---- 64 rows at a time as fp32 [64][BN + 4]; the residual pieces of a pass are requested a pass ahead ----
 #pragma unroll
       for (int sp = 0; sp < BM / HR; ++sp) {
         if (sp) __syncthreads();
-        if (wm == sp / 2) {
+        if (wm == sp) {
 #pragma unroll
-          for (int jn = 0; jn < NI; ++jn)
+          for (int i = 0; i < MI; ++i)
 #pragma unroll
-            for (int e = 0; e < 16; ++e)
-              ep[(8 * (e >> 2) + 4 * g + (e & 3)) * (BN + 4) + wn * 64 + jn * 32 + l32] = acc[sp % 2][jn][e];
+            for (int jn = 0; jn < NI; ++jn)
+#pragma unroll
+              for (int e = 0; e < 16; ++e)
+                ep[(i * 32 + 8 * (e >> 2) + 4 * g + (e & 3)) * (BN + 4) + wn * 64 + jn * 32 + l32] = acc[i][jn][e];
         }
         __syncthreads();
         Vec<T, 8> ad[EPT];
