@@ -708,15 +708,16 @@ void launch_bn_stats_finalize(hipStream_t st, float* partial, int64_t rows, int 
                      eps, mom, gamma, beta, stats, running, flags);
 }
 
-// Row blocks of the apply kernels: sixteen rows per thread (the per-channel constants are fetched once per block:
-// 64.2 -> 62.9 ms per step for the class on the largest workload against four rows per thread) when that still
-// leaves about four blocks per CU, else fewer (small tensors), from the shape only.
+// Row blocks of the apply kernels: eight rows per thread (the per-channel constants are fetched once per block; with
+// two-row trips the whole backward of a block output at 262 144 x 1024, bf16, takes 556 / 543 / 532 / 545 / 575 us at
+// 32 / 16 / 8 / 4 / 2 rows) when that still leaves about four blocks per CU, else fewer (small tensors), from the
+// shape only.
 static void row_tiling(int64_t rows, int C, int V, RowArgs& g, dim3& grid) {
   const int CG = C / V;
   const int TX = CG < 256 ? CG : 256;
   const int TY = 256 / TX;
   const int ytiles = ceil_div(CG, TX);
-  int per_thread = 16;
+  int per_thread = 8;
   while (per_thread > 1 && (int64_t)ceil_div(rows, (int64_t)TY * per_thread) * ytiles < 1024) per_thread /= 2;
   g.rows = rows; g.C = C; g.rows_per_block = TY * per_thread;
   grid = dim3(ceil_div(rows, g.rows_per_block), ytiles);
