@@ -103,6 +103,8 @@ LAYER_NETS = {
     "pointwise_rows_128": (64, 33, 61, [W.conv(64, 512, ksize=1), W.bottleneck(512, 512, 1), W.gap_linear_ce(512, 10)]),
     "pointwise_rows_256": (64, 33, 61, [W.conv(64, 256, ksize=1), W.conv(256, 1024, ksize=1), W.conv(1024, 256, ksize=1),
                                         W.gap_linear_ce(256, 10)]),
+    # the weights-stationary forward kernel with a bias and no BatchNorm behind it (no sums), on a folded BatchNorm
+    "pointwise_rows_bias": (64, 33, 61, [W.conv(64, 128, ksize=1), W.conv(128, 512, ksize=1, bn=False), W.gap_linear_ce(512, 10)]),
     "pointwise_bottlenecks": (64, 16, 64, [W.conv(64, 64, ksize=1), W.bottleneck(64, 256, 1), W.bottleneck(256, 512, 2),
                                            W.gap_linear_ce(512, 10)]),
 }
@@ -112,7 +114,7 @@ LAYER_NETS = {
 @pytest.mark.parametrize("precision", [W.FP32, W.BF16, W.FP16])
 def test_layers_at_benchmark_shapes_match_oracle(name, precision):
     cin, hw, b, units = LAYER_NETS[name]
-    if precision == W.FP32 and name in ("pointwise_large_tile", "pointwise_rows_128", "pointwise_rows_256"):
+    if precision == W.FP32 and name in ("pointwise_large_tile", "pointwise_rows_128", "pointwise_rows_256", "pointwise_rows_bias"):
         pytest.skip("the kernel this case is for exists in the 16-bit modes only")
     p, x, y = _inputs(units, b, hw, hw, 10, seed=9, channels=cin)
     r, info = gpu_step(units, p, x, y, precision=precision, k=2, classes=10, loss_scale_init=_scale(precision))
