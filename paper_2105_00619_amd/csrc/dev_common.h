@@ -20,6 +20,17 @@ template <> __device__ __forceinline__ float from_f32<float>(float v) { return v
 template <> __device__ __forceinline__ f16_t from_f32<f16_t>(float v) { return (f16_t)v; }    // round to nearest even
 template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float v) { return (bf16_t)v; }  // round to nearest even
 
+// Two floats rounded (to nearest even) into a pair of 16-bit values in one register: one packed conversion instead of
+// two conversions and a merge.
+typedef __attribute__((ext_vector_type(2))) float f32x2_t;
+template <class T> struct Pair16;
+template <> struct Pair16<f16_t> { typedef __attribute__((ext_vector_type(2))) _Float16 V; };
+template <> struct Pair16<bf16_t> { typedef __attribute__((ext_vector_type(2))) __bf16 V; };
+template <class T> __device__ __forceinline__ typename Pair16<T>::V from_f32x2(float a, float b) {
+  const f32x2_t v = {a, b};
+  return __builtin_convertvector(v, typename Pair16<T>::V);
+}
+
 // V consecutive elements of T, loaded and stored as one access.
 template <class T, int V>
 struct alignas(sizeof(T) * V) Vec {
@@ -35,8 +46,16 @@ __device__ __forceinline__ void load_f32(const T* p, float (&out)[V]) {
 template <class T, int V>
 __device__ __forceinline__ void store_f32(T* p, const float (&in)[V]) {
   Vec<T, V> t;
+  if constexpr (sizeof(T) == 2 && V % 2 == 0) {
 #pragma unroll
-  for (int i = 0; i < V; ++i) t.v[i] = from_f32<T>(in[i]);
+    for (int i = 0; i < V; i += 2) {
+      const typename Pair16<T>::V q = from_f32x2<T>(in[i], in[i + 1]);
+      t.v[i] = q[0]; t.v[i + 1] = q[1];
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < V; ++i) t.v[i] = from_f32<T>(in[i]);
+  }
   *reinterpret_cast<Vec<T, V>*>(p) = t;
 }
 

@@ -724,8 +724,13 @@ conv1x1_ws_kernel(const T* __restrict__ X, const T* __restrict__ W, const float*
       float sc[8], sh[8];
       load_f32<float, 8>(ftab + cc * 8, sc);
       load_f32<float, 8>(ftab + KD + cc * 8, sh);
+      if (a.fold_relu) {  // one branch per tile
 #pragma unroll
-      for (int i = 0; i < A_CH; ++i) ra[i] = bn_fold_chunk<T>(ra[i], sc, sh, a.fold_relu);
+        for (int i = 0; i < A_CH; ++i) ra[i] = bn_fold_chunk_t<T, true>(ra[i], sc, sh);
+      } else {
+#pragma unroll
+        for (int i = 0; i < A_CH; ++i) ra[i] = bn_fold_chunk_t<T, false>(ra[i], sc, sh);
+      }
     }
 #pragma unroll
     for (int i = 0; i < A_CH; ++i) *reinterpret_cast<Chunk*>(&abuf[(r0 + i * RPI) * APITCH + cc * 8]) = ra[i];
@@ -758,26 +763,33 @@ conv1x1_ws_kernel(const T* __restrict__ X, const T* __restrict__ W, const float*
 
     const int64_t m0 = (int64_t)t * BM;
     const bool ragged = m0 + BM > a.M;
-    float s1 = 0.f, s2 = 0.f;
+    // the ReLU flag and whether the tile has rows past the last pixel are the same for the whole block: one branch
+    // per tile picks the straight-line variant, instead of selects and compares per element
+    auto round_tile = [&](auto RELU, auto RAGGED) {
+      constexpr bool rag = decltype(RAGGED)::value != 0;
+      const bool relu = decltype(RELU)::value == 2 ? a.relu != 0 : decltype(RELU)::value != 0;
+      float s1 = 0.f, s2 = 0.f;
 #pragma unroll
-    for (int i = 0; i < MI; ++i)
+      for (int i = 0; i < MI; ++i)
 #pragma unroll
-      for (int e = 0; e < 16; e += 2) {
-        const int r = i * 32 + 8 * (e >> 2) + 4 * g + (e & 3);  // and r + 1
-        float v0 = acc[i][e] + bj, v1 = acc[i][e + 1] + bj;
-        if (a.relu) { v0 = fmaxf(v0, 0.f); v1 = fmaxf(v1, 0.f); }
-        if (ragged) {  // rows past the last pixel count as zero
-          if (m0 + r >= a.M) v0 = 0.f;
-          if (m0 + r + 1 >= a.M) v1 = 0.f;
+        for (int e = 0; e < 16; e += 2) {
+          const int r = i * 32 + 8 * (e >> 2) + 4 * g + (e & 3);  // and r + 1
+          float v0 = acc[i][e] + bj, v1 = acc[i][e + 1] + bj;
+          if (relu) { v0 = fmaxf(v0, 0.f); v1 = fmaxf(v1, 0.f); }
+          if (rag) {  // rows past the last pixel count as zero
+            if (m0 + r >= a.M) v0 = 0.f;
+            if (m0 + r + 1 >= a.M) v1 = 0.f;
+          }
+          const T2 p2 = from_f32x2<T>(v0, v1);
+          s1 = Dot2<T>::run(p2, one2, s1);
+          s2 = Dot2<T>::run(p2, p2, s2);
+          stg[r * EPITCH + cj] = p2[0];
+          stg[(r + 1) * EPITCH + cj] = p2[1];
         }
-        T2 p2;
-        p2[0] = from_f32<T>(v0); p2[1] = from_f32<T>(v1);
-        s1 = Dot2<T>::run(p2, one2, s1);
-        s2 = Dot2<T>::run(p2, p2, s2);
-        stg[r * EPITCH + cj] = p2[0];
-        stg[(r + 1) * EPITCH + cj] = p2[1];
-      }
-    S1 += s1; S2 += s2;
+      S1 += s1; S2 += s2;
+    };
+    if (ragged) round_tile(IC<2>{}, IC<1>{});
+    else round_tile(IC<2>{}, IC<0>{});
     __syncthreads();
 #pragma unroll
     for (int it = 0; it < BM * (BN / 8) / NT; ++it) {
