@@ -43,8 +43,9 @@ __device__ __forceinline__ void load_f32(const T* p, float (&out)[V]) {
 #pragma unroll
   for (int i = 0; i < V; ++i) out[i] = to_f32(t.v[i]);
 }
+// V floats rounded to T (16-bit types: pairwise, one packed conversion per pair)
 template <class T, int V>
-__device__ __forceinline__ void store_f32(T* p, const float (&in)[V]) {
+__device__ __forceinline__ Vec<T, V> round_vec(const float (&in)[V]) {
   Vec<T, V> t;
   if constexpr (sizeof(T) == 2 && V % 2 == 0) {
 #pragma unroll
@@ -56,7 +57,11 @@ __device__ __forceinline__ void store_f32(T* p, const float (&in)[V]) {
 #pragma unroll
     for (int i = 0; i < V; ++i) t.v[i] = from_f32<T>(in[i]);
   }
-  *reinterpret_cast<Vec<T, V>*>(p) = t;
+  return t;
+}
+template <class T, int V>
+__device__ __forceinline__ void store_f32(T* p, const float (&in)[V]) {
+  *reinterpret_cast<Vec<T, V>*>(p) = round_vec<T, V>(in);
 }
 
 // 16 bytes held in registers between a global load and an LDS store (a plain vector type: arrays of it stay in

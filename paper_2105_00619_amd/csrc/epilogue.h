@@ -74,9 +74,7 @@ __device__ __forceinline__ void epi_store_rows_nt(const float* ep, int tid, int 
 #pragma unroll
       for (int k = 0; k < 8; ++k) v[k] = fmaxf(v[k], 0.f);
     }
-    Vec<T, 8> t;
-#pragma unroll
-    for (int k = 0; k < 8; ++k) t.v[k] = from_f32<T>(v[k]);
+    const Vec<T, 8> t = round_vec<T, 8>(v);
     if (ro[it] >= 0) *reinterpret_cast<Vec<T, 8>*>(out + ro[it] + col) = t;
     if (STAT) {
 #pragma unroll
@@ -126,12 +124,9 @@ __device__ __forceinline__ void epi_store_rows_pre_nt(const float* ep, int tid, 
     const epi_v4f x0 = *reinterpret_cast<const epi_v4f*>(&ep[row * EP_PITCH + c8]);
     const epi_v4f x1 = *reinterpret_cast<const epi_v4f*>(&ep[row * EP_PITCH + c8 + 4]);
     float v[8] = {x0[0], x0[1], x0[2], x0[3], x1[0], x1[1], x1[2], x1[3]};
-    Vec<T, 8> t;
 #pragma unroll
-    for (int k = 0; k < 8; ++k) {
-      v[k] += ((mb[it] >> k) & 1u) ? to_f32(ad[it].v[k]) : 0.f;
-      t.v[k] = from_f32<T>(v[k]);
-    }
+    for (int k = 0; k < 8; ++k) v[k] += ((mb[it] >> k) & 1u) ? to_f32(ad[it].v[k]) : 0.f;
+    const Vec<T, 8> t = round_vec<T, 8>(v);
     if (ro >= 0) *reinterpret_cast<Vec<T, 8>*>(out + ro + col) = t;
   }
 }

@@ -625,8 +625,12 @@ conv1x1_rows_kernel(const T* __restrict__ X, const T* __restrict__ W, const T* _
 #pragma unroll
         for (int i = 0; i < MI; ++i)
 #pragma unroll
-          for (int e = 0; e < 16; ++e)
-            stg[(wm * 64 + i * 32 + 8 * (e >> 2) + 4 * g + (e & 3)) * EPITCH + cj] = from_f32<T>(acc[i][jn][e]);
+          for (int e = 0; e < 16; e += 2) {  // rows r and r + 1: one packed conversion
+            const int r = wm * 64 + i * 32 + 8 * (e >> 2) + 4 * g + (e & 3);
+            const typename Pair16<T>::V q = from_f32x2<T>(acc[i][jn][e], acc[i][jn][e + 1]);
+            stg[r * EPITCH + cj] = q[0];
+            stg[(r + 1) * EPITCH + cj] = q[1];
+          }
       }
       __syncthreads();
       constexpr int SPT = BM * (BN / 8) / NT;  // 16-byte pieces per thread
