@@ -31,6 +31,17 @@ template <class T> __device__ __forceinline__ typename Pair16<T>::V from_f32x2(f
   return __builtin_convertvector(v, typename Pair16<T>::V);
 }
 
+// sum of the two products of a pair of 16-bit values, added to c in fp32 (one instruction)
+template <class T> struct Dot2;
+template <> struct Dot2<bf16_t> {
+  typedef __attribute__((ext_vector_type(2))) __bf16 V;
+  __device__ static __forceinline__ float run(V a, V b, float c) { return __builtin_amdgcn_fdot2_f32_bf16(a, b, c, false); }
+};
+template <> struct Dot2<f16_t> {
+  typedef __attribute__((ext_vector_type(2))) _Float16 V;
+  __device__ static __forceinline__ float run(V a, V b, float c) { return __builtin_amdgcn_fdot2(a, b, c, false); }
+};
+
 // V consecutive elements of T, loaded and stored as one access.
 template <class T, int V>
 struct alignas(sizeof(T) * V) Vec {

@@ -54,6 +54,8 @@ __device__ __forceinline__ void epi_store_rows_nt(const float* ep, int tid, int 
       }
     }
   }
+  constexpr bool PAIRS = sizeof(T) == 2 && PER_THREAD % 2 == 0;
+  Vec<T, 8> tv[STAT && PAIRS ? PER_THREAD : 1];
   // straight-line code for all rows (only the store is predicated), so that the LDS reads of the later rows are issued
   // while the earlier ones are converted
 #pragma unroll
@@ -76,13 +78,32 @@ __device__ __forceinline__ void epi_store_rows_nt(const float* ep, int tid, int 
     }
     const Vec<T, 8> t = round_vec<T, 8>(v);
     if (ro[it] >= 0) *reinterpret_cast<Vec<T, 8>*>(out + ro[it] + col) = t;
-    if (STAT) {
+    if constexpr (STAT && PAIRS) {
+      tv[it] = t;
+      if (ro[it] < 0) tv[it] = Vec<T, 8>{};  // a row that is not stored counts as zero
+    } else if (STAT) {
 #pragma unroll
       for (int k = 0; k < 8; ++k) {
         const float r = ro[it] >= 0 ? to_f32(t.v[k]) : 0.f;
         ss[k] += r; qq[k] = __fmaf_rn(r, r, qq[k]);
       }
     }
+  }
+  // 16-bit types: two rows of a channel as one pair, its sum and its sum of squares one dot-product instruction each
+  // (exact products, fp32 sum) instead of four operations per element
+  if constexpr (STAT && PAIRS) {
+    typedef typename Dot2<T>::V T2;
+    T2 one2;
+    one2[0] = from_f32<T>(1.f); one2[1] = from_f32<T>(1.f);
+#pragma unroll
+    for (int it = 0; it < PER_THREAD; it += 2)
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        T2 p2;
+        p2[0] = tv[it].v[k]; p2[1] = tv[it + 1].v[k];
+        ss[k] = Dot2<T>::run(p2, one2, ss[k]);
+        qq[k] = Dot2<T>::run(p2, p2, qq[k]);
+      }
   }
 }
 

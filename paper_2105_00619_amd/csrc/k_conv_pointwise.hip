@@ -468,17 +468,6 @@ template <int KD> constexpr size_t pwr_smem_bytes() {
   return (size_t)2 * PWR_BN * PWR_PITCH * 2 + (size_t)PWR_BM * (KD + 8) * 2;
 }
 
-// sum of the two products of a pair of 16-bit values, added to c in fp32 (one instruction)
-template <class T> struct Dot2;
-template <> struct Dot2<bf16_t> {
-  typedef __attribute__((ext_vector_type(2))) __bf16 V;
-  __device__ static __forceinline__ float run(V a, V b, float c) { return __builtin_amdgcn_fdot2_f32_bf16(a, b, c, false); }
-};
-template <> struct Dot2<f16_t> {
-  typedef __attribute__((ext_vector_type(2))) _Float16 V;
-  __device__ static __forceinline__ float run(V a, V b, float c) { return __builtin_amdgcn_fdot2(a, b, c, false); }
-};
-
 template <class T, int KD>
 __global__ void __launch_bounds__(512)
 conv1x1_rows_kernel(const T* __restrict__ X, const T* __restrict__ W, const T* __restrict__ addend, T* __restrict__ out,
