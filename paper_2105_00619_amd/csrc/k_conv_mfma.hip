@@ -1176,7 +1176,11 @@ constexpr size_t wgrad_lds_bytes() {
   return (size_t)3 * (sizeof(T) == 4 ? 16 : 32) * (BM + BN + 2 * (sizeof(T) == 4 ? 4 : 16)) * sizeof(T);
 }
 
-template <class T, int BM, int BN, int WGM = 2, int WGN = 2, bool FOLD = false>
+// PW: a 1x1 layer with unit stride and no padding -- pixel m of x is row m, as it is of dz; the loads of a depth tile
+// are then one uniform base per tensor plus per-thread offsets that never change (the general path divides every
+// pixel index into image, row and column and multiplies it back into an address, a few dozen quarter-rate integer
+// multiplies per depth tile that the 256 x 256 tile, with one block per CU, has nobody to hide behind).
+template <class T, int BM, int BN, int WGM = 2, int WGN = 2, bool FOLD = false, bool PW = false>
 __global__ void __launch_bounds__(64 * WGM * WGN) conv_wgrad_kernel(const T* __restrict__ x, const T* __restrict__ dz,
                                                                     float* __restrict__ out, WGradArgs a) {
   constexpr bool F32 = sizeof(T) == 4;
@@ -1233,10 +1237,46 @@ __global__ void __launch_bounds__(64 * WGM * WGN) conv_wgrad_kernel(const T* __r
     off = ok ? (((int64_t)n_ * H + ih) * W + iw) * C : 0;
     return ok;
   };
-  auto gload = [&](auto G, int t) {
+  // PW: element offsets of a thread's pieces from the first row of a depth tile
+  int offa[PW ? A_CH32 : 1], offb[PW ? B_CH32 : 1];
+  if constexpr (PW) {
+#pragma unroll
+    for (int i = 0; i < A_CH32; ++i) {
+      const int id = tid + i * NT, px = id / (BM / EV), kv = id % (BM / EV);
+      offa[i] = px * K + k0 + kv * EV;
+    }
+#pragma unroll
+    for (int i = 0; i < B_CH32; ++i) {
+      const int id = tid + i * NT, px = id / (BN / EV), cv = id % (BN / EV);
+      offb[i] = px * C + c0 + cv * EV;
+    }
+  }
+  // CHK = 0: the tile is known to lie inside the range (every tile but a range's last one)
+  auto gload = [&](auto G, auto CHKC, int t) {
     constexpr int p = decltype(G)::value;
+    constexpr bool CHK = decltype(CHKC)::value != 0;
     const int mt = mbeg + t * DEPTH;
     unsigned ma = 0u, mb = 0u;
+    if constexpr (PW) {
+      const T* dzt = dz + (int64_t)mt * K;
+      const T* xt = x + (int64_t)mt * C;
+#pragma unroll
+      for (int i = 0; i < A_CH32; ++i) {
+        const int px = (tid + i * NT) / (BM / EV);
+        const bool ok = !CHK || mt + px < mend;  // a row past the range reads the same piece of the range's first row
+        ra[p][i] = *reinterpret_cast<const Chunk*>(ok ? dzt + offa[i] : dz + (int64_t)mbeg * K + (offa[i] - px * K));
+        ma |= ok ? (1u << i) : 0u;
+      }
+#pragma unroll
+      for (int i = 0; i < B_CH32; ++i) {
+        const int px = (tid + i * NT) / (BN / EV);
+        const bool ok = !CHK || mt + px < mend;
+        rb[p][i] = *reinterpret_cast<const Chunk*>(ok ? xt + offb[i] : x + (int64_t)mbeg * C + (offb[i] - px * C));
+        mb |= ok ? (1u << i) : 0u;
+      }
+      va[p] = ma; vb[p] = mb;
+      return;
+    }
 #pragma unroll
     for (int i = 0; i < A_CH32; ++i) {
       const int id = tid + i * NT, px = id / (BM / EV), kv = id % (BM / EV);
@@ -1267,8 +1307,10 @@ __global__ void __launch_bounds__(64 * WGM * WGN) conv_wgrad_kernel(const T* __r
     load_f32<float, EV>(a.fold + 2 * C + c0 + cv * EV, fsc);
     load_f32<float, EV>(a.fold + 3 * C + c0 + cv * EV, fsh);
   }
-  auto sstore = [&](auto G, int stage) {
+  // FULL (PW only): every piece of the tile is known to be valid
+  auto sstore = [&](auto G, auto FULLC, int stage) {
     constexpr int p = decltype(G)::value;
+    constexpr bool FULL = PW && decltype(FULLC)::value != 0;
     T* sa = lds + stage * STAGE;
     T* sb = sa + A_ELEMS;
     if (FOLD) {
@@ -1278,12 +1320,12 @@ __global__ void __launch_bounds__(64 * WGM * WGN) conv_wgrad_kernel(const T* __r
 #pragma unroll
     for (int i = 0; i < A_CH32; ++i) {
       const int id = tid + i * NT, px = id / (BM / EV), kv = id % (BM / EV);
-      *reinterpret_cast<Chunk*>(&sa[px * (BM + PADE) + kv * EV]) = ((va[p] >> i) & 1u) ? ra[p][i] : zero_chunk();
+      *reinterpret_cast<Chunk*>(&sa[px * (BM + PADE) + kv * EV]) = (FULL || ((va[p] >> i) & 1u)) ? ra[p][i] : zero_chunk();
     }
 #pragma unroll
     for (int i = 0; i < B_CH32; ++i) {
       const int id = tid + i * NT, px = id / (BN / EV), cv = id % (BN / EV);
-      *reinterpret_cast<Chunk*>(&sb[px * (BN + PADE) + cv * EV]) = ((vb[p] >> i) & 1u) ? rb[p][i] : zero_chunk();
+      *reinterpret_cast<Chunk*>(&sb[px * (BN + PADE) + cv * EV]) = (FULL || ((vb[p] >> i) & 1u)) ? rb[p][i] : zero_chunk();
     }
   };
 
@@ -1352,9 +1394,9 @@ __global__ void __launch_bounds__(64 * WGM * WGN) conv_wgrad_kernel(const T* __r
   };
 
   // pipeline as in the forward kernel: three LDS stages, two register generations, operand reload under the MFMAs
-  if (n > 0) { gload(IC<0>{}, 0); sstore(IC<0>{}, 0); }
-  if (n > 1) { gload(IC<1>{}, 1); sstore(IC<1>{}, 1); }
-  if (n > 2) gload(IC<0>{}, 2);
+  if (n > 0) { gload(IC<0>{}, IC<1>{}, 0); sstore(IC<0>{}, IC<0>{}, 0); }
+  if (n > 1) { gload(IC<1>{}, IC<1>{}, 1); sstore(IC<1>{}, IC<0>{}, 1); }
+  if (n > 2) gload(IC<0>{}, IC<1>{}, 2);
   __syncthreads();
   if (n > 0) { load_half(0, 0); load_half(1, 0); }
   auto body = [&](auto G, auto TAILC, int j, int stage) {
@@ -1362,7 +1404,8 @@ __global__ void __launch_bounds__(64 * WGM * WGN) conv_wgrad_kernel(const T* __r
     constexpr bool TAIL = decltype(TAILC)::value != 0;  // 0: steady state without range checks
     const int nstage = stage == 2 ? 0 : stage + 1;
     const bool has_next = TAIL ? j + 1 < n : true;
-    if (!TAIL || j + 3 < n) gload(IC<1 - p>{}, j + 3);
+    // steady state (j + 4 < n): tiles j + 2 and j + 3 are not the range's last one, all of their rows are inside it
+    if (!TAIL || j + 3 < n) gload(IC<1 - p>{}, IC<TAIL ? 1 : 0>{}, j + 3);
     mma_half(0);
     __builtin_amdgcn_sched_barrier(0);
     if (has_next) load_half(0, nstage);
@@ -1370,7 +1413,7 @@ __global__ void __launch_bounds__(64 * WGM * WGN) conv_wgrad_kernel(const T* __r
     mma_half(1);
     __builtin_amdgcn_sched_barrier(0);
     if (has_next) load_half(1, nstage);
-    if (!TAIL || j + 2 < n) sstore(G, stage == 0 ? 2 : stage - 1);
+    if (!TAIL || j + 2 < n) sstore(G, IC<TAIL ? 0 : 1>{}, stage == 0 ? 2 : stage - 1);
     __syncthreads();
   };
   {
@@ -1471,11 +1514,18 @@ static void launch_wgrad_t(hipStream_t st, const void* x, const void* dz, float*
       constexpr size_t sm = wgrad_lds_bytes<T, 256, 256, 2>();
       static bool attr_done = false;
       if (!attr_done) {
-        (void)hipFuncSetAttribute((const void*)conv_wgrad_kernel<T, 256, 256, 2, 4, FOLD>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sm);
+        (void)hipFuncSetAttribute((const void*)conv_wgrad_kernel<T, 256, 256, 2, 4, FOLD, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sm);
+        (void)hipFuncSetAttribute((const void*)conv_wgrad_kernel<T, 256, 256, 2, 4, FOLD, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sm);
         attr_done = true;
       }
-      OSEQ_LAUNCH((conv_wgrad_kernel<T, 256, 256, 2, 4, FOLD>), dim3(g.K / 256, g.C / 256, gz), dim3(512), sm, st, (const T*)x,
-                  (const T*)dz, dst, a);
+      // rows of x = pixels of dz, and the row offsets fit 32 bits
+      const bool pw = g.stride == 1 && g.pad == 0 && (int64_t)32 * std::max(g.K, g.C) < (1 << 30);
+      if (pw)
+        OSEQ_LAUNCH((conv_wgrad_kernel<T, 256, 256, 2, 4, FOLD, true>), dim3(g.K / 256, g.C / 256, gz), dim3(512), sm, st, (const T*)x,
+                    (const T*)dz, dst, a);
+      else
+        OSEQ_LAUNCH((conv_wgrad_kernel<T, 256, 256, 2, 4, FOLD, false>), dim3(g.K / 256, g.C / 256, gz), dim3(512), sm, st, (const T*)x,
+                    (const T*)dz, dst, a);
       return;
     }
   }
