@@ -1532,10 +1532,20 @@ static void launch_wgrad_t(hipStream_t st, const void* x, const void* dz, float*
   const bool m128 = g.K % 128 == 0, n128 = g.C % 128 == 0;
   const int bm = m128 ? 128 : 64, bn = n128 ? 128 : 64;
   dim3 grid(g.K / bm, g.R * g.S * (g.C / bn), gz), block(256);
-  if (m128 && n128) OSEQ_LAUNCH((conv_wgrad_kernel<T, 128, 128, 2, 2, FOLD>), grid, block, (wgrad_lds_bytes<T, 128, 128, 2>()), st, (const T*)x, (const T*)dz, dst, a);
-  else if (m128) OSEQ_LAUNCH((conv_wgrad_kernel<T, 128, 64, 2, 2, FOLD>), grid, block, (wgrad_lds_bytes<T, 128, 64, 2>()), st, (const T*)x, (const T*)dz, dst, a);
-  else if (n128) OSEQ_LAUNCH((conv_wgrad_kernel<T, 64, 128, 2, 2, FOLD>), grid, block, (wgrad_lds_bytes<T, 64, 128, 2>()), st, (const T*)x, (const T*)dz, dst, a);
-  else OSEQ_LAUNCH((conv_wgrad_kernel<T, 64, 64, 2, 2, FOLD>), grid, block, (wgrad_lds_bytes<T, 64, 64, 2>()), st, (const T*)x, (const T*)dz, dst, a);
+  // 1x1, unit stride, no padding: rows of x = pixels of dz, and the row offsets fit 32 bits
+  const bool pw = g.R * g.S == 1 && g.stride == 1 && g.pad == 0 && (int64_t)32 * std::max(g.K, g.C) < (1 << 30);
+#define WGRAD_LAUNCH(BM_, BN_)                                                                                              \
+  {                                                                                                                         \
+    if (pw) OSEQ_LAUNCH((conv_wgrad_kernel<T, BM_, BN_, 2, 2, FOLD, true>), grid, block, (wgrad_lds_bytes<T, BM_, BN_, 2>()), st, \
+                        (const T*)x, (const T*)dz, dst, a);                                                                 \
+    else OSEQ_LAUNCH((conv_wgrad_kernel<T, BM_, BN_, 2, 2, FOLD, false>), grid, block, (wgrad_lds_bytes<T, BM_, BN_, 2>()), st,  \
+                     (const T*)x, (const T*)dz, dst, a);                                                                    \
+  }
+  if (m128 && n128) WGRAD_LAUNCH(128, 128)
+  else if (m128) WGRAD_LAUNCH(128, 64)
+  else if (n128) WGRAD_LAUNCH(64, 128)
+  else WGRAD_LAUNCH(64, 64)
+#undef WGRAD_LAUNCH
 }
 
 // out[i] = sum over pixel ranges s of partial[s][i], in a fixed order: G groups of threads each add the ranges

@@ -697,12 +697,21 @@ conv1x1_ws_kernel(const T* __restrict__ X, const T* __restrict__ W, const float*
 
   const int cc = tid % CPR, r0 = tid / CPR;
   Chunk ra[A_CH];
-  // rows past the last pixel read row 0 (never stored, nothing added to the sums)
+  // A tile's loads: one base for the block plus offsets that are the same for every tile; only the last tile can have
+  // rows past the last pixel, which read row 0 (never stored, nothing added to the sums)
+  const int xoff = r0 * KD + cc * 8;
   auto gload = [&](int t) {
+    const int64_t m0t = (int64_t)t * BM;
+    if (m0t + BM <= a.M) {
+      const T* Xt = X + m0t * KD;
 #pragma unroll
-    for (int i = 0; i < A_CH; ++i) {
-      const int64_t m = (int64_t)t * BM + r0 + i * RPI;
-      ra[i] = *reinterpret_cast<const Chunk*>(X + (m < a.M ? m : 0) * KD + cc * 8);
+      for (int i = 0; i < A_CH; ++i) ra[i] = *reinterpret_cast<const Chunk*>(Xt + (xoff + i * (RPI * KD)));
+    } else {
+#pragma unroll
+      for (int i = 0; i < A_CH; ++i) {
+        const int64_t m = m0t + r0 + i * RPI;
+        ra[i] = *reinterpret_cast<const Chunk*>(X + (m < a.M ? m : 0) * KD + cc * 8);
+      }
     }
   };
   const int afrag = l32 * APITCH + g * 16;
@@ -756,18 +765,19 @@ conv1x1_ws_kernel(const T* __restrict__ X, const T* __restrict__ W, const float*
 
     const int64_t m0 = (int64_t)t * BM;
     const bool ragged = m0 + BM > a.M;
-    // the ReLU flag and whether the tile has rows past the last pixel are the same for the whole block: one branch
-    // per tile picks the straight-line variant, instead of selects and compares per element
-    auto round_tile = [&](auto RELU, auto RAGGED) {
-      constexpr bool rag = decltype(RAGGED)::value != 0;
-      const bool relu = decltype(RELU)::value == 2 ? a.relu != 0 : decltype(RELU)::value != 0;
+    // whether the tile has rows past the last pixel is the same for the whole block: one branch per tile picks the
+    // straight-line variant, instead of compares and selects per element
+    auto round_tile = [&](auto GENERAL, auto RAGGED) {
+      constexpr bool rag = decltype(RAGGED)::value != 0, general = decltype(GENERAL)::value != 0;
+      const bool relu = general && a.relu != 0;
       float s1 = 0.f, s2 = 0.f;
 #pragma unroll
       for (int i = 0; i < MI; ++i)
 #pragma unroll
         for (int e = 0; e < 16; e += 2) {
           const int r = i * 32 + 8 * (e >> 2) + 4 * g + (e & 3);  // and r + 1
-          float v0 = acc[i][e] + bj, v1 = acc[i][e + 1] + bj;
+          float v0 = acc[i][e], v1 = acc[i][e + 1];
+          if (general) { v0 += bj; v1 += bj; }
           if (relu) { v0 = fmaxf(v0, 0.f); v1 = fmaxf(v1, 0.f); }
           if (rag) {  // rows past the last pixel count as zero
             if (m0 + r >= a.M) v0 = 0.f;
@@ -781,14 +791,21 @@ conv1x1_ws_kernel(const T* __restrict__ X, const T* __restrict__ W, const float*
         }
       S1 += s1; S2 += s2;
     };
-    if (ragged) round_tile(IC<2>{}, IC<1>{});
-    else round_tile(IC<2>{}, IC<0>{});
+    // a convolution in front of a BatchNorm has neither bias nor ReLU: its tiles (but a ragged last one) take the
+    // version without either
+    if (ragged) round_tile(IC<1>{}, IC<1>{});
+    else if (bias || a.relu) round_tile(IC<1>{}, IC<0>{});
+    else round_tile(IC<0>{}, IC<0>{});
     __syncthreads();
+    {
+      T* ot = out + m0 * a.Ng + n0;  // the tile's first row at the block's first channel: the same for every thread
+      const int ooff = erow * a.Ng + c8, ostep = (NT / (BN / 8)) * a.Ng;
 #pragma unroll
-    for (int it = 0; it < BM * (BN / 8) / NT; ++it) {
-      const int row = erow + it * (NT / (BN / 8));
-      const Chunk c = *reinterpret_cast<const Chunk*>(&stg[row * EPITCH + c8]);
-      if (!ragged || m0 + row < a.M) *reinterpret_cast<Chunk*>(out + (m0 + row) * a.Ng + n0 + c8) = c;
+      for (int it = 0; it < BM * (BN / 8) / NT; ++it) {
+        const int row = erow + it * (NT / (BN / 8));
+        const Chunk c = *reinterpret_cast<const Chunk*>(&stg[row * EPITCH + c8]);
+        if (!ragged || m0 + row < a.M) *reinterpret_cast<Chunk*>(ot + (ooff + it * ostep)) = c;
+      }
     }
     t += RGN;
     if (t >= MT) break;
