@@ -102,9 +102,10 @@ extern "C" int optorch_seq_create(const optorch_unit_t* units, int32_t n_units, 
         p.fops[i + 1].stat_blocks = p.fops[i].stat_blocks, p.fops[i].stat_fold = p.fops[i + 1].stat_fold = bn_stats_fold_rows(p.fops[i].stat_blocks);
       else if (p.fops[i].kind == F_CONV)
         p.fops[i].stat_blocks = 0;
-    // A BatchNorm apply (+ReLU) without a skip connection whose output has one reader, a convolution of the same unit
+    // A BatchNorm apply + ReLU without a skip connection whose output has one reader, a convolution of the same unit
     // whose forward and weight-gradient kernels can do it themselves, is folded into that convolution: the activation
     // is never written (storage mode 2 keeps every activation instead).  From the network and the layer shapes only.
+    // (A BatchNorm without ReLU keeps its apply launch: the folding kernels always apply the ReLU.)
     if (p.cfg.storage_mode != 2) {
       std::vector<int> readers(p.tensors.size(), 0), reader(p.tensors.size(), -1);
       for (size_t i = 0; i < p.fops.size(); ++i) {
@@ -114,7 +115,7 @@ extern "C" int optorch_seq_create(const optorch_unit_t* units, int32_t n_units, 
       }
       for (size_t i = 0; i < p.fops.size(); ++i) {
         FOp& b = p.fops[i];
-        if (b.kind != F_BN_APPLY || b.skip >= 0 || b.mask >= 0 || readers[b.out] != 1) continue;
+        if (b.kind != F_BN_APPLY || !b.relu || b.skip >= 0 || b.mask >= 0 || readers[b.out] != 1) continue;
         FOp& cv = p.fops[reader[b.out]];
         if (cv.kind != F_CONV || cv.x != b.out || cv.unit != b.unit) continue;
         if (cv.fwd_algo != ALGO_MFMA || cv.wgrad_algo != ALGO_MFMA) continue;
@@ -305,7 +306,7 @@ void run_op(const Ctx& c, const SOp& s) {
       if (f.fwd_algo == ALGO_MFMA)
         launch_conv_fwd_mfma(st, dt, c.at(s.in[0]), c.wc(f.w_off), f.has_bias ? c.w32(f.b_off) : nullptr, c.at(s.out[0]),
                              (float*)c.at(s.out[1]), (float*)c.at(s.out[2]), f.fwd_splits, geom(f), f.relu,
-                             (const float*)c.at(s.in[1]), f.fold_src >= 0 ? h->plan.fops[f.fold_src].relu : 0);
+                             (const float*)c.at(s.in[1]));
       else if (f.fwd_algo == ALGO_SMALLC)
         launch_conv_fwd_smallc(st, dt, c.at(s.in[0]), c.wc(f.w_off), f.has_bias ? c.w32(f.b_off) : nullptr, c.at(s.out[0]),
                                geom(f), f.relu);
@@ -365,7 +366,7 @@ void run_op(const Ctx& c, const SOp& s) {
     case S_WGRAD:
       if (f.wgrad_algo == ALGO_MFMA)
         launch_conv_wgrad_mfma(st, dt, c.at(s.in[0]), c.at(s.in[1]), c.g32(f.w_off), (float*)c.at(s.out[0]), f.wgrad_splits,
-                               geom(f), (const float*)c.at(s.in[2]), f.fold_src >= 0 ? h->plan.fops[f.fold_src].relu : 0);
+                               geom(f), (const float*)c.at(s.in[2]));
       else if (f.wgrad_algo == ALGO_SMALLC)
         launch_conv_wgrad_smallc(st, dt, c.at(s.in[0]), c.at(s.in[1]), c.g32(f.w_off), (float*)c.at(s.out[0]),
                                  f.wgrad_splits, geom(f));

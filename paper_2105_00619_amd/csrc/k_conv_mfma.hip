@@ -377,9 +377,9 @@ struct PatchArgs {
                              // 2: so that the channel blocks and depth ranges of one row tile do (row_blocks: row tiles)
   int row_blocks;
   const uint8_t* amask;      // data gradient with an addend: ReLU bit mask the addend is multiplied by, or null
-  const float* fold;         // FOLD (forward): src is the z of a BatchNorm, this its [4][srcC] statistics tensor; the pieces
-  int fold_relu;             // of the patch become the activation (scale, shift, ReLU if fold_relu, one rounding) on
-                             // their way to LDS; positions outside the image stay zero
+  const float* fold;         // FOLD (forward): src is the z of a BatchNorm + ReLU, this its [4][srcC] statistics tensor; the
+                             // pieces of the patch become the activation (scale, shift, ReLU, one rounding) on their way
+                             // to LDS; positions outside the image stay zero
 };
 
 constexpr int PATCH_MAX_POS = 256;  // positions per sub-tile
@@ -516,7 +516,7 @@ conv3x3_patch_kernel(const T* __restrict__ src, const T* __restrict__ wmat, cons
   auto patch_store = [&](int slot, int buf, const Chunk& c) {
     if ((pstore >> slot) & 1u) {
       Chunk v = c;
-      if (FOLD) v = bn_fold_chunk<T>(c, fsc, fsh, a.fold_relu);
+      if (FOLD) v = bn_fold_chunk<T>(c, fsc, fsh);
       *reinterpret_cast<Chunk*>(&patch[buf * PBUF + pdst[slot]]) = ((pvalid >> slot) & 1u) ? v : zero_chunk();
     }
   };
@@ -1025,17 +1025,16 @@ bool conv_fold_fwd_ok(int dt, const ConvGeom& g) {
 }
 
 void launch_conv_fwd_mfma(hipStream_t st, int dt, const void* x, const void* w, const float* bias, void* out,
-                          float* partial, float* stat_partial, int splits, const ConvGeom& g, int relu, const float* fold,
-                          int fold_relu) {
+                          float* partial, float* stat_partial, int splits, const ConvGeom& g, int relu, const float* fold) {
   PatchShape pv; PatchArgs pa{};
   if (conv_pointwise_fwd_ok(dt, g)) {
-    launch_conv_fwd_pointwise(st, dt, x, w, bias, out, stat_partial, g, relu, fold, fold_relu);
+    launch_conv_fwd_pointwise(st, dt, x, w, bias, out, stat_partial, g, relu, fold);
     return;
   }
   if (patch_pick(dt, g.N, g.P, g.Q, g.C, g.K, g.R, g.S, g.stride, pv, pa)) {
     pa.N = g.N; pa.srcH = g.H; pa.srcW = g.W; pa.srcC = g.C; pa.dstH = g.P; pa.dstW = g.Q; pa.Ng = g.K;
     pa.pad = g.pad; pa.flip = 0; pa.relu = relu;
-    pa.fold = dt == DT_F32 ? nullptr : fold; pa.fold_relu = fold_relu;
+    pa.fold = dt == DT_F32 ? nullptr : fold;
     launch_patch(st, dt, x, w, bias, nullptr, out, partial, stat_partial, pv, pa);
     return;
   }
@@ -1137,8 +1136,8 @@ struct WGradArgs {
   int H, W, C, K, R, S, stride, pad, P, Q;
   int pixels, chunk;  // chunk: pixels per blockIdx.z, a multiple of the depth tile
   FastDiv divQ, divPQ;
-  const float* fold;  // FOLD: x is the z of a BatchNorm, this its [4][C] statistics tensor; the pieces of x become the
-  int fold_relu;      // activation (scale, shift, ReLU if fold_relu, one rounding) on their way to LDS
+  const float* fold;  // FOLD: x is the z of a BatchNorm + ReLU, this its [4][C] statistics tensor; the pieces of x become
+                      // the activation (scale, shift, ReLU, one rounding) on their way to LDS
   int xcd_group;      // 1: the tiles of a pixel range share an XCD (see the kernel); ranges: the number of pixel ranges
   int ranges;
 };
@@ -1315,7 +1314,7 @@ __global__ void __launch_bounds__(64 * WGM * WGN) conv_wgrad_kernel(const T* __r
     T* sb = sa + A_ELEMS;
     if (FOLD) {
 #pragma unroll
-      for (int i = 0; i < B_CH32; ++i) rb[p][i] = bn_fold_chunk<T>(rb[p][i], fsc, fsh, a.fold_relu);
+      for (int i = 0; i < B_CH32; ++i) rb[p][i] = bn_fold_chunk<T>(rb[p][i], fsc, fsh);
     }
 #pragma unroll
     for (int i = 0; i < A_CH32; ++i) {
@@ -1496,7 +1495,7 @@ int conv_mfma_wgrad_splits(int dt, const ConvGeom& g) {
 
 template <class T, bool FOLD>
 static void launch_wgrad_t(hipStream_t st, const void* x, const void* dz, float* dst, int splits, const ConvGeom& g,
-                           const float* fold, int fold_relu) {
+                           const float* fold) {
   constexpr int depth = sizeof(T) == 4 ? 16 : 32;
   WGradArgs a;
   a.H = g.H; a.W = g.W; a.C = g.C; a.K = g.K; a.R = g.R; a.S = g.S; a.stride = g.stride; a.pad = g.pad; a.P = g.P; a.Q = g.Q;
@@ -1505,7 +1504,7 @@ static void launch_wgrad_t(hipStream_t st, const void* x, const void* dz, float*
   a.chunk = (chunk + depth - 1) / depth * depth;
   a.divQ = make_fastdiv((uint32_t)g.Q);
   a.divPQ = make_fastdiv((uint32_t)(g.P * g.Q));
-  a.fold = fold; a.fold_relu = fold_relu;
+  a.fold = fold;
   a.ranges = splits;
   a.xcd_group = g.R * g.S == 1 && splits >= 8;
   const int gz = a.xcd_group ? (splits + 7) / 8 * 8 : splits;
@@ -1592,16 +1591,16 @@ static void launch_wgrad_reduce(hipStream_t st, const float* partial, float* out
 bool conv_fold_wgrad_ok(int dt, const ConvGeom& g) { return dt != DT_F32 && conv_mfma_wgrad_ok(dt, g); }
 
 void launch_conv_wgrad_mfma(hipStream_t st, int dt, const void* x, const void* dz, float* dw, float* partial, int splits,
-                            const ConvGeom& g, const float* fold, int fold_relu) {
+                            const ConvGeom& g, const float* fold) {
   float* dst = splits > 1 ? partial : dw;
-  if (conv_wgrad3x3_ok(dt, g)) launch_conv_wgrad3x3(st, dt, x, dz, dst, g, fold, fold_relu);  // splits == conv_wgrad3x3_splits(dt, g)
-  else if (dt == DT_F32) launch_wgrad_t<float, false>(st, x, dz, dst, splits, g, nullptr, 0);
+  if (conv_wgrad3x3_ok(dt, g)) launch_conv_wgrad3x3(st, dt, x, dz, dst, g, fold);  // splits == conv_wgrad3x3_splits(dt, g)
+  else if (dt == DT_F32) launch_wgrad_t<float, false>(st, x, dz, dst, splits, g, nullptr);
   else if (dt == DT_BF16) {
-    if (fold) launch_wgrad_t<bf16_t, true>(st, x, dz, dst, splits, g, fold, fold_relu);
-    else launch_wgrad_t<bf16_t, false>(st, x, dz, dst, splits, g, nullptr, 0);
+    if (fold) launch_wgrad_t<bf16_t, true>(st, x, dz, dst, splits, g, fold);
+    else launch_wgrad_t<bf16_t, false>(st, x, dz, dst, splits, g, nullptr);
   } else {
-    if (fold) launch_wgrad_t<f16_t, true>(st, x, dz, dst, splits, g, fold, fold_relu);
-    else launch_wgrad_t<f16_t, false>(st, x, dz, dst, splits, g, nullptr, 0);
+    if (fold) launch_wgrad_t<f16_t, true>(st, x, dz, dst, splits, g, fold);
+    else launch_wgrad_t<f16_t, false>(st, x, dz, dst, splits, g, nullptr);
   }
   if (splits > 1) {
     launch_wgrad_reduce(st, partial, dw, (int64_t)g.K * g.R * g.S * g.C, splits);

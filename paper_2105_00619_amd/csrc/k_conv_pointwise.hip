@@ -50,8 +50,8 @@ struct PwArgs {
   int dstH, dstW, srcH, srcW;
   FastDiv div_w, div_hw;  // by dstW and dstH * dstW
   const uint8_t* amask;   // data gradient with an addend: ReLU bit mask the addend is multiplied by, or null
-  const float* fold;      // forward: X is the z of a BatchNorm whose [4][Kd] statistics tensor this is; the rows are turned
-  int fold_relu;          //          into the activation (scale, shift, ReLU if fold_relu, one rounding) on their way to LDS
+  const float* fold;      // forward: X is the z of a BatchNorm + ReLU whose [4][Kd] statistics tensor this is; the rows are
+                          //          turned into the activation (scale, shift, ReLU, one rounding) on their way to LDS
 };
 
 template <int V> struct IC { static constexpr int value = V; };
@@ -175,7 +175,7 @@ conv1x1_kernel(const T* __restrict__ X, const T* __restrict__ W, const float* __
       load_f32<float, 8>(ftab + kt * BK + vec * 8, sc);
       load_f32<float, 8>(ftab + Kd + kt * BK + vec * 8, sh);
 #pragma unroll
-      for (int i = 0; i < A_CH; ++i) ra[p][i] = bn_fold_chunk<T>(ra[p][i], sc, sh, a.fold_relu);
+      for (int i = 0; i < A_CH; ++i) ra[p][i] = bn_fold_chunk<T>(ra[p][i], sc, sh);
     }
 #pragma unroll
     for (int i = 0; i < A_CH; ++i) *reinterpret_cast<Chunk*>(&st[(row0 + i * 64) * PITCH + vec * 8]) = ra[p][i];
@@ -348,7 +348,7 @@ conv1x1_large_kernel(const T* __restrict__ X, const T* __restrict__ W, const flo
       load_f32<float, 8>(ftab + kt * BK + vec * 8, sc);
       load_f32<float, 8>(ftab + Kd + kt * BK + vec * 8, sh);
 #pragma unroll
-      for (int i = 0; i < A_CH; ++i) ra[p][i] = bn_fold_chunk<T>(ra[p][i], sc, sh, a.fold_relu);
+      for (int i = 0; i < A_CH; ++i) ra[p][i] = bn_fold_chunk<T>(ra[p][i], sc, sh);
     }
 #pragma unroll
     for (int i = 0; i < A_CH; ++i) *reinterpret_cast<Chunk*>(&st[(row0 + i * RSTEP) * PITCH + vec * 8]) = ra[p][i];
@@ -726,13 +726,8 @@ conv1x1_ws_kernel(const T* __restrict__ X, const T* __restrict__ W, const float*
       float sc[8], sh[8];
       load_f32<float, 8>(ftab + cc * 8, sc);
       load_f32<float, 8>(ftab + KD + cc * 8, sh);
-      if (a.fold_relu) {  // one branch per tile
 #pragma unroll
-        for (int i = 0; i < A_CH; ++i) ra[i] = bn_fold_chunk_t<T, true>(ra[i], sc, sh);
-      } else {
-#pragma unroll
-        for (int i = 0; i < A_CH; ++i) ra[i] = bn_fold_chunk_t<T, false>(ra[i], sc, sh);
-      }
+      for (int i = 0; i < A_CH; ++i) ra[i] = bn_fold_chunk<T>(ra[i], sc, sh);
     }
 #pragma unroll
     for (int i = 0; i < A_CH; ++i) *reinterpret_cast<Chunk*>(&abuf[(r0 + i * RPI) * APITCH + cc * 8]) = ra[i];
@@ -1013,9 +1008,9 @@ bool conv_pointwise_fold_ok(int dt, const ConvGeom& g) { return conv_pointwise_f
 
 // fold: null, or the [4][C_in] statistics tensor of the BatchNorm whose z the tensor x is (see PwArgs::fold)
 void launch_conv_fwd_pointwise(hipStream_t st, int dt, const void* x, const void* w, const float* bias, void* out,
-                               float* stat_partial, const ConvGeom& g, int relu, const float* fold, int fold_relu) {
+                               float* stat_partial, const ConvGeom& g, int relu, const float* fold) {
   PwArgs a{};
-  a.fold = fold; a.fold_relu = fold_relu;
+  a.fold = fold;
   a.M = (int64_t)g.N * g.P * g.Q; a.Ng = g.K; a.Kd = g.C; a.relu = relu; a.stride = g.stride;
   a.dstH = g.P; a.dstW = g.Q; a.srcH = g.H; a.srcW = g.W;
   a.div_w = make_fastdiv((uint32_t)g.Q); a.div_hw = make_fastdiv((uint32_t)(g.P * g.Q));

@@ -42,8 +42,8 @@ struct W9Args {
   int tiles_r, tiles_c, NT;          // sub-tiles per image rows / columns; in total
   int tiles_per_split;
   int xcd_group, splits;  // xcd_group: the tiles of a pixel range share an XCD (see the kernel); splits: pixel ranges
-  const float* fold;  // FOLD: x is the z of a BatchNorm, this its [4][C] statistics tensor; the staged pieces of x become
-  int fold_relu;      // the activation (scale, shift, ReLU if fold_relu, one rounding); positions outside the image stay zero
+  const float* fold;  // FOLD: x is the z of a BatchNorm + ReLU, this its [4][C] statistics tensor; the staged pieces of x
+                      // become the activation (scale, shift, ReLU, one rounding); positions outside the image stay zero
 };
 
 template <class T> struct W9Cfg;
@@ -199,7 +199,7 @@ conv_wgrad3x3_kernel(const T* __restrict__ x, const T* __restrict__ dz, float* _
     T* ds = xs + L::XS;
     if (FOLD) {
 #pragma unroll
-      for (int sl = 0; sl < XSLOTS; ++sl) xr[sl] = bn_fold_chunk<T>(xr[sl], fsc, fsh, a.fold_relu);
+      for (int sl = 0; sl < XSLOTS; ++sl) xr[sl] = bn_fold_chunk<T>(xr[sl], fsc, fsh);
     }
 #pragma unroll
     for (int sl = 0; sl < XSLOTS; ++sl) {
@@ -390,10 +390,10 @@ int conv_wgrad3x3_splits(int dt, const ConvGeom& g) {
 
 // dst: [splits][K][9][C] floats (dw itself when splits == 1); fold: see W9Args (16-bit modes only)
 void launch_conv_wgrad3x3(hipStream_t st, int dt, const void* x, const void* dz, float* dst, const ConvGeom& g,
-                          const float* fold, int fold_relu) {
+                          const float* fold) {
   W9Plan pl;
   if (!w9_plan(dt, g, pl)) return;
-  pl.a.fold = dt == DT_F32 ? nullptr : fold; pl.a.fold_relu = fold_relu;
+  pl.a.fold = dt == DT_F32 ? nullptr : fold;
   if (dt == DT_F32) launch_w9<float, 1, 2, false>(st, x, dz, dst, pl);
   else if (dt == DT_BF16) launch_w9_16<bf16_t>(st, x, dz, dst, pl);
   else launch_w9_16<f16_t>(st, x, dz, dst, pl);

@@ -79,15 +79,15 @@ int conv_mfma_fwd_splits(int dt, const ConvGeom& g);
 int conv_mfma_dgrad_splits(int dt, const ConvGeom& g);
 // partial: fp32 workspace of splits * (output elements) floats when splits > 1, else unused
 int conv_mfma_fwd_stat_blocks(int dt, const ConvGeom& g);
-// fold (null: none): x is not the input activation but the z of the BatchNorm(+ReLU if fold_relu) in front of the layer,
-// and fold that BatchNorm's [4][C_in] statistics tensor (mean, rstd, scale, shift): the kernel turns z into the
-// activation -- the very values the apply kernel would have stored -- while it stages its operand.  Only where
-// conv_fold_fwd_ok / conv_fold_wgrad_ok say so (from the layer shape only).
+// fold (null: none): x is not the input activation but the z of the BatchNorm + ReLU in front of the layer, and fold
+// that BatchNorm's [4][C_in] statistics tensor (mean, rstd, scale, shift): the kernel turns z into the activation --
+// the very values the apply kernel would have stored -- while it stages its operand.  Only where conv_fold_fwd_ok /
+// conv_fold_wgrad_ok say so (from the layer shape only), and only for a BatchNorm that is followed by a ReLU.
 bool conv_fold_fwd_ok(int dt, const ConvGeom& g);
 bool conv_fold_wgrad_ok(int dt, const ConvGeom& g);
 void launch_conv_fwd_mfma(hipStream_t st, int dt, const void* x, const void* w, const float* bias, void* out,
                           float* partial, float* stat_partial, int splits, const ConvGeom& g, int relu,
-                          const float* fold = nullptr, int fold_relu = 0);
+                          const float* fold = nullptr);
 // addend_mask (null, or with an addend): ReLU decisions as bits (as launch_bn_apply writes them); the addend counts
 // as zero where its bit is clear
 void launch_conv_dgrad_mfma(hipStream_t st, int dt, const void* dz, const void* wt, const void* addend,
@@ -98,18 +98,18 @@ bool conv_pointwise_dgrad_ok(int dt, const ConvGeom& g);
 int conv_pointwise_stat_blocks(const ConvGeom& g);
 bool conv_pointwise_fold_ok(int dt, const ConvGeom& g);
 void launch_conv_fwd_pointwise(hipStream_t st, int dt, const void* x, const void* w, const float* bias, void* out,
-                               float* stat_partial, const ConvGeom& g, int relu, const float* fold, int fold_relu);
+                               float* stat_partial, const ConvGeom& g, int relu, const float* fold);
 void launch_conv_dgrad_pointwise(hipStream_t st, int dt, const void* dz, const void* wt, const void* addend,
                                  const uint8_t* addend_mask, void* dx, const ConvGeom& g);
 // 3x3 stride-1 weight gradient with all nine taps per block (k_conv_wgrad3x3.hip); used by the MFMA launcher below
 bool conv_wgrad3x3_ok(int dt, const ConvGeom& g);
 int conv_wgrad3x3_splits(int dt, const ConvGeom& g);
 void launch_conv_wgrad3x3(hipStream_t st, int dt, const void* x, const void* dz, float* dst, const ConvGeom& g,
-                          const float* fold, int fold_relu);
+                          const float* fold);
 bool conv_mfma_wgrad_ok(int dt, const ConvGeom& g);
 int conv_mfma_wgrad_splits(int dt, const ConvGeom& g);
 void launch_conv_wgrad_mfma(hipStream_t st, int dt, const void* x, const void* dz, float* dw, float* partial, int splits,
-                            const ConvGeom& g, const float* fold = nullptr, int fold_relu = 0);
+                            const ConvGeom& g, const float* fold = nullptr);
 // Transposed weight copies for the data-gradient GEMMs, all layers in one launch (per 48 layers).  w_off: element
 // offset of the layer's weights in the flat parameter vector (the same offset is used in the transposed copy).
 struct TransposeJob { int64_t w_off; int K, RS, C, first_block; };
