@@ -82,7 +82,13 @@ __device__ __forceinline__ typename V8<T>::type tr_read8(const T* p0, const T* p
   return __builtin_bit_cast(typename V8<T>::type, r);
 }
 
-template <class T, int MI, int WGM, bool FOLD = false>
+// WHOLE: every sub-tile is TI whole images (small images: 8 x 8, 4 x 4).  The (row, column) part of a chunk's address and
+// of its bounds check is then the same for every sub-tile: a chunk keeps its pixel index within the sub-tile, the
+// sub-tile adds its first image's, and one full-rate 24-bit multiply by the channel count gives the address (pixel
+// indices and channel counts are below 2^24 where this kernel is chosen) -- the general path decodes image, row and
+// column, checks each against the image and multiplies them back together with quarter-rate 32- and 64-bit multiplies,
+// per chunk and sub-tile, in a kernel whose instruction stream is what bounds it.
+template <class T, int MI, int WGM, bool FOLD = false, bool WHOLE = false>
 __global__ void __launch_bounds__(128 * WGM) __attribute__((amdgpu_waves_per_eu(WGM / 2, WGM / 2)))
 conv_wgrad3x3_kernel(const T* __restrict__ x, const T* __restrict__ dz, float* __restrict__ out, W9Args a) {
   typedef W9Lds<T, MI, WGM> L;
@@ -142,6 +148,10 @@ conv_wgrad3x3_kernel(const T* __restrict__ x, const T* __restrict__ dz, float* _
       const int ti = pos / (a.SR * SC), rr = pos - ti * (a.SR * SC);
       const int sy = rr / SC, sx = rr - sy * SC;
       info = (ti << 20) | (sy << 10) | sx;
+      if (WHOLE) {  // image in the high bits, (ti * H + y) * W + x in the low ones; a halo position outside the image: none
+        const int y = sy - pad, xx = sx - pad;
+        info = y >= 0 && y < H && xx >= 0 && xx < W ? (ti << 20) | ((ti * H + y) * W + xx) : -1;
+      }
     }
     xinfo[sl] = info;
   }
@@ -153,6 +163,7 @@ conv_wgrad3x3_kernel(const T* __restrict__ x, const T* __restrict__ dz, float* _
       const int ti = m / (TR * TC), rr = m - ti * (TR * TC);
       const int tr = rr / TC, tc = rr - tr * TC;
       info = (ti << 20) | (tr << 10) | tc;
+      if (WHOLE) info = (ti << 20) | ((ti * P + tr) * Q + tc);
     }
     dinfo[sl] = info;
   }
@@ -161,6 +172,31 @@ conv_wgrad3x3_kernel(const T* __restrict__ x, const T* __restrict__ dz, float* _
   Chunk xr[XSLOTS], dr[DSLOTS];
   unsigned xok = 0u, dok = 0u;
   auto gload = [&](int tile) {
+    if constexpr (WHOLE) {
+      const int nb = tile * TI;
+      const uint32_t xbase = (uint32_t)nb * (uint32_t)(H * W), dbase = (uint32_t)nb * (uint32_t)(P * Q);
+      unsigned xm = 0u, dm = 0u;
+#pragma unroll
+      for (int sl = 0; sl < XSLOTS; ++sl) {
+        const int info = xinfo[sl];
+        const bool ok = info >= 0 && nb + (info >> 20) < N;
+        const uint64_t off = ok ? (uint64_t)((xbase + (uint32_t)(info & 0xfffff)) & 0xffffffu) * (uint64_t)((uint32_t)C & 0xffffffu) : 0;
+        const int v = (sl * NTH + tid) % XCP;
+        xr[sl] = *reinterpret_cast<const Chunk*>(x + off + c0 + v * EV);
+        xm |= ok ? (1u << sl) : 0u;
+      }
+#pragma unroll
+      for (int sl = 0; sl < DSLOTS; ++sl) {
+        const int info = dinfo[sl];
+        const bool ok = info >= 0 && nb + (info >> 20) < N;
+        const uint64_t off = ok ? (uint64_t)((dbase + (uint32_t)(info & 0xfffff)) & 0xffffffu) * (uint64_t)((uint32_t)K & 0xffffffu) : 0;
+        const int v = (sl * NTH + tid) % DCP;
+        dr[sl] = *reinterpret_cast<const Chunk*>(dz + off + k0 + v * EV);
+        dm |= ok ? (1u << sl) : 0u;
+      }
+      xok = xm; dok = dm;
+      return;
+    }
     const int ci = tile % a.tiles_c, t2 = tile / a.tiles_c;
     const int ri = t2 % a.tiles_r, ii = t2 / a.tiles_r;
     const int nb = ii * TI, yb = ri * TR, xb = ci * TC;
@@ -353,7 +389,8 @@ void launch_w9(hipStream_t st, const void* x, const void* dz, float* dst, const 
   constexpr size_t sm = W9Lds<T, MI, WGM>::bytes;
   static bool attr_done = false;
   if (!attr_done) {
-    (void)hipFuncSetAttribute((const void*)conv_wgrad3x3_kernel<T, MI, WGM, FOLD>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sm);
+    (void)hipFuncSetAttribute((const void*)conv_wgrad3x3_kernel<T, MI, WGM, FOLD, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sm);
+    (void)hipFuncSetAttribute((const void*)conv_wgrad3x3_kernel<T, MI, WGM, FOLD, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sm);
     attr_done = true;
   }
   W9Args a = pl.a;
@@ -361,7 +398,12 @@ void launch_w9(hipStream_t st, const void* x, const void* dz, float* dst, const 
   a.splits = pl.splits;
   a.xcd_group = tiles > 1 && pl.splits >= 8;  // (from the shape only)
   dim3 grid(a.K / (32 * MI * WGM), a.C / 64, a.xcd_group ? (pl.splits + 7) / 8 * 8 : pl.splits), block(128 * WGM);
-  OSEQ_LAUNCH((conv_wgrad3x3_kernel<T, MI, WGM, FOLD>), grid, block, sm, st, (const T*)x, (const T*)dz, dst, a);
+  // sub-tiles of whole images, every index that is multiplied below 2^24, the pixel index within a sub-tile below 2^20
+  const bool whole = a.tiles_r == 1 && a.tiles_c == 1 && a.TR == a.P && a.TC == a.Q && a.H == a.P && a.W == a.Q &&
+                     (int64_t)a.N * a.H * a.W + (int64_t)a.TI * a.H * a.W < (1 << 24) && a.C < (1 << 24) && a.K < (1 << 24) &&
+                     a.TI < 256 && (int64_t)a.TI * a.H * a.W < (1 << 20);
+  if (whole) OSEQ_LAUNCH((conv_wgrad3x3_kernel<T, MI, WGM, FOLD, true>), grid, block, sm, st, (const T*)x, (const T*)dz, dst, a);
+  else OSEQ_LAUNCH((conv_wgrad3x3_kernel<T, MI, WGM, FOLD, false>), grid, block, sm, st, (const T*)x, (const T*)dz, dst, a);
 }
 
 template <class T>
