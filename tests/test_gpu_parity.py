@@ -105,6 +105,10 @@ LAYER_NETS = {
                                         W.gap_linear_ce(256, 10)]),
     # the weights-stationary forward kernel with a bias and no BatchNorm behind it (no sums), on a folded BatchNorm
     "pointwise_rows_bias": (64, 33, 61, [W.conv(64, 128, ksize=1), W.conv(128, 512, ksize=1, bn=False), W.gap_linear_ce(512, 10)]),
+    # small maps with an odd batch: the sub-tiles of the 3x3 weight gradient are whole images (two of 8x8, eight of 4x4)
+    # and the last one is only partly inside the batch
+    "whole_image_tiles_8x8_odd": (256, 8, 193, [W.conv(256, 256), W.conv(256, 256), W.gap_linear_ce(256, 10)]),
+    "whole_image_tiles_4x4_odd": (512, 4, 67, [W.conv(512, 512), W.conv(512, 512), W.gap_linear_ce(512, 10)]),
     "pointwise_bottlenecks": (64, 16, 64, [W.conv(64, 64, ksize=1), W.bottleneck(64, 256, 1), W.bottleneck(256, 512, 2),
                                            W.gap_linear_ce(512, 10)]),
 }
