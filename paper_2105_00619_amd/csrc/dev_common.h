@@ -48,6 +48,21 @@ struct alignas(sizeof(T) * V) Vec {
   T v[V];
 };
 
+// the same as a streaming (non-temporal) load where the V elements are 16 bytes
+template <class T, int V>
+__device__ __forceinline__ void load_f32_nt(const T* p, float (&out)[V]) {
+  if constexpr (sizeof(T) * V == 16) {
+    typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+    const u32x4 c = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+    const Vec<T, V> t = __builtin_bit_cast(Vec<T, V>, c);
+#pragma unroll
+    for (int i = 0; i < V; ++i) out[i] = to_f32(t.v[i]);
+  } else {
+    Vec<T, V> t = *reinterpret_cast<const Vec<T, V>*>(p);
+#pragma unroll
+    for (int i = 0; i < V; ++i) out[i] = to_f32(t.v[i]);
+  }
+}
 template <class T, int V>
 __device__ __forceinline__ void load_f32(const T* p, float (&out)[V]) {
   Vec<T, V> t = *reinterpret_cast<const Vec<T, V>*>(p);

@@ -69,6 +69,9 @@ __global__ void __launch_bounds__(256) colreduce_kernel(RedArgs g) {
     const T* z = static_cast<const T*>(g.z);
     const T* ao = MODE == RED_BN_BWD_AOUT ? static_cast<const T*>(g.aout) : nullptr;
     const uint8_t* mk = MODE == RED_BN_BWD_MASK ? g.mask : nullptr;
+    // (the row loads below are non-temporal: nothing a reduction reads is read again from the cache it would fill --
+    // -2 % on the BatchNorm backward of the bottleneck networks; in the apply kernels, whose output the next kernel
+    // reads, the same hint slowed that reader down by as much as it gained)
     // one row's contribution, from values already in registers
     auto accumulate = [&](const float (&va)[V], const float (&vz)[V], const float (&vo)[V], unsigned bits) {
       if (MODE == RED_STATS) {
@@ -101,10 +104,10 @@ __global__ void __launch_bounds__(256) colreduce_kernel(RedArgs g) {
 #pragma unroll
       for (int u = 0; u < RT; ++u) {
         const int64_t off = (r + (int64_t)u * TY) * g.C + c0;
-        load_f32<T, V>(a + off, va[u]);
+        load_f32_nt<T, V>(a + off, va[u]);
         mb[u] = 0u;
         if (BWD) {
-          load_f32<T, V>(z + off, vz[u]);
+          load_f32_nt<T, V>(z + off, vz[u]);
           if (MODE == RED_BN_BWD_MASK) mb[u] = mk[(r + (int64_t)u * TY) * CG + cg];
           else if (MODE == RED_BN_BWD_AOUT) load_f32<T, V>(ao + off, vo[u]);
         }
@@ -116,9 +119,9 @@ __global__ void __launch_bounds__(256) colreduce_kernel(RedArgs g) {
       const int64_t off = r * g.C + c0;
       float va[V], vz[V], vo[V];
       unsigned mb = 0u;
-      load_f32<T, V>(a + off, va);
+      load_f32_nt<T, V>(a + off, va);
       if (BWD) {
-        load_f32<T, V>(z + off, vz);
+        load_f32_nt<T, V>(z + off, vz);
         if (MODE == RED_BN_BWD_MASK) mb = mk[r * CG + cg];
         else if (MODE == RED_BN_BWD_AOUT) load_f32<T, V>(ao + off, vo);
       }
