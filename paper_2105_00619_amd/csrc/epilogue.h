@@ -121,7 +121,12 @@ __device__ __forceinline__ void epi_load_addend_nt(int tid, int n0, const T* __r
   for (int it = 0; it < PER_THREAD; ++it) {
     const int64_t ro = rowoff(erow + it * RG);
     const int64_t e = (ro >= 0 ? ro : 0) + col;  // rows that are not stored read the tensor's first row
-    ad[it] = *reinterpret_cast<const Vec<T, 8>*>(addend + e);
+    if constexpr (sizeof(T) == 2) {  // read once, by this block only
+      typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+      ad[it] = __builtin_bit_cast(Vec<T, 8>, __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(addend + e)));
+    } else {
+      ad[it] = *reinterpret_cast<const Vec<T, 8>*>(addend + e);
+    }
     mb[it] = 0xffu;
     if (amask) {
       if (sizeof(T) == 2) mb[it] = amask[e >> 3];
