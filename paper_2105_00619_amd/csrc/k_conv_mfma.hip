@@ -1179,7 +1179,9 @@ constexpr size_t wgrad_lds_bytes() {
 // are then one uniform base per tensor plus per-thread offsets that never change (the general path divides every
 // pixel index into image, row and column and multiplies it back into an address, a few dozen quarter-rate integer
 // multiplies per depth tile that the 256 x 256 tile, with one block per CU, has nobody to hide behind).
-template <class T, int BM, int BN, int WGM = 2, int WGN = 2, bool FOLD = false, bool PW = false>
+// NTL (PW only): 1 / 2: the rows of dz / of x are read by this block's tile alone (one input- / output-channel tile) and
+// are loaded non-temporally
+template <class T, int BM, int BN, int WGM = 2, int WGN = 2, bool FOLD = false, bool PW = false, int NTL = 0>
 __global__ void __launch_bounds__(64 * WGM * WGN) conv_wgrad_kernel(const T* __restrict__ x, const T* __restrict__ dz,
                                                                     float* __restrict__ out, WGradArgs a) {
   constexpr bool F32 = sizeof(T) == 4;
@@ -1263,14 +1265,16 @@ __global__ void __launch_bounds__(64 * WGM * WGN) conv_wgrad_kernel(const T* __r
       for (int i = 0; i < A_CH32; ++i) {
         const int px = (tid + i * NT) / (BM / EV);
         const bool ok = !CHK || mt + px < mend;  // a row past the range reads the same piece of the range's first row
-        ra[p][i] = *reinterpret_cast<const Chunk*>(ok ? dzt + offa[i] : dz + (int64_t)mbeg * K + (offa[i] - px * K));
+        const Chunk* pa = reinterpret_cast<const Chunk*>(ok ? dzt + offa[i] : dz + (int64_t)mbeg * K + (offa[i] - px * K));
+        ra[p][i] = NTL == 1 ? __builtin_nontemporal_load(pa) : *pa;
         ma |= ok ? (1u << i) : 0u;
       }
 #pragma unroll
       for (int i = 0; i < B_CH32; ++i) {
         const int px = (tid + i * NT) / (BN / EV);
         const bool ok = !CHK || mt + px < mend;
-        rb[p][i] = *reinterpret_cast<const Chunk*>(ok ? xt + offb[i] : x + (int64_t)mbeg * C + (offb[i] - px * C));
+        const Chunk* pb = reinterpret_cast<const Chunk*>(ok ? xt + offb[i] : x + (int64_t)mbeg * C + (offb[i] - px * C));
+        rb[p][i] = NTL == 2 ? __builtin_nontemporal_load(pb) : *pb;
         mb |= ok ? (1u << i) : 0u;
       }
       va[p] = ma; vb[p] = mb;
@@ -1515,11 +1519,19 @@ static void launch_wgrad_t(hipStream_t st, const void* x, const void* dz, float*
       if (!attr_done) {
         (void)hipFuncSetAttribute((const void*)conv_wgrad_kernel<T, 256, 256, 2, 4, FOLD, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sm);
         (void)hipFuncSetAttribute((const void*)conv_wgrad_kernel<T, 256, 256, 2, 4, FOLD, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sm);
+        (void)hipFuncSetAttribute((const void*)conv_wgrad_kernel<T, 256, 256, 2, 4, FOLD, true, 1>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sm);
+        (void)hipFuncSetAttribute((const void*)conv_wgrad_kernel<T, 256, 256, 2, 4, FOLD, true, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sm);
         attr_done = true;
       }
       // rows of x = pixels of dz, and the row offsets fit 32 bits
       const bool pw = g.stride == 1 && g.pad == 0 && (int64_t)32 * std::max(g.K, g.C) < (1 << 30);
-      if (pw)
+      if (pw && g.C == 256 && g.K > 256)
+        OSEQ_LAUNCH((conv_wgrad_kernel<T, 256, 256, 2, 4, FOLD, true, 1>), dim3(g.K / 256, g.C / 256, gz), dim3(512), sm, st, (const T*)x,
+                    (const T*)dz, dst, a);
+      else if (pw && g.K == 256 && g.C > 256)
+        OSEQ_LAUNCH((conv_wgrad_kernel<T, 256, 256, 2, 4, FOLD, true, 2>), dim3(g.K / 256, g.C / 256, gz), dim3(512), sm, st, (const T*)x,
+                    (const T*)dz, dst, a);
+      else if (pw)
         OSEQ_LAUNCH((conv_wgrad_kernel<T, 256, 256, 2, 4, FOLD, true>), dim3(g.K / 256, g.C / 256, gz), dim3(512), sm, st, (const T*)x,
                     (const T*)dz, dst, a);
       else
